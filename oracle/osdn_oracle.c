@@ -1,0 +1,339 @@
+/*
+ * OSDN CPU oracle -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, fp64, token-by-token implementation of the gated delta-rule
+ * recurrence whose write-side key is rescaled by OSDN's online diagonal
+ * preconditioner.  It exists to check the HIP library; nothing in the product
+ * path may call it, and it shares no source with the HIP library.
+ *
+ * What it follows (paper: "OSDN: Improving Delta Rule with Provable Online
+ * Preconditioning in Linear Attention"):
+ *   - phase 1 (preconditioner sweep): Algorithm 1, Eq. (dt_update), and with
+ *     retention Eq. (dt_update_apf); constants and the order of operations of
+ *     the reference semantics in Appendix C, Listing 1 (eps floors the squared
+ *     key norm, the alignment <d,k^2> uses the un-retained d, clamp after every
+ *     step, non-beta-aware mode replaces beta by 1 in the d update only);
+ *   - phase 2 (state): Eq. (equiv_update) / Eq. (recurrent_form) with the gate
+ *     of Appendix B.1 ("post-gate" form: decay S first, read with the unscaled
+ *     key k, write with k~ = d (.) k), read-out o_t = S_t q_t from Table
+ *     "Recurrence and read-out" (post-write state), query scale as Listing 1;
+ *   - backward: Section 4.5 chain rule (dL/dd_t = k_t (.) dL/dk~_t,
+ *     dL/dk_t += d_t (.) dL/dk~_t) and a reverse sweep through the projected
+ *     affine recurrence; everything else is ordinary reverse-mode
+ *     differentiation of the forward loop written below.
+ *
+ * Layouts (all row-major, fp64): q,k [B,T,H,K]; v,o [B,T,H,V]; beta,
+ * log_alpha, retention [B,T,H]; d [B,H,K]; S [B,H,V,K].
+ * NULL log_alpha => alpha = 1 (ungated OSDN); NULL retention => r = 1;
+ * NULL d_in => ones; NULL S_in => zeros.  d_min > d_max => no projection.
+ *
+ * The only parallelism is an OpenMP loop over the independent (b,h) chains.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+    int B, T, H, K, V;
+    double scale;      /* multiplies q (Listing 1: K^-0.5) */
+    double eta;        /* online step size (0.003 in the paper's runs) */
+    double d_min, d_max;
+    double eps;        /* floor of the squared key norm (1e-6) */
+    int beta_aware;    /* 1: beta enters the d update; 0: beta replaced by 1 there */
+} osdn_oracle_params;
+
+int osdn_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---- one token of phase 1: returns quantities the backward also needs ---- */
+typedef struct {
+    double n_raw, n, p, bp, c;
+} p1_scalars;
+
+/* d (in/out, K), k (K) ; writes k_tilde (K) if non-NULL, d_bar (K) if non-NULL */
+static void phase1_step(const osdn_oracle_params *P, const double *k, double beta,
+                        double r, double *d, double *k_tilde, double *d_bar,
+                        p1_scalars *out)
+{
+    const int K = P->K;
+    double n_raw = 0.0, p = 0.0;
+    for (int j = 0; j < K; ++j) {
+        double s = k[j] * k[j];
+        if (k_tilde) k_tilde[j] = d[j] * k[j];   /* uses d BEFORE this token's update */
+        n_raw += s;
+        p += d[j] * s;
+    }
+    double n = n_raw > P->eps ? n_raw : P->eps;
+    double bp = P->beta_aware ? beta : 1.0;
+    double c = P->eta * bp * (1.0 - bp * p) / n;
+    const int project = P->d_min <= P->d_max;
+    for (int j = 0; j < K; ++j) {
+        double s = k[j] * k[j];
+        double db = r * d[j] + c * s;
+        if (d_bar) d_bar[j] = db;
+        if (project) {
+            if (db < P->d_min) db = P->d_min;
+            if (db > P->d_max) db = P->d_max;
+        }
+        d[j] = db;
+    }
+    if (out) { out->n_raw = n_raw; out->n = n; out->p = p; out->bp = bp; out->c = c; }
+}
+
+/* ---- one token of phase 2 on S (V x K): decay, read with k, write with k~ ----
+ * u (V) receives the residual v - (alpha S) k ; S is updated in place. */
+static void phase2_step(int K, int V, double alpha, double beta, const double *k,
+                        const double *k_tilde, const double *v, double *S, double *u)
+{
+    for (int a = 0; a < V; ++a) {
+        double *row = S + (size_t)a * K;
+        double acc = 0.0;
+        for (int j = 0; j < K; ++j) { row[j] *= alpha; acc += row[j] * k[j]; }
+        u[a] = v[a] - acc;
+        double e = beta * u[a];
+        for (int j = 0; j < K; ++j) row[j] += e * k_tilde[j];
+    }
+}
+
+/* Phase 1 alone.  k_tilde [B,T,H,K]; d_out [B,H,K]; d_traj (optional) [B,T,H,K]
+ * holds d_t, the value used for token t (before its update). */
+int osdn_oracle_precond(const osdn_oracle_params *P, const double *k, const double *beta,
+                        const double *retention, const double *d_in,
+                        double *k_tilde, double *d_out, double *d_traj)
+{
+    const int B = P->B, T = P->T, H = P->H, K = P->K;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            double *d = d_out + ((size_t)b * H + h) * K;
+            for (int j = 0; j < K; ++j) d[j] = d_in ? d_in[((size_t)b * H + h) * K + j] : 1.0;
+            for (int t = 0; t < T; ++t) {
+                size_t th = ((size_t)b * T + t) * H + h;
+                if (d_traj) memcpy(d_traj + th * K, d, sizeof(double) * K);
+                phase1_step(P, k + th * K, beta[th], retention ? retention[th] : 1.0, d,
+                            k_tilde ? k_tilde + th * K : NULL, NULL, NULL);
+            }
+        }
+    return 0;
+}
+
+int osdn_oracle_fwd(const osdn_oracle_params *P, const double *q, const double *k,
+                    const double *v, const double *beta, const double *log_alpha,
+                    const double *retention, const double *d_in, const double *S_in,
+                    double *o, double *S_out, double *d_out)
+{
+    const int B = P->B, T = P->T, H = P->H, K = P->K, V = P->V;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            size_t bh = (size_t)b * H + h;
+            double *S = S_out + bh * V * K;
+            double *d = d_out + bh * K;
+            double *kt = (double *)malloc(sizeof(double) * K);
+            double *u = (double *)malloc(sizeof(double) * V);
+            if (!kt || !u) { fail = 1; free(kt); free(u); continue; }
+            for (int j = 0; j < K; ++j) d[j] = d_in ? d_in[bh * K + j] : 1.0;
+            for (size_t i = 0; i < (size_t)V * K; ++i) S[i] = S_in ? S_in[bh * V * K + i] : 0.0;
+            for (int t = 0; t < T; ++t) {
+                size_t th = ((size_t)b * T + t) * H + h;
+                const double *kk = k + th * K, *qq = q + th * K, *vv = v + th * V;
+                double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
+                /* phase 1 for this token: emits k~_t from d_t, then advances d */
+                phase1_step(P, kk, beta[th], retention ? retention[th] : 1.0, d, kt, NULL, NULL);
+                /* phase 2 for this token */
+                phase2_step(K, V, alpha, beta[th], kk, kt, vv, S, u);
+                /* read-out from the post-write state */
+                for (int a = 0; a < V; ++a) {
+                    double acc = 0.0;
+                    for (int j = 0; j < K; ++j) acc += S[(size_t)a * K + j] * qq[j];
+                    o[th * V + a] = P->scale * acc;
+                }
+            }
+            free(kt); free(u);
+        }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Backward: reverse-mode differentiation of the loop in osdn_oracle_fwd.
+ * To bound memory the chain is replayed in segments: a forward sweep keeps S
+ * and d at the start of every segment of SEG tokens; the reverse sweep re-runs
+ * one segment at a time keeping S_{t-1} and d_t for its tokens.  This is a
+ * storage scheme only: every token's adjoint is computed from exactly the
+ * values the forward loop produced.
+ *
+ * dS_out / dd_out: incoming adjoints of the returned S_T and d_{T+1} (NULL => 0).
+ * dlog_alpha may be NULL when log_alpha is NULL; dretention NULL when retention is.
+ */
+#define SEG 64
+int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *k,
+                    const double *v, const double *beta, const double *log_alpha,
+                    const double *retention, const double *d_in, const double *S_in,
+                    const double *dO, const double *dS_out, const double *dd_out,
+                    double *dq, double *dk, double *dv, double *dbeta, double *dlog_alpha,
+                    double *dretention, double *dd_in, double *dS_in)
+{
+    const int B = P->B, T = P->T, H = P->H, K = P->K, V = P->V;
+    const size_t VK = (size_t)V * K;
+    const int nseg = (T + SEG - 1) / SEG;
+    const int project = P->d_min <= P->d_max;
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            size_t bh = (size_t)b * H + h;
+            double *ckS = (double *)malloc(sizeof(double) * VK * (size_t)(nseg > 0 ? nseg : 1));
+            double *ckd = (double *)malloc(sizeof(double) * K * (size_t)(nseg > 0 ? nseg : 1));
+            double *Sprev = (double *)malloc(sizeof(double) * VK * SEG); /* S_{t-1} per token */
+            double *dtr = (double *)malloc(sizeof(double) * K * SEG);    /* d_t per token */
+            double *S = (double *)malloc(sizeof(double) * VK);
+            double *Sbar = (double *)malloc(sizeof(double) * VK);
+            double *gS = (double *)malloc(sizeof(double) * VK);
+            double *d = (double *)malloc(sizeof(double) * K);
+            double *gd = (double *)malloc(sizeof(double) * K);
+            double *gdn = (double *)malloc(sizeof(double) * K);
+            double *kt = (double *)malloc(sizeof(double) * K);
+            double *dbar = (double *)malloc(sizeof(double) * K);
+            double *gkt = (double *)malloc(sizeof(double) * K);
+            double *u = (double *)malloc(sizeof(double) * V);
+            double *ge = (double *)malloc(sizeof(double) * V);
+            if (!ckS || !ckd || !Sprev || !dtr || !S || !Sbar || !gS || !d || !gd || !gdn ||
+                !kt || !dbar || !gkt || !u || !ge) {
+                fail = 1;
+                goto done;
+            }
+            /* forward sweep, keeping segment-start checkpoints */
+            for (int j = 0; j < K; ++j) d[j] = d_in ? d_in[bh * K + j] : 1.0;
+            for (size_t i = 0; i < VK; ++i) S[i] = S_in ? S_in[bh * VK + i] : 0.0;
+            for (int t = 0; t < T; ++t) {
+                size_t th = ((size_t)b * T + t) * H + h;
+                if (t % SEG == 0) {
+                    memcpy(ckS + (size_t)(t / SEG) * VK, S, sizeof(double) * VK);
+                    memcpy(ckd + (size_t)(t / SEG) * K, d, sizeof(double) * K);
+                }
+                double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
+                phase1_step(P, k + th * K, beta[th], retention ? retention[th] : 1.0, d, kt, NULL, NULL);
+                phase2_step(K, V, alpha, beta[th], k + th * K, kt, v + th * V, S, u);
+            }
+            /* adjoints of the returned state and preconditioner */
+            for (size_t i = 0; i < VK; ++i) gS[i] = dS_out ? dS_out[bh * VK + i] : 0.0;
+            for (int j = 0; j < K; ++j) gd[j] = dd_out ? dd_out[bh * K + j] : 0.0;
+
+            for (int sgm = nseg - 1; sgm >= 0; --sgm) {
+                int t0 = sgm * SEG, t1 = t0 + SEG < T ? t0 + SEG : T;
+                /* replay the segment, recording S_{t-1} and d_t */
+                memcpy(S, ckS + (size_t)sgm * VK, sizeof(double) * VK);
+                memcpy(d, ckd + (size_t)sgm * K, sizeof(double) * K);
+                for (int t = t0; t < t1; ++t) {
+                    size_t th = ((size_t)b * T + t) * H + h;
+                    memcpy(Sprev + (size_t)(t - t0) * VK, S, sizeof(double) * VK);
+                    memcpy(dtr + (size_t)(t - t0) * K, d, sizeof(double) * K);
+                    double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
+                    phase1_step(P, k + th * K, beta[th], retention ? retention[th] : 1.0, d, kt, NULL, NULL);
+                    phase2_step(K, V, alpha, beta[th], k + th * K, kt, v + th * V, S, u);
+                }
+                for (int t = t1 - 1; t >= t0; --t) {
+                    size_t th = ((size_t)b * T + t) * H + h;
+                    const double *kk = k + th * K, *qq = q + th * K, *vv = v + th * V;
+                    const double *go = dO + th * V;
+                    const double bt = beta[th];
+                    const double r = retention ? retention[th] : 1.0;
+                    const double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
+                    const double *Sm1 = Sprev + (size_t)(t - t0) * VK;
+                    double *gk = dk + th * K;
+                    /* recompute this token's forward values from d_t and S_{t-1} */
+                    memcpy(d, dtr + (size_t)(t - t0) * K, sizeof(double) * K);
+                    p1_scalars sc;
+                    double *dcur = dtr + (size_t)(t - t0) * K; /* d_t (kept intact) */
+                    phase1_step(P, kk, bt, r, d, kt, dbar, &sc);       /* d now holds d_{t+1} */
+                    memcpy(Sbar, Sm1, sizeof(double) * VK);
+                    /* S_t = phase2(S_{t-1}); keep Sbar = alpha S_{t-1} separately */
+                    memcpy(S, Sm1, sizeof(double) * VK);
+                    phase2_step(K, V, alpha, bt, kk, kt, vv, S, u);     /* S = S_t, u = residual */
+                    for (size_t i = 0; i < VK; ++i) Sbar[i] *= alpha;
+
+                    for (int j = 0; j < K; ++j) gk[j] = 0.0;
+
+                    /* ---- phase-1 adjoint: d_{t+1} = clip(r d_t + c s) ---- */
+                    double g_r = 0.0, g_c = 0.0;
+                    for (int j = 0; j < K; ++j) {
+                        double g = gd[j];
+                        if (project && !(dbar[j] >= P->d_min && dbar[j] <= P->d_max)) g = 0.0;
+                        gd[j] = g;                       /* now adjoint of d_bar */
+                        g_r += g * dcur[j];
+                        g_c += g * kk[j] * kk[j];
+                    }
+                    double g_p = g_c * (-P->eta * sc.bp * sc.bp / sc.n);
+                    double g_n = -g_c * sc.c / sc.n;
+                    double g_bp = g_c * P->eta * (1.0 - 2.0 * sc.bp * sc.p) / sc.n;
+                    double g_nraw = (sc.n_raw >= P->eps) ? g_n : 0.0;
+                    double gbeta = P->beta_aware ? g_bp : 0.0;
+                    for (int j = 0; j < K; ++j) {
+                        double s = kk[j] * kk[j];
+                        double gs = sc.c * gd[j] + g_p * dcur[j] + g_nraw;
+                        gk[j] += 2.0 * kk[j] * gs;
+                        gdn[j] = r * gd[j] + g_p * s;   /* adjoint of d_t, phase-1 part */
+                    }
+                    if (dretention) dretention[th] = g_r;
+
+                    /* ---- phase-2 adjoint ---- */
+                    /* o = scale S_t q */
+                    for (int j = 0; j < K; ++j) dq[th * K + j] = 0.0;
+                    for (int a = 0; a < V; ++a) {
+                        double w = P->scale * go[a];
+                        for (int j = 0; j < K; ++j) {
+                            gS[(size_t)a * K + j] += w * qq[j];
+                            dq[th * K + j] += w * S[(size_t)a * K + j];
+                        }
+                    }
+                    /* S_t = Sbar + e k~^T, e = beta u */
+                    for (int j = 0; j < K; ++j) gkt[j] = 0.0;
+                    for (int a = 0; a < V; ++a) {
+                        double acc = 0.0, e = bt * u[a];
+                        for (int j = 0; j < K; ++j) {
+                            acc += gS[(size_t)a * K + j] * kt[j];
+                            gkt[j] += gS[(size_t)a * K + j] * e;
+                        }
+                        ge[a] = acc;
+                    }
+                    for (int a = 0; a < V; ++a) gbeta += ge[a] * u[a];
+                    /* u = v - Sbar k  (gu = beta ge) ; gS now becomes adjoint of Sbar */
+                    double g_alpha = 0.0;
+                    for (int a = 0; a < V; ++a) {
+                        double gu = bt * ge[a];
+                        dv[th * V + a] = gu;
+                        for (int j = 0; j < K; ++j) {
+                            gS[(size_t)a * K + j] -= gu * kk[j];
+                            gk[j] -= Sbar[(size_t)a * K + j] * gu;
+                        }
+                    }
+                    /* Sbar = alpha S_{t-1} */
+                    for (size_t i = 0; i < VK; ++i) { g_alpha += gS[i] * Sm1[i]; gS[i] *= alpha; }
+                    if (dlog_alpha) dlog_alpha[th] = log_alpha ? alpha * g_alpha : 0.0;
+                    dbeta[th] = gbeta;
+                    /* k~ = d_t (.) k */
+                    for (int j = 0; j < K; ++j) {
+                        gdn[j] += kk[j] * gkt[j];
+                        gk[j] += dcur[j] * gkt[j];
+                        gd[j] = gdn[j];
+                    }
+                }
+            }
+            memcpy(dS_in + bh * VK, gS, sizeof(double) * VK);
+            memcpy(dd_in + bh * K, gd, sizeof(double) * K);
+        done:
+            free(ckS); free(ckd); free(Sprev); free(dtr); free(S); free(Sbar); free(gS);
+            free(d); free(gd); free(gdn); free(kt); free(dbar); free(gkt); free(u); free(ge);
+        }
+    return fail ? -1 : 0;
+}

@@ -1,0 +1,425 @@
+"""Pins for the CPU oracle: every check compares it with something other than
+itself -- an identity the paper proves, a closed form, a special case with an
+independently coded recurrence, a brute-force computation, a second (chunkwise)
+implementation, or central finite differences."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import Hyper
+from paper_2605_13473_amd.inputs import make_stress_inputs
+from tests.chunk_model import chunk_fwd_chain, chunk_bwd_chain
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(B, T, H, K, V, seed=0, gated=True, unit_keys=True):
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((B, T, H, K))
+    k = rng.standard_normal((B, T, H, K))
+    if unit_keys:
+        k /= np.linalg.norm(k, axis=-1, keepdims=True)
+    v = rng.standard_normal((B, T, H, V))
+    beta = 1 / (1 + np.exp(-rng.standard_normal((B, T, H))))
+    g = -np.logaddexp(0, rng.standard_normal((B, T, H))) if gated else None
+    return q, k, v, beta, g
+
+
+# ---------------------------------------------------------------- phase 2 ----
+def test_write_key_equivalence_dense_preconditioner():
+    """Eq. (equiv_update): S - beta grad f(S) D with a dense diagonal D equals the
+    scaled-key write.  One token from a random state, ungated, eta irrelevant."""
+    B, T, H, K, V = 1, 1, 1, 7, 5
+    q, k, v, beta, _ = _rand(B, T, H, K, V, seed=1, gated=False, unit_keys=False)
+    rng = np.random.default_rng(2)
+    d0 = rng.uniform(0.5, 2.0, (B, H, K))
+    S0 = rng.standard_normal((B, H, V, K))
+    _, S1, _ = oracle.fwd(q, k, v, beta, d_in=d0, S_in=S0, hp=Hyper(scale=1.0))
+    kk, vv, S = k[0, 0, 0], v[0, 0, 0], S0[0, 0]
+    grad = np.outer(S @ kk - vv, kk)                       # grad of 1/2 |S k - v|^2
+    expect = S - beta[0, 0, 0] * grad @ np.diag(d0[0, 0])
+    np.testing.assert_allclose(S1[0, 0], expect, rtol=0, atol=1e-13)
+
+
+def _gated_deltanet(q, k, v, beta, g, scale):
+    """Independent recurrence: S <- S alpha (I - beta k k^T) + beta v k^T; o = scale S q."""
+    B, T, H, K = k.shape
+    V = v.shape[-1]
+    o = np.zeros((B, T, H, V))
+    S = np.zeros((B, H, V, K))
+    for b in range(B):
+        for h in range(H):
+            M = np.zeros((V, K))
+            for t in range(T):
+                a = 1.0 if g is None else np.exp(g[b, t, h])
+                kk = k[b, t, h]
+                M = M @ (a * (np.eye(K) - beta[b, t, h] * np.outer(kk, kk))) \
+                    + beta[b, t, h] * np.outer(v[b, t, h], kk)
+                o[b, t, h] = scale * M @ q[b, t, h]
+            S[b, h] = M
+    return o, S
+
+
+@pytest.mark.parametrize("gated", [True, False])
+def test_d_identically_one_is_gated_deltanet(gated):
+    """eta = 0 and d_in = 1 reduce OSDN to (gated) DeltaNet, the table of recurrences."""
+    q, k, v, beta, g = _rand(2, 40, 2, 6, 5, seed=3, gated=gated, unit_keys=False)
+    o, S, d = oracle.fwd(q, k, v, beta, log_alpha=g, hp=Hyper(eta=0.0, scale=0.37))
+    o2, S2 = _gated_deltanet(q, k, v, beta, g, 0.37)
+    np.testing.assert_allclose(o, o2, atol=1e-12)
+    np.testing.assert_allclose(S, S2, atol=1e-12)
+    assert np.all(d == 1.0)
+
+
+def test_recurrent_form_matrix_transition():
+    """Eq. (recurrent_form), gated version: S_t = S_{t-1} alpha (I - beta k k~^T) + beta v k~^T
+    with k~ taken from the oracle's own phase 1."""
+    q, k, v, beta, g = _rand(1, 30, 1, 5, 4, seed=4, unit_keys=False)
+    hp = Hyper(eta=0.5, scale=1.0)
+    kt, _ = oracle.precond(k, beta, hp=hp)
+    _, S, _ = oracle.fwd(q, k, v, beta, log_alpha=g, hp=hp)
+    M = np.zeros((4, 5))
+    for t in range(30):
+        a = np.exp(g[0, t, 0]); b = beta[0, t, 0]
+        M = M @ (a * (np.eye(5) - b * np.outer(k[0, t, 0], kt[0, t, 0]))) + b * np.outer(v[0, t, 0], kt[0, t, 0])
+    np.testing.assert_allclose(S[0, 0], M, atol=1e-12)
+
+
+def test_unit_step_unit_key_replaces_value():
+    """beta = 1, |k| = 1, d = 1: after the write, S_t k_t = v_t exactly (Appendix A.1)."""
+    q, k, v, beta, g = _rand(1, 12, 1, 6, 3, seed=5)
+    beta[:] = 1.0
+    for t in range(1, 13):
+        _, S, _ = oracle.fwd(q[:, :t], k[:, :t], v[:, :t], beta[:, :t], log_alpha=g[:, :t],
+                             hp=Hyper(eta=0.0))
+        np.testing.assert_allclose(S[0, 0] @ k[0, t - 1, 0], v[0, t - 1, 0], atol=1e-13)
+
+
+def test_scalar_alternating_toy_golden():
+    """K = V = 1, k = 1, v = (-1)^t, exact Newton step beta d = 1: the state alternates
+    between -1 and +1 (the counter-example after the token-local contraction theorem).
+    Values stored in tests/golden/scalar_alternating.txt."""
+    want = np.loadtxt(os.path.join(GOLDEN, "scalar_alternating.txt"), comments="#")
+    T = want.shape[0]
+    k = np.ones((1, T, 1, 1)); q = np.ones((1, T, 1, 1))
+    v = np.array([(-1.0) ** (t + 1) for t in range(T)]).reshape(1, T, 1, 1)
+    beta = np.full((1, T, 1), 0.5)
+    d0 = np.full((1, 1, 1), 2.0)                 # beta d = 1, the fixed point of the d update
+    o, S, d = oracle.fwd(q, k, v, beta, d_in=d0, hp=Hyper(scale=1.0, eta=0.003))
+    np.testing.assert_allclose(o[0, :, 0, 0], want[:, 1], atol=1e-14)
+    assert d[0, 0, 0] == 2.0                     # beta <d,k^2> = 1 leaves d unchanged
+
+
+@pytest.mark.parametrize("gated", [False, True])
+def test_residual_contraction_ratio(gated):
+    """|S_t k_t - v_t|^2 / |Sbar k_t - v_t|^2 = (1 - beta <d_t,k_t^2>)^2 for any key norm,
+    with Sbar = alpha_t S_{t-1} (proof of the hypergradient lemma; post-gate form)."""
+    q, k, v, beta, g = _rand(1, 25, 1, 6, 4, seed=6, gated=gated, unit_keys=False)
+    hp = Hyper(eta=0.4)
+    kt, _, traj = oracle.precond(k, beta, hp=hp, want_traj=True)
+    for t in range(1, 25):
+        ga = None if g is None else g[:, :t]
+        gb = None if g is None else g[:, :t + 1]
+        _, Sprev, _ = oracle.fwd(q[:, :t], k[:, :t], v[:, :t], beta[:, :t], log_alpha=ga, hp=hp)
+        _, Snow, _ = oracle.fwd(q[:, :t + 1], k[:, :t + 1], v[:, :t + 1], beta[:, :t + 1],
+                                log_alpha=gb, hp=hp)
+        a = 1.0 if g is None else np.exp(g[0, t, 0])
+        kk, vv = k[0, t, 0], v[0, t, 0]
+        num = np.sum((Snow[0, 0] @ kk - vv) ** 2)
+        den = np.sum((a * Sprev[0, 0] @ kk - vv) ** 2)
+        ratio = (1 - beta[0, t, 0] * np.dot(traj[0, t, 0], kk ** 2)) ** 2
+        np.testing.assert_allclose(num / den, ratio, rtol=1e-10)
+
+
+def test_monotone_descent_inside_box():
+    """Unit keys, d in [0.5, 2], beta in (0,1): the contraction factor is < 1 at every token."""
+    q, k, v, beta, g = _rand(1, 200, 2, 8, 4, seed=7)
+    _, _, traj = oracle.precond(k, beta, hp=Hyper(eta=1.0), want_traj=True)
+    fac = (1 - beta * np.einsum("bthk,bthk->bth", traj, k ** 2)) ** 2
+    assert np.all(fac < 1.0)
+    assert traj.min() >= 0.5 and traj.max() <= 2.0
+
+
+def test_repeated_keys_corollary():
+    """Block-orthogonal repeated keys: prod_c F_c(S_T)/F_c(S_0) = prod_t q_t."""
+    rng = np.random.default_rng(8)
+    K, V, ncls, T = 6, 3, 3, 17
+    keys = np.zeros((ncls, K))
+    for c in range(ncls):
+        blk = rng.standard_normal(2)
+        keys[c, 2 * c:2 * c + 2] = blk / np.linalg.norm(blk)
+    vals = rng.standard_normal((ncls, V))
+    cls = np.concatenate([np.arange(ncls), rng.integers(0, ncls, T - ncls)])
+    k = keys[cls].reshape(1, T, 1, K); v = vals[cls].reshape(1, T, 1, V)
+    q = np.zeros_like(k)
+    beta = rng.uniform(0.2, 0.9, (1, T, 1))
+    S0 = rng.standard_normal((1, 1, V, K))
+    hp = Hyper(eta=0.8)
+    _, _, traj = oracle.precond(k, beta, hp=hp, want_traj=True)
+    _, S_T, _ = oracle.fwd(q, k, v, beta, S_in=S0, hp=hp)
+    F = lambda S, c: 0.5 * np.sum((S @ keys[c] - vals[c]) ** 2)
+    lhs = np.prod([F(S_T[0, 0], c) / F(S0[0, 0], c) for c in range(ncls)])
+    rhs = np.prod((1 - beta[0, :, 0] * np.einsum("tk,tk->t", traj[0, :, 0], k[0, :, 0] ** 2)) ** 2)
+    np.testing.assert_allclose(lhs, rhs, rtol=1e-10)
+
+
+# ---------------------------------------------------------------- phase 1 ----
+def _h_from_definition(S, k, v, beta, d):
+    """h_t(d) = [f_t(S_t) - f_t(S_{t-1})] / |grad f_t(S_{t-1})|_F^2 with S_t from the write."""
+    f = lambda M: 0.5 * np.sum((M @ k - v) ** 2)
+    u = v - S @ k
+    S1 = S + beta * np.outer(u, d * k)
+    grad = -np.outer(u, k)
+    return (f(S1) - f(S)) / np.sum(grad ** 2)
+
+
+def test_hypergradient_closed_form_and_step():
+    """The closed form of h_t, its gradient (finite differences of the *definition*), and
+    the unprojected update d - eta grad h (Lemma 4.1, Eq. (dt_update)) against the oracle."""
+    rng = np.random.default_rng(9)
+    K, V = 6, 4
+    S = rng.standard_normal((V, K)); k = rng.standard_normal(K); v = rng.standard_normal(V)
+    beta, d = 0.63, rng.uniform(0.5, 2.0, K)
+    h = _h_from_definition(S, k, v, beta, d)
+    closed = ((1 - beta * np.dot(d, k ** 2)) ** 2 - 1) / (2 * np.dot(k, k))
+    np.testing.assert_allclose(h, closed, rtol=1e-11)
+    grad = np.zeros(K)
+    for j in range(K):
+        e = np.zeros(K); e[j] = 1e-6
+        grad[j] = (_h_from_definition(S, k, v, beta, d + e) - _h_from_definition(S, k, v, beta, d - e)) / 2e-6
+    eta = 0.7
+    _, d1 = oracle.precond(k.reshape(1, 1, 1, K), np.full((1, 1, 1), beta), d_in=d.reshape(1, 1, K),
+                           hp=Hyper(eta=eta, d_min=1.0, d_max=0.0))          # no projection
+    np.testing.assert_allclose(d1[0, 0], d - eta * grad, rtol=1e-7, atol=1e-9)
+    # matrix form of Eq. (dt_update)
+    s = k ** 2; n = np.dot(k, k)
+    dbar = (np.eye(K) - eta * beta ** 2 / n * np.outer(s, s)) @ d + eta * beta / n * s
+    np.testing.assert_allclose(d1[0, 0], dbar, rtol=1e-13)
+
+
+def test_projection_retention_and_flags():
+    """Clamp after every step; APF multiplies the old d while <d,k^2> uses the un-retained d;
+    r == 1 is bit-identical to no retention; non-beta-aware puts 1 for beta in the d update
+    only; eps floors the squared norm (Listing 1 semantics), coded here step by step."""
+    rng = np.random.default_rng(10)
+    B, T, H, K = 2, 50, 2, 5
+    k = rng.standard_normal((B, T, H, K)) * rng.choice([1e-4, 1.0], (B, T, H, 1))
+    beta = rng.uniform(0.05, 0.95, (B, T, H))
+    k[0, :, :, 0] += 5.0            # batch 0: unit keys with one dominant coordinate and small
+    k[0] /= np.linalg.norm(k[0], axis=-1, keepdims=True)   # beta: fixed point 1/beta > d_max
+    beta[0] *= 0.3
+    r = rng.uniform(0.8, 1.0, (B, T, H))
+    r[0] = 1.0
+    d0 = rng.uniform(0.5, 2.0, (B, H, K))
+    for aware in (True, False):
+        hp = Hyper(eta=1.3, beta_aware=aware)
+        kt, dT = oracle.precond(k, beta, retention=r, d_in=d0, hp=hp)
+        d = d0.copy()
+        hit_lo = hit_hi = False
+        for t in range(T):
+            np.testing.assert_allclose(kt[:, t], d * k[:, t], rtol=1e-15)
+            s = k[:, t] ** 2
+            n = np.maximum(s.sum(-1), 1e-6)
+            bp = beta[:, t] if aware else np.ones_like(beta[:, t])
+            step = 1.3 * bp * (1 - bp * (d * s).sum(-1)) / n
+            d = np.clip(r[:, t][..., None] * d + step[..., None] * s, 0.5, 2.0)
+            hit_lo |= bool((d == 0.5).any()); hit_hi |= bool((d == 2.0).any())
+        np.testing.assert_allclose(dT, d, rtol=1e-13)
+        assert hit_lo and (hit_hi or not aware)             # both faces of the box were hit
+    a = oracle.precond(k, beta, retention=np.ones_like(beta), d_in=d0, hp=Hyper(eta=0.3))
+    b = oracle.precond(k, beta, retention=None, d_in=d0, hp=Hyper(eta=0.3))
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_pure_retention_closed_form():
+    """eta = 0, r < 1: d_T = max(d_min, prod r * d_0)."""
+    rng = np.random.default_rng(11)
+    k = rng.standard_normal((1, 300, 1, 4)); beta = rng.uniform(0.1, 0.9, (1, 300, 1))
+    r = rng.uniform(0.99, 1.0, (1, 300, 1)); d0 = rng.uniform(0.5, 2.0, (1, 1, 4))
+    _, dT = oracle.precond(k, beta, retention=r, d_in=d0, hp=Hyper(eta=0.0))
+    np.testing.assert_allclose(dT, np.maximum(0.5, np.prod(r) * d0), rtol=1e-12)
+
+
+def test_fixed_point_of_beta_aware_update():
+    """beta <d,k^2> = 1 leaves d unchanged (the post-gate-regret fixed point)."""
+    k = np.zeros((1, 5, 1, 4)); k[..., 1] = 1.0
+    beta = np.full((1, 5, 1), 0.8); d0 = np.array([[[1.0, 1.25, 0.7, 1.9]]])
+    _, dT = oracle.precond(k, beta, d_in=d0, hp=Hyper(eta=0.5))
+    assert np.array_equal(dT, d0)
+
+
+# ---------------------------------------------------- chunkwise == recurrent ----
+def _run_chunk_model(q, k, v, beta, g, d0, S0, hp, C):
+    B, T, H, K = k.shape
+    kt, _ = oracle.precond(k, beta, d_in=d0, hp=hp)
+    scale = K ** -0.5 if hp.scale is None else hp.scale
+    o = np.empty_like(v); S = np.empty((B, H, v.shape[-1], K))
+    for b in range(B):
+        for h in range(H):
+            o[b, :, h], S[b, h] = chunk_fwd_chain(q[b, :, h], k[b, :, h], kt[b, :, h], v[b, :, h],
+                                                  beta[b, :, h], g[b, :, h], S0[b, h], scale, C)
+    return o, S
+
+
+@pytest.mark.parametrize("strong_decay", [False, True])
+def test_chunkwise_form_matches_token_loop(strong_decay):
+    """The WY chunk form with decay ratios equals the token loop, also when the cumulative
+    log-decay over one chunk is about -50 (no clamp on gamma anywhere)."""
+    x = make_stress_inputs(2, 192, 2, 16, 12, seed=12)
+    x = {n: (None if a is None else a.astype(np.float64)) for n, a in x.items()}
+    g = x["log_alpha"] * (1.0 if strong_decay else 0.05)
+    if strong_decay:
+        assert g[:, :64].sum(1).min() < -40
+    hp = Hyper(eta=0.5)
+    o, S, _ = oracle.fwd(x["q"], x["k"], x["v"], x["beta"], log_alpha=g, d_in=x["d_in"],
+                         S_in=x["S_in"], hp=hp)
+    o2, S2 = _run_chunk_model(x["q"], x["k"], x["v"], x["beta"], g, x["d_in"], x["S_in"], hp, 64)
+    np.testing.assert_allclose(o, o2, atol=1e-11)
+    np.testing.assert_allclose(S, S2, atol=1e-11)
+
+
+def test_ut_inverse_brute_force_and_wy_product():
+    """(I + tril(beta K K~^T,-1))^-1 by Gauss-Jordan equals forward substitution, and the
+    ordered product of (I - beta_i k_i k~_i^T) equals I - W^T K~ (Appendix A.2)."""
+    rng = np.random.default_rng(13)
+    C, K = 24, 7
+    Km = rng.standard_normal((C, K)); Kt = Km * rng.uniform(0.5, 2.0, (C, K))
+    beta = rng.uniform(0.1, 0.9, C)
+    A = np.tril(beta[:, None] * (Km @ Kt.T), -1)
+    # Gauss-Jordan on [I + A | I]
+    aug = np.hstack([np.eye(C) + A, np.eye(C)])
+    for i in range(C):
+        aug[i] /= aug[i, i]
+        for r in range(C):
+            if r != i:
+                aug[r] -= aug[r, i] * aug[i]
+    Tgj = aug[:, C:]
+    Tfs = np.zeros((C, C))
+    for i in range(C):                                  # forward substitution, row by row
+        Tfs[i] = np.eye(C)[i] - A[i, :i] @ Tfs[:i]
+    np.testing.assert_allclose(Tgj, Tfs, atol=1e-11)
+    W = Tfs @ (beta[:, None] * Km)
+    prod = np.eye(K)
+    for i in range(C):
+        prod = prod @ (np.eye(K) - beta[i] * np.outer(Km[i], Kt[i]))
+    np.testing.assert_allclose(prod, np.eye(K) - W.T @ Kt, atol=1e-11)
+
+
+def test_resume_from_carried_state():
+    """One call on T tokens equals two calls on T/2 with (S, d) carried."""
+    x = make_stress_inputs(1, 64, 2, 8, 6, seed=14, retention=0.97)
+    x = {n: (None if a is None else a.astype(np.float64)) for n, a in x.items()}
+    hp = Hyper(eta=0.6)
+    full = oracle.fwd(x["q"], x["k"], x["v"], x["beta"], x["log_alpha"], x["retention"],
+                      x["d_in"], x["S_in"], hp)
+    h = 32
+    a = oracle.fwd(x["q"][:, :h], x["k"][:, :h], x["v"][:, :h], x["beta"][:, :h],
+                   x["log_alpha"][:, :h], x["retention"][:, :h], x["d_in"], x["S_in"], hp)
+    b = oracle.fwd(x["q"][:, h:], x["k"][:, h:], x["v"][:, h:], x["beta"][:, h:],
+                   x["log_alpha"][:, h:], x["retention"][:, h:], a[2], a[1], hp)
+    np.testing.assert_allclose(np.concatenate([a[0], b[0]], 1), full[0], atol=1e-13)
+    np.testing.assert_allclose(b[1], full[1], atol=1e-13)
+    np.testing.assert_allclose(b[2], full[2], atol=1e-14)
+
+
+# ---------------------------------------------------------------- backward ----
+def _loss(x, hp, wO, wS, wd):
+    o, S, d = oracle.fwd(x["q"], x["k"], x["v"], x["beta"], x["log_alpha"], x["retention"],
+                         x["d_in"], x["S_in"], hp)
+    return (o * wO).sum() + (S * wS).sum() + (d * wd).sum()
+
+
+@pytest.mark.parametrize("case", ["plain", "clamp_active", "non_beta_aware", "ungated_noapf"])
+def test_backward_against_central_differences(case):
+    """Every gradient the oracle returns, against central finite differences of its forward
+    (fp64, h = 1e-6), including through the box projection (clamp-active case: coordinates
+    sitting on a face get zero gradient, free ones pass through)."""
+    B, T, H, K, V = 1, 70, 2, 5, 4          # T > 64 crosses a replay-segment boundary
+    gated = case != "ungated_noapf"
+    x = make_stress_inputs(B, T, H, K, V, seed=15, gated=gated,
+                           retention={"ungated_noapf": 0.0, "clamp_active": 0.85}.get(case, 0.95))
+    x = {n: (None if a is None else a.astype(np.float64)) for n, a in x.items()}
+    eta = {"plain": 0.05, "clamp_active": 2.5, "non_beta_aware": 0.05, "ungated_noapf": 0.05}[case]
+    if case == "plain":
+        x["d_in"] = 1.0 + 0.2 * (x["d_in"] - 1.25)       # stay inside the box
+    hp = Hyper(eta=eta, beta_aware=(case != "non_beta_aware"))
+    rng = np.random.default_rng(16)
+    wO = x["dO"]; wS = rng.standard_normal(x["S_in"].shape); wd = rng.standard_normal(x["d_in"].shape)
+    g = oracle.bwd(x["q"], x["k"], x["v"], x["beta"], wO, x["log_alpha"], x["retention"],
+                   x["d_in"], x["S_in"], dS_out=wS, dd_out=wd, hp=hp)
+    if case == "clamp_active":
+        _, _, traj = oracle.precond(x["k"], x["beta"], x["retention"], x["d_in"], hp, want_traj=True)
+        frac = np.mean((traj == 0.5) | (traj == 2.0))
+        assert frac > 0.05, frac
+    names = {"q": "dq", "k": "dk", "v": "dv", "beta": "dbeta", "log_alpha": "dlog_alpha",
+             "retention": "dretention", "d_in": "dd_in", "S_in": "dS_in"}
+    h = 1e-6
+    for name, gname in names.items():
+        if x[name] is None:
+            assert g[gname] is None
+            continue
+        flat = x[name].reshape(-1)
+        idx = rng.choice(flat.size, size=min(flat.size, 25), replace=False)
+        for i in idx:
+            old = flat[i]
+            flat[i] = old + h; lp = _loss(x, hp, wO, wS, wd)
+            flat[i] = old - h; lm = _loss(x, hp, wO, wS, wd)
+            flat[i] = old
+            fd = (lp - lm) / (2 * h)
+            an = g[gname].reshape(-1)[i]
+            assert abs(fd - an) <= 2e-6 * max(1.0, abs(fd)), (case, name, i, fd, an)
+
+
+def test_backward_clamp_tie_passes_gradient():
+    """A coordinate whose unprojected value lands exactly on a face passes its gradient
+    (inclusive convention): k has an exact zero there, r = 1, d_in on the face."""
+    K = 3
+    k = np.array([0.0, 0.6, 0.8]).reshape(1, 1, 1, K)
+    beta = np.full((1, 1, 1), 0.5); d0 = np.array([[[0.5, 1.0, 1.2]]])
+    q = np.ones((1, 1, 1, K)); v = np.ones((1, 1, 1, 2)); dO = np.zeros((1, 1, 1, 2))
+    wd = np.array([[[1.0, 0.0, 0.0]]])
+    g = oracle.bwd(q, k, v, beta, dO, d_in=d0, dd_out=wd, hp=Hyper(eta=0.1))
+    assert g["dd_in"][0, 0, 0] == 1.0
+
+
+def test_chain_rule_through_key_scaling():
+    """Section 4.5: with the phase-1 update frozen (eta = 0, r = 1), dL/dd_in = sum_t k_t . dL/dk~_t
+    and dL/dk_t = (read-side part) + d . dL/dk~_t, using the chunk model's dL/dk~."""
+    x = make_stress_inputs(1, 64, 1, 8, 6, seed=17)
+    x = {n: (None if a is None else a.astype(np.float64)) for n, a in x.items()}
+    hp = Hyper(eta=0.0)
+    g = oracle.bwd(x["q"], x["k"], x["v"], x["beta"], x["dO"], x["log_alpha"], None,
+                   x["d_in"], x["S_in"], hp=hp)
+    d = x["d_in"][0, 0]
+    kt = x["k"][0, :, 0] * d
+    dq, dk, dkt, dv, dbeta, dg, dS0 = chunk_bwd_chain(
+        x["q"][0, :, 0], x["k"][0, :, 0], kt, x["v"][0, :, 0], x["beta"][0, :, 0],
+        x["log_alpha"][0, :, 0], x["S_in"][0, 0], 8 ** -0.5, x["dO"][0, :, 0],
+        np.zeros_like(x["S_in"][0, 0]), C=64)
+    np.testing.assert_allclose(g["dd_in"][0, 0], (x["k"][0, :, 0] * dkt).sum(0), atol=1e-11)
+    np.testing.assert_allclose(g["dk"][0, :, 0], dk + d * dkt, atol=1e-11)
+
+
+def test_chunk_backward_model_matches_oracle():
+    """The chunk-level backward algebra (used as the blueprint for the GPU kernels) against
+    the oracle's token-level reverse mode, two chunks, strong gates, eta = 0."""
+    x = make_stress_inputs(1, 128, 1, 8, 6, seed=18)
+    x = {n: (None if a is None else a.astype(np.float64)) for n, a in x.items()}
+    rng = np.random.default_rng(19)
+    wS = rng.standard_normal(x["S_in"].shape)
+    hp = Hyper(eta=0.0)
+    g = oracle.bwd(x["q"], x["k"], x["v"], x["beta"], x["dO"], x["log_alpha"], None,
+                   x["d_in"], x["S_in"], dS_out=wS, hp=hp)
+    d = x["d_in"][0, 0]
+    kt = x["k"][0, :, 0] * d
+    dq, dk, dkt, dv, dbeta, dg, dS0 = chunk_bwd_chain(
+        x["q"][0, :, 0], x["k"][0, :, 0], kt, x["v"][0, :, 0], x["beta"][0, :, 0],
+        x["log_alpha"][0, :, 0], x["S_in"][0, 0], 8 ** -0.5, x["dO"][0, :, 0], wS[0, 0], C=64)
+    np.testing.assert_allclose(g["dq"][0, :, 0], dq, atol=1e-11)
+    np.testing.assert_allclose(g["dv"][0, :, 0], dv, atol=1e-11)
+    np.testing.assert_allclose(g["dbeta"][0, :, 0], dbeta, atol=1e-11)
+    np.testing.assert_allclose(g["dlog_alpha"][0, :, 0], dg, atol=1e-11)
+    np.testing.assert_allclose(g["dS_in"][0, 0], dS0, atol=1e-11)
+    np.testing.assert_allclose(g["dk"][0, :, 0], dk + d * dkt, atol=1e-11)
