@@ -1,0 +1,128 @@
+/*
+ * libosdn -- OSDN hot path on one AMD MI355X (gfx950): the chunkwise-parallel gated
+ * delta-rule recurrence whose write-side key is rescaled per feature by an online
+ * diagonal preconditioner, forward and backward.
+ *
+ * What is computed (paper: "OSDN: Improving Delta Rule with Provable Online
+ * Preconditioning in Linear Attention"), per batch b and head h independently, for
+ * t = 1..T, with S in R^{V x K}, d in R^K:
+ *
+ *   phase 1 (Algorithm 1; Eq. (dt_update), with retention Eq. (dt_update_apf)):
+ *       k~_t = d_t (.) k_t
+ *       s = k_t (.) k_t,  n = max(sum s, eps),  p = <d_t, s>,  b' = beta_t (or 1 if !beta_aware)
+ *       d_{t+1} = clip( r_t d_t + eta b' (1 - b' p)/n * s , d_min, d_max )
+ *   phase 2 (Eq. (equiv_update)/(recurrent_form), gated as in Appendix B.1):
+ *       S_t = alpha_t S_{t-1} + beta_t (v_t - alpha_t S_{t-1} k_t) k~_t^T ,  alpha_t = exp(log_alpha_t)
+ *       o_t = scale * S_t q_t
+ *
+ * The library evaluates phase 2 in the chunkwise WY/UT form (Appendix A.2, B.1) with
+ * chunk length 64; results equal the recurrence up to floating-point reassociation.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; tensors are contiguous,
+ *     row-major, in the stated layout.  Inputs are never written; outputs must not alias
+ *     inputs or each other.  Optional pointers may be NULL where stated.
+ *   - q, k, v, o, dO, dq, dk, dv, k_tilde have element type params->io_dtype (fp32 or
+ *     bf16).  beta, log_alpha, retention, every d and every S (and their gradients) are
+ *     always fp32: the recurrent state and the preconditioner are kept in fp32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and return without synchronising.
+ *   - Return value: OSDN_OK (0) or a negative osdn_status.  On an argument error nothing
+ *     is launched.  osdn_strerror() gives a static description.
+ *   - The library keeps no global state and allocates no device memory: scratch comes
+ *     from the caller's `workspace` (256-byte aligned, at least osdn_workspace_bytes()).
+ *   - Supported shapes: chunk == 64; T % 64 == 0 for osdn_fwd/osdn_bwd (any T >= 1 for
+ *     osdn_precond_update when d_ckpt is NULL); K in {64, 128}; V a multiple of 64 up to
+ *     512; B, H >= 1.  Anything else returns OSDN_ERR_SHAPE.
+ */
+#ifndef OSDN_H
+#define OSDN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { OSDN_F32 = 0, OSDN_BF16 = 1 } osdn_dtype;
+
+typedef enum {
+    OSDN_OK = 0,
+    OSDN_ERR_NULL = -1,       /* a required pointer is NULL */
+    OSDN_ERR_SHAPE = -2,      /* unsupported B/T/H/K/V/chunk */
+    OSDN_ERR_DTYPE = -3,      /* io_dtype is neither OSDN_F32 nor OSDN_BF16 */
+    OSDN_ERR_WORKSPACE = -4,  /* workspace too small or not 256-byte aligned */
+    OSDN_ERR_PARAM = -5,      /* eta < 0, eps <= 0, or a non-finite scalar */
+    OSDN_ERR_LAUNCH = -6      /* the HIP runtime reported a launch error */
+} osdn_status;
+
+typedef struct {
+    int32_t B, T, H, K, V, chunk;   /* chunk must be 64 */
+    int32_t io_dtype;               /* osdn_dtype */
+    float scale;                    /* multiplies q in the read-out (Listing 1: K^-0.5) */
+    float eta;                      /* online step size of the d update (paper: 0.003) */
+    float d_min, d_max;             /* box of the projection (paper: 0.5, 2.0); d_min > d_max => none */
+    float eps;                      /* floor of the squared key norm (Listing 1: 1e-6) */
+    int32_t beta_aware;             /* 1: beta enters the d update (default); 0: replaced by 1 there */
+} osdn_params;
+
+/* Bytes of scratch osdn_fwd needs (for_backward == 0) or osdn_fwd followed by osdn_bwd
+ * needs (for_backward != 0).  Returns 0 if the parameters are invalid. */
+size_t osdn_workspace_bytes(const osdn_params *p, int for_backward);
+
+const char *osdn_strerror(int status);
+
+/*
+ * Phase 1 alone (Algorithm 1 / Eq. (dt_update_apf)); also the preconditioner half of a
+ * streaming decode step (T may be 1).
+ *   k         [B,T,H,K] io_dtype   keys (read side)
+ *   beta      [B,T,H]   fp32
+ *   retention [B,T,H]   fp32 or NULL (=> r = 1)
+ *   d_in      [B,H,K]   fp32 or NULL (=> ones); not projected on entry
+ *   k_tilde   [B,T,H,K] io_dtype   out: d_t (.) k_t, rounded once from fp32
+ *   d_out     [B,H,K]   fp32       out: d after the last token
+ *   d_ckpt    [B,H,T/64,K] fp32 or NULL   out: d at the start of every chunk (needs T % 64 == 0)
+ */
+int osdn_precond_update(const osdn_params *p, const void *k, const float *beta,
+                        const float *retention, const float *d_in, void *k_tilde, float *d_out,
+                        float *d_ckpt, void *stream);
+
+/*
+ * Forward (both phases).
+ *   q, k      [B,T,H,K] io_dtype ;  v [B,T,H,V] io_dtype
+ *   beta      [B,T,H] fp32 ; log_alpha [B,T,H] fp32 (<= 0) or NULL (=> ungated, alpha = 1)
+ *   retention, d_in as above ;  S_in [B,H,V,K] fp32 or NULL (=> zeros)
+ *   o         [B,T,H,V] io_dtype  out
+ *   S_out     [B,H,V,K] fp32      out: state after the last token
+ *   d_out     [B,H,K]   fp32      out
+ *   workspace: scratch; when osdn_bwd follows, pass the same buffer, untouched, to it.
+ */
+int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+             const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+             void *o, float *S_out, float *d_out, void *workspace, size_t workspace_bytes,
+             void *stream);
+
+/*
+ * Backward of osdn_fwd (Section 4.5: phase 2 yields dL/dk~; dL/dd_t = k_t (.) dL/dk~_t,
+ * dL/dk_t += d_t (.) dL/dk~_t; reverse sweep through the projected affine d recurrence,
+ * whose projection passes gradient where d_min <= unprojected value <= d_max).
+ *   forward inputs exactly as given to osdn_fwd, and the workspace it filled
+ *   dO        [B,T,H,V] io_dtype   gradient of o
+ *   dS_out    [B,H,V,K] fp32 or NULL (=> 0)   gradient of S_out
+ *   dd_out    [B,H,K]   fp32 or NULL (=> 0)   gradient of d_out
+ *   dq, dk    [B,T,H,K] io_dtype out ; dv [B,T,H,V] io_dtype out
+ *   dbeta     [B,T,H] fp32 out ; dlog_alpha [B,T,H] fp32 out (may be NULL iff log_alpha is)
+ *   dretention [B,T,H] fp32 out (may be NULL iff retention is)
+ *   dd_in     [B,H,K] fp32 out ; dS_in [B,H,V,K] fp32 out
+ */
+int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+             const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+             const void *dO, const float *dS_out, const float *dd_out, void *dq, void *dk, void *dv,
+             float *dbeta, float *dlog_alpha, float *dretention, float *dd_in, float *dS_in,
+             void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OSDN_H */

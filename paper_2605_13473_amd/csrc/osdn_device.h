@@ -1,0 +1,190 @@
+// Device-side building blocks shared by the OSDN kernels (gfx950 / CDNA4, wave64).
+//
+//  - element types: float and __bf16; all accumulation is fp32
+//  - MFMA 16x16 tiles: v_mfma_f32_16x16x32_bf16 (8 bf16 per lane and operand) and
+//    v_mfma_f32_16x16x4_f32 (1 float per lane and operand).  Both leave the 16x16
+//    result in the same place: lane l holds rows 4*(l/16)+r, r=0..3, of column l%16,
+//    so every kernel is written once and instantiated for both element types.
+//  - wave-level sums and scans by DPP / shuffles
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace osdn {
+
+typedef __bf16 bf16;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+constexpr int C = 64;          // chunk length
+constexpr int NT = 256;        // threads per workgroup of the chunk kernels (4 waves)
+
+// 16 bytes of padding per LDS row keeps 16-lane fragment reads on distinct banks
+template <typename T> struct Pad { static constexpr int v = 16 / sizeof(T); };
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16 x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float x) { return (bf16)x; }  // RNE
+
+// ------------------------------------------------------------------ MFMA ----
+// Operand conventions: an operand tile is addressed as X(row, k) where `row` is the
+// M index (A operand) or the N index (B operand) and k the contraction index.
+// KCONTIG = true : X(row,k) = base[row*ld + k]   (k contiguous)
+// KCONTIG = false: X(row,k) = base[k*ld + row]   (stored transposed)
+template <typename T> struct Mfma;
+
+template <> struct Mfma<float> {
+    static constexpr int KSTEP = 4;
+    typedef float Frag;
+    template <bool KCONTIG>
+    static __device__ __forceinline__ Frag load(const float *base, int ld, int lane) {
+        const int row = lane & 15, kk = lane >> 4;
+        return KCONTIG ? base[row * ld + kk] : base[kk * ld + row];
+    }
+    static __device__ __forceinline__ f32x4 mma(Frag a, Frag b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+};
+
+template <> struct Mfma<bf16> {
+    static constexpr int KSTEP = 32;
+    typedef bf16x8 Frag;
+    template <bool KCONTIG>
+    static __device__ __forceinline__ Frag load(const bf16 *base, int ld, int lane) {
+        const int row = lane & 15, kk = (lane >> 4) * 8;
+        if (KCONTIG) {
+            return *reinterpret_cast<const bf16x8 *>(base + row * ld + kk);   // 16-byte aligned by layout
+        } else {
+            Frag f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = base[(kk + e) * ld + row];
+            return f;
+        }
+    }
+    static __device__ __forceinline__ f32x4 mma(Frag a, Frag b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+// acc(16x16) += A(16 x kdim) * B(16 x kdim)^T ; A, B point at (row 0, k 0) of their tiles
+template <typename T, bool A_KC, bool B_KC>
+__device__ __forceinline__ void mma_tile(f32x4 &acc, const T *A, int lda, const T *B, int ldb,
+                                         int kdim, int lane) {
+    constexpr int KS = Mfma<T>::KSTEP;
+    for (int k0 = 0; k0 < kdim; k0 += KS) {
+        typename Mfma<T>::Frag a = Mfma<T>::template load<A_KC>(A_KC ? A + k0 : A + k0 * lda, lda, lane);
+        typename Mfma<T>::Frag b = Mfma<T>::template load<B_KC>(B_KC ? B + k0 : B + k0 * ldb, ldb, lane);
+        acc = Mfma<T>::mma(a, b, acc);
+    }
+}
+
+// position of accumulator element r of this lane inside its 16x16 tile
+__device__ __forceinline__ int acc_row(int lane, int r) { return ((lane >> 4) << 2) + r; }
+__device__ __forceinline__ int acc_col(int lane) { return lane & 15; }
+
+// store a 16x16 accumulator tile into LDS as dst[row*ld + col]  (four scalar stores)
+template <typename T>
+__device__ __forceinline__ void store_tile(T *dst, int ld, f32x4 acc, int lane) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) dst[acc_row(lane, r) * ld + acc_col(lane)] = from_f32<T>(acc[r]);
+}
+// store transposed, dst[col*ld + row]: the four rows of a lane are contiguous
+template <typename T>
+__device__ __forceinline__ void store_tile_t(T *dst, int ld, f32x4 acc, int lane);
+template <>
+__device__ __forceinline__ void store_tile_t<float>(float *dst, int ld, f32x4 acc, int lane) {
+    *reinterpret_cast<f32x4 *>(dst + acc_col(lane) * ld + acc_row(lane, 0)) = acc;
+}
+template <>
+__device__ __forceinline__ void store_tile_t<bf16>(bf16 *dst, int ld, f32x4 acc, int lane) {
+    bf16x4 v;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) v[r] = (bf16)acc[r];
+    *reinterpret_cast<bf16x4 *>(dst + acc_col(lane) * ld + acc_row(lane, 0)) = v;
+}
+
+// ------------------------------------------------------- global <-> LDS ----
+// element e (compile-time after unrolling) of a 16-byte vector of T held in a uint4, as fp32
+__device__ __forceinline__ uint32_t vec_word(const uint4 &v, int w) {
+    return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w;
+}
+template <typename T> __device__ __forceinline__ float vec_get(const uint4 &v, int e);
+template <> __device__ __forceinline__ float vec_get<float>(const uint4 &v, int e) {
+    return __builtin_bit_cast(float, vec_word(v, e));
+}
+template <> __device__ __forceinline__ float vec_get<bf16>(const uint4 &v, int e) {
+    const uint32_t w = vec_word(v, e >> 1);
+    return __builtin_bit_cast(float, (e & 1) ? (w & 0xffff0000u) : (w << 16));
+}
+
+// copy a [rows x cols] tile of T from global (row stride g_ld elements) into LDS (row
+// stride s_ld), 16 bytes per thread and step; cols must be a multiple of 16/sizeof(T)
+template <typename T>
+__device__ __forceinline__ void load_tile(T *s, int s_ld, const T *g, size_t g_ld, int rows,
+                                          int cols, int tid, int nthreads) {
+    constexpr int VN = 16 / sizeof(T);
+    const int vpr = cols / VN;
+    for (int i = tid; i < rows * vpr; i += nthreads) {
+        const int r = i / vpr, c = (i % vpr) * VN;
+        *reinterpret_cast<uint4 *>(s + r * s_ld + c) =
+            *reinterpret_cast<const uint4 *>(g + (size_t)r * g_ld + c);
+    }
+}
+template <typename T>
+__device__ __forceinline__ void store_tile_global(T *g, size_t g_ld, const T *s, int s_ld, int rows,
+                                                  int cols, int tid, int nthreads) {
+    constexpr int VN = 16 / sizeof(T);
+    const int vpr = cols / VN;
+    for (int i = tid; i < rows * vpr; i += nthreads) {
+        const int r = i / vpr, c = (i % vpr) * VN;
+        *reinterpret_cast<uint4 *>(g + (size_t)r * g_ld + c) =
+            *reinterpret_cast<const uint4 *>(s + r * s_ld + c);
+    }
+}
+
+// --------------------------------------------------------- wave helpers ----
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_f32(float src, float old = 0.f) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old),
+                                                                 __builtin_bit_cast(int, src), CTRL,
+                                                                 ROW_MASK, 0xF, false));
+}
+// sum over the 64 lanes, returned to every lane (fixed reduction tree => deterministic)
+__device__ __forceinline__ float wave_sum(float x) {
+    x += dpp_f32<0xB1>(x);         // quad_perm [1,0,3,2]
+    x += dpp_f32<0x4E>(x);         // quad_perm [2,3,0,1]
+    x += dpp_f32<0x141>(x);        // row_half_mirror
+    x += dpp_f32<0x140>(x);        // row_mirror: every lane of a row of 16 holds the row sum
+    x += dpp_f32<0x142, 0xA>(x);   // row_bcast:15 into rows 1 and 3
+    x += dpp_f32<0x143, 0xC>(x);   // row_bcast:31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+// inclusive prefix sum over the 64 lanes of a wave
+__device__ __forceinline__ float wave_cumsum(float x, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        float y = __shfl_up(x, off, 64);
+        if (lane >= off) x += y;
+    }
+    return x;
+}
+// exclusive-from-the-right ("suffix") inclusive sum: out[l] = sum_{m >= l} x[m]
+__device__ __forceinline__ float wave_suffix_sum(float x, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        float y = __shfl_down(x, off, 64);
+        if (lane + off < 64) x += y;
+    }
+    return x;
+}
+
+// offsets into the caller's [B,T,H,D] tensors and the library's per-chunk tiles
+__device__ __forceinline__ size_t tok_off(int b, int t, int h, int T, int H, int D) {
+    return (((size_t)b * T + t) * H + h) * (size_t)D;
+}
+
+}  // namespace osdn

@@ -1,0 +1,74 @@
+// Argument blocks and launchers of the OSDN kernels (internal to the library).
+#pragma once
+#include "osdn_device.h"
+
+namespace osdn {
+
+struct PrecondArgs {
+    int B, T, H, K;
+    float eta, d_min, d_max, eps;
+    int beta_aware;
+    const void *k;            // [B,T,H,K] io
+    const float *beta;        // [B,T,H]
+    const float *retention;   // [B,T,H] or null
+    const float *d_in;        // [B,H,K] or null
+    void *k_tilde;            // [B,T,H,K] io
+    float *d_out;             // [B,H,K]
+    float *d_ckpt;            // [B,H,T/64,K] or null
+};
+
+struct PrecondBwdArgs {
+    int B, T, H, K;
+    float eta, d_min, d_max, eps;
+    int beta_aware;
+    const void *k;
+    const float *beta, *retention, *d_ckpt;
+    const float *dkt;         // [B,T,H,K] fp32: dL/dk~ from phase 2
+    const float *dk_read;     // [B,T,H,K] fp32: read-side dL/dk from phase 2
+    const float *dd_out;      // [B,H,K] or null
+    void *dk;                 // [B,T,H,K] io
+    float *dbeta;             // [B,T,H] in/out
+    float *dretention;        // [B,T,H] or null
+    float *dd_in;             // [B,H,K]
+};
+
+// Everything the chunkwise (phase 2) kernels need.  Per-chunk tiles live in the workspace
+// in [B,H,N,rows,cols] order (one contiguous tile per chunk and head).
+struct ChunkArgs {
+    int B, T, H, K, V, N;
+    float scale;
+    // caller tensors
+    const void *q, *k, *v;            // [B,T,H,*] io
+    const float *beta, *log_alpha;    // [B,T,H]; log_alpha may be null
+    const float *S_in;                // [B,H,V,K] or null
+    void *o;                          // [B,T,H,V] io
+    float *S_out;                     // [B,H,V,K]
+    // workspace (forward)
+    void *kt;                         // [B,T,H,K] io      k~
+    void *Tm;                         // [B,H,N,64,64] io  (I + A)^-1
+    void *W;                          // [B,H,N,64,K] io
+    void *U;                          // [B,H,N,64,V] io
+    void *Et;                         // [B,H,N,V,64] io   E transposed
+    void *S_ckpt;                     // [B,H,N,V,K] io    state at the start of each chunk (null: not kept)
+    // backward
+    const void *dO;                   // [B,T,H,V] io
+    const float *dS_out;              // [B,H,V,K] or null
+    void *dEl;                        // [B,H,N,64,V] io   local part of dE: scale * P^T dO
+    void *dEt;                        // [B,H,N,V,64] io   dE transposed (complete)
+    void *dS_ckpt;                    // [B,H,N,V,K] io    adjoint of the state at the END of each chunk
+    float *dS_in;                     // [B,H,V,K]
+    void *dq, *dv;                    // io
+    float *dk_read, *dkt;             // [B,T,H,K] fp32
+    float *dbeta, *dlog_alpha;        // [B,T,H]; dlog_alpha may be null
+};
+
+int launch_precond_fwd(const PrecondArgs &a, bool bf16_io, hipStream_t st);
+int launch_precond_bwd(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
+int launch_chunk_prep(const ChunkArgs &a, bool bf16_io, hipStream_t st);
+int launch_state_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st);
+int launch_output_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st);
+int launch_bwd_local(const ChunkArgs &a, bool bf16_io, hipStream_t st);
+int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st);
+int launch_bwd_post(const ChunkArgs &a, bool bf16_io, hipStream_t st);
+
+}  // namespace osdn
