@@ -1,7 +1,539 @@
-// placeholder: backward kernels of phase 2 (to be filled in)
+// Phase 2 backward of OSDN in chunkwise form.  The paper prints only the chain rule through
+// k~ = d . k (Section 4.5); the chunk-level adjoints below are plain matrix calculus on the
+// forward formulas (Appendix A.2 / B.1), per chunk, with S the state at the start of the
+// chunk, dS' the adjoint of the state at its end, G the in-chunk cumulative log-decay,
+// gamma = e^G, rho = e^{G_C - G}, Gamma_ij = e^{G_i - G_j}:
+//
+//   forward:  A = tril(beta_i Gamma_ij <k_i,k~_j>, -1), T = (I+A)^-1, R0 = V - gamma.(K S^T),
+//             E = T (beta . R0), P = tril(Gamma . Q K~^T), O = scale[gamma.(Q S^T) + P E],
+//             S' = gamma_C S + E^T (rho . K~)
+//   bwd_local (parallel):  dEl = scale P^T dO
+//   bwd_chain (sequential, right to left, per (b, h, slice of V)):
+//             dE = dEl + (rho . K~) dS'^T ;  dS = gamma_C dS' + scale dO^T (gamma . Q) - dE^T W
+//   bwd_post  (parallel):  dR = T^T dE ; dV = beta . dR ; dA = -tril(dR E^T, -1) ;
+//             dP = scale tril(dO E^T) ; cA = dA . beta_i Gamma ; cP = dP . Gamma ;
+//             dQ = cP K~ + scale gamma . (dO S) ; dK = cA K~ - gamma beta . (dR S) ;
+//             dK~ = cA^T K + cP^T Q + rho . (E dS') ;
+//             dbeta_i = <dR_i, R0_i> + sum_j dA_ij Gamma_ij <k_i,k~_j> ;
+//             dG from every place G enters; dlog_alpha = suffix sums of dG inside the chunk.
 #include "osdn_kernels.h"
+
 namespace osdn {
-int launch_bwd_local(const ChunkArgs &, bool, hipStream_t) { return -1; }
-int launch_bwd_chain(const ChunkArgs &, bool, hipStream_t) { return -1; }
-int launch_bwd_post(const ChunkArgs &, bool, hipStream_t) { return -1; }
+
+constexpr int VS = 32;      // rows of S owned by one workgroup of the chain kernel
+
+// sum over the 16 lanes of a DPP row (lanes sharing lane>>4), returned to all of them
+__device__ __forceinline__ float row16_sum(float x) {
+    x += dpp_f32<0xB1>(x);
+    x += dpp_f32<0x4E>(x);
+    x += dpp_f32<0x141>(x);
+    x += dpp_f32<0x140>(x);
+    return x;
+}
+
+// ------------------------------------------------------------- bwd_local ----
+template <typename T, int K>
+__global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
+    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
+    __shared__ __attribute__((aligned(16))) T Qs[C * LDK];
+    __shared__ __attribute__((aligned(16))) T Kts[C * LDK];
+    __shared__ __attribute__((aligned(16))) T PT[C * LDC];      // scale * P^T
+    __shared__ __attribute__((aligned(16))) T dOs[C * LDC];
+    __shared__ __attribute__((aligned(16))) T Os[C * LDC];
+    __shared__ float Gs[C];
+
+    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
+    const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+    const size_t tstride = a.H;
+
+    if (wave == 0) {
+        const float g = a.log_alpha ? a.log_alpha[tok0 + (size_t)lane * tstride] : 0.f;
+        Gs[lane] = wave_cumsum(g, lane);
+    }
+    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, NT);
+    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, NT);
+    __syncthreads();
+    for (int idx = wave; idx < 16; idx += 4) {
+        const int ib = idx >> 2, jb = idx & 3;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (jb <= ib) {
+            mma_tile<T, true, true>(acc, Qs + ib * 16 * LDK, LDK, Kts + jb * 16 * LDK, LDK, K, lane);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = ib * 16 + acc_row(lane, r), j = jb * 16 + acc_col(lane);
+                acc[r] = (j <= i) ? a.scale * __expf(Gs[i] - Gs[j]) * acc[r] : 0.f;
+            }
+        }
+        store_tile_t(PT + jb * 16 * LDC + ib * 16, LDC, acc, lane);
+    }
+    const int k0 = (wave * 16) / Mfma<T>::KSTEP * Mfma<T>::KSTEP;   // P^T rows 16*wave.. are zero left of here
+    for (int v0 = 0; v0 < a.V; v0 += C) {
+        __syncthreads();
+        load_tile(dOs, LDC, static_cast<const T *>(a.dO) + tok0 * a.V + v0, tstride * a.V, C, C, tid, NT);
+        __syncthreads();
+#pragma unroll
+        for (int vt = 0; vt < 4; ++vt) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            mma_tile<T, true, false>(acc, PT + wave * 16 * LDC + k0, LDC, dOs + k0 * LDC + vt * 16, LDC,
+                                     C - k0, lane);
+            store_tile(Os + wave * 16 * LDC + vt * 16, LDC, acc, lane);
+        }
+        __syncthreads();
+        store_tile_global(static_cast<T *>(a.dEl) + bhn * C * a.V + v0, (size_t)a.V, Os, LDC, C, C, tid, NT);
+    }
+}
+
+// ------------------------------------------------------------- bwd_chain ----
+template <typename T, int K>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void bwd_chain_kernel(ChunkArgs a) {
+    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDU = VS + PAD;
+    constexpr int VN = 16 / sizeof(T);
+    constexpr int NKT = K / 64;
+    constexpr int NW = C * K / VN / NT;
+    constexpr int NU = C * VS / VN / NT;
+    constexpr bool PF = sizeof(T) == 2;         // prefetch the next chunk through registers
+    __shared__ __attribute__((aligned(16))) T Kts[C * LDK];     // rho . K~
+    __shared__ __attribute__((aligned(16))) T Wtt[K * LDC];     // -W^T
+    __shared__ __attribute__((aligned(16))) T Qtt[K * LDC];     // (scale gamma . Q)^T
+    __shared__ __attribute__((aligned(16))) T dOt[VS * LDC];    // dO^T (this slice of V)
+    __shared__ __attribute__((aligned(16))) T dEls[C * LDU];    // dEl (this slice)
+    __shared__ __attribute__((aligned(16))) T dSb[VS * LDK];    // dS' in the I/O type
+    __shared__ __attribute__((aligned(16))) T dEt[VS * LDC];    // dE^T
+
+    const int vs = blockIdx.x * VS, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const size_t bh = (size_t)b * a.H + h;
+    const size_t tstride = a.H;
+
+    f32x4 dS[2][NKT];
+#pragma unroll
+    for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+        for (int qn = 0; qn < NKT; ++qn)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int v = vs + vt * 16 + acc_row(lane, r), c = (wave * NKT + qn) * 16 + acc_col(lane);
+                dS[vt][qn][r] = a.dS_out ? a.dS_out[(bh * a.V + v) * K + c] : 0.f;
+            }
+
+    uint4 kreg[NW], wreg[NW], qreg[NW], oreg[NU], ereg[NU];
+    float greg;
+#define OSDN_CHAIN_LOAD(n_)                                                                      \
+    {                                                                                            \
+        const size_t bhn_ = bh * a.N + (n_);                                                     \
+        const size_t tok_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                      \
+        const T *kg = static_cast<const T *>(a.kt) + tok_ * K;                                   \
+        const T *qg = static_cast<const T *>(a.q) + tok_ * K;                                    \
+        const T *wg = static_cast<const T *>(a.W) + bhn_ * C * K;                                \
+        const T *og = static_cast<const T *>(a.dO) + tok_ * a.V + vs;                            \
+        const T *eg = static_cast<const T *>(a.dEl) + bhn_ * C * a.V + vs;                       \
+        _Pragma("unroll") for (int m = 0; m < NW; ++m) {                                         \
+            const int i = tid + m * NT, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
+            kreg[m] = *reinterpret_cast<const uint4 *>(kg + (size_t)r * tstride * K + c);        \
+            qreg[m] = *reinterpret_cast<const uint4 *>(qg + (size_t)r * tstride * K + c);        \
+            wreg[m] = *reinterpret_cast<const uint4 *>(wg + (size_t)r * K + c);                  \
+        }                                                                                        \
+        _Pragma("unroll") for (int m = 0; m < NU; ++m) {                                         \
+            const int i = tid + m * NT, r = i / (VS / VN), c = (i % (VS / VN)) * VN;             \
+            oreg[m] = *reinterpret_cast<const uint4 *>(og + (size_t)r * tstride * a.V + c);      \
+            ereg[m] = *reinterpret_cast<const uint4 *>(eg + (size_t)r * a.V + c);                \
+        }                                                                                        \
+        greg = a.log_alpha ? a.log_alpha[tok_ + (size_t)lane * tstride] : 0.f;                   \
+    }
+    if (PF) OSDN_CHAIN_LOAD(a.N - 1)
+
+    for (int n = a.N - 1; n >= 0; --n) {
+        const size_t bhn = bh * a.N + n;
+        if (!PF) OSDN_CHAIN_LOAD(n)
+        const float G = wave_cumsum(greg, lane);
+        const float GC = __shfl(G, 63, 64);
+#pragma unroll
+        for (int m = 0; m < NW; ++m) {
+            const int i = tid + m * NT, r = i / (K / VN), c = (i % (K / VN)) * VN;
+            const float Gr = __shfl(G, r, 64);
+            const float rho = __expf(GC - Gr), sg = a.scale * __expf(Gr);
+#pragma unroll
+            for (int e = 0; e < VN; ++e) {
+                Kts[r * LDK + c + e] = from_f32<T>(rho * vec_get<T>(kreg[m], e));
+                Wtt[(c + e) * LDC + r] = from_f32<T>(-vec_get<T>(wreg[m], e));
+                Qtt[(c + e) * LDC + r] = from_f32<T>(sg * vec_get<T>(qreg[m], e));
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < NU; ++m) {
+            const int i = tid + m * NT, r = i / (VS / VN), c = (i % (VS / VN)) * VN;
+            *reinterpret_cast<uint4 *>(dEls + r * LDU + c) = ereg[m];
+#pragma unroll
+            for (int e = 0; e < VN; ++e) dOt[(c + e) * LDC + r] = from_f32<T>(vec_get<T>(oreg[m], e));
+        }
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+            for (int qn = 0; qn < NKT; ++qn)
+                store_tile(dSb + vt * 16 * LDK + (wave * NKT + qn) * 16, LDK, dS[vt][qn], lane);
+        __syncthreads();
+        store_tile_global(static_cast<T *>(a.dS_ckpt) + (bhn * a.V + vs) * K, (size_t)K, dSb, LDK, VS, K, tid, NT);
+        if (PF && n > 0) OSDN_CHAIN_LOAD(n - 1)
+        // dE = dEl + (rho . K~) dS'^T   (rows 16*wave .. +16), kept transposed
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            mma_tile<T, true, true>(acc, Kts + wave * 16 * LDK, LDK, dSb + vt * 16 * LDK, LDK, K, lane);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[r] += to_f32(dEls[(wave * 16 + acc_row(lane, r)) * LDU + vt * 16 + acc_col(lane)]);
+            store_tile_t(dEt + vt * 16 * LDC + wave * 16, LDC, acc, lane);
+        }
+        __syncthreads();
+        store_tile_global(static_cast<T *>(a.dEt) + (bhn * a.V + vs) * C, (size_t)C, dEt, LDC, VS, C, tid, NT);
+        // dS <- gamma_C dS' + scale dO^T (gamma . Q) - dE^T W
+        const float gC = __expf(GC);
+#pragma unroll
+        for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+            for (int qn = 0; qn < NKT; ++qn) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dS[vt][qn][r] *= gC;
+                const int ct = (wave * NKT + qn) * 16;
+                mma_tile<T, true, true>(dS[vt][qn], dOt + vt * 16 * LDC, LDC, Qtt + ct * LDC, LDC, C, lane);
+                mma_tile<T, true, true>(dS[vt][qn], dEt + vt * 16 * LDC, LDC, Wtt + ct * LDC, LDC, C, lane);
+            }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+        for (int qn = 0; qn < NKT; ++qn)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int v = vs + vt * 16 + acc_row(lane, r), c = (wave * NKT + qn) * 16 + acc_col(lane);
+                a.dS_in[(bh * a.V + v) * K + c] = dS[vt][qn][r];
+            }
+}
+
+// -------------------------------------------------------------- bwd_post ----
+// One workgroup per chunk and head.  V is walked in slabs of VB columns; the slab buffers
+// are reused for Q and K~ once the walk is over.
+template <typename T, int K>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void bwd_post_kernel(ChunkArgs a) {
+    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
+    constexpr int VB = sizeof(T) == 2 ? 64 : 32;        // slab width
+    constexpr int LDV = VB + PAD;
+    constexpr int NKT = K / 64;                          // [64 x K] column tiles per wave
+    constexpr int NVT = VB / 16;
+    constexpr int KS = Mfma<T>::KSTEP;
+    // persistent
+    __shared__ __attribute__((aligned(16))) T Ks[C * LDK];
+    __shared__ __attribute__((aligned(16))) T Tt[C * LDC];
+    __shared__ float Gs[C], Bs[C];
+    __shared__ float red[4 * C];                         // [4][64] partial sums across tiles / waves
+    __shared__ float red2[4 * C];
+    __shared__ float red3[4 * C];
+    __shared__ float dbeta_s[C];
+    __shared__ float sdot[NT / 64];
+    // slab buffers, later Q / K~ / cA / cP
+    constexpr int SLAB_ELEMS = 3 * C * LDV + 2 * VB * LDC + 2 * VB * LDK;
+    constexpr int POST_ELEMS = 2 * C * LDK + 2 * C * LDC;
+    constexpr int POOL = SLAB_ELEMS > POST_ELEMS ? SLAB_ELEMS : POST_ELEMS;
+    __shared__ __attribute__((aligned(16))) T pool[POOL];
+    T *dOs = pool;                      // [64][LDV]  dO slab (natural), later dV staging
+    T *Vs = dOs + C * LDV;              // [64][LDV]  V slab
+    T *dRs = Vs + C * LDV;              // [64][LDV]  dR slab (natural)
+    T *Ets = dRs + C * LDV;             // [VB][LDC]  E^T slab
+    T *dEts = Ets + VB * LDC;           // [VB][LDC]  dE^T slab
+    T *Ss = dEts + VB * LDC;            // [VB][LDK]  S slab
+    T *dSs = Ss + VB * LDK;             // [VB][LDK]  dS' slab
+    T *Qs = pool;                       // after the walk
+    T *Kts = Qs + C * LDK;
+    T *cAs = Kts + C * LDK;             // [64][LDC]
+    T *cPs = cAs + C * LDC;             // [64][LDC]
+
+    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
+    const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+    const size_t tstride = a.H;
+
+    if (wave == 0) {
+        const size_t th = tok0 + (size_t)lane * tstride;
+        const float g = a.log_alpha ? a.log_alpha[th] : 0.f;
+        Gs[lane] = wave_cumsum(g, lane);
+        Bs[lane] = a.beta[th];
+    }
+    load_tile(Ks, LDK, static_cast<const T *>(a.k) + tok0 * K, tstride * K, C, K, tid, NT);
+    load_tile(Tt, LDC, static_cast<const T *>(a.Tm) + bhn * C * C, (size_t)C, C, C, tid, NT);
+
+    // accumulators over the walk
+    f32x4 dP[3], dA[3];                 // the lower tiles idx = wave, wave+4, wave+8 (< 10)
+    f32x4 dQg[4][NKT], dKg[4][NKT], dKr[4][NKT];   // [row block][column tile of this wave]
+    float dbeta_part[4] = {0.f, 0.f, 0.f, 0.f};     // rows 16*wave + acc_row(lane, r)
+    float ss_part = 0.f;                // <dS', S>
+#pragma unroll
+    for (int t = 0; t < 3; ++t) { dP[t] = f32x4{0.f, 0.f, 0.f, 0.f}; dA[t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+        for (int qn = 0; qn < NKT; ++qn) {
+            dQg[ib][qn] = f32x4{0.f, 0.f, 0.f, 0.f};
+            dKg[ib][qn] = f32x4{0.f, 0.f, 0.f, 0.f};
+            dKr[ib][qn] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+
+    for (int v0 = 0; v0 < a.V; v0 += VB) {
+        __syncthreads();
+        load_tile(dOs, LDV, static_cast<const T *>(a.dO) + tok0 * a.V + v0, tstride * a.V, C, VB, tid, NT);
+        load_tile(Vs, LDV, static_cast<const T *>(a.v) + tok0 * a.V + v0, tstride * a.V, C, VB, tid, NT);
+        load_tile(Ets, LDC, static_cast<const T *>(a.Et) + (bhn * a.V + v0) * C, (size_t)C, VB, C, tid, NT);
+        load_tile(dEts, LDC, static_cast<const T *>(a.dEt) + (bhn * a.V + v0) * C, (size_t)C, VB, C, tid, NT);
+        load_tile(Ss, LDK, static_cast<const T *>(a.S_ckpt) + (bhn * a.V + v0) * K, (size_t)K, VB, K, tid, NT);
+        load_tile(dSs, LDK, static_cast<const T *>(a.dS_ckpt) + (bhn * a.V + v0) * K, (size_t)K, VB, K, tid, NT);
+        __syncthreads();
+        // <dS', S> over this slab
+        for (int idx = tid; idx < VB * K; idx += NT) {
+            const int r = idx / K, c = idx % K;
+            ss_part += to_f32(Ss[r * LDK + c]) * to_f32(dSs[r * LDK + c]);
+        }
+        // (1) dR = T^T dE, rows j = 16*wave.. ; (2) R0 = V - gamma . (K S^T), same rows
+        {
+            const int k0 = (wave * 16) / KS * KS;       // T[i][j] = 0 for i < j
+#pragma unroll
+            for (int vt = 0; vt < NVT; ++vt) {
+                f32x4 dr = {0.f, 0.f, 0.f, 0.f}, ks = {0.f, 0.f, 0.f, 0.f};
+                mma_tile<T, false, true>(dr, Tt + k0 * LDC + wave * 16, LDC, dEts + vt * 16 * LDC + k0, LDC,
+                                         C - k0, lane);
+                mma_tile<T, true, true>(ks, Ks + wave * 16 * LDK, LDK, Ss + vt * 16 * LDK, LDK, K, lane);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int i = wave * 16 + acc_row(lane, r), c = vt * 16 + acc_col(lane);
+                    const float r0 = to_f32(Vs[i * LDV + c]) - __expf(Gs[i]) * ks[r];
+                    dbeta_part[r] += dr[r] * r0;
+                }
+                store_tile(dRs + wave * 16 * LDV + vt * 16, LDV, dr, lane);
+            }
+        }
+        __syncthreads();
+        // (3,4) dP += dO E^T, dA -= dR E^T on the lower tiles
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            const int idx = wave + 4 * t;
+            if (idx < 10) {
+                const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
+                const int jb = idx - (ib * (ib + 1)) / 2;
+                for (int kk = 0; kk < VB; kk += KS) {
+                    typename Mfma<T>::Frag fb = Mfma<T>::template load<false>(Ets + kk * LDC + jb * 16, LDC, lane);
+                    typename Mfma<T>::Frag fo = Mfma<T>::template load<true>(dOs + ib * 16 * LDV + kk, LDV, lane);
+                    typename Mfma<T>::Frag fr = Mfma<T>::template load<true>(dRs + ib * 16 * LDV + kk, LDV, lane);
+                    dP[t] = Mfma<T>::mma(fo, fb, dP[t]);
+                    dA[t] = Mfma<T>::mma(fr, fb, dA[t]);
+                }
+            }
+        }
+        // (5,6,7) dQg += dO S ; dKg += dR S ; dKr += E dS'
+#pragma unroll
+        for (int qn = 0; qn < NKT; ++qn) {
+            const int ct = (wave * NKT + qn) * 16;
+            for (int kk = 0; kk < VB; kk += KS) {
+                typename Mfma<T>::Frag fs = Mfma<T>::template load<false>(Ss + kk * LDK + ct, LDK, lane);
+                typename Mfma<T>::Frag fd = Mfma<T>::template load<false>(dSs + kk * LDK + ct, LDK, lane);
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) {
+                    typename Mfma<T>::Frag fo = Mfma<T>::template load<true>(dOs + ib * 16 * LDV + kk, LDV, lane);
+                    typename Mfma<T>::Frag fr = Mfma<T>::template load<true>(dRs + ib * 16 * LDV + kk, LDV, lane);
+                    typename Mfma<T>::Frag fe = Mfma<T>::template load<false>(Ets + kk * LDC + ib * 16, LDC, lane);
+                    dQg[ib][qn] = Mfma<T>::mma(fo, fs, dQg[ib][qn]);
+                    dKg[ib][qn] = Mfma<T>::mma(fr, fs, dKg[ib][qn]);
+                    dKr[ib][qn] = Mfma<T>::mma(fe, fd, dKr[ib][qn]);
+                }
+            }
+        }
+        __syncthreads();
+        // dV = beta . dR for this slab, staged through the dO buffer
+        for (int idx = tid; idx < C * VB; idx += NT) {
+            const int r = idx / VB, c = idx % VB;
+            dOs[r * LDV + c] = from_f32<T>(Bs[r] * to_f32(dRs[r * LDV + c]));
+        }
+        __syncthreads();
+        store_tile_global(static_cast<T *>(a.dv) + tok0 * a.V + v0, tstride * a.V, dOs, LDV, C, VB, tid, NT);
+    }
+    __syncthreads();
+    // ---- after the walk: Q, K~ into the pool ----
+    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, NT);
+    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, NT);
+    for (int idx = tid; idx < C * C; idx += NT) {       // upper triangle of cA, cP is zero
+        const int i = idx >> 6, j = idx & 63;
+        cAs[i * LDC + j] = from_f32<T>(0.f);
+        cPs[i * LDC + j] = from_f32<T>(0.f);
+    }
+    ss_part = wave_sum(ss_part);
+    if (lane == 0) sdot[wave] = ss_part;
+    for (int idx = tid; idx < 4 * C; idx += NT) { red[idx] = 0.f; red2[idx] = 0.f; red3[idx] = 0.f; }
+    __syncthreads();
+    // ---- lower tiles: A0, P, X, cA, cP ----
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        const int idx = wave + 4 * t;
+        if (idx < 10) {
+            const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
+            const int jb = idx - (ib * (ib + 1)) / 2;
+            f32x4 kk = {0.f, 0.f, 0.f, 0.f}, qk = {0.f, 0.f, 0.f, 0.f};
+            mma_tile<T, true, true>(kk, Ks + ib * 16 * LDK, LDK, Kts + jb * 16 * LDK, LDK, K, lane);
+            mma_tile<T, true, true>(qk, Qs + ib * 16 * LDK, LDK, Kts + jb * 16 * LDK, LDK, K, lane);
+            f32x4 ca, cp;
+            float colx = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = ib * 16 + acc_row(lane, r), j = jb * 16 + acc_col(lane);
+                const float gam = (j <= i) ? __expf(Gs[i] - Gs[j]) : 0.f;
+                const float da = (j < i) ? -dA[t][r] : 0.f;             // dA_ij
+                const float dp = (j <= i) ? a.scale * dP[t][r] : 0.f;   // dP_ij
+                const float a0 = gam * kk[r];                            // A_ij / beta_i
+                const float x = da * Bs[i] * a0 + dp * gam * qk[r];      // dA.A + dP.P
+                ca[r] = da * Bs[i] * gam;
+                cp[r] = dp * gam;
+                const float rs_a = row16_sum(da * a0);
+                const float rs_x = row16_sum(x);
+                if (acc_col(lane) == 0) {
+                    red[jb * C + i] = rs_a;          // each (jb, i) is written by exactly one lane
+                    red2[jb * C + i] = rs_x;
+                }
+                colx += x;
+            }
+            colx += __shfl_xor(colx, 16, 64);
+            colx += __shfl_xor(colx, 32, 64);
+            if (lane < 16) red3[ib * C + jb * 16 + lane] = colx;     // each (ib, j) written once
+            store_tile(cAs + ib * 16 * LDC + jb * 16, LDC, ca, lane);
+            store_tile(cPs + ib * 16 * LDC + jb * 16, LDC, cp, lane);
+        }
+    }
+    // dbeta: the walk's part (rows 16*wave + acc_row) reduced over the 16 lanes of a row
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float s = row16_sum(dbeta_part[r]);
+        if (acc_col(lane) == 0) dbeta_s[wave * 16 + acc_row(lane, r)] = s;
+    }
+    __syncthreads();
+    // ---- dQ, dK (read side), dK~ and the inner products that enter dG ----
+    float tq[4][4], tk[4][4], tr[4][4];     // [row block][r]: partial row dots over this wave's columns
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { tq[ib][r] = 0.f; tk[ib][r] = 0.f; tr[ib][r] = 0.f; }
+    T *dq_g = static_cast<T *>(a.dq) + tok0 * K;
+    float *dk_g = a.dk_read + tok0 * K;
+    float *dkt_g = a.dkt + tok0 * K;
+#pragma unroll
+    for (int qn = 0; qn < NKT; ++qn) {
+        const int ct = (wave * NKT + qn) * 16;
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib) {
+            f32x4 aq = {0.f, 0.f, 0.f, 0.f}, ak = {0.f, 0.f, 0.f, 0.f}, at = {0.f, 0.f, 0.f, 0.f};
+            // cP K~ and cA K~: contraction over j <= i
+            const int kd = min(C, ((ib + 1) * 16 + KS - 1) / KS * KS);
+            for (int kk = 0; kk < kd; kk += KS) {
+                typename Mfma<T>::Frag fk = Mfma<T>::template load<false>(Kts + kk * LDK + ct, LDK, lane);
+                typename Mfma<T>::Frag fp = Mfma<T>::template load<true>(cPs + ib * 16 * LDC + kk, LDC, lane);
+                typename Mfma<T>::Frag fa = Mfma<T>::template load<true>(cAs + ib * 16 * LDC + kk, LDC, lane);
+                aq = Mfma<T>::mma(fp, fk, aq);
+                ak = Mfma<T>::mma(fa, fk, ak);
+            }
+            // cA^T K + cP^T Q: rows j = 16*ib.., contraction over i >= j
+            const int k0 = (ib * 16) / KS * KS;
+            for (int kk = k0; kk < C; kk += KS) {
+                typename Mfma<T>::Frag fat = Mfma<T>::template load<false>(cAs + kk * LDC + ib * 16, LDC, lane);
+                typename Mfma<T>::Frag fpt = Mfma<T>::template load<false>(cPs + kk * LDC + ib * 16, LDC, lane);
+                typename Mfma<T>::Frag fkk = Mfma<T>::template load<false>(Ks + kk * LDK + ct, LDK, lane);
+                typename Mfma<T>::Frag fqq = Mfma<T>::template load<false>(Qs + kk * LDK + ct, LDK, lane);
+                at = Mfma<T>::mma(fat, fkk, at);
+                at = Mfma<T>::mma(fpt, fqq, at);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = ib * 16 + acc_row(lane, r), c = ct + acc_col(lane);
+                const float gam = __expf(Gs[i]), rho = __expf(Gs[C - 1] - Gs[i]);
+                const float gq = a.scale * gam * dQg[ib][qn][r];        // gamma . d(gamma Q)
+                const float gk = -Bs[i] * gam * dKg[ib][qn][r];          // gamma . d(gamma K)
+                const float gr = rho * dKr[ib][qn][r];                   // rho . d(rho K~)
+                const float qv = to_f32(Qs[i * LDK + c]), kv = to_f32(Ks[i * LDK + c]),
+                            ktv = to_f32(Kts[i * LDK + c]);
+                tq[ib][r] += gq * qv;
+                tk[ib][r] += gk * kv;
+                tr[ib][r] += gr * ktv;
+                dq_g[(size_t)i * tstride * K + c] = from_f32<T>(aq[r] + gq);
+                dk_g[(size_t)i * tstride * K + c] = ak[r] + gk;
+                dkt_g[(size_t)i * tstride * K + c] = at[r] + gr;
+            }
+        }
+    }
+    __syncthreads();        // red/red2/red3 consumers below; also everyone is done with Qs/Ks/Kts
+    // per-row sums across the 16 lanes of a row, then across waves through LDS
+    float *pq = reinterpret_cast<float *>(pool);      // [4 waves][64 rows] x 3, reusing the pool
+    float *pk = pq + 4 * C, *pr = pk + 4 * C;
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float sq = row16_sum(tq[ib][r]), sk = row16_sum(tk[ib][r]), sr = row16_sum(tr[ib][r]);
+            if (acc_col(lane) == 0) {
+                const int i = ib * 16 + acc_row(lane, r);
+                pq[wave * C + i] = sq; pk[wave * C + i] = sk; pr[wave * C + i] = sr;
+            }
+        }
+    __syncthreads();
+    if (wave == 0) {
+        const int i = lane;
+        const float t_q = pq[i] + pq[C + i] + pq[2 * C + i] + pq[3 * C + i];
+        const float t_k = pk[i] + pk[C + i] + pk[2 * C + i] + pk[3 * C + i];
+        const float t_r = pr[i] + pr[C + i] + pr[2 * C + i] + pr[3 * C + i];
+        const float rowa = red[i] + red[C + i] + red[2 * C + i] + red[3 * C + i];
+        const float rowx = red2[i] + red2[C + i] + red2[2 * C + i] + red2[3 * C + i];
+        const float colx = red3[i] + red3[C + i] + red3[2 * C + i] + red3[3 * C + i];
+        const size_t th = tok0 + (size_t)i * tstride;
+        a.dbeta[th] = dbeta_s[i] + rowa;
+        if (a.dlog_alpha) {
+            float dG = rowx - colx + t_q + t_k - t_r;
+            const float tr_sum = wave_sum(t_r);
+            const float ss = sdot[0] + sdot[1] + sdot[2] + sdot[3];
+            if (i == C - 1) dG += tr_sum + __expf(Gs[C - 1]) * ss;
+            a.dlog_alpha[th] = wave_suffix_sum(dG, lane);
+        }
+    }
+}
+
+// -------------------------------------------------------------- launchers ----
+template <typename T>
+static int launch_local_t(const ChunkArgs &a, hipStream_t st) {
+    dim3 grid(a.N, a.H, a.B), block(NT);
+    if (a.K == 64) hipLaunchKernelGGL((bwd_local_kernel<T, 64>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((bwd_local_kernel<T, 128>), grid, block, 0, st, a);
+    else return -1;
+    return 0;
+}
+int launch_bwd_local(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
+    return bf16_io ? launch_local_t<bf16>(a, st) : launch_local_t<float>(a, st);
+}
+template <typename T>
+static int launch_chain_t(const ChunkArgs &a, hipStream_t st) {
+    dim3 grid(a.V / VS, a.H, a.B), block(NT);
+    if (a.K == 64) hipLaunchKernelGGL((bwd_chain_kernel<T, 64>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((bwd_chain_kernel<T, 128>), grid, block, 0, st, a);
+    else return -1;
+    return 0;
+}
+int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
+    return bf16_io ? launch_chain_t<bf16>(a, st) : launch_chain_t<float>(a, st);
+}
+template <typename T>
+static int launch_post_t(const ChunkArgs &a, hipStream_t st) {
+    dim3 grid(a.N, a.H, a.B), block(NT);
+    if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128>), grid, block, 0, st, a);
+    else return -1;
+    return 0;
+}
+int launch_bwd_post(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
+    return bf16_io ? launch_post_t<bf16>(a, st) : launch_post_t<float>(a, st);
+}
+
 }  // namespace osdn
