@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the OSDN hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input: osdn_fwd
+followed by osdn_bwd on the 1.3B-shaped configuration (B=4, T=4096, H=16, d_k=d_v=128,
+chunk 64, bf16 I/O, fp32 state and gates) -- the configuration the headline metric is quoted
+on.  Inputs are resident in HBM before the timed region.  Prints ONE JSON line with
+
+  value       whole-job tokens/s (B*T*steps / wall time between two device synchronisations)
+  roofline    the dominant kernel (largest share of the step), its algorithmic bytes or flops
+              per launch divided by its mean launch duration, measured with HIP events on the
+              stream the kernel runs on (second pass over the same steps, events enabled)
+  cpu_baseline  the fp64 CPU oracle timed on a bounded sample of the same workload
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_FLOPS = 2.5e15       # MI355X dense bf16 MFMA
+PEAK_HBM_BYTES = 8.0e12        # MI355X HBM3E
+PEAK_FP32_VALU = 157.3e12
+
+
+def kernel_models(cfg, es):
+    """Algorithmic work of each kernel per launch: (bound, amount, unit-per-second peak).
+    bytes = compulsory HBM traffic of the kernel's own inputs and outputs (every tensor
+    once); flops = MFMA flops of its contractions (triangular products at half)."""
+    B, T, H, K, V, C = cfg.B, cfg.T, cfg.H, cfg.K, cfg.V, 64
+    th = B * T * H                       # token-heads
+    nch = th // C                        # chunk-heads
+    g = 4                                # bytes of an fp32 gate
+    m = {}
+    # phase 1: read k, beta; write k~ ; sequential, bandwidth/latency bound
+    m["precond_fwd"] = ("hbm", th * (2 * K * es + g))
+    m["precond_bwd"] = ("hbm", th * (K * es + 2 * K * 4 + K * es + 3 * g))
+    # chunk_prep: read k, k~, v, beta, g ; write T, W, U
+    m["chunk_prep"] = ("hbm", th * (2 * K * es + V * es + 2 * g + C * es + K * es + V * es))
+    # state_fwd: read W, k~, U ; write E^T, S checkpoints ; 2 KV-class GEMMs
+    m["state_fwd"] = ("hbm", th * (2 * K * es + 2 * V * es + g) + nch * V * K * es)
+    # output_fwd: read q, k~, S ckpt, E^T ; write o
+    m["output_fwd"] = ("hbm", th * (2 * K * es + 2 * V * es + g) + nch * V * K * es)
+    m["bwd_local"] = ("hbm", th * (2 * K * es + 2 * V * es + g))
+    m["bwd_chain"] = ("hbm", th * (3 * K * es + 3 * V * es + g) + nch * V * K * es)
+    # bwd_post: read q,k,k~,v,dO,E^T,dE^T,T, S and dS' ckpts ; write dq, dv, dk_read, dk~ (fp32), dbeta, dg
+    m["bwd_post"] = ("hbm", th * (3 * K * es + 4 * V * es + C * es + 2 * g + K * es + V * es + 2 * K * 4 + 2 * g)
+                     + 2 * nch * V * K * es)
+    flops = {
+        "chunk_prep": th * (C * K + C * K + C * V + C * C / 3.0),               # Gram, W, U (half), inverse
+        "state_fwd": th * 4 * K * V,
+        "output_fwd": th * (C * K + 2 * K * V + C * V),
+        "bwd_local": th * (C * K + C * V),
+        "bwd_chain": th * 6 * K * V,
+        "bwd_post": th * (C * V + 2 * K * V + 2 * C * V + 6 * K * V + 2 * C * K + 4 * C * K),
+    }
+    return m, flops
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="index into the benchmark configurations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (every (batch, head) chain is independent; "
+              "see DESIGN.md for how the path would shard). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_13473_amd import binding as ob
+    from paper_2605_13473_amd.inputs import CONFIGS, make_inputs
+
+    cfg = CONFIGS[args.config]
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    ob.lib()                                        # fail loudly if the HIP library is not built
+    x = make_inputs(cfg, seed=0)
+    dt = torch.bfloat16 if cfg.bf16 else torch.float32
+    es = 2 if cfg.bf16 else 4
+    dev = "cuda:0"
+    tq, tk, tv, tdO = (torch.from_numpy(x[n]).to(dev).to(dt) for n in ("q", "k", "v", "dO"))
+    tb = torch.from_numpy(x["beta"]).to(dev)
+    tg = None if x["log_alpha"] is None else torch.from_numpy(x["log_alpha"]).to(dev)
+    tr = None if x["retention"] is None else torch.from_numpy(x["retention"]).to(dev)
+    hp = ob.Hyper()
+    p = ob.make_params(cfg.B, cfg.T, cfg.H, cfg.K, cfg.V, cfg.bf16, hp)
+    ws = ob.alloc_workspace(p, cfg.backward, dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    o = torch.empty_like(tv)
+    S_out = torch.empty(cfg.B, cfg.H, cfg.V, cfg.K, **f32)
+    d_out = torch.empty(cfg.B, cfg.H, cfg.K, **f32)
+    dq, dk, dv = torch.empty_like(tq), torch.empty_like(tk), torch.empty_like(tv)
+    dbeta = torch.empty_like(tb)
+    dg = None if tg is None else torch.empty_like(tb)
+    dr = None if tr is None else torch.empty_like(tb)
+    dd_in = torch.empty(cfg.B, cfg.H, cfg.K, **f32)
+    dS_in = torch.empty(cfg.B, cfg.H, cfg.V, cfg.K, **f32)
+
+    def step():
+        ob.osdn_fwd(p, tq, tk, tv, tb, tg, tr, None, None, o, S_out, d_out, ws)
+        if cfg.backward:
+            ob.osdn_bwd(p, tq, tk, tv, tb, tg, tr, None, None, tdO, None, None, dq, dk, dv, dbeta, dg, dr,
+                        dd_in, dS_in, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = 1e3 * (t1 - t0) / args.steps
+    tokens_per_s = cfg.B * cfg.T * args.steps / (t1 - t0)
+
+    # per-kernel durations: same steps again, each kernel bracketed by HIP events on its stream
+    ob.osdn_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = ob.osdn_profile_read()
+    ob.osdn_profile_enable(False)
+    per_kernel = {k: (ms / max(n, 1)) for k, (ms, n) in prof.items() if n > 0}
+    dominant = max(per_kernel, key=per_kernel.get)
+    models, flops = kernel_models(cfg, es)
+    bound, nbytes = models[dominant]
+    dur = per_kernel[dominant] * 1e-3
+    hbm_frac = nbytes / dur / PEAK_HBM_BYTES
+    mfma_frac = flops.get(dominant, 0.0) / dur / PEAK_BF16_FLOPS if cfg.bf16 else 0.0
+    if mfma_frac > hbm_frac:
+        roof = {"bound": "mfma", "achieved": flops[dominant] / dur / 1e12, "peak": PEAK_BF16_FLOPS / 1e12,
+                "unit": "TFLOP/s", "frac": mfma_frac, "traffic": None}
+    else:
+        roof = {"bound": "hbm", "achieved": nbytes / dur / 1e9, "peak": PEAK_HBM_BYTES / 1e9,
+                "unit": "GB/s", "frac": hbm_frac, "traffic": None}
+    roof["kernel"] = dominant
+    roof["kernel_ms"] = per_kernel[dominant]
+    roof["per_kernel_ms"] = {k: round(v, 4) for k, v in per_kernel.items()}
+
+    # whole-path algorithmic flops (MFMA only) per token-head, for the %-of-peak figure
+    K, V, C = cfg.K, cfg.V, 64
+    f_fwd = 6 * K * V + 3 * C * K + 2 * C * V + C * C / 3.0
+    f_bwd = 12 * K * V + 4 * C * K + 4 * C * V
+    th = cfg.B * cfg.T * cfg.H
+    total_flops = th * (f_fwd + (f_bwd if cfg.backward else 0.0))
+    mfma_peak_frac = total_flops / (ms_per_step * 1e-3) / PEAK_BF16_FLOPS
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        nthreads = oracle.threads()
+        nch = min(cfg.B * cfg.H, 2 * nthreads)
+        chains = [(i // cfg.H, i % cfg.H) for i in range(nch)]
+        sub = {}
+        for name in ("q", "k", "v", "dO", "beta", "log_alpha", "retention"):
+            a = x[name]
+            sub[name] = None if a is None else np.ascontiguousarray(
+                np.stack([a[b, :, h] for b, h in chains], 1)[None]).astype(np.float64)
+        ohp = oracle.Hyper()
+        c0 = time.perf_counter()
+        oracle.fwd(sub["q"], sub["k"], sub["v"], sub["beta"], sub["log_alpha"], sub["retention"], hp=ohp)
+        if cfg.backward:
+            oracle.bwd(sub["q"], sub["k"], sub["v"], sub["beta"], sub["dO"], sub["log_alpha"],
+                       sub["retention"], hp=ohp)
+        c1 = time.perf_counter()
+        cpu = {"value": nch * cfg.T / cfg.H / (c1 - c0), "unit": "tokens/s", "cores": nthreads,
+               "kind": "oracle",
+               "sample": f"{nch} of {cfg.B * cfg.H} (batch, head) chains, full T={cfg.T}, "
+                         f"{'fwd+bwd' if cfg.backward else 'fwd'}, fp64 token-by-token recurrence; "
+                         f"tokens/s scaled by 1/H to whole-token units; {c1 - c0:.1f} s"}
+
+    line = {
+        "metric": "OSDN chunkwise fwd+bwd tokens/sec @ H=16,d=128,T=4096 bf16; % MFMA peak",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.bf16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {cfg.name}: B={cfg.B} T={cfg.T} H={cfg.H} "
+                               f"K={cfg.K} V={cfg.V} chunk=64 {'fwd+bwd' if cfg.backward else 'fwd'}",
+                   "global_batch": cfg.B, "seq_len": cfg.T, "apf": cfg.apf},
+        "mfma_peak_frac": mfma_peak_frac,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -29,7 +29,8 @@
  *     enqueue work and return without synchronising.
  *   - Return value: OSDN_OK (0) or a negative osdn_status.  On an argument error nothing
  *     is launched.  osdn_strerror() gives a static description.
- *   - The library keeps no global state and allocates no device memory: scratch comes
+ *   - The library keeps no global state (apart from the optional profiling switch at the
+ *     end of this file) and allocates no device memory: scratch comes
  *     from the caller's `workspace` (256-byte aligned, at least osdn_workspace_bytes()).
  *   - Supported shapes: chunk == 64; T % 64 == 0 for osdn_fwd/osdn_bwd (any T >= 1 for
  *     osdn_precond_update when d_ckpt is NULL); K in {64, 128}; V a multiple of 64 up to
@@ -121,6 +122,19 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
              const void *dO, const float *dS_out, const float *dd_out, void *dq, void *dk, void *dv,
              float *dbeta, float *dlog_alpha, float *dretention, float *dd_in, float *dS_in,
              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Optional per-kernel timing (for benchmarks; off by default; not thread-safe -- this switch
+ * and its event list are the only process-wide state of the library).  While enabled, every
+ * kernel an entry point launches is bracketed by a pair of HIP events on the caller's stream.
+ * osdn_profile_read() waits for the recorded events, returns for each kernel id the summed
+ * duration in milliseconds and the number of launches since the previous read (arrays of
+ * n >= osdn_profile_kernel_count() host elements), and forgets them.
+ */
+void osdn_profile_enable(int on);
+int osdn_profile_kernel_count(void);
+const char *osdn_profile_kernel_name(int id);
+int osdn_profile_read(double *ms_sum, int *launches, int n);
 
 #ifdef __cplusplus
 }

@@ -62,8 +62,29 @@ def lib():
         L.osdn_fwd.argtypes = [pp, vp, vp, vp, fp, fp, fp, fp, fp, vp, fp, fp, vp, ctypes.c_size_t, vp]
         L.osdn_bwd.restype = ctypes.c_int
         L.osdn_bwd.argtypes = [pp] + [vp] * 19 + [vp, ctypes.c_size_t, vp]
+        L.osdn_profile_enable.restype = None
+        L.osdn_profile_enable.argtypes = [ctypes.c_int]
+        L.osdn_profile_kernel_count.restype = ctypes.c_int
+        L.osdn_profile_kernel_name.restype = ctypes.c_char_p
+        L.osdn_profile_kernel_name.argtypes = [ctypes.c_int]
+        L.osdn_profile_read.restype = ctypes.c_int
+        L.osdn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int), ctypes.c_int]
         _lib = L
     return _lib
+
+
+def osdn_profile_enable(on: bool) -> None:
+    lib().osdn_profile_enable(int(bool(on)))
+
+
+def osdn_profile_read() -> dict:
+    """{kernel name: (summed milliseconds, launches)} since the previous read."""
+    L = lib()
+    n = L.osdn_profile_kernel_count()
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int * n)()
+    _check(L.osdn_profile_read(ms, cnt, n))
+    return {L.osdn_profile_kernel_name(i).decode(): (ms[i], cnt[i]) for i in range(n)}
 
 
 def osdn_strerror(status: int) -> str:

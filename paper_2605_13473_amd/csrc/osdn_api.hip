@@ -4,10 +4,32 @@
 #include "osdn_kernels.h"
 
 #include <cmath>
+#include <vector>
 
 namespace {
 
 using namespace osdn;
+
+// Optional per-kernel timing with HIP events on the caller's stream (off by default; the
+// only process-wide state the library has).  Not thread-safe; meant for benchmarks.
+enum { KID_PRECOND_FWD, KID_CHUNK_PREP, KID_STATE_FWD, KID_OUTPUT_FWD, KID_BWD_LOCAL, KID_BWD_CHAIN,
+       KID_BWD_POST, KID_PRECOND_BWD, KID_COUNT };
+const char *const kKernelNames[KID_COUNT] = {"precond_fwd", "chunk_prep", "state_fwd", "output_fwd",
+                                             "bwd_local", "bwd_chain", "bwd_post", "precond_bwd"};
+struct Timed { int id; hipEvent_t e0, e1; };
+bool g_prof_on = false;
+std::vector<Timed> g_prof;
+
+template <typename F> int timed(int id, hipStream_t st, F &&launch) {
+    if (!g_prof_on) return launch();
+    Timed t{id, nullptr, nullptr};
+    if (hipEventCreate(&t.e0) != hipSuccess || hipEventCreate(&t.e1) != hipSuccess) return launch();
+    (void)hipEventRecord(t.e0, st);
+    const int rc = launch();
+    (void)hipEventRecord(t.e1, st);
+    g_prof.push_back(t);
+    return rc;
+}
 
 struct Layout {
     size_t kt, d_ckpt, Tm, W, U, Et, S_ckpt;            // forward
@@ -115,8 +137,9 @@ int osdn_precond_update(const osdn_params *p, const void *k, const float *beta,
     PrecondArgs a = precond_args(p);
     a.k = k; a.beta = beta; a.retention = retention; a.d_in = d_in;
     a.k_tilde = k_tilde; a.d_out = d_out; a.d_ckpt = d_ckpt;
-    if (launch_precond_fwd(a, p->io_dtype == OSDN_BF16, static_cast<hipStream_t>(stream)) != 0)
-        return OSDN_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool bf = p->io_dtype == OSDN_BF16;
+    if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(a, bf, st); }) != 0) return OSDN_ERR_SHAPE;
     return launch_status();
 }
 
@@ -137,14 +160,14 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     PrecondArgs pa = precond_args(p);
     pa.k = k; pa.beta = beta; pa.retention = retention; pa.d_in = d_in;
     pa.k_tilde = ws + L.kt; pa.d_out = d_out; pa.d_ckpt = reinterpret_cast<float *>(ws + L.d_ckpt);
-    if (launch_precond_fwd(pa, bf, st) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(pa, bf, st); }) != 0) return OSDN_ERR_SHAPE;
 
     ChunkArgs c = chunk_args(p, L, ws);
     c.q = q; c.k = k; c.v = v; c.beta = beta; c.log_alpha = log_alpha; c.S_in = S_in;
     c.o = o; c.S_out = S_out;
-    if (launch_chunk_prep(c, bf, st) != 0) return OSDN_ERR_SHAPE;
-    if (launch_state_fwd(c, bf, st) != 0) return OSDN_ERR_SHAPE;
-    if (launch_output_fwd(c, bf, st) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_CHUNK_PREP, st, [&] { return launch_chunk_prep(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_STATE_FWD, st, [&] { return launch_state_fwd(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_OUTPUT_FWD, st, [&] { return launch_output_fwd(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
     return launch_status();
 }
 
@@ -174,9 +197,9 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     c.dk_read = reinterpret_cast<float *>(ws + L.dk_read);
     c.dkt = reinterpret_cast<float *>(ws + L.dkt);
     c.dbeta = dbeta; c.dlog_alpha = log_alpha ? dlog_alpha : nullptr;
-    if (launch_bwd_local(c, bf, st) != 0) return OSDN_ERR_SHAPE;
-    if (launch_bwd_chain(c, bf, st) != 0) return OSDN_ERR_SHAPE;
-    if (launch_bwd_post(c, bf, st) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_BWD_LOCAL, st, [&] { return launch_bwd_local(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_BWD_CHAIN, st, [&] { return launch_bwd_chain(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_BWD_POST, st, [&] { return launch_bwd_post(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
 
     PrecondBwdArgs pb{};
     pb.B = p->B; pb.T = p->T; pb.H = p->H; pb.K = p->K;
@@ -186,8 +209,29 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     pb.d_ckpt = reinterpret_cast<const float *>(ws + L.d_ckpt);
     pb.dkt = c.dkt; pb.dk_read = c.dk_read; pb.dd_out = dd_out;
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
-    if (launch_precond_bwd(pb, bf, st) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_PRECOND_BWD, st, [&] { return launch_precond_bwd(pb, bf, st); }) != 0) return OSDN_ERR_SHAPE;
     return launch_status();
+}
+
+void osdn_profile_enable(int on) { g_prof_on = on != 0; }
+
+int osdn_profile_kernel_count(void) { return KID_COUNT; }
+
+const char *osdn_profile_kernel_name(int id) { return (id >= 0 && id < KID_COUNT) ? kKernelNames[id] : ""; }
+
+int osdn_profile_read(double *ms_sum, int *launches, int n) {
+    for (int i = 0; i < n; ++i) { ms_sum[i] = 0.0; launches[i] = 0; }
+    int rc = OSDN_OK;
+    for (Timed &t : g_prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(t.e1) != hipSuccess || hipEventElapsedTime(&ms, t.e0, t.e1) != hipSuccess)
+            rc = OSDN_ERR_LAUNCH;
+        else if (t.id < n) { ms_sum[t.id] += ms; launches[t.id] += 1; }
+        (void)hipEventDestroy(t.e0);
+        (void)hipEventDestroy(t.e1);
+    }
+    g_prof.clear();
+    return rc;
 }
 
 }  // extern "C"

@@ -1,0 +1,204 @@
+"""GPU parity: the HIP library (through the C-ABI and its thin binding) against the CPU
+oracle, element by element, on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_13473_amd import binding as ob
+from paper_2605_13473_amd.inputs import CONFIGS, make_inputs, make_stress_inputs
+from tests.gpu_util import check, compare_backward, compare_forward, f64, gpu_forward, oracle_hp, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config0_tiny_fp32_forward():
+    """Configuration 0 exactly: B=1, H=2, T=256, K=V=64, fp32, paper's eta/box, APF off."""
+    x = make_inputs(CONFIGS[0], seed=0)
+    compare_forward(x, ob.Hyper(), bf16=False)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", [(1, 64, 1, 64, 64), (2, 192, 3, 64, 128), (1, 256, 2, 128, 192),
+                                   (3, 128, 1, 128, 64)])
+def test_stress_forward(shape, bf16):
+    """Large eta, peaky keys, random d_in in the box, carried S_in, retention: d moves by
+    O(1) and both faces of the box are hit, so a kernel that ignored d would fail."""
+    B, T, H, K, V = shape
+    x = make_stress_inputs(B, T, H, K, V, seed=21, bf16=bf16, retention=0.97)
+    compare_forward(x, ob.Hyper(eta=0.5), bf16)
+    # the stress inputs really exercise the preconditioner
+    _, _, traj = oracle.precond(x["k"], x["beta"], x["retention"], x["d_in"], oracle.Hyper(eta=0.5),
+                                want_traj=True)
+    assert traj.max() - traj.min() > 0.5
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", [(1, 64, 1, 64, 64), (2, 192, 3, 64, 128), (1, 256, 2, 128, 192)])
+def test_stress_backward(shape, bf16):
+    B, T, H, K, V = shape
+    x = make_stress_inputs(B, T, H, K, V, seed=22, bf16=bf16, retention=0.97)
+    rng = np.random.default_rng(23)
+    dS = rng.standard_normal((B, H, V, K)).astype(np.float32)
+    dd = rng.standard_normal((B, H, K)).astype(np.float32)
+    compare_backward(x, ob.Hyper(eta=0.5), bf16, dS, dd)
+
+
+@pytest.mark.parametrize("variant", ["ungated", "no_retention", "non_beta_aware", "no_projection",
+                                     "eta_one_clamped", "defaults_null"])
+def test_variants_fwd_bwd_fp32(variant):
+    B, T, H, K, V = 2, 128, 2, 64, 64
+    x = make_stress_inputs(B, T, H, K, V, seed=24, gated=(variant != "ungated"),
+                           retention=0.0 if variant in ("no_retention", "defaults_null") else 0.9)
+    hp = ob.Hyper(eta=0.5)
+    if variant == "non_beta_aware":
+        hp = ob.Hyper(eta=0.5, beta_aware=False)
+    if variant == "no_projection":
+        hp = ob.Hyper(eta=0.2, d_min=1.0, d_max=0.0)
+    if variant == "eta_one_clamped":
+        hp = ob.Hyper(eta=1.0)
+    if variant == "defaults_null":
+        x["d_in"] = None
+        x["S_in"] = None
+    compare_forward(x, hp, False)
+    compare_backward(x, hp, False)
+
+
+def test_precond_update_streaming_lengths():
+    """osdn_precond_update for T = 1 (decode step), T = 7 and T = 200 (not multiples of the
+    unroll or the chunk), fp32 and bf16 keys, against the oracle's phase 1."""
+    for T in (1, 7, 200):
+        for bf16 in (False, True):
+            x = make_stress_inputs(2, T, 3, 128, 64, seed=25, bf16=bf16, retention=0.95)
+            t = to_dev(x, bf16)
+            hp = ob.Hyper(eta=0.7)
+            kt, d_out = ob.precond_update(t["k"], t["beta"], t["retention"], t["d_in"], hp)
+            torch.cuda.synchronize()
+            okt, od = oracle.precond(x["k"], x["beta"], x["retention"], x["d_in"], oracle_hp(hp))
+            check("k_tilde", kt, okt, bf16)
+            check("d_out", d_out, od, False)
+
+
+def test_precond_checkpoints_and_carry():
+    """d_ckpt holds d at every chunk start; two calls with carried d equal one call bit for bit."""
+    x = make_stress_inputs(1, 256, 2, 64, 64, seed=26, retention=0.98)
+    t = to_dev(x, False)
+    hp = ob.Hyper(eta=0.4)
+    kt, d_out, ck = ob.precond_update(t["k"], t["beta"], t["retention"], t["d_in"], hp, want_ckpt=True)
+    _, _, traj = oracle.precond(x["k"], x["beta"], x["retention"], x["d_in"], oracle_hp(hp), want_traj=True)
+    check("d_ckpt", ck, traj[:, ::64].transpose(0, 2, 1, 3), False)
+    k1, d1 = ob.precond_update(t["k"][:, :100].contiguous(), t["beta"][:, :100].contiguous(),
+                               t["retention"][:, :100].contiguous(), t["d_in"], hp)
+    k2, d2 = ob.precond_update(t["k"][:, 100:].contiguous(), t["beta"][:, 100:].contiguous(),
+                               t["retention"][:, 100:].contiguous(), d1, hp)
+    assert torch.equal(torch.cat([k1, k2], 1), kt) and torch.equal(d2, d_out)
+
+
+def test_resume_split_sequence():
+    """One call on T tokens equals two calls on T/2 with (S, d) carried (both vs the oracle, and
+    the two GPU results against each other bit for bit at a chunk boundary)."""
+    x = make_stress_inputs(2, 256, 2, 64, 128, seed=27, retention=0.97)
+    hp = ob.Hyper(eta=0.3)
+    o, S, d, _, t = gpu_forward(x, hp, False)
+    h = 128
+    cut = lambda a, s: None if a is None else a[:, s].contiguous()
+    o1, S1, d1, _ = ob.forward(cut(t["q"], slice(0, h)), cut(t["k"], slice(0, h)), cut(t["v"], slice(0, h)),
+                               cut(t["beta"], slice(0, h)), cut(t["log_alpha"], slice(0, h)),
+                               cut(t["retention"], slice(0, h)), t["d_in"], t["S_in"], hp)
+    o2, S2, d2, _ = ob.forward(cut(t["q"], slice(h, None)), cut(t["k"], slice(h, None)),
+                               cut(t["v"], slice(h, None)), cut(t["beta"], slice(h, None)),
+                               cut(t["log_alpha"], slice(h, None)), cut(t["retention"], slice(h, None)),
+                               d1, S1, hp)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.cat([o1, o2], 1), o) and torch.equal(S2, S) and torch.equal(d2, d)
+    compare_forward(x, hp, False)
+
+
+def test_degenerate_inputs():
+    """Zero keys (squared norm floored by eps), beta at 0 and 1, zero gate (alpha = 1) and a
+    very strong gate, d_in on the faces of the box."""
+    B, T, H, K, V = 1, 128, 2, 64, 64
+    x = make_stress_inputs(B, T, H, K, V, seed=28, retention=0.9)
+    x["k"][:, 5] = 0.0
+    x["k"][:, 70, :, 1:] = 0.0
+    x["beta"][:, 10] = 0.0
+    x["beta"][:, 11] = 1.0
+    x["log_alpha"][:, 20:40] = 0.0
+    x["log_alpha"][:, 64:70] = -30.0
+    x["d_in"][:, 0] = 0.5
+    x["d_in"][:, 1] = 2.0
+    compare_forward(x, ob.Hyper(eta=0.5), False)
+    compare_backward(x, ob.Hyper(eta=0.5), False)
+
+
+def test_bitwise_repeatable():
+    x = make_stress_inputs(2, 128, 2, 128, 128, seed=29, bf16=True, retention=0.97)
+    outs = []
+    for _ in range(2):
+        o, S, d, ctx, t = gpu_forward(x, ob.Hyper(eta=0.5), True, for_backward=True)
+        g = ob.backward(ctx, t["dO"])
+        torch.cuda.synchronize()
+        outs.append([o, S, d] + [g[n] for n in sorted(g) if g[n] is not None])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_argument_errors_launch_nothing():
+    x = make_stress_inputs(1, 64, 1, 64, 64, seed=30)
+    t = to_dev(x, False)
+    p = ob.make_params(1, 64, 1, 64, 64, False)
+    o = torch.full((1, 64, 1, 64), 7.0, device="cuda")
+    S = torch.empty(1, 1, 64, 64, device="cuda"); d = torch.empty(1, 1, 64, device="cuda")
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ob.OsdnError) as e:
+        ob.osdn_fwd(p, t["q"], t["k"], t["v"], t["beta"], t["log_alpha"], None, None, None, o, S, d, small)
+    assert e.value.status == -4
+    torch.cuda.synchronize()
+    assert bool((o == 7.0).all())
+
+
+# ----------------------------------------------------------- full-size configs ----
+def _sample_chains(x, chains):
+    """Slice (b,h) chains out of a full batch as a [1, T, n, .] batch (chains are independent)."""
+    out = {}
+    for name, a in x.items():
+        if a is None:
+            out[name] = None
+        elif name in ("d_in",):
+            out[name] = np.stack([a[b, h] for b, h in chains], 0)[None]
+        elif name in ("S_in",):
+            out[name] = np.stack([a[b, h] for b, h in chains], 0)[None]
+        else:
+            out[name] = np.stack([a[b, :, h] for b, h in chains], 1)[None]
+    return out
+
+
+@pytest.mark.parametrize("ci", [1, 2, 3, 4])
+def test_full_size_configs_sampled_chains(ci):
+    """The benchmark configurations at full size, in the launch configuration the benchmark
+    times; the oracle recomputes two whole (b,h) chains (first and last)."""
+    cfg = CONFIGS[ci]
+    x = make_inputs(cfg, seed=0)
+    hp = ob.Hyper()
+    o, S, d, ctx, t = gpu_forward(x, hp, cfg.bf16, for_backward=cfg.backward)
+    assert torch.isfinite(o.float()).all()
+    assert float(d.min()) >= hp.d_min and float(d.max()) <= hp.d_max
+    chains = [(0, 0), (cfg.B - 1, cfg.H - 1)]
+    y = f64(_sample_chains(x, chains))
+    oo, oS, od = oracle.fwd(y["q"], y["k"], y["v"], y["beta"], y["log_alpha"], y["retention"], None, None,
+                            oracle_hp(hp))
+    pick = lambda tns, tok: torch.stack([tns[b, :, h] for b, h in chains], 1)[None] if tok else \
+        torch.stack([tns[b, h] for b, h in chains], 0)[None]
+    check("o", pick(o, True), oo, cfg.bf16)
+    check("S_out", pick(S, False), oS, cfg.bf16)
+    check("d_out", pick(d, False), od, False)
+    if cfg.backward:
+        g = ob.backward(ctx, t["dO"])
+        torch.cuda.synchronize()
+        og = oracle.bwd(y["q"], y["k"], y["v"], y["beta"], y["dO"], y["log_alpha"], y["retention"],
+                        None, None, hp=oracle_hp(hp))
+        for name, ref in og.items():
+            if ref is None:
+                continue
+            tok = name not in ("dd_in", "dS_in")
+            check(name, pick(g[name], tok), ref, cfg.bf16)

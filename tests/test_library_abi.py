@@ -1,0 +1,79 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol include/osdn.h
+declares, sizes its workspace, and rejects bad arguments before touching any pointer
+(no compute is launched here, so no GPU is needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_13473_amd import binding as ob
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "osdn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(osdn_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = ob.lib()
+    names = _declared_symbols()
+    assert {"osdn_fwd", "osdn_bwd", "osdn_precond_update", "osdn_workspace_bytes", "osdn_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_workspace_size_and_shape_validation():
+    p = ob.make_params(4, 4096, 16, 128, 128, True)
+    fwd, bwd = ob.osdn_workspace_bytes(p, False), ob.osdn_workspace_bytes(p, True)
+    assert 0 < fwd < bwd
+    # at least k~ plus W, U, E^T and the per-chunk state
+    assert fwd >= 4 * 4096 * 16 * 128 * 2 * 4
+    for bad in (dict(T=100), dict(K=256), dict(K=96), dict(V=96), dict(chunk=32), dict(B=0)):
+        q = ob.make_params(1, 128, 1, 64, 64, False)
+        for k, v in bad.items():
+            setattr(q, k, v)
+        assert ob.osdn_workspace_bytes(q, False) == 0, bad
+
+
+def test_argument_errors_before_any_pointer_is_used():
+    L = ob.lib()
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    p = ob.make_params(1, 100, 1, 64, 64, False)
+    rc = L.osdn_fwd(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
+                    fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == -2 and "shape" in ob.osdn_strerror(rc)
+    p = ob.make_params(1, 128, 1, 64, 64, False)
+    p.io_dtype = 5
+    assert L.osdn_fwd(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
+                      fake, ctypes.c_size_t(1 << 30), None) == -3
+    p = ob.make_params(1, 128, 1, 64, 64, False, ob.Hyper(eta=-1.0))
+    assert L.osdn_precond_update(ctypes.byref(p), fake, fake, None, None, fake, fake, None, None) == -5
+    p = ob.make_params(1, 128, 1, 64, 64, False)
+    assert L.osdn_fwd(ctypes.byref(p), None, fake, fake, fake, None, None, None, None, fake, fake, fake,
+                      fake, ctypes.c_size_t(1 << 30), None) == -1
+    # misaligned and too-small workspaces
+    assert L.osdn_fwd(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
+                      ctypes.c_void_p(0x1010), ctypes.c_size_t(1 << 30), None) == -4
+    assert L.osdn_fwd(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
+                      fake, ctypes.c_size_t(16), None) == -4
+    # d_ckpt needs whole chunks
+    p = ob.make_params(1, 7, 1, 64, 64, False)
+    assert L.osdn_precond_update(ctypes.byref(p), fake, fake, None, None, fake, fake, fake, None) == -2
+    # gradient outputs that must accompany optional inputs
+    p = ob.make_params(1, 128, 1, 64, 64, False)
+    args = [fake] * 19
+    args[4] = fake      # log_alpha given ...
+    args[15] = None     # ... but dlog_alpha missing
+    assert L.osdn_bwd(ctypes.byref(p), *args, fake, ctypes.c_size_t(1 << 30), None) == -1
+
+
+def test_binding_rejects_cpu_tensors_and_wrong_dtypes():
+    import torch
+    p = ob.make_params(1, 64, 1, 64, 64, False)
+    k = torch.zeros(1, 64, 1, 64)
+    with pytest.raises(TypeError):
+        ob.osdn_precond_update(p, k, k[..., 0], None, None, k.clone(), torch.zeros(1, 1, 64))
