@@ -32,7 +32,7 @@ template <typename F> int timed(int id, hipStream_t st, F &&launch) {
 }
 
 struct Layout {
-    size_t kt, d_ckpt, Tm, W, U, Et, S_ckpt;            // forward
+    size_t kt, d_ckpt, tok_scalars, Tm, W, U, Et, S_ckpt;   // forward
     size_t dEl, dEt, dS_ckpt, dk_read, dkt;             // backward only
     size_t total_fwd, total_bwd;
 };
@@ -64,6 +64,7 @@ Layout make_layout(const osdn_params *p) {
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
     L.kt = take(B * T * H * K * es);
     L.d_ckpt = take(B * H * N * K * 4);
+    L.tok_scalars = take(B * T * H * 4 * 4);
     L.Tm = take(B * H * N * C * C * es);
     L.W = take(B * T * H * K * es);
     L.U = take(B * T * H * V * es);
@@ -136,7 +137,7 @@ int osdn_precond_update(const osdn_params *p, const void *k, const float *beta,
     if (d_ckpt && p->T % C != 0) return OSDN_ERR_SHAPE;
     PrecondArgs a = precond_args(p);
     a.k = k; a.beta = beta; a.retention = retention; a.d_in = d_in;
-    a.k_tilde = k_tilde; a.d_out = d_out; a.d_ckpt = d_ckpt;
+    a.k_tilde = k_tilde; a.d_out = d_out; a.d_ckpt = d_ckpt; a.tok_scalars = nullptr;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = p->io_dtype == OSDN_BF16;
     if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(a, bf, st); }) != 0) return OSDN_ERR_SHAPE;
@@ -160,6 +161,7 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     PrecondArgs pa = precond_args(p);
     pa.k = k; pa.beta = beta; pa.retention = retention; pa.d_in = d_in;
     pa.k_tilde = ws + L.kt; pa.d_out = d_out; pa.d_ckpt = reinterpret_cast<float *>(ws + L.d_ckpt);
+    pa.tok_scalars = reinterpret_cast<float *>(ws + L.tok_scalars);
     if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(pa, bf, st); }) != 0) return OSDN_ERR_SHAPE;
 
     ChunkArgs c = chunk_args(p, L, ws);
@@ -207,6 +209,7 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     pb.beta_aware = p->beta_aware;
     pb.k = k; pb.beta = beta; pb.retention = retention;
     pb.d_ckpt = reinterpret_cast<const float *>(ws + L.d_ckpt);
+    pb.tok_scalars = reinterpret_cast<const float *>(ws + L.tok_scalars);
     pb.dkt = c.dkt; pb.dk_read = c.dk_read; pb.dd_out = dd_out;
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
     if (timed(KID_PRECOND_BWD, st, [&] { return launch_precond_bwd(pb, bf, st); }) != 0) return OSDN_ERR_SHAPE;

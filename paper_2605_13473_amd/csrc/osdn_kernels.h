@@ -15,6 +15,7 @@ struct PrecondArgs {
     void *k_tilde;            // [B,T,H,K] io
     float *d_out;             // [B,H,K]
     float *d_ckpt;            // [B,H,T/64,K] or null
+    float *tok_scalars;       // [B,T,H,4] or null: per token (step, <d,k^2>, sum k^2, unused), kept for the backward
 };
 
 struct PrecondBwdArgs {
@@ -23,6 +24,7 @@ struct PrecondBwdArgs {
     int beta_aware;
     const void *k;
     const float *beta, *retention, *d_ckpt;
+    const float *tok_scalars; // [B,T,H,4] from the forward sweep
     const float *dkt;         // [B,T,H,K] fp32: dL/dk~ from phase 2
     const float *dk_read;     // [B,T,H,K] fp32: read-side dL/dk from phase 2
     const float *dd_out;      // [B,H,K] or null

@@ -1,228 +1,421 @@
 // Phase 1 of OSDN: the online preconditioner sweep (Algorithm 1, Eq. (dt_update) and its
 // retention form Eq. (dt_update_apf)), and its reverse sweep (Section 4.5).
 //
-// The recurrence over d is sequential in t with O(K) work per token, so one wavefront
-// owns one (batch, head) chain: lane l keeps K/64 consecutive coordinates of d in
-// registers, the two inner products per token are wave reductions over DPP, and key rows
-// are fetched several tokens ahead so that only the d-dependent part sits on the critical
-// path.  All arithmetic is fp32; k~ is rounded once, from fp32 d * k, to the I/O type.
+// The recurrence  d_{t+1} = clip(r_t d_t + c_t s_t),  s_t = k_t (.) k_t,
+//                 c_t = eta b'(1 - b' p_t)/n_t,  p_t = <d_t, s_t>
+// couples the K coordinates only through the scalar p_t.  One workgroup owns one
+// (batch, head) chain and walks it in chunks of 64 tokens held in LDS.  Inside a chunk it
+// solves for the 64 scalars p by fixed-point sweeps: given p (first guess: <d_0, s_t>), the
+// recurrence separates into K independent scalar recurrences (one thread per coordinate,
+// 64 steps of fma + median-of-three, clip included); from the resulting trajectory the 64
+// inner products are recomputed in parallel; the sweep repeats until they reproduce
+// themselves.  Sweep m fixes at least the first m tokens exactly, so 64 sweeps always
+// suffice; because the coupling is O(eta) two do in practice (also when coordinates sit on a
+// face of the box, which the scalar recurrences handle by themselves).  No per-token
+// cross-lane reduction is left on the sequential path.  All arithmetic is fp32; k~ is
+// rounded once, from fp32 d * k.
+//
+// The reverse sweep has the same structure: with sigma_t = <s_t, abar_t> known, the adjoint
+// recurrence  abar_t = mask_t (.) a_{t+1},  a_t = k_t (.) dL/dk~_t + r_t abar_t - ca_t sigma_t s_t
+// separates per coordinate; sigma is found by the same kind of sweeps.
 #include "osdn_kernels.h"
 
 namespace osdn {
 
-template <typename T, int EPL> struct alignas(sizeof(T) * EPL) Row { T v[EPL]; };
+constexpr int P1_MAX_SWEEPS = 66;       // 64 guarantee exactness
+constexpr float P1_TOL = 1e-6f;         // relative agreement of the inner products between sweeps
 
-constexpr int P1_UNROLL = 8;
-
-template <typename T, int EPL>
-__global__ __launch_bounds__(64) void precond_fwd_kernel(PrecondArgs a) {
-    const int lane = threadIdx.x;
-    const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
-    const int K = 64 * EPL;
-    const int j0 = lane * EPL;
-    const T *k = static_cast<const T *>(a.k);
-    T *kt = static_cast<T *>(a.k_tilde);
-    const size_t bh = (size_t)b * a.H + h;
-    const bool project = a.d_min <= a.d_max;
-
-    float d[EPL];
+// projection onto [lo, hi] as one median-of-three (lo = -inf, hi = +inf when there is none)
+__device__ __forceinline__ float clip3(float x, float lo, float hi) { return __builtin_amdgcn_fmed3f(x, lo, hi); }
+// the affine step before projection, written once so that forward and replay round identically
+template <bool HAS_RET>
+__device__ __forceinline__ float d_bar(float r, float d, float step, float s) {
+    return HAS_RET ? __builtin_fmaf(step, s, r * d) : __builtin_fmaf(step, s, d);
+}
+__device__ __forceinline__ void store_vec(float *dst, const float (&v)[4]) {
+    *reinterpret_cast<f32x4 *>(dst) = f32x4{v[0], v[1], v[2], v[3]};
+}
+__device__ __forceinline__ void store_vec(bf16 *dst, const float (&v)[8]) {
+    bf16x8 o;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) d[e] = a.d_in ? a.d_in[bh * K + j0 + e] : 1.f;
-
-    for (int t0 = 0; t0 < a.T; t0 += P1_UNROLL) {
-        // ---- everything that does not depend on d, for P1_UNROLL tokens ----
-        Row<T, EPL> kr[P1_UNROLL];
-        float bet[P1_UNROLL], ret[P1_UNROLL];
+    for (int e = 0; e < 8; ++e) o[e] = (bf16)v[e];
+    *reinterpret_cast<bf16x8 *>(dst) = o;
+}
+__device__ __forceinline__ void store_vec(bf16 *dst, const float (&v)[4]) {
+    bf16x4 o;
 #pragma unroll
-        for (int u = 0; u < P1_UNROLL; ++u) {
-            const int t = min(t0 + u, a.T - 1);
-            const size_t th = ((size_t)b * a.T + t) * a.H + h;
-            kr[u] = *reinterpret_cast<const Row<T, EPL> *>(k + th * K + j0);
-            bet[u] = a.beta[th];
-            ret[u] = a.retention ? a.retention[th] : 1.f;
-        }
-        float s[P1_UNROLL][EPL], ca[P1_UNROLL], cb[P1_UNROLL];
+    for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+    *reinterpret_cast<bf16x4 *>(dst) = o;
+}
+__device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
-        for (int u = 0; u < P1_UNROLL; ++u) {
-            float part = 0.f;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                const float kv = to_f32(kr[u].v[e]);
-                s[u][e] = kv * kv;
-                part += s[u][e];
-            }
-            const float n = fmaxf(wave_sum(part), a.eps);
-            const float bp = a.beta_aware ? bet[u] : 1.f;
-            // step = cb - ca * p  with p = <d, s>
-            cb[u] = a.eta * bp / n;
-            ca[u] = cb[u] * bp;
-        }
-        // ---- the sequential part ----
-#pragma unroll
-        for (int u = 0; u < P1_UNROLL; ++u) {
-            const int t = t0 + u;
-            if (t < a.T) {
-                const size_t th = ((size_t)b * a.T + t) * a.H + h;
-                if (a.d_ckpt && (t % C) == 0) {
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e)
-                        a.d_ckpt[(bh * (a.T / C) + t / C) * K + j0 + e] = d[e];
-                }
-                Row<T, EPL> out;
-                float part = 0.f;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) {
-                    out.v[e] = from_f32<T>(d[e] * to_f32(kr[u].v[e]));
-                    part += d[e] * s[u][e];
-                }
-                *reinterpret_cast<Row<T, EPL> *>(kt + th * K + j0) = out;
-                const float p = wave_sum(part);
-                const float step = cb[u] - ca[u] * p;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) {
-                    float dn = ret[u] * d[e] + step * s[u][e];
-                    if (project) dn = fminf(fmaxf(dn, a.d_min), a.d_max);
-                    d[e] = dn;
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) a.d_out[bh * K + j0 + e] = d[e];
+    for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+    return x;
+}
+// sum of four per-wave partials of row i
+__device__ __forceinline__ float sum4(const float *part, int i) {
+    return (part[i] + part[C + i]) + (part[2 * C + i] + part[3 * C + i]);
 }
 
-// Reverse sweep (Section 4.5; the projection passes gradient where the unprojected value
-// lies in [d_min, d_max]).  One wavefront per chain, chunk by chunk from the right: the
-// chunk's d trajectory is replayed from the stored chunk-start value into LDS, then the
-// tokens are visited in reverse carrying the adjoint of d.
-//   in : k, beta, retention, d_ckpt, dkt (dL/dk~, fp32), dk_read (dL/dk read side, fp32),
-//        dbeta (partial, from phase 2), dd_out
-//   out: dk (io type) = dk_read + d_t . dkt + phase-1 terms ; dbeta += ; dretention ; dd_in
-template <typename T, int EPL>
-__global__ __launch_bounds__(64) void precond_bwd_kernel(PrecondBwdArgs a) {
-    constexpr int K = 64 * EPL;
-    __shared__ float d_traj[C][K];      // d_t for the tokens of the current chunk
-    const int lane = threadIdx.x;
+template <typename T, int K, bool HAS_RET>
+__global__ __launch_bounds__(NT) void precond_fwd_kernel(PrecondArgs a) {
+    constexpr int LD = K + 1;                    // odd stride: rows and columns both conflict-free
+    constexpr int VN = 16 / sizeof(T);
+    constexpr int NW = C * K / VN / NT;          // 16-byte vectors per thread for a [64 x K] tile
+    constexpr int KQ = K / 4;                    // columns per thread in a row dot
+    __shared__ float ss[C * LD];                 // s = k^2 of the chunk
+    __shared__ float Dt[C * LD];                 // d_i for the tokens of the chunk
+    __shared__ float d0[K], dnew[K];
+    __shared__ float cbs[C], cas[C], nraws[C], ps[C];
+    __shared__ __attribute__((aligned(16))) float cs[C];
+    __shared__ __attribute__((aligned(16))) float rs[C];
+    __shared__ float part[4 * C], part2[4 * C];
+    __shared__ int done;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
-    const int j0 = lane * EPL;
+    const size_t bh = (size_t)b * a.H + h;
+    const T *k = static_cast<const T *>(a.k);
+    T *kt = static_cast<T *>(a.k_tilde);
+    const bool project = a.d_min <= a.d_max;
+    const float lo = project ? a.d_min : -INFINITY, hi = project ? a.d_max : INFINITY;
+    const int N = (a.T + C - 1) / C;
+
+    if (tid < K) d0[tid] = a.d_in ? a.d_in[bh * K + tid] : 1.f;
+
+    uint4 kreg[NW];
+    float betreg = 0.f, retreg = 1.f;
+#define OSDN_P1_LOAD(n_)                                                                         \
+    {                                                                                            \
+        const int t0_ = (n_) * C;                                                                \
+        _Pragma("unroll") for (int m = 0; m < NW; ++m) {                                         \
+            const int i = tid + m * NT, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
+            const int t = min(t0_ + r, a.T - 1);                                                 \
+            kreg[m] = *reinterpret_cast<const uint4 *>(k + (((size_t)b * a.T + t) * a.H + h) * K + c); \
+        }                                                                                        \
+        if (tid < C) {                                                                           \
+            const int t = min(t0_ + tid, a.T - 1);                                               \
+            const size_t th = ((size_t)b * a.T + t) * a.H + h;                                   \
+            betreg = a.beta[th];                                                                 \
+            if (HAS_RET) retreg = a.retention[th];                                               \
+        }                                                                                        \
+    }
+    OSDN_P1_LOAD(0)
+
+    for (int n = 0; n < N; ++n) {
+        const int t0 = n * C;
+        const int nvalid = min(C, a.T - t0);
+        // ---- registers -> LDS (rows past the end of the sequence become no-op tokens) ----
+        uint4 kcur[NW];
+#pragma unroll
+        for (int m = 0; m < NW; ++m) {
+            kcur[m] = kreg[m];
+            const int i = tid + m * NT, r = i / (K / VN), c = (i % (K / VN)) * VN;
+#pragma unroll
+            for (int e = 0; e < VN; ++e) {
+                const float kv = r < nvalid ? vec_get<T>(kcur[m], e) : 0.f;
+                ss[r * LD + c + e] = kv * kv;
+            }
+        }
+        const float bet = betreg, ret = retreg;
+        __syncthreads();
+        if (n + 1 < N) OSDN_P1_LOAD(n + 1)
+        if (a.d_ckpt && tid < K) a.d_ckpt[(bh * N + n) * K + tid] = d0[tid];
+        // ---- per token: n_raw = sum s, and the first guess p = <d_0, s> ----
+        {
+            const int i = lane, q0 = wave * KQ;
+            float sn = 0.f, sp = 0.f;
+#pragma unroll 8
+            for (int c = 0; c < KQ; ++c) {
+                const float s = ss[i * LD + q0 + c];
+                sn += s;
+                sp = __builtin_fmaf(s, d0[q0 + c], sp);
+            }
+            part[wave * C + i] = sn;
+            part2[wave * C + i] = sp;
+        }
+        __syncthreads();
+        if (tid < C) {
+            const int i = tid;
+            const float nraw = sum4(part, i), p = sum4(part2, i);
+            const bool valid = i < nvalid;
+            const float nn = fmaxf(nraw, a.eps);
+            const float bp = a.beta_aware ? bet : 1.f;
+            const float cb = valid ? a.eta * bp / nn : 0.f;
+            const float ca = cb * bp;
+            nraws[i] = nraw; cbs[i] = cb; cas[i] = ca; rs[i] = valid ? ret : 1.f;
+            ps[i] = p;
+            cs[i] = cb - ca * p;
+        }
+        __syncthreads();
+        // ---- fixed-point sweeps ----
+        for (int sweep = 0; sweep < P1_MAX_SWEEPS; ++sweep) {
+            if (tid < K) {                      // K independent scalar recurrences
+                float d = d0[tid];
+#pragma unroll 16
+                for (int i = 0; i < C; ++i) {
+                    Dt[i * LD + tid] = d;
+                    d = clip3(d_bar<HAS_RET>(rs[i], d, cs[i], ss[i * LD + tid]), lo, hi);
+                }
+                dnew[tid] = d;
+            }
+            __syncthreads();
+            {                                   // recompute p_i = <d_i, s_i> from the trajectory
+                const int i = lane, q0 = wave * KQ;
+                float sp = 0.f;
+#pragma unroll 8
+                for (int c = 0; c < KQ; ++c) sp = __builtin_fmaf(ss[i * LD + q0 + c], Dt[i * LD + q0 + c], sp);
+                part2[wave * C + i] = sp;
+            }
+            __syncthreads();
+            if (tid < C) {
+                const int i = tid;
+                const float p = sum4(part2, i);
+                const bool ok = fabsf(p - ps[i]) <= P1_TOL * fabsf(p);
+                const bool all_ok = __all(ok);
+                if (all_ok) {
+                    if (tid == 0) done = 1;
+                } else {
+                    if (tid == 0) done = 0;
+                    ps[i] = p;
+                    cs[i] = cbs[i] - cas[i] * p;
+                }
+            }
+            __syncthreads();
+            if (done) break;
+        }
+        // ---- accepted: (cs, ps) generated Dt and dnew ----
+#pragma unroll
+        for (int m = 0; m < NW; ++m) {
+            const int i = tid + m * NT, r = i / (K / VN), c = (i % (K / VN)) * VN;
+            if (r < nvalid) {
+                float out[VN];
+#pragma unroll
+                for (int e = 0; e < VN; ++e) out[e] = Dt[r * LD + c + e] * vec_get<T>(kcur[m], e);
+                store_vec(kt + (((size_t)b * a.T + t0 + r) * a.H + h) * K + c, out);
+            }
+        }
+        if (a.tok_scalars && tid < nvalid) {
+            const size_t th = ((size_t)b * a.T + t0 + tid) * a.H + h;
+            *reinterpret_cast<float4 *>(a.tok_scalars + th * 4) = make_float4(cs[tid], ps[tid], nraws[tid], 0.f);
+        }
+        if (tid < K) d0[tid] = dnew[tid];
+        __syncthreads();
+    }
+    if (tid < K) a.d_out[bh * K + tid] = d0[tid];
+}
+
+// Reverse sweep.  Per chunk, right to left: replay the chunk's d trajectory from the stored
+// chunk-start value with the per-token step the forward pass kept (recording, per
+// coordinate, a 64-bit mask of the tokens whose unprojected value stayed inside the box);
+// find sigma by sweeps; then every output of the chunk is elementwise.
+//   in : k, beta, retention, d_ckpt, tok_scalars (step, p, n_raw per token), dkt (dL/dk~,
+//        fp32), dk_read (dL/dk read side, fp32), dbeta (partial, from phase 2), dd_out
+//   out: dk (io type) = dk_read + d_t . dkt + phase-1 terms ; dbeta += ; dretention ; dd_in
+template <typename T, int K, bool HAS_RET>
+__global__ __launch_bounds__(NT) void precond_bwd_kernel(PrecondBwdArgs a) {
+    constexpr int LD = K + 1;
+    constexpr int VN = 16 / sizeof(T);
+    constexpr int NW = C * K / VN / NT;
+    constexpr int NF = C * K / 4 / NT;           // float4 vectors per thread for a [64 x K] fp32 tile
+    constexpr int KQ = K / 4;
+    static_assert(VN == 4 || VN == 8, "I/O element is 2 or 4 bytes");
+    __shared__ float ss[C * LD];                 // s = k^2
+    __shared__ float Dt[C * LD];                 // d_i
+    __shared__ float At[C * LD];                 // masked adjoint abar_i
+    __shared__ float lam[C * LD];                // lambda_i = k_i (.) dL/dk~_i
+    __shared__ float ga[K], ganew[K];            // adjoint of d at the right / left end of the chunk
+    __shared__ float cas[C], sig[C];
+    __shared__ __attribute__((aligned(16))) float steps[C];
+    __shared__ __attribute__((aligned(16))) float rs[C];
+    __shared__ __attribute__((aligned(16))) float casig[C];
+    __shared__ float part[4 * C], part2[4 * C];
+    __shared__ int done;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
     const size_t bh = (size_t)b * a.H + h;
     const T *k = static_cast<const T *>(a.k);
     T *dk = static_cast<T *>(a.dk);
     const bool project = a.d_min <= a.d_max;
+    const float lo = project ? a.d_min : -INFINITY, hi = project ? a.d_max : INFINITY;
     const int N = a.T / C;
 
-    float gd[EPL];                      // adjoint of d_{t+1}
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) gd[e] = a.dd_out ? a.dd_out[bh * K + j0 + e] : 0.f;
+    if (tid < K) ga[tid] = a.dd_out ? a.dd_out[bh * K + tid] : 0.f;
+
+    // the [64 x K] tiles are walked as float4 groups: thread -> (row r, 4 columns from c)
+    uint2 kreg2[NF];        // bf16: 4 elements = 8 bytes ; fp32 uses kreg4
+    uint4 kreg4[NF];
+    float4 greg[NF];
+    float4 screg = make_float4(0.f, 0.f, 0.f, 0.f);
+    float betreg = 0.f, retreg = 1.f;
+#define OSDN_P1_BLOAD(n_)                                                                        \
+    {                                                                                            \
+        const size_t tokc_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                     \
+        _Pragma("unroll") for (int m = 0; m < NF; ++m) {                                         \
+            const int i = tid + m * NT, r = i / (K / 4), c = (i % (K / 4)) * 4;                  \
+            const size_t off = (tokc_ + (size_t)r * a.H) * K + c;                                \
+            if (sizeof(T) == 2) kreg2[m] = *reinterpret_cast<const uint2 *>(k + off);            \
+            else kreg4[m] = *reinterpret_cast<const uint4 *>(k + off);                           \
+            greg[m] = *reinterpret_cast<const float4 *>(a.dkt + off);                            \
+        }                                                                                        \
+        if (tid < C) {                                                                           \
+            const size_t th = tokc_ + (size_t)tid * a.H;                                         \
+            screg = *reinterpret_cast<const float4 *>(a.tok_scalars + th * 4);                   \
+            betreg = a.beta[th];                                                                 \
+            if (HAS_RET) retreg = a.retention[th];                                               \
+        }                                                                                        \
+    }
+    OSDN_P1_BLOAD(N - 1)
 
     for (int n = N - 1; n >= 0; --n) {
-        // replay the chunk forward: same arithmetic, same order as precond_fwd_kernel
-        float d[EPL];
+        const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+        // ---- registers -> LDS: s and lambda; k and dL/dk~ stay in registers for the outputs ----
+        float kc[NF][4], gc[NF][4];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) d[e] = a.d_ckpt[(bh * N + n) * K + j0 + e];
-        for (int i = 0; i < C; ++i) {
-            const size_t th = ((size_t)b * a.T + n * C + i) * a.H + h;
-            Row<T, EPL> kr = *reinterpret_cast<const Row<T, EPL> *>(k + th * K + j0);
-            float s[EPL], part_n = 0.f, part_p = 0.f;
+        for (int m = 0; m < NF; ++m) {
+            const int i = tid + m * NT, r = i / (K / 4), c = (i % (K / 4)) * 4;
+            const uint4 kv4 = sizeof(T) == 2 ? make_uint4(kreg2[m].x, kreg2[m].y, 0u, 0u) : kreg4[m];
+            gc[m][0] = greg[m].x; gc[m][1] = greg[m].y; gc[m][2] = greg[m].z; gc[m][3] = greg[m].w;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                d_traj[i][j0 + e] = d[e];
-                const float kv = to_f32(kr.v[e]);
-                s[e] = kv * kv;
-                part_n += s[e];
-                part_p += d[e] * s[e];
-            }
-            const float nn = fmaxf(wave_sum(part_n), a.eps);
-            const float bp = a.beta_aware ? a.beta[th] : 1.f;
-            const float cb = a.eta * bp / nn, ca = cb * bp;
-            const float step = cb - ca * wave_sum(part_p);
-            const float r = a.retention ? a.retention[th] : 1.f;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                float dn = r * d[e] + step * s[e];
-                if (project) dn = fminf(fmaxf(dn, a.d_min), a.d_max);
-                d[e] = dn;
+            for (int e = 0; e < 4; ++e) {
+                kc[m][e] = vec_get<T>(kv4, e);
+                ss[r * LD + c + e] = kc[m][e] * kc[m][e];
+                lam[r * LD + c + e] = kc[m][e] * gc[m][e];
             }
         }
-        // reverse over the chunk (d_traj is private to this wave: no barrier needed,
-        // each lane reads back only what it wrote)
-        for (int i = C - 1; i >= 0; --i) {
-            const size_t th = ((size_t)b * a.T + n * C + i) * a.H + h;
-            Row<T, EPL> kr = *reinterpret_cast<const Row<T, EPL> *>(k + th * K + j0);
-            const float beta = a.beta[th];
-            const float r = a.retention ? a.retention[th] : 1.f;
-            float kv[EPL], s[EPL], dt[EPL], part_n = 0.f, part_p = 0.f;
+        // per-token scalars of this chunk (threads < 64 keep theirs in registers as well)
+        const float step = screg.x, p = screg.y, n_raw = screg.z, bet = betreg, ret = retreg;
+        const float nn = fmaxf(n_raw, a.eps);
+        const float bp = a.beta_aware ? bet : 1.f;
+        const float ca = a.eta * bp / nn * bp;
+        if (tid < C) { steps[tid] = step; rs[tid] = ret; cas[tid] = ca; sig[tid] = 0.f; casig[tid] = 0.f; }
+        float d = 0.f;
+        if (tid < K) d = a.d_ckpt[(bh * N + n) * K + tid];
+        __syncthreads();
+        if (n > 0) OSDN_P1_BLOAD(n - 1)
+        // ---- replay the chunk forward (same arithmetic as the forward kernel) ----
+        uint32_t mlo = 0u, mhi = 0u;            // bit i: the unprojected d_{i+1} lies inside the box
+        if (tid < K) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                kv[e] = to_f32(kr.v[e]);
-                s[e] = kv[e] * kv[e];
-                dt[e] = d_traj[i][j0 + e];
-                part_n += s[e];
-                part_p += dt[e] * s[e];
+            for (int i = 0; i < C; ++i) {
+                Dt[i * LD + tid] = d;
+                const float db = d_bar<HAS_RET>(rs[i], d, steps[i], ss[i * LD + tid]);
+                d = clip3(db, lo, hi);
+                const uint32_t in = (d == db) ? 1u : 0u;
+                if (i < 32) mlo |= in << i; else mhi |= in << (i - 32);
             }
-            const float n_raw = wave_sum(part_n);
-            const float nn = fmaxf(n_raw, a.eps);
-            const float p = wave_sum(part_p);
-            const float bp = a.beta_aware ? beta : 1.f;
-            const float cb = a.eta * bp / nn, ca = cb * bp;
-            const float step = cb - ca * p;
-            // mask by the projection, then the two inner products with the masked adjoint
-            float part_r = 0.f, part_c = 0.f;
+        }
+        // ---- sweeps for sigma_i = <s_i, abar_i> ----
+        for (int sweep = 0; sweep < P1_MAX_SWEEPS; ++sweep) {
+            if (tid < K) {
+                float av = ga[tid];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                const float dbar = r * dt[e] + step * s[e];
-                if (project && !(dbar >= a.d_min && dbar <= a.d_max)) gd[e] = 0.f;
-                part_r += gd[e] * dt[e];
-                part_c += gd[e] * s[e];
+                for (int i = C - 1; i >= 0; --i) {
+                    const uint32_t bit = i < 32 ? (mlo >> i) & 1u : (mhi >> (i - 32)) & 1u;
+                    const float ab = bit ? av : 0.f;
+                    At[i * LD + tid] = ab;
+                    const float t = HAS_RET ? __builtin_fmaf(rs[i], ab, lam[i * LD + tid]) : ab + lam[i * LD + tid];
+                    av = __builtin_fmaf(-casig[i], ss[i * LD + tid], t);
+                }
+                ganew[tid] = av;
             }
-            const float g_r = wave_sum(part_r);
-            const float g_c = wave_sum(part_c);
+            __syncthreads();
+            {
+                const int i = lane, q0 = wave * KQ;
+                float sp = 0.f;
+#pragma unroll 8
+                for (int c = 0; c < KQ; ++c) sp = __builtin_fmaf(ss[i * LD + q0 + c], At[i * LD + q0 + c], sp);
+                part[wave * C + i] = sp;
+            }
+            __syncthreads();
+            if (tid < C) {
+                const int i = tid;
+                const float sg = sum4(part, i);
+                const float mx = wave_max(fabsf(sg));
+                const bool ok = fabsf(sg - sig[i]) <= P1_TOL * mx;
+                const bool all_ok = __all(ok);
+                if (all_ok) {
+                    if (tid == 0) done = 1;
+                } else {
+                    if (tid == 0) done = 0;
+                    sig[i] = sg;
+                    casig[i] = cas[i] * sg;
+                }
+            }
+            __syncthreads();
+            if (done) break;
+        }
+        // ---- accepted: sig generated At and ganew.  g_r = <abar_i, d_i> if it is asked for ----
+        if (a.dretention) {
+            const int i = lane, q0 = wave * KQ;
+            float sp = 0.f;
+#pragma unroll 8
+            for (int c = 0; c < KQ; ++c) sp = __builtin_fmaf(At[i * LD + q0 + c], Dt[i * LD + q0 + c], sp);
+            part2[wave * C + i] = sp;
+        }
+        // per-token scalars that enter the elementwise outputs: g_p, g_nraw -> part[0..2*64)
+        if (tid < C) {
+            const float g_c = sig[tid];
             const float g_p = -g_c * ca;
             const float g_nraw = (n_raw >= a.eps) ? -g_c * step / nn : 0.f;
             const float g_bp = g_c * a.eta * (1.f - 2.f * bp * p) / nn;
-            const size_t off = th * K + j0;
-            Row<T, EPL> out;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                const float gkt = a.dkt[off + e];
-                const float gs = step * gd[e] + g_p * dt[e] + g_nraw;
-                const float gk = a.dk_read[off + e] + dt[e] * gkt + 2.f * kv[e] * gs;
-                out.v[e] = from_f32<T>(gk);
-                gd[e] = r * gd[e] + g_p * s[e] + kv[e] * gkt;
-            }
-            *reinterpret_cast<Row<T, EPL> *>(dk + off) = out;
-            if (lane == 0) {
-                if (a.beta_aware) a.dbeta[th] += g_bp;
-                if (a.dretention) a.dretention[th] = g_r;
-            }
+            part[tid] = g_p;
+            part[C + tid] = g_nraw;
+            const size_t th = tokc + (size_t)tid * a.H;
+            if (a.beta_aware) a.dbeta[th] += g_bp;
         }
-    }
+        __syncthreads();
+        if (a.dretention && tid < C) a.dretention[tokc + (size_t)tid * a.H] = sum4(part2, tid);
+        // dk = dk_read + d_i . dkt + 2 k (step abar + g_p d_i + g_nraw)
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) a.dd_in[bh * K + j0 + e] = gd[e];
+        for (int m = 0; m < NF; ++m) {
+            const int i = tid + m * NT, r = i / (K / 4), c = (i % (K / 4)) * 4;
+            const size_t off = (tokc + (size_t)r * a.H) * K + c;
+            const float4 rd = *reinterpret_cast<const float4 *>(a.dk_read + off);
+            const float rdv[4] = {rd.x, rd.y, rd.z, rd.w};
+            const float st = steps[r], g_p = part[r], g_nraw = part[C + r];
+            float out[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int x = r * LD + c + e;
+                const float gs = st * At[x] + g_p * Dt[x] + g_nraw;
+                out[e] = rdv[e] + Dt[x] * gc[m][e] + 2.f * kc[m][e] * gs;
+            }
+            store_vec(dk + off, out);
+        }
+        if (tid < K) ga[tid] = ganew[tid];
+        __syncthreads();
+    }
+    if (tid < K) a.dd_in[bh * K + tid] = ga[tid];
 }
 
-template <typename T>
+template <typename T, bool HAS_RET>
 static int launch_precond_fwd_t(const PrecondArgs &a, hipStream_t st) {
-    dim3 grid(a.B * a.H), block(64);
-    if (a.K == 64) hipLaunchKernelGGL((precond_fwd_kernel<T, 1>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((precond_fwd_kernel<T, 2>), grid, block, 0, st, a);
+    dim3 grid(a.B * a.H), block(NT);
+    if (a.K == 64) hipLaunchKernelGGL((precond_fwd_kernel<T, 64, HAS_RET>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((precond_fwd_kernel<T, 128, HAS_RET>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
 int launch_precond_fwd(const PrecondArgs &a, bool bf16_io, hipStream_t st) {
-    return bf16_io ? launch_precond_fwd_t<bf16>(a, st) : launch_precond_fwd_t<float>(a, st);
+    if (a.retention)
+        return bf16_io ? launch_precond_fwd_t<bf16, true>(a, st) : launch_precond_fwd_t<float, true>(a, st);
+    return bf16_io ? launch_precond_fwd_t<bf16, false>(a, st) : launch_precond_fwd_t<float, false>(a, st);
 }
 
-template <typename T>
+template <typename T, bool HAS_RET>
 static int launch_precond_bwd_t(const PrecondBwdArgs &a, hipStream_t st) {
-    dim3 grid(a.B * a.H), block(64);
-    if (a.K == 64) hipLaunchKernelGGL((precond_bwd_kernel<T, 1>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((precond_bwd_kernel<T, 2>), grid, block, 0, st, a);
+    dim3 grid(a.B * a.H), block(NT);
+    if (a.K == 64) hipLaunchKernelGGL((precond_bwd_kernel<T, 64, HAS_RET>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((precond_bwd_kernel<T, 128, HAS_RET>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
 int launch_precond_bwd(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) {
-    return bf16_io ? launch_precond_bwd_t<bf16>(a, st) : launch_precond_bwd_t<float>(a, st);
+    if (a.retention)
+        return bf16_io ? launch_precond_bwd_t<bf16, true>(a, st) : launch_precond_bwd_t<float, true>(a, st);
+    return bf16_io ? launch_precond_bwd_t<bf16, false>(a, st) : launch_precond_bwd_t<float, false>(a, st);
 }
 
 }  // namespace osdn

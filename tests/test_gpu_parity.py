@@ -87,11 +87,16 @@ def test_precond_checkpoints_and_carry():
     kt, d_out, ck = ob.precond_update(t["k"], t["beta"], t["retention"], t["d_in"], hp, want_ckpt=True)
     _, _, traj = oracle.precond(x["k"], x["beta"], x["retention"], x["d_in"], oracle_hp(hp), want_traj=True)
     check("d_ckpt", ck, traj[:, ::64].transpose(0, 2, 1, 3), False)
-    k1, d1 = ob.precond_update(t["k"][:, :100].contiguous(), t["beta"][:, :100].contiguous(),
-                               t["retention"][:, :100].contiguous(), t["d_in"], hp)
-    k2, d2 = ob.precond_update(t["k"][:, 100:].contiguous(), t["beta"][:, 100:].contiguous(),
-                               t["retention"][:, 100:].contiguous(), d1, hp)
-    assert torch.equal(torch.cat([k1, k2], 1), kt) and torch.equal(d2, d_out)
+    for cut in (128, 100):
+        k1, d1 = ob.precond_update(t["k"][:, :cut].contiguous(), t["beta"][:, :cut].contiguous(),
+                                   t["retention"][:, :cut].contiguous(), t["d_in"], hp)
+        k2, d2 = ob.precond_update(t["k"][:, cut:].contiguous(), t["beta"][:, cut:].contiguous(),
+                                   t["retention"][:, cut:].contiguous(), d1, hp)
+        if cut % 64 == 0:       # same chunking => same arithmetic, bit for bit
+            assert torch.equal(torch.cat([k1, k2], 1), kt) and torch.equal(d2, d_out)
+        else:                   # chunks shifted against the sweep's 64-token windows: rounding only
+            assert (torch.cat([k1, k2], 1) - kt).abs().max() <= 1e-5
+            assert (d2 - d_out).abs().max() <= 1e-5
 
 
 def test_resume_split_sequence():
