@@ -31,6 +31,14 @@ PEAK_BF16_FLOPS = 2.5e15       # MI355X dense bf16 MFMA
 PEAK_HBM_BYTES = 8.0e12        # MI355X HBM3E
 PEAK_FP32_VALU = 157.3e12
 
+# HBM bytes per launch on configs[2], from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by the
+# factors a 1 GiB device copy gives: fetch x 2.0, write x 1.0); see
+# profiles/hbm_traffic_configs2_fwd_bwd.txt.  Offline figures: bench.py cannot read PMCs.
+MEASURED_TRAFFIC_CONFIG2 = {
+    "precond_fwd": 153.2e6, "chunk_prep": 372.1e6, "state_fwd": 885.1e6, "output_fwd": 404.3e6,
+    "bwd_local": 270.0e6, "bwd_chain": 1287.9e6, "bwd_post": 1252.5e6, "precond_bwd": 463.7e6,
+}
+
 
 def kernel_models(cfg, es):
     """Algorithmic work of each kernel per launch: (bound, amount, unit-per-second peak).
@@ -73,6 +81,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain device copy of 1 GiB (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every (batch, head) chain is independent; "
@@ -114,6 +124,12 @@ def main():
             ob.osdn_bwd(p, tq, tk, tv, tb, tg, tr, None, None, tdO, None, None, dq, dk, dv, dbeta, dg, dr,
                         dd_in, dS_in, ws)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                               # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -145,6 +161,8 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": nbytes / dur / 1e9, "peak": PEAK_HBM_BYTES / 1e9,
                 "unit": "GB/s", "frac": hbm_frac, "traffic": None}
+    if args.config == 2:
+        roof["traffic"] = MEASURED_TRAFFIC_CONFIG2.get(dominant)
     roof["kernel"] = dominant
     roof["kernel_ms"] = per_kernel[dominant]
     roof["per_kernel_ms"] = {k: round(v, 4) for k, v in per_kernel.items()}
@@ -161,7 +179,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         nthreads = oracle.threads()
-        nch = min(cfg.B * cfg.H, 2 * nthreads)
+        nch = min(cfg.B * cfg.H, 8 * nthreads)       # ~10-30 core-seconds of oracle work
         chains = [(i // cfg.H, i % cfg.H) for i in range(nch)]
         sub = {}
         for name in ("q", "k", "v", "dO", "beta", "log_alpha", "retention"):

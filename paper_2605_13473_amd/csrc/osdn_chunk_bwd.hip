@@ -102,7 +102,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
     __shared__ __attribute__((aligned(16))) T dSb[VS * LDK];    // dS' in the I/O type
     __shared__ __attribute__((aligned(16))) T dEt[VS * LDC];    // dE^T
 
-    const int vs = blockIdx.x * VS, h = blockIdx.y, b = blockIdx.z;
+    int chain, slice;
+    chain_slice_of(blockIdx.x, a.V / VS, a.B * a.H, chain, slice);
+    const int vs = slice * VS, h = chain % a.H, b = chain / a.H;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const size_t bh = (size_t)b * a.H + h;
     const size_t tstride = a.H;
@@ -515,7 +517,7 @@ int launch_bwd_local(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T>
 static int launch_chain_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.V / VS, a.H, a.B), block(NT);
+    dim3 grid((a.V / VS) * a.H * a.B), block(NT);
     if (a.K == 64) hipLaunchKernelGGL((bwd_chain_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((bwd_chain_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;

@@ -187,4 +187,19 @@ __device__ __forceinline__ size_t tok_off(int b, int t, int h, int T, int H, int
     return (((size_t)b * T + t) * H + h) * (size_t)D;
 }
 
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  The chain kernels
+// run V/VS workgroups per (batch, head) chain that all read the same W / K~ / Q tiles: this
+// maps a 1-D workgroup id so that the slices of one chain share an XCD (and its L2).
+constexpr int NUM_XCD = 8;
+__device__ __forceinline__ void chain_slice_of(int wg, int nslices, int nchains, int &chain, int &slice) {
+    if (nchains % NUM_XCD == 0) {
+        const int xcd = wg % NUM_XCD, j = wg / NUM_XCD;
+        slice = j % nslices;
+        chain = xcd + NUM_XCD * (j / nslices);
+    } else {
+        slice = wg % nslices;
+        chain = wg / nslices;
+    }
+}
+
 }  // namespace osdn
