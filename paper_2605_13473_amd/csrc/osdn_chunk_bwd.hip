@@ -216,28 +216,31 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
 }
 
 // -------------------------------------------------------------- bwd_post ----
-// One workgroup per chunk and head.  V is walked in slabs of VB columns; the slab buffers
-// are reused for Q and K~ once the walk is over.
+// One workgroup of 8 wavefronts per chunk and head (two per SIMD, so that LDS and MFMA
+// latencies of one overlap with the other's issue).  V is walked in slabs of VB columns; the
+// slab buffers are reused for Q and K~ once the walk is over.
+constexpr int PT_ = 512, PW_ = PT_ / 64;     // threads / wavefronts of bwd_post
+
 template <typename T, int K>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void bwd_post_kernel(ChunkArgs a) {
+__global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
     constexpr int VB = sizeof(T) == 2 ? 64 : 32;        // slab width
     constexpr int LDV = VB + PAD;
-    constexpr int NKT = K / 64;                          // [64 x K] column tiles per wave
-    constexpr int NVT = VB / 16;
+    constexpr int NVT = VB / 16;                         // column tiles of a slab
+    constexpr int NVW = NVT / 2;                         // ... per wave in step (1)
     constexpr int KS = Mfma<T>::KSTEP;
     // persistent
     __shared__ __attribute__((aligned(16))) T Ks[C * LDK];
-    __shared__ __attribute__((aligned(16))) T Tt[C * LDC];
+    __shared__ __attribute__((aligned(16))) T Tt[C * LDC];       // T; after the walk: cA
     __shared__ float Gs[C], Bs[C];
-    __shared__ float red[4 * C];                         // [4][64] partial sums across tiles / waves
+    __shared__ float red[4 * C];                         // [4][64] partial sums across tiles
     __shared__ float red2[4 * C];
     __shared__ float red3[4 * C];
-    __shared__ float dbeta_s[C];
-    __shared__ float sdot[NT / 64];
-    // slab buffers, later Q / K~ / cA / cP
+    __shared__ float dbeta_s[2 * C];
+    __shared__ float sdot[PW_];
+    // slab buffers, later Q / K~ / cP and the row-dot partials
     constexpr int SLAB_ELEMS = 3 * C * LDV + 2 * VB * LDC + 2 * VB * LDK;
-    constexpr int POST_ELEMS = 2 * C * LDK + 2 * C * LDC;
+    constexpr int POST_ELEMS = 2 * C * LDK + C * LDC + (3 * PW_ * C * 4) / (int)sizeof(T);
     constexpr int POOL = SLAB_ELEMS > POST_ELEMS ? SLAB_ELEMS : POST_ELEMS;
     __shared__ __attribute__((aligned(16))) T pool[POOL];
     T *dOs = pool;                      // [64][LDV]  dO slab (natural), later dV staging
@@ -249,14 +252,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
     T *dSs = Ss + VB * LDK;             // [VB][LDK]  dS' slab
     T *Qs = pool;                       // after the walk
     T *Kts = Qs + C * LDK;
-    T *cAs = Kts + C * LDK;             // [64][LDC]
-    T *cPs = cAs + C * LDC;             // [64][LDC]
+    T *cPs = Kts + C * LDK;             // [64][LDC]
+    float *pq = reinterpret_cast<float *>(cPs + C * LDC);        // [PW_][64] x 3
+    T *cAs = Tt;                        // [64][LDC]
 
     const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
     const size_t tstride = a.H;
+    const int ct = wave * 16;           // this wave's column tile of the [64 x K] results
+    const bool has_ct = ct < K;
 
     if (wave == 0) {
         const size_t th = tok0 + (size_t)lane * tstride;
@@ -264,62 +270,79 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
         Gs[lane] = wave_cumsum(g, lane);
         Bs[lane] = a.beta[th];
     }
-    load_tile(Ks, LDK, static_cast<const T *>(a.k) + tok0 * K, tstride * K, C, K, tid, NT);
-    load_tile(Tt, LDC, static_cast<const T *>(a.Tm) + bhn * C * C, (size_t)C, C, C, tid, NT);
+    load_tile(Ks, LDK, static_cast<const T *>(a.k) + tok0 * K, tstride * K, C, K, tid, PT_);
+    load_tile(Tt, LDC, static_cast<const T *>(a.Tm) + bhn * C * C, (size_t)C, C, C, tid, PT_);
 
     // accumulators over the walk
-    f32x4 dP[3], dA[3];                 // the lower tiles idx = wave, wave+4, wave+8 (< 10)
-    f32x4 dQg[4][NKT], dKg[4][NKT], dKr[4][NKT];   // [row block][column tile of this wave]
-    float dbeta_part[4] = {0.f, 0.f, 0.f, 0.f};     // rows 16*wave + acc_row(lane, r)
+    f32x4 dP[2], dA[2];                 // the lower tiles idx = wave, wave + 8 (< 10)
+    f32x4 dQg[4], dKg[4], dKr[4];       // [row block], column tile ct
+    float dbeta_part[4] = {0.f, 0.f, 0.f, 0.f};     // rows 16*(wave/2) + acc_row(lane, r), this wave's columns
     float ss_part = 0.f;                // <dS', S>
 #pragma unroll
-    for (int t = 0; t < 3; ++t) { dP[t] = f32x4{0.f, 0.f, 0.f, 0.f}; dA[t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int t = 0; t < 2; ++t) { dP[t] = f32x4{0.f, 0.f, 0.f, 0.f}; dA[t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-    for (int ib = 0; ib < 4; ++ib)
-#pragma unroll
-        for (int qn = 0; qn < NKT; ++qn) {
-            dQg[ib][qn] = f32x4{0.f, 0.f, 0.f, 0.f};
-            dKg[ib][qn] = f32x4{0.f, 0.f, 0.f, 0.f};
-            dKr[ib][qn] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+    for (int ib = 0; ib < 4; ++ib) {
+        dQg[ib] = f32x4{0.f, 0.f, 0.f, 0.f};
+        dKg[ib] = f32x4{0.f, 0.f, 0.f, 0.f};
+        dKr[ib] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const int rb = wave >> 1;           // row block of steps (1), (2)
 
     for (int v0 = 0; v0 < a.V; v0 += VB) {
         __syncthreads();
-        load_tile(dOs, LDV, static_cast<const T *>(a.dO) + tok0 * a.V + v0, tstride * a.V, C, VB, tid, NT);
-        load_tile(Vs, LDV, static_cast<const T *>(a.v) + tok0 * a.V + v0, tstride * a.V, C, VB, tid, NT);
-        load_tile(Ets, LDC, static_cast<const T *>(a.Et) + (bhn * a.V + v0) * C, (size_t)C, VB, C, tid, NT);
-        load_tile(dEts, LDC, static_cast<const T *>(a.dEt) + (bhn * a.V + v0) * C, (size_t)C, VB, C, tid, NT);
-        load_tile(Ss, LDK, static_cast<const T *>(a.S_ckpt) + (bhn * a.V + v0) * K, (size_t)K, VB, K, tid, NT);
-        load_tile(dSs, LDK, static_cast<const T *>(a.dS_ckpt) + (bhn * a.V + v0) * K, (size_t)K, VB, K, tid, NT);
+        load_tile(dOs, LDV, static_cast<const T *>(a.dO) + tok0 * a.V + v0, tstride * a.V, C, VB, tid, PT_);
+        load_tile(Vs, LDV, static_cast<const T *>(a.v) + tok0 * a.V + v0, tstride * a.V, C, VB, tid, PT_);
+        load_tile(Ets, LDC, static_cast<const T *>(a.Et) + (bhn * a.V + v0) * C, (size_t)C, VB, C, tid, PT_);
+        load_tile(dEts, LDC, static_cast<const T *>(a.dEt) + (bhn * a.V + v0) * C, (size_t)C, VB, C, tid, PT_);
+        load_tile(Ss, LDK, static_cast<const T *>(a.S_ckpt) + (bhn * a.V + v0) * K, (size_t)K, VB, K, tid, PT_);
+        load_tile(dSs, LDK, static_cast<const T *>(a.dS_ckpt) + (bhn * a.V + v0) * K, (size_t)K, VB, K, tid, PT_);
         __syncthreads();
         // <dS', S> over this slab
-        for (int idx = tid; idx < VB * K; idx += NT) {
+        for (int idx = tid; idx < VB * K; idx += PT_) {
             const int r = idx / K, c = idx % K;
             ss_part += to_f32(Ss[r * LDK + c]) * to_f32(dSs[r * LDK + c]);
         }
-        // (1) dR = T^T dE, rows j = 16*wave.. ; (2) R0 = V - gamma . (K S^T), same rows
+        // (1) dR = T^T dE, rows j = 16*rb.. ; (2) R0 = V - gamma . (K S^T), same rows
         {
-            const int k0 = (wave * 16) / KS * KS;       // T[i][j] = 0 for i < j
+            const int k0 = (rb * 16) / KS * KS;         // T[i][j] = 0 for i < j
+            f32x4 dr[NVW], ks[NVW];
 #pragma unroll
-            for (int vt = 0; vt < NVT; ++vt) {
-                f32x4 dr = {0.f, 0.f, 0.f, 0.f}, ks = {0.f, 0.f, 0.f, 0.f};
-                mma_tile<T, false, true>(dr, Tt + k0 * LDC + wave * 16, LDC, dEts + vt * 16 * LDC + k0, LDC,
-                                         C - k0, lane);
-                mma_tile<T, true, true>(ks, Ks + wave * 16 * LDK, LDK, Ss + vt * 16 * LDK, LDK, K, lane);
+            for (int q = 0; q < NVW; ++q) { dr[q] = f32x4{0.f, 0.f, 0.f, 0.f}; ks[q] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+            for (int kk = k0; kk < C; kk += KS) {
+                typename Mfma<T>::Frag ft = Mfma<T>::template load<false>(Tt + kk * LDC + rb * 16, LDC, lane);
+#pragma unroll
+                for (int q = 0; q < NVW; ++q) {
+                    const int vt = (wave & 1) * NVW + q;
+                    typename Mfma<T>::Frag fe = Mfma<T>::template load<true>(dEts + vt * 16 * LDC + kk, LDC, lane);
+                    dr[q] = Mfma<T>::mma(ft, fe, dr[q]);
+                }
+            }
+            for (int kk = 0; kk < K; kk += KS) {
+                typename Mfma<T>::Frag fk = Mfma<T>::template load<true>(Ks + rb * 16 * LDK + kk, LDK, lane);
+#pragma unroll
+                for (int q = 0; q < NVW; ++q) {
+                    const int vt = (wave & 1) * NVW + q;
+                    typename Mfma<T>::Frag fs = Mfma<T>::template load<true>(Ss + vt * 16 * LDK + kk, LDK, lane);
+                    ks[q] = Mfma<T>::mma(fk, fs, ks[q]);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < NVW; ++q) {
+                const int vt = (wave & 1) * NVW + q;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int i = wave * 16 + acc_row(lane, r), c = vt * 16 + acc_col(lane);
-                    const float r0 = to_f32(Vs[i * LDV + c]) - __expf(Gs[i]) * ks[r];
-                    dbeta_part[r] += dr[r] * r0;
+                    const int i = rb * 16 + acc_row(lane, r), c = vt * 16 + acc_col(lane);
+                    const float r0 = to_f32(Vs[i * LDV + c]) - __expf(Gs[i]) * ks[q][r];
+                    dbeta_part[r] += dr[q][r] * r0;
                 }
-                store_tile(dRs + wave * 16 * LDV + vt * 16, LDV, dr, lane);
+                store_tile(dRs + rb * 16 * LDV + vt * 16, LDV, dr[q], lane);
             }
         }
         __syncthreads();
         // (3,4) dP += dO E^T, dA -= dR E^T on the lower tiles
 #pragma unroll
-        for (int t = 0; t < 3; ++t) {
-            const int idx = wave + 4 * t;
+        for (int t = 0; t < 2; ++t) {
+            const int idx = wave + PW_ * t;
             if (idx < 10) {
                 const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
                 const int jb = idx - (ib * (ib + 1)) / 2;
@@ -332,10 +355,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
                 }
             }
         }
-        // (5,6,7) dQg += dO S ; dKg += dR S ; dKr += E dS'
-#pragma unroll
-        for (int qn = 0; qn < NKT; ++qn) {
-            const int ct = (wave * NKT + qn) * 16;
+        // (5,6,7) dQg += dO S ; dKg += dR S ; dKr += E dS'   (column tile ct)
+        if (has_ct) {
             for (int kk = 0; kk < VB; kk += KS) {
                 typename Mfma<T>::Frag fs = Mfma<T>::template load<false>(Ss + kk * LDK + ct, LDK, lane);
                 typename Mfma<T>::Frag fd = Mfma<T>::template load<false>(dSs + kk * LDK + ct, LDK, lane);
@@ -344,38 +365,44 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
                     typename Mfma<T>::Frag fo = Mfma<T>::template load<true>(dOs + ib * 16 * LDV + kk, LDV, lane);
                     typename Mfma<T>::Frag fr = Mfma<T>::template load<true>(dRs + ib * 16 * LDV + kk, LDV, lane);
                     typename Mfma<T>::Frag fe = Mfma<T>::template load<false>(Ets + kk * LDC + ib * 16, LDC, lane);
-                    dQg[ib][qn] = Mfma<T>::mma(fo, fs, dQg[ib][qn]);
-                    dKg[ib][qn] = Mfma<T>::mma(fr, fs, dKg[ib][qn]);
-                    dKr[ib][qn] = Mfma<T>::mma(fe, fd, dKr[ib][qn]);
+                    dQg[ib] = Mfma<T>::mma(fo, fs, dQg[ib]);
+                    dKg[ib] = Mfma<T>::mma(fr, fs, dKg[ib]);
+                    dKr[ib] = Mfma<T>::mma(fe, fd, dKr[ib]);
                 }
             }
         }
         __syncthreads();
         // dV = beta . dR for this slab, staged through the dO buffer
-        for (int idx = tid; idx < C * VB; idx += NT) {
+        for (int idx = tid; idx < C * VB; idx += PT_) {
             const int r = idx / VB, c = idx % VB;
             dOs[r * LDV + c] = from_f32<T>(Bs[r] * to_f32(dRs[r * LDV + c]));
         }
         __syncthreads();
-        store_tile_global(static_cast<T *>(a.dv) + tok0 * a.V + v0, tstride * a.V, dOs, LDV, C, VB, tid, NT);
+        store_tile_global(static_cast<T *>(a.dv) + tok0 * a.V + v0, tstride * a.V, dOs, LDV, C, VB, tid, PT_);
     }
     __syncthreads();
     // ---- after the walk: Q, K~ into the pool ----
-    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, NT);
-    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, NT);
-    for (int idx = tid; idx < C * C; idx += NT) {       // upper triangle of cA, cP is zero
+    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, PT_);
+    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, PT_);
+    for (int idx = tid; idx < C * C; idx += PT_) {      // upper triangle of cA, cP is zero
         const int i = idx >> 6, j = idx & 63;
         cAs[i * LDC + j] = from_f32<T>(0.f);
         cPs[i * LDC + j] = from_f32<T>(0.f);
     }
     ss_part = wave_sum(ss_part);
     if (lane == 0) sdot[wave] = ss_part;
-    for (int idx = tid; idx < 4 * C; idx += NT) { red[idx] = 0.f; red2[idx] = 0.f; red3[idx] = 0.f; }
+    for (int idx = tid; idx < 4 * C; idx += PT_) { red[idx] = 0.f; red2[idx] = 0.f; red3[idx] = 0.f; }
+    // dbeta: the walk's part, reduced over the 16 lanes of a row; two waves share a row block
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float sred = row16_sum(dbeta_part[r]);
+        if (acc_col(lane) == 0) dbeta_s[(wave & 1) * C + rb * 16 + acc_row(lane, r)] = sred;
+    }
     __syncthreads();
     // ---- lower tiles: A0, P, X, cA, cP ----
 #pragma unroll
-    for (int t = 0; t < 3; ++t) {
-        const int idx = wave + 4 * t;
+    for (int t = 0; t < 2; ++t) {
+        const int idx = wave + PW_ * t;
         if (idx < 10) {
             const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
             const int jb = idx - (ib * (ib + 1)) / 2;
@@ -409,14 +436,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
             store_tile(cPs + ib * 16 * LDC + jb * 16, LDC, cp, lane);
         }
     }
-    // dbeta: the walk's part (rows 16*wave + acc_row) reduced over the 16 lanes of a row
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const float s = row16_sum(dbeta_part[r]);
-        if (acc_col(lane) == 0) dbeta_s[wave * 16 + acc_row(lane, r)] = s;
-    }
     __syncthreads();
-    // ---- dQ, dK (read side), dK~ and the inner products that enter dG ----
+    // ---- dQ, dK (read side), dK~ and the inner products that enter dG (column tile ct) ----
     float tq[4][4], tk[4][4], tr[4][4];     // [row block][r]: partial row dots over this wave's columns
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib)
@@ -425,9 +446,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
     T *dq_g = static_cast<T *>(a.dq) + tok0 * K;
     float *dk_g = a.dk_read + tok0 * K;
     float *dkt_g = a.dkt + tok0 * K;
-#pragma unroll
-    for (int qn = 0; qn < NKT; ++qn) {
-        const int ct = (wave * NKT + qn) * 16;
+    if (has_ct) {
 #pragma unroll
         for (int ib = 0; ib < 4; ++ib) {
             f32x4 aq = {0.f, 0.f, 0.f, 0.f}, ak = {0.f, 0.f, 0.f, 0.f}, at = {0.f, 0.f, 0.f, 0.f};
@@ -454,9 +473,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
             for (int r = 0; r < 4; ++r) {
                 const int i = ib * 16 + acc_row(lane, r), c = ct + acc_col(lane);
                 const float gam = __expf(Gs[i]), rho = __expf(Gs[C - 1] - Gs[i]);
-                const float gq = a.scale * gam * dQg[ib][qn][r];        // gamma . d(gamma Q)
-                const float gk = -Bs[i] * gam * dKg[ib][qn][r];          // gamma . d(gamma K)
-                const float gr = rho * dKr[ib][qn][r];                   // rho . d(rho K~)
+                const float gq = a.scale * gam * dQg[ib][r];         // gamma . d(gamma Q)
+                const float gk = -Bs[i] * gam * dKg[ib][r];           // gamma . d(gamma K)
+                const float gr = rho * dKr[ib][r];                    // rho . d(rho K~)
                 const float qv = to_f32(Qs[i * LDK + c]), kv = to_f32(Ks[i * LDK + c]),
                             ktv = to_f32(Kts[i * LDK + c]);
                 tq[ib][r] += gq * qv;
@@ -468,10 +487,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
             }
         }
     }
-    __syncthreads();        // red/red2/red3 consumers below; also everyone is done with Qs/Ks/Kts
     // per-row sums across the 16 lanes of a row, then across waves through LDS
-    float *pq = reinterpret_cast<float *>(pool);      // [4 waves][64 rows] x 3, reusing the pool
-    float *pk = pq + 4 * C, *pr = pk + 4 * C;
+    float *pk = pq + PW_ * C, *pr = pk + PW_ * C;
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
@@ -485,19 +502,21 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void
     __syncthreads();
     if (wave == 0) {
         const int i = lane;
-        const float t_q = pq[i] + pq[C + i] + pq[2 * C + i] + pq[3 * C + i];
-        const float t_k = pk[i] + pk[C + i] + pk[2 * C + i] + pk[3 * C + i];
-        const float t_r = pr[i] + pr[C + i] + pr[2 * C + i] + pr[3 * C + i];
+        float t_q = 0.f, t_k = 0.f, t_r = 0.f;
+#pragma unroll
+        for (int w = 0; w < PW_; ++w) { t_q += pq[w * C + i]; t_k += pk[w * C + i]; t_r += pr[w * C + i]; }
         const float rowa = red[i] + red[C + i] + red[2 * C + i] + red[3 * C + i];
         const float rowx = red2[i] + red2[C + i] + red2[2 * C + i] + red2[3 * C + i];
         const float colx = red3[i] + red3[C + i] + red3[2 * C + i] + red3[3 * C + i];
         const size_t th = tok0 + (size_t)i * tstride;
-        a.dbeta[th] = dbeta_s[i] + rowa;
+        a.dbeta[th] = dbeta_s[i] + dbeta_s[C + i] + rowa;
         if (a.dlog_alpha) {
             float dG = rowx - colx + t_q + t_k - t_r;
             const float tr_sum = wave_sum(t_r);
-            const float ss = sdot[0] + sdot[1] + sdot[2] + sdot[3];
-            if (i == C - 1) dG += tr_sum + __expf(Gs[C - 1]) * ss;
+            float ssum = 0.f;
+#pragma unroll
+            for (int w = 0; w < PW_; ++w) ssum += sdot[w];
+            if (i == C - 1) dG += tr_sum + __expf(Gs[C - 1]) * ssum;
             a.dlog_alpha[th] = wave_suffix_sum(dG, lane);
         }
     }
@@ -528,7 +547,7 @@ int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T>
 static int launch_post_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.N, a.H, a.B), block(NT);
+    dim3 grid(a.N, a.H, a.B), block(PT_);
     if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;
