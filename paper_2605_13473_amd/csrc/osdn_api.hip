@@ -32,8 +32,8 @@ template <typename F> int timed(int id, hipStream_t st, F &&launch) {
 }
 
 struct Layout {
-    size_t kt, d_ckpt, tok_scalars, Tm, W, U, Et, S_ckpt;   // forward
-    size_t dEl, dEt, dS_ckpt, dk_read, dkt;             // backward only
+    size_t kt, d_ckpt, tok_scalars, Tm, W, Wt, Ktr, Ut, Et, S_ckpt;   // forward
+    size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt;   // backward only
     size_t total_fwd, total_bwd;
 };
 
@@ -67,11 +67,15 @@ Layout make_layout(const osdn_params *p) {
     L.tok_scalars = take(B * T * H * 4 * 4);
     L.Tm = take(B * H * N * C * C * es);
     L.W = take(B * T * H * K * es);
-    L.U = take(B * T * H * V * es);
+    L.Wt = take(B * T * H * K * es);
+    L.Ktr = take(B * T * H * K * es);
+    L.Ut = take(B * T * H * V * es);
     L.Et = take(B * T * H * V * es);
     L.S_ckpt = take(B * H * N * V * K * es);
     L.total_fwd = off;
-    L.dEl = take(B * T * H * V * es);
+    L.dElt = take(B * T * H * V * es);
+    L.Qt = take(B * T * H * K * es);
+    L.dOt = take(B * T * H * V * es);
     L.dEt = take(B * T * H * V * es);
     L.dS_ckpt = take(B * H * N * V * K * es);
     L.dk_read = take(B * T * H * K * 4);
@@ -100,7 +104,8 @@ ChunkArgs chunk_args(const osdn_params *p, const Layout &L, char *ws) {
     ChunkArgs c{};
     c.B = p->B; c.T = p->T; c.H = p->H; c.K = p->K; c.V = p->V; c.N = p->T / C;
     c.scale = p->scale;
-    c.kt = ws + L.kt; c.Tm = ws + L.Tm; c.W = ws + L.W; c.U = ws + L.U; c.Et = ws + L.Et;
+    c.kt = ws + L.kt; c.Tm = ws + L.Tm; c.W = ws + L.W; c.Wt = ws + L.Wt; c.Ktr = ws + L.Ktr;
+    c.Ut = ws + L.Ut; c.Et = ws + L.Et;
     c.S_ckpt = ws + L.S_ckpt;
     return c;
 }
@@ -194,7 +199,7 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     ChunkArgs c = chunk_args(p, L, ws);
     c.q = q; c.k = k; c.v = v; c.beta = beta; c.log_alpha = log_alpha;
     c.dO = dO; c.dS_out = dS_out;
-    c.dEl = ws + L.dEl; c.dEt = ws + L.dEt; c.dS_ckpt = ws + L.dS_ckpt;
+    c.dElt = ws + L.dElt; c.Qt = ws + L.Qt; c.dOt = ws + L.dOt; c.dEt = ws + L.dEt; c.dS_ckpt = ws + L.dS_ckpt;
     c.dS_in = dS_in; c.dq = dq; c.dv = dv;
     c.dk_read = reinterpret_cast<float *>(ws + L.dk_read);
     c.dkt = reinterpret_cast<float *>(ws + L.dkt);

@@ -32,13 +32,18 @@ __device__ __forceinline__ float row16_sum(float x) {
 }
 
 // ------------------------------------------------------------- bwd_local ----
+// dEl = scale P^T dO, stored transposed; also leaves (scale gamma . Q)^T and dO^T in the layout
+// the chain kernel's MFMA operands want.
 template <typename T, int K>
 __global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
+    constexpr int NKT = K / 64;
     __shared__ __attribute__((aligned(16))) T Qs[C * LDK];
-    __shared__ __attribute__((aligned(16))) T Kts[C * LDK];
+    constexpr int KTS_ELEMS = C * LDK > K * LDC ? C * LDK : K * LDC;
+    __shared__ __attribute__((aligned(16))) T Kts[KTS_ELEMS];   // K~, later the (scale gamma Q)^T staging
     __shared__ __attribute__((aligned(16))) T PT[C * LDC];      // scale * P^T
     __shared__ __attribute__((aligned(16))) T dOs[C * LDC];
+    __shared__ __attribute__((aligned(16))) T dOt[C * LDC];
     __shared__ __attribute__((aligned(16))) T Os[C * LDC];
     __shared__ float Gs[C];
 
@@ -68,151 +73,205 @@ __global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
         }
         store_tile_t(PT + jb * 16 * LDC + ib * 16, LDC, acc, lane);
     }
+    __syncthreads();                    // K~ is no longer needed: its buffer takes (scale gamma Q)^T
+    T *Qtt = Kts;
+#pragma unroll
+    for (int qn = 0; qn < NKT; ++qn) {
+        const int nb = wave * NKT + qn;
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib) {
+            f32x4 acc = pick16<T>(Qs + ib * 16 * LDK, LDK, nb * 16, lane);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] *= a.scale * __expf(Gs[ib * 16 + acc_row(lane, r)]);
+            store_tile_t(Qtt + nb * 16 * LDC + ib * 16, LDC, acc, lane);
+        }
+    }
+    __syncthreads();
+    store_tile_global(static_cast<T *>(a.Qt) + bhn * K * C, (size_t)C, Qtt, LDC, K, C, tid, NT);
     const int k0 = (wave * 16) / Mfma<T>::KSTEP * Mfma<T>::KSTEP;   // P^T rows 16*wave.. are zero left of here
     for (int v0 = 0; v0 < a.V; v0 += C) {
         __syncthreads();
         load_tile(dOs, LDC, static_cast<const T *>(a.dO) + tok0 * a.V + v0, tstride * a.V, C, C, tid, NT);
         __syncthreads();
+        // dO^T for this slab: wave w transposes the 16 columns 16*w ..
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib) {
+            const f32x4 acc = pick16<T>(dOs + ib * 16 * LDC, LDC, wave * 16, lane);
+            store_tile_t(dOt + wave * 16 * LDC + ib * 16, LDC, acc, lane);
+        }
+        __syncthreads();
+        store_tile_global(static_cast<T *>(a.dOt) + (bhn * a.V + v0) * C, (size_t)C, dOt, LDC, C, C, tid, NT);
+        // dEl rows j = 16*wave .. : sum_i P^T[j][i] dO[i][v], stored transposed
 #pragma unroll
         for (int vt = 0; vt < 4; ++vt) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            mma_tile<T, true, false>(acc, PT + wave * 16 * LDC + k0, LDC, dOs + k0 * LDC + vt * 16, LDC,
-                                     C - k0, lane);
-            store_tile(Os + wave * 16 * LDC + vt * 16, LDC, acc, lane);
+            mma_tile<T, true, true>(acc, PT + wave * 16 * LDC + k0, LDC, dOt + vt * 16 * LDC + k0, LDC, C - k0, lane);
+            store_tile_t(Os + vt * 16 * LDC + wave * 16, LDC, acc, lane);
         }
         __syncthreads();
-        store_tile_global(static_cast<T *>(a.dEl) + bhn * C * a.V + v0, (size_t)a.V, Os, LDC, C, C, tid, NT);
+        store_tile_global(static_cast<T *>(a.dElt) + (bhn * a.V + v0) * C, (size_t)C, Os, LDC, C, C, tid, NT);
     }
 }
 
 // ------------------------------------------------------------- bwd_chain ----
+// Mirror image of state_fwd, right to left: wavefronts 0-3 carry dS (transposed, fp32, in
+// MFMA accumulators), wavefronts 4-7 bring the next chunk's operand tiles into the other LDS
+// buffer (rho . K~ is scaled on the way) and write the dS' checkpoint and dE^T back.
+constexpr int CT_ = 512, CL_ = 256;
+
 template <typename T, int K>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void bwd_chain_kernel(ChunkArgs a) {
-    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDU = VS + PAD;
+__global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
+    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
     constexpr int VN = 16 / sizeof(T);
     constexpr int NKT = K / 64;
-    constexpr int NW = C * K / VN / NT;
-    constexpr int NU = C * VS / VN / NT;
-    constexpr bool PF = sizeof(T) == 2;         // prefetch the next chunk through registers
-    __shared__ __attribute__((aligned(16))) T Kts[C * LDK];     // rho . K~
-    __shared__ __attribute__((aligned(16))) T Wtt[K * LDC];     // -W^T
-    __shared__ __attribute__((aligned(16))) T Qtt[K * LDC];     // (scale gamma . Q)^T
-    __shared__ __attribute__((aligned(16))) T dOt[VS * LDC];    // dO^T (this slice of V)
-    __shared__ __attribute__((aligned(16))) T dEls[C * LDU];    // dEl (this slice)
-    __shared__ __attribute__((aligned(16))) T dSb[VS * LDK];    // dS' in the I/O type
-    __shared__ __attribute__((aligned(16))) T dEt[VS * LDC];    // dE^T
+    constexpr int NB = sizeof(T) == 2 ? 2 : 1;
+    constexpr int NWV = C * K / VN / CL_;
+    constexpr int NUV = VS * C / VN / CL_;
+    static_assert(VS * C / VN % CL_ == 0 && C * K / VN % CL_ == 0, "tiles must split evenly over the loaders");
+    __shared__ __attribute__((aligned(16))) T Krn[NB][C * LDK];     // rho . K~   [i][kf]
+    __shared__ __attribute__((aligned(16))) T Wtt[NB][K * LDC];     // -W^T        [kf][i]
+    __shared__ __attribute__((aligned(16))) T Qtt[NB][K * LDC];     // (scale gamma . Q)^T
+    __shared__ __attribute__((aligned(16))) T dOts[NB][VS * LDC];   // dO^T slice  [v][i]
+    __shared__ __attribute__((aligned(16))) T dEls[NB][VS * LDC];   // dEl^T slice [v][i]
+    __shared__ __attribute__((aligned(16))) T dSb[VS * LDK];        // dS' in the I/O type [v][kf]
+    __shared__ __attribute__((aligned(16))) T dEt[VS * LDC];        // dE^T [v][i]
+    __shared__ float gCs[NB];
 
     int chain, slice;
     chain_slice_of(blockIdx.x, a.V / VS, a.B * a.H, chain, slice);
     const int vs = slice * VS, h = chain % a.H, b = chain / a.H;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const bool loader = wave >= 4;
+    const int lt = tid - CL_;
     const size_t bh = (size_t)b * a.H + h;
     const size_t tstride = a.H;
 
-    f32x4 dS[2][NKT];
+    f32x4 dSt[2][NKT];                  // rows = features, cols = values
+    if (!loader) {
 #pragma unroll
-    for (int vt = 0; vt < 2; ++vt)
+        for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-        for (int qn = 0; qn < NKT; ++qn)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int v = vs + vt * 16 + acc_row(lane, r), c = (wave * NKT + qn) * 16 + acc_col(lane);
-                dS[vt][qn][r] = a.dS_out ? a.dS_out[(bh * a.V + v) * K + c] : 0.f;
+            for (int q = 0; q < NKT; ++q) {
+                const int v = vs + vt * 16 + acc_col(lane), c0 = (wave * NKT + q) * 16 + acc_row(lane, 0);
+                if (a.dS_out) dSt[vt][q] = *reinterpret_cast<const f32x4 *>(a.dS_out + (bh * a.V + v) * K + c0);
+                else dSt[vt][q] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
-
-    uint4 kreg[NW], wreg[NW], qreg[NW], oreg[NU], ereg[NU];
-    float greg;
-#define OSDN_CHAIN_LOAD(n_)                                                                      \
+    }
+    u32x4 kreg[NWV], wreg[NWV], qreg[NWV], oreg[NUV], ereg[NUV];
+    float greg = 0.f;
+#define OSDN_BC_LOAD(n_)                                                                         \
     {                                                                                            \
         const size_t bhn_ = bh * a.N + (n_);                                                     \
         const size_t tok_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                      \
         const T *kg = static_cast<const T *>(a.kt) + tok_ * K;                                   \
-        const T *qg = static_cast<const T *>(a.q) + tok_ * K;                                    \
-        const T *wg = static_cast<const T *>(a.W) + bhn_ * C * K;                                \
-        const T *og = static_cast<const T *>(a.dO) + tok_ * a.V + vs;                            \
-        const T *eg = static_cast<const T *>(a.dEl) + bhn_ * C * a.V + vs;                       \
-        _Pragma("unroll") for (int m = 0; m < NW; ++m) {                                         \
-            const int i = tid + m * NT, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
-            kreg[m] = *reinterpret_cast<const uint4 *>(kg + (size_t)r * tstride * K + c);        \
-            qreg[m] = *reinterpret_cast<const uint4 *>(qg + (size_t)r * tstride * K + c);        \
-            wreg[m] = *reinterpret_cast<const uint4 *>(wg + (size_t)r * K + c);                  \
+        const T *wg = static_cast<const T *>(a.Wt) + bhn_ * K * C;                               \
+        const T *qg = static_cast<const T *>(a.Qt) + bhn_ * K * C;                               \
+        const T *og = static_cast<const T *>(a.dOt) + (bhn_ * a.V + vs) * C;                     \
+        const T *eg = static_cast<const T *>(a.dElt) + (bhn_ * a.V + vs) * C;                    \
+        _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
+            const int i = lt + m * CL_, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
+            kreg[m] = *reinterpret_cast<const u32x4 *>(kg + (size_t)r * tstride * K + c);        \
+            wreg[m] = *reinterpret_cast<const u32x4 *>(wg + (size_t)i * VN);                     \
+            qreg[m] = *reinterpret_cast<const u32x4 *>(qg + (size_t)i * VN);                     \
         }                                                                                        \
-        _Pragma("unroll") for (int m = 0; m < NU; ++m) {                                         \
-            const int i = tid + m * NT, r = i / (VS / VN), c = (i % (VS / VN)) * VN;             \
-            oreg[m] = *reinterpret_cast<const uint4 *>(og + (size_t)r * tstride * a.V + c);      \
-            ereg[m] = *reinterpret_cast<const uint4 *>(eg + (size_t)r * a.V + c);                \
+        _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
+            const int i = lt + m * CL_;                                                          \
+            oreg[m] = *reinterpret_cast<const u32x4 *>(og + (size_t)i * VN);                     \
+            ereg[m] = *reinterpret_cast<const u32x4 *>(eg + (size_t)i * VN);                     \
         }                                                                                        \
         greg = a.log_alpha ? a.log_alpha[tok_ + (size_t)lane * tstride] : 0.f;                   \
     }
-    if (PF) OSDN_CHAIN_LOAD(a.N - 1)
+#define OSDN_BC_STORE(buf_)                                                                      \
+    {                                                                                            \
+        const float G_ = wave_cumsum(greg, lane);                                                \
+        const float GC_ = __shfl(G_, 63, 64);                                                    \
+        _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
+            const int i = lt + m * CL_;                                                          \
+            { const int r = i / (K / VN), c = (i % (K / VN)) * VN;                               \
+              const float rho = __expf(GC_ - __shfl(G_, r, 64));                                 \
+              _Pragma("unroll") for (int e = 0; e < VN; ++e)                                     \
+                  Krn[buf_][r * LDK + c + e] = from_f32<T>(rho * vec_get<T>(kreg[m], e)); }      \
+            { const int r = i / (C / VN), c = (i % (C / VN)) * VN;                               \
+              *reinterpret_cast<u32x4 *>(&Wtt[buf_][r * LDC + c]) = wreg[m];                     \
+              *reinterpret_cast<u32x4 *>(&Qtt[buf_][r * LDC + c]) = qreg[m]; }                   \
+        }                                                                                        \
+        _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
+            const int i = lt + m * CL_, r = i / (C / VN), c = (i % (C / VN)) * VN;               \
+            *reinterpret_cast<u32x4 *>(&dOts[buf_][r * LDC + c]) = oreg[m];                      \
+            *reinterpret_cast<u32x4 *>(&dEls[buf_][r * LDC + c]) = ereg[m];                      \
+        }                                                                                        \
+        if (tid == CL_) gCs[buf_] = __expf(GC_);                                                 \
+    }
+    if (loader) {
+        OSDN_BC_LOAD(a.N - 1)
+        OSDN_BC_STORE(NB == 2 ? ((a.N - 1) & 1) : 0)
+        OSDN_BC_LOAD(max(a.N - 2, 0))
+    }
 
     for (int n = a.N - 1; n >= 0; --n) {
+        const int buf = NB == 2 ? (n & 1) : 0;
         const size_t bhn = bh * a.N + n;
-        if (!PF) OSDN_CHAIN_LOAD(n)
-        const float G = wave_cumsum(greg, lane);
-        const float GC = __shfl(G, 63, 64);
+        // ---- phase A (compute): dS', rounded, into LDS ----
+        if (!loader) {
 #pragma unroll
-        for (int m = 0; m < NW; ++m) {
-            const int i = tid + m * NT, r = i / (K / VN), c = (i % (K / VN)) * VN;
-            const float Gr = __shfl(G, r, 64);
-            const float rho = __expf(GC - Gr), sg = a.scale * __expf(Gr);
+            for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-            for (int e = 0; e < VN; ++e) {
-                Kts[r * LDK + c + e] = from_f32<T>(rho * vec_get<T>(kreg[m], e));
-                Wtt[(c + e) * LDC + r] = from_f32<T>(-vec_get<T>(wreg[m], e));
-                Qtt[(c + e) * LDC + r] = from_f32<T>(sg * vec_get<T>(qreg[m], e));
+                for (int q = 0; q < NKT; ++q)
+                    store_tile_t(dSb + vt * 16 * LDK + (wave * NKT + q) * 16, LDK, dSt[vt][q], lane);
+        }
+        __syncthreads();                                            // barrier 1
+        if (loader) {
+            store_tile_global(static_cast<T *>(a.dS_ckpt) + (bhn * a.V + vs) * K, (size_t)K, dSb, LDK, VS, K, lt, CL_);
+            if (NB == 2 && n > 0) {
+                OSDN_BC_STORE((n - 1) & 1)
+                OSDN_BC_LOAD(max(n - 2, 0))         // (the last one is a harmless reload of chunk 0)
+            }
+        } else {
+            // ---- phase B: dE = dEl + (rho . K~) dS'^T (rows 16*wave ..), kept transposed ----
+#pragma unroll
+            for (int vt = 0; vt < 2; ++vt) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                mma_tile<T, true, true>(acc, &Krn[buf][wave * 16 * LDK], LDK, dSb + vt * 16 * LDK, LDK, K, lane);
+                const T *ep = &dEls[buf][(vt * 16 + acc_col(lane)) * LDC + wave * 16 + acc_row(lane, 0)];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] += to_f32(ep[r]);
+                store_tile_t(dEt + vt * 16 * LDC + wave * 16, LDC, acc, lane);
             }
         }
+        __syncthreads();                                            // barrier 2
+        if (loader) {
+            store_tile_global(static_cast<T *>(a.dEt) + (bhn * a.V + vs) * C, (size_t)C, dEt, LDC, VS, C, lt, CL_);
+        } else {
+            // ---- phase C: dS <- gamma_C dS' + scale dO^T (gamma . Q) - dE^T W, transposed ----
+            const float gC = gCs[buf];
 #pragma unroll
-        for (int m = 0; m < NU; ++m) {
-            const int i = tid + m * NT, r = i / (VS / VN), c = (i % (VS / VN)) * VN;
-            *reinterpret_cast<uint4 *>(dEls + r * LDU + c) = ereg[m];
+            for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-            for (int e = 0; e < VN; ++e) dOt[(c + e) * LDC + r] = from_f32<T>(vec_get<T>(oreg[m], e));
+                for (int q = 0; q < NKT; ++q) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) dSt[vt][q][r] *= gC;
+                    const int ct = (wave * NKT + q) * 16;
+                    mma_tile<T, true, true>(dSt[vt][q], &Qtt[buf][ct * LDC], LDC, &dOts[buf][vt * 16 * LDC], LDC, C, lane);
+                    mma_tile<T, true, true>(dSt[vt][q], &Wtt[buf][ct * LDC], LDC, dEt + vt * 16 * LDC, LDC, C, lane);
+                }
         }
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-            for (int qn = 0; qn < NKT; ++qn)
-                store_tile(dSb + vt * 16 * LDK + (wave * NKT + qn) * 16, LDK, dS[vt][qn], lane);
-        __syncthreads();
-        store_tile_global(static_cast<T *>(a.dS_ckpt) + (bhn * a.V + vs) * K, (size_t)K, dSb, LDK, VS, K, tid, NT);
-        if (PF && n > 0) OSDN_CHAIN_LOAD(n - 1)
-        // dE = dEl + (rho . K~) dS'^T   (rows 16*wave .. +16), kept transposed
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            mma_tile<T, true, true>(acc, Kts + wave * 16 * LDK, LDK, dSb + vt * 16 * LDK, LDK, K, lane);
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                acc[r] += to_f32(dEls[(wave * 16 + acc_row(lane, r)) * LDU + vt * 16 + acc_col(lane)]);
-            store_tile_t(dEt + vt * 16 * LDC + wave * 16, LDC, acc, lane);
-        }
-        __syncthreads();
-        store_tile_global(static_cast<T *>(a.dEt) + (bhn * a.V + vs) * C, (size_t)C, dEt, LDC, VS, C, tid, NT);
-        // dS <- gamma_C dS' + scale dO^T (gamma . Q) - dE^T W
-        const float gC = __expf(GC);
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-            for (int qn = 0; qn < NKT; ++qn) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) dS[vt][qn][r] *= gC;
-                const int ct = (wave * NKT + qn) * 16;
-                mma_tile<T, true, true>(dS[vt][qn], dOt + vt * 16 * LDC, LDC, Qtt + ct * LDC, LDC, C, lane);
-                mma_tile<T, true, true>(dS[vt][qn], dEt + vt * 16 * LDC, LDC, Wtt + ct * LDC, LDC, C, lane);
+        if (NB == 1) {
+            __syncthreads();
+            if (loader && n > 0) {
+                OSDN_BC_STORE(0)
+                OSDN_BC_LOAD(max(n - 2, 0))
             }
-        __syncthreads();
+        }
     }
+    if (!loader) {
 #pragma unroll
-    for (int vt = 0; vt < 2; ++vt)
+        for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-        for (int qn = 0; qn < NKT; ++qn)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int v = vs + vt * 16 + acc_row(lane, r), c = (wave * NKT + qn) * 16 + acc_col(lane);
-                a.dS_in[(bh * a.V + v) * K + c] = dS[vt][qn][r];
+            for (int q = 0; q < NKT; ++q) {
+                const int v = vs + vt * 16 + acc_col(lane), c0 = (wave * NKT + q) * 16 + acc_row(lane, 0);
+                *reinterpret_cast<f32x4 *>(a.dS_in + (bh * a.V + v) * K + c0) = dSt[vt][q];
             }
+    }
 }
 
 // -------------------------------------------------------------- bwd_post ----
@@ -536,7 +595,7 @@ int launch_bwd_local(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T>
 static int launch_chain_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid((a.V / VS) * a.H * a.B), block(NT);
+    dim3 grid((a.V / VS) * a.H * a.B), block(CT_);
     if (a.K == 64) hipLaunchKernelGGL((bwd_chain_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((bwd_chain_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;

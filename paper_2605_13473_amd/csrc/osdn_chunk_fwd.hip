@@ -15,15 +15,23 @@
 namespace osdn {
 
 // ------------------------------------------------------------ chunk_prep ----
+// Besides T, W it leaves the tiles the chain kernels consume in exactly the layout their MFMA
+// operands want, so that those kernels only copy: -W^T, (rho . K~)^T and U^T (transposes come
+// for free from the accumulator layout, or from a 0/1 selector product for K~).
 template <typename T, int K>
 __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDF = C + 1;
+    constexpr int NKT = K / 64;                                 // column tiles of a [64 x K] result per wave
     __shared__ __attribute__((aligned(16))) T X1[C * LDK];      // K, then beta gamma K, then V slabs
-    __shared__ __attribute__((aligned(16))) T X2[C * LDK];      // K~, then output staging
+    __shared__ __attribute__((aligned(16))) T X2[C * LDK];      // K~, then W staging
     __shared__ __attribute__((aligned(16))) T Tt[C * LDC];      // T in the I/O type
-    __shared__ float Af[C * LDF];                               // A (fp32)
-    __shared__ float Ti[C * LDF];                               // (I + A)^-1 (fp32)
-    __shared__ float Xs[3 * 16 * 17];                           // block-product scratch
+    constexpr int SCR = 2 * C * LDF + 3 * 16 * 17;
+    constexpr int SCR_MIN = (K * LDC * (int)sizeof(T) + 3) / 4;
+    __shared__ __attribute__((aligned(16))) float scratch[SCR > SCR_MIN ? SCR : SCR_MIN];
+    float *Af = scratch;                                        // A (fp32)
+    float *Ti = Af + C * LDF;                                   // (I + A)^-1 (fp32)
+    float *Xs = Ti + C * LDF;                                   // block-product scratch
+    T *stage = reinterpret_cast<T *>(scratch);                  // [K][LDC] / [64][LDC], once T is final
     __shared__ float Gs[C], Bs[C];
 
     const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -103,12 +111,30 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
         const int j = idx / K, c = idx % K;
         X1[j * LDK + c] = from_f32<T>(Bs[j] * __expf(Gs[j]) * to_f32(X1[j * LDK + c]));
     }
-    __syncthreads();
+    __syncthreads();            // Af, Ti are dead from here on: their space is the staging tile
     store_tile_global(static_cast<T *>(a.Tm) + bhn * C * C, C, Tt, LDC, C, C, tid, NT);
 
-    // ---- W = T (beta gamma . K) ----
+    // ---- (rho . K~)^T: pick 16x16 blocks of K~, scale rows by rho_j, store transposed ----
     {
-        constexpr int NKT = K / 64;     // column tiles per wave
+        const float GC = Gs[C - 1];
+#pragma unroll
+        for (int qn = 0; qn < NKT; ++qn) {
+            const int nb = wave * NKT + qn;                     // 16 features of K~
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+                f32x4 acc = pick16<T>(X2 + jb * 16 * LDK, LDK, nb * 16, lane);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] *= __expf(GC - Gs[jb * 16 + acc_row(lane, r)]);
+                store_tile_t(stage + nb * 16 * LDC + jb * 16, LDC, acc, lane);
+            }
+        }
+    }
+    __syncthreads();
+    store_tile_global(static_cast<T *>(a.Ktr) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, NT);
+    __syncthreads();
+
+    // ---- W = T (beta gamma . K), and -W^T ----
+    {
 #pragma unroll
         for (int qn = 0; qn < NKT; ++qn) {
             const int nb = wave * NKT + qn;
@@ -118,20 +144,24 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
                 const int kdim = min(C, ((ib + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
                 mma_tile<T, true, false>(acc, Tt + ib * 16 * LDC, LDC, X1 + nb * 16, LDK, kdim, lane);
                 store_tile(X2 + ib * 16 * LDK + nb * 16, LDK, acc, lane);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] = -acc[r];
+                store_tile_t(stage + nb * 16 * LDC + ib * 16, LDC, acc, lane);
             }
         }
     }
     __syncthreads();
     store_tile_global(static_cast<T *>(a.W) + bhn * C * K, K, X2, LDK, C, K, tid, NT);
+    store_tile_global(static_cast<T *>(a.Wt) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, NT);
 
-    // ---- U = T (beta . V), 64 columns of V at a time ----
+    // ---- U^T = (T (beta . V))^T, 64 columns of V at a time ----
     const T *vg = static_cast<const T *>(a.v) + tok0 * a.V;
     for (int v0 = 0; v0 < a.V; v0 += C) {
         __syncthreads();
         constexpr int VN = 16 / sizeof(T);
         for (int i = tid; i < C * (C / VN); i += NT) {
             const int r = i / (C / VN), c = (i % (C / VN)) * VN;
-            uint4 raw = *reinterpret_cast<const uint4 *>(vg + (size_t)r * tstride * a.V + v0 + c);
+            u32x4 raw = *reinterpret_cast<const u32x4 *>(vg + (size_t)r * tstride * a.V + v0 + c);
             const float br = Bs[r];
 #pragma unroll
             for (int e = 0; e < VN; ++e) X1[r * LDC + c + e] = from_f32<T>(br * vec_get<T>(raw, e));
@@ -142,133 +172,171 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
             const int kdim = min(C, ((ib + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
             mma_tile<T, true, false>(acc, Tt + ib * 16 * LDC, LDC, X1 + wave * 16, LDC, kdim, lane);
-            store_tile(X2 + ib * 16 * LDC + wave * 16, LDC, acc, lane);
+            store_tile_t(stage + wave * 16 * LDC + ib * 16, LDC, acc, lane);
         }
         __syncthreads();
-        store_tile_global(static_cast<T *>(a.U) + bhn * C * a.V + v0, a.V, X2, LDC, C, C, tid, NT);
+        store_tile_global(static_cast<T *>(a.Ut) + (bhn * a.V + v0) * C, (size_t)C, stage, LDC, C, C, tid, NT);
     }
 }
 
 // ------------------------------------------------------------- state_fwd ----
-constexpr int VS = 32;      // rows of S (values) owned by one workgroup
+// Sequential over the chunks of one (batch, head), one workgroup per slice of VS rows of S.
+// Wavefronts 0-3 carry the dependent chain  S_n -> E_n -> S_{n+1}: the state slice lives
+// transposed in their MFMA accumulators (fp32), so that its rounding to the I/O type lands in
+// LDS with vector stores.  Wavefronts 4-7 only move data: they bring the next chunk's W,
+// (rho . K~)^T and U^T tiles (already in operand layout) into the other LDS buffer and write
+// the state checkpoint and E^T back, off the chain.  Two barriers per chunk.
+constexpr int VS = 32;          // rows of S (values) owned by one workgroup
+constexpr int CT_ = 512;        // threads of a chain workgroup
+constexpr int CL_ = 256;        // ... of which loaders
 
-// (one workgroup per CU is the intended residency: let the register allocator use the file)
 template <typename T, int K>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 2))) void state_fwd_kernel(ChunkArgs a) {
-    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDU = VS + PAD;
+__global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
+    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
     constexpr int VN = 16 / sizeof(T);
-    constexpr int NKT = K / 64;                 // S column tiles per wave
-    constexpr int NW = C * K / VN / NT;         // 16-byte vectors per thread for a [64 x K] tile
-    constexpr int NU = C * VS / VN / NT;          // (exact: C*VS/VN is a multiple of NT)
-    static_assert(C * VS / VN % NT == 0, "U slab must split evenly over the workgroup");
-    __shared__ __attribute__((aligned(16))) T Ws[C * LDK];
-    __shared__ __attribute__((aligned(16))) T Ktt[K * LDC];     // (rho . K~)^T
-    __shared__ __attribute__((aligned(16))) T Us[C * LDU];
+    constexpr int NKT = K / 64;                 // state row tiles (features) per compute wave
+    constexpr int NB = sizeof(T) == 2 ? 2 : 1;  // LDS operand buffers (fp32 tiles are too big for two)
+    constexpr int NWV = C * K / VN / CL_;       // 16-byte vectors per loader thread, [64 x K] tile
+    constexpr int NUV = VS * C / VN / CL_;
+    static_assert(VS * C / VN % CL_ == 0 && C * K / VN % CL_ == 0, "tiles must split evenly over the loaders");
+    __shared__ __attribute__((aligned(16))) T Ws[NB][C * LDK];
+    __shared__ __attribute__((aligned(16))) T Ktr[NB][K * LDC];
+    __shared__ __attribute__((aligned(16))) T Uts[NB][VS * LDC];
     __shared__ __attribute__((aligned(16))) T Sb[VS * LDK];     // S in the I/O type
     __shared__ __attribute__((aligned(16))) T Et[VS * LDC];     // E^T
+    __shared__ float gCs[NB];
 
     int chain, slice;
     chain_slice_of(blockIdx.x, a.V / VS, a.B * a.H, chain, slice);
     const int vs = slice * VS, h = chain % a.H, b = chain / a.H;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const bool loader = wave >= 4;
+    const int lt = tid - CL_;                   // loader thread index
     const size_t bh = (size_t)b * a.H + h;
     const size_t tstride = a.H;
 
-    f32x4 S[2][NKT];
+    // ---- compute waves: state slice, transposed: St[vt][q] rows = features, cols = values ----
+    f32x4 St[2][NKT];
+    if (!loader) {
 #pragma unroll
-    for (int vt = 0; vt < 2; ++vt)
+        for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-        for (int qn = 0; qn < NKT; ++qn)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int v = vs + vt * 16 + acc_row(lane, r), c = (wave * NKT + qn) * 16 + acc_col(lane);
-                S[vt][qn][r] = a.S_in ? a.S_in[(bh * a.V + v) * K + c] : 0.f;
+            for (int q = 0; q < NKT; ++q) {
+                const int v = vs + vt * 16 + acc_col(lane), c0 = (wave * NKT + q) * 16 + acc_row(lane, 0);
+                if (a.S_in) St[vt][q] = *reinterpret_cast<const f32x4 *>(a.S_in + (bh * a.V + v) * K + c0);
+                else St[vt][q] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
-
-    uint4 wreg[NW], kreg[NW], ureg[NU];
-    float greg;
-#define OSDN_STATE_PREFETCH(n_)                                                                  \
+    }
+    // ---- loader waves: registers for one chunk ----
+    u32x4 wreg[NWV], kreg[NWV], ureg[NUV];
+    float greg = 0.f;
+#define OSDN_SF_LOAD(n_)                                                                         \
     {                                                                                            \
         const size_t bhn_ = bh * a.N + (n_);                                                     \
-        const size_t tok_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                      \
         const T *wg = static_cast<const T *>(a.W) + bhn_ * C * K;                                \
-        const T *kg = static_cast<const T *>(a.kt) + tok_ * K;                                   \
-        const T *ug = static_cast<const T *>(a.U) + bhn_ * C * a.V + vs;                         \
-        _Pragma("unroll") for (int m = 0; m < NW; ++m) {                                         \
-            const int i = tid + m * NT, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
-            wreg[m] = *reinterpret_cast<const uint4 *>(wg + (size_t)r * K + c);                  \
-            kreg[m] = *reinterpret_cast<const uint4 *>(kg + (size_t)r * tstride * K + c);        \
+        const T *kg = static_cast<const T *>(a.Ktr) + bhn_ * K * C;                              \
+        const T *ug = static_cast<const T *>(a.Ut) + (bhn_ * a.V + vs) * C;                      \
+        _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
+            const int i = lt + m * CL_;                                                          \
+            wreg[m] = *reinterpret_cast<const u32x4 *>(wg + (size_t)i * VN);                     \
+            kreg[m] = *reinterpret_cast<const u32x4 *>(kg + (size_t)i * VN);                     \
         }                                                                                        \
-        _Pragma("unroll") for (int m = 0; m < NU; ++m) {                                         \
-            const int i = tid + m * NT, r = i / (VS / VN), c = (i % (VS / VN)) * VN;             \
-            ureg[m] = *reinterpret_cast<const uint4 *>(ug + (size_t)r * a.V + c);                \
+        _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
+            const int i = lt + m * CL_;                                                          \
+            ureg[m] = *reinterpret_cast<const u32x4 *>(ug + (size_t)i * VN);                     \
         }                                                                                        \
-        greg = a.log_alpha ? a.log_alpha[tok_ + (size_t)lane * tstride] : 0.f;                   \
+        if (wave == 4)                                                                           \
+            greg = a.log_alpha ? a.log_alpha[((size_t)b * a.T + (size_t)(n_) * C + lane) * a.H + h] : 0.f; \
     }
-    OSDN_STATE_PREFETCH(0)
+#define OSDN_SF_STORE(buf_)                                                                      \
+    {                                                                                            \
+        _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
+            const int i = lt + m * CL_;                                                          \
+            { const int r = i / (K / VN), c = (i % (K / VN)) * VN;                               \
+              *reinterpret_cast<u32x4 *>(&Ws[buf_][r * LDK + c]) = wreg[m]; }                    \
+            { const int r = i / (C / VN), c = (i % (C / VN)) * VN;                               \
+              *reinterpret_cast<u32x4 *>(&Ktr[buf_][r * LDC + c]) = kreg[m]; }                   \
+        }                                                                                        \
+        _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
+            const int i = lt + m * CL_, r = i / (C / VN), c = (i % (C / VN)) * VN;               \
+            *reinterpret_cast<u32x4 *>(&Uts[buf_][r * LDC + c]) = ureg[m];                       \
+        }                                                                                        \
+        if (wave == 4) {                                                                         \
+            const float G_ = wave_cumsum(greg, lane);                                            \
+            if (lane == 63) gCs[buf_] = __expf(G_);                                              \
+        }                                                                                        \
+    }
+    if (loader) {
+        OSDN_SF_LOAD(0)
+        OSDN_SF_STORE(0)
+        OSDN_SF_LOAD(min(1, a.N - 1))
+    }
 
     for (int n = 0; n < a.N; ++n) {
+        const int buf = NB == 2 ? (n & 1) : 0;
         const size_t bhn = bh * a.N + n;
-        // ---- 1. registers -> LDS ----
-        const float G = wave_cumsum(greg, lane);
-        const float GC = __shfl(G, 63, 64);
+        // ---- phase A (compute): S, rounded, into LDS ----
+        if (!loader) {
 #pragma unroll
-        for (int m = 0; m < NW; ++m) {
-            const int i = tid + m * NT, r = i / (K / VN), c = (i % (K / VN)) * VN;
-            *reinterpret_cast<uint4 *>(Ws + r * LDK + c) = wreg[m];
-            const float rho = __expf(GC - __shfl(G, r, 64));
+            for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-            for (int e = 0; e < VN; ++e) Ktt[(c + e) * LDC + r] = from_f32<T>(rho * vec_get<T>(kreg[m], e));
+                for (int q = 0; q < NKT; ++q)
+                    store_tile_t(Sb + vt * 16 * LDK + (wave * NKT + q) * 16, LDK, St[vt][q], lane);
         }
-#pragma unroll
-        for (int m = 0; m < NU; ++m) {
-            const int i = tid + m * NT, r = i / (VS / VN), c = (i % (VS / VN)) * VN;
-            *reinterpret_cast<uint4 *>(Us + r * LDU + c) = ureg[m];
-        }
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-            for (int qn = 0; qn < NKT; ++qn)
-                store_tile(Sb + vt * 16 * LDK + (wave * NKT + qn) * 16, LDK, S[vt][qn], lane);
-        __syncthreads();
-        if (a.S_ckpt)
-            store_tile_global(static_cast<T *>(a.S_ckpt) + (bhn * a.V + vs) * K, K, Sb, LDK, VS, K, tid, NT);
-        // ---- 2. fetch the next chunk while this one is computed ----
-        if (n + 1 < a.N) OSDN_STATE_PREFETCH(n + 1)
-        // ---- 3. E = U - W S^T (rows 16*wave .. +16), kept transposed ----
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            mma_tile<T, true, true>(acc, Ws + wave * 16 * LDK, LDK, Sb + vt * 16 * LDK, LDK, K, lane);
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                acc[r] = to_f32(Us[(wave * 16 + acc_row(lane, r)) * LDU + vt * 16 + acc_col(lane)]) - acc[r];
-            store_tile_t(Et + vt * 16 * LDC + wave * 16, LDC, acc, lane);
-        }
-        __syncthreads();
-        store_tile_global(static_cast<T *>(a.Et) + (bhn * a.V + vs) * C, C, Et, LDC, VS, C, tid, NT);
-        // ---- 4. S <- gamma_C S + E^T (rho . K~) ----
-        const float gC = __expf(GC);
-#pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
-#pragma unroll
-            for (int qn = 0; qn < NKT; ++qn) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) S[vt][qn][r] *= gC;
-                mma_tile<T, true, true>(S[vt][qn], Et + vt * 16 * LDC, LDC,
-                                        Ktt + (wave * NKT + qn) * 16 * LDC, LDC, C, lane);
+        __syncthreads();                                            // barrier 1
+        if (loader) {
+            // checkpoint of the chunk-start state (read between barrier 1 and barrier 2)
+            if (a.S_ckpt)
+                store_tile_global(static_cast<T *>(a.S_ckpt) + (bhn * a.V + vs) * K, (size_t)K, Sb, LDK, VS, K, lt, CL_);
+            if (NB == 2 && n + 1 < a.N) {
+                OSDN_SF_STORE((n + 1) & 1)                          // free since barrier 1
+                OSDN_SF_LOAD(min(n + 2, a.N - 1))                   // (the last one is a harmless reload)
             }
-        __syncthreads();
+        } else {
+            // ---- phase B: E = U - W S^T (rows 16*wave ..), kept transposed ----
+#pragma unroll
+            for (int vt = 0; vt < 2; ++vt) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                mma_tile<T, true, true>(acc, &Ws[buf][wave * 16 * LDK], LDK, Sb + vt * 16 * LDK, LDK, K, lane);
+                const T *up = &Uts[buf][(vt * 16 + acc_col(lane)) * LDC + wave * 16 + acc_row(lane, 0)];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] = to_f32(up[r]) - acc[r];
+                store_tile_t(Et + vt * 16 * LDC + wave * 16, LDC, acc, lane);
+            }
+        }
+        __syncthreads();                                            // barrier 2
+        if (loader) {
+            store_tile_global(static_cast<T *>(a.Et) + (bhn * a.V + vs) * C, (size_t)C, Et, LDC, VS, C, lt, CL_);
+        } else {
+            // ---- phase C: S <- gamma_C S + E^T (rho . K~), transposed ----
+            const float gC = gCs[buf];
+#pragma unroll
+            for (int vt = 0; vt < 2; ++vt)
+#pragma unroll
+                for (int q = 0; q < NKT; ++q) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) St[vt][q][r] *= gC;
+                    mma_tile<T, true, true>(St[vt][q], &Ktr[buf][(wave * NKT + q) * 16 * LDC], LDC,
+                                            Et + vt * 16 * LDC, LDC, C, lane);
+                }
+        }
+        if (NB == 1) {                                              // single buffer: refill it now
+            __syncthreads();
+            if (loader && n + 1 < a.N) {
+                OSDN_SF_STORE(0)
+                OSDN_SF_LOAD(min(n + 2, a.N - 1))
+            }
+        }
     }
+    if (!loader) {
 #pragma unroll
-    for (int vt = 0; vt < 2; ++vt)
+        for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
-        for (int qn = 0; qn < NKT; ++qn)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int v = vs + vt * 16 + acc_row(lane, r), c = (wave * NKT + qn) * 16 + acc_col(lane);
-                a.S_out[(bh * a.V + v) * K + c] = S[vt][qn][r];
+            for (int q = 0; q < NKT; ++q) {
+                const int v = vs + vt * 16 + acc_col(lane), c0 = (wave * NKT + q) * 16 + acc_row(lane, 0);
+                *reinterpret_cast<f32x4 *>(a.S_out + (bh * a.V + v) * K + c0) = St[vt][q];
             }
+    }
 }
 
 // ------------------------------------------------------------ output_fwd ----
@@ -345,7 +413,7 @@ int launch_chunk_prep(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T>
 static int launch_state_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid((a.V / VS) * a.H * a.B), block(NT);
+    dim3 grid((a.V / VS) * a.H * a.B), block(CT_);
     if (a.K == 64) hipLaunchKernelGGL((state_fwd_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((state_fwd_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;

@@ -16,6 +16,8 @@ typedef __bf16 bf16;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16))) uint32_t u32x4;      // 16 raw bytes (a native vector: stays in registers)
+typedef __attribute__((__vector_size__(8))) uint32_t u32x2;
 
 constexpr int C = 64;          // chunk length
 constexpr int NT = 256;        // threads per workgroup of the chunk kernels (4 waves)
@@ -106,16 +108,38 @@ __device__ __forceinline__ void store_tile_t<bf16>(bf16 *dst, int ld, f32x4 acc,
     *reinterpret_cast<bf16x4 *>(dst + acc_col(lane) * ld + acc_row(lane, 0)) = v;
 }
 
-// ------------------------------------------------------- global <-> LDS ----
-// element e (compile-time after unrolling) of a 16-byte vector of T held in a uint4, as fp32
-__device__ __forceinline__ uint32_t vec_word(const uint4 &v, int w) {
-    return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w;
+// acc(row m, col c) = X[m][c0 + c], a 16x16 block of a row-major LDS tile (X points at its
+// first row), obtained by multiplying with a 0/1 selector on the MFMA unit (exact).  Followed
+// by store_tile_t this transposes a block with vector LDS accesses only.
+template <typename T> __device__ __forceinline__ f32x4 pick16(const T *X, int ld, int c0, int lane);
+template <> __device__ __forceinline__ f32x4 pick16<float>(const float *X, int ld, int c0, int lane) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const int n = lane & 15, kq = lane >> 4;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(X[n * ld + c0 + 4 * s + kq], (n == 4 * s + kq) ? 1.f : 0.f,
+                                                   acc, 0, 0, 0);
+    return acc;
 }
-template <typename T> __device__ __forceinline__ float vec_get(const uint4 &v, int e);
-template <> __device__ __forceinline__ float vec_get<float>(const uint4 &v, int e) {
+template <> __device__ __forceinline__ f32x4 pick16<bf16>(const bf16 *X, int ld, int c0, int lane) {
+    const int n = lane & 15, k8 = (lane >> 4) * 8;
+    const int kk = c0 & ~31, half = (c0 >> 4) & 1;
+    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(X + n * ld + kk + k8);
+    bf16x8 sel;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sel[e] = (bf16)((k8 + e == n + 16 * half) ? 1.f : 0.f);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sel, acc, 0, 0, 0);
+}
+
+// ------------------------------------------------------- global <-> LDS ----
+// element e (compile-time after unrolling) of a 16-byte vector of T held in a u32x4, as fp32
+__device__ __forceinline__ uint32_t vec_word(const u32x4 &v, int w) { return v[w]; }
+template <typename T> __device__ __forceinline__ float vec_get(const u32x4 &v, int e);
+template <> __device__ __forceinline__ float vec_get<float>(const u32x4 &v, int e) {
     return __builtin_bit_cast(float, vec_word(v, e));
 }
-template <> __device__ __forceinline__ float vec_get<bf16>(const uint4 &v, int e) {
+template <> __device__ __forceinline__ float vec_get<bf16>(const u32x4 &v, int e) {
     const uint32_t w = vec_word(v, e >> 1);
     return __builtin_bit_cast(float, (e & 1) ? (w & 0xffff0000u) : (w << 16));
 }
@@ -129,8 +153,8 @@ __device__ __forceinline__ void load_tile(T *s, int s_ld, const T *g, size_t g_l
     const int vpr = cols / VN;
     for (int i = tid; i < rows * vpr; i += nthreads) {
         const int r = i / vpr, c = (i % vpr) * VN;
-        *reinterpret_cast<uint4 *>(s + r * s_ld + c) =
-            *reinterpret_cast<const uint4 *>(g + (size_t)r * g_ld + c);
+        *reinterpret_cast<u32x4 *>(s + r * s_ld + c) =
+            *reinterpret_cast<const u32x4 *>(g + (size_t)r * g_ld + c);
     }
 }
 template <typename T>
@@ -140,8 +164,8 @@ __device__ __forceinline__ void store_tile_global(T *g, size_t g_ld, const T *s,
     const int vpr = cols / VN;
     for (int i = tid; i < rows * vpr; i += nthreads) {
         const int r = i / vpr, c = (i % vpr) * VN;
-        *reinterpret_cast<uint4 *>(g + (size_t)r * g_ld + c) =
-            *reinterpret_cast<const uint4 *>(s + r * s_ld + c);
+        *reinterpret_cast<u32x4 *>(g + (size_t)r * g_ld + c) =
+            *reinterpret_cast<const u32x4 *>(s + r * s_ld + c);
     }
 }
 

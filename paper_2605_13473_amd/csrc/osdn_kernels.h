@@ -49,13 +49,17 @@ struct ChunkArgs {
     void *kt;                         // [B,T,H,K] io      k~
     void *Tm;                         // [B,H,N,64,64] io  (I + A)^-1
     void *W;                          // [B,H,N,64,K] io
-    void *U;                          // [B,H,N,64,V] io
+    void *Wt;                         // [B,H,N,K,64] io   -W^T
+    void *Ktr;                        // [B,H,N,K,64] io   (rho . K~)^T
+    void *Ut;                         // [B,H,N,V,64] io   U^T
     void *Et;                         // [B,H,N,V,64] io   E transposed
     void *S_ckpt;                     // [B,H,N,V,K] io    state at the start of each chunk (null: not kept)
     // backward
     const void *dO;                   // [B,T,H,V] io
     const float *dS_out;              // [B,H,V,K] or null
-    void *dEl;                        // [B,H,N,64,V] io   local part of dE: scale * P^T dO
+    void *dElt;                       // [B,H,N,V,64] io   local part of dE, transposed: (scale P^T dO)^T
+    void *Qt;                         // [B,H,N,K,64] io   (scale gamma . Q)^T
+    void *dOt;                        // [B,H,N,V,64] io   dO^T
     void *dEt;                        // [B,H,N,V,64] io   dE transposed (complete)
     void *dS_ckpt;                    // [B,H,N,V,K] io    adjoint of the state at the END of each chunk
     float *dS_in;                     // [B,H,V,K]

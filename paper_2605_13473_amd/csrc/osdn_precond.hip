@@ -95,7 +95,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
 
     if (tid < K) d0[tid] = a.d_in ? a.d_in[bh * K + tid] : 1.f;
 
-    uint4 kreg[NW];                              // (bf16: only .x, .y are used)
+    u32x4 kreg[NW];                              // (bf16: only .x, .y are used)
     float betreg = 0.f, retreg = 1.f;
 #define OSDN_P1_LOAD(n_)                                                                         \
     {                                                                                            \
@@ -104,8 +104,8 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
             const int i = tid + m * P1T, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
             const int t = min(t0_ + r, a.T - 1);                                                 \
             const T *src_ = k + (((size_t)b * a.T + t) * a.H + h) * K + c;                       \
-            if (sizeof(T) == 2) { const uint2 v_ = *reinterpret_cast<const uint2 *>(src_); kreg[m] = make_uint4(v_.x, v_.y, 0u, 0u); } \
-            else kreg[m] = *reinterpret_cast<const uint4 *>(src_);                               \
+            if (sizeof(T) == 2) { const u32x2 v_ = *reinterpret_cast<const u32x2 *>(src_); kreg[m] = u32x4{v_[0], v_[1], 0u, 0u}; } \
+            else kreg[m] = *reinterpret_cast<const u32x4 *>(src_);                               \
         }                                                                                        \
         if (tid < C) {                                                                           \
             const int t = min(t0_ + tid, a.T - 1);                                               \
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
         const int t0 = n * C;
         const int nvalid = min(C, a.T - t0);
         // ---- registers -> LDS (rows past the end of the sequence become no-op tokens) ----
-        uint4 kcur[NW];
+        u32x4 kcur[NW];
 #pragma unroll
         for (int m = 0; m < NW; ++m) {
             kcur[m] = kreg[m];
@@ -285,8 +285,8 @@ __global__ __launch_bounds__(P1T) void precond_bwd_kernel(PrecondBwdArgs a) {
     if (tid < K) ga[tid] = a.dd_out ? a.dd_out[bh * K + tid] : 0.f;
 
     // the [64 x K] tiles are walked as groups of 4 columns: thread -> (row r, columns c..c+3)
-    uint2 kreg2[NF];        // bf16: 4 elements = 8 bytes ; fp32 uses kreg4
-    uint4 kreg4[NF];
+    u32x2 kreg2[NF];        // bf16: 4 elements = 8 bytes ; fp32 uses kreg4
+    u32x4 kreg4[NF];
     float4 greg[NF];
     float4 screg = make_float4(0.f, 0.f, 0.f, 0.f);
     float betreg = 0.f, retreg = 1.f, dbreg = 0.f;
@@ -296,8 +296,8 @@ __global__ __launch_bounds__(P1T) void precond_bwd_kernel(PrecondBwdArgs a) {
         _Pragma("unroll") for (int m = 0; m < NF; ++m) {                                         \
             const int i = tid + m * P1T, r = i / (K / 4), c = (i % (K / 4)) * 4;                  \
             const size_t off = (tokc_ + (size_t)r * a.H) * K + c;                                \
-            if (sizeof(T) == 2) kreg2[m] = *reinterpret_cast<const uint2 *>(k + off);            \
-            else kreg4[m] = *reinterpret_cast<const uint4 *>(k + off);                           \
+            if (sizeof(T) == 2) kreg2[m] = *reinterpret_cast<const u32x2 *>(k + off);            \
+            else kreg4[m] = *reinterpret_cast<const u32x4 *>(k + off);                           \
             greg[m] = *reinterpret_cast<const float4 *>(a.dkt + off);                            \
         }                                                                                        \
         if (tid < C) {                                                                           \
@@ -319,7 +319,7 @@ __global__ __launch_bounds__(P1T) void precond_bwd_kernel(PrecondBwdArgs a) {
 #pragma unroll
         for (int m = 0; m < NF; ++m) {
             const int i = tid + m * P1T, r = i / (K / 4), c = (i % (K / 4)) * 4;
-            const uint4 kv4 = sizeof(T) == 2 ? make_uint4(kreg2[m].x, kreg2[m].y, 0u, 0u) : kreg4[m];
+            const u32x4 kv4 = sizeof(T) == 2 ? u32x4{kreg2[m][0], kreg2[m][1], 0u, 0u} : kreg4[m];
             const float g4[4] = {greg[m].x, greg[m].y, greg[m].z, greg[m].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
