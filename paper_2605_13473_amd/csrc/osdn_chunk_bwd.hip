@@ -125,9 +125,10 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     constexpr int VN = 16 / sizeof(T);
     constexpr int NKT = K / 64;
     constexpr int NB = sizeof(T) == 2 ? 2 : 1;
-    constexpr int NWV = C * K / VN / CL_;
-    constexpr int NUV = VS * C / VN / CL_;
-    static_assert(VS * C / VN % CL_ == 0 && C * K / VN % CL_ == 0, "tiles must split evenly over the loaders");
+    constexpr int LTN = NB == 2 ? CL_ / 2 : CL_;    // two loader groups (one per chunk parity) when double-buffered
+    constexpr int NWV = C * K / VN / LTN;
+    constexpr int NUV = VS * C / VN / LTN;
+    static_assert(VS * C / VN % LTN == 0 && C * K / VN % LTN == 0, "tiles must split evenly over the loaders");
     __shared__ __attribute__((aligned(16))) T Krn[NB][C * LDK];     // rho . K~   [i][kf]
     __shared__ __attribute__((aligned(16))) T Wtt[NB][K * LDC];     // -W^T        [kf][i]
     __shared__ __attribute__((aligned(16))) T Qtt[NB][K * LDC];     // (scale gamma . Q)^T
@@ -143,6 +144,8 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool loader = wave >= 4;
     const int lt = tid - CL_;
+    const int lgrp = NB == 2 ? (lt >> 7) & 1 : 0;
+    const int lti = NB == 2 ? lt & 127 : lt;
     const size_t bh = (size_t)b * a.H + h;
     const size_t tstride = a.H;
 
@@ -169,13 +172,13 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         const T *og = static_cast<const T *>(a.dOt) + (bhn_ * a.V + vs) * C;                     \
         const T *eg = static_cast<const T *>(a.dElt) + (bhn_ * a.V + vs) * C;                    \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
-            const int i = lt + m * CL_, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
+            const int i = lti + m * LTN, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
             kreg[m] = *reinterpret_cast<const u32x4 *>(kg + (size_t)r * tstride * K + c);        \
             wreg[m] = *reinterpret_cast<const u32x4 *>(wg + (size_t)i * VN);                     \
             qreg[m] = *reinterpret_cast<const u32x4 *>(qg + (size_t)i * VN);                     \
         }                                                                                        \
         _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
-            const int i = lt + m * CL_;                                                          \
+            const int i = lti + m * LTN;                                                          \
             oreg[m] = *reinterpret_cast<const u32x4 *>(og + (size_t)i * VN);                     \
             ereg[m] = *reinterpret_cast<const u32x4 *>(eg + (size_t)i * VN);                     \
         }                                                                                        \
@@ -186,7 +189,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         const float G_ = wave_cumsum(greg, lane);                                                \
         const float GC_ = __shfl(G_, 63, 64);                                                    \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
-            const int i = lt + m * CL_;                                                          \
+            const int i = lti + m * LTN;                                                          \
             { const int r = i / (K / VN), c = (i % (K / VN)) * VN;                               \
               const float rho = __expf(GC_ - __shfl(G_, r, 64));                                 \
               _Pragma("unroll") for (int e = 0; e < VN; ++e)                                     \
@@ -196,16 +199,26 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
               *reinterpret_cast<u32x4 *>(&Qtt[buf_][r * LDC + c]) = qreg[m]; }                   \
         }                                                                                        \
         _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
-            const int i = lt + m * CL_, r = i / (C / VN), c = (i % (C / VN)) * VN;               \
+            const int i = lti + m * LTN, r = i / (C / VN), c = (i % (C / VN)) * VN;               \
             *reinterpret_cast<u32x4 *>(&dOts[buf_][r * LDC + c]) = oreg[m];                      \
             *reinterpret_cast<u32x4 *>(&dEls[buf_][r * LDC + c]) = ereg[m];                      \
         }                                                                                        \
-        if (tid == CL_) gCs[buf_] = __expf(GC_);                                                 \
+        if (lti == 0) gCs[buf_] = __expf(GC_);                                                 \
     }
     if (loader) {
-        OSDN_BC_LOAD(a.N - 1)
-        OSDN_BC_STORE(NB == 2 ? ((a.N - 1) & 1) : 0)
-        OSDN_BC_LOAD(max(a.N - 2, 0))
+        if (NB == 2) {
+            if (lgrp == ((a.N - 1) & 1)) {
+                OSDN_BC_LOAD(a.N - 1)
+                OSDN_BC_STORE((a.N - 1) & 1)
+                OSDN_BC_LOAD(max(a.N - 3, 0))
+            } else {
+                OSDN_BC_LOAD(max(a.N - 2, 0))
+            }
+        } else {
+            OSDN_BC_LOAD(a.N - 1)
+            OSDN_BC_STORE(0)
+            OSDN_BC_LOAD(max(a.N - 2, 0))
+        }
     }
 
     for (int n = a.N - 1; n >= 0; --n) {
@@ -221,10 +234,17 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         }
         __syncthreads();                                            // barrier 1
         if (loader) {
-            store_tile_global(static_cast<T *>(a.dS_ckpt) + (bhn * a.V + vs) * K, (size_t)K, dSb, LDK, VS, K, lt, CL_);
-            if (NB == 2 && n > 0) {
-                OSDN_BC_STORE((n - 1) & 1)
-                OSDN_BC_LOAD(max(n - 2, 0))         // (the last one is a harmless reload of chunk 0)
+            if (NB == 2) {
+                if (lgrp == ((n + 1) & 1)) {                        // this group's chunk (n - 1) comes next
+                    if (n > 0) {
+                        OSDN_BC_STORE((n - 1) & 1)
+                        OSDN_BC_LOAD(max(n - 3, 0))                 // (past the start: a harmless reload)
+                    }
+                } else {
+                    store_tile_global(static_cast<T *>(a.dS_ckpt) + (bhn * a.V + vs) * K, (size_t)K, dSb, LDK, VS, K, lti, LTN);
+                }
+            } else {
+                store_tile_global(static_cast<T *>(a.dS_ckpt) + (bhn * a.V + vs) * K, (size_t)K, dSb, LDK, VS, K, lt, CL_);
             }
         } else {
             // ---- phase B: dE = dEl + (rho . K~) dS'^T (rows 16*wave ..), kept transposed ----
@@ -240,7 +260,12 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         }
         __syncthreads();                                            // barrier 2
         if (loader) {
-            store_tile_global(static_cast<T *>(a.dEt) + (bhn * a.V + vs) * C, (size_t)C, dEt, LDC, VS, C, lt, CL_);
+            if (NB == 2) {
+                if (lgrp == ((n + 1) & 1))                          // the group with no load wait ahead
+                    store_tile_global(static_cast<T *>(a.dEt) + (bhn * a.V + vs) * C, (size_t)C, dEt, LDC, VS, C, lti, LTN);
+            } else {
+                store_tile_global(static_cast<T *>(a.dEt) + (bhn * a.V + vs) * C, (size_t)C, dEt, LDC, VS, C, lt, CL_);
+            }
         } else {
             // ---- phase C: dS <- gamma_C dS' + scale dO^T (gamma . Q) - dE^T W, transposed ----
             const float gC = gCs[buf];

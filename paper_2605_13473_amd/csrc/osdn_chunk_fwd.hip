@@ -196,9 +196,13 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     constexpr int VN = 16 / sizeof(T);
     constexpr int NKT = K / 64;                 // state row tiles (features) per compute wave
     constexpr int NB = sizeof(T) == 2 ? 2 : 1;  // LDS operand buffers (fp32 tiles are too big for two)
-    constexpr int NWV = C * K / VN / CL_;       // 16-byte vectors per loader thread, [64 x K] tile
-    constexpr int NUV = VS * C / VN / CL_;
-    static_assert(VS * C / VN % CL_ == 0 && C * K / VN % CL_ == 0, "tiles must split evenly over the loaders");
+    // With two buffers the loaders work as two groups of two wavefronts, one per chunk parity:
+    // a group fetches chunk c + 2 right after it has put chunk c into LDS, so every global
+    // load has two chunk times to arrive.
+    constexpr int LTN = NB == 2 ? CL_ / 2 : CL_;    // threads that share one chunk's tiles
+    constexpr int NWV = C * K / VN / LTN;       // 16-byte vectors per loader thread, [64 x K] tile
+    constexpr int NUV = VS * C / VN / LTN;
+    static_assert(VS * C / VN % LTN == 0 && C * K / VN % LTN == 0, "tiles must split evenly over the loaders");
     __shared__ __attribute__((aligned(16))) T Ws[NB][C * LDK];
     __shared__ __attribute__((aligned(16))) T Ktr[NB][K * LDC];
     __shared__ __attribute__((aligned(16))) T Uts[NB][VS * LDC];
@@ -212,6 +216,9 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool loader = wave >= 4;
     const int lt = tid - CL_;                   // loader thread index
+    const int lgrp = NB == 2 ? (lt >> 7) & 1 : 0;   // loader group (chunk parity it serves)
+    const int lti = NB == 2 ? lt & 127 : lt;    // index inside the group
+    const bool gwave = NB == 2 ? (wave & 1) == 0 : wave == 4;   // the group's wave that handles the gate
     const size_t bh = (size_t)b * a.H + h;
     const size_t tstride = a.H;
 
@@ -237,41 +244,57 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
         const T *kg = static_cast<const T *>(a.Ktr) + bhn_ * K * C;                              \
         const T *ug = static_cast<const T *>(a.Ut) + (bhn_ * a.V + vs) * C;                      \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
-            const int i = lt + m * CL_;                                                          \
+            const int i = lti + m * LTN;                                                          \
             wreg[m] = *reinterpret_cast<const u32x4 *>(wg + (size_t)i * VN);                     \
             kreg[m] = *reinterpret_cast<const u32x4 *>(kg + (size_t)i * VN);                     \
         }                                                                                        \
         _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
-            const int i = lt + m * CL_;                                                          \
+            const int i = lti + m * LTN;                                                          \
             ureg[m] = *reinterpret_cast<const u32x4 *>(ug + (size_t)i * VN);                     \
         }                                                                                        \
-        if (wave == 4)                                                                           \
+        if (gwave)                                                                               \
             greg = a.log_alpha ? a.log_alpha[((size_t)b * a.T + (size_t)(n_) * C + lane) * a.H + h] : 0.f; \
     }
 #define OSDN_SF_STORE(buf_)                                                                      \
     {                                                                                            \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
-            const int i = lt + m * CL_;                                                          \
+            const int i = lti + m * LTN;                                                          \
             { const int r = i / (K / VN), c = (i % (K / VN)) * VN;                               \
               *reinterpret_cast<u32x4 *>(&Ws[buf_][r * LDK + c]) = wreg[m]; }                    \
             { const int r = i / (C / VN), c = (i % (C / VN)) * VN;                               \
               *reinterpret_cast<u32x4 *>(&Ktr[buf_][r * LDC + c]) = kreg[m]; }                   \
         }                                                                                        \
         _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
-            const int i = lt + m * CL_, r = i / (C / VN), c = (i % (C / VN)) * VN;               \
+            const int i = lti + m * LTN, r = i / (C / VN), c = (i % (C / VN)) * VN;               \
             *reinterpret_cast<u32x4 *>(&Uts[buf_][r * LDC + c]) = ureg[m];                       \
         }                                                                                        \
-        if (wave == 4) {                                                                         \
+        if (gwave) {                                                                             \
             const float G_ = wave_cumsum(greg, lane);                                            \
             if (lane == 63) gCs[buf_] = __expf(G_);                                              \
         }                                                                                        \
     }
     if (loader) {
-        OSDN_SF_LOAD(0)
-        OSDN_SF_STORE(0)
-        OSDN_SF_LOAD(min(1, a.N - 1))
+        if (NB == 2) {
+            if (lgrp == 0) {
+                OSDN_SF_LOAD(0)
+                OSDN_SF_STORE(0)
+                OSDN_SF_LOAD(min(2, a.N - 1))
+            } else {
+                OSDN_SF_LOAD(min(1, a.N - 1))
+            }
+        } else {
+            OSDN_SF_LOAD(0)
+            OSDN_SF_STORE(0)
+            OSDN_SF_LOAD(min(1, a.N - 1))
+        }
     }
 
+#ifdef OSDN_DIAG
+    long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
+#define OSDN_TICK(j) { const long long now_ = clock64(); tph[j] += now_ - tlast; tlast = now_; }
+#else
+#define OSDN_TICK(j)
+#endif
     for (int n = 0; n < a.N; ++n) {
         const int buf = NB == 2 ? (n & 1) : 0;
         const size_t bhn = bh * a.N + n;
@@ -283,14 +306,25 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
                 for (int q = 0; q < NKT; ++q)
                     store_tile_t(Sb + vt * 16 * LDK + (wave * NKT + q) * 16, LDK, St[vt][q], lane);
         }
+        OSDN_TICK(0)
         __syncthreads();                                            // barrier 1
+        OSDN_TICK(1)
         if (loader) {
-            // checkpoint of the chunk-start state (read between barrier 1 and barrier 2)
-            if (a.S_ckpt)
+            if (NB == 2) {
+                if (lgrp == ((n + 1) & 1)) {                        // this group's chunk comes next
+                    if (n + 1 < a.N) {
+                        OSDN_SF_STORE((n + 1) & 1)                  // free since barrier 1
+                        OSDN_TICK(5)
+                        OSDN_SF_LOAD(min(n + 3, a.N - 1))           // (past the end: a harmless reload)
+                        OSDN_TICK(6)
+                    }
+                } else if (a.S_ckpt) {
+                    // checkpoint of the chunk-start state (read between barrier 1 and barrier 2)
+                    store_tile_global(static_cast<T *>(a.S_ckpt) + (bhn * a.V + vs) * K, (size_t)K, Sb, LDK, VS, K, lti, LTN);
+                    OSDN_TICK(7)
+                }
+            } else if (a.S_ckpt) {
                 store_tile_global(static_cast<T *>(a.S_ckpt) + (bhn * a.V + vs) * K, (size_t)K, Sb, LDK, VS, K, lt, CL_);
-            if (NB == 2 && n + 1 < a.N) {
-                OSDN_SF_STORE((n + 1) & 1)                          // free since barrier 1
-                OSDN_SF_LOAD(min(n + 2, a.N - 1))                   // (the last one is a harmless reload)
             }
         } else {
             // ---- phase B: E = U - W S^T (rows 16*wave ..), kept transposed ----
@@ -304,9 +338,16 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
                 store_tile_t(Et + vt * 16 * LDC + wave * 16, LDC, acc, lane);
             }
         }
+        OSDN_TICK(2)
         __syncthreads();                                            // barrier 2
+        OSDN_TICK(3)
         if (loader) {
-            store_tile_global(static_cast<T *>(a.Et) + (bhn * a.V + vs) * C, (size_t)C, Et, LDC, VS, C, lt, CL_);
+            if (NB == 2) {
+                if (lgrp == ((n + 1) & 1))                          // the group with no load wait ahead
+                    store_tile_global(static_cast<T *>(a.Et) + (bhn * a.V + vs) * C, (size_t)C, Et, LDC, VS, C, lti, LTN);
+            } else {
+                store_tile_global(static_cast<T *>(a.Et) + (bhn * a.V + vs) * C, (size_t)C, Et, LDC, VS, C, lt, CL_);
+            }
         } else {
             // ---- phase C: S <- gamma_C S + E^T (rho . K~), transposed ----
             const float gC = gCs[buf];
@@ -327,7 +368,14 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
                 OSDN_SF_LOAD(min(n + 2, a.N - 1))
             }
         }
+        OSDN_TICK(4)
     }
+#ifdef OSDN_DIAG
+    if (blockIdx.x == 0 && lane == 0 && (wave == 0 || wave == 4 || wave == 6))
+        for (int j = 0; j < 8; ++j) a.S_out[(wave == 0 ? 0 : wave == 4 ? 8 : 16) + j] = (float)tph[j];
+    __syncthreads();
+    if (blockIdx.x == 0) return;
+#endif
     if (!loader) {
 #pragma unroll
         for (int vt = 0; vt < 2; ++vt)
