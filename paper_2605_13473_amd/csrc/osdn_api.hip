@@ -13,9 +13,10 @@ using namespace osdn;
 // Optional per-kernel timing with HIP events on the caller's stream (off by default; the
 // only process-wide state the library has).  Not thread-safe; meant for benchmarks.
 enum { KID_PRECOND_FWD, KID_CHUNK_PREP, KID_STATE_FWD, KID_OUTPUT_FWD, KID_BWD_LOCAL, KID_BWD_CHAIN,
-       KID_BWD_POST, KID_PRECOND_BWD, KID_COUNT };
+       KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_COUNT };
 const char *const kKernelNames[KID_COUNT] = {"precond_fwd", "chunk_prep", "state_fwd", "output_fwd",
-                                             "bwd_local", "bwd_chain", "bwd_post", "precond_bwd"};
+                                             "bwd_local", "bwd_chain", "bwd_post", "precond_mask",
+                                             "precond_chain", "precond_post"};
 struct Timed { int id; hipEvent_t e0, e1; };
 bool g_prof_on = false;
 std::vector<Timed> g_prof;
@@ -33,7 +34,7 @@ template <typename F> int timed(int id, hipStream_t st, F &&launch) {
 
 struct Layout {
     size_t kt, d_ckpt, tok_scalars, Tm, W, Wt, Ktr, Ut, Et, S_ckpt;   // forward
-    size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt;   // backward only
+    size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;   // backward only
     size_t total_fwd, total_bwd;
 };
 
@@ -80,6 +81,8 @@ Layout make_layout(const osdn_params *p) {
     L.dS_ckpt = take(B * H * N * V * K * es);
     L.dk_read = take(B * T * H * K * 4);
     L.dkt = take(B * T * H * K * 4);
+    L.masks = take(B * H * N * K * 8);
+    L.a_ckpt = take(B * H * N * K * 4);
     L.total_bwd = off;
     return L;
 }
@@ -214,10 +217,15 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     pb.beta_aware = p->beta_aware;
     pb.k = k; pb.beta = beta; pb.retention = retention;
     pb.d_ckpt = reinterpret_cast<const float *>(ws + L.d_ckpt);
-    pb.tok_scalars = reinterpret_cast<const float *>(ws + L.tok_scalars);
+    pb.tok_scalars = reinterpret_cast<float *>(ws + L.tok_scalars);
+    pb.masks = reinterpret_cast<uint2 *>(ws + L.masks);
+    pb.a_ckpt = reinterpret_cast<float *>(ws + L.a_ckpt);
     pb.dkt = c.dkt; pb.dk_read = c.dk_read; pb.dd_out = dd_out;
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
-    if (timed(KID_PRECOND_BWD, st, [&] { return launch_precond_bwd(pb, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+    if (pb.d_min <= pb.d_max &&
+        timed(KID_PRECOND_MASK, st, [&] { return launch_precond_mask(pb, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_PRECOND_CHAIN, st, [&] { return launch_precond_chain(pb, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+    if (timed(KID_PRECOND_POST, st, [&] { return launch_precond_post(pb, bf, st); }) != 0) return OSDN_ERR_SHAPE;
     return launch_status();
 }
 

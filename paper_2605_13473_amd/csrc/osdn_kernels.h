@@ -24,7 +24,10 @@ struct PrecondBwdArgs {
     int beta_aware;
     const void *k;
     const float *beta, *retention, *d_ckpt;
-    const float *tok_scalars; // [B,T,H,4] from the forward sweep
+    float *tok_scalars;       // [B,T,H,4] from the forward sweep: (step, <d,k^2>, sum k^2, -); the chain
+                              // kernel puts sigma_t into the fourth slot for the post kernel
+    uint2 *masks;             // [B,H,T/64,K]: bit i = token i of the chunk stayed inside the box
+    float *a_ckpt;            // [B,H,T/64,K]: adjoint of d at the right end of every chunk
     const float *dkt;         // [B,T,H,K] fp32: dL/dk~ from phase 2
     const float *dk_read;     // [B,T,H,K] fp32: read-side dL/dk from phase 2
     const float *dd_out;      // [B,H,K] or null
@@ -69,7 +72,9 @@ struct ChunkArgs {
 };
 
 int launch_precond_fwd(const PrecondArgs &a, bool bf16_io, hipStream_t st);
-int launch_precond_bwd(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
+int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
+int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
+int launch_precond_post(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_chunk_prep(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 int launch_state_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 int launch_output_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st);

@@ -1,0 +1,355 @@
+// Reverse sweep over the projected affine recurrence of the preconditioner (Section 4.5),
+// split so that only what is sequential stays on the sequential path.
+//
+// With  abar_t = mask_t (.) a_{t+1},  sigma_t = <s_t, abar_t>,  s_t = k_t (.) k_t,
+//       a_t    = k_t (.) dL/dk~_t + r_t abar_t - ca_t sigma_t s_t        (ca_t = eta b'^2 / n_t)
+// the only coupling between chunks is the K-vector a at the chunk boundary, and inside a chunk
+// the only coupling between coordinates is the scalar sigma_t.  Three kernels:
+//   precond_mask   one workgroup per (chain, chunk), all chunks in parallel: replays d from the
+//                  stored chunk-start value and step scalars and records, per coordinate, the
+//                  64-bit mask of tokens whose unprojected update stayed inside the box
+//   precond_chain  one workgroup per chain, chunks right to left: finds sigma by fixed-point
+//                  sweeps (as the forward kernel finds <d, s>), keeps the adjoint at every chunk
+//                  boundary and the 64 sigmas of every chunk, nothing else
+//   precond_post   one workgroup per (chain, chunk), all chunks in parallel, one thread per
+//                  coordinate: replays d, re-runs the adjoint recurrence of its chunk from the
+//                  stored boundary value and sigmas, and writes dk, dbeta, dretention
+#include "osdn_precond.h"
+
+namespace osdn {
+
+// ---------------------------------------------------------------- precond_mask ----
+template <typename T, int K, bool HAS_RET>
+__global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
+    __shared__ __attribute__((aligned(16))) float steps[C];
+    __shared__ __attribute__((aligned(16))) float rs[C];
+    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int N = a.T / C;
+    const size_t bh = (size_t)b * a.H + h;
+    const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+    const bool project = a.d_min <= a.d_max;
+    const float lo = project ? a.d_min : -INFINITY, hi = project ? a.d_max : INFINITY;
+    if (tid < C) {
+        const size_t th = tokc + (size_t)tid * a.H;
+        steps[tid] = a.tok_scalars[th * 4];
+        rs[tid] = HAS_RET ? a.retention[th] : 1.f;
+    }
+    const T *kp = static_cast<const T *>(a.k) + tokc * K;
+    const uint32_t kstride = (uint32_t)a.H * K;
+    float kv[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) kv[i] = to_f32(kp[(uint32_t)tid + (uint32_t)i * kstride]);
+    float d = a.d_ckpt[(bh * N + n) * K + tid];
+    __syncthreads();
+    uint32_t mlo = 0u, mhi = 0u;
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        const float db = d_bar<HAS_RET>(rs[i], d, steps[i], kv[i] * kv[i]);
+        d = clip3(db, lo, hi);
+        const uint32_t in = (d == db) ? (1u << (i & 31)) : 0u;
+        if (i < 32) mlo |= in; else mhi |= in;
+    }
+    a.masks[(bh * N + n) * K + tid] = make_uint2(mlo, mhi);
+}
+
+// --------------------------------------------------------------- precond_chain ----
+template <typename T, int K, bool HAS_RET>
+__global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
+    constexpr int LD = K + 1;
+    constexpr int NF = C * K / 4 / P1T;           // groups of 4 columns per thread for a [64 x K] tile
+    constexpr int KQ = K / P1W;
+    __shared__ float ss[C * LD];                 // s = k^2
+    __shared__ float Ls[C * LD];                 // lambda = k . dL/dk~
+    __shared__ float At[C * LD];                 // source term, then the masked adjoint abar_i
+    __shared__ float ga[K], ganew[K];            // adjoint of d at the right / left end of the chunk
+    __shared__ float cas[C], sig[C];
+    __shared__ __attribute__((aligned(16))) float rs[C];
+    __shared__ __attribute__((aligned(16))) float casig[C];
+    __shared__ float part[P1W * C];
+    __shared__ int done;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
+    const size_t bh = (size_t)b * a.H + h;
+    const T *k = static_cast<const T *>(a.k);
+    const bool project = a.d_min <= a.d_max;
+    const int N = a.T / C;
+
+    if (tid < K) ga[tid] = a.dd_out ? a.dd_out[bh * K + tid] : 0.f;
+
+    u32x2 kreg2[NF];        // bf16: 4 elements = 8 bytes ; fp32 uses kreg4
+    u32x4 kreg4[NF];
+    float4 greg[NF];
+    float nrawreg = 1.f, betreg = 0.f, retreg = 1.f;
+    uint2 mreg = make_uint2(0xffffffffu, 0xffffffffu);
+#define OSDN_P1_BLOAD(n_)                                                                        \
+    {                                                                                            \
+        const size_t tokc_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                     \
+        _Pragma("unroll") for (int m = 0; m < NF; ++m) {                                         \
+            const int i = tid + m * P1T, r = i / (K / 4), c = (i % (K / 4)) * 4;                  \
+            const size_t off = (tokc_ + (size_t)r * a.H) * K + c;                                \
+            if (sizeof(T) == 2) kreg2[m] = *reinterpret_cast<const u32x2 *>(k + off);            \
+            else kreg4[m] = *reinterpret_cast<const u32x4 *>(k + off);                           \
+            greg[m] = *reinterpret_cast<const float4 *>(a.dkt + off);                            \
+        }                                                                                        \
+        if (tid < C) {                                                                           \
+            const size_t th = tokc_ + (size_t)tid * a.H;                                         \
+            nrawreg = a.tok_scalars[th * 4 + 2];                                                 \
+            betreg = a.beta[th];                                                                 \
+            if (HAS_RET) retreg = a.retention[th];                                               \
+        }                                                                                        \
+        if (project && tid < K) mreg = a.masks[(bh * N + (n_)) * K + tid];                       \
+    }
+    OSDN_P1_BLOAD(N - 1)
+
+#ifdef OSDN_DIAG
+    long long tph[6] = {0, 0, 0, 0, 0, 0}, tlast = clock64();
+#define OSDN_TICK(j) { const long long now_ = clock64(); tph[j] += now_ - tlast; tlast = now_; }
+#else
+#define OSDN_TICK(j)
+#endif
+    for (int n = N - 1; n >= 0; --n) {
+        const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+        // ---- registers -> LDS ----
+#pragma unroll
+        for (int m = 0; m < NF; ++m) {
+            const int i = tid + m * P1T, r = i / (K / 4), c = (i % (K / 4)) * 4;
+            const u32x4 kv4 = sizeof(T) == 2 ? u32x4{kreg2[m][0], kreg2[m][1], 0u, 0u} : kreg4[m];
+            const float g4[4] = {greg[m].x, greg[m].y, greg[m].z, greg[m].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float kv = vec_get<T>(kv4, e);
+                ss[r * LD + c + e] = kv * kv;
+                Ls[r * LD + c + e] = kv * g4[e];
+            }
+        }
+        if (tid < C) {
+            const float nn = fmaxf(nrawreg, a.eps);
+            const float bp = a.beta_aware ? betreg : 1.f;
+            rs[tid] = retreg; cas[tid] = a.eta * bp / nn * bp; sig[tid] = 0.f; casig[tid] = 0.f;
+        }
+        const uint32_t mlo = mreg.x, mhi = mreg.y;
+        if (tid < K) a.a_ckpt[(bh * N + n) * K + tid] = ga[tid];
+        __syncthreads();
+        OSDN_TICK(0)
+        if (n > 0) OSDN_P1_BLOAD(n - 1)         // next chunk: in flight during the sweeps
+        const bool all_in = __all(mlo == 0xffffffffu && mhi == 0xffffffffu);    // per wave
+        // ---- sweeps for sigma_i = <s_i, abar_i> ----
+        float dprev = 0.f;
+        for (int sweep = 0; sweep < P1_MAX_SWEEPS; ++sweep) {
+            // source term of the adjoint recurrence, all threads: At <- lambda_i - ca_i sigma_i s_i
+#pragma unroll
+            for (int j = 0; j < C * K / P1T; ++j) {      // consecutive lanes -> consecutive columns
+                const int e = tid + j * P1T, r = e / K, x = r * LD + e % K;
+                At[x] = __builtin_fmaf(-casig[r], ss[x], Ls[x]);
+            }
+            __syncthreads();
+            OSDN_TICK(1)
+            if (tid < K) {
+                float av = ga[tid];
+                float sb[2][PB], rb[2][PB];
+#define OSDN_VLOAD(buf, ih_)                                                                     \
+    _Pragma("unroll") for (int u = 0; u < PB; ++u) {                                             \
+        sb[buf][u] = At[((ih_) - u) * LD + tid];                                                 \
+        if (HAS_RET) rb[buf][u] = rs[(ih_) - u];                                                 \
+    }
+                OSDN_VLOAD(0, C - 1)
+                if (all_in) {       // no coordinate of this wave touched the box in this chunk
+#pragma unroll
+                    for (int blk = 0; blk < C / PB; ++blk) {
+                        const int ih = C - 1 - blk * PB;
+                        if (blk + 1 < C / PB) OSDN_VLOAD((blk + 1) & 1, ih - PB)
+#pragma unroll
+                        for (int u = 0; u < PB; ++u) {
+                            At[(ih - u) * LD + tid] = av;
+                            av = HAS_RET ? __builtin_fmaf(rb[blk & 1][u], av, sb[blk & 1][u]) : av + sb[blk & 1][u];
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int blk = 0; blk < C / PB; ++blk) {
+                        const int ih = C - 1 - blk * PB;
+                        if (blk + 1 < C / PB) OSDN_VLOAD((blk + 1) & 1, ih - PB)
+#pragma unroll
+                        for (int u = 0; u < PB; ++u) {
+                            const int i = ih - u;
+                            const uint32_t bit = (i < 32 ? mlo : mhi) & (1u << (i & 31));
+                            const float ab = bit ? av : 0.f;
+                            At[i * LD + tid] = ab;  // the source of token i was fetched a block ahead
+                            av = HAS_RET ? __builtin_fmaf(rb[blk & 1][u], ab, sb[blk & 1][u]) : ab + sb[blk & 1][u];
+                        }
+                    }
+                }
+                ganew[tid] = av;
+            }
+            __syncthreads();
+            OSDN_TICK(2)
+            {
+                const int i = lane, q0 = wave * KQ;
+                float sp = 0.f;
+#pragma unroll 8
+                for (int c = 0; c < KQ; ++c) sp = __builtin_fmaf(ss[i * LD + q0 + c], At[i * LD + q0 + c], sp);
+                part[wave * C + i] = sp;
+            }
+            __syncthreads();
+            if (tid < C) {
+                const int i = tid;
+                const float sg = sumw(part, i);
+                const float mx = wave_max(fabsf(sg));
+                const float dcur = wave_max(fabsf(sg - sig[i]));
+                // converged, or (from the second pass on) the observed contraction ratio says
+                // that the next difference would be below the tolerance
+                const bool all_ok = dcur <= P1_TOL * mx ||
+                                    (sweep >= 1 && dcur <= 0.1f * dprev && dcur * dcur <= P1_TOL * mx * dprev);
+                dprev = dcur;
+                sig[i] = sg;
+                casig[i] = cas[i] * sg;
+                if (tid == 0) done = all_ok ? 1 : 0;
+            }
+            __syncthreads();
+            OSDN_TICK(3)
+            if (done) break;
+        }
+        // ---- accepted: sig generated ganew ----
+        if (tid < C) a.tok_scalars[(tokc + (size_t)tid * a.H) * 4 + 3] = sig[tid];
+        if (tid < K) ga[tid] = ganew[tid];
+        __syncthreads();
+        OSDN_TICK(4)
+    }
+#ifdef OSDN_DIAG
+    if (tid == 0 && blockIdx.x == 0)
+        for (int j = 0; j < 6; ++j) a.a_ckpt[j] = (float)tph[j];
+#endif
+    if (tid < K) a.dd_in[bh * K + tid] = ga[tid];
+}
+
+// ---------------------------------------------------------------- precond_post ----
+//   in : k, beta, retention, d_ckpt, tok_scalars (step, <d,s>, sum s, sigma per token),
+//        a_ckpt (adjoint of d at the right end of every chunk), dkt (dL/dk~, fp32),
+//        dk_read (read-side dL/dk, fp32), dbeta (partial, from phase 2)
+//   out: dk (io type) = dk_read + d_t . dkt + 2 k_t (step_t abar_t + g_p d_t + g_nraw),
+//        dbeta += sigma_t eta (1 - 2 b' p_t)/n_t,  dretention_t = <abar_t, d_t>
+template <typename T, int K, bool HAS_RET>
+__global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void precond_post_kernel(PrecondBwdArgs a) {
+    constexpr int LD = K + 1;
+    __shared__ __attribute__((aligned(16))) float st_s[C];
+    __shared__ __attribute__((aligned(16))) float r_s[C];
+    __shared__ __attribute__((aligned(16))) float casig_s[C];
+    __shared__ __attribute__((aligned(16))) float gp_s[C];
+    __shared__ __attribute__((aligned(16))) float gn_s[C];
+    __shared__ float prod[HAS_RET ? C * LD : 1];    // abar_i d_i per coordinate, for dL/dr
+    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int N = a.T / C;
+    const size_t bh = (size_t)b * a.H + h;
+    const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+    const bool project = a.d_min <= a.d_max;
+    const float lo = project ? a.d_min : -INFINITY, hi = project ? a.d_max : INFINITY;
+    if (tid < C) {
+        const size_t th = tokc + (size_t)tid * a.H;
+        const float4 sc = *reinterpret_cast<const float4 *>(a.tok_scalars + th * 4);
+        const float step = sc.x, p = sc.y, n_raw = sc.z, sg = sc.w;
+        const float bet = a.beta[th];
+        const float nn = fmaxf(n_raw, a.eps);
+        const float bp = a.beta_aware ? bet : 1.f;
+        const float ca = a.eta * bp / nn * bp;
+        st_s[tid] = step;
+        r_s[tid] = HAS_RET ? a.retention[th] : 1.f;
+        casig_s[tid] = ca * sg;
+        gp_s[tid] = -sg * ca;
+        gn_s[tid] = (n_raw >= a.eps) ? -sg * step / nn : 0.f;
+        if (a.beta_aware) a.dbeta[th] += sg * a.eta * (1.f - 2.f * bp * p) / nn;
+    }
+    // uniform bases + 32-bit per-thread offsets (64 rows of H*K elements: below 2^31)
+    const T *kp = static_cast<const T *>(a.k) + tokc * K;
+    const float *gp = a.dkt + tokc * K, *rp = a.dk_read + tokc * K;
+    T *op = static_cast<T *>(a.dk) + tokc * K;
+    const uint32_t kstride = (uint32_t)a.H * K;
+    float Dv[C];
+    uint32_t mlo = 0u, mhi = 0u;
+    {   // ---- replay d over the chunk (same arithmetic as the forward kernel) ----
+        float kv[C];
+#pragma unroll
+        for (int i = 0; i < C; ++i) kv[i] = to_f32(kp[(uint32_t)tid + (uint32_t)i * kstride]);
+        float d = a.d_ckpt[(bh * N + n) * K + tid];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            Dv[i] = d;
+            const float db = d_bar<HAS_RET>(r_s[i], d, st_s[i], kv[i] * kv[i]);
+            d = clip3(db, lo, hi);
+            const uint32_t in = (d == db) ? (1u << (i & 31)) : 0u;
+            if (i < 32) mlo |= in; else mhi |= in;
+        }
+    }
+    // ---- the chunk's adjoint recurrence, right to left, and the elementwise outputs ----
+    float av = a.a_ckpt[(bh * N + n) * K + tid];
+    // (the per-token scalars are read again through pointers the compiler cannot identify with
+    // the arrays, so that it does not keep the replay's 128 values in registers)
+    const float *st_p = st_s, *r_p = r_s, *casig_p = casig_s, *gp_p = gp_s, *gn_p = gn_s;
+    asm volatile("" : "+v"(st_p), "+v"(r_p), "+v"(casig_p), "+v"(gp_p), "+v"(gn_p));
+    float kb[2][PB], gb[2][PB], rb[2][PB];
+    uint32_t lofs = (uint32_t)tid + (uint32_t)(C - 1) * kstride;    // offset of the next row to fetch
+    asm volatile("" : "+v"(lofs));
+    uint32_t sofs = lofs;                                            // ... and of the next row to write
+#define OSDN_PLOAD(buf, ih_)                                                                     \
+    _Pragma("unroll") for (int u = 0; u < PB; ++u) {                                             \
+        kb[buf][u] = to_f32(kp[lofs]); gb[buf][u] = gp[lofs]; rb[buf][u] = rp[lofs];             \
+        lofs -= kstride;                                                                         \
+    }
+    OSDN_PLOAD(0, C - 1)
+#pragma unroll
+    for (int blk = 0; blk < C / PB; ++blk) {
+        const int ih = C - 1 - blk * PB;
+        if (blk + 1 < C / PB) OSDN_PLOAD((blk + 1) & 1, ih - PB)
+#pragma unroll
+        for (int u = 0; u < PB; ++u) {
+            const int i = ih - u;
+            const uint32_t bit = (i < 32 ? mlo : mhi) & (1u << (i & 31));
+            const float ab = bit ? av : 0.f;
+            const float kv = kb[blk & 1][u], g = gb[blk & 1][u], Di = Dv[i];
+            const float gsum = st_p[i] * ab + gp_p[i] * Di + gn_p[i];
+            op[sofs] = from_f32<T>(rb[blk & 1][u] + Di * g + 2.f * kv * gsum);
+            sofs -= kstride;
+            if (HAS_RET) prod[i * LD + tid] = ab * Di;
+            const float src = __builtin_fmaf(-casig_p[i], kv * kv, kv * g);
+            av = HAS_RET ? __builtin_fmaf(r_p[i], ab, src) : ab + src;
+        }
+    }
+    if (HAS_RET) {
+        __syncthreads();
+        if (tid < C && a.dretention) {
+            float s = 0.f;
+#pragma unroll 8
+            for (int c = 0; c < K; ++c) s += prod[tid * LD + c];
+            a.dretention[tokc + (size_t)tid * a.H] = s;
+        }
+    }
+}
+
+// -------------------------------------------------------------------- launchers ----
+template <typename T, bool HAS_RET>
+static int launch_precond_bwd_t(const PrecondBwdArgs &a, int which, hipStream_t st) {
+    const dim3 per_chunk(a.T / C, a.H, a.B);
+    if (a.K == 64) {
+        if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 64, HAS_RET>), per_chunk, dim3(64), 0, st, a);
+        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 64, HAS_RET>), dim3(a.B * a.H), dim3(P1T), 0, st, a);
+        else hipLaunchKernelGGL((precond_post_kernel<T, 64, HAS_RET>), per_chunk, dim3(64), 0, st, a);
+    } else if (a.K == 128) {
+        if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 128, HAS_RET>), per_chunk, dim3(128), 0, st, a);
+        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 128, HAS_RET>), dim3(a.B * a.H), dim3(P1T), 0, st, a);
+        else hipLaunchKernelGGL((precond_post_kernel<T, 128, HAS_RET>), per_chunk, dim3(128), 0, st, a);
+    } else {
+        return -1;
+    }
+    return 0;
+}
+static int launch_precond_bwd_any(const PrecondBwdArgs &a, bool bf16_io, int which, hipStream_t st) {
+    if (a.retention)
+        return bf16_io ? launch_precond_bwd_t<bf16, true>(a, which, st) : launch_precond_bwd_t<float, true>(a, which, st);
+    return bf16_io ? launch_precond_bwd_t<bf16, false>(a, which, st) : launch_precond_bwd_t<float, false>(a, which, st);
+}
+int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) { return launch_precond_bwd_any(a, bf16_io, 0, st); }
+int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) { return launch_precond_bwd_any(a, bf16_io, 1, st); }
+int launch_precond_post(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) { return launch_precond_bwd_any(a, bf16_io, 2, st); }
+
+}  // namespace osdn
