@@ -372,15 +372,41 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     }
     const int rb = wave >> 1;           // row block of steps (1), (2)
 
+    // the slab tiles travel through registers: the next slab (after the last one: Q and K~) is
+    // fetched while the workgroup computes on the current one
+    TileRegs<T, C, VB, PT_> r_dO, r_V;
+    TileRegs<T, VB, C, PT_> r_Et, r_dEt;
+    TileRegs<T, VB, K, PT_> r_S, r_dS;
+    TileRegs<T, C, K, PT_> r_Q, r_Kt;
+#define OSDN_BP_FETCH(v0_)                                                                        \
+    {                                                                                            \
+        r_dO.fetch(static_cast<const T *>(a.dO) + tok0 * a.V + (v0_), tstride * a.V, tid);       \
+        r_V.fetch(static_cast<const T *>(a.v) + tok0 * a.V + (v0_), tstride * a.V, tid);         \
+        r_Et.fetch(static_cast<const T *>(a.Et) + (bhn * a.V + (v0_)) * C, (size_t)C, tid);      \
+        r_dEt.fetch(static_cast<const T *>(a.dEt) + (bhn * a.V + (v0_)) * C, (size_t)C, tid);    \
+        r_S.fetch(static_cast<const T *>(a.S_ckpt) + (bhn * a.V + (v0_)) * K, (size_t)K, tid);   \
+        r_dS.fetch(static_cast<const T *>(a.dS_ckpt) + (bhn * a.V + (v0_)) * K, (size_t)K, tid); \
+    }
+    OSDN_BP_FETCH(0)
+#ifdef OSDN_DIAG
+    long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
+#define OSDN_PTICK(j) { const long long now_ = clock64(); tph[j] += now_ - tlast; tlast = now_; }
+#else
+#define OSDN_PTICK(j)
+#endif
     for (int v0 = 0; v0 < a.V; v0 += VB) {
         __syncthreads();
-        load_tile(dOs, LDV, static_cast<const T *>(a.dO) + tok0 * a.V + v0, tstride * a.V, C, VB, tid, PT_);
-        load_tile(Vs, LDV, static_cast<const T *>(a.v) + tok0 * a.V + v0, tstride * a.V, C, VB, tid, PT_);
-        load_tile(Ets, LDC, static_cast<const T *>(a.Et) + (bhn * a.V + v0) * C, (size_t)C, VB, C, tid, PT_);
-        load_tile(dEts, LDC, static_cast<const T *>(a.dEt) + (bhn * a.V + v0) * C, (size_t)C, VB, C, tid, PT_);
-        load_tile(Ss, LDK, static_cast<const T *>(a.S_ckpt) + (bhn * a.V + v0) * K, (size_t)K, VB, K, tid, PT_);
-        load_tile(dSs, LDK, static_cast<const T *>(a.dS_ckpt) + (bhn * a.V + v0) * K, (size_t)K, VB, K, tid, PT_);
+        r_dO.put(dOs, LDV, tid); r_V.put(Vs, LDV, tid);
+        r_Et.put(Ets, LDC, tid); r_dEt.put(dEts, LDC, tid);
+        r_S.put(Ss, LDK, tid); r_dS.put(dSs, LDK, tid);
+        if (v0 + VB < a.V) {
+            OSDN_BP_FETCH(v0 + VB)
+        } else {
+            r_Q.fetch(static_cast<const T *>(a.q) + tok0 * K, tstride * K, tid);
+            r_Kt.fetch(static_cast<const T *>(a.kt) + tok0 * K, tstride * K, tid);
+        }
         __syncthreads();
+        OSDN_PTICK(0)
         // <dS', S> over this slab
         for (int idx = tid; idx < VB * K; idx += PT_) {
             const int r = idx / K, c = idx % K;
@@ -423,6 +449,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
             }
         }
         __syncthreads();
+        OSDN_PTICK(1)
         // (3,4) dP += dO E^T, dA -= dR E^T on the lower tiles
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -456,6 +483,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
             }
         }
         __syncthreads();
+        OSDN_PTICK(2)
         // dV = beta . dR for this slab, staged through the dO buffer
         for (int idx = tid; idx < C * VB; idx += PT_) {
             const int r = idx / VB, c = idx % VB;
@@ -463,11 +491,12 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
         }
         __syncthreads();
         store_tile_global(static_cast<T *>(a.dv) + tok0 * a.V + v0, tstride * a.V, dOs, LDV, C, VB, tid, PT_);
+        OSDN_PTICK(3)
     }
     __syncthreads();
     // ---- after the walk: Q, K~ into the pool ----
-    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, PT_);
-    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, PT_);
+    r_Q.put(Qs, LDK, tid);
+    r_Kt.put(Kts, LDK, tid);
     for (int idx = tid; idx < C * C; idx += PT_) {      // upper triangle of cA, cP is zero
         const int i = idx >> 6, j = idx & 63;
         cAs[i * LDC + j] = from_f32<T>(0.f);
@@ -483,6 +512,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
         if (acc_col(lane) == 0) dbeta_s[(wave & 1) * C + rb * 16 + acc_row(lane, r)] = sred;
     }
     __syncthreads();
+    OSDN_PTICK(4)
     // ---- lower tiles: A0, P, X, cA, cP ----
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -521,6 +551,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
         }
     }
     __syncthreads();
+    OSDN_PTICK(5)
     // ---- dQ, dK (read side), dK~ and the inner products that enter dG (column tile ct) ----
     float tq[4][4], tk[4][4], tr[4][4];     // [row block][r]: partial row dots over this wave's columns
 #pragma unroll
@@ -584,6 +615,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
             }
         }
     __syncthreads();
+    OSDN_PTICK(6)
     if (wave == 0) {
         const int i = lane;
         float t_q = 0.f, t_k = 0.f, t_r = 0.f;
@@ -604,6 +636,11 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
             a.dlog_alpha[th] = wave_suffix_sum(dG, lane);
         }
     }
+#ifdef OSDN_DIAG
+    OSDN_PTICK(7)
+    if (tid == 0 && blockIdx.x == 5 && blockIdx.y == 0 && blockIdx.z == 0 && a.dlog_alpha)
+        for (int j = 0; j < 8; ++j) a.dlog_alpha[tok0 + (size_t)j * tstride] = (float)tph[j];
+#endif
 }
 
 // -------------------------------------------------------------- launchers ----

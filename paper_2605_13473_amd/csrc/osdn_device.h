@@ -60,10 +60,18 @@ template <> struct Mfma<bf16> {
         if (KCONTIG) {
             return *reinterpret_cast<const bf16x8 *>(base + row * ld + kk);   // 16-byte aligned by layout
         } else {
-            Frag f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) f[e] = base[(kk + e) * ld + row];
-            return f;
+            // LDS transpose read (ds_read_b64_tr_b16): inside a group of 16 lanes, lane j passes the
+            // address of 4 contiguous 16-bit values, (row j/4, columns 4(j%4)..) of a 4 x 16 block,
+            // and receives column j of that block, i.e. 4 consecutive k for its own row index.
+            // Two of them give the 8 values of the fragment.  base must be an LDS address with
+            // 8-byte aligned rows (ld a multiple of 4).
+            typedef short v4s __attribute__((ext_vector_type(4)));
+            typedef short v8s __attribute__((ext_vector_type(8)));
+            typedef __attribute__((address_space(3))) v4s *lds_v4s;
+            const bf16 *p = base + (kk + (row >> 2)) * ld + 4 * (row & 3);
+            const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p));
+            const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + 4 * ld));
+            return __builtin_bit_cast(Frag, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
     }
     static __device__ __forceinline__ f32x4 mma(Frag a, Frag b, f32x4 c) {
@@ -168,6 +176,30 @@ __device__ __forceinline__ void store_tile_global(T *g, size_t g_ld, const T *s,
             *reinterpret_cast<const u32x4 *>(s + r * s_ld + c);
     }
 }
+
+// The same copy in two halves, so that the global loads of a tile can be in flight while the
+// workgroup computes on the previous one: tile_fetch issues them into registers, tile_put
+// writes the registers into LDS.  NT threads share a [ROWS x COLS] tile.
+template <typename T, int ROWS, int COLS, int NT_>
+struct TileRegs {
+    static constexpr int VN = 16 / sizeof(T), VPR = COLS / VN, NV = ROWS * VPR / NT_;
+    static_assert(ROWS * VPR % NT_ == 0 && NV >= 1, "tile must split evenly over the threads");
+    u32x4 v[NV];
+    __device__ __forceinline__ void fetch(const T *g, size_t g_ld, int tid) {
+#pragma unroll
+        for (int m = 0; m < NV; ++m) {
+            const int i = tid + m * NT_, r = i / VPR, c = (i % VPR) * VN;
+            v[m] = *reinterpret_cast<const u32x4 *>(g + (size_t)r * g_ld + c);
+        }
+    }
+    __device__ __forceinline__ void put(T *s, int s_ld, int tid) const {
+#pragma unroll
+        for (int m = 0; m < NV; ++m) {
+            const int i = tid + m * NT_, r = i / VPR, c = (i % VPR) * VN;
+            *reinterpret_cast<u32x4 *>(s + r * s_ld + c) = v[m];
+        }
+    }
+};
 
 // --------------------------------------------------------- wave helpers ----
 template <int CTRL, int ROW_MASK = 0xF>

@@ -56,11 +56,12 @@ __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
 template <typename T, int K, bool HAS_RET>
 __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
     constexpr int LD = K + 1;
-    constexpr int NF = C * K / 4 / P1T;           // groups of 4 columns per thread for a [64 x K] tile
+    constexpr int LD2 = 2 * K + 2;                // row stride of the interleaved (s, lambda) tile, in floats
+    constexpr int NF = C * K / 2 / P1T;           // column pairs per thread for a [64 x K] tile
     constexpr int KQ = K / P1W;
-    __shared__ float ss[C * LD];                 // s = k^2
-    __shared__ float Ls[C * LD];                 // lambda = k . dL/dk~
-    __shared__ float At[C * LD];                 // source term, then the masked adjoint abar_i
+    // (s, lambda) = (k^2, k . dL/dk~) of the chunk, interleaved so that one 8-byte read brings both
+    __shared__ __attribute__((aligned(16))) float2 SL[C * (LD2 / 2)];
+    __shared__ float At[C * LD];                 // masked adjoint abar_i
     __shared__ float ga[K], ganew[K];            // adjoint of d at the right / left end of the chunk
     __shared__ float cas[C], sig[C];
     __shared__ __attribute__((aligned(16))) float rs[C];
@@ -77,20 +78,21 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 
     if (tid < K) ga[tid] = a.dd_out ? a.dd_out[bh * K + tid] : 0.f;
 
-    u32x2 kreg2[NF];        // bf16: 4 elements = 8 bytes ; fp32 uses kreg4
-    u32x4 kreg4[NF];
-    float4 greg[NF];
+    // a thread stages pairs of columns: consecutive lanes -> consecutive pairs of one row
+    uint32_t kreg1[NF];     // bf16: 2 elements = 4 bytes ; fp32 uses kreg2
+    u32x2 kreg2[NF];
+    float2 greg[NF];
     float nrawreg = 1.f, betreg = 0.f, retreg = 1.f;
     uint2 mreg = make_uint2(0xffffffffu, 0xffffffffu);
 #define OSDN_P1_BLOAD(n_)                                                                        \
     {                                                                                            \
         const size_t tokc_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                     \
         _Pragma("unroll") for (int m = 0; m < NF; ++m) {                                         \
-            const int i = tid + m * P1T, r = i / (K / 4), c = (i % (K / 4)) * 4;                  \
+            const int i = tid + m * P1T, r = i / (K / 2), c = (i % (K / 2)) * 2;                  \
             const size_t off = (tokc_ + (size_t)r * a.H) * K + c;                                \
-            if (sizeof(T) == 2) kreg2[m] = *reinterpret_cast<const u32x2 *>(k + off);            \
-            else kreg4[m] = *reinterpret_cast<const u32x4 *>(k + off);                           \
-            greg[m] = *reinterpret_cast<const float4 *>(a.dkt + off);                            \
+            if (sizeof(T) == 2) kreg1[m] = *reinterpret_cast<const uint32_t *>(k + off);         \
+            else kreg2[m] = *reinterpret_cast<const u32x2 *>(k + off);                           \
+            greg[m] = *reinterpret_cast<const float2 *>(a.dkt + off);                            \
         }                                                                                        \
         if (tid < C) {                                                                           \
             const size_t th = tokc_ + (size_t)tid * a.H;                                         \
@@ -113,15 +115,11 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         // ---- registers -> LDS ----
 #pragma unroll
         for (int m = 0; m < NF; ++m) {
-            const int i = tid + m * P1T, r = i / (K / 4), c = (i % (K / 4)) * 4;
-            const u32x4 kv4 = sizeof(T) == 2 ? u32x4{kreg2[m][0], kreg2[m][1], 0u, 0u} : kreg4[m];
-            const float g4[4] = {greg[m].x, greg[m].y, greg[m].z, greg[m].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float kv = vec_get<T>(kv4, e);
-                ss[r * LD + c + e] = kv * kv;
-                Ls[r * LD + c + e] = kv * g4[e];
-            }
+            const int i = tid + m * P1T, r = i / (K / 2), c = (i % (K / 2)) * 2;
+            const u32x4 kv4 = sizeof(T) == 2 ? u32x4{kreg1[m], 0u, 0u, 0u} : u32x4{kreg2[m][0], kreg2[m][1], 0u, 0u};
+            const float k0 = vec_get<T>(kv4, 0), k1 = vec_get<T>(kv4, 1);
+            SL[r * (LD2 / 2) + c] = make_float2(k0 * k0, k0 * greg[m].x);
+            SL[r * (LD2 / 2) + c + 1] = make_float2(k1 * k1, k1 * greg[m].y);
         }
         if (tid < C) {
             const float nn = fmaxf(nrawreg, a.eps);
@@ -137,20 +135,15 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         // ---- sweeps for sigma_i = <s_i, abar_i> ----
         float dprev = 0.f;
         for (int sweep = 0; sweep < P1_MAX_SWEEPS; ++sweep) {
-            // source term of the adjoint recurrence, all threads: At <- lambda_i - ca_i sigma_i s_i
-#pragma unroll
-            for (int j = 0; j < C * K / P1T; ++j) {      // consecutive lanes -> consecutive columns
-                const int e = tid + j * P1T, r = e / K, x = r * LD + e % K;
-                At[x] = __builtin_fmaf(-casig[r], ss[x], Ls[x]);
-            }
-            __syncthreads();
-            OSDN_TICK(1)
+            // the source term  lambda_i - ca_i sigma_i s_i  is formed inside the recurrence
             if (tid < K) {
                 float av = ga[tid];
-                float sb[2][PB], rb[2][PB];
+                float sb[2][PB], lb[2][PB], cb[2][PB], rb[2][PB];
 #define OSDN_VLOAD(buf, ih_)                                                                     \
     _Pragma("unroll") for (int u = 0; u < PB; ++u) {                                             \
-        sb[buf][u] = At[((ih_) - u) * LD + tid];                                                 \
+        const float2 sl_ = SL[((ih_) - u) * (LD2 / 2) + tid];                                    \
+        sb[buf][u] = sl_.x; lb[buf][u] = sl_.y;                                                  \
+        cb[buf][u] = casig[(ih_) - u];                                                           \
         if (HAS_RET) rb[buf][u] = rs[(ih_) - u];                                                 \
     }
                 OSDN_VLOAD(0, C - 1)
@@ -162,7 +155,8 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 #pragma unroll
                         for (int u = 0; u < PB; ++u) {
                             At[(ih - u) * LD + tid] = av;
-                            av = HAS_RET ? __builtin_fmaf(rb[blk & 1][u], av, sb[blk & 1][u]) : av + sb[blk & 1][u];
+                            const float src = __builtin_fmaf(-cb[blk & 1][u], sb[blk & 1][u], lb[blk & 1][u]);
+                            av = HAS_RET ? __builtin_fmaf(rb[blk & 1][u], av, src) : av + src;
                         }
                     }
                 } else {
@@ -175,8 +169,9 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
                             const int i = ih - u;
                             const uint32_t bit = (i < 32 ? mlo : mhi) & (1u << (i & 31));
                             const float ab = bit ? av : 0.f;
-                            At[i * LD + tid] = ab;  // the source of token i was fetched a block ahead
-                            av = HAS_RET ? __builtin_fmaf(rb[blk & 1][u], ab, sb[blk & 1][u]) : ab + sb[blk & 1][u];
+                            At[i * LD + tid] = ab;
+                            const float src = __builtin_fmaf(-cb[blk & 1][u], sb[blk & 1][u], lb[blk & 1][u]);
+                            av = HAS_RET ? __builtin_fmaf(rb[blk & 1][u], ab, src) : ab + src;
                         }
                     }
                 }
@@ -188,7 +183,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
                 const int i = lane, q0 = wave * KQ;
                 float sp = 0.f;
 #pragma unroll 8
-                for (int c = 0; c < KQ; ++c) sp = __builtin_fmaf(ss[i * LD + q0 + c], At[i * LD + q0 + c], sp);
+                for (int c = 0; c < KQ; ++c) sp = __builtin_fmaf(SL[i * (LD2 / 2) + q0 + c].x, At[i * LD + q0 + c], sp);
                 part[wave * C + i] = sp;
             }
             __syncthreads();
@@ -216,11 +211,12 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         __syncthreads();
         OSDN_TICK(4)
     }
-#ifdef OSDN_DIAG
-    if (tid == 0 && blockIdx.x == 0)
-        for (int j = 0; j < 6; ++j) a.a_ckpt[j] = (float)tph[j];
-#endif
     if (tid < K) a.dd_in[bh * K + tid] = ga[tid];
+#ifdef OSDN_DIAG
+    __syncthreads();
+    if (tid == 0 && blockIdx.x == 0)
+        for (int j = 0; j < 6; ++j) a.dd_in[j] = (float)tph[j];
+#endif
 }
 
 // ---------------------------------------------------------------- precond_post ----
