@@ -51,7 +51,11 @@ def kernel_models(cfg, es):
     m = {}
     # phase 1: read k, beta; write k~ ; sequential, bandwidth/latency bound
     m["precond_fwd"] = ("hbm", th * (2 * K * es + g))
-    m["precond_bwd"] = ("hbm", th * (K * es + 2 * K * 4 + K * es + 3 * g))
+    # phase 1 backward: masks (read k, write 8 B per chunk and coordinate), the sigma chain
+    # (read k and dk~), the per-chunk outputs (read k, dk~, dk_read; write dk, dbeta, dr)
+    m["precond_mask"] = ("hbm", th * (K * es + g) + nch * K * 8)
+    m["precond_chain"] = ("hbm", th * (K * es + K * 4 + 2 * g) + nch * K * (8 + 4))
+    m["precond_post"] = ("hbm", th * (K * es + 2 * K * 4 + K * es + 6 * g) + nch * K * 8)
     # chunk_prep: read k, k~, v, beta, g ; write T, W, U
     m["chunk_prep"] = ("hbm", th * (2 * K * es + V * es + 2 * g + C * es + K * es + V * es))
     # state_fwd: read W, k~, U ; write E^T, S checkpoints ; 2 KV-class GEMMs
@@ -148,7 +152,10 @@ def main():
     torch.cuda.synchronize()
     prof = ob.osdn_profile_read()
     ob.osdn_profile_enable(False)
-    per_kernel = {k: (ms / max(n, 1)) for k, (ms, n) in prof.items() if n > 0}
+    # a kernel may be launched once per segment of the sequence: durations and work are
+    # summed over the launches of one step (= launch-weighted average rate)
+    per_kernel = {k: ms / args.steps for k, (ms, n) in prof.items() if n > 0}
+    launches = {k: n // args.steps for k, (ms, n) in prof.items() if n > 0}
     dominant = max(per_kernel, key=per_kernel.get)
     models, flops = kernel_models(cfg, es)
     bound, nbytes = models[dominant]
@@ -166,6 +173,7 @@ def main():
     roof["kernel"] = dominant
     roof["kernel_ms"] = per_kernel[dominant]
     roof["per_kernel_ms"] = {k: round(v, 4) for k, v in per_kernel.items()}
+    roof["launches_per_step"] = launches[dominant]
 
     # whole-path algorithmic flops (MFMA only) per token-head, for the %-of-peak figure
     K, V, C = cfg.K, cfg.V, 64

@@ -4,6 +4,9 @@
 #include "osdn_kernels.h"
 
 #include <cmath>
+#include <cstdlib>
+#include <map>
+#include <mutex>
 #include <vector>
 
 namespace {
@@ -113,6 +116,59 @@ ChunkArgs chunk_args(const osdn_params *p, const Layout &L, char *ws) {
     return c;
 }
 
+
+// ---- pipelining of the two phases --------------------------------------------------------
+// Phase 1 (the preconditioner chains, one workgroup per (batch, head)) leaves most of the chip
+// idle, and phase 2 only needs the k~ of the chunks it is working on.  With more than one
+// segment the sequence is cut into ranges of chunks: phase 1 runs on a side stream, segment by
+// segment, and phase 2 follows one segment behind on the caller's stream (in the backward
+// pass the other way round, right to left).  The side stream is forked from and joined back
+// into the caller's stream with events, so to the caller the call still behaves as work
+// enqueued on its stream.  One side stream and one set of events per device, created on first
+// use and kept; calls are serialised by a mutex while they enqueue.
+constexpr int MAX_SEGMENTS = 16;
+struct Pipeline {
+    hipStream_t side = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, a[MAX_SEGMENTS] = {};
+    bool ok = false;
+};
+std::mutex g_pipe_mu;
+std::map<int, Pipeline> g_pipes;
+
+Pipeline *pipeline_for_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    auto it = g_pipes.find(dev);
+    if (it == g_pipes.end()) {
+        Pipeline pl;
+        bool ok = hipStreamCreateWithFlags(&pl.side, hipStreamNonBlocking) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&pl.fork, hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&pl.join, hipEventDisableTiming) == hipSuccess;
+        for (int i = 0; ok && i < MAX_SEGMENTS; ++i)
+            ok = hipEventCreateWithFlags(&pl.a[i], hipEventDisableTiming) == hipSuccess;
+        pl.ok = ok;
+        it = g_pipes.emplace(dev, pl).first;
+    }
+    return it->second.ok ? &it->second : nullptr;
+}
+
+// number of segments for a sequence of N chunks: about 16 chunks each, between two (any
+// sequence of at least two chunks, so that short sequences take the same path) and four:
+// more segments buy little overlap and cost launches and cross-stream waits
+// (OSDN_SEGMENTS in the environment overrides it; 1 = no pipelining)
+int segment_count(int N) {
+    static const int forced = [] { const char *e = std::getenv("OSDN_SEGMENTS"); return e ? std::atoi(e) : 0; }();
+    int S = forced > 0 ? forced : N / 16;
+    if (forced <= 0 && S > 4) S = 4;
+    if (forced <= 0 && S < 2 && N >= 2) S = 2;
+    if (S > MAX_SEGMENTS) S = MAX_SEGMENTS;
+    if (S > N) S = N;
+    return S < 1 ? 1 : S;
+}
+inline int seg_begin(int N, int S, int s) { return (int)((long long)N * s / S); }
+
+#define OSDN_HIP_OK(x) do { if ((x) != hipSuccess) return OSDN_ERR_LAUNCH; } while (0)
+
 }  // namespace
 
 extern "C" {
@@ -146,6 +202,7 @@ int osdn_precond_update(const osdn_params *p, const void *k, const float *beta,
     PrecondArgs a = precond_args(p);
     a.k = k; a.beta = beta; a.retention = retention; a.d_in = d_in;
     a.k_tilde = k_tilde; a.d_out = d_out; a.d_ckpt = d_ckpt; a.tok_scalars = nullptr;
+    a.n0 = 0; a.n1 = (p->T + C - 1) / C;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = p->io_dtype == OSDN_BF16;
     if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(a, bf, st); }) != 0) return OSDN_ERR_SHAPE;
@@ -167,17 +224,52 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     const bool bf = p->io_dtype == OSDN_BF16;
 
     PrecondArgs pa = precond_args(p);
-    pa.k = k; pa.beta = beta; pa.retention = retention; pa.d_in = d_in;
+    pa.k = k; pa.beta = beta; pa.retention = retention;
     pa.k_tilde = ws + L.kt; pa.d_out = d_out; pa.d_ckpt = reinterpret_cast<float *>(ws + L.d_ckpt);
     pa.tok_scalars = reinterpret_cast<float *>(ws + L.tok_scalars);
-    if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(pa, bf, st); }) != 0) return OSDN_ERR_SHAPE;
-
     ChunkArgs c = chunk_args(p, L, ws);
-    c.q = q; c.k = k; c.v = v; c.beta = beta; c.log_alpha = log_alpha; c.S_in = S_in;
+    c.q = q; c.k = k; c.v = v; c.beta = beta; c.log_alpha = log_alpha;
     c.o = o; c.S_out = S_out;
-    if (timed(KID_CHUNK_PREP, st, [&] { return launch_chunk_prep(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
-    if (timed(KID_STATE_FWD, st, [&] { return launch_state_fwd(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
-    if (timed(KID_OUTPUT_FWD, st, [&] { return launch_output_fwd(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+
+    const int N = p->T / C;
+    int S = segment_count(N);
+    std::lock_guard<std::mutex> lock(g_pipe_mu);
+    Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
+    if (!pl) S = 1;
+    auto seg_range = [&](int sidx, int &n0, int &n1) { n0 = seg_begin(N, S, sidx); n1 = seg_begin(N, S, sidx + 1); };
+    auto precond = [&](int sidx, hipStream_t s1) {
+        seg_range(sidx, pa.n0, pa.n1);
+        pa.d_in = sidx == 0 ? d_in : d_out;          // d is carried in d_out
+        return timed(KID_PRECOND_FWD, s1, [&] { return launch_precond_fwd(pa, bf, s1); });
+    };
+    auto phase2 = [&](int kid, int sidx) {
+        seg_range(sidx, c.n0, c.n1);
+        c.S_in = sidx == 0 ? S_in : S_out;           // S is carried in S_out
+        return timed(kid, st, [&] {
+            return kid == KID_CHUNK_PREP ? launch_chunk_prep(c, bf, st)
+                 : kid == KID_STATE_FWD ? launch_state_fwd(c, bf, st) : launch_output_fwd(c, bf, st);
+        });
+    };
+    if (!pl) {
+        if (precond(0, st) != 0 || phase2(KID_CHUNK_PREP, 0) != 0 || phase2(KID_STATE_FWD, 0) != 0 ||
+            phase2(KID_OUTPUT_FWD, 0) != 0)
+            return OSDN_ERR_SHAPE;
+        return launch_status();
+    }
+    // side: phase 1, segment after segment          (a[s]: phase 1 of segment s done)
+    // main: phase 2 of segment s once a[s] has fired
+    hipStream_t s1 = pl->side;
+    OSDN_HIP_OK(hipEventRecord(pl->fork, st));
+    OSDN_HIP_OK(hipStreamWaitEvent(s1, pl->fork, 0));
+    for (int s = 0; s < S; ++s) {
+        if (precond(s, s1) != 0) return OSDN_ERR_SHAPE;
+        OSDN_HIP_OK(hipEventRecord(pl->a[s], s1));
+    }
+    for (int s = 0; s < S; ++s) {
+        OSDN_HIP_OK(hipStreamWaitEvent(st, pl->a[s], 0));
+        if (phase2(KID_CHUNK_PREP, s) != 0 || phase2(KID_STATE_FWD, s) != 0 || phase2(KID_OUTPUT_FWD, s) != 0)
+            return OSDN_ERR_SHAPE;
+    }
     return launch_status();
 }
 
@@ -207,10 +299,6 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     c.dk_read = reinterpret_cast<float *>(ws + L.dk_read);
     c.dkt = reinterpret_cast<float *>(ws + L.dkt);
     c.dbeta = dbeta; c.dlog_alpha = log_alpha ? dlog_alpha : nullptr;
-    if (timed(KID_BWD_LOCAL, st, [&] { return launch_bwd_local(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
-    if (timed(KID_BWD_CHAIN, st, [&] { return launch_bwd_chain(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
-    if (timed(KID_BWD_POST, st, [&] { return launch_bwd_post(c, bf, st); }) != 0) return OSDN_ERR_SHAPE;
-
     PrecondBwdArgs pb{};
     pb.B = p->B; pb.T = p->T; pb.H = p->H; pb.K = p->K;
     pb.eta = p->eta; pb.d_min = p->d_min; pb.d_max = p->d_max; pb.eps = p->eps;
@@ -220,12 +308,51 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     pb.tok_scalars = reinterpret_cast<float *>(ws + L.tok_scalars);
     pb.masks = reinterpret_cast<uint2 *>(ws + L.masks);
     pb.a_ckpt = reinterpret_cast<float *>(ws + L.a_ckpt);
-    pb.dkt = c.dkt; pb.dk_read = c.dk_read; pb.dd_out = dd_out;
+    pb.dkt = c.dkt; pb.dk_read = c.dk_read;
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
-    if (pb.d_min <= pb.d_max &&
-        timed(KID_PRECOND_MASK, st, [&] { return launch_precond_mask(pb, bf, st); }) != 0) return OSDN_ERR_SHAPE;
-    if (timed(KID_PRECOND_CHAIN, st, [&] { return launch_precond_chain(pb, bf, st); }) != 0) return OSDN_ERR_SHAPE;
-    if (timed(KID_PRECOND_POST, st, [&] { return launch_precond_post(pb, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+
+    const int N = p->T / C;
+    int S = segment_count(N);
+    std::lock_guard<std::mutex> lock(g_pipe_mu);
+    Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
+    if (!pl) S = 1;
+    auto seg_range = [&](int sidx, int &n0, int &n1) { n0 = seg_begin(N, S, sidx); n1 = seg_begin(N, S, sidx + 1); };
+    auto phase2 = [&](int kid, int sidx) {
+        seg_range(sidx, c.n0, c.n1);
+        c.dS_out = sidx == S - 1 ? dS_out : dS_in;   // dS is carried in dS_in
+        return timed(kid, st, [&] {
+            return kid == KID_BWD_LOCAL ? launch_bwd_local(c, bf, st)
+                 : kid == KID_BWD_CHAIN ? launch_bwd_chain(c, bf, st) : launch_bwd_post(c, bf, st);
+        });
+    };
+    auto phase1 = [&](int sidx, hipStream_t s1) {
+        seg_range(sidx, pb.n0, pb.n1);
+        pb.dd_out = sidx == S - 1 ? dd_out : dd_in;  // the adjoint of d is carried in dd_in
+        if (pb.d_min <= pb.d_max &&
+            timed(KID_PRECOND_MASK, s1, [&] { return launch_precond_mask(pb, bf, s1); }) != 0) return -1;
+        if (timed(KID_PRECOND_CHAIN, s1, [&] { return launch_precond_chain(pb, bf, s1); }) != 0) return -1;
+        return timed(KID_PRECOND_POST, s1, [&] { return launch_precond_post(pb, bf, s1); });
+    };
+    if (!pl) {
+        if (phase2(KID_BWD_LOCAL, 0) != 0 || phase2(KID_BWD_CHAIN, 0) != 0 || phase2(KID_BWD_POST, 0) != 0 ||
+            phase1(0, st) != 0)
+            return OSDN_ERR_SHAPE;
+        return launch_status();
+    }
+    // main: phase 2, segments right to left          (a[s]: phase 2 of segment s done)
+    // side: phase 1 of segment s once a[s] has fired; joined back at the end
+    hipStream_t s1 = pl->side;
+    for (int s = S - 1; s >= 0; --s) {
+        if (phase2(KID_BWD_LOCAL, s) != 0 || phase2(KID_BWD_CHAIN, s) != 0 || phase2(KID_BWD_POST, s) != 0)
+            return OSDN_ERR_SHAPE;
+        OSDN_HIP_OK(hipEventRecord(pl->a[s], st));
+    }
+    for (int s = S - 1; s >= 0; --s) {
+        OSDN_HIP_OK(hipStreamWaitEvent(s1, pl->a[s], 0));
+        if (phase1(s, s1) != 0) return OSDN_ERR_SHAPE;
+    }
+    OSDN_HIP_OK(hipEventRecord(pl->join, s1));
+    OSDN_HIP_OK(hipStreamWaitEvent(st, pl->join, 0));
     return launch_status();
 }
 

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
     __shared__ __attribute__((aligned(16))) T Os[C * LDC];
     __shared__ float Gs[C];
 
-    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
@@ -207,21 +207,21 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     }
     if (loader) {
         if (NB == 2) {
-            if (lgrp == ((a.N - 1) & 1)) {
-                OSDN_BC_LOAD(a.N - 1)
-                OSDN_BC_STORE((a.N - 1) & 1)
-                OSDN_BC_LOAD(max(a.N - 3, 0))
+            if (lgrp == ((a.n1 - 1) & 1)) {
+                OSDN_BC_LOAD(a.n1 - 1)
+                OSDN_BC_STORE((a.n1 - 1) & 1)
+                OSDN_BC_LOAD(max(a.n1 - 3, a.n0))
             } else {
-                OSDN_BC_LOAD(max(a.N - 2, 0))
+                OSDN_BC_LOAD(max(a.n1 - 2, a.n0))
             }
         } else {
-            OSDN_BC_LOAD(a.N - 1)
+            OSDN_BC_LOAD(a.n1 - 1)
             OSDN_BC_STORE(0)
-            OSDN_BC_LOAD(max(a.N - 2, 0))
+            OSDN_BC_LOAD(max(a.n1 - 2, a.n0))
         }
     }
 
-    for (int n = a.N - 1; n >= 0; --n) {
+    for (int n = a.n1 - 1; n >= a.n0; --n) {
         const int buf = NB == 2 ? (n & 1) : 0;
         const size_t bhn = bh * a.N + n;
         // ---- phase A (compute): dS', rounded, into LDS ----
@@ -236,9 +236,9 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         if (loader) {
             if (NB == 2) {
                 if (lgrp == ((n + 1) & 1)) {                        // this group's chunk (n - 1) comes next
-                    if (n > 0) {
+                    if (n > a.n0) {
                         OSDN_BC_STORE((n - 1) & 1)
-                        OSDN_BC_LOAD(max(n - 3, 0))                 // (past the start: a harmless reload)
+                        OSDN_BC_LOAD(max(n - 3, a.n0))              // (past the start: a harmless reload)
                     }
                 } else {
                     store_tile_global(static_cast<T *>(a.dS_ckpt) + (bhn * a.V + vs) * K, (size_t)K, dSb, LDK, VS, K, lti, LTN);
@@ -282,9 +282,9 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         }
         if (NB == 1) {
             __syncthreads();
-            if (loader && n > 0) {
+            if (loader && n > a.n0) {
                 OSDN_BC_STORE(0)
-                OSDN_BC_LOAD(max(n - 2, 0))
+                OSDN_BC_LOAD(max(n - 2, a.n0))
             }
         }
     }
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     float *pq = reinterpret_cast<float *>(cPs + C * LDC);        // [PW_][64] x 3
     T *cAs = Tt;                        // [64][LDC]
 
-    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
@@ -646,7 +646,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
 // -------------------------------------------------------------- launchers ----
 template <typename T>
 static int launch_local_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.N, a.H, a.B), block(NT);
+    dim3 grid(a.n1 - a.n0, a.H, a.B), block(NT);
     if (a.K == 64) hipLaunchKernelGGL((bwd_local_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((bwd_local_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;
@@ -668,7 +668,7 @@ int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T>
 static int launch_post_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.N, a.H, a.B), block(PT_);
+    dim3 grid(a.n1 - a.n0, a.H, a.B), block(PT_);
     if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;

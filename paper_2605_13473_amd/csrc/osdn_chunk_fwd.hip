@@ -34,7 +34,7 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     T *stage = reinterpret_cast<T *>(scratch);                  // [K][LDC] / [64][LDC], once T is final
     __shared__ float Gs[C], Bs[C];
 
-    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;      // (b, first token, h)
@@ -275,17 +275,17 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     }
     if (loader) {
         if (NB == 2) {
-            if (lgrp == 0) {
-                OSDN_SF_LOAD(0)
-                OSDN_SF_STORE(0)
-                OSDN_SF_LOAD(min(2, a.N - 1))
+            if (lgrp == (a.n0 & 1)) {
+                OSDN_SF_LOAD(a.n0)
+                OSDN_SF_STORE(a.n0 & 1)
+                OSDN_SF_LOAD(min(a.n0 + 2, a.n1 - 1))
             } else {
-                OSDN_SF_LOAD(min(1, a.N - 1))
+                OSDN_SF_LOAD(min(a.n0 + 1, a.n1 - 1))
             }
         } else {
-            OSDN_SF_LOAD(0)
+            OSDN_SF_LOAD(a.n0)
             OSDN_SF_STORE(0)
-            OSDN_SF_LOAD(min(1, a.N - 1))
+            OSDN_SF_LOAD(min(a.n0 + 1, a.n1 - 1))
         }
     }
 
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
 #else
 #define OSDN_TICK(j)
 #endif
-    for (int n = 0; n < a.N; ++n) {
+    for (int n = a.n0; n < a.n1; ++n) {
         const int buf = NB == 2 ? (n & 1) : 0;
         const size_t bhn = bh * a.N + n;
         // ---- phase A (compute): S, rounded, into LDS ----
@@ -312,10 +312,10 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
         if (loader) {
             if (NB == 2) {
                 if (lgrp == ((n + 1) & 1)) {                        // this group's chunk comes next
-                    if (n + 1 < a.N) {
+                    if (n + 1 < a.n1) {
                         OSDN_SF_STORE((n + 1) & 1)                  // free since barrier 1
                         OSDN_TICK(5)
-                        OSDN_SF_LOAD(min(n + 3, a.N - 1))           // (past the end: a harmless reload)
+                        OSDN_SF_LOAD(min(n + 3, a.n1 - 1))          // (past the end: a harmless reload)
                         OSDN_TICK(6)
                     }
                 } else if (a.S_ckpt) {
@@ -363,9 +363,9 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
         }
         if (NB == 1) {                                              // single buffer: refill it now
             __syncthreads();
-            if (loader && n + 1 < a.N) {
+            if (loader && n + 1 < a.n1) {
                 OSDN_SF_STORE(0)
-                OSDN_SF_LOAD(min(n + 2, a.N - 1))
+                OSDN_SF_LOAD(min(n + 2, a.n1 - 1))
             }
         }
         OSDN_TICK(4)
@@ -398,7 +398,7 @@ __global__ __launch_bounds__(NT) void output_fwd_kernel(ChunkArgs a) {
     __shared__ __attribute__((aligned(16))) T Ets[C * LDC];     // 64 rows of E^T
     __shared__ float Gs[C];
 
-    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(NT) void output_fwd_kernel(ChunkArgs a) {
 // -------------------------------------------------------------- launchers ----
 template <typename T>
 static int launch_prep_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.N, a.H, a.B), block(NT);
+    dim3 grid(a.n1 - a.n0, a.H, a.B), block(NT);
     if (a.K == 64) hipLaunchKernelGGL((chunk_prep_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((chunk_prep_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;
@@ -472,7 +472,7 @@ int launch_state_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T>
 static int launch_output_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.N, a.H, a.B), block(NT);
+    dim3 grid(a.n1 - a.n0, a.H, a.B), block(NT);
     if (a.K == 64) hipLaunchKernelGGL((output_fwd_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((output_fwd_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;

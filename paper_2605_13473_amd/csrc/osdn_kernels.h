@@ -4,8 +4,13 @@
 
 namespace osdn {
 
+// Every kernel works on the chunks [n0, n1) of the sequence (all of them in one launch, or a
+// segment when the two phases are pipelined against each other); what a sequential kernel
+// carries across a segment boundary (d, S, dS, the adjoint of d) goes through the same
+// buffers that hold it at the ends of the sequence.
 struct PrecondArgs {
     int B, T, H, K;
+    int n0, n1;
     float eta, d_min, d_max, eps;
     int beta_aware;
     const void *k;            // [B,T,H,K] io
@@ -20,6 +25,7 @@ struct PrecondArgs {
 
 struct PrecondBwdArgs {
     int B, T, H, K;
+    int n0, n1;
     float eta, d_min, d_max, eps;
     int beta_aware;
     const void *k;
@@ -41,6 +47,7 @@ struct PrecondBwdArgs {
 // in [B,H,N,rows,cols] order (one contiguous tile per chunk and head).
 struct ChunkArgs {
     int B, T, H, K, V, N;
+    int n0, n1;
     float scale;
     // caller tensors
     const void *q, *k, *v;            // [B,T,H,*] io

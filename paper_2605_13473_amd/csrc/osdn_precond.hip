@@ -68,7 +68,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
             if (HAS_RET) retreg = a.retention[th];                                               \
         }                                                                                        \
     }
-    OSDN_P1_LOAD(0)
+    OSDN_P1_LOAD(a.n0)
 
 #ifdef OSDN_DIAG
     long long tph[6] = {0, 0, 0, 0, 0, 0}, tlast = clock64();
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
 #else
 #define OSDN_TICK(j)
 #endif
-    for (int n = 0; n < N; ++n) {
+    for (int n = a.n0; n < a.n1; ++n) {
         const int t0 = n * C;
         const int nvalid = min(C, a.T - t0);
         // ---- registers -> LDS (rows past the end of the sequence become no-op tokens) ----
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
         const float bet = betreg, ret = retreg;
         __syncthreads();
         OSDN_TICK(0)
-        if (n + 1 < N) OSDN_P1_LOAD(n + 1)
+        if (n + 1 < a.n1) OSDN_P1_LOAD(n + 1)
         if (a.d_ckpt && tid < K) a.d_ckpt[(bh * N + n) * K + tid] = d0[tid];
         // ---- per token: n_raw = sum s, and the first guess p = <d_0, s> ----
         {

@@ -23,7 +23,7 @@ template <typename T, int K, bool HAS_RET>
 __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
     __shared__ __attribute__((aligned(16))) float steps[C];
     __shared__ __attribute__((aligned(16))) float rs[C];
-    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int N = a.T / C;
     const size_t bh = (size_t)b * a.H + h;
     const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         }                                                                                        \
         if (project && tid < K) mreg = a.masks[(bh * N + (n_)) * K + tid];                       \
     }
-    OSDN_P1_BLOAD(N - 1)
+    OSDN_P1_BLOAD(a.n1 - 1)
 
 #ifdef OSDN_DIAG
     long long tph[6] = {0, 0, 0, 0, 0, 0}, tlast = clock64();
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 #else
 #define OSDN_TICK(j)
 #endif
-    for (int n = N - 1; n >= 0; --n) {
+    for (int n = a.n1 - 1; n >= a.n0; --n) {
         const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
         // ---- registers -> LDS ----
 #pragma unroll
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         if (tid < K) a.a_ckpt[(bh * N + n) * K + tid] = ga[tid];
         __syncthreads();
         OSDN_TICK(0)
-        if (n > 0) OSDN_P1_BLOAD(n - 1)         // next chunk: in flight during the sweeps
+        if (n > a.n0) OSDN_P1_BLOAD(n - 1)      // next chunk: in flight during the sweeps
         const bool all_in = __all(mlo == 0xffffffffu && mhi == 0xffffffffu);    // per wave
         // ---- sweeps for sigma_i = <s_i, abar_i> ----
         float dprev = 0.f;
@@ -234,7 +234,7 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     __shared__ __attribute__((aligned(16))) float gp_s[C];
     __shared__ __attribute__((aligned(16))) float gn_s[C];
     __shared__ float prod[HAS_RET ? C * LD : 1];    // abar_i d_i per coordinate, for dL/dr
-    const int n = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int N = a.T / C;
     const size_t bh = (size_t)b * a.H + h;
     const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
 // -------------------------------------------------------------------- launchers ----
 template <typename T, bool HAS_RET>
 static int launch_precond_bwd_t(const PrecondBwdArgs &a, int which, hipStream_t st) {
-    const dim3 per_chunk(a.T / C, a.H, a.B);
+    const dim3 per_chunk(a.n1 - a.n0, a.H, a.B);
     if (a.K == 64) {
         if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 64, HAS_RET>), per_chunk, dim3(64), 0, st, a);
         else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 64, HAS_RET>), dim3(a.B * a.H), dim3(P1T), 0, st, a);
