@@ -53,46 +53,69 @@ __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
 }
 
 // --------------------------------------------------------------- precond_chain ----
+// The adjoint recurrence is linear in a (the masks are data of the forward pass), so a chunk
+// is cut into NSEG = 512 / K runs of TS tokens and every thread owns one coordinate of one
+// run, all in registers: it runs the recurrence over its TS tokens from a zero right-hand
+// value, keeping abar_i = L_i + P_i * carry in the two parts L_i, P_i; the runs are chained
+// through LDS (one fma per run); the TS products s_i abar_i of a thread are folded over the
+// lanes of the wavefront (each lane ends with the sum of one token over a group of lanes) and
+// the sigma of a token is the sum of K / TS such partials.  No tile of the chunk is ever in LDS.
+template <int TS>
+__device__ __forceinline__ float lane_fold(const float (&v)[TS], int lane) {
+    static_assert(TS == 16 || TS == 8, "run length");
+    // after the step with lane bit b, a lane keeps the values whose index has bit b equal to
+    // its own and adds the partner lane's copy of them: the count halves, the group doubles
+    float w[TS / 2], x[TS / 4], y[TS / 8];
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4, b3 = lane & 8;
+#pragma unroll
+    for (int m = 0; m < TS / 2; ++m)
+        w[m] = (b0 ? v[2 * m + 1] : v[2 * m]) + dpp_f32<0xB1>(b0 ? v[2 * m] : v[2 * m + 1]);     // lane ^ 1
+#pragma unroll
+    for (int m = 0; m < TS / 4; ++m)
+        x[m] = (b1 ? w[2 * m + 1] : w[2 * m]) + dpp_f32<0x4E>(b1 ? w[2 * m] : w[2 * m + 1]);     // lane ^ 2
+#pragma unroll
+    for (int m = 0; m < TS / 8; ++m)
+        y[m] = (b2 ? x[2 * m + 1] : x[2 * m]) + __shfl_xor(b2 ? x[2 * m] : x[2 * m + 1], 4, 64);
+    if (TS == 8) return y[0];                  // token lane % 8, summed over its 8 lanes
+    return (b3 ? y[TS / 8 - 1] : y[0]) + __shfl_xor(b3 ? y[0] : y[TS / 8 - 1], 8, 64);   // token lane % 16, over 16 lanes
+}
+
 template <typename T, int K, bool HAS_RET>
 __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
-    constexpr int LD = K + 1;
-    constexpr int LD2 = 2 * K + 2;                // row stride of the interleaved (s, lambda) tile, in floats
-    constexpr int NF = C * K / 2 / P1T;           // column pairs per thread for a [64 x K] tile
-    constexpr int KQ = K / P1W;
-    // (s, lambda) = (k^2, k . dL/dk~) of the chunk, interleaved so that one 8-byte read brings both
-    __shared__ __attribute__((aligned(16))) float2 SL[C * (LD2 / 2)];
-    __shared__ float At[C * LD];                 // masked adjoint abar_i
-    __shared__ float ga[K], ganew[K];            // adjoint of d at the right / left end of the chunk
+    constexpr int NSEG = P1T / K;                 // runs per chunk
+    constexpr int TS = C / NSEG;                  // tokens per run
+    constexpr int WPS = K / 64;                   // wavefronts per run
+    constexpr int NPART = K / TS;                 // partial sums per token
+    __shared__ float ga[K];                      // adjoint of d at the right end of the chunk
+    __shared__ float segL[NSEG * K], segP[NSEG * K];
     __shared__ float cas[C], sig[C];
     __shared__ __attribute__((aligned(16))) float rs[C];
     __shared__ __attribute__((aligned(16))) float casig[C];
-    __shared__ float part[P1W * C];
+    __shared__ float part[P1W * 64];
     __shared__ int done;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c = tid % K, sg = tid / K;          // coordinate and run of this thread
     const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
     const size_t bh = (size_t)b * a.H + h;
-    const T *k = static_cast<const T *>(a.k);
     const bool project = a.d_min <= a.d_max;
     const int N = a.T / C;
+    const uint32_t kstride = (uint32_t)a.H * K;   // elements between consecutive tokens
 
     if (tid < K) ga[tid] = a.dd_out ? a.dd_out[bh * K + tid] : 0.f;
 
-    // a thread stages pairs of columns: consecutive lanes -> consecutive pairs of one row
-    uint32_t kreg1[NF];     // bf16: 2 elements = 4 bytes ; fp32 uses kreg2
-    u32x2 kreg2[NF];
-    float2 greg[NF];
+    T kreg[TS];
+    float greg[TS];
     float nrawreg = 1.f, betreg = 0.f, retreg = 1.f;
     uint2 mreg = make_uint2(0xffffffffu, 0xffffffffu);
 #define OSDN_P1_BLOAD(n_)                                                                        \
     {                                                                                            \
         const size_t tokc_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                     \
-        _Pragma("unroll") for (int m = 0; m < NF; ++m) {                                         \
-            const int i = tid + m * P1T, r = i / (K / 2), c = (i % (K / 2)) * 2;                  \
-            const size_t off = (tokc_ + (size_t)r * a.H) * K + c;                                \
-            if (sizeof(T) == 2) kreg1[m] = *reinterpret_cast<const uint32_t *>(k + off);         \
-            else kreg2[m] = *reinterpret_cast<const u32x2 *>(k + off);                           \
-            greg[m] = *reinterpret_cast<const float2 *>(a.dkt + off);                            \
+        const T *kp_ = static_cast<const T *>(a.k) + tokc_ * K;                                  \
+        const float *gp_ = a.dkt + tokc_ * K;                                                    \
+        _Pragma("unroll") for (int u = 0; u < TS; ++u) {                                         \
+            const uint32_t o_ = (uint32_t)(sg * TS + u) * kstride + (uint32_t)c;                 \
+            kreg[u] = kp_[o_]; greg[u] = gp_[o_];                                                \
         }                                                                                        \
         if (tid < C) {                                                                           \
             const size_t th = tokc_ + (size_t)tid * a.H;                                         \
@@ -100,7 +123,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
             betreg = a.beta[th];                                                                 \
             if (HAS_RET) retreg = a.retention[th];                                               \
         }                                                                                        \
-        if (project && tid < K) mreg = a.masks[(bh * N + (n_)) * K + tid];                       \
+        if (project) mreg = a.masks[(bh * N + (n_)) * K + c];                                    \
     }
     OSDN_P1_BLOAD(a.n1 - 1)
 
@@ -112,102 +135,100 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 #endif
     for (int n = a.n1 - 1; n >= a.n0; --n) {
         const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
-        // ---- registers -> LDS ----
+        // ---- this thread's (s, lambda) = (k^2, k . dL/dk~) and mask bits ----
+        float sv[TS], lam[TS];
 #pragma unroll
-        for (int m = 0; m < NF; ++m) {
-            const int i = tid + m * P1T, r = i / (K / 2), c = (i % (K / 2)) * 2;
-            const u32x4 kv4 = sizeof(T) == 2 ? u32x4{kreg1[m], 0u, 0u, 0u} : u32x4{kreg2[m][0], kreg2[m][1], 0u, 0u};
-            const float k0 = vec_get<T>(kv4, 0), k1 = vec_get<T>(kv4, 1);
-            SL[r * (LD2 / 2) + c] = make_float2(k0 * k0, k0 * greg[m].x);
-            SL[r * (LD2 / 2) + c + 1] = make_float2(k1 * k1, k1 * greg[m].y);
+        for (int u = 0; u < TS; ++u) {
+            const float kv = to_f32(kreg[u]);
+            sv[u] = kv * kv;
+            lam[u] = kv * greg[u];
         }
+        const uint32_t mword = (sg * TS) < 32 ? mreg.x : mreg.y;
+        const uint32_t mbits = (mword >> ((sg * TS) & 31)) & ((1u << TS) - 1u);
         if (tid < C) {
             const float nn = fmaxf(nrawreg, a.eps);
             const float bp = a.beta_aware ? betreg : 1.f;
             rs[tid] = retreg; cas[tid] = a.eta * bp / nn * bp; sig[tid] = 0.f; casig[tid] = 0.f;
         }
-        const uint32_t mlo = mreg.x, mhi = mreg.y;
         if (tid < K) a.a_ckpt[(bh * N + n) * K + tid] = ga[tid];
         __syncthreads();
         OSDN_TICK(0)
         if (n > a.n0) OSDN_P1_BLOAD(n - 1)      // next chunk: in flight during the sweeps
-        const bool all_in = __all(mlo == 0xffffffffu && mhi == 0xffffffffu);    // per wave
+        // a wavefront whose coordinates never touched the box in this run, without retention:
+        // P stays 1 and L is a plain running sum
+        const bool plain = !HAS_RET && __all(mbits == ((1u << TS) - 1u));
+        float rv[TS];
+        if (HAS_RET) {
+#pragma unroll
+            for (int u = 0; u < TS; ++u) rv[u] = rs[sg * TS + u];
+        }
         // ---- sweeps for sigma_i = <s_i, abar_i> ----
-        float dprev = 0.f;
+        float dprev = 0.f, a_left = 0.f;
         for (int sweep = 0; sweep < P1_MAX_SWEEPS; ++sweep) {
-            // the source term  lambda_i - ca_i sigma_i s_i  is formed inside the recurrence
-            if (tid < K) {
-                float av = ga[tid];
-                float sb[2][PB], lb[2][PB], cb[2][PB], rb[2][PB];
-#define OSDN_VLOAD(buf, ih_)                                                                     \
-    _Pragma("unroll") for (int u = 0; u < PB; ++u) {                                             \
-        const float2 sl_ = SL[((ih_) - u) * (LD2 / 2) + tid];                                    \
-        sb[buf][u] = sl_.x; lb[buf][u] = sl_.y;                                                  \
-        cb[buf][u] = casig[(ih_) - u];                                                           \
-        if (HAS_RET) rb[buf][u] = rs[(ih_) - u];                                                 \
-    }
-                OSDN_VLOAD(0, C - 1)
-                if (all_in) {       // no coordinate of this wave touched the box in this chunk
+            float abL[TS], abP[TS];
+            float loc = 0.f, P = 1.f;
+            if (plain) {
 #pragma unroll
-                    for (int blk = 0; blk < C / PB; ++blk) {
-                        const int ih = C - 1 - blk * PB;
-                        if (blk + 1 < C / PB) OSDN_VLOAD((blk + 1) & 1, ih - PB)
-#pragma unroll
-                        for (int u = 0; u < PB; ++u) {
-                            At[(ih - u) * LD + tid] = av;
-                            const float src = __builtin_fmaf(-cb[blk & 1][u], sb[blk & 1][u], lb[blk & 1][u]);
-                            av = HAS_RET ? __builtin_fmaf(rb[blk & 1][u], av, src) : av + src;
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int blk = 0; blk < C / PB; ++blk) {
-                        const int ih = C - 1 - blk * PB;
-                        if (blk + 1 < C / PB) OSDN_VLOAD((blk + 1) & 1, ih - PB)
-#pragma unroll
-                        for (int u = 0; u < PB; ++u) {
-                            const int i = ih - u;
-                            const uint32_t bit = (i < 32 ? mlo : mhi) & (1u << (i & 31));
-                            const float ab = bit ? av : 0.f;
-                            At[i * LD + tid] = ab;
-                            const float src = __builtin_fmaf(-cb[blk & 1][u], sb[blk & 1][u], lb[blk & 1][u]);
-                            av = HAS_RET ? __builtin_fmaf(rb[blk & 1][u], ab, src) : ab + src;
-                        }
-                    }
+                for (int u = TS - 1; u >= 0; --u) {
+                    abL[u] = loc;
+                    loc += __builtin_fmaf(-casig[sg * TS + u], sv[u], lam[u]);
                 }
-                ganew[tid] = av;
+            } else {
+#pragma unroll
+                for (int u = TS - 1; u >= 0; --u) {
+                    const bool in = (mbits >> u) & 1u;
+                    abL[u] = in ? loc : 0.f;
+                    abP[u] = in ? P : 0.f;
+                    const float src = __builtin_fmaf(-casig[sg * TS + u], sv[u], lam[u]);
+                    loc = HAS_RET ? __builtin_fmaf(rv[u], abL[u], src) : abL[u] + src;
+                    P = HAS_RET ? rv[u] * abP[u] : abP[u];
+                }
             }
+            segL[sg * K + c] = loc;
+            segP[sg * K + c] = P;
+            __syncthreads();
+            OSDN_TICK(1)
+            // value of a at the right end of this run: chain the runs to its right
+            float carry = ga[c];
+#pragma unroll
+            for (int s2 = NSEG - 1; s2 > 0; --s2)
+                if (s2 > sg) carry = __builtin_fmaf(segP[s2 * K + c], carry, segL[s2 * K + c]);
+            a_left = __builtin_fmaf(P, carry, loc);      // (meaningful in run 0: left end of the chunk)
+            float prod[TS];
+            if (plain) {
+#pragma unroll
+                for (int u = 0; u < TS; ++u) prod[u] = sv[u] * (abL[u] + carry);
+            } else {
+#pragma unroll
+                for (int u = 0; u < TS; ++u) prod[u] = sv[u] * __builtin_fmaf(abP[u], carry, abL[u]);
+            }
+            part[wave * 64 + lane] = lane_fold<TS>(prod, lane);
             __syncthreads();
             OSDN_TICK(2)
-            {
-                const int i = lane, q0 = wave * KQ;
-                float sp = 0.f;
-#pragma unroll 8
-                for (int c = 0; c < KQ; ++c) sp = __builtin_fmaf(SL[i * (LD2 / 2) + q0 + c].x, At[i * LD + q0 + c], sp);
-                part[wave * C + i] = sp;
-            }
-            __syncthreads();
             if (tid < C) {
-                const int i = tid;
-                const float sg = sumw(part, i);
-                const float mx = wave_max(fabsf(sg));
-                const float dcur = wave_max(fabsf(sg - sig[i]));
+                const int i = tid, w0 = (i / TS) * WPS, u = i % TS;
+                float sg_ = 0.f;
+#pragma unroll
+                for (int j = 0; j < NPART; ++j)     // fixed order: wavefronts of the run, lane groups
+                    sg_ += part[(w0 + j / (64 / TS)) * 64 + (j % (64 / TS)) * TS + u];
+                const float mx = wave_max(fabsf(sg_));
+                const float dcur = wave_max(fabsf(sg_ - sig[i]));
                 // converged, or (from the second pass on) the observed contraction ratio says
                 // that the next difference would be below the tolerance
                 const bool all_ok = dcur <= P1_TOL * mx ||
                                     (sweep >= 1 && dcur <= 0.1f * dprev && dcur * dcur <= P1_TOL * mx * dprev);
                 dprev = dcur;
-                sig[i] = sg;
-                casig[i] = cas[i] * sg;
+                sig[i] = sg_;
+                casig[i] = cas[i] * sg_;
                 if (tid == 0) done = all_ok ? 1 : 0;
             }
             __syncthreads();
             OSDN_TICK(3)
             if (done) break;
         }
-        // ---- accepted: sig generated ganew ----
+        // ---- accepted: sig generated a_left ----
         if (tid < C) a.tok_scalars[(tokc + (size_t)tid * a.H) * 4 + 3] = sig[tid];
-        if (tid < K) ga[tid] = ganew[tid];
+        if (sg == 0) ga[c] = a_left;
         __syncthreads();
         OSDN_TICK(4)
     }
