@@ -39,8 +39,7 @@ __device__ __forceinline__ float wave_max(float x) {      // x >= 0
     x = fmaxf(x, dpp_f32<0x143, 0xC>(x));
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
-// One workgroup = 16 wavefronts: the sequential loops run on K/64 of them, the parallel
-// phases (row dots, tile conversion, outputs) on all, four per SIMD, to hide LDS latency.
+// One workgroup = 8 wavefronts, two per SIMD.
 constexpr int P1T = 512, P1W = P1T / 64;
 // sum of the per-wave partials of row i (fixed order)
 __device__ __forceinline__ float sumw(const float *part, int i) {
@@ -48,6 +47,48 @@ __device__ __forceinline__ float sumw(const float *part, int i) {
 #pragma unroll
     for (int w = 0; w < P1W; ++w) s += part[w * C + i];
     return s;
+}
+
+// partner lane ^ 4 inside a row of 16 lanes: two DPP moves (row_shl:4 into lanes 0-3 and 8-11 of
+// every row, row_shr:4 into the others)
+__device__ __forceinline__ float lane_xor4(float x) {
+    const int xi = __builtin_bit_cast(int, x);
+    int t = __builtin_amdgcn_update_dpp(0, xi, 0x104, 0xF, 0x5, false);
+    t = __builtin_amdgcn_update_dpp(t, xi, 0x114, 0xF, 0xA, false);
+    return __builtin_bit_cast(float, t);
+}
+// Every lane holds TS values v[0..TS); returns to lane l the sum of v[l % TS] over the group of
+// TS lanes it belongs to (the 64 / TS partial sums per value are left to the caller).
+template <int TS>
+__device__ __forceinline__ float lane_fold(const float (&v)[TS], int lane) {
+    static_assert(TS == 16 || TS == 8, "run length");
+    // after the step with lane bit b, a lane keeps the values whose index has bit b equal to
+    // its own and adds the partner lane's copy of them: the count halves, the group doubles
+    float w[TS / 2], x[TS / 4], y[TS / 8];
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4, b3 = lane & 8;
+#pragma unroll
+    for (int m = 0; m < TS / 2; ++m)
+        w[m] = (b0 ? v[2 * m + 1] : v[2 * m]) + dpp_f32<0xB1>(b0 ? v[2 * m] : v[2 * m + 1]);     // lane ^ 1
+#pragma unroll
+    for (int m = 0; m < TS / 4; ++m)
+        x[m] = (b1 ? w[2 * m + 1] : w[2 * m]) + dpp_f32<0x4E>(b1 ? w[2 * m] : w[2 * m + 1]);     // lane ^ 2
+#pragma unroll
+    for (int m = 0; m < TS / 8; ++m)
+        y[m] = (b2 ? x[2 * m + 1] : x[2 * m]) + lane_xor4(b2 ? x[2 * m] : x[2 * m + 1]);         // lane ^ 4
+    if (TS == 8) return y[0];                  // value lane % 8, summed over its 8 lanes
+    return (b3 ? y[TS / 8 - 1] : y[0]) + dpp_f32<0x128>(b3 ? y[0] : y[TS / 8 - 1]);   // lane ^ 8 (row_ror:8)
+}
+// the same for 8 values, carried on to the sum over the whole wavefront: every lane gets the
+// total of v[lane % 8] (fixed order of additions)
+__device__ __forceinline__ float lane_fold8_all(const float (&v)[8], int lane) {
+    float y = lane_fold<8>(v, lane);
+    y += dpp_f32<0x128>(y);
+    y += __shfl_xor(y, 16, 64);
+    y += __shfl_xor(y, 32, 64);
+    return y;
+}
+__device__ __forceinline__ float lane_bcast(float x, int src_lane) {     // src_lane uniform
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), src_lane));
 }
 
 }  // namespace osdn

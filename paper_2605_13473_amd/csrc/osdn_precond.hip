@@ -1,72 +1,99 @@
 // Phase 1 of OSDN: the online preconditioner sweep (Algorithm 1, Eq. (dt_update) and its
-// retention form Eq. (dt_update_apf)), and its reverse sweep (Section 4.5).
+// retention form Eq. (dt_update_apf)).
 //
 // The recurrence  d_{t+1} = clip(r_t d_t + c_t s_t),  s_t = k_t (.) k_t,
 //                 c_t = eta b'(1 - b' p_t)/n_t,  p_t = <d_t, s_t>
 // couples the K coordinates only through the scalar p_t.  One workgroup owns one
-// (batch, head) chain and walks it in chunks of 64 tokens held in LDS.  Inside a chunk it
-// solves for the 64 scalars p by fixed-point sweeps: given p (first guess: <d_0, s_t>), the
-// recurrence separates into K independent scalar recurrences (one thread per coordinate,
-// 64 steps of fma + median-of-three, clip included); from the resulting trajectory the 64
-// inner products are recomputed in parallel; the sweep repeats until they reproduce
-// themselves.  Sweep m fixes at least the first m tokens exactly, so 64 sweeps always
-// suffice; because the coupling is O(eta) two do in practice (also when coordinates sit on a
-// face of the box, which the scalar recurrences handle by themselves).  No per-token
-// cross-lane reduction is left on the sequential path.  All arithmetic is fp32; k~ is
-// rounded once, from fp32 d * k.
+// (batch, head) chain and walks it in chunks of 64 tokens.  Inside a chunk it solves for the
+// 64 scalars p by fixed-point sweeps: given p (first guess: <d_0, s_t>) the recurrence
+// separates into K independent scalar recurrences; from the resulting trajectory the 64 inner
+// products are recomputed; the sweep repeats until they reproduce themselves.  Sweep m fixes
+// at least the first m tokens exactly, so 64 sweeps always suffice; because the coupling is
+// O(eta) two do in practice, also when coordinates sit on a face of the box.
 //
-// The reverse sweep has the same structure: with sigma_t = <s_t, abar_t> known, the adjoint
-// recurrence  abar_t = mask_t (.) a_{t+1},  a_t = k_t (.) dL/dk~_t + r_t abar_t - ca_t sigma_t s_t
-// separates per coordinate; sigma is found by the same kind of sweeps.
+// A sweep does not walk the 64 tokens one after the other.  The chunk is cut into 8 runs of
+// 8 tokens, one wavefront per run, a lane per coordinate (pair): everything a thread needs of
+// the chunk (its k, s, d) stays in registers.  One token maps d to clip(r d + c s), and maps
+// of that form compose to x -> clip3(A x + B, L, H) with
+//     A' = r A,  B' = r B + c s,  L' = clip(r L + c s),  H' = clip(r H + c s)      (r >= 0),
+// so a thread first composes the map of its run, the runs are chained through LDS (one
+// fma + median-of-three per run), and with its run's starting value known the thread replays
+// its 8 tokens.  The products s d are folded over the lanes of the wavefront and the p of a
+// token is the sum of 8 partials.  All arithmetic is fp32; k~ is rounded once, from fp32 d k.
 #include "osdn_precond.h"
+
+#include <cfloat>
 
 namespace osdn {
 
+constexpr int RUN = 8;                           // tokens per run; C / RUN runs = wavefronts
+
+// CPT adjacent elements of type T <-> floats, as one memory access
+template <typename T, int CPT> struct Pack;
+template <> struct Pack<bf16, 2> {
+    typedef uint32_t Raw;
+    static __device__ __forceinline__ void unpack(Raw w, float (&o)[2]) {
+        o[0] = __builtin_bit_cast(float, w << 16);
+        o[1] = __builtin_bit_cast(float, w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ Raw pack(const float (&v)[2]) {
+        const uint32_t lo = __builtin_bit_cast(unsigned short, (bf16)v[0]);
+        const uint32_t hi = __builtin_bit_cast(unsigned short, (bf16)v[1]);
+        return lo | (hi << 16);
+    }
+};
+template <> struct Pack<bf16, 1> {
+    typedef bf16 Raw;
+    static __device__ __forceinline__ void unpack(Raw w, float (&o)[1]) { o[0] = (float)w; }
+    static __device__ __forceinline__ Raw pack(const float (&v)[1]) { return (bf16)v[0]; }
+};
+template <> struct Pack<float, 2> {
+    typedef float2 Raw;
+    static __device__ __forceinline__ void unpack(Raw w, float (&o)[2]) { o[0] = w.x; o[1] = w.y; }
+    static __device__ __forceinline__ Raw pack(const float (&v)[2]) { return make_float2(v[0], v[1]); }
+};
+template <> struct Pack<float, 1> {
+    typedef float Raw;
+    static __device__ __forceinline__ void unpack(Raw w, float (&o)[1]) { o[0] = w; }
+    static __device__ __forceinline__ Raw pack(const float (&v)[1]) { return v[0]; }
+};
+
 template <typename T, int K, bool HAS_RET>
 __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
-    constexpr int LD = K + 1;                    // odd stride: rows and columns both conflict-free
-    constexpr int VN = 4;                        // a thread moves groups of 4 consecutive columns
-    constexpr int NW = C * K / VN / P1T;         // groups per thread for a [64 x K] tile
-    static_assert(NW >= 1, "tile smaller than the workgroup");
-    constexpr int KQ = K / P1W;                   // columns per thread in a row dot
-    __shared__ float ss[C * LD];                 // s = k^2 of the chunk
-    __shared__ float Dt[C * LD];                 // d_i for the tokens of the chunk
-    __shared__ float d0[K], dnew[K];
-    __shared__ float cbs[C], cas[C], nraws[C], ps[C];
-    __shared__ __attribute__((aligned(16))) float cs[C];
-    __shared__ __attribute__((aligned(16))) float rs[C];
-    __shared__ float part[P1W * C], part2[P1W * C];
-    __shared__ int done;
+    constexpr int CPT = K / 64;                   // coordinates per thread (adjacent)
+    constexpr int NRUN = C / RUN;                 // = wavefronts of the workgroup
+    static_assert(NRUN == P1W && RUN == 8, "one wavefront per run of 8 tokens");
+    typedef Pack<T, CPT> Pk;
+    __shared__ float dcur[K];                    // d at the start of the chunk
+    __shared__ __attribute__((aligned(16))) float4 maps[NRUN * K];   // (A, B, L, H) per run and coordinate
+    __shared__ int okflag[NRUN];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, run = tid >> 6, lane = tid & 63;
+    const int c0 = lane * CPT;                    // first coordinate of this thread
+    const int u_own = lane & (RUN - 1);           // the token of the run whose scalars this lane keeps
     const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
     const size_t bh = (size_t)b * a.H + h;
-    const T *k = static_cast<const T *>(a.k);
-    T *kt = static_cast<T *>(a.k_tilde);
     const bool project = a.d_min <= a.d_max;
     const float lo = project ? a.d_min : -INFINITY, hi = project ? a.d_max : INFINITY;
     const int N = (a.T + C - 1) / C;
+    const uint32_t kstride = (uint32_t)a.H * K;   // elements between consecutive tokens
 
-    if (tid < K) d0[tid] = a.d_in ? a.d_in[bh * K + tid] : 1.f;
+    if (tid < K) dcur[tid] = a.d_in ? a.d_in[bh * K + tid] : 1.f;
 
-    u32x4 kreg[NW];                              // (bf16: only .x, .y are used)
-    float betreg = 0.f, retreg = 1.f;
+    typename Pk::Raw kreg[RUN];                  // this thread's k of the next chunk
+    float betreg = 0.f, retreg = 1.f;            // gates of token (run, u_own) of the next chunk
 #define OSDN_P1_LOAD(n_)                                                                         \
     {                                                                                            \
         const int t0_ = (n_) * C;                                                                \
-        _Pragma("unroll") for (int m = 0; m < NW; ++m) {                                         \
-            const int i = tid + m * P1T, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
-            const int t = min(t0_ + r, a.T - 1);                                                 \
-            const T *src_ = k + (((size_t)b * a.T + t) * a.H + h) * K + c;                       \
-            if (sizeof(T) == 2) { const u32x2 v_ = *reinterpret_cast<const u32x2 *>(src_); kreg[m] = u32x4{v_[0], v_[1], 0u, 0u}; } \
-            else kreg[m] = *reinterpret_cast<const u32x4 *>(src_);                               \
+        const T *kp_ = static_cast<const T *>(a.k) + (((size_t)b * a.T + t0_) * a.H + h) * K;    \
+        _Pragma("unroll") for (int u = 0; u < RUN; ++u) {                                        \
+            const int i_ = min(run * RUN + u, a.T - 1 - t0_);    /* rows past the end: reread */ \
+            kreg[u] = *reinterpret_cast<const typename Pk::Raw *>(kp_ + (uint32_t)i_ * kstride + c0); \
         }                                                                                        \
-        if (tid < C) {                                                                           \
-            const int t = min(t0_ + tid, a.T - 1);                                               \
-            const size_t th = ((size_t)b * a.T + t) * a.H + h;                                   \
-            betreg = a.beta[th];                                                                 \
-            if (HAS_RET) retreg = a.retention[th];                                               \
-        }                                                                                        \
+        const int t = min(t0_ + run * RUN + u_own, a.T - 1);                                     \
+        const size_t th = ((size_t)b * a.T + t) * a.H + h;                                       \
+        betreg = a.beta[th];                                                                     \
+        if (HAS_RET) retreg = a.retention[th];                                                   \
     }
     OSDN_P1_LOAD(a.n0)
 
@@ -76,131 +103,149 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
 #else
 #define OSDN_TICK(j)
 #endif
+    __syncthreads();
     for (int n = a.n0; n < a.n1; ++n) {
         const int t0 = n * C;
         const int nvalid = min(C, a.T - t0);
-        // ---- registers -> LDS (rows past the end of the sequence become no-op tokens) ----
-        u32x4 kcur[NW];
+        // ---- this thread's k and s = k^2 (rows past the end of the sequence: no-op tokens) ----
+        float kf[RUN][CPT], sv[RUN][CPT];
 #pragma unroll
-        for (int m = 0; m < NW; ++m) {
-            kcur[m] = kreg[m];
-            const int i = tid + m * P1T, r = i / (K / VN), c = (i % (K / VN)) * VN;
+        for (int u = 0; u < RUN; ++u) {
+            Pk::unpack(kreg[u], kf[u]);
 #pragma unroll
-            for (int e = 0; e < VN; ++e) {
-                const float kv = r < nvalid ? vec_get<T>(kcur[m], e) : 0.f;
-                ss[r * LD + c + e] = kv * kv;
+            for (int e = 0; e < CPT; ++e) {
+                if (run * RUN + u >= nvalid) kf[u][e] = 0.f;
+                sv[u][e] = kf[u][e] * kf[u][e];
             }
         }
         const float bet = betreg, ret = retreg;
-        __syncthreads();
-        OSDN_TICK(0)
-        if (n + 1 < a.n1) OSDN_P1_LOAD(n + 1)
-        if (a.d_ckpt && tid < K) a.d_ckpt[(bh * N + n) * K + tid] = d0[tid];
-        // ---- per token: n_raw = sum s, and the first guess p = <d_0, s> ----
+        // ---- the scalars of token (run, u_own): n_raw = sum s, first guess p = <d_0, s> ----
+        float nraw, cb, ca, p_cur, c_cur;
         {
-            const int i = lane, q0 = wave * KQ;
-            float sn = 0.f, sp = 0.f;
-#pragma unroll 8
-            for (int c = 0; c < KQ; ++c) {
-                const float s = ss[i * LD + q0 + c];
-                sn += s;
-                sp = __builtin_fmaf(s, d0[q0 + c], sp);
+            float dst[CPT];
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) dst[e] = dcur[c0 + e];
+            if (a.d_ckpt && run == 0) {
+#pragma unroll
+                for (int e = 0; e < CPT; ++e) a.d_ckpt[(bh * N + n) * K + c0 + e] = dst[e];
             }
-            part[wave * C + i] = sn;
-            part2[wave * C + i] = sp;
-        }
-        __syncthreads();
-        if (tid < C) {
-            const int i = tid;
-            const float nraw = sumw(part, i), p = sumw(part2, i);
-            const bool valid = i < nvalid;
+            float vn[RUN], vp[RUN];
+#pragma unroll
+            for (int u = 0; u < RUN; ++u) {
+                vn[u] = 0.f; vp[u] = 0.f;
+#pragma unroll
+                for (int e = 0; e < CPT; ++e) { vn[u] += sv[u][e]; vp[u] = __builtin_fmaf(sv[u][e], dst[e], vp[u]); }
+            }
+            nraw = lane_fold8_all(vn, lane);
+            p_cur = lane_fold8_all(vp, lane);
+            const bool valid = run * RUN + u_own < nvalid;
             const float nn = fmaxf(nraw, a.eps);
             const float bp = a.beta_aware ? bet : 1.f;
-            const float cb = valid ? a.eta * bp / nn : 0.f;
-            const float ca = cb * bp;
-            nraws[i] = nraw; cbs[i] = cb; cas[i] = ca; rs[i] = valid ? ret : 1.f;
-            ps[i] = p;
-            cs[i] = cb - ca * p;
+            cb = valid ? a.eta * bp / nn : 0.f;
+            ca = cb * bp;
+            c_cur = cb - ca * p_cur;
         }
-        __syncthreads();
+        float rv[RUN];
+#pragma unroll
+        for (int u = 0; u < RUN; ++u) rv[u] = HAS_RET ? lane_bcast(run * RUN + u < nvalid ? ret : 1.f, u) : 1.f;
+        OSDN_TICK(0)
+        if (n + 1 < a.n1) OSDN_P1_LOAD(n + 1)
         OSDN_TICK(1)
         // ---- fixed-point sweeps ----
         int sweeps_used = 0;
+        float dtr[RUN][CPT], dend[CPT];
         for (int sweep = 0; sweep < P1_MAX_SWEEPS; ++sweep) {
             ++sweeps_used;
-            if (tid < K) {                      // K independent scalar recurrences
-                float d = d0[tid];
-                // LDS operands are fetched one block of PB tokens ahead of their use
-                float sb[2][PB], cb_[2][PB], rb[2][PB];
-#define OSDN_QLOAD(buf, i0_)                                                                     \
-    _Pragma("unroll") for (int u = 0; u < PB; ++u) {                                             \
-        sb[buf][u] = ss[((i0_) + u) * LD + tid]; cb_[buf][u] = cs[(i0_) + u];                     \
-        if (HAS_RET) rb[buf][u] = rs[(i0_) + u];                                                 \
-    }
-                OSDN_QLOAD(0, 0)
+            float cv[RUN];
 #pragma unroll
-                for (int blk = 0; blk < C / PB; ++blk) {
-                    if (blk + 1 < C / PB) OSDN_QLOAD((blk + 1) & 1, (blk + 1) * PB)
+            for (int u = 0; u < RUN; ++u) cv[u] = lane_bcast(c_cur, u);
+            // the map of this run, x -> clip3(A x + B, L, H), per coordinate
 #pragma unroll
-                    for (int u = 0; u < PB; ++u) {
-                        const int i = blk * PB + u;
-                        Dt[i * LD + tid] = d;
-                        d = clip3(d_bar<HAS_RET>(rb[blk & 1][u], d, cb_[blk & 1][u], sb[blk & 1][u]), lo, hi);
+            for (int e = 0; e < CPT; ++e) {
+                float A = 1.f, B = 0.f, L = -FLT_MAX, H = FLT_MAX;
+#pragma unroll
+                for (int u = 0; u < RUN; ++u) {
+                    const float bs = cv[u] * sv[u][e];
+                    if (HAS_RET) {
+                        A *= rv[u];
+                        B = __builtin_fmaf(rv[u], B, bs);
+                        L = clip3(__builtin_fmaf(rv[u], L, bs), lo, hi);
+                        H = clip3(__builtin_fmaf(rv[u], H, bs), lo, hi);
+                    } else {
+                        B += bs;
+                        L = clip3(L + bs, lo, hi);
+                        H = clip3(H + bs, lo, hi);
                     }
                 }
-                dnew[tid] = d;
+                maps[run * K + c0 + e] = make_float4(A, B, L, H);
             }
             __syncthreads();
             OSDN_TICK(2)
-            {                                   // recompute p_i = <d_i, s_i> from the trajectory
-                const int i = lane, q0 = wave * KQ;
-                float sp = 0.f;
-#pragma unroll 8
-                for (int c = 0; c < KQ; ++c) sp = __builtin_fmaf(ss[i * LD + q0 + c], Dt[i * LD + q0 + c], sp);
-                part2[wave * C + i] = sp;
-            }
-            __syncthreads();
-            if (tid < C) {
-                const int i = tid;
-                const float p = sumw(part2, i);
-                const bool ok = fabsf(p - ps[i]) <= P1_TOL * fabsf(p);
-                const bool all_ok = __all(ok);
-                if (all_ok) {
-                    if (tid == 0) done = 1;
-                } else {
-                    if (tid == 0) done = 0;
-                    ps[i] = p;
-                    cs[i] = cbs[i] - cas[i] * p;
+            float vp[RUN];
+#pragma unroll
+            for (int u = 0; u < RUN; ++u) vp[u] = 0.f;
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) {
+                // d at the start of this run: the runs to its left applied to d at the chunk start
+                float d = dcur[c0 + e];
+#pragma unroll
+                for (int j = 0; j < NRUN - 1; ++j)
+                    if (j < run) {
+                        const float4 m = maps[j * K + c0 + e];
+                        d = clip3(__builtin_fmaf(m.x, d, m.y), m.z, m.w);
+                    }
+                // replay of the run's tokens (the same arithmetic as the reverse sweep's replay)
+#pragma unroll
+                for (int u = 0; u < RUN; ++u) {
+                    dtr[u][e] = d;
+                    vp[u] = __builtin_fmaf(sv[u][e], d, vp[u]);
+                    d = clip3(d_bar<HAS_RET>(rv[u], d, cv[u], sv[u][e]), lo, hi);
                 }
+                dend[e] = d;
             }
+            const float p_new = lane_fold8_all(vp, lane);
+            const bool ok = fabsf(p_new - p_cur) <= P1_TOL * fabsf(p_new);
+            const bool wave_ok = __all(ok);
+            if (lane == 0) okflag[run] = wave_ok ? 1 : 0;
             __syncthreads();
             OSDN_TICK(3)
-            if (done) break;
+            bool all_ok = true;
+#pragma unroll
+            for (int w = 0; w < NRUN; ++w) all_ok = all_ok && okflag[w] != 0;
+            if (all_ok) break;
+            p_cur = p_new;
+            c_cur = cb - ca * p_new;
         }
-        // ---- accepted: (cs, ps) generated Dt and dnew ----
+        // ---- accepted: (c_cur, p_cur) generated dtr and dend ----
+        {
+            T *ktp = static_cast<T *>(a.k_tilde) + (((size_t)b * a.T + t0) * a.H + h) * K;
 #pragma unroll
-        for (int m = 0; m < NW; ++m) {
-            const int i = tid + m * P1T, r = i / (K / VN), c = (i % (K / VN)) * VN;
-            if (r < nvalid) {
-                float out[VN];
+            for (int u = 0; u < RUN; ++u) {
+                const int i = run * RUN + u;
+                if (i < nvalid) {
+                    float out[CPT];
 #pragma unroll
-                for (int e = 0; e < VN; ++e) out[e] = Dt[r * LD + c + e] * vec_get<T>(kcur[m], e);
-                store_vec(kt + (((size_t)b * a.T + t0 + r) * a.H + h) * K + c, out);
+                    for (int e = 0; e < CPT; ++e) out[e] = dtr[u][e] * kf[u][e];
+                    *reinterpret_cast<typename Pk::Raw *>(ktp + (uint32_t)i * kstride + c0) = Pk::pack(out);
+                }
             }
         }
-        if (a.tok_scalars && tid < nvalid) {
-            const size_t th = ((size_t)b * a.T + t0 + tid) * a.H + h;
-            *reinterpret_cast<float4 *>(a.tok_scalars + th * 4) = make_float4(cs[tid], ps[tid], nraws[tid], (float)sweeps_used);
+        if (a.tok_scalars && lane < RUN && run * RUN + lane < nvalid) {
+            const size_t th = ((size_t)b * a.T + t0 + run * RUN + lane) * a.H + h;
+            *reinterpret_cast<float4 *>(a.tok_scalars + th * 4) = make_float4(c_cur, p_cur, nraw, (float)sweeps_used);
         }
-        if (tid < K) d0[tid] = dnew[tid];
+        if (run == NRUN - 1) {
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) dcur[c0 + e] = dend[e];
+        }
         __syncthreads();
         OSDN_TICK(4)
     }
 #ifdef OSDN_DIAG
     if (a.tok_scalars && tid == 0 && blockIdx.x == 0)
-        for (int j = 0; j < 5; ++j) a.tok_scalars[(((size_t)b * a.T + 2 + j) * a.H + h) * 4 + 3] = (float)tph[j];
+        for (int j = 0; j < 6; ++j) a.tok_scalars[(((size_t)b * a.T + 2 + j) * a.H + h) * 4 + 3] = (float)tph[j];
 #endif
-    if (tid < K) a.d_out[bh * K + tid] = d0[tid];
+    if (tid < K) a.d_out[bh * K + tid] = dcur[tid];
 }
 
 template <typename T, bool HAS_RET>

@@ -60,26 +60,6 @@ __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
 // through LDS (one fma per run); the TS products s_i abar_i of a thread are folded over the
 // lanes of the wavefront (each lane ends with the sum of one token over a group of lanes) and
 // the sigma of a token is the sum of K / TS such partials.  No tile of the chunk is ever in LDS.
-template <int TS>
-__device__ __forceinline__ float lane_fold(const float (&v)[TS], int lane) {
-    static_assert(TS == 16 || TS == 8, "run length");
-    // after the step with lane bit b, a lane keeps the values whose index has bit b equal to
-    // its own and adds the partner lane's copy of them: the count halves, the group doubles
-    float w[TS / 2], x[TS / 4], y[TS / 8];
-    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4, b3 = lane & 8;
-#pragma unroll
-    for (int m = 0; m < TS / 2; ++m)
-        w[m] = (b0 ? v[2 * m + 1] : v[2 * m]) + dpp_f32<0xB1>(b0 ? v[2 * m] : v[2 * m + 1]);     // lane ^ 1
-#pragma unroll
-    for (int m = 0; m < TS / 4; ++m)
-        x[m] = (b1 ? w[2 * m + 1] : w[2 * m]) + dpp_f32<0x4E>(b1 ? w[2 * m] : w[2 * m + 1]);     // lane ^ 2
-#pragma unroll
-    for (int m = 0; m < TS / 8; ++m)
-        y[m] = (b2 ? x[2 * m + 1] : x[2 * m]) + __shfl_xor(b2 ? x[2 * m] : x[2 * m + 1], 4, 64);
-    if (TS == 8) return y[0];                  // token lane % 8, summed over its 8 lanes
-    return (b3 ? y[TS / 8 - 1] : y[0]) + __shfl_xor(b3 ? y[0] : y[TS / 8 - 1], 8, 64);   // token lane % 16, over 16 lanes
-}
-
 template <typename T, int K, bool HAS_RET>
 __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
     constexpr int NSEG = P1T / K;                 // runs per chunk
@@ -186,6 +166,9 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
             }
             segL[sg * K + c] = loc;
             segP[sg * K + c] = P;
+#ifdef OSDN_DIAG
+            if (sweep == 0) OSDN_TICK(5)
+#endif
             __syncthreads();
             OSDN_TICK(1)
             // value of a at the right end of this run: chain the runs to its right
