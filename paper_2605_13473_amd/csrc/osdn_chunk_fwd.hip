@@ -18,20 +18,27 @@ namespace osdn {
 // Besides T, W it leaves the tiles the chain kernels consume in exactly the layout their MFMA
 // operands want, so that those kernels only copy: -W^T, (rho . K~)^T and U^T (transposes come
 // for free from the accumulator layout, or from a 0/1 selector product for K~).
+// The row scalings of the right-hand sides move into T: W = (T diag(beta gamma)) K and
+// U = (T diag(beta)) V, so that K and V enter the products as they come from memory.
 template <typename T, int K>
 __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDF = C + 1;
     constexpr int NKT = K / 64;                                 // column tiles of a [64 x K] result per wave
-    __shared__ __attribute__((aligned(16))) T X1[C * LDK];      // K, then beta gamma K, then V slabs
+    __shared__ __attribute__((aligned(16))) T X1[C * LDK];      // K, then V slabs
     __shared__ __attribute__((aligned(16))) T X2[C * LDK];      // K~, then W staging
-    __shared__ __attribute__((aligned(16))) T Tt[C * LDC];      // T in the I/O type
-    constexpr int SCR = 2 * C * LDF + 3 * 16 * 17;
-    constexpr int SCR_MIN = (K * LDC * (int)sizeof(T) + 3) / 4;
-    __shared__ __attribute__((aligned(16))) float scratch[SCR > SCR_MIN ? SCR : SCR_MIN];
+    __shared__ __attribute__((aligned(16))) T Tu[C * LDC];      // T diag(beta)
+    // scratch: A (fp32) | (I + A)^-1 (fp32) | per-wave 16x16 block products.  A's space later holds
+    // T diag(beta gamma); the rest doubles as the staging tile for the transposed outputs.
+    constexpr int STAGE_F = (K * LDC * (int)sizeof(T) + 3) / 4;
+    constexpr int TI_F = C * LDF + 3 * 16 * 17;
+    constexpr int TW_F = C * LDC * (int)sizeof(T) / 4;
+    constexpr int AF_F = ((C * LDF > TW_F ? C * LDF : TW_F) + 3) & ~3;
+    __shared__ __attribute__((aligned(16))) float scratch[AF_F + (TI_F > STAGE_F ? TI_F : STAGE_F)];
     float *Af = scratch;                                        // A (fp32)
-    float *Ti = Af + C * LDF;                                   // (I + A)^-1 (fp32)
-    float *Xs = Ti + C * LDF;                                   // block-product scratch
-    T *stage = reinterpret_cast<T *>(scratch);                  // [K][LDC] / [64][LDC], once T is final
+    float *Ti = scratch + AF_F;                                 // (I + A)^-1 (fp32), 16-byte aligned
+    float *Xs = Ti + C * LDF;                                   // [3][16][17]: at most three blocks per round
+    T *Tw = reinterpret_cast<T *>(Af);                          // [64][LDC], once A is dead
+    T *stage = reinterpret_cast<T *>(Ti);                       // [K][LDC] / [64][LDC], while Ti is not live
     __shared__ float Gs[C], Bs[C];
 
     const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -40,6 +47,12 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;      // (b, first token, h)
     const size_t tstride = a.H;                                           // tokens are H rows apart
 
+#ifdef OSDN_DIAG
+    long long cph[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, clast = clock64();
+#define OSDN_CTICK(j) { const long long now_ = clock64(); cph[j] += now_ - clast; clast = now_; }
+#else
+#define OSDN_CTICK(j)
+#endif
     if (wave == 0) {
         const size_t th = tok0 + (size_t)lane * tstride;
         const float g = a.log_alpha ? a.log_alpha[th] : 0.f;
@@ -48,7 +61,12 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     }
     load_tile(X1, LDK, static_cast<const T *>(a.k) + tok0 * K, tstride * K, C, K, tid, NT);
     load_tile(X2, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, NT);
+    // the first slab of V travels through registers while the chunk's T is being built
+    const T *vg = static_cast<const T *>(a.v) + tok0 * a.V;
+    TileRegs<T, C, C, NT> r_V;
+    r_V.fetch(vg, tstride * a.V, tid);
     __syncthreads();
+    OSDN_CTICK(0)
 
     // ---- A = tril(beta_i Gamma_ij <k_i, k~_j>, -1): the ten lower 16x16 tiles ----
     for (int idx = wave; idx < 10; idx += 4) {
@@ -62,58 +80,6 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
             Af[i * LDF + j] = (j < i) ? Bs[i] * __expf(Gs[i] - Gs[j]) * acc[r] : 0.f;
         }
     }
-    __syncthreads();
-
-    // ---- T = (I + A)^-1, 16x16 blocks.  Diagonal blocks: forward substitution, one
-    //      column per lane.  Block (i,j), i > j: T_ij = -T_ii sum_{m=j}^{i-1} A_im T_mj. ----
-    if (lane < 16) {
-        const int o = wave * 16;
-        float x[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            float v = (i == lane) ? 1.f : 0.f;
-#pragma unroll
-            for (int j = 0; j < i; ++j) v -= Af[(o + i) * LDF + o + j] * x[j];
-            x[i] = v;
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) Ti[(o + i) * LDF + o + lane] = x[i];
-    }
-    __syncthreads();
-    for (int s = 1; s <= 3; ++s) {
-        const int nblk = 4 - s;
-        for (int task = tid; task < nblk * 256; task += NT) {
-            const int bi = task >> 8, e = task & 255, r = e >> 4, c = e & 15;
-            const int i = s + bi, j = bi;
-            float acc = 0.f;
-            for (int m = j; m < i; ++m)
-#pragma unroll
-                for (int l = 0; l < 16; ++l)
-                    acc += Af[(i * 16 + r) * LDF + m * 16 + l] * Ti[(m * 16 + l) * LDF + j * 16 + c];
-            Xs[(bi * 16 + r) * 17 + c] = acc;
-        }
-        __syncthreads();
-        for (int task = tid; task < nblk * 256; task += NT) {
-            const int bi = task >> 8, e = task & 255, r = e >> 4, c = e & 15;
-            const int i = s + bi, j = bi;
-            float acc = 0.f;
-            for (int l = 0; l <= r; ++l) acc += Ti[(i * 16 + r) * LDF + i * 16 + l] * Xs[(bi * 16 + l) * 17 + c];
-            Ti[(i * 16 + r) * LDF + j * 16 + c] = -acc;
-        }
-        __syncthreads();
-    }
-    // T in the I/O type (upper triangle exactly zero), and beta gamma . K in place
-    for (int idx = tid; idx < C * C; idx += NT) {
-        const int i = idx >> 6, j = idx & 63;
-        Tt[i * LDC + j] = from_f32<T>(j <= i ? Ti[i * LDF + j] : 0.f);
-    }
-    for (int idx = tid; idx < C * K; idx += NT) {
-        const int j = idx / K, c = idx % K;
-        X1[j * LDK + c] = from_f32<T>(Bs[j] * __expf(Gs[j]) * to_f32(X1[j * LDK + c]));
-    }
-    __syncthreads();            // Af, Ti are dead from here on: their space is the staging tile
-    store_tile_global(static_cast<T *>(a.Tm) + bhn * C * C, C, Tt, LDC, C, C, tid, NT);
-
     // ---- (rho . K~)^T: pick 16x16 blocks of K~, scale rows by rho_j, store transposed ----
     {
         const float GC = Gs[C - 1];
@@ -130,10 +96,68 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
         }
     }
     __syncthreads();
+    OSDN_CTICK(1)
     store_tile_global(static_cast<T *>(a.Ktr) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, NT);
-    __syncthreads();
+    __syncthreads();                // the staging tile is free again: (I + A)^-1 is built in its place
 
-    // ---- W = T (beta gamma . K), and -W^T ----
+    // ---- T = (I + A)^-1, 16x16 blocks.  Diagonal blocks: forward substitution, one
+    //      column per lane.  Block (i,j), i > j: T_ij = -T_ii sum_{m=j}^{i-1} A_im T_mj,
+    //      both products on the fp32 MFMA, one wavefront per block. ----
+    if (lane < 16) {
+        const int o = wave * 16;
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float v = (i == lane) ? 1.f : 0.f;
+#pragma unroll
+            for (int j = 0; j < i; ++j) v -= Af[(o + i) * LDF + o + j] * x[j];
+            x[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Ti[(o + i) * LDF + o + lane] = x[i];
+    }
+    __syncthreads();
+    for (int s = 1; s <= 3; ++s) {
+        if (wave < 4 - s) {
+            const int i = s + wave, j = wave;
+            float *xw = Xs + wave * 16 * 17;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int m = j; m < i; ++m)
+                mma_tile<float, true, false>(acc, Af + i * 16 * LDF + m * 16, LDF, Ti + m * 16 * LDF + j * 16, LDF, 16, lane);
+            store_tile(xw, 17, acc, lane);
+            f32x4 t = {0.f, 0.f, 0.f, 0.f};
+            mma_tile<float, true, false>(t, Ti + i * 16 * LDF + i * 16, LDF, xw, 17, 16, lane);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) t[r] = -t[r];
+            store_tile(Ti + i * 16 * LDF + j * 16, LDF, t, lane);
+        }
+        __syncthreads();
+    }
+    OSDN_CTICK(2)
+    // ---- T in the I/O type, three times: as it is (straight to memory), with the columns scaled
+    //      by beta (for U) and by beta gamma (for W); the upper triangle is exactly zero ----
+    {
+        constexpr int VN = 16 / sizeof(T);
+        T *tg = static_cast<T *>(a.Tm) + bhn * C * C;
+        for (int v = tid; v < C * C / VN; v += NT) {
+            const int i = v / (C / VN), j0 = (v % (C / VN)) * VN;
+            float plain[VN];
+#pragma unroll
+            for (int e = 0; e < VN; ++e) {
+                const int j = j0 + e;
+                const float t = j <= i ? Ti[i * LDF + j] : 0.f;
+                const float bj = Bs[j];
+                plain[e] = t;
+                Tu[i * LDC + j] = from_f32<T>(t * bj);
+                Tw[i * LDC + j] = from_f32<T>(t * bj * __expf(Gs[j]));
+            }
+            store_vec_t(tg + i * C + j0, plain);
+        }
+    }
+    __syncthreads();                // Ti is dead from here on: its space is the staging tile again
+    OSDN_CTICK(3)
+
+    // ---- W = (T diag(beta gamma)) K, and -W^T ----
     {
 #pragma unroll
         for (int qn = 0; qn < NKT; ++qn) {
@@ -142,7 +166,7 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
             for (int ib = 0; ib < 4; ++ib) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
                 const int kdim = min(C, ((ib + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
-                mma_tile<T, true, false>(acc, Tt + ib * 16 * LDC, LDC, X1 + nb * 16, LDK, kdim, lane);
+                mma_tile<T, true, false>(acc, Tw + ib * 16 * LDC, LDC, X1 + nb * 16, LDK, kdim, lane);
                 store_tile(X2 + ib * 16 * LDK + nb * 16, LDK, acc, lane);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[r] = -acc[r];
@@ -151,32 +175,32 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
         }
     }
     __syncthreads();
+    OSDN_CTICK(4)
     store_tile_global(static_cast<T *>(a.W) + bhn * C * K, K, X2, LDK, C, K, tid, NT);
     store_tile_global(static_cast<T *>(a.Wt) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, NT);
+    OSDN_CTICK(5)
 
-    // ---- U^T = (T (beta . V))^T, 64 columns of V at a time ----
-    const T *vg = static_cast<const T *>(a.v) + tok0 * a.V;
+    // ---- U^T = ((T diag(beta)) V)^T, 64 columns of V at a time ----
     for (int v0 = 0; v0 < a.V; v0 += C) {
         __syncthreads();
-        constexpr int VN = 16 / sizeof(T);
-        for (int i = tid; i < C * (C / VN); i += NT) {
-            const int r = i / (C / VN), c = (i % (C / VN)) * VN;
-            u32x4 raw = *reinterpret_cast<const u32x4 *>(vg + (size_t)r * tstride * a.V + v0 + c);
-            const float br = Bs[r];
-#pragma unroll
-            for (int e = 0; e < VN; ++e) X1[r * LDC + c + e] = from_f32<T>(br * vec_get<T>(raw, e));
-        }
+        r_V.put(X1, LDC, tid);
+        if (v0 + C < a.V) r_V.fetch(vg + v0 + C, tstride * a.V, tid);
         __syncthreads();
 #pragma unroll
         for (int ib = 0; ib < 4; ++ib) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
             const int kdim = min(C, ((ib + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
-            mma_tile<T, true, false>(acc, Tt + ib * 16 * LDC, LDC, X1 + wave * 16, LDC, kdim, lane);
+            mma_tile<T, true, false>(acc, Tu + ib * 16 * LDC, LDC, X1 + wave * 16, LDC, kdim, lane);
             store_tile_t(stage + wave * 16 * LDC + ib * 16, LDC, acc, lane);
         }
         __syncthreads();
         store_tile_global(static_cast<T *>(a.Ut) + (bhn * a.V + v0) * C, (size_t)C, stage, LDC, C, C, tid, NT);
     }
+#ifdef OSDN_DIAG
+    OSDN_CTICK(6)
+    if (tid == 0 && blockIdx.x == 7 && blockIdx.y == 0 && blockIdx.z == 0)
+        for (int j = 0; j < 7; ++j) static_cast<T *>(a.Tm)[bhn * C * C + j] = from_f32<T>((float)cph[j] / 64.f);
+#endif
 }
 
 // ------------------------------------------------------------- state_fwd ----

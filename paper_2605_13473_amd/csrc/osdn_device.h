@@ -177,6 +177,17 @@ __device__ __forceinline__ void store_tile_global(T *g, size_t g_ld, const T *s,
     }
 }
 
+// 16 bytes of T from floats (4 fp32 or 8 bf16), one vector store
+__device__ __forceinline__ void store_vec_t(float *dst, const float (&v)[4]) {
+    *reinterpret_cast<f32x4 *>(dst) = f32x4{v[0], v[1], v[2], v[3]};
+}
+__device__ __forceinline__ void store_vec_t(bf16 *dst, const float (&v)[8]) {
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (bf16)v[e];
+    *reinterpret_cast<bf16x8 *>(dst) = o;
+}
+
 // The same copy in two halves, so that the global loads of a tile can be in flight while the
 // workgroup computes on the previous one: tile_fetch issues them into registers, tile_put
 // writes the registers into LDS.  NT threads share a [ROWS x COLS] tile.
