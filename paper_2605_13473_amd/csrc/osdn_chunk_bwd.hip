@@ -59,6 +59,8 @@ __global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
     }
     load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, NT);
     load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, NT);
+    TileRegs<T, C, C, NT> r_dO;          // the slabs of dO travel through registers, one slab ahead
+    r_dO.fetch(static_cast<const T *>(a.dO) + tok0 * a.V, tstride * a.V, tid);
     __syncthreads();
     for (int idx = wave; idx < 16; idx += 4) {
         const int ib = idx >> 2, jb = idx & 3;
@@ -91,7 +93,8 @@ __global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
     const int k0 = (wave * 16) / Mfma<T>::KSTEP * Mfma<T>::KSTEP;   // P^T rows 16*wave.. are zero left of here
     for (int v0 = 0; v0 < a.V; v0 += C) {
         __syncthreads();
-        load_tile(dOs, LDC, static_cast<const T *>(a.dO) + tok0 * a.V + v0, tstride * a.V, C, C, tid, NT);
+        r_dO.put(dOs, LDC, tid);
+        if (v0 + C < a.V) r_dO.fetch(static_cast<const T *>(a.dO) + tok0 * a.V + v0 + C, tstride * a.V, tid);
         __syncthreads();
         // dO^T for this slab: wave w transposes the 16 columns 16*w ..
 #pragma unroll

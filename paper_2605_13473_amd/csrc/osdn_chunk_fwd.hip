@@ -434,6 +434,11 @@ __global__ __launch_bounds__(NT) void output_fwd_kernel(ChunkArgs a) {
     }
     load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, NT);
     load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, NT);
+    // the slabs of S and E^T travel through registers, one slab ahead of the products
+    TileRegs<T, C, K, NT> r_S;
+    TileRegs<T, C, C, NT> r_E;
+    r_S.fetch(static_cast<const T *>(a.S_ckpt) + bhn * a.V * K, (size_t)K, tid);
+    r_E.fetch(static_cast<const T *>(a.Et) + bhn * a.V * C, (size_t)C, tid);
     __syncthreads();
     // P^T tiles (rows j, columns i) so that the store lands k-contiguous in Ps[i][j]
     for (int idx = wave; idx < 16; idx += 4) {
@@ -452,8 +457,12 @@ __global__ __launch_bounds__(NT) void output_fwd_kernel(ChunkArgs a) {
     T *Os = Kts;
     for (int v0 = 0; v0 < a.V; v0 += C) {
         __syncthreads();
-        load_tile(Ss, LDK, static_cast<const T *>(a.S_ckpt) + (bhn * a.V + v0) * K, (size_t)K, C, K, tid, NT);
-        load_tile(Ets, LDC, static_cast<const T *>(a.Et) + (bhn * a.V + v0) * C, (size_t)C, C, C, tid, NT);
+        r_S.put(Ss, LDK, tid);
+        r_E.put(Ets, LDC, tid);
+        if (v0 + C < a.V) {
+            r_S.fetch(static_cast<const T *>(a.S_ckpt) + (bhn * a.V + v0 + C) * K, (size_t)K, tid);
+            r_E.fetch(static_cast<const T *>(a.Et) + (bhn * a.V + v0 + C) * C, (size_t)C, tid);
+        }
         __syncthreads();
         const int kdim = min(C, ((wave + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
 #pragma unroll
