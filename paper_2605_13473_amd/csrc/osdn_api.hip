@@ -82,8 +82,8 @@ Layout make_layout(const osdn_params *p) {
     L.dOt = take(B * T * H * V * es);
     L.dEt = take(B * T * H * V * es);
     L.dS_ckpt = take(B * H * N * V * K * es);
-    L.dk_read = take(B * T * H * K * 4);
-    L.dkt = take(B * T * H * K * 4);
+    L.dk_read = take(B * T * H * K * es);
+    L.dkt = take(B * T * H * K * es);
     L.masks = take(B * H * N * K * 8);
     L.a_ckpt = take(B * H * N * K * 4);
     L.total_bwd = off;
@@ -152,20 +152,28 @@ Pipeline *pipeline_for_current_device() {
     return it->second.ok ? &it->second : nullptr;
 }
 
-// number of segments for a sequence of N chunks: about 16 chunks each, between two (any
+// number of segments for a sequence of N chunks: about 20 chunks each, between two (any
 // sequence of at least two chunks, so that short sequences take the same path) and four:
 // more segments buy little overlap and cost launches and cross-stream waits
 // (OSDN_SEGMENTS in the environment overrides it; 1 = no pipelining)
 int segment_count(int N) {
     static const int forced = [] { const char *e = std::getenv("OSDN_SEGMENTS"); return e ? std::atoi(e) : 0; }();
-    int S = forced > 0 ? forced : N / 16;
+    int S = forced > 0 ? forced : N / 20;
     if (forced <= 0 && S > 4) S = 4;
     if (forced <= 0 && S < 2 && N >= 2) S = 2;
     if (S > MAX_SEGMENTS) S = MAX_SEGMENTS;
     if (S > N) S = N;
     return S < 1 ? 1 : S;
 }
-inline int seg_begin(int N, int S, int s) { return (int)((long long)N * s / S); }
+// first chunk of segment s.  Segment 0 is half as long as the others: it is the one that runs
+// without a partner (phase 1 of it before anything of phase 2 can start in the forward pass,
+// and after everything else in the backward pass).
+inline int seg_begin(int N, int S, int s) {
+    if (s <= 0) return 0;
+    if (s >= S) return N;
+    const int first = N / (2 * S) > 0 ? N / (2 * S) : 1;
+    return first + (int)((long long)(N - first) * (s - 1) / (S - 1));
+}
 
 #define OSDN_HIP_OK(x) do { if ((x) != hipSuccess) return OSDN_ERR_LAUNCH; } while (0)
 
@@ -296,8 +304,8 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     c.dO = dO; c.dS_out = dS_out;
     c.dElt = ws + L.dElt; c.Qt = ws + L.Qt; c.dOt = ws + L.dOt; c.dEt = ws + L.dEt; c.dS_ckpt = ws + L.dS_ckpt;
     c.dS_in = dS_in; c.dq = dq; c.dv = dv;
-    c.dk_read = reinterpret_cast<float *>(ws + L.dk_read);
-    c.dkt = reinterpret_cast<float *>(ws + L.dkt);
+    c.dk_read = ws + L.dk_read;
+    c.dkt = ws + L.dkt;
     c.dbeta = dbeta; c.dlog_alpha = log_alpha ? dlog_alpha : nullptr;
     PrecondBwdArgs pb{};
     pb.B = p->B; pb.T = p->T; pb.H = p->H; pb.K = p->K;

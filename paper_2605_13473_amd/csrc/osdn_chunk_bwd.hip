@@ -562,8 +562,8 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) { tq[ib][r] = 0.f; tk[ib][r] = 0.f; tr[ib][r] = 0.f; }
     T *dq_g = static_cast<T *>(a.dq) + tok0 * K;
-    float *dk_g = a.dk_read + tok0 * K;
-    float *dkt_g = a.dkt + tok0 * K;
+    T *dk_g = static_cast<T *>(a.dk_read) + tok0 * K;
+    T *dkt_g = static_cast<T *>(a.dkt) + tok0 * K;
     if (has_ct) {
 #pragma unroll
         for (int ib = 0; ib < 4; ++ib) {
@@ -600,8 +600,8 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
                 tk[ib][r] += gk * kv;
                 tr[ib][r] += gr * ktv;
                 dq_g[(size_t)i * tstride * K + c] = from_f32<T>(aq[r] + gq);
-                dk_g[(size_t)i * tstride * K + c] = ak[r] + gk;
-                dkt_g[(size_t)i * tstride * K + c] = at[r] + gr;
+                dk_g[(size_t)i * tstride * K + c] = from_f32<T>(ak[r] + gk);
+                dkt_g[(size_t)i * tstride * K + c] = from_f32<T>(at[r] + gr);
             }
         }
     }

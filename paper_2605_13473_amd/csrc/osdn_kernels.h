@@ -34,8 +34,8 @@ struct PrecondBwdArgs {
                               // kernel puts sigma_t into the fourth slot for the post kernel
     uint2 *masks;             // [B,H,T/64,K]: bit i = token i of the chunk stayed inside the box
     float *a_ckpt;            // [B,H,T/64,K]: adjoint of d at the right end of every chunk
-    const float *dkt;         // [B,T,H,K] fp32: dL/dk~ from phase 2
-    const float *dk_read;     // [B,T,H,K] fp32: read-side dL/dk from phase 2
+    const void *dkt;          // [B,T,H,K] io: dL/dk~ from phase 2
+    const void *dk_read;      // [B,T,H,K] io: read-side dL/dk from phase 2
     const float *dd_out;      // [B,H,K] or null
     void *dk;                 // [B,T,H,K] io
     float *dbeta;             // [B,T,H] in/out
@@ -74,7 +74,7 @@ struct ChunkArgs {
     void *dS_ckpt;                    // [B,H,N,V,K] io    adjoint of the state at the END of each chunk
     float *dS_in;                     // [B,H,V,K]
     void *dq, *dv;                    // io
-    float *dk_read, *dkt;             // [B,T,H,K] fp32
+    void *dk_read, *dkt;              // [B,T,H,K] io: the two parts of dL/dk that phase 1 combines
     float *dbeta, *dlog_alpha;        // [B,T,H]; dlog_alpha may be null
 };
 

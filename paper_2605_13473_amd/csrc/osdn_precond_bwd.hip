@@ -84,15 +84,14 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 
     if (tid < K) ga[tid] = a.dd_out ? a.dd_out[bh * K + tid] : 0.f;
 
-    T kreg[TS];
-    float greg[TS];
+    T kreg[TS], greg[TS];
     float nrawreg = 1.f, betreg = 0.f, retreg = 1.f;
     uint2 mreg = make_uint2(0xffffffffu, 0xffffffffu);
 #define OSDN_P1_BLOAD(n_)                                                                        \
     {                                                                                            \
         const size_t tokc_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                     \
         const T *kp_ = static_cast<const T *>(a.k) + tokc_ * K;                                  \
-        const float *gp_ = a.dkt + tokc_ * K;                                                    \
+        const T *gp_ = static_cast<const T *>(a.dkt) + tokc_ * K;                                \
         _Pragma("unroll") for (int u = 0; u < TS; ++u) {                                         \
             const uint32_t o_ = (uint32_t)(sg * TS + u) * kstride + (uint32_t)c;                 \
             kreg[u] = kp_[o_]; greg[u] = gp_[o_];                                                \
@@ -121,7 +120,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         for (int u = 0; u < TS; ++u) {
             const float kv = to_f32(kreg[u]);
             sv[u] = kv * kv;
-            lam[u] = kv * greg[u];
+            lam[u] = kv * to_f32(greg[u]);
         }
         const uint32_t mword = (sg * TS) < 32 ? mreg.x : mreg.y;
         const uint32_t mbits = (mword >> ((sg * TS) & 31)) & ((1u << TS) - 1u);
@@ -225,8 +224,8 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 
 // ---------------------------------------------------------------- precond_post ----
 //   in : k, beta, retention, d_ckpt, tok_scalars (step, <d,s>, sum s, sigma per token),
-//        a_ckpt (adjoint of d at the right end of every chunk), dkt (dL/dk~, fp32),
-//        dk_read (read-side dL/dk, fp32), dbeta (partial, from phase 2)
+//        a_ckpt (adjoint of d at the right end of every chunk), dkt (dL/dk~),
+//        dk_read (read-side dL/dk), dbeta (partial, from phase 2)
 //   out: dk (io type) = dk_read + d_t . dkt + 2 k_t (step_t abar_t + g_p d_t + g_nraw),
 //        dbeta += sigma_t eta (1 - 2 b' p_t)/n_t,  dretention_t = <abar_t, d_t>
 template <typename T, int K, bool HAS_RET>
@@ -261,7 +260,7 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     }
     // uniform bases + 32-bit per-thread offsets (64 rows of H*K elements: below 2^31)
     const T *kp = static_cast<const T *>(a.k) + tokc * K;
-    const float *gp = a.dkt + tokc * K, *rp = a.dk_read + tokc * K;
+    const T *gp = static_cast<const T *>(a.dkt) + tokc * K, *rp = static_cast<const T *>(a.dk_read) + tokc * K;
     T *op = static_cast<T *>(a.dk) + tokc * K;
     const uint32_t kstride = (uint32_t)a.H * K;
     float Dv[C];
@@ -293,7 +292,7 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     uint32_t sofs = lofs;                                            // ... and of the next row to write
 #define OSDN_PLOAD(buf, ih_)                                                                     \
     _Pragma("unroll") for (int u = 0; u < PB; ++u) {                                             \
-        kb[buf][u] = to_f32(kp[lofs]); gb[buf][u] = gp[lofs]; rb[buf][u] = rp[lofs];             \
+        kb[buf][u] = to_f32(kp[lofs]); gb[buf][u] = to_f32(gp[lofs]); rb[buf][u] = to_f32(rp[lofs]); \
         lofs -= kstride;                                                                         \
     }
     OSDN_PLOAD(0, C - 1)
