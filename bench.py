@@ -31,12 +31,13 @@ PEAK_BF16_FLOPS = 2.5e15       # MI355X dense bf16 MFMA
 PEAK_HBM_BYTES = 8.0e12        # MI355X HBM3E
 PEAK_FP32_VALU = 157.3e12
 
-# HBM bytes per launch on configs[2], from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by the
+# HBM bytes per step (summed over a kernel's launches) on configs[2], from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by the
 # factors a 1 GiB device copy gives: fetch x 2.0, write x 1.0); see
 # profiles/hbm_traffic_configs2_fwd_bwd.txt.  Offline figures: bench.py cannot read PMCs.
 MEASURED_TRAFFIC_CONFIG2 = {
-    "precond_fwd": 153.2e6, "chunk_prep": 372.1e6, "state_fwd": 885.1e6, "output_fwd": 404.3e6,
-    "bwd_local": 270.0e6, "bwd_chain": 1287.9e6, "bwd_post": 1252.5e6, "precond_bwd": 463.7e6,
+    "precond_fwd": 153.6e6, "chunk_prep": 526.2e6, "state_fwd": 432.6e6, "output_fwd": 413.8e6,
+    "bwd_local": 414.0e6, "bwd_chain": 566.8e6, "bwd_post": 1085.2e6, "precond_mask": 104.6e6,
+    "precond_chain": 191.5e6, "precond_post": 357.6e6,
 }
 
 
@@ -54,19 +55,20 @@ def kernel_models(cfg, es):
     # phase 1 backward: masks (read k, write 8 B per chunk and coordinate), the sigma chain
     # (read k and dk~), the per-chunk outputs (read k, dk~, dk_read; write dk, dbeta, dr)
     m["precond_mask"] = ("hbm", th * (K * es + g) + nch * K * 8)
-    m["precond_chain"] = ("hbm", th * (K * es + K * 4 + 2 * g) + nch * K * (8 + 4))
-    m["precond_post"] = ("hbm", th * (K * es + 2 * K * 4 + K * es + 6 * g) + nch * K * 8)
-    # chunk_prep: read k, k~, v, beta, g ; write T, W, U
-    m["chunk_prep"] = ("hbm", th * (2 * K * es + V * es + 2 * g + C * es + K * es + V * es))
-    # state_fwd: read W, k~, U ; write E^T, S checkpoints ; 2 KV-class GEMMs
+    m["precond_chain"] = ("hbm", th * (2 * K * es + 2 * g) + nch * K * (8 + 4))
+    m["precond_post"] = ("hbm", th * (4 * K * es + 6 * g) + nch * K * 8)
+    # chunk_prep: read k, k~, v, beta, g ; write T, W, -W^T, (rho k~)^T, U^T
+    m["chunk_prep"] = ("hbm", th * (5 * K * es + 2 * V * es + C * es + 2 * g))
+    # state_fwd: read W, (rho k~)^T, U^T ; write E^T, S checkpoints ; 2 KV-class GEMMs
     m["state_fwd"] = ("hbm", th * (2 * K * es + 2 * V * es + g) + nch * V * K * es)
     # output_fwd: read q, k~, S ckpt, E^T ; write o
     m["output_fwd"] = ("hbm", th * (2 * K * es + 2 * V * es + g) + nch * V * K * es)
-    m["bwd_local"] = ("hbm", th * (2 * K * es + 2 * V * es + g))
+    # bwd_local: read q, k~, dO ; write (gamma q)^T, dO^T, dEl^T
+    m["bwd_local"] = ("hbm", th * (3 * K * es + 3 * V * es + g))
+    # bwd_chain: read -W^T, k~, (gamma q)^T, dO^T, dEl^T ; write dE^T, dS' checkpoints
     m["bwd_chain"] = ("hbm", th * (3 * K * es + 3 * V * es + g) + nch * V * K * es)
-    # bwd_post: read q,k,k~,v,dO,E^T,dE^T,T, S and dS' ckpts ; write dq, dv, dk_read, dk~ (fp32), dbeta, dg
-    m["bwd_post"] = ("hbm", th * (3 * K * es + 4 * V * es + C * es + 2 * g + K * es + V * es + 2 * K * 4 + 2 * g)
-                     + 2 * nch * V * K * es)
+    # bwd_post: read q, k, k~, v, dO, E^T, dE^T, T, S and dS' ckpts ; write dq, dv, dk (read side), dk~, dbeta, dg
+    m["bwd_post"] = ("hbm", th * (6 * K * es + 5 * V * es + C * es + 4 * g) + 2 * nch * V * K * es)
     flops = {
         "chunk_prep": th * (C * K + C * K + C * V + C * C / 3.0),               # Gram, W, U (half), inverse
         "state_fwd": th * 4 * K * V,

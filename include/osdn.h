@@ -90,6 +90,23 @@ int osdn_precond_update(const osdn_params *p, const void *k, const float *beta,
                         float *d_ckpt, void *stream);
 
 /*
+ * The same map as osdn_fwd in its recurrent form, for short inputs: the decode step of
+ * Appendix K (state gate, rank-one write with the scaled key, read, then the preconditioner
+ * update with its projection), token by token for 1 <= T <= 64 tokens in one launch, the state
+ * in registers and fp32 throughout (k~ is not rounded to io_dtype here).  No workspace.
+ *   q, k      [B,T,H,K] io_dtype ;  v [B,T,H,V] io_dtype
+ *   beta      [B,T,H] fp32 ;  log_alpha, retention [B,T,H] fp32 or NULL
+ *   d_in      [B,H,K] fp32 or NULL (=> ones) ;  S_in [B,H,V,K] fp32 or NULL (=> zeros)
+ *   o         [B,T,H,V] io_dtype  out
+ *   S_out     [B,H,V,K] fp32      out; MAY be the same buffer as S_in (updated in place)
+ *   d_out     [B,H,K]   fp32      out; must NOT be d_in (OSDN_ERR_NULL if it is)
+ * T > 64 returns OSDN_ERR_SHAPE (use osdn_fwd); params->chunk is still required to be 64.
+ */
+int osdn_step(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+              const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+              void *o, float *S_out, float *d_out, void *stream);
+
+/*
  * Forward (both phases).
  *   q, k      [B,T,H,K] io_dtype ;  v [B,T,H,V] io_dtype
  *   beta      [B,T,H] fp32 ; log_alpha [B,T,H] fp32 (<= 0) or NULL (=> ungated, alpha = 1)

@@ -62,6 +62,8 @@ def lib():
         L.osdn_fwd.argtypes = [pp, vp, vp, vp, fp, fp, fp, fp, fp, vp, fp, fp, vp, ctypes.c_size_t, vp]
         L.osdn_bwd.restype = ctypes.c_int
         L.osdn_bwd.argtypes = [pp] + [vp] * 19 + [vp, ctypes.c_size_t, vp]
+        L.osdn_step.restype = ctypes.c_int
+        L.osdn_step.argtypes = [pp, vp, vp, vp, fp, fp, fp, fp, fp, vp, fp, fp, vp]
         L.osdn_profile_enable.restype = None
         L.osdn_profile_enable.argtypes = [ctypes.c_int]
         L.osdn_profile_kernel_count.restype = ctypes.c_int
@@ -133,6 +135,19 @@ def osdn_precond_update(params, k, beta, retention, d_in, k_tilde, d_out, d_ckpt
         _ptr(retention, f32, (p.B, p.T, p.H), "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
         _ptr(k_tilde, io, (p.B, p.T, p.H, p.K), "k_tilde"), _ptr(d_out, f32, (p.B, p.H, p.K), "d_out"),
         _ptr(d_ckpt, f32, None, "d_ckpt"), _stream_ptr(stream)))
+
+
+def osdn_step(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, stream=None):
+    p = params
+    io, f32 = _io_torch_dtype(p), torch.float32
+    bth, bthk, bthv = (p.B, p.T, p.H), (p.B, p.T, p.H, p.K), (p.B, p.T, p.H, p.V)
+    _check(lib().osdn_step(
+        ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
+        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
+        _ptr(retention, f32, bth, "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
+        _ptr(S_in, f32, (p.B, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
+        _ptr(S_out, f32, (p.B, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (p.B, p.H, p.K), "d_out"),
+        _stream_ptr(stream)))
 
 
 def osdn_fwd(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, workspace,
@@ -225,6 +240,21 @@ def backward(ctx, dO, dS_out=None, dd_out=None):
              g["dq"], g["dk"], g["dv"], g["dbeta"], g["dlog_alpha"], g["dretention"], g["dd_in"],
              g["dS_in"], ctx["workspace"])
     return g
+
+
+def step(q, k, v, beta, log_alpha=None, retention=None, d_in=None, S_in=None, hp: Hyper = Hyper(),
+         in_place: bool = False):
+    """Recurrent form for 1..64 tokens: returns (o, S_out, d_out); with in_place the state S_in
+    is updated where it is (and returned)."""
+    B, T, H, K = k.shape
+    V = v.shape[-1]
+    p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp)
+    f32 = dict(dtype=torch.float32, device=k.device)
+    o = torch.empty_like(v)
+    S_out = S_in if (in_place and S_in is not None) else torch.empty(B, H, V, K, **f32)
+    d_out = torch.empty(B, H, K, **f32)
+    osdn_step(p, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out)
+    return o, S_out, d_out
 
 
 def precond_update(k, beta, retention=None, d_in=None, hp: Hyper = Hyper(), want_ckpt: bool = False):

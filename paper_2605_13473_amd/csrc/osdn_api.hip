@@ -16,10 +16,10 @@ using namespace osdn;
 // Optional per-kernel timing with HIP events on the caller's stream (off by default; the
 // only process-wide state the library has).  Not thread-safe; meant for benchmarks.
 enum { KID_PRECOND_FWD, KID_CHUNK_PREP, KID_STATE_FWD, KID_OUTPUT_FWD, KID_BWD_LOCAL, KID_BWD_CHAIN,
-       KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_COUNT };
+       KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_STEP, KID_COUNT };
 const char *const kKernelNames[KID_COUNT] = {"precond_fwd", "chunk_prep", "state_fwd", "output_fwd",
                                              "bwd_local", "bwd_chain", "bwd_post", "precond_mask",
-                                             "precond_chain", "precond_post"};
+                                             "precond_chain", "precond_post", "step"};
 struct Timed { int id; hipEvent_t e0, e1; };
 bool g_prof_on = false;
 std::vector<Timed> g_prof;
@@ -214,6 +214,26 @@ int osdn_precond_update(const osdn_params *p, const void *k, const float *beta,
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = p->io_dtype == OSDN_BF16;
     if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(a, bf, st); }) != 0) return OSDN_ERR_SHAPE;
+    return launch_status();
+}
+
+int osdn_step(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+              const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+              void *o, float *S_out, float *d_out, void *stream) {
+    int rc = check_params(p, false);
+    if (rc != OSDN_OK) return rc;
+    if (p->T > C || p->V < 64 || p->V > 512 || p->V % 64 != 0) return OSDN_ERR_SHAPE;
+    if (!q || !k || !v || !beta || !o || !S_out || !d_out) return OSDN_ERR_NULL;
+    if (d_out == d_in) return OSDN_ERR_NULL;         // every workgroup of a chain reads d_in
+    StepArgs a{};
+    a.B = p->B; a.T = p->T; a.H = p->H; a.K = p->K; a.V = p->V;
+    a.scale = p->scale; a.eta = p->eta; a.d_min = p->d_min; a.d_max = p->d_max; a.eps = p->eps;
+    a.beta_aware = p->beta_aware;
+    a.q = q; a.k = k; a.v = v; a.beta = beta; a.log_alpha = log_alpha; a.retention = retention;
+    a.d_in = d_in; a.S_in = S_in; a.o = o; a.S_out = S_out; a.d_out = d_out;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool bf = p->io_dtype == OSDN_BF16;
+    if (timed(KID_STEP, st, [&] { return launch_step(a, bf, st); }) != 0) return OSDN_ERR_SHAPE;
     return launch_status();
 }
 

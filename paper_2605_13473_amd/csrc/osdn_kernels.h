@@ -43,6 +43,18 @@ struct PrecondBwdArgs {
     float *dd_in;             // [B,H,K]
 };
 
+// The recurrent step (decode): state in registers, 1..64 tokens per launch.
+struct StepArgs {
+    int B, T, H, K, V;
+    float scale, eta, d_min, d_max, eps;
+    int beta_aware;
+    const void *q, *k, *v;            // [B,T,H,*] io
+    const float *beta, *log_alpha, *retention;   // [B,T,H]; log_alpha, retention may be null
+    const float *d_in, *S_in;         // [B,H,K], [B,H,V,K]; may be null (ones / zeros)
+    void *o;                          // [B,T,H,V] io
+    float *S_out, *d_out;             // S_out may be S_in (a workgroup reads its rows before it writes them)
+};
+
 // Everything the chunkwise (phase 2) kernels need.  Per-chunk tiles live in the workspace
 // in [B,H,N,rows,cols] order (one contiguous tile per chunk and head).
 struct ChunkArgs {
@@ -79,6 +91,7 @@ struct ChunkArgs {
 };
 
 int launch_precond_fwd(const PrecondArgs &a, bool bf16_io, hipStream_t st);
+int launch_step(const StepArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_post(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);

@@ -1,0 +1,114 @@
+"""GPU parity of the recurrent step (decode) entry point against the CPU oracle, and its
+agreement with the chunkwise path (Appendix K: chunk vs. single-token kernel, prefill + one
+decode token vs. one chunkwise call on the concatenation)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_13473_amd import binding as ob
+from paper_2605_13473_amd.inputs import make_stress_inputs
+from tests.gpu_util import check, f64, oracle_hp, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_fwd(x, hp):
+    y = f64(x)
+    return oracle.fwd(y["q"], y["k"], y["v"], y["beta"], y.get("log_alpha"), y.get("retention"),
+                      y.get("d_in"), y.get("S_in"), oracle_hp(hp))
+
+
+def _slice_t(x, t0, t1):
+    return {n: (a[:, t0:t1] if (a is not None and n in ("q", "k", "v", "dO", "beta", "log_alpha", "retention"))
+                else a) for n, a in x.items()}
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 64, 64), (2, 5, 3, 64, 128), (1, 64, 2, 128, 192), (3, 17, 1, 128, 64)])
+def test_step_against_oracle(shape, bf16):
+    """1..64 tokens in one launch, stress inputs (large eta, both faces of the box, carried state)."""
+    B, T, H, K, V = shape
+    x = make_stress_inputs(B, T, H, K, V, seed=31, bf16=bf16, retention=0.97)
+    hp = ob.Hyper(eta=0.5)
+    t = to_dev(x, bf16)
+    o, S, d = ob.step(t["q"], t["k"], t["v"], t["beta"], t["log_alpha"], t["retention"], t["d_in"], t["S_in"], hp)
+    torch.cuda.synchronize()
+    oo, oS, od = _oracle_fwd(x, hp)
+    check("o", o, oo, bf16)
+    check("S_out", S, oS, bf16)
+    check("d_out", d, od, False)
+
+
+def test_token_by_token_equals_one_call_and_updates_in_place():
+    """Sixteen launches of one token each, state carried in place, against one launch of 16."""
+    B, T, H, K, V = 2, 16, 2, 128, 64
+    x = make_stress_inputs(B, T, H, K, V, seed=32, bf16=False, retention=0.95)
+    hp = ob.Hyper(eta=0.3)
+    t = to_dev(x, False)
+    o_all, S_all, d_all = ob.step(t["q"], t["k"], t["v"], t["beta"], t["log_alpha"], t["retention"],
+                                  t["d_in"], t["S_in"], hp)
+    S = t["S_in"].clone()
+    d = t["d_in"].clone()
+    outs = []
+    for i in range(T):
+        sl = slice(i, i + 1)
+        o, S2, d = ob.step(t["q"][:, sl].contiguous(), t["k"][:, sl].contiguous(), t["v"][:, sl].contiguous(),
+                           t["beta"][:, sl].contiguous(), t["log_alpha"][:, sl].contiguous(),
+                           t["retention"][:, sl].contiguous(), d, S, hp, in_place=True)
+        assert S2.data_ptr() == S.data_ptr()
+        outs.append(o)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.cat(outs, 1), o_all)            # the same arithmetic in the same order
+    assert torch.equal(S, S_all) and torch.equal(d, d_all)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_prefill_then_one_decode_token(bf16):
+    """Chunkwise prefill of 128 tokens + one recurrent step against the oracle on 129 tokens."""
+    B, T, H, K, V = 2, 129, 2, 128, 128
+    x = make_stress_inputs(B, T, H, K, V, seed=33, bf16=bf16, retention=0.98)
+    hp = ob.Hyper(eta=0.2)
+    t = to_dev(x, bf16)
+    pre = {n: (a[:, :128].contiguous() if (a is not None and a.dim() >= 3 and a.shape[1] == T) else a) for n, a in t.items()}
+    last = {n: (a[:, 128:].contiguous() if (a is not None and a.dim() >= 3 and a.shape[1] == T) else a) for n, a in t.items()}
+    o1, S1, d1, _ = ob.forward(pre["q"], pre["k"], pre["v"], pre["beta"], pre["log_alpha"], pre["retention"],
+                               pre["d_in"], pre["S_in"], hp)
+    o2, S2, d2 = ob.step(last["q"], last["k"], last["v"], last["beta"], last["log_alpha"], last["retention"],
+                         d1, S1, hp)
+    torch.cuda.synchronize()
+    oo, oS, od = _oracle_fwd(x, hp)
+    check("o[:128]", o1, oo[:, :128], bf16)
+    check("o[128]", o2, oo[:, 128:], bf16)
+    check("S_out", S2, oS, bf16)
+    check("d_out", d2, od, False)
+
+
+def test_chunk_equals_step_on_one_chunk():
+    """One chunk through the chunkwise kernels and through the recurrent kernel: fp32, so the two
+    evaluation orders agree to fp32 reassociation."""
+    B, T, H, K, V = 1, 64, 2, 64, 64
+    x = make_stress_inputs(B, T, H, K, V, seed=34, bf16=False, retention=0.97)
+    hp = ob.Hyper(eta=0.5)
+    t = to_dev(x, False)
+    args = (t["q"], t["k"], t["v"], t["beta"], t["log_alpha"], t["retention"], t["d_in"], t["S_in"], hp)
+    o1, S1, d1, _ = ob.forward(*args)
+    o2, S2, d2 = ob.step(*args)
+    torch.cuda.synchronize()
+    for name, a, b in (("o", o1, o2), ("S", S1, S2), ("d", d1, d2)):
+        err = (a - b).abs().max().item()
+        assert err <= 1e-4 * max(b.abs().max().item(), 1e-30), (name, err)
+
+
+def test_step_argument_errors():
+    p = ob.make_params(1, 65, 1, 64, 64, False)
+    z = torch.zeros(1, 65, 1, 64, device="cuda")
+    with pytest.raises(ob.OsdnError):        # more than 64 tokens: chunkwise path
+        ob.osdn_step(p, z, z, z, z[..., 0].contiguous(), None, None, None, None, z.clone(),
+                     torch.zeros(1, 1, 64, 64, device="cuda"), torch.zeros(1, 1, 64, device="cuda"))
+    p = ob.make_params(1, 1, 1, 64, 64, False)
+    z = torch.zeros(1, 1, 1, 64, device="cuda")
+    d = torch.ones(1, 1, 64, device="cuda")
+    with pytest.raises(ob.OsdnError):        # d_out must not be d_in
+        ob.osdn_step(p, z, z, z, z[..., 0].contiguous(), None, None, d, None, z.clone(),
+                     torch.zeros(1, 1, 64, 64, device="cuda"), d)

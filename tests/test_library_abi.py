@@ -21,7 +21,8 @@ def _declared_symbols():
 def test_library_exports_every_declared_symbol():
     L = ob.lib()
     names = _declared_symbols()
-    assert {"osdn_fwd", "osdn_bwd", "osdn_precond_update", "osdn_workspace_bytes", "osdn_strerror"} <= set(names)
+    assert {"osdn_fwd", "osdn_bwd", "osdn_precond_update", "osdn_step", "osdn_workspace_bytes",
+            "osdn_strerror"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -60,6 +61,12 @@ def test_argument_errors_before_any_pointer_is_used():
                       ctypes.c_void_p(0x1010), ctypes.c_size_t(1 << 30), None) == -4
     assert L.osdn_fwd(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
                       fake, ctypes.c_size_t(16), None) == -4
+    # the recurrent step takes at most one chunk of tokens, and d_out apart from d_in
+    p = ob.make_params(1, 65, 1, 64, 64, False)
+    assert L.osdn_step(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake, None) == -2
+    p = ob.make_params(1, 1, 1, 64, 64, False)
+    assert L.osdn_step(ctypes.byref(p), fake, fake, fake, fake, None, None, fake, None, fake, fake, fake, None) == -1
+    assert L.osdn_step(ctypes.byref(p), fake, fake, None, fake, None, None, None, None, fake, fake, fake, None) == -1
     # d_ckpt needs whole chunks
     p = ob.make_params(1, 7, 1, 64, 64, False)
     assert L.osdn_precond_update(ctypes.byref(p), fake, fake, None, None, fake, fake, fake, None) == -2
