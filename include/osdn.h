@@ -29,11 +29,16 @@
  *     enqueue work and return without synchronising.
  *   - Return value: OSDN_OK (0) or a negative osdn_status.  On an argument error nothing
  *     is launched.  osdn_strerror() gives a static description.
- *   - The library keeps no global state (apart from the optional profiling switch at the
- *     end of this file) and allocates no device memory: scratch comes
- *     from the caller's `workspace` (256-byte aligned, at least osdn_workspace_bytes()).
+ *   - The library allocates no device memory: scratch comes from the caller's `workspace`
+ *     (256-byte aligned, at least osdn_workspace_bytes()).  Its only process-wide state is the
+ *     optional profiling switch at the end of this file and, created on first use and kept
+ *     (one per device), a side stream with a few events: osdn_fwd / osdn_bwd run the
+ *     preconditioner phase on it, forked from and joined back into `stream`, so that to the
+ *     caller all work still is ordered as if enqueued on `stream`.  Calls are serialised by a
+ *     mutex while they enqueue.  OSDN_SEGMENTS=1 in the environment keeps everything on `stream`.
+ *   - retention values are assumed >= 0 (they are sigmoid gates in the paper).
  *   - Supported shapes: chunk == 64; T % 64 == 0 for osdn_fwd/osdn_bwd (any T >= 1 for
- *     osdn_precond_update when d_ckpt is NULL); K in {64, 128}; V a multiple of 64 up to
+ *     osdn_precond_update when d_ckpt is NULL, 1 <= T <= 64 for osdn_step); K in {64, 128}; V a multiple of 64 up to
  *     512; B, H >= 1.  Anything else returns OSDN_ERR_SHAPE.
  */
 #ifndef OSDN_H
