@@ -119,7 +119,7 @@ __global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
 // ------------------------------------------------------------- bwd_chain ----
 // Mirror image of state_fwd, right to left: wavefronts 0-3 carry dS (transposed, fp32, in
 // MFMA accumulators), wavefronts 4-7 bring the next chunk's operand tiles into the other LDS
-// buffer (rho . K~ is scaled on the way) and write the dS' checkpoint and dE^T back.
+// buffer and write the dS' checkpoint and dE^T back.
 constexpr int CT_ = 512, CL_ = 256;
 
 template <typename T, int K>
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     constexpr int NWV = C * K / VN / LTN;
     constexpr int NUV = VS * C / VN / LTN;
     static_assert(VS * C / VN % LTN == 0 && C * K / VN % LTN == 0, "tiles must split evenly over the loaders");
-    __shared__ __attribute__((aligned(16))) T Krn[NB][C * LDK];     // rho . K~   [i][kf]
+    __shared__ __attribute__((aligned(16))) T Krt[NB][K * LDC];     // (rho . K~)^T   [kf][i], as chunk_prep left it
     __shared__ __attribute__((aligned(16))) T Wtt[NB][K * LDC];     // -W^T        [kf][i]
     __shared__ __attribute__((aligned(16))) T Qtt[NB][K * LDC];     // (scale gamma . Q)^T
     __shared__ __attribute__((aligned(16))) T dOts[NB][VS * LDC];   // dO^T slice  [v][i]
@@ -169,14 +169,14 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     {                                                                                            \
         const size_t bhn_ = bh * a.N + (n_);                                                     \
         const size_t tok_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                      \
-        const T *kg = static_cast<const T *>(a.kt) + tok_ * K;                                   \
+        const T *kg = static_cast<const T *>(a.Ktr) + bhn_ * K * C;                              \
         const T *wg = static_cast<const T *>(a.Wt) + bhn_ * K * C;                               \
         const T *qg = static_cast<const T *>(a.Qt) + bhn_ * K * C;                               \
         const T *og = static_cast<const T *>(a.dOt) + (bhn_ * a.V + vs) * C;                     \
         const T *eg = static_cast<const T *>(a.dElt) + (bhn_ * a.V + vs) * C;                    \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
-            const int i = lti + m * LTN, r = i / (K / VN), c = (i % (K / VN)) * VN;               \
-            kreg[m] = *reinterpret_cast<const u32x4 *>(kg + (size_t)r * tstride * K + c);        \
+            const int i = lti + m * LTN;                                                          \
+            kreg[m] = *reinterpret_cast<const u32x4 *>(kg + (size_t)i * VN);                     \
             wreg[m] = *reinterpret_cast<const u32x4 *>(wg + (size_t)i * VN);                     \
             qreg[m] = *reinterpret_cast<const u32x4 *>(qg + (size_t)i * VN);                     \
         }                                                                                        \
@@ -193,11 +193,8 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         const float GC_ = __shfl(G_, 63, 64);                                                    \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
             const int i = lti + m * LTN;                                                          \
-            { const int r = i / (K / VN), c = (i % (K / VN)) * VN;                               \
-              const float rho = __expf(GC_ - __shfl(G_, r, 64));                                 \
-              _Pragma("unroll") for (int e = 0; e < VN; ++e)                                     \
-                  Krn[buf_][r * LDK + c + e] = from_f32<T>(rho * vec_get<T>(kreg[m], e)); }      \
             { const int r = i / (C / VN), c = (i % (C / VN)) * VN;                               \
+              *reinterpret_cast<u32x4 *>(&Krt[buf_][r * LDC + c]) = kreg[m];                     \
               *reinterpret_cast<u32x4 *>(&Wtt[buf_][r * LDC + c]) = wreg[m];                     \
               *reinterpret_cast<u32x4 *>(&Qtt[buf_][r * LDC + c]) = qreg[m]; }                   \
         }                                                                                        \
@@ -254,7 +251,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-                mma_tile<T, true, true>(acc, &Krn[buf][wave * 16 * LDK], LDK, dSb + vt * 16 * LDK, LDK, K, lane);
+                mma_tile<T, false, true>(acc, &Krt[buf][wave * 16], LDC, dSb + vt * 16 * LDK, LDK, K, lane);
                 const T *ep = &dEls[buf][(vt * 16 + acc_col(lane)) * LDC + wave * 16 + acc_row(lane, 0)];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[r] += to_f32(ep[r]);
