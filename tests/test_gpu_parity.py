@@ -119,6 +119,24 @@ def test_resume_split_sequence():
     compare_forward(x, hp, False)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_largest_supported_head(bf16):
+    """K = 128, V = 512: the largest tiles every kernel is built for (LDS and register limits),
+    with three segments of chunks so that every carry across a segment boundary is exercised."""
+    B, T, H, K, V = 1, 64 * 60, 1, 128, 512
+    x = make_stress_inputs(B, T, H, K, V, seed=27, bf16=bf16, retention=0.97)
+    compare_forward(x, ob.Hyper(eta=0.3), bf16)
+    compare_backward(x, ob.Hyper(eta=0.3), bf16)
+
+
+def test_single_chunk_and_two_chunks():
+    """T = 64 (one segment, no side stream) and T = 128 (two segments of one chunk)."""
+    for T in (64, 128):
+        x = make_stress_inputs(2, T, 2, 128, 64, seed=26, bf16=True, retention=0.95)
+        compare_forward(x, ob.Hyper(eta=0.5), True)
+        compare_backward(x, ob.Hyper(eta=0.5), True)
+
+
 def test_degenerate_inputs():
     """Zero keys (squared norm floored by eps), beta at 0 and 1, zero gate (alpha = 1) and a
     very strong gate, d_in on the faces of the box."""
