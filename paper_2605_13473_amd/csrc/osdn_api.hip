@@ -353,23 +353,30 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
                  : kid == KID_BWD_CHAIN ? launch_bwd_chain(c, bf, st) : launch_bwd_post(c, bf, st);
         });
     };
+    // the box masks depend on the forward pass only: one launch for the whole sequence, up front
+    auto masks = [&](hipStream_t s1) {
+        if (!(pb.d_min <= pb.d_max)) return 0;
+        pb.n0 = 0; pb.n1 = N;
+        return timed(KID_PRECOND_MASK, s1, [&] { return launch_precond_mask(pb, bf, s1); });
+    };
     auto phase1 = [&](int sidx, hipStream_t s1) {
         seg_range(sidx, pb.n0, pb.n1);
         pb.dd_out = sidx == S - 1 ? dd_out : dd_in;  // the adjoint of d is carried in dd_in
-        if (pb.d_min <= pb.d_max &&
-            timed(KID_PRECOND_MASK, s1, [&] { return launch_precond_mask(pb, bf, s1); }) != 0) return -1;
         if (timed(KID_PRECOND_CHAIN, s1, [&] { return launch_precond_chain(pb, bf, s1); }) != 0) return -1;
         return timed(KID_PRECOND_POST, s1, [&] { return launch_precond_post(pb, bf, s1); });
     };
     if (!pl) {
         if (phase2(KID_BWD_LOCAL, 0) != 0 || phase2(KID_BWD_CHAIN, 0) != 0 || phase2(KID_BWD_POST, 0) != 0 ||
-            phase1(0, st) != 0)
+            masks(st) != 0 || phase1(0, st) != 0)
             return OSDN_ERR_SHAPE;
         return launch_status();
     }
     // main: phase 2, segments right to left          (a[s]: phase 2 of segment s done)
-    // side: phase 1 of segment s once a[s] has fired; joined back at the end
+    // side: the masks at once, then phase 1 of segment s once a[s] has fired; joined back at the end
     hipStream_t s1 = pl->side;
+    OSDN_HIP_OK(hipEventRecord(pl->fork, st));
+    OSDN_HIP_OK(hipStreamWaitEvent(s1, pl->fork, 0));
+    if (masks(s1) != 0) return OSDN_ERR_SHAPE;
     for (int s = S - 1; s >= 0; --s) {
         if (phase2(KID_BWD_LOCAL, s) != 0 || phase2(KID_BWD_CHAIN, s) != 0 || phase2(KID_BWD_POST, s) != 0)
             return OSDN_ERR_SHAPE;
