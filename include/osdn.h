@@ -37,8 +37,10 @@
  *     caller all work still is ordered as if enqueued on `stream`.  Calls are serialised by a
  *     mutex while they enqueue.  OSDN_SEGMENTS=1 in the environment keeps everything on `stream`.
  *   - retention values are assumed >= 0 (they are sigmoid gates in the paper).
- *   - Supported shapes: chunk == 64; T % 64 == 0 for osdn_fwd/osdn_bwd (any T >= 1 for
- *     osdn_precond_update when d_ckpt is NULL, 1 <= T <= 64 for osdn_step); K in {64, 128}; V a multiple of 64 up to
+ *   - Supported shapes: chunk == 64; any T >= 1 (osdn_fwd/osdn_bwd pad a ragged last chunk
+ *     inside the workspace with tokens that change nothing; osdn_precond_update needs
+ *     T % 64 == 0 only when d_ckpt is asked for; 1 <= T <= 64 for osdn_step); K in {64, 128};
+ *     V a multiple of 64 up to
  *     512; B, H >= 1.  Anything else returns OSDN_ERR_SHAPE.
  */
 #ifndef OSDN_H

@@ -16,10 +16,10 @@ using namespace osdn;
 // Optional per-kernel timing with HIP events on the caller's stream (off by default; the
 // only process-wide state the library has).  Not thread-safe; meant for benchmarks.
 enum { KID_PRECOND_FWD, KID_CHUNK_PREP, KID_STATE_FWD, KID_OUTPUT_FWD, KID_BWD_LOCAL, KID_BWD_CHAIN,
-       KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_STEP, KID_COUNT };
+       KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_STEP, KID_PAD, KID_COUNT };
 const char *const kKernelNames[KID_COUNT] = {"precond_fwd", "chunk_prep", "state_fwd", "output_fwd",
                                              "bwd_local", "bwd_chain", "bwd_post", "precond_mask",
-                                             "precond_chain", "precond_post", "step"};
+                                             "precond_chain", "precond_post", "step", "pad"};
 struct Timed { int id; hipEvent_t e0, e1; };
 bool g_prof_on = false;
 std::vector<Timed> g_prof;
@@ -38,6 +38,9 @@ template <typename F> int timed(int id, hipStream_t st, F &&launch) {
 struct Layout {
     size_t kt, d_ckpt, tok_scalars, Tm, W, Wt, Ktr, Ut, Et, S_ckpt;   // forward
     size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;   // backward only
+    // padded copies of the caller's tensors, only when T is not a multiple of the chunk length
+    size_t p_q, p_k, p_v, p_beta, p_g, p_r, p_o;                        // forward
+    size_t p_dO, p_dq, p_dk, p_dv, p_dbeta, p_dg, p_dr;                 // backward
     size_t total_fwd, total_bwd;
 };
 
@@ -49,7 +52,6 @@ int check_params(const osdn_params *p, bool need_chunks) {
     if (p->B < 1 || p->T < 1 || p->H < 1 || p->chunk != C) return OSDN_ERR_SHAPE;
     if (p->K != 64 && p->K != 128) return OSDN_ERR_SHAPE;
     if (need_chunks) {
-        if (p->T % C != 0) return OSDN_ERR_SHAPE;
         if (p->V < 64 || p->V > 512 || p->V % 64 != 0) return OSDN_ERR_SHAPE;
         if (p->B > 65535 || p->H > 65535) return OSDN_ERR_SHAPE;
     }
@@ -62,8 +64,9 @@ int check_params(const osdn_params *p, bool need_chunks) {
 
 Layout make_layout(const osdn_params *p) {
     const size_t es = p->io_dtype == OSDN_BF16 ? 2 : 4;
-    const size_t B = p->B, T = p->T, H = p->H, K = p->K, V = p->V, N = T / C;
-    Layout L;
+    const size_t B = p->B, H = p->H, K = p->K, V = p->V, N = ((size_t)p->T + C - 1) / C, T = N * C;
+    const bool ragged = T != (size_t)p->T;      // every buffer is sized for whole chunks
+    Layout L{};
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
     L.kt = take(B * T * H * K * es);
@@ -76,6 +79,11 @@ Layout make_layout(const osdn_params *p) {
     L.Ut = take(B * T * H * V * es);
     L.Et = take(B * T * H * V * es);
     L.S_ckpt = take(B * H * N * V * K * es);
+    if (ragged) {
+        L.p_q = take(B * T * H * K * es); L.p_k = take(B * T * H * K * es);
+        L.p_v = take(B * T * H * V * es); L.p_o = take(B * T * H * V * es);
+        L.p_beta = take(B * T * H * 4); L.p_g = take(B * T * H * 4); L.p_r = take(B * T * H * 4);
+    }
     L.total_fwd = off;
     L.dElt = take(B * T * H * V * es);
     L.Qt = take(B * T * H * K * es);
@@ -86,6 +94,11 @@ Layout make_layout(const osdn_params *p) {
     L.dkt = take(B * T * H * K * es);
     L.masks = take(B * H * N * K * 8);
     L.a_ckpt = take(B * H * N * K * 4);
+    if (ragged) {
+        L.p_dO = take(B * T * H * V * es); L.p_dv = take(B * T * H * V * es);
+        L.p_dq = take(B * T * H * K * es); L.p_dk = take(B * T * H * K * es);
+        L.p_dbeta = take(B * T * H * 4); L.p_dg = take(B * T * H * 4); L.p_dr = take(B * T * H * 4);
+    }
     L.total_bwd = off;
     return L;
 }
@@ -191,7 +204,7 @@ const char *osdn_strerror(int status) {
     switch (status) {
         case OSDN_OK: return "ok";
         case OSDN_ERR_NULL: return "a required pointer is NULL";
-        case OSDN_ERR_SHAPE: return "unsupported shape (chunk must be 64, T % 64 == 0, K in {64,128}, V % 64 == 0, V <= 512)";
+        case OSDN_ERR_SHAPE: return "unsupported shape (chunk must be 64, K in {64,128}, V % 64 == 0, V <= 512, at most 64 tokens per osdn_step)";
         case OSDN_ERR_DTYPE: return "io_dtype must be OSDN_F32 or OSDN_BF16";
         case OSDN_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned";
         case OSDN_ERR_PARAM: return "invalid scalar parameter (eta < 0, eps <= 0 or non-finite)";
@@ -251,6 +264,34 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = p->io_dtype == OSDN_BF16;
 
+    // a ragged last chunk: work on padded copies (no-op pad tokens) and cut the output at the end
+    osdn_params padded = *p;
+    padded.T = (p->T + C - 1) / C * C;
+    const int T_user = p->T;
+    const bool ragged = padded.T != T_user;
+    void *o_user = o;
+    if (ragged) {
+        const size_t es = bf ? 2 : 4, rk = (size_t)p->H * p->K * es, rv = (size_t)p->H * p->V * es, rg = (size_t)p->H * 4;
+        auto pad = [&](const void *src, size_t off, size_t row, uint32_t fill) {
+            return timed(KID_PAD, st, [&] { return launch_copy_rows(src, T_user, ws + off, padded.T, p->B, row, fill, st); });
+        };
+        if (pad(q, L.p_q, rk, 0u) != 0 || pad(k, L.p_k, rk, 0u) != 0 || pad(v, L.p_v, rv, 0u) != 0 ||
+            pad(beta, L.p_beta, rg, 0u) != 0 || (log_alpha && pad(log_alpha, L.p_g, rg, 0u) != 0) ||
+            (retention && pad(retention, L.p_r, rg, 0x3f800000u) != 0))
+            return OSDN_ERR_SHAPE;
+        q = ws + L.p_q; k = ws + L.p_k; v = ws + L.p_v; o = ws + L.p_o;
+        beta = reinterpret_cast<const float *>(ws + L.p_beta);
+        if (log_alpha) log_alpha = reinterpret_cast<const float *>(ws + L.p_g);
+        if (retention) retention = reinterpret_cast<const float *>(ws + L.p_r);
+        p = &padded;
+    }
+    auto finish = [&]() -> int {
+        if (ragged &&
+            timed(KID_PAD, st, [&] { return launch_copy_rows(o, padded.T, o_user, T_user, p->B, (size_t)p->H * p->V * (bf ? 2 : 4), 0u, st); }) != 0)
+            return OSDN_ERR_SHAPE;
+        return launch_status();
+    };
+
     PrecondArgs pa = precond_args(p);
     pa.k = k; pa.beta = beta; pa.retention = retention;
     pa.k_tilde = ws + L.kt; pa.d_out = d_out; pa.d_ckpt = reinterpret_cast<float *>(ws + L.d_ckpt);
@@ -282,7 +323,7 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
         if (precond(0, st) != 0 || phase2(KID_CHUNK_PREP, 0) != 0 || phase2(KID_STATE_FWD, 0) != 0 ||
             phase2(KID_OUTPUT_FWD, 0) != 0)
             return OSDN_ERR_SHAPE;
-        return launch_status();
+        return finish();
     }
     // side: phase 1, segment after segment          (a[s]: phase 1 of segment s done)
     // main: phase 2 of segment s once a[s] has fired
@@ -298,7 +339,7 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
         if (phase2(KID_CHUNK_PREP, s) != 0 || phase2(KID_STATE_FWD, s) != 0 || phase2(KID_OUTPUT_FWD, s) != 0)
             return OSDN_ERR_SHAPE;
     }
-    return launch_status();
+    return finish();
 }
 
 int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
@@ -318,6 +359,41 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = p->io_dtype == OSDN_BF16;
+
+    // a ragged last chunk: the padded inputs are the ones osdn_fwd left in the workspace; dO is
+    // padded here, the gradients are produced padded and cut at the end
+    osdn_params padded = *p;
+    padded.T = (p->T + C - 1) / C * C;
+    const int T_user = p->T;
+    const bool ragged = padded.T != T_user;
+    void *dq_user = dq, *dk_user = dk, *dv_user = dv;
+    float *dbeta_user = dbeta, *dg_user = dlog_alpha, *dr_user = dretention;
+    const size_t es_ = bf ? 2 : 4, rk_ = (size_t)p->H * p->K * es_, rv_ = (size_t)p->H * p->V * es_, rg_ = (size_t)p->H * 4;
+    if (ragged) {
+        if (timed(KID_PAD, st, [&] { return launch_copy_rows(dO, T_user, ws + L.p_dO, padded.T, p->B, rv_, 0u, st); }) != 0)
+            return OSDN_ERR_SHAPE;
+        q = ws + L.p_q; k = ws + L.p_k; v = ws + L.p_v; dO = ws + L.p_dO;
+        beta = reinterpret_cast<const float *>(ws + L.p_beta);
+        if (log_alpha) log_alpha = reinterpret_cast<const float *>(ws + L.p_g);
+        if (retention) retention = reinterpret_cast<const float *>(ws + L.p_r);
+        dq = ws + L.p_dq; dk = ws + L.p_dk; dv = ws + L.p_dv;
+        dbeta = reinterpret_cast<float *>(ws + L.p_dbeta);
+        dlog_alpha = reinterpret_cast<float *>(ws + L.p_dg);
+        dretention = reinterpret_cast<float *>(ws + L.p_dr);
+        p = &padded;
+    }
+    auto finish = [&]() -> int {
+        if (ragged) {
+            auto cut = [&](const void *src, void *dst, size_t row) {
+                return timed(KID_PAD, st, [&] { return launch_copy_rows(src, padded.T, dst, T_user, p->B, row, 0u, st); });
+            };
+            if (cut(dq, dq_user, rk_) != 0 || cut(dk, dk_user, rk_) != 0 || cut(dv, dv_user, rv_) != 0 ||
+                cut(dbeta, dbeta_user, rg_) != 0 || (log_alpha && cut(dlog_alpha, dg_user, rg_) != 0) ||
+                (retention && cut(dretention, dr_user, rg_) != 0))
+                return OSDN_ERR_SHAPE;
+        }
+        return launch_status();
+    };
 
     ChunkArgs c = chunk_args(p, L, ws);
     c.q = q; c.k = k; c.v = v; c.beta = beta; c.log_alpha = log_alpha;
@@ -369,7 +445,7 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
         if (phase2(KID_BWD_LOCAL, 0) != 0 || phase2(KID_BWD_CHAIN, 0) != 0 || phase2(KID_BWD_POST, 0) != 0 ||
             masks(st) != 0 || phase1(0, st) != 0)
             return OSDN_ERR_SHAPE;
-        return launch_status();
+        return finish();
     }
     // main: phase 2, segments right to left          (a[s]: phase 2 of segment s done)
     // side: the masks at once, then phase 1 of segment s once a[s] has fired; joined back at the end
@@ -388,7 +464,7 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     }
     OSDN_HIP_OK(hipEventRecord(pl->join, s1));
     OSDN_HIP_OK(hipStreamWaitEvent(st, pl->join, 0));
-    return launch_status();
+    return finish();
 }
 
 void osdn_profile_enable(int on) { g_prof_on = on != 0; }

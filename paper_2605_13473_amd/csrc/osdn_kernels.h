@@ -92,6 +92,8 @@ struct ChunkArgs {
 
 int launch_precond_fwd(const PrecondArgs &a, bool bf16_io, hipStream_t st);
 int launch_step(const StepArgs &a, bool bf16_io, hipStream_t st);
+int launch_copy_rows(const void *src, int Ts, void *dst, int Td, int B, size_t row_bytes, uint32_t fill,
+                     hipStream_t st);
 int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_post(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);

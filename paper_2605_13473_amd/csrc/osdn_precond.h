@@ -5,7 +5,8 @@
 namespace osdn {
 
 constexpr int P1_MAX_SWEEPS = 66;       // 64 guarantee exactness
-constexpr float P1_TOL = 1e-6f;         // relative agreement of the inner products between sweeps
+constexpr float P1_TOL = 1e-6f;         // relative agreement of the inner products between sweeps (forward)
+constexpr float P1_TOL_BWD = 1e-7f;     // ... of sigma in the reverse sweep, whose errors add up in the adjoint of d
 constexpr int PB = 8;                   // tokens per LDS prefetch block in the sequential loops
 
 // projection onto [lo, hi] as one median-of-three (lo = -inf, hi = +inf when there is none)

@@ -197,8 +197,8 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
                 const float dcur = wave_max(fabsf(sg_ - sig[i]));
                 // converged, or (from the second pass on) the observed contraction ratio says
                 // that the next difference would be below the tolerance
-                const bool all_ok = dcur <= P1_TOL * mx ||
-                                    (sweep >= 1 && dcur <= 0.1f * dprev && dcur * dcur <= P1_TOL * mx * dprev);
+                const bool all_ok = dcur <= P1_TOL_BWD * mx ||
+                                    (sweep >= 1 && dcur <= 0.1f * dprev && dcur * dcur <= P1_TOL_BWD * mx * dprev);
                 dprev = dcur;
                 sig[i] = sg_;
                 casig[i] = cas[i] * sg_;

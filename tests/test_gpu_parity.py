@@ -137,6 +137,20 @@ def test_single_chunk_and_two_chunks():
         compare_backward(x, ob.Hyper(eta=0.5), True)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("T", [1, 37, 65, 200])
+def test_ragged_lengths(T, bf16):
+    """T not a multiple of the chunk length: padded inside the library with no-op tokens."""
+    B, H, K, V = 2, 2, 64, 128
+    x = make_stress_inputs(B, T, H, K, V, seed=25, bf16=bf16, retention=0.96)
+    rng = np.random.default_rng(T)
+    dS = rng.standard_normal((B, H, V, K)).astype(np.float32)
+    dd = rng.standard_normal((B, H, K)).astype(np.float32)
+    compare_forward(x, ob.Hyper(eta=0.4), bf16)
+    compare_backward(x, ob.Hyper(eta=0.4), bf16, dS, dd)
+    compare_backward(x, ob.Hyper(eta=0.4, beta_aware=False), bf16, dS, dd)
+
+
 def test_degenerate_inputs():
     """Zero keys (squared norm floored by eps), beta at 0 and 1, zero gate (alpha = 1) and a
     very strong gate, d_in on the faces of the box."""

@@ -33,7 +33,10 @@ def test_workspace_size_and_shape_validation():
     assert 0 < fwd < bwd
     # at least k~ plus W, U, E^T and the per-chunk state
     assert fwd >= 4 * 4096 * 16 * 128 * 2 * 4
-    for bad in (dict(T=100), dict(K=256), dict(K=96), dict(V=96), dict(chunk=32), dict(B=0)):
+    # a ragged length costs the padded copies of the caller's tensors on top
+    q = ob.make_params(4, 4096 - 7, 16, 128, 128, True)
+    assert ob.osdn_workspace_bytes(q, False) > fwd and ob.osdn_workspace_bytes(q, True) > bwd
+    for bad in (dict(T=0), dict(K=256), dict(K=96), dict(V=96), dict(chunk=32), dict(B=0)):
         q = ob.make_params(1, 128, 1, 64, 64, False)
         for k, v in bad.items():
             setattr(q, k, v)
@@ -43,7 +46,7 @@ def test_workspace_size_and_shape_validation():
 def test_argument_errors_before_any_pointer_is_used():
     L = ob.lib()
     fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
-    p = ob.make_params(1, 100, 1, 64, 64, False)
+    p = ob.make_params(1, 128, 1, 96, 64, False)          # K must be 64 or 128
     rc = L.osdn_fwd(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
                     fake, ctypes.c_size_t(1 << 30), None)
     assert rc == -2 and "shape" in ob.osdn_strerror(rc)
