@@ -40,8 +40,7 @@
  *   - Supported shapes: chunk == 64; any T >= 1 (osdn_fwd/osdn_bwd pad a ragged last chunk
  *     inside the workspace with tokens that change nothing; osdn_precond_update needs
  *     T % 64 == 0 only when d_ckpt is asked for; 1 <= T <= 64 for osdn_step); K in {64, 128};
- *     V a multiple of 64 up to
- *     512; B, H >= 1.  Anything else returns OSDN_ERR_SHAPE.
+ *     V a multiple of 64 up to 512; B, H >= 1.  Anything else returns OSDN_ERR_SHAPE.
  */
 #ifndef OSDN_H
 #define OSDN_H
@@ -146,6 +145,43 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
              const void *dO, const float *dS_out, const float *dd_out, void *dq, void *dk, void *dv,
              float *dbeta, float *dlog_alpha, float *dretention, float *dd_in, float *dS_in,
              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Packed sequences (the training set-up in the appendix on training and evaluation details,
+ * paragraph on optimizer, batch and precision: one long token axis per device that holds
+ * variable-length segments back to back, their boundaries in cu_seqlens, the recurrent state
+ * reset at every boundary).  The _packed entry points are osdn_fwd / osdn_bwd for that input:
+ *   params->B must be 1 and params->T the total number of tokens;
+ *   cu_seqlens  HOST pointer to n_seqs + 1 ascending int32 token offsets, cu_seqlens[0] = 0,
+ *               cu_seqlens[n_seqs] = T; sequence s is the tokens [cu_seqlens[s], cu_seqlens[s+1]);
+ *               read before the call returns (it need not outlive the call); every sequence
+ *               has at least one token, else OSDN_ERR_SHAPE;
+ *   token tensors (q, k, v, beta, log_alpha, retention, o, dO and the token gradients) are
+ *               [1,T,H,*] as before;
+ *   carried tensors have one entry per sequence: d_in, d_out, dd_out, dd_in are [n_seqs,H,K];
+ *               S_in, S_out, dS_out, dS_in are [n_seqs,H,V,K].  Every sequence starts from its own
+ *               d_in / S_in entry (NULL => ones / zeros: the reset) and leaves its own final
+ *               d and S; no state crosses a boundary.
+ * Sequences need not be whole chunks: inside the workspace each sequence is moved to start on
+ * a chunk boundary and padded with tokens that change nothing (no copies are made when every
+ * length is a multiple of 64).  The sequential kernels run one chain per (sequence, head).
+ * osdn_workspace_bytes_packed sizes the workspace for exactly this cu_seqlens (0 on invalid
+ * arguments); osdn_bwd_packed takes the same cu_seqlens and the workspace osdn_fwd_packed filled.
+ */
+size_t osdn_workspace_bytes_packed(const osdn_params *p, const int32_t *cu_seqlens, int32_t n_seqs,
+                                   int for_backward);
+
+int osdn_fwd_packed(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+                    const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+                    void *o, float *S_out, float *d_out, const int32_t *cu_seqlens, int32_t n_seqs,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+int osdn_bwd_packed(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+                    const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+                    const void *dO, const float *dS_out, const float *dd_out, void *dq, void *dk, void *dv,
+                    float *dbeta, float *dlog_alpha, float *dretention, float *dd_in, float *dS_in,
+                    const int32_t *cu_seqlens, int32_t n_seqs, void *workspace, size_t workspace_bytes,
+                    void *stream);
 
 /*
  * Optional per-kernel timing (for benchmarks; off by default; not thread-safe -- this switch

@@ -62,6 +62,14 @@ def lib():
         L.osdn_fwd.argtypes = [pp, vp, vp, vp, fp, fp, fp, fp, fp, vp, fp, fp, vp, ctypes.c_size_t, vp]
         L.osdn_bwd.restype = ctypes.c_int
         L.osdn_bwd.argtypes = [pp] + [vp] * 19 + [vp, ctypes.c_size_t, vp]
+        ip = ctypes.POINTER(ctypes.c_int32)
+        L.osdn_workspace_bytes_packed.restype = ctypes.c_size_t
+        L.osdn_workspace_bytes_packed.argtypes = [pp, ip, ctypes.c_int32, ctypes.c_int]
+        L.osdn_fwd_packed.restype = ctypes.c_int
+        L.osdn_fwd_packed.argtypes = [pp, vp, vp, vp, fp, fp, fp, fp, fp, vp, fp, fp, ip, ctypes.c_int32, vp,
+                                      ctypes.c_size_t, vp]
+        L.osdn_bwd_packed.restype = ctypes.c_int
+        L.osdn_bwd_packed.argtypes = [pp] + [vp] * 19 + [ip, ctypes.c_int32, vp, ctypes.c_size_t, vp]
         L.osdn_step.restype = ctypes.c_int
         L.osdn_step.argtypes = [pp, vp, vp, vp, fp, fp, fp, fp, fp, vp, fp, fp, vp]
         L.osdn_profile_enable.restype = None
@@ -184,6 +192,53 @@ def osdn_bwd(params, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out
         _stream_ptr(stream)))
 
 
+def _cu(cu_seqlens):
+    """Host int32 array of n_seqs + 1 offsets from a sequence of ints."""
+    vals = [int(x) for x in cu_seqlens]
+    return (ctypes.c_int32 * len(vals))(*vals), len(vals) - 1
+
+
+def osdn_workspace_bytes_packed(params: OsdnParams, cu_seqlens, for_backward: bool) -> int:
+    cu, n = _cu(cu_seqlens)
+    return int(lib().osdn_workspace_bytes_packed(ctypes.byref(params), cu, n, int(bool(for_backward))))
+
+
+def osdn_fwd_packed(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, cu_seqlens,
+                    workspace, stream=None):
+    p = params
+    cu, n = _cu(cu_seqlens)
+    io, f32 = _io_torch_dtype(p), torch.float32
+    bth, bthk, bthv = (p.B, p.T, p.H), (p.B, p.T, p.H, p.K), (p.B, p.T, p.H, p.V)
+    _check(lib().osdn_fwd_packed(
+        ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
+        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
+        _ptr(retention, f32, bth, "retention"), _ptr(d_in, f32, (n, p.H, p.K), "d_in"),
+        _ptr(S_in, f32, (n, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
+        _ptr(S_out, f32, (n, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (n, p.H, p.K), "d_out"),
+        cu, n, _ptr(workspace, torch.uint8, None, "workspace"), ctypes.c_size_t(workspace.numel()),
+        _stream_ptr(stream)))
+
+
+def osdn_bwd_packed(params, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out, dd_out,
+                    dq, dk, dv, dbeta, dlog_alpha, dretention, dd_in, dS_in, cu_seqlens, workspace, stream=None):
+    p = params
+    cu, n = _cu(cu_seqlens)
+    io, f32 = _io_torch_dtype(p), torch.float32
+    bth, bthk, bthv = (p.B, p.T, p.H), (p.B, p.T, p.H, p.K), (p.B, p.T, p.H, p.V)
+    bhk, bhvk = (n, p.H, p.K), (n, p.H, p.V, p.K)
+    _check(lib().osdn_bwd_packed(
+        ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
+        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
+        _ptr(retention, f32, bth, "retention"), _ptr(d_in, f32, bhk, "d_in"),
+        _ptr(S_in, f32, bhvk, "S_in"), _ptr(dO, io, bthv, "dO"), _ptr(dS_out, f32, bhvk, "dS_out"),
+        _ptr(dd_out, f32, bhk, "dd_out"), _ptr(dq, io, bthk, "dq"), _ptr(dk, io, bthk, "dk"),
+        _ptr(dv, io, bthv, "dv"), _ptr(dbeta, f32, bth, "dbeta"),
+        _ptr(dlog_alpha, f32, bth, "dlog_alpha"), _ptr(dretention, f32, bth, "dretention"),
+        _ptr(dd_in, f32, bhk, "dd_in"), _ptr(dS_in, f32, bhvk, "dS_in"),
+        cu, n, _ptr(workspace, torch.uint8, None, "workspace"), ctypes.c_size_t(workspace.numel()),
+        _stream_ptr(stream)))
+
+
 # ------------------------------------------------------------- conveniences ----
 @dataclass
 class Hyper:
@@ -209,18 +264,32 @@ def alloc_workspace(params: OsdnParams, for_backward: bool, device="cuda") -> to
 
 
 def forward(q, k, v, beta, log_alpha=None, retention=None, d_in=None, S_in=None, hp: Hyper = Hyper(),
-            for_backward: bool = False, workspace=None):
-    """Allocate outputs (+ workspace) and call osdn_fwd.  Returns (o, S_out, d_out, ctx)."""
+            for_backward: bool = False, workspace=None, cu_seqlens=None):
+    """Allocate outputs (+ workspace) and call osdn_fwd (osdn_fwd_packed when cu_seqlens is
+    given: B == 1, one carried entry per sequence).  Returns (o, S_out, d_out, ctx)."""
     B, T, H, K = k.shape
     V = v.shape[-1]
     p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp)
+    if cu_seqlens is not None:
+        cu_seqlens = [int(x) for x in cu_seqlens]
     if workspace is None:
-        workspace = alloc_workspace(p, for_backward, k.device)
+        if cu_seqlens is None:
+            workspace = alloc_workspace(p, for_backward, k.device)
+        else:
+            n = osdn_workspace_bytes_packed(p, cu_seqlens, for_backward)
+            if n == 0:
+                raise OsdnError(-2)
+            workspace = torch.empty(n, dtype=torch.uint8, device=k.device)
+    nb = B if cu_seqlens is None else len(cu_seqlens) - 1
     o = torch.empty_like(v)
-    S_out = torch.empty(B, H, V, K, dtype=torch.float32, device=k.device)
-    d_out = torch.empty(B, H, K, dtype=torch.float32, device=k.device)
-    osdn_fwd(p, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, workspace)
-    ctx = dict(params=p, inputs=(q, k, v, beta, log_alpha, retention, d_in, S_in), workspace=workspace)
+    S_out = torch.empty(nb, H, V, K, dtype=torch.float32, device=k.device)
+    d_out = torch.empty(nb, H, K, dtype=torch.float32, device=k.device)
+    if cu_seqlens is None:
+        osdn_fwd(p, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, workspace)
+    else:
+        osdn_fwd_packed(p, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, cu_seqlens, workspace)
+    ctx = dict(params=p, inputs=(q, k, v, beta, log_alpha, retention, d_in, S_in), workspace=workspace,
+               cu_seqlens=cu_seqlens)
     return o, S_out, d_out, ctx
 
 
@@ -228,17 +297,24 @@ def backward(ctx, dO, dS_out=None, dd_out=None):
     """Allocate gradients and call osdn_bwd on the context returned by ``forward``."""
     p = ctx["params"]
     q, k, v, beta, log_alpha, retention, d_in, S_in = ctx["inputs"]
+    cu = ctx.get("cu_seqlens")
+    nb = p.B if cu is None else len(cu) - 1
     f32 = dict(dtype=torch.float32, device=k.device)
     g = {
         "dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v),
         "dbeta": torch.empty_like(beta),
         "dlog_alpha": torch.empty_like(beta) if log_alpha is not None else None,
         "dretention": torch.empty_like(beta) if retention is not None else None,
-        "dd_in": torch.empty(p.B, p.H, p.K, **f32), "dS_in": torch.empty(p.B, p.H, p.V, p.K, **f32),
+        "dd_in": torch.empty(nb, p.H, p.K, **f32), "dS_in": torch.empty(nb, p.H, p.V, p.K, **f32),
     }
-    osdn_bwd(p, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out, dd_out,
-             g["dq"], g["dk"], g["dv"], g["dbeta"], g["dlog_alpha"], g["dretention"], g["dd_in"],
-             g["dS_in"], ctx["workspace"])
+    if cu is None:
+        osdn_bwd(p, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out, dd_out,
+                 g["dq"], g["dk"], g["dv"], g["dbeta"], g["dlog_alpha"], g["dretention"], g["dd_in"],
+                 g["dS_in"], ctx["workspace"])
+    else:
+        osdn_bwd_packed(p, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out, dd_out,
+                        g["dq"], g["dk"], g["dv"], g["dbeta"], g["dlog_alpha"], g["dretention"], g["dd_in"],
+                        g["dS_in"], cu, ctx["workspace"])
     return g
 
 

@@ -36,6 +36,7 @@ template <typename F> int timed(int id, hipStream_t st, F &&launch) {
 }
 
 struct Layout {
+    size_t tables;                                                       // packed sequences: the index tables
     size_t kt, d_ckpt, tok_scalars, Tm, W, Wt, Ktr, Ut, Et, S_ckpt;   // forward
     size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;   // backward only
     // padded copies of the caller's tensors, only when T is not a multiple of the chunk length
@@ -62,13 +63,57 @@ int check_params(const osdn_params *p, bool need_chunks) {
     return OSDN_OK;
 }
 
-Layout make_layout(const osdn_params *p) {
+// Host-side description of a batch of packed sequences (n_seqs == 0: a plain [B,T] batch).
+struct Packing {
+    int n_seqs = 0;
+    int N = 0;                   // chunks of the padded token axis (per batch entry)
+    bool ragged = false;         // some sequence is not a whole number of chunks: work on padded copies
+    std::vector<int> tables;     // seq_chunks [n_seqs + 1], chunk_row [N], chunk_len [N]
+};
+
+// cu_seqlens: n_seqs + 1 ascending token offsets, from 0 to T, on the host
+int make_packing(const osdn_params *p, const int32_t *cu, int n_seqs, Packing &pk) {
+    if (!cu) return OSDN_ERR_NULL;
+    if (p->B != 1 || n_seqs < 1 || (long long)n_seqs * p->H > 0x7fffffffLL / 64) return OSDN_ERR_SHAPE;
+    if (cu[0] != 0 || cu[n_seqs] != p->T) return OSDN_ERR_SHAPE;
+    long long N = 0;
+    for (int s = 0; s < n_seqs; ++s) {
+        const long long len = (long long)cu[s + 1] - cu[s];
+        if (len < 1) return OSDN_ERR_SHAPE;
+        N += (len + C - 1) / C;
+        pk.ragged = pk.ragged || len % C != 0;
+    }
+    if (N * C > 0x7fffffffLL) return OSDN_ERR_SHAPE;
+    pk.n_seqs = n_seqs;
+    pk.N = (int)N;
+    pk.tables.assign((size_t)n_seqs + 1 + 2 * (size_t)N, 0);
+    int *seq_chunks = pk.tables.data(), *chunk_row = seq_chunks + n_seqs + 1, *chunk_len = chunk_row + N;
+    int c = 0;
+    for (int s = 0; s < n_seqs; ++s) {
+        seq_chunks[s] = c;
+        for (int t = cu[s]; t < cu[s + 1]; t += C, ++c) {
+            chunk_row[c] = t;
+            chunk_len[c] = cu[s + 1] - t < C ? cu[s + 1] - t : C;
+        }
+    }
+    seq_chunks[n_seqs] = c;
+    return OSDN_OK;
+}
+
+void plain_packing(const osdn_params *p, Packing &pk) {
+    pk.N = (p->T + C - 1) / C;
+    pk.ragged = pk.N * C != p->T;
+}
+
+// every buffer is sized for the padded token axis of pk.N whole chunks
+Layout make_layout(const osdn_params *p, const Packing &pk) {
     const size_t es = p->io_dtype == OSDN_BF16 ? 2 : 4;
-    const size_t B = p->B, H = p->H, K = p->K, V = p->V, N = ((size_t)p->T + C - 1) / C, T = N * C;
-    const bool ragged = T != (size_t)p->T;      // every buffer is sized for whole chunks
+    const size_t B = p->B, H = p->H, K = p->K, V = p->V, N = (size_t)pk.N, T = N * C;
+    const bool ragged = pk.ragged;
     Layout L{};
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+    L.tables = take(pk.tables.size() * sizeof(int));
     L.kt = take(B * T * H * K * es);
     L.d_ckpt = take(B * H * N * K * 4);
     L.tok_scalars = take(B * T * H * 4 * 4);
@@ -119,7 +164,7 @@ PrecondArgs precond_args(const osdn_params *p) {
     return a;
 }
 
-ChunkArgs chunk_args(const osdn_params *p, const Layout &L, char *ws) {
+ChunkArgs chunk_args(const osdn_params *p, const Layout &L, char *ws) {      // p: the padded problem
     ChunkArgs c{};
     c.B = p->B; c.T = p->T; c.H = p->H; c.K = p->K; c.V = p->V; c.N = p->T / C;
     c.scale = p->scale;
@@ -196,7 +241,17 @@ extern "C" {
 
 size_t osdn_workspace_bytes(const osdn_params *p, int for_backward) {
     if (check_params(p, true) != OSDN_OK) return 0;
-    Layout L = make_layout(p);
+    Packing pk;
+    plain_packing(p, pk);
+    Layout L = make_layout(p, pk);
+    return for_backward ? L.total_bwd : L.total_fwd;
+}
+
+size_t osdn_workspace_bytes_packed(const osdn_params *p, const int32_t *cu_seqlens, int32_t n_seqs,
+                                   int for_backward) {
+    Packing pk;
+    if (check_params(p, true) != OSDN_OK || make_packing(p, cu_seqlens, n_seqs, pk) != OSDN_OK) return 0;
+    Layout L = make_layout(p, pk);
     return for_backward ? L.total_bwd : L.total_fwd;
 }
 
@@ -250,31 +305,50 @@ int osdn_step(const osdn_params *p, const void *q, const void *k, const void *v,
     return launch_status();
 }
 
-int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+// cu_seqlens == null: a plain [B,T] batch; otherwise n_seqs sequences packed on the token axis (B == 1)
+static int fwd_impl(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
              const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
-             void *o, float *S_out, float *d_out, void *workspace, size_t workspace_bytes,
-             void *stream) {
+             void *o, float *S_out, float *d_out, const int32_t *cu_seqlens, int n_seqs, void *workspace,
+             size_t workspace_bytes, void *stream) {
     int rc = check_params(p, true);
     if (rc != OSDN_OK) return rc;
     if (!q || !k || !v || !beta || !o || !S_out || !d_out) return OSDN_ERR_NULL;
-    Layout L = make_layout(p);
+    Packing pk;
+    if (cu_seqlens || n_seqs != 0) {
+        rc = make_packing(p, cu_seqlens, n_seqs, pk);
+        if (rc != OSDN_OK) return rc;
+    } else {
+        plain_packing(p, pk);
+    }
+    Layout L = make_layout(p, pk);
     rc = check_ws(workspace, workspace_bytes, L.total_fwd);
     if (rc != OSDN_OK) return rc;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = p->io_dtype == OSDN_BF16;
+    int *tables = reinterpret_cast<int *>(ws + L.tables);
+    const int *seq_chunks = pk.n_seqs ? tables : nullptr;
+    const int *chunk_row = tables + pk.n_seqs + 1, *chunk_len = chunk_row + pk.N;
+    if (pk.n_seqs && timed(KID_PAD, st, [&] { return launch_upload_ints(pk.tables.data(), pk.tables.size(), tables, st); }) != 0)
+        return OSDN_ERR_SHAPE;
 
-    // a ragged last chunk: work on padded copies (no-op pad tokens) and cut the output at the end
+    // ragged chunks (the tail of the sequence, or of any packed sequence): work on padded copies
+    // (no-op pad tokens) and move the output back at the end
     osdn_params padded = *p;
-    padded.T = (p->T + C - 1) / C * C;
+    padded.T = pk.N * C;
     const int T_user = p->T;
-    const bool ragged = padded.T != T_user;
+    const bool ragged = pk.ragged;
     void *o_user = o;
+    auto move = [&](const void *src, void *dst, size_t row, bool to_padded, uint32_t fill) {
+        return timed(KID_PAD, st, [&] {
+            if (pk.n_seqs) return launch_move_chunk_rows(src, dst, chunk_row, chunk_len, pk.N, row, to_padded, fill, st);
+            return to_padded ? launch_copy_rows(src, T_user, dst, padded.T, p->B, row, fill, st)
+                             : launch_copy_rows(src, padded.T, dst, T_user, p->B, row, fill, st);
+        });
+    };
     if (ragged) {
         const size_t es = bf ? 2 : 4, rk = (size_t)p->H * p->K * es, rv = (size_t)p->H * p->V * es, rg = (size_t)p->H * 4;
-        auto pad = [&](const void *src, size_t off, size_t row, uint32_t fill) {
-            return timed(KID_PAD, st, [&] { return launch_copy_rows(src, T_user, ws + off, padded.T, p->B, row, fill, st); });
-        };
+        auto pad = [&](const void *src, size_t off, size_t row, uint32_t fill) { return move(src, ws + off, row, true, fill); };
         if (pad(q, L.p_q, rk, 0u) != 0 || pad(k, L.p_k, rk, 0u) != 0 || pad(v, L.p_v, rv, 0u) != 0 ||
             pad(beta, L.p_beta, rg, 0u) != 0 || (log_alpha && pad(log_alpha, L.p_g, rg, 0u) != 0) ||
             (retention && pad(retention, L.p_r, rg, 0x3f800000u) != 0))
@@ -286,9 +360,7 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
         p = &padded;
     }
     auto finish = [&]() -> int {
-        if (ragged &&
-            timed(KID_PAD, st, [&] { return launch_copy_rows(o, padded.T, o_user, T_user, p->B, (size_t)p->H * p->V * (bf ? 2 : 4), 0u, st); }) != 0)
-            return OSDN_ERR_SHAPE;
+        if (ragged && move(o, o_user, (size_t)p->H * p->V * (bf ? 2 : 4), false, 0u) != 0) return OSDN_ERR_SHAPE;
         return launch_status();
     };
 
@@ -296,9 +368,11 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     pa.k = k; pa.beta = beta; pa.retention = retention;
     pa.k_tilde = ws + L.kt; pa.d_out = d_out; pa.d_ckpt = reinterpret_cast<float *>(ws + L.d_ckpt);
     pa.tok_scalars = reinterpret_cast<float *>(ws + L.tok_scalars);
+    pa.n_seqs = pk.n_seqs; pa.seq_chunks = seq_chunks; pa.d_first = d_in;
     ChunkArgs c = chunk_args(p, L, ws);
     c.q = q; c.k = k; c.v = v; c.beta = beta; c.log_alpha = log_alpha;
     c.o = o; c.S_out = S_out;
+    c.n_seqs = pk.n_seqs; c.seq_chunks = seq_chunks; c.S_first = S_in;
 
     const int N = p->T / C;
     int S = segment_count(N);
@@ -342,36 +416,54 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     return finish();
 }
 
-int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+static int bwd_impl(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
              const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
              const void *dO, const float *dS_out, const float *dd_out, void *dq, void *dk, void *dv,
              float *dbeta, float *dlog_alpha, float *dretention, float *dd_in, float *dS_in,
-             void *workspace, size_t workspace_bytes, void *stream) {
+             const int32_t *cu_seqlens, int n_seqs, void *workspace, size_t workspace_bytes, void *stream) {
     int rc = check_params(p, true);
     if (rc != OSDN_OK) return rc;
     if (!q || !k || !v || !beta || !dO || !dq || !dk || !dv || !dbeta || !dd_in || !dS_in)
         return OSDN_ERR_NULL;
     if ((log_alpha && !dlog_alpha) || (retention && !dretention)) return OSDN_ERR_NULL;
     (void)d_in; (void)S_in;
-    Layout L = make_layout(p);
+    Packing pk;
+    if (cu_seqlens || n_seqs != 0) {
+        rc = make_packing(p, cu_seqlens, n_seqs, pk);
+        if (rc != OSDN_OK) return rc;
+    } else {
+        plain_packing(p, pk);
+    }
+    Layout L = make_layout(p, pk);
     rc = check_ws(workspace, workspace_bytes, L.total_bwd);
     if (rc != OSDN_OK) return rc;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = p->io_dtype == OSDN_BF16;
+    int *tables = reinterpret_cast<int *>(ws + L.tables);
+    const int *seq_chunks = pk.n_seqs ? tables : nullptr;
+    const int *chunk_row = tables + pk.n_seqs + 1, *chunk_len = chunk_row + pk.N;
+    if (pk.n_seqs && timed(KID_PAD, st, [&] { return launch_upload_ints(pk.tables.data(), pk.tables.size(), tables, st); }) != 0)
+        return OSDN_ERR_SHAPE;
 
-    // a ragged last chunk: the padded inputs are the ones osdn_fwd left in the workspace; dO is
-    // padded here, the gradients are produced padded and cut at the end
+    // ragged chunks: the padded inputs are the ones the forward call left in the workspace; dO
+    // is padded here, the gradients are produced padded and moved back at the end
     osdn_params padded = *p;
-    padded.T = (p->T + C - 1) / C * C;
+    padded.T = pk.N * C;
     const int T_user = p->T;
-    const bool ragged = padded.T != T_user;
+    const bool ragged = pk.ragged;
+    auto move = [&](const void *src, void *dst, size_t row, bool to_padded) {
+        return timed(KID_PAD, st, [&] {
+            if (pk.n_seqs) return launch_move_chunk_rows(src, dst, chunk_row, chunk_len, pk.N, row, to_padded, 0u, st);
+            return to_padded ? launch_copy_rows(src, T_user, dst, padded.T, p->B, row, 0u, st)
+                             : launch_copy_rows(src, padded.T, dst, T_user, p->B, row, 0u, st);
+        });
+    };
     void *dq_user = dq, *dk_user = dk, *dv_user = dv;
     float *dbeta_user = dbeta, *dg_user = dlog_alpha, *dr_user = dretention;
     const size_t es_ = bf ? 2 : 4, rk_ = (size_t)p->H * p->K * es_, rv_ = (size_t)p->H * p->V * es_, rg_ = (size_t)p->H * 4;
     if (ragged) {
-        if (timed(KID_PAD, st, [&] { return launch_copy_rows(dO, T_user, ws + L.p_dO, padded.T, p->B, rv_, 0u, st); }) != 0)
-            return OSDN_ERR_SHAPE;
+        if (move(dO, ws + L.p_dO, rv_, true) != 0) return OSDN_ERR_SHAPE;
         q = ws + L.p_q; k = ws + L.p_k; v = ws + L.p_v; dO = ws + L.p_dO;
         beta = reinterpret_cast<const float *>(ws + L.p_beta);
         if (log_alpha) log_alpha = reinterpret_cast<const float *>(ws + L.p_g);
@@ -384,9 +476,7 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     }
     auto finish = [&]() -> int {
         if (ragged) {
-            auto cut = [&](const void *src, void *dst, size_t row) {
-                return timed(KID_PAD, st, [&] { return launch_copy_rows(src, padded.T, dst, T_user, p->B, row, 0u, st); });
-            };
+            auto cut = [&](const void *src, void *dst, size_t row) { return move(src, dst, row, false); };
             if (cut(dq, dq_user, rk_) != 0 || cut(dk, dk_user, rk_) != 0 || cut(dv, dv_user, rv_) != 0 ||
                 cut(dbeta, dbeta_user, rg_) != 0 || (log_alpha && cut(dlog_alpha, dg_user, rg_) != 0) ||
                 (retention && cut(dretention, dr_user, rg_) != 0))
@@ -403,6 +493,7 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     c.dk_read = ws + L.dk_read;
     c.dkt = ws + L.dkt;
     c.dbeta = dbeta; c.dlog_alpha = log_alpha ? dlog_alpha : nullptr;
+    c.n_seqs = pk.n_seqs; c.seq_chunks = seq_chunks; c.dS_last = dS_out;
     PrecondBwdArgs pb{};
     pb.B = p->B; pb.T = p->T; pb.H = p->H; pb.K = p->K;
     pb.eta = p->eta; pb.d_min = p->d_min; pb.d_max = p->d_max; pb.eps = p->eps;
@@ -413,6 +504,7 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     pb.masks = reinterpret_cast<uint2 *>(ws + L.masks);
     pb.a_ckpt = reinterpret_cast<float *>(ws + L.a_ckpt);
     pb.dkt = c.dkt; pb.dk_read = c.dk_read;
+    pb.n_seqs = pk.n_seqs; pb.seq_chunks = seq_chunks; pb.dd_last = dd_out;
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
 
     const int N = p->T / C;
@@ -465,6 +557,43 @@ int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, 
     OSDN_HIP_OK(hipEventRecord(pl->join, s1));
     OSDN_HIP_OK(hipStreamWaitEvent(st, pl->join, 0));
     return finish();
+}
+
+int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+             const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+             void *o, float *S_out, float *d_out, void *workspace, size_t workspace_bytes,
+             void *stream) {
+    return fwd_impl(p, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, nullptr, 0, workspace,
+                    workspace_bytes, stream);
+}
+
+int osdn_fwd_packed(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+                    const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+                    void *o, float *S_out, float *d_out, const int32_t *cu_seqlens, int32_t n_seqs,
+                    void *workspace, size_t workspace_bytes, void *stream) {
+    if (!cu_seqlens) return OSDN_ERR_NULL;
+    return fwd_impl(p, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, cu_seqlens, n_seqs,
+                    workspace, workspace_bytes, stream);
+}
+
+int osdn_bwd(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+             const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+             const void *dO, const float *dS_out, const float *dd_out, void *dq, void *dk, void *dv,
+             float *dbeta, float *dlog_alpha, float *dretention, float *dd_in, float *dS_in,
+             void *workspace, size_t workspace_bytes, void *stream) {
+    return bwd_impl(p, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out, dd_out, dq, dk, dv, dbeta,
+                    dlog_alpha, dretention, dd_in, dS_in, nullptr, 0, workspace, workspace_bytes, stream);
+}
+
+int osdn_bwd_packed(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+                    const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+                    const void *dO, const float *dS_out, const float *dd_out, void *dq, void *dk, void *dv,
+                    float *dbeta, float *dlog_alpha, float *dretention, float *dd_in, float *dS_in,
+                    const int32_t *cu_seqlens, int32_t n_seqs, void *workspace, size_t workspace_bytes,
+                    void *stream) {
+    if (!cu_seqlens) return OSDN_ERR_NULL;
+    return bwd_impl(p, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out, dd_out, dq, dk, dv, dbeta,
+                    dlog_alpha, dretention, dd_in, dS_in, cu_seqlens, n_seqs, workspace, workspace_bytes, stream);
 }
 
 void osdn_profile_enable(int on) { g_prof_on = on != 0; }

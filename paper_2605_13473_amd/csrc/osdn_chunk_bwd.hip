@@ -142,14 +142,22 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     __shared__ float gCs[NB];
 
     int chain, slice;
-    chain_slice_of(blockIdx.x, a.V / VS, a.B * a.H, chain, slice);
-    const int vs = slice * VS, h = chain % a.H, b = chain / a.H;
+    chain_slice_of(blockIdx.x, a.V / VS, (a.seq_chunks ? a.n_seqs : a.B) * a.H, chain, slice);
+    const int vs = slice * VS, h = chain % a.H, b = chain / a.H;   // b: batch entry, or packed sequence
+    int bt = b;                                 // batch entry of the token tensors
+    if (a.seq_chunks) {
+        bool begins, ends;
+        if (!clip_to_sequence(a.seq_chunks, b, a.n0, a.n1, begins, ends)) return;
+        a.dS_out = ends ? a.dS_last : a.dS_in;
+        bt = 0;
+    }
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool loader = wave >= 4;
     const int lt = tid - CL_;
     const int lgrp = NB == 2 ? (lt >> 7) & 1 : 0;
     const int lti = NB == 2 ? lt & 127 : lt;
-    const size_t bh = (size_t)b * a.H + h;
+    const size_t bh = (size_t)b * a.H + h;      // the chain: indexes dS_out / dS_in
+    const size_t bth = (size_t)bt * a.H + h;    // indexes the per-chunk buffers
     const size_t tstride = a.H;
 
     f32x4 dSt[2][NKT];                  // rows = features, cols = values
@@ -167,8 +175,8 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     float greg = 0.f;
 #define OSDN_BC_LOAD(n_)                                                                         \
     {                                                                                            \
-        const size_t bhn_ = bh * a.N + (n_);                                                     \
-        const size_t tok_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                      \
+        const size_t bhn_ = bth * a.N + (n_);                                                    \
+        const size_t tok_ = ((size_t)bt * a.T + (size_t)(n_) * C) * a.H + h;                     \
         const T *kg = static_cast<const T *>(a.Ktr) + bhn_ * K * C;                              \
         const T *wg = static_cast<const T *>(a.Wt) + bhn_ * K * C;                               \
         const T *qg = static_cast<const T *>(a.Qt) + bhn_ * K * C;                               \
@@ -223,7 +231,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
 
     for (int n = a.n1 - 1; n >= a.n0; --n) {
         const int buf = NB == 2 ? (n & 1) : 0;
-        const size_t bhn = bh * a.N + n;
+        const size_t bhn = bth * a.N + n;
         // ---- phase A (compute): dS', rounded, into LDS ----
         if (!loader) {
 #pragma unroll
@@ -657,7 +665,7 @@ int launch_bwd_local(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T>
 static int launch_chain_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid((a.V / VS) * a.H * a.B), block(CT_);
+    dim3 grid((a.V / VS) * a.H * (a.seq_chunks ? a.n_seqs : a.B)), block(CT_);
     if (a.K == 64) hipLaunchKernelGGL((bwd_chain_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((bwd_chain_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;

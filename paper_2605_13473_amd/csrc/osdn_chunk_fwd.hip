@@ -235,15 +235,23 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     __shared__ float gCs[NB];
 
     int chain, slice;
-    chain_slice_of(blockIdx.x, a.V / VS, a.B * a.H, chain, slice);
-    const int vs = slice * VS, h = chain % a.H, b = chain / a.H;
+    chain_slice_of(blockIdx.x, a.V / VS, (a.seq_chunks ? a.n_seqs : a.B) * a.H, chain, slice);
+    const int vs = slice * VS, h = chain % a.H, b = chain / a.H;   // b: batch entry, or packed sequence
+    int bt = b;                                 // batch entry of the token tensors
+    if (a.seq_chunks) {
+        bool begins, ends;
+        if (!clip_to_sequence(a.seq_chunks, b, a.n0, a.n1, begins, ends)) return;
+        a.S_in = begins ? a.S_first : a.S_out;
+        bt = 0;
+    }
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool loader = wave >= 4;
     const int lt = tid - CL_;                   // loader thread index
     const int lgrp = NB == 2 ? (lt >> 7) & 1 : 0;   // loader group (chunk parity it serves)
     const int lti = NB == 2 ? lt & 127 : lt;    // index inside the group
     const bool gwave = NB == 2 ? (wave & 1) == 0 : wave == 4;   // the group's wave that handles the gate
-    const size_t bh = (size_t)b * a.H + h;
+    const size_t bh = (size_t)b * a.H + h;      // the chain: indexes S_in / S_out
+    const size_t bth = (size_t)bt * a.H + h;    // indexes the per-chunk buffers
     const size_t tstride = a.H;
 
     // ---- compute waves: state slice, transposed: St[vt][q] rows = features, cols = values ----
@@ -263,7 +271,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     float greg = 0.f;
 #define OSDN_SF_LOAD(n_)                                                                         \
     {                                                                                            \
-        const size_t bhn_ = bh * a.N + (n_);                                                     \
+        const size_t bhn_ = bth * a.N + (n_);                                                    \
         const T *wg = static_cast<const T *>(a.W) + bhn_ * C * K;                                \
         const T *kg = static_cast<const T *>(a.Ktr) + bhn_ * K * C;                              \
         const T *ug = static_cast<const T *>(a.Ut) + (bhn_ * a.V + vs) * C;                      \
@@ -277,7 +285,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
             ureg[m] = *reinterpret_cast<const u32x4 *>(ug + (size_t)i * VN);                     \
         }                                                                                        \
         if (gwave)                                                                               \
-            greg = a.log_alpha ? a.log_alpha[((size_t)b * a.T + (size_t)(n_) * C + lane) * a.H + h] : 0.f; \
+            greg = a.log_alpha ? a.log_alpha[((size_t)bt * a.T + (size_t)(n_) * C + lane) * a.H + h] : 0.f; \
     }
 #define OSDN_SF_STORE(buf_)                                                                      \
     {                                                                                            \
@@ -321,7 +329,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
 #endif
     for (int n = a.n0; n < a.n1; ++n) {
         const int buf = NB == 2 ? (n & 1) : 0;
-        const size_t bhn = bh * a.N + n;
+        const size_t bhn = bth * a.N + n;
         // ---- phase A (compute): S, rounded, into LDS ----
         if (!loader) {
 #pragma unroll
@@ -494,7 +502,7 @@ int launch_chunk_prep(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T>
 static int launch_state_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid((a.V / VS) * a.H * a.B), block(CT_);
+    dim3 grid((a.V / VS) * a.H * (a.seq_chunks ? a.n_seqs : a.B)), block(CT_);
     if (a.K == 64) hipLaunchKernelGGL((state_fwd_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((state_fwd_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;

@@ -269,4 +269,17 @@ __device__ __forceinline__ void chain_slice_of(int wg, int nslices, int nchains,
     }
 }
 
+
+// Packed sequences: clip the chunk range [n0, n1) of a launch to the chunks of sequence s.
+// begins / ends: the sequence starts / stops inside the launch's range.  False: nothing left.
+__device__ __forceinline__ bool clip_to_sequence(const int *seq_chunks, int s, int &n0, int &n1, bool &begins,
+                                                 bool &ends) {
+    const int cb = seq_chunks[s], ce = seq_chunks[s + 1];
+    begins = cb >= n0;
+    ends = ce <= n1;
+    n0 = max(n0, cb);
+    n1 = min(n1, ce);
+    return n0 < n1;
+}
+
 }  // namespace osdn

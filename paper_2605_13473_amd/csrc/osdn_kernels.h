@@ -8,9 +8,20 @@ namespace osdn {
 // segment when the two phases are pipelined against each other); what a sequential kernel
 // carries across a segment boundary (d, S, dS, the adjoint of d) goes through the same
 // buffers that hold it at the ends of the sequence.
+//
+// Packed sequences (seq_chunks != null): the token axis holds n_seqs sequences one after the
+// other, each starting on a chunk boundary; sequence s owns the chunks
+// [seq_chunks[s], seq_chunks[s+1]).  The token tensors and per-chunk buffers then have one
+// batch entry, the carried tensors (d, S and their adjoints) one entry per sequence, and the
+// sequential kernels run one chain per (sequence, head).  A chain takes its start value from
+// the *_first / *_last pointer when its sequence begins (ends, in the backward pass) inside
+// [n0, n1), and from the carry buffer otherwise.
 struct PrecondArgs {
     int B, T, H, K;
     int n0, n1;
+    int n_seqs;               // 0: plain batch
+    const int *seq_chunks;    // [n_seqs + 1] or null
+    const float *d_first;     // packed sequences: d before the first token, [n_seqs,H,K] or null
     float eta, d_min, d_max, eps;
     int beta_aware;
     const void *k;            // [B,T,H,K] io
@@ -26,6 +37,9 @@ struct PrecondArgs {
 struct PrecondBwdArgs {
     int B, T, H, K;
     int n0, n1;
+    int n_seqs;
+    const int *seq_chunks;
+    const float *dd_last;     // packed sequences: adjoint of the final d, [n_seqs,H,K] or null
     float eta, d_min, d_max, eps;
     int beta_aware;
     const void *k;
@@ -60,6 +74,10 @@ struct StepArgs {
 struct ChunkArgs {
     int B, T, H, K, V, N;
     int n0, n1;
+    int n_seqs;
+    const int *seq_chunks;
+    const float *S_first;             // packed sequences: [n_seqs,H,V,K] or null
+    const float *dS_last;             // packed sequences: adjoint of the final S, or null
     float scale;
     // caller tensors
     const void *q, *k, *v;            // [B,T,H,*] io
@@ -94,6 +112,9 @@ int launch_precond_fwd(const PrecondArgs &a, bool bf16_io, hipStream_t st);
 int launch_step(const StepArgs &a, bool bf16_io, hipStream_t st);
 int launch_copy_rows(const void *src, int Ts, void *dst, int Td, int B, size_t row_bytes, uint32_t fill,
                      hipStream_t st);
+int launch_upload_ints(const int *host, size_t count, int *dst, hipStream_t st);
+int launch_move_chunk_rows(const void *src, void *dst, const int *chunk_row, const int *chunk_len, int n_chunks,
+                           size_t row_bytes, bool to_padded, uint32_t fill, hipStream_t st);
 int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_post(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);

@@ -28,4 +28,60 @@ int launch_copy_rows(const void *src, int Ts, void *dst, int Td, int B, size_t r
     return 0;
 }
 
+// ---- packed sequences -------------------------------------------------------------------
+// Sequences packed back to back on one token axis are moved so that each starts on a chunk
+// boundary.  Two small tables, one entry per chunk of the padded axis, describe the move:
+// chunk_row[c] = packed row of the chunk's first token, chunk_len[c] = its tokens (1..64).
+
+// small host arrays reach the device as kernel arguments: nothing to keep alive, no copy engine
+constexpr int UPLOAD_INTS = 512;
+struct IntBlock { int v[UPLOAD_INTS]; };
+__global__ __launch_bounds__(256) void upload_ints_kernel(IntBlock blk, int count, int *dst) {
+    for (int i = threadIdx.x; i < count; i += blockDim.x) dst[i] = blk.v[i];
+}
+
+int launch_upload_ints(const int *host, size_t count, int *dst, hipStream_t st) {
+    for (size_t at = 0; at < count; at += UPLOAD_INTS) {
+        IntBlock blk;
+        const int n = (int)(count - at < (size_t)UPLOAD_INTS ? count - at : (size_t)UPLOAD_INTS);
+        for (int i = 0; i < UPLOAD_INTS; ++i) blk.v[i] = i < n ? host[at + i] : 0;
+        hipLaunchKernelGGL(upload_ints_kernel, dim3(1), dim3(256), 0, st, blk, n, dst + at);
+    }
+    return 0;
+}
+
+// to_padded: padded[c*64 + t][:] = t < chunk_len[c] ? packed[chunk_row[c] + t][:] : fill
+// otherwise: packed[chunk_row[c] + t][:] = padded[c*64 + t][:] for t < chunk_len[c]
+template <bool TO_PADDED>
+__global__ __launch_bounds__(256) void move_chunk_rows_kernel(const uint32_t *src, uint32_t *dst, const int *chunk_row,
+                                                               const int *chunk_len, uint32_t wpr, uint32_t fill,
+                                                               size_t total) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t row = i / wpr;
+        const uint32_t w = (uint32_t)(i % wpr);
+        const size_t c = row / C;
+        const int t = (int)(row % C);
+        const bool valid = t < chunk_len[c];
+        const size_t packed = ((size_t)chunk_row[c] + t) * wpr + w;
+        if (TO_PADDED) dst[i] = valid ? src[packed] : fill;
+        else if (valid) dst[packed] = src[i];
+    }
+}
+
+int launch_move_chunk_rows(const void *src, void *dst, const int *chunk_row, const int *chunk_len, int n_chunks,
+                           size_t row_bytes, bool to_padded, uint32_t fill, hipStream_t st) {
+    if (row_bytes % 4 != 0) return -1;
+    const uint32_t wpr = (uint32_t)(row_bytes / 4);
+    const size_t total = (size_t)n_chunks * C * wpr;
+    const size_t blocks = (total + 255) / 256;
+    const dim3 grid((unsigned)(blocks < 65535 * 16 ? blocks : 65535 * 16));
+    if (to_padded)
+        hipLaunchKernelGGL(move_chunk_rows_kernel<true>, grid, dim3(256), 0, st, static_cast<const uint32_t *>(src),
+                           static_cast<uint32_t *>(dst), chunk_row, chunk_len, wpr, fill, total);
+    else
+        hipLaunchKernelGGL(move_chunk_rows_kernel<false>, grid, dim3(256), 0, st, static_cast<const uint32_t *>(src),
+                           static_cast<uint32_t *>(dst), chunk_row, chunk_len, wpr, fill, total);
+    return 0;
+}
+
 }  // namespace osdn

@@ -16,6 +16,16 @@ template <bool HAS_RET>
 __device__ __forceinline__ float d_bar(float r, float d, float step, float s) {
     return HAS_RET ? __builtin_fmaf(step, s, r * d) : __builtin_fmaf(step, s, d);
 }
+// Did the step land inside the box (the projection's gradient mask)?  Decided from the signs
+// of (r d - face) + step s, each evaluated with a single rounding at its own scale, rather
+// than by comparing the rounded sum with the face: a coordinate that sits on a face, or
+// comes within an ulp of it, is then told apart from one pushed across it by less than an ulp.
+template <bool HAS_RET>
+__device__ __forceinline__ bool lands_inside(float r, float d, float step, float s, float lo, float hi) {
+    const float above_lo = HAS_RET ? __builtin_fmaf(r, d, -lo) : d - lo;
+    const float above_hi = HAS_RET ? __builtin_fmaf(r, d, -hi) : d - hi;
+    return __builtin_fmaf(step, s, above_lo) >= 0.f && __builtin_fmaf(step, s, above_hi) <= 0.f;
+}
 __device__ __forceinline__ void store_vec(float *dst, const float (&v)[4]) {
     *reinterpret_cast<f32x4 *>(dst) = f32x4{v[0], v[1], v[2], v[3]};
 }

@@ -71,8 +71,16 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     const int tid = threadIdx.x, run = tid >> 6, lane = tid & 63;
     const int c0 = lane * CPT;                    // first coordinate of this thread
     const int u_own = lane & (RUN - 1);           // the token of the run whose scalars this lane keeps
-    const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
-    const size_t bh = (size_t)b * a.H + h;
+    const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;     // b: batch entry, or packed sequence
+    const size_t bh = (size_t)b * a.H + h;                    // the chain: indexes d_in / d_out
+    int bt = b;                                               // batch entry of the token tensors
+    if (a.seq_chunks) {
+        bool begins, ends;
+        if (!clip_to_sequence(a.seq_chunks, b, a.n0, a.n1, begins, ends)) return;
+        a.d_in = begins ? a.d_first : a.d_out;
+        bt = 0;
+    }
+    const size_t bth = (size_t)bt * a.H + h;                  // indexes the per-chunk buffers
     const bool project = a.d_min <= a.d_max;
     const float lo = project ? a.d_min : -INFINITY, hi = project ? a.d_max : INFINITY;
     const int N = (a.T + C - 1) / C;
@@ -85,13 +93,13 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
 #define OSDN_P1_LOAD(n_)                                                                         \
     {                                                                                            \
         const int t0_ = (n_) * C;                                                                \
-        const T *kp_ = static_cast<const T *>(a.k) + (((size_t)b * a.T + t0_) * a.H + h) * K;    \
+        const T *kp_ = static_cast<const T *>(a.k) + (((size_t)bt * a.T + t0_) * a.H + h) * K;   \
         _Pragma("unroll") for (int u = 0; u < RUN; ++u) {                                        \
             const int i_ = min(run * RUN + u, a.T - 1 - t0_);    /* rows past the end: reread */ \
             kreg[u] = *reinterpret_cast<const typename Pk::Raw *>(kp_ + (uint32_t)i_ * kstride + c0); \
         }                                                                                        \
         const int t = min(t0_ + run * RUN + u_own, a.T - 1);                                     \
-        const size_t th = ((size_t)b * a.T + t) * a.H + h;                                       \
+        const size_t th = ((size_t)bt * a.T + t) * a.H + h;                                      \
         betreg = a.beta[th];                                                                     \
         if (HAS_RET) retreg = a.retention[th];                                                   \
     }
@@ -127,7 +135,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
             for (int e = 0; e < CPT; ++e) dst[e] = dcur[c0 + e];
             if (a.d_ckpt && run == 0) {
 #pragma unroll
-                for (int e = 0; e < CPT; ++e) a.d_ckpt[(bh * N + n) * K + c0 + e] = dst[e];
+                for (int e = 0; e < CPT; ++e) a.d_ckpt[(bth * N + n) * K + c0 + e] = dst[e];
             }
             float vn[RUN], vp[RUN];
 #pragma unroll
@@ -218,7 +226,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
         }
         // ---- accepted: (c_cur, p_cur) generated dtr and dend ----
         {
-            T *ktp = static_cast<T *>(a.k_tilde) + (((size_t)b * a.T + t0) * a.H + h) * K;
+            T *ktp = static_cast<T *>(a.k_tilde) + (((size_t)bt * a.T + t0) * a.H + h) * K;
 #pragma unroll
             for (int u = 0; u < RUN; ++u) {
                 const int i = run * RUN + u;
@@ -231,7 +239,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
             }
         }
         if (a.tok_scalars && lane < RUN && run * RUN + lane < nvalid) {
-            const size_t th = ((size_t)b * a.T + t0 + run * RUN + lane) * a.H + h;
+            const size_t th = ((size_t)bt * a.T + t0 + run * RUN + lane) * a.H + h;
             *reinterpret_cast<float4 *>(a.tok_scalars + th * 4) = make_float4(c_cur, p_cur, nraw, (float)sweeps_used);
         }
         if (run == NRUN - 1) {
@@ -243,14 +251,14 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     }
 #ifdef OSDN_DIAG
     if (a.tok_scalars && tid == 0 && blockIdx.x == 0)
-        for (int j = 0; j < 6; ++j) a.tok_scalars[(((size_t)b * a.T + 2 + j) * a.H + h) * 4 + 3] = (float)tph[j];
+        for (int j = 0; j < 6; ++j) a.tok_scalars[(((size_t)bt * a.T + 2 + j) * a.H + h) * 4 + 3] = (float)tph[j];
 #endif
     if (tid < K) a.d_out[bh * K + tid] = dcur[tid];
 }
 
 template <typename T, bool HAS_RET>
 static int launch_precond_fwd_t(const PrecondArgs &a, hipStream_t st) {
-    dim3 grid(a.B * a.H), block(P1T);
+    dim3 grid((a.seq_chunks ? a.n_seqs : a.B) * a.H), block(P1T);
     if (a.K == 64) hipLaunchKernelGGL((precond_fwd_kernel<T, 64, HAS_RET>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((precond_fwd_kernel<T, 128, HAS_RET>), grid, block, 0, st, a);
     else return -1;

@@ -44,9 +44,9 @@ __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
     uint32_t mlo = 0u, mhi = 0u;
 #pragma unroll
     for (int i = 0; i < C; ++i) {
-        const float db = d_bar<HAS_RET>(rs[i], d, steps[i], kv[i] * kv[i]);
-        d = clip3(db, lo, hi);
-        const uint32_t in = (d == db) ? (1u << (i & 31)) : 0u;
+        const float sq = kv[i] * kv[i];
+        const uint32_t in = lands_inside<HAS_RET>(rs[i], d, steps[i], sq, lo, hi) ? (1u << (i & 31)) : 0u;
+        d = clip3(d_bar<HAS_RET>(rs[i], d, steps[i], sq), lo, hi);
         if (i < 32) mlo |= in; else mhi |= in;
     }
     a.masks[(bh * N + n) * K + tid] = make_uint2(mlo, mhi);
@@ -76,8 +76,16 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c = tid % K, sg = tid / K;          // coordinate and run of this thread
-    const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;
-    const size_t bh = (size_t)b * a.H + h;
+    const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;     // b: batch entry, or packed sequence
+    const size_t bh = (size_t)b * a.H + h;                    // the chain: indexes dd_out / dd_in
+    int bt = b;                                               // batch entry of the token tensors
+    if (a.seq_chunks) {
+        bool begins, ends;
+        if (!clip_to_sequence(a.seq_chunks, b, a.n0, a.n1, begins, ends)) return;
+        a.dd_out = ends ? a.dd_last : a.dd_in;
+        bt = 0;
+    }
+    const size_t bth = (size_t)bt * a.H + h;                  // indexes the per-chunk buffers
     const bool project = a.d_min <= a.d_max;
     const int N = a.T / C;
     const uint32_t kstride = (uint32_t)a.H * K;   // elements between consecutive tokens
@@ -89,7 +97,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
     uint2 mreg = make_uint2(0xffffffffu, 0xffffffffu);
 #define OSDN_P1_BLOAD(n_)                                                                        \
     {                                                                                            \
-        const size_t tokc_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                     \
+        const size_t tokc_ = ((size_t)bt * a.T + (size_t)(n_) * C) * a.H + h;                    \
         const T *kp_ = static_cast<const T *>(a.k) + tokc_ * K;                                  \
         const T *gp_ = static_cast<const T *>(a.dkt) + tokc_ * K;                                \
         _Pragma("unroll") for (int u = 0; u < TS; ++u) {                                         \
@@ -102,7 +110,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
             betreg = a.beta[th];                                                                 \
             if (HAS_RET) retreg = a.retention[th];                                               \
         }                                                                                        \
-        if (project) mreg = a.masks[(bh * N + (n_)) * K + c];                                    \
+        if (project) mreg = a.masks[(bth * N + (n_)) * K + c];                                   \
     }
     OSDN_P1_BLOAD(a.n1 - 1)
 
@@ -113,7 +121,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 #define OSDN_TICK(j)
 #endif
     for (int n = a.n1 - 1; n >= a.n0; --n) {
-        const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+        const size_t tokc = ((size_t)bt * a.T + (size_t)n * C) * a.H + h;
         // ---- this thread's (s, lambda) = (k^2, k . dL/dk~) and mask bits ----
         float sv[TS], lam[TS];
 #pragma unroll
@@ -129,7 +137,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
             const float bp = a.beta_aware ? betreg : 1.f;
             rs[tid] = retreg; cas[tid] = a.eta * bp / nn * bp; sig[tid] = 0.f; casig[tid] = 0.f;
         }
-        if (tid < K) a.a_ckpt[(bh * N + n) * K + tid] = ga[tid];
+        if (tid < K) a.a_ckpt[(bth * N + n) * K + tid] = ga[tid];
         __syncthreads();
         OSDN_TICK(0)
         if (n > a.n0) OSDN_P1_BLOAD(n - 1)      // next chunk: in flight during the sweeps
@@ -264,7 +272,9 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     T *op = static_cast<T *>(a.dk) + tokc * K;
     const uint32_t kstride = (uint32_t)a.H * K;
     float Dv[C];
-    uint32_t mlo = 0u, mhi = 0u;
+    // which steps landed inside the box: decided once, by the mask kernel
+    const uint2 mbits = project ? a.masks[(bh * N + n) * K + tid] : make_uint2(0xffffffffu, 0xffffffffu);
+    const uint32_t mlo = mbits.x, mhi = mbits.y;
     {   // ---- replay d over the chunk (same arithmetic as the forward kernel) ----
         float kv[C];
 #pragma unroll
@@ -274,10 +284,7 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
 #pragma unroll
         for (int i = 0; i < C; ++i) {
             Dv[i] = d;
-            const float db = d_bar<HAS_RET>(r_s[i], d, st_s[i], kv[i] * kv[i]);
-            d = clip3(db, lo, hi);
-            const uint32_t in = (d == db) ? (1u << (i & 31)) : 0u;
-            if (i < 32) mlo |= in; else mhi |= in;
+            d = clip3(d_bar<HAS_RET>(r_s[i], d, st_s[i], kv[i] * kv[i]), lo, hi);
         }
     }
     // ---- the chunk's adjoint recurrence, right to left, and the elementwise outputs ----
@@ -329,13 +336,14 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
 template <typename T, bool HAS_RET>
 static int launch_precond_bwd_t(const PrecondBwdArgs &a, int which, hipStream_t st) {
     const dim3 per_chunk(a.n1 - a.n0, a.H, a.B);
+    const int nchains = (a.seq_chunks ? a.n_seqs : a.B) * a.H;
     if (a.K == 64) {
         if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 64, HAS_RET>), per_chunk, dim3(64), 0, st, a);
-        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 64, HAS_RET>), dim3(a.B * a.H), dim3(P1T), 0, st, a);
+        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 64, HAS_RET>), dim3(nchains), dim3(P1T), 0, st, a);
         else hipLaunchKernelGGL((precond_post_kernel<T, 64, HAS_RET>), per_chunk, dim3(64), 0, st, a);
     } else if (a.K == 128) {
         if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 128, HAS_RET>), per_chunk, dim3(128), 0, st, a);
-        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 128, HAS_RET>), dim3(a.B * a.H), dim3(P1T), 0, st, a);
+        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 128, HAS_RET>), dim3(nchains), dim3(P1T), 0, st, a);
         else hipLaunchKernelGGL((precond_post_kernel<T, 128, HAS_RET>), per_chunk, dim3(128), 0, st, a);
     } else {
         return -1;

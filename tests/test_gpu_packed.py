@@ -1,0 +1,144 @@
+"""GPU parity for packed sequences: several sequences back to back on one token axis, the
+recurrent state reset at every boundary.  The oracle knows nothing of packing: it is run on
+every sequence by itself (its own slice of the tokens, its own d_in / S_in and terminal
+adjoints) and the results are laid side by side."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_13473_amd import binding as ob
+from paper_2605_13473_amd.inputs import make_stress_inputs
+from tests.gpu_util import check, f64, oracle_hp, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _cu(lens):
+    return [0] + [int(c) for c in np.cumsum(lens)]
+
+
+def _packed_inputs(lens, H, K, V, seed, bf16, retention=0.95, gated=True, carried=True):
+    """One token axis of sum(lens) tokens; carried tensors with one entry per sequence."""
+    T, n = int(sum(lens)), len(lens)
+    x = make_stress_inputs(1, T, H, K, V, seed=seed, bf16=bf16, retention=retention, gated=gated)
+    rng = np.random.default_rng(seed + 1000)
+    f32 = np.float32
+    if carried:
+        x["d_in"] = (0.5 + 1.5 * rng.random((n, H, K))).astype(f32)
+        x["S_in"] = (0.5 * rng.standard_normal((n, H, V, K))).astype(f32)
+        x["dS_out"] = rng.standard_normal((n, H, V, K)).astype(f32)
+        x["dd_out"] = rng.standard_normal((n, H, K)).astype(f32)
+    else:
+        x["d_in"] = x["S_in"] = x["dS_out"] = x["dd_out"] = None
+    return x
+
+
+def _oracle_per_sequence(x, lens, hp, backward):
+    """Run the oracle on every sequence alone and concatenate."""
+    y = f64(x)
+    cu = _cu(lens)
+    tok = lambda a, s: None if a is None else np.ascontiguousarray(a[:, cu[s]:cu[s + 1]])
+    car = lambda a, s: None if a is None else np.ascontiguousarray(a[s:s + 1])
+    outs = []
+    for s in range(len(lens)):
+        args = dict(log_alpha=tok(y["log_alpha"], s), retention=tok(y["retention"], s),
+                    d_in=car(y["d_in"], s), S_in=car(y["S_in"], s))
+        o, S, d = oracle.fwd(tok(y["q"], s), tok(y["k"], s), tok(y["v"], s), tok(y["beta"], s), hp=oracle_hp(hp),
+                             **args)
+        r = {"o": o, "S_out": S, "d_out": d}
+        if backward:
+            r.update(oracle.bwd(tok(y["q"], s), tok(y["k"], s), tok(y["v"], s), tok(y["beta"], s), tok(y["dO"], s),
+                                dS_out=car(y["dS_out"], s), dd_out=car(y["dd_out"], s), hp=oracle_hp(hp), **args))
+        outs.append(r)
+    cat = {}
+    for name in outs[0]:
+        if outs[0][name] is None:
+            cat[name] = None
+        else:
+            axis = 0 if name in ("S_out", "d_out", "dd_in", "dS_in") else 1
+            cat[name] = np.concatenate([r[name] for r in outs], axis=axis)
+    return cat
+
+
+def _gpu_packed(x, lens, hp, bf16, backward):
+    t = to_dev({n: x[n] for n in ("q", "k", "v", "dO", "beta", "log_alpha", "retention", "d_in", "S_in")}, bf16)
+    o, S, d, ctx = ob.forward(t["q"], t["k"], t["v"], t["beta"], t["log_alpha"], t["retention"], t["d_in"],
+                              t["S_in"], hp, for_backward=backward, cu_seqlens=_cu(lens))
+    got = {"o": o, "S_out": S, "d_out": d}
+    if backward:
+        dS = None if x["dS_out"] is None else torch.from_numpy(x["dS_out"]).cuda()
+        dd = None if x["dd_out"] is None else torch.from_numpy(x["dd_out"]).cuda()
+        got.update(ob.backward(ctx, t["dO"], dS, dd))
+    torch.cuda.synchronize()
+    return got, t
+
+
+def _compare(lens, H, K, V, seed, bf16, hp, backward=True, **kw):
+    x = _packed_inputs(lens, H, K, V, seed, bf16, **kw)
+    got, _ = _gpu_packed(x, lens, hp, bf16, backward)
+    ref = _oracle_per_sequence(x, lens, hp, backward)
+    for name, r in ref.items():
+        if r is None:
+            assert got[name] is None, name
+            continue
+        check(name, got[name], r, bf16 and name not in ("d_out",))
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_ragged_mix_fwd_bwd(bf16):
+    """Lengths of one token, just under, exactly, and just over a chunk, and several chunks."""
+    _compare([1, 37, 64, 65, 200, 128, 3], H=2, K=64, V=64, seed=61, bf16=bf16, hp=ob.Hyper(eta=0.5))
+
+
+def test_whole_chunk_lengths_take_no_copies():
+    """Every length a multiple of the chunk length: the kernels work on the caller's tensors."""
+    lens = [64, 192, 128]
+    p = ob.make_params(1, sum(lens), 2, 128, 128, True)
+    dense = ob.osdn_workspace_bytes(p, True)
+    packed = ob.osdn_workspace_bytes_packed(p, _cu(lens), True)
+    assert dense <= packed <= dense + 4096          # only the index tables on top
+    _compare(lens, H=2, K=128, V=128, seed=62, bf16=True, hp=ob.Hyper(eta=0.5))
+
+
+def test_long_packed_axis_spans_segments():
+    """Enough chunks that the two phases are pipelined over several segments, with sequences
+    that begin and end inside, and straddle, the segment boundaries."""
+    lens = [700, 1300, 64 * 10 + 5, 900, 17]
+    _compare(lens, H=1, K=64, V=64, seed=63, bf16=False, hp=ob.Hyper(eta=0.3))
+
+
+def test_defaults_null_ungated_no_retention():
+    _compare([100, 28, 130], H=2, K=128, V=64, seed=64, bf16=False, hp=ob.Hyper(eta=0.5), retention=0.0,
+             gated=False, carried=False)
+
+
+def test_paper_hyperparameters_bf16_k128():
+    """The paper's eta and box on a packed axis shaped like a training batch in miniature:
+    documents of uneven length, capped, K = V = 128 in bf16."""
+    rng = np.random.default_rng(65)
+    lens = [int(v) for v in np.minimum(rng.geometric(1.0 / 300.0, size=8) + 1, 1024)]
+    _compare(lens, H=2, K=128, V=128, seed=65, bf16=True, hp=ob.Hyper())
+
+
+def test_packed_equals_separate_calls_bitwise():
+    """Each sequence starts on a chunk boundary inside the library, so the packed call must give
+    exactly what one call per sequence gives."""
+    lens = [130, 64, 5, 257]
+    H, K, V, bf16, hp = 2, 64, 128, True, ob.Hyper(eta=0.5)
+    x = _packed_inputs(lens, H, K, V, seed=66, bf16=bf16)
+    got, t = _gpu_packed(x, lens, hp, bf16, backward=True)
+    cu = _cu(lens)
+    for s in range(len(lens)):
+        sl = slice(cu[s], cu[s + 1])
+        tk = lambda a: None if a is None else a[:, sl].contiguous()
+        cr = lambda a: None if a is None else a[s:s + 1].contiguous()
+        o, S, d, ctx = ob.forward(tk(t["q"]), tk(t["k"]), tk(t["v"]), tk(t["beta"]), tk(t["log_alpha"]),
+                                  tk(t["retention"]), cr(t["d_in"]), cr(t["S_in"]), hp, for_backward=True)
+        g = ob.backward(ctx, tk(t["dO"]), torch.from_numpy(x["dS_out"][s:s + 1]).cuda(),
+                        torch.from_numpy(x["dd_out"][s:s + 1]).cuda())
+        torch.cuda.synchronize()
+        one = {"o": o, "S_out": S, "d_out": d, **g}
+        for name, val in one.items():
+            ref = got[name][s:s + 1] if name in ("S_out", "d_out", "dd_in", "dS_in") else got[name][:, sl]
+            assert torch.equal(val, ref), (name, s)

@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     L = ob.lib()
     names = _declared_symbols()
     assert {"osdn_fwd", "osdn_bwd", "osdn_precond_update", "osdn_step", "osdn_workspace_bytes",
-            "osdn_strerror"} <= set(names)
+            "osdn_fwd_packed", "osdn_bwd_packed", "osdn_workspace_bytes_packed", "osdn_strerror"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -79,6 +79,30 @@ def test_argument_errors_before_any_pointer_is_used():
     args[4] = fake      # log_alpha given ...
     args[15] = None     # ... but dlog_alpha missing
     assert L.osdn_bwd(ctypes.byref(p), *args, fake, ctypes.c_size_t(1 << 30), None) == -1
+
+
+def test_packed_sequences_workspace_and_validation():
+    p = ob.make_params(1, 128, 1, 64, 64, False)
+    dense = ob.osdn_workspace_bytes(p, True)
+    aligned = ob.osdn_workspace_bytes_packed(p, [0, 64, 128], True)
+    assert dense <= aligned <= dense + 4096               # whole chunks: only the index tables on top
+    # ragged sequences are padded to whole chunks each, and copied
+    assert ob.osdn_workspace_bytes_packed(p, [0, 60, 128], True) > aligned
+    # offsets must start at 0, end at T and ascend strictly (no empty sequence); packed means B == 1
+    for bad in ([1, 64, 128], [0, 64, 100], [0, 64, 64, 128], [0, 128, 64, 128]):
+        assert ob.osdn_workspace_bytes_packed(p, bad, True) == 0, bad
+    assert ob.osdn_workspace_bytes_packed(ob.make_params(2, 128, 1, 64, 64, False), [0, 64, 128], True) == 0
+    L = ob.lib()
+    fake = ctypes.c_void_p(0x1000)
+    cu = (ctypes.c_int32 * 3)(0, 64, 100)
+    rc = L.osdn_fwd_packed(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
+                           cu, 2, fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == -2
+    rc = L.osdn_fwd_packed(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
+                           None, 2, fake, ctypes.c_size_t(1 << 30), None)
+    assert rc == -1
+    args = [fake] * 19
+    assert L.osdn_bwd_packed(ctypes.byref(p), *args, cu, 2, fake, ctypes.c_size_t(1 << 30), None) == -2
 
 
 def test_binding_rejects_cpu_tensors_and_wrong_dtypes():
