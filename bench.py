@@ -87,6 +87,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--packed-tokens", type=int, default=0,
+                    help="side workload, not the headline: the configuration's heads on ONE packed token axis of this "
+                         "many tokens (the paper trains on 65536 per GPU), cut into documents of uneven length "
+                         "capped at 4096 tokens, state and preconditioner reset at every boundary")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain device copy of 1 GiB (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -100,6 +104,14 @@ def main():
     from paper_2605_13473_amd.inputs import CONFIGS, make_inputs
 
     cfg = CONFIGS[args.config]
+    cu = None
+    if args.packed_tokens > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, B=1, T=args.packed_tokens, name=cfg.name + "_packed")
+        rng = np.random.Generator(np.random.Philox(1))
+        cu = [0]
+        while cu[-1] < cfg.T:       # document lengths: 1 + exponential of mean 1200, capped at 4096
+            cu.append(min(cfg.T, cu[-1] + min(4096, 1 + int(rng.exponential(1200.0)))))
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     ob.lib()                                        # fail loudly if the HIP library is not built
     x = make_inputs(cfg, seed=0)
@@ -112,19 +124,29 @@ def main():
     tr = None if x["retention"] is None else torch.from_numpy(x["retention"]).to(dev)
     hp = ob.Hyper()
     p = ob.make_params(cfg.B, cfg.T, cfg.H, cfg.K, cfg.V, cfg.bf16, hp)
-    ws = ob.alloc_workspace(p, cfg.backward, dev)
+    if cu is None:
+        ws = ob.alloc_workspace(p, cfg.backward, dev)
+    else:
+        ws = torch.empty(ob.osdn_workspace_bytes_packed(p, cu, cfg.backward), dtype=torch.uint8, device=dev)
+    nb = cfg.B if cu is None else len(cu) - 1           # entries of the carried tensors
     f32 = dict(dtype=torch.float32, device=dev)
     o = torch.empty_like(tv)
-    S_out = torch.empty(cfg.B, cfg.H, cfg.V, cfg.K, **f32)
-    d_out = torch.empty(cfg.B, cfg.H, cfg.K, **f32)
+    S_out = torch.empty(nb, cfg.H, cfg.V, cfg.K, **f32)
+    d_out = torch.empty(nb, cfg.H, cfg.K, **f32)
     dq, dk, dv = torch.empty_like(tq), torch.empty_like(tk), torch.empty_like(tv)
     dbeta = torch.empty_like(tb)
     dg = None if tg is None else torch.empty_like(tb)
     dr = None if tr is None else torch.empty_like(tb)
-    dd_in = torch.empty(cfg.B, cfg.H, cfg.K, **f32)
-    dS_in = torch.empty(cfg.B, cfg.H, cfg.V, cfg.K, **f32)
+    dd_in = torch.empty(nb, cfg.H, cfg.K, **f32)
+    dS_in = torch.empty(nb, cfg.H, cfg.V, cfg.K, **f32)
 
     def step():
+        if cu is not None:
+            ob.osdn_fwd_packed(p, tq, tk, tv, tb, tg, tr, None, None, o, S_out, d_out, cu, ws)
+            if cfg.backward:
+                ob.osdn_bwd_packed(p, tq, tk, tv, tb, tg, tr, None, None, tdO, None, None, dq, dk, dv, dbeta, dg,
+                                   dr, dd_in, dS_in, cu, ws)
+            return
         ob.osdn_fwd(p, tq, tk, tv, tb, tg, tr, None, None, o, S_out, d_out, ws)
         if cfg.backward:
             ob.osdn_bwd(p, tq, tk, tv, tb, tg, tr, None, None, tdO, None, None, dq, dk, dv, dbeta, dg, dr,
@@ -157,6 +179,7 @@ def main():
     # a kernel may be launched once per segment of the sequence: durations and work are
     # summed over the launches of one step (= launch-weighted average rate)
     per_kernel = {k: ms / args.steps for k, (ms, n) in prof.items() if n > 0}
+    copies_ms = per_kernel.pop("pad", None)         # moving ragged / packed sequences onto chunk boundaries
     launches = {k: n // args.steps for k, (ms, n) in prof.items() if n > 0}
     dominant = max(per_kernel, key=per_kernel.get)
     models, flops = kernel_models(cfg, es)
@@ -170,12 +193,14 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": nbytes / dur / 1e9, "peak": PEAK_HBM_BYTES / 1e9,
                 "unit": "GB/s", "frac": hbm_frac, "traffic": None}
-    if args.config == 2:
+    if args.config == 2 and cu is None:
         roof["traffic"] = MEASURED_TRAFFIC_CONFIG2.get(dominant)
     roof["kernel"] = dominant
     roof["kernel_ms"] = per_kernel[dominant]
     roof["per_kernel_ms"] = {k: round(v, 4) for k, v in per_kernel.items()}
     roof["launches_per_step"] = launches[dominant]
+    if copies_ms is not None:
+        roof["per_kernel_ms"]["pad (copies)"] = round(copies_ms, 4)
 
     # whole-path algorithmic flops (MFMA only) per token-head, for the %-of-peak figure
     K, V, C = cfg.K, cfg.V, 64
@@ -186,7 +211,7 @@ def main():
     mfma_peak_frac = total_flops / (ms_per_step * 1e-3) / PEAK_BF16_FLOPS
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and cu is None:
         import oracle
         nthreads = oracle.threads()
         nch = min(cfg.B * cfg.H, 8 * nthreads)       # ~10-30 core-seconds of oracle work
@@ -217,7 +242,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg.name}: B={cfg.B} T={cfg.T} H={cfg.H} "
                                f"K={cfg.K} V={cfg.V} chunk=64 {'fwd+bwd' if cfg.backward else 'fwd'}",
-                   "global_batch": cfg.B, "seq_len": cfg.T, "apf": cfg.apf},
+                   "global_batch": cfg.B, "seq_len": cfg.T, "apf": cfg.apf,
+                   **({} if cu is None else {"packed_sequences": len(cu) - 1})},
         "mfma_peak_frac": mfma_peak_frac,
         "roofline": roof,
         "cpu_baseline": cpu,

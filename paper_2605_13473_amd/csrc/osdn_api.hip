@@ -67,6 +67,7 @@ int check_params(const osdn_params *p, bool need_chunks) {
 struct Packing {
     int n_seqs = 0;
     int N = 0;                   // chunks of the padded token axis (per batch entry)
+    int longest = 0;             // chunks of the longest sequence
     bool ragged = false;         // some sequence is not a whole number of chunks: work on padded copies
     std::vector<int> tables;     // seq_chunks [n_seqs + 1], chunk_row [N], chunk_len [N]
 };
@@ -81,6 +82,7 @@ int make_packing(const osdn_params *p, const int32_t *cu, int n_seqs, Packing &p
         const long long len = (long long)cu[s + 1] - cu[s];
         if (len < 1) return OSDN_ERR_SHAPE;
         N += (len + C - 1) / C;
+        if ((len + C - 1) / C > pk.longest) pk.longest = (int)((len + C - 1) / C);
         pk.ragged = pk.ragged || len % C != 0;
     }
     if (N * C > 0x7fffffffLL) return OSDN_ERR_SHAPE;
@@ -102,6 +104,7 @@ int make_packing(const osdn_params *p, const int32_t *cu, int n_seqs, Packing &p
 
 void plain_packing(const osdn_params *p, Packing &pk) {
     pk.N = (p->T + C - 1) / C;
+    pk.longest = pk.N;
     pk.ragged = pk.N * C != p->T;
 }
 
@@ -213,9 +216,14 @@ Pipeline *pipeline_for_current_device() {
 // number of segments for a sequence of N chunks: about 20 chunks each, between two (any
 // sequence of at least two chunks, so that short sequences take the same path) and four:
 // more segments buy little overlap and cost launches and cross-stream waits
-// (OSDN_SEGMENTS in the environment overrides it; 1 = no pipelining)
-int segment_count(int N) {
+// (OSDN_SEGMENTS in the environment overrides it; 1 = no pipelining).
+// Segments cut the chunk axis as a whole.  With packed sequences the sequential kernels of a
+// segment only have the sequences that cross it to work on, one after the other segment by
+// segment, so cutting pays only while one sequence makes up most of the axis; otherwise the
+// many independent chains fill the chip by themselves and everything runs in one piece.
+int segment_count(int N, int longest) {
     static const int forced = [] { const char *e = std::getenv("OSDN_SEGMENTS"); return e ? std::atoi(e) : 0; }();
+    if (forced <= 0 && (long long)longest * 4 < (long long)N * 3) return 1;
     int S = forced > 0 ? forced : N / 20;
     if (forced <= 0 && S > 4) S = 4;
     if (forced <= 0 && S < 2 && N >= 2) S = 2;
@@ -375,7 +383,7 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     c.n_seqs = pk.n_seqs; c.seq_chunks = seq_chunks; c.S_first = S_in;
 
     const int N = p->T / C;
-    int S = segment_count(N);
+    int S = segment_count(N, pk.longest);
     std::lock_guard<std::mutex> lock(g_pipe_mu);
     Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
     if (!pl) S = 1;
@@ -508,7 +516,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
 
     const int N = p->T / C;
-    int S = segment_count(N);
+    int S = segment_count(N, pk.longest);
     std::lock_guard<std::mutex> lock(g_pipe_mu);
     Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
     if (!pl) S = 1;

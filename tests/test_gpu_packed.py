@@ -101,11 +101,17 @@ def test_whole_chunk_lengths_take_no_copies():
     _compare(lens, H=2, K=128, V=128, seed=62, bf16=True, hp=ob.Hyper(eta=0.5))
 
 
-def test_long_packed_axis_spans_segments():
-    """Enough chunks that the two phases are pipelined over several segments, with sequences
-    that begin and end inside, and straddle, the segment boundaries."""
+def test_long_packed_axis_many_sequences():
+    """Many chunks, no dominant sequence: the chains of all sequences run side by side in one piece."""
     lens = [700, 1300, 64 * 10 + 5, 900, 17]
     _compare(lens, H=1, K=64, V=64, seed=63, bf16=False, hp=ob.Hyper(eta=0.3))
+
+
+@pytest.mark.parametrize("lens", [[150, 3000, 100, 200], [2500, 70, 1]])
+def test_dominant_sequence_is_pipelined_over_segments(lens):
+    """One sequence makes up most of the axis: the two phases are pipelined over segments of the
+    chunk axis, with sequences that begin and end inside a segment and one that straddles them."""
+    _compare(lens, H=1, K=64, V=64, seed=67, bf16=False, hp=ob.Hyper(eta=0.3))
 
 
 def test_defaults_null_ungated_no_retention():
