@@ -80,6 +80,54 @@ def kernel_models(cfg, es):
     return m, flops
 
 
+def decode_bench(args, cfg):
+    """osdn_step on [B,1,H,*]: every launch reads and writes the whole state once (HBM-bound)."""
+    import torch
+    from paper_2605_13473_amd import binding as ob
+    B, H, K, V = args.decode_batch, cfg.H, cfg.K, cfg.V
+    dev, dt = "cuda:0", torch.bfloat16 if cfg.bf16 else torch.float32
+    g = torch.Generator(device=dev).manual_seed(0)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, generator=g)
+    unit = lambda a: a / a.norm(dim=-1, keepdim=True)
+    q, k, v = unit(rnd(B, 1, H, K)).to(dt), unit(rnd(B, 1, H, K)).to(dt), rnd(B, 1, H, V).to(dt)
+    beta, la = torch.sigmoid(rnd(B, 1, H)), -torch.nn.functional.softplus(rnd(B, 1, H))
+    ret = torch.sigmoid(6.9 + rnd(B, 1, H)) if cfg.apf else None
+    S = 0.1 * rnd(B, H, V, K)
+    d = [torch.ones(B, H, K, device=dev), torch.empty(B, H, K, device=dev)]
+    o = torch.empty_like(v)
+    p = ob.make_params(B, 1, H, K, V, cfg.bf16, ob.Hyper())
+
+    def step(i):
+        ob.osdn_step(p, q, k, v, beta, la, ret, d[i & 1], S, o, S, d[(i + 1) & 1])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ob.osdn_profile_enable(True)
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms, n = ob.osdn_profile_read()["step"]
+    ob.osdn_profile_enable(False)
+    es = 2 if cfg.bf16 else 4
+    nbytes = B * H * (2 * V * K * 4 + 2 * K * 4 + (2 * K + 2 * V) * es + 12)     # S and d in and out, q k v o, gates
+    dur = ms / n * 1e-3
+    print(json.dumps({
+        "metric": "OSDN recurrent step (decode), tokens/s", "value": B * args.steps / (t1 - t0), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * (t1 - t0) / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"decode step: B={B} T=1 H={H} K={K} V={V}, state in place, "
+                               f"{'bf16' if cfg.bf16 else 'f32'} I/O, fp32 state"},
+        "roofline": {"bound": "hbm", "achieved": nbytes / dur / 1e9, "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s",
+                     "frac": nbytes / dur / PEAK_HBM_BYTES, "traffic": None, "kernel": "step", "kernel_ms": ms / n},
+        "cpu_baseline": None}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,6 +139,9 @@ def main():
                     help="side workload, not the headline: the configuration's heads on ONE packed token axis of this "
                          "many tokens (the paper trains on 65536 per GPU), cut into documents of uneven length "
                          "capped at 4096 tokens, state and preconditioner reset at every boundary")
+    ap.add_argument("--decode-batch", type=int, default=0,
+                    help="side workload, not the headline: time osdn_step (one token per sequence and launch, state "
+                         "updated in place) for this many sequences with the configuration's heads")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain device copy of 1 GiB (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -104,6 +155,8 @@ def main():
     from paper_2605_13473_amd.inputs import CONFIGS, make_inputs
 
     cfg = CONFIGS[args.config]
+    if args.decode_batch > 0:
+        return decode_bench(args, cfg)
     cu = None
     if args.packed_tokens > 0:
         import dataclasses
