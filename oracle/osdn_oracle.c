@@ -13,6 +13,9 @@
  *     the reference semantics in Appendix C, Listing 1 (eps floors the squared
  *     key norm, the alignment <d,k^2> uses the un-retained d, clamp after every
  *     step, non-beta-aware mode replaces beta by 1 in the d update only);
+ *     with ret_vec the retention is one value per coordinate, diag(r_t) in
+ *     place of r_t I (the vector-retention extension stated with the
+ *     proposition that APF is a piecewise-affine recurrence, appendix on APF);
  *   - phase 2 (state): Eq. (equiv_update) / Eq. (recurrent_form) with the gate
  *     of Appendix B.1 ("post-gate" form: decay S first, read with the unscaled
  *     key k, write with k~ = d (.) k), read-out o_t = S_t q_t from Table
@@ -23,7 +26,8 @@
  *     differentiation of the forward loop written below.
  *
  * Layouts (all row-major, fp64): q,k [B,T,H,K]; v,o [B,T,H,V]; beta,
- * log_alpha, retention [B,T,H]; d [B,H,K]; S [B,H,V,K].
+ * log_alpha, retention [B,T,H] (retention and its gradient [B,T,H,K] with
+ * ret_vec); d [B,H,K]; S [B,H,V,K].
  * NULL log_alpha => alpha = 1 (ungated OSDN); NULL retention => r = 1;
  * NULL d_in => ones; NULL S_in => zeros.  d_min > d_max => no projection.
  *
@@ -43,7 +47,17 @@ typedef struct {
     double d_min, d_max;
     double eps;        /* floor of the squared key norm (1e-6) */
     int beta_aware;    /* 1: beta enters the d update; 0: beta replaced by 1 there */
+    int ret_vec;       /* 1: retention is a vector per token and head, [B,T,H,K]: the
+                          diag(r_t) extension of the APF step (proposition on APF being a
+                          piecewise-affine recurrence, appendix); 0: scalar, [B,T,H] */
 } osdn_oracle_params;
+
+/* retention of coordinate j of token-head th (NULL => 1) */
+static double ret_at(const osdn_oracle_params *P, const double *retention, size_t th, int j)
+{
+    if (!retention) return 1.0;
+    return P->ret_vec ? retention[th * (size_t)P->K + j] : retention[th];
+}
 
 int osdn_oracle_threads(void)
 {
@@ -59,10 +73,11 @@ typedef struct {
     double n_raw, n, p, bp, c;
 } p1_scalars;
 
-/* d (in/out, K), k (K) ; writes k_tilde (K) if non-NULL, d_bar (K) if non-NULL */
+/* d (in/out, K), k (K) ; writes k_tilde (K) if non-NULL, d_bar (K) if non-NULL ;
+ * retention / th: as for ret_at */
 static void phase1_step(const osdn_oracle_params *P, const double *k, double beta,
-                        double r, double *d, double *k_tilde, double *d_bar,
-                        p1_scalars *out)
+                        const double *retention, size_t th, double *d, double *k_tilde,
+                        double *d_bar, p1_scalars *out)
 {
     const int K = P->K;
     double n_raw = 0.0, p = 0.0;
@@ -78,7 +93,7 @@ static void phase1_step(const osdn_oracle_params *P, const double *k, double bet
     const int project = P->d_min <= P->d_max;
     for (int j = 0; j < K; ++j) {
         double s = k[j] * k[j];
-        double db = r * d[j] + c * s;
+        double db = ret_at(P, retention, th, j) * d[j] + c * s;
         if (d_bar) d_bar[j] = db;
         if (project) {
             if (db < P->d_min) db = P->d_min;
@@ -119,7 +134,7 @@ int osdn_oracle_precond(const osdn_oracle_params *P, const double *k, const doub
             for (int t = 0; t < T; ++t) {
                 size_t th = ((size_t)b * T + t) * H + h;
                 if (d_traj) memcpy(d_traj + th * K, d, sizeof(double) * K);
-                phase1_step(P, k + th * K, beta[th], retention ? retention[th] : 1.0, d,
+                phase1_step(P, k + th * K, beta[th], retention, th, d,
                             k_tilde ? k_tilde + th * K : NULL, NULL, NULL);
             }
         }
@@ -149,7 +164,7 @@ int osdn_oracle_fwd(const osdn_oracle_params *P, const double *q, const double *
                 const double *kk = k + th * K, *qq = q + th * K, *vv = v + th * V;
                 double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
                 /* phase 1 for this token: emits k~_t from d_t, then advances d */
-                phase1_step(P, kk, beta[th], retention ? retention[th] : 1.0, d, kt, NULL, NULL);
+                phase1_step(P, kk, beta[th], retention, th, d, kt, NULL, NULL);
                 /* phase 2 for this token */
                 phase2_step(K, V, alpha, beta[th], kk, kt, vv, S, u);
                 /* read-out from the post-write state */
@@ -222,7 +237,7 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                     memcpy(ckd + (size_t)(t / SEG) * K, d, sizeof(double) * K);
                 }
                 double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
-                phase1_step(P, k + th * K, beta[th], retention ? retention[th] : 1.0, d, kt, NULL, NULL);
+                phase1_step(P, k + th * K, beta[th], retention, th, d, kt, NULL, NULL);
                 phase2_step(K, V, alpha, beta[th], k + th * K, kt, v + th * V, S, u);
             }
             /* adjoints of the returned state and preconditioner */
@@ -239,7 +254,7 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                     memcpy(Sprev + (size_t)(t - t0) * VK, S, sizeof(double) * VK);
                     memcpy(dtr + (size_t)(t - t0) * K, d, sizeof(double) * K);
                     double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
-                    phase1_step(P, k + th * K, beta[th], retention ? retention[th] : 1.0, d, kt, NULL, NULL);
+                    phase1_step(P, k + th * K, beta[th], retention, th, d, kt, NULL, NULL);
                     phase2_step(K, V, alpha, beta[th], k + th * K, kt, v + th * V, S, u);
                 }
                 for (int t = t1 - 1; t >= t0; --t) {
@@ -247,7 +262,6 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                     const double *kk = k + th * K, *qq = q + th * K, *vv = v + th * V;
                     const double *go = dO + th * V;
                     const double bt = beta[th];
-                    const double r = retention ? retention[th] : 1.0;
                     const double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
                     const double *Sm1 = Sprev + (size_t)(t - t0) * VK;
                     double *gk = dk + th * K;
@@ -255,7 +269,7 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                     memcpy(d, dtr + (size_t)(t - t0) * K, sizeof(double) * K);
                     p1_scalars sc;
                     double *dcur = dtr + (size_t)(t - t0) * K; /* d_t (kept intact) */
-                    phase1_step(P, kk, bt, r, d, kt, dbar, &sc);       /* d now holds d_{t+1} */
+                    phase1_step(P, kk, bt, retention, th, d, kt, dbar, &sc);   /* d now holds d_{t+1} */
                     memcpy(Sbar, Sm1, sizeof(double) * VK);
                     /* S_t = phase2(S_{t-1}); keep Sbar = alpha S_{t-1} separately */
                     memcpy(S, Sm1, sizeof(double) * VK);
@@ -264,12 +278,13 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
 
                     for (int j = 0; j < K; ++j) gk[j] = 0.0;
 
-                    /* ---- phase-1 adjoint: d_{t+1} = clip(r d_t + c s) ---- */
+                    /* ---- phase-1 adjoint: d_{t+1} = clip(r (.) d_t + c s) ---- */
                     double g_r = 0.0, g_c = 0.0;
                     for (int j = 0; j < K; ++j) {
                         double g = gd[j];
                         if (project && !(dbar[j] >= P->d_min && dbar[j] <= P->d_max)) g = 0.0;
                         gd[j] = g;                       /* now adjoint of d_bar */
+                        if (dretention && P->ret_vec) dretention[th * K + j] = g * dcur[j];
                         g_r += g * dcur[j];
                         g_c += g * kk[j] * kk[j];
                     }
@@ -282,9 +297,9 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                         double s = kk[j] * kk[j];
                         double gs = sc.c * gd[j] + g_p * dcur[j] + g_nraw;
                         gk[j] += 2.0 * kk[j] * gs;
-                        gdn[j] = r * gd[j] + g_p * s;   /* adjoint of d_t, phase-1 part */
+                        gdn[j] = ret_at(P, retention, th, j) * gd[j] + g_p * s;   /* adjoint of d_t, phase-1 part */
                     }
-                    if (dretention) dretention[th] = g_r;
+                    if (dretention && !P->ret_vec) dretention[th] = g_r;
 
                     /* ---- phase-2 adjoint ---- */
                     /* o = scale S_t q */

@@ -242,6 +242,65 @@ def test_pure_retention_closed_form():
     np.testing.assert_allclose(dT, np.maximum(0.5, np.prod(r) * d0), rtol=1e-12)
 
 
+def test_vector_retention_definition_and_scalar_special_case():
+    """One retention per coordinate (the diag(r_t) extension of the APF step): the step coded
+    here from its definition, token by token; a vector whose entries are all equal is the
+    scalar gate, forward and backward (the scalar's gradient is the sum over coordinates)."""
+    rng = np.random.default_rng(12)
+    B, T, H, K, V = 2, 40, 2, 6, 3
+    k = rng.standard_normal((B, T, H, K)); k /= np.linalg.norm(k, axis=-1, keepdims=True)
+    beta = rng.uniform(0.05, 0.95, (B, T, H))
+    rv = rng.uniform(0.7, 1.0, (B, T, H, K))
+    d0 = rng.uniform(0.5, 2.0, (B, H, K))
+    hp = Hyper(eta=1.1)
+    kt, dT, traj = oracle.precond(k, beta, retention=rv, d_in=d0, hp=hp, want_traj=True)
+    d = d0.copy()
+    for t in range(T):
+        np.testing.assert_allclose(traj[:, t], d, rtol=1e-13)
+        np.testing.assert_allclose(kt[:, t], d * k[:, t], rtol=1e-13)
+        s = k[:, t] ** 2
+        step = 1.1 * beta[:, t] * (1 - beta[:, t] * (d * s).sum(-1)) / np.maximum(s.sum(-1), 1e-6)
+        d = np.clip(rv[:, t] * d + step[..., None] * s, 0.5, 2.0)
+    np.testing.assert_allclose(dT, d, rtol=1e-13)
+    assert ((traj == 0.5).any() or (dT == 0.5).any()) and (traj < 2.0).any()      # the box is active
+    # equal entries == the scalar gate
+    q = rng.standard_normal((B, T, H, K)); v = rng.standard_normal((B, T, H, V))
+    g = -np.log1p(np.exp(rng.standard_normal((B, T, H)))); dO = rng.standard_normal((B, T, H, V))
+    rs = rng.uniform(0.7, 1.0, (B, T, H))
+    rb = np.ascontiguousarray(np.broadcast_to(rs[..., None], (B, T, H, K)))
+    wS = rng.standard_normal((B, H, V, K)); wd = rng.standard_normal((B, H, K))
+    a = oracle.fwd(q, k, v, beta, g, rs, d0, None, hp)
+    b = oracle.fwd(q, k, v, beta, g, rb, d0, None, hp)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    ga = oracle.bwd(q, k, v, beta, dO, g, rs, d0, None, dS_out=wS, dd_out=wd, hp=hp)
+    gb = oracle.bwd(q, k, v, beta, dO, g, rb, d0, None, dS_out=wS, dd_out=wd, hp=hp)
+    for name in ga:
+        if name == "dretention":
+            assert gb[name].shape == (B, T, H, K)
+            np.testing.assert_allclose(gb[name].sum(-1), ga[name], rtol=1e-12, atol=1e-14)
+        else:
+            assert np.array_equal(ga[name], gb[name]), name
+
+
+def test_pure_vector_retention_closed_form():
+    """eta = 0, no projection: d_T = (prod_t r_t) (.) d_0 coordinate by coordinate, and the
+    gradients of sum(w (.) d_T) are the products that leave one factor out."""
+    rng = np.random.default_rng(13)
+    B, T, H, K, V = 1, 30, 1, 4, 2
+    k = rng.standard_normal((B, T, H, K)); beta = rng.uniform(0.1, 0.9, (B, T, H))
+    r = rng.uniform(0.9, 1.0, (B, T, H, K)); d0 = rng.uniform(0.5, 2.0, (B, H, K))
+    hp = Hyper(eta=0.0, d_min=1.0, d_max=0.0)
+    _, dT = oracle.precond(k, beta, retention=r, d_in=d0, hp=hp)
+    P = np.prod(r, axis=1)                                   # [B,H,K]
+    np.testing.assert_allclose(dT, P * d0, rtol=1e-13)
+    w = rng.standard_normal((B, H, K))
+    z = np.zeros((B, T, H, V))
+    g = oracle.bwd(np.zeros_like(k), k, z, beta, z, None, r, d0, None, dd_out=w, hp=hp)
+    np.testing.assert_allclose(g["dd_in"], w * P, rtol=1e-12)
+    np.testing.assert_allclose(g["dretention"], (w * P * d0)[:, None] / r, rtol=1e-12)
+
+
 def test_fixed_point_of_beta_aware_update():
     """beta <d,k^2> = 1 leaves d unchanged (the post-gate-regret fixed point)."""
     k = np.zeros((1, 5, 1, 4)); k[..., 1] = 1.0
@@ -331,7 +390,8 @@ def _loss(x, hp, wO, wS, wd):
     return (o * wO).sum() + (S * wS).sum() + (d * wd).sum()
 
 
-@pytest.mark.parametrize("case", ["plain", "clamp_active", "non_beta_aware", "ungated_noapf"])
+@pytest.mark.parametrize("case", ["plain", "clamp_active", "non_beta_aware", "ungated_noapf",
+                                  "vector_retention", "vector_retention_clamp_active"])
 def test_backward_against_central_differences(case):
     """Every gradient the oracle returns, against central finite differences of its forward
     (fp64, h = 1e-6), including through the box projection (clamp-active case: coordinates
@@ -339,9 +399,14 @@ def test_backward_against_central_differences(case):
     B, T, H, K, V = 1, 70, 2, 5, 4          # T > 64 crosses a replay-segment boundary
     gated = case != "ungated_noapf"
     x = make_stress_inputs(B, T, H, K, V, seed=15, gated=gated,
-                           retention={"ungated_noapf": 0.0, "clamp_active": 0.85}.get(case, 0.95))
+                           retention={"ungated_noapf": 0.0, "clamp_active": 0.85,
+                                      "vector_retention_clamp_active": 0.85}.get(case, 0.95))
     x = {n: (None if a is None else a.astype(np.float64)) for n, a in x.items()}
-    eta = {"plain": 0.05, "clamp_active": 2.5, "non_beta_aware": 0.05, "ungated_noapf": 0.05}[case]
+    if case.startswith("vector_retention"):     # one retention per coordinate: diag(r_t)
+        x["retention"] = np.clip(x["retention"][..., None]
+                                 + 0.04 * np.random.default_rng(17).standard_normal((B, T, H, K)), 0.0, 1.0)
+    eta = {"plain": 0.05, "clamp_active": 2.5, "non_beta_aware": 0.05, "ungated_noapf": 0.05,
+           "vector_retention": 0.05, "vector_retention_clamp_active": 2.5}[case]
     if case == "plain":
         x["d_in"] = 1.0 + 0.2 * (x["d_in"] - 1.25)       # stay inside the box
     hp = Hyper(eta=eta, beta_aware=(case != "non_beta_aware"))
@@ -349,7 +414,7 @@ def test_backward_against_central_differences(case):
     wO = x["dO"]; wS = rng.standard_normal(x["S_in"].shape); wd = rng.standard_normal(x["d_in"].shape)
     g = oracle.bwd(x["q"], x["k"], x["v"], x["beta"], wO, x["log_alpha"], x["retention"],
                    x["d_in"], x["S_in"], dS_out=wS, dd_out=wd, hp=hp)
-    if case == "clamp_active":
+    if case.endswith("clamp_active"):
         _, _, traj = oracle.precond(x["k"], x["beta"], x["retention"], x["d_in"], hp, want_traj=True)
         frac = np.mean((traj == 0.5) | (traj == 2.0))
         assert frac > 0.05, frac
