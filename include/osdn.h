@@ -36,7 +36,9 @@
  *     preconditioner phase on it, forked from and joined back into `stream`, so that to the
  *     caller all work still is ordered as if enqueued on `stream`.  Calls are serialised by a
  *     mutex while they enqueue.  OSDN_SEGMENTS=1 in the environment keeps everything on `stream`.
- *   - retention values are assumed >= 0 (they are sigmoid gates in the paper).
+ *   - retention values are assumed >= 0 (they are sigmoid gates in the paper).  Wherever a
+ *     signature says retention / dretention [B,T,H], params->retention_per_channel = 1 makes
+ *     it [B,T,H,K]: one value per coordinate.
  *   - Supported shapes: chunk == 64; any T >= 1 (osdn_fwd/osdn_bwd pad a ragged last chunk
  *     inside the workspace with tokens that change nothing; osdn_precond_update needs
  *     T % 64 == 0 only when d_ckpt is asked for; 1 <= T <= 64 for osdn_step); K in {64, 128};
@@ -72,6 +74,10 @@ typedef struct {
     float d_min, d_max;             /* box of the projection (paper: 0.5, 2.0); d_min > d_max => none */
     float eps;                      /* floor of the squared key norm (Listing 1: 1e-6) */
     int32_t beta_aware;             /* 1: beta enters the d update (default); 0: replaced by 1 there */
+    int32_t retention_per_channel;  /* 0: retention is one gate per (token, head), [B,T,H] (Section 4.4);
+                                       1: one per coordinate, [B,T,H,K], diag(r_t) in place of r_t I (the
+                                       vector-retention extension stated with the proposition that APF is a
+                                       piecewise-affine recurrence); dretention then has that shape too */
 } osdn_params;
 
 /* Bytes of scratch osdn_fwd needs (for_backward == 0) or osdn_fwd followed by osdn_bwd

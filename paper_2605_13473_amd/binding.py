@@ -31,7 +31,7 @@ class OsdnParams(ctypes.Structure):
         ("io_dtype", ctypes.c_int32),
         ("scale", ctypes.c_float), ("eta", ctypes.c_float),
         ("d_min", ctypes.c_float), ("d_max", ctypes.c_float), ("eps", ctypes.c_float),
-        ("beta_aware", ctypes.c_int32),
+        ("beta_aware", ctypes.c_int32), ("retention_per_channel", ctypes.c_int32),
     ]
 
 
@@ -140,7 +140,7 @@ def osdn_precond_update(params, k, beta, retention, d_in, k_tilde, d_out, d_ckpt
     _check(lib().osdn_precond_update(
         ctypes.byref(p),
         _ptr(k, io, (p.B, p.T, p.H, p.K), "k"), _ptr(beta, f32, (p.B, p.T, p.H), "beta"),
-        _ptr(retention, f32, (p.B, p.T, p.H), "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
+        _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
         _ptr(k_tilde, io, (p.B, p.T, p.H, p.K), "k_tilde"), _ptr(d_out, f32, (p.B, p.H, p.K), "d_out"),
         _ptr(d_ckpt, f32, None, "d_ckpt"), _stream_ptr(stream)))
 
@@ -152,7 +152,7 @@ def osdn_step(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out,
     _check(lib().osdn_step(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
         _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
-        _ptr(retention, f32, bth, "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
+        _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
         _ptr(S_in, f32, (p.B, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
         _ptr(S_out, f32, (p.B, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (p.B, p.H, p.K), "d_out"),
         _stream_ptr(stream)))
@@ -166,7 +166,7 @@ def osdn_fwd(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, 
     _check(lib().osdn_fwd(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
         _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
-        _ptr(retention, f32, bth, "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
+        _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
         _ptr(S_in, f32, (p.B, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
         _ptr(S_out, f32, (p.B, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (p.B, p.H, p.K), "d_out"),
         _ptr(workspace, torch.uint8, None, "workspace"), ctypes.c_size_t(workspace.numel()),
@@ -182,11 +182,11 @@ def osdn_bwd(params, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out
     _check(lib().osdn_bwd(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
         _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
-        _ptr(retention, f32, bth, "retention"), _ptr(d_in, f32, bhk, "d_in"),
+        _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, bhk, "d_in"),
         _ptr(S_in, f32, bhvk, "S_in"), _ptr(dO, io, bthv, "dO"), _ptr(dS_out, f32, bhvk, "dS_out"),
         _ptr(dd_out, f32, bhk, "dd_out"), _ptr(dq, io, bthk, "dq"), _ptr(dk, io, bthk, "dk"),
         _ptr(dv, io, bthv, "dv"), _ptr(dbeta, f32, bth, "dbeta"),
-        _ptr(dlog_alpha, f32, bth, "dlog_alpha"), _ptr(dretention, f32, bth, "dretention"),
+        _ptr(dlog_alpha, f32, bth, "dlog_alpha"), _ptr(dretention, f32, _ret_shape(p), "dretention"),
         _ptr(dd_in, f32, bhk, "dd_in"), _ptr(dS_in, f32, bhvk, "dS_in"),
         _ptr(workspace, torch.uint8, None, "workspace"), ctypes.c_size_t(workspace.numel()),
         _stream_ptr(stream)))
@@ -212,7 +212,7 @@ def osdn_fwd_packed(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, 
     _check(lib().osdn_fwd_packed(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
         _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
-        _ptr(retention, f32, bth, "retention"), _ptr(d_in, f32, (n, p.H, p.K), "d_in"),
+        _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, (n, p.H, p.K), "d_in"),
         _ptr(S_in, f32, (n, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
         _ptr(S_out, f32, (n, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (n, p.H, p.K), "d_out"),
         cu, n, _ptr(workspace, torch.uint8, None, "workspace"), ctypes.c_size_t(workspace.numel()),
@@ -229,11 +229,11 @@ def osdn_bwd_packed(params, q, k, v, beta, log_alpha, retention, d_in, S_in, dO,
     _check(lib().osdn_bwd_packed(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
         _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
-        _ptr(retention, f32, bth, "retention"), _ptr(d_in, f32, bhk, "d_in"),
+        _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, bhk, "d_in"),
         _ptr(S_in, f32, bhvk, "S_in"), _ptr(dO, io, bthv, "dO"), _ptr(dS_out, f32, bhvk, "dS_out"),
         _ptr(dd_out, f32, bhk, "dd_out"), _ptr(dq, io, bthk, "dq"), _ptr(dk, io, bthk, "dk"),
         _ptr(dv, io, bthv, "dv"), _ptr(dbeta, f32, bth, "dbeta"),
-        _ptr(dlog_alpha, f32, bth, "dlog_alpha"), _ptr(dretention, f32, bth, "dretention"),
+        _ptr(dlog_alpha, f32, bth, "dlog_alpha"), _ptr(dretention, f32, _ret_shape(p), "dretention"),
         _ptr(dd_in, f32, bhk, "dd_in"), _ptr(dS_in, f32, bhvk, "dS_in"),
         cu, n, _ptr(workspace, torch.uint8, None, "workspace"), ctypes.c_size_t(workspace.numel()),
         _stream_ptr(stream)))
@@ -250,10 +250,18 @@ class Hyper:
     beta_aware: bool = True
 
 
-def make_params(B, T, H, K, V, bf16: bool, hp: Hyper = Hyper()) -> OsdnParams:
+def make_params(B, T, H, K, V, bf16: bool, hp: Hyper = Hyper(), retention_per_channel: bool = False) -> OsdnParams:
     scale = float(K) ** -0.5 if hp.scale is None else float(hp.scale)
     return OsdnParams(B, T, H, K, V, 64, OSDN_BF16 if bf16 else OSDN_F32, scale, hp.eta, hp.d_min,
-                      hp.d_max, hp.eps, int(hp.beta_aware))
+                      hp.d_max, hp.eps, int(hp.beta_aware), int(bool(retention_per_channel)))
+
+
+def _ret_shape(p: OsdnParams):
+    return (p.B, p.T, p.H, p.K) if p.retention_per_channel else (p.B, p.T, p.H)
+
+
+def _per_channel(retention) -> bool:
+    return retention is not None and retention.dim() == 4
 
 
 def alloc_workspace(params: OsdnParams, for_backward: bool, device="cuda") -> torch.Tensor:
@@ -269,7 +277,7 @@ def forward(q, k, v, beta, log_alpha=None, retention=None, d_in=None, S_in=None,
     given: B == 1, one carried entry per sequence).  Returns (o, S_out, d_out, ctx)."""
     B, T, H, K = k.shape
     V = v.shape[-1]
-    p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp)
+    p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp, _per_channel(retention))
     if cu_seqlens is not None:
         cu_seqlens = [int(x) for x in cu_seqlens]
     if workspace is None:
@@ -304,7 +312,7 @@ def backward(ctx, dO, dS_out=None, dd_out=None):
         "dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v),
         "dbeta": torch.empty_like(beta),
         "dlog_alpha": torch.empty_like(beta) if log_alpha is not None else None,
-        "dretention": torch.empty_like(beta) if retention is not None else None,
+        "dretention": torch.empty_like(retention) if retention is not None else None,
         "dd_in": torch.empty(nb, p.H, p.K, **f32), "dS_in": torch.empty(nb, p.H, p.V, p.K, **f32),
     }
     if cu is None:
@@ -324,7 +332,7 @@ def step(q, k, v, beta, log_alpha=None, retention=None, d_in=None, S_in=None, hp
     is updated where it is (and returned)."""
     B, T, H, K = k.shape
     V = v.shape[-1]
-    p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp)
+    p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp, _per_channel(retention))
     f32 = dict(dtype=torch.float32, device=k.device)
     o = torch.empty_like(v)
     S_out = S_in if (in_place and S_in is not None) else torch.empty(B, H, V, K, **f32)
@@ -336,7 +344,7 @@ def step(q, k, v, beta, log_alpha=None, retention=None, d_in=None, S_in=None, hp
 def precond_update(k, beta, retention=None, d_in=None, hp: Hyper = Hyper(), want_ckpt: bool = False):
     """Allocate outputs and call osdn_precond_update.  Returns (k_tilde, d_out[, d_ckpt])."""
     B, T, H, K = k.shape
-    p = make_params(B, T, H, K, 64, k.dtype == torch.bfloat16, hp)
+    p = make_params(B, T, H, K, 64, k.dtype == torch.bfloat16, hp, _per_channel(retention))
     kt = torch.empty_like(k)
     d_out = torch.empty(B, H, K, dtype=torch.float32, device=k.device)
     ck = torch.empty(B, H, T // 64, K, dtype=torch.float32, device=k.device) if want_ckpt else None

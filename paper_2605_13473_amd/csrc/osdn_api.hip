@@ -60,6 +60,7 @@ int check_params(const osdn_params *p, bool need_chunks) {
     if (!(p->eta >= 0.f) || !(p->eps > 0.f) || !std::isfinite(p->eta) || !std::isfinite(p->eps) ||
         !std::isfinite(p->scale) || std::isnan(p->d_min) || std::isnan(p->d_max))
         return OSDN_ERR_PARAM;
+    if (p->retention_per_channel != 0 && p->retention_per_channel != 1) return OSDN_ERR_PARAM;
     return OSDN_OK;
 }
 
@@ -112,6 +113,7 @@ void plain_packing(const osdn_params *p, Packing &pk) {
 Layout make_layout(const osdn_params *p, const Packing &pk) {
     const size_t es = p->io_dtype == OSDN_BF16 ? 2 : 4;
     const size_t B = p->B, H = p->H, K = p->K, V = p->V, N = (size_t)pk.N, T = N * C;
+    const size_t RK = p->retention_per_channel ? K : 1;    // retention values per (token, head)
     const bool ragged = pk.ragged;
     Layout L{};
     size_t off = 0;
@@ -130,7 +132,7 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     if (ragged) {
         L.p_q = take(B * T * H * K * es); L.p_k = take(B * T * H * K * es);
         L.p_v = take(B * T * H * V * es); L.p_o = take(B * T * H * V * es);
-        L.p_beta = take(B * T * H * 4); L.p_g = take(B * T * H * 4); L.p_r = take(B * T * H * 4);
+        L.p_beta = take(B * T * H * 4); L.p_g = take(B * T * H * 4); L.p_r = take(B * T * H * 4 * RK);
     }
     L.total_fwd = off;
     L.dElt = take(B * T * H * V * es);
@@ -145,7 +147,7 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     if (ragged) {
         L.p_dO = take(B * T * H * V * es); L.p_dv = take(B * T * H * V * es);
         L.p_dq = take(B * T * H * K * es); L.p_dk = take(B * T * H * K * es);
-        L.p_dbeta = take(B * T * H * 4); L.p_dg = take(B * T * H * 4); L.p_dr = take(B * T * H * 4);
+        L.p_dbeta = take(B * T * H * 4); L.p_dg = take(B * T * H * 4); L.p_dr = take(B * T * H * 4 * RK);
     }
     L.total_bwd = off;
     return L;
@@ -164,6 +166,7 @@ PrecondArgs precond_args(const osdn_params *p) {
     a.B = p->B; a.T = p->T; a.H = p->H; a.K = p->K;
     a.eta = p->eta; a.d_min = p->d_min; a.d_max = p->d_max; a.eps = p->eps;
     a.beta_aware = p->beta_aware;
+    a.ret_vec = p->retention_per_channel;
     return a;
 }
 
@@ -305,6 +308,7 @@ int osdn_step(const osdn_params *p, const void *q, const void *k, const void *v,
     a.B = p->B; a.T = p->T; a.H = p->H; a.K = p->K; a.V = p->V;
     a.scale = p->scale; a.eta = p->eta; a.d_min = p->d_min; a.d_max = p->d_max; a.eps = p->eps;
     a.beta_aware = p->beta_aware;
+    a.ret_vec = p->retention_per_channel;
     a.q = q; a.k = k; a.v = v; a.beta = beta; a.log_alpha = log_alpha; a.retention = retention;
     a.d_in = d_in; a.S_in = S_in; a.o = o; a.S_out = S_out; a.d_out = d_out;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -359,7 +363,7 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
         auto pad = [&](const void *src, size_t off, size_t row, uint32_t fill) { return move(src, ws + off, row, true, fill); };
         if (pad(q, L.p_q, rk, 0u) != 0 || pad(k, L.p_k, rk, 0u) != 0 || pad(v, L.p_v, rv, 0u) != 0 ||
             pad(beta, L.p_beta, rg, 0u) != 0 || (log_alpha && pad(log_alpha, L.p_g, rg, 0u) != 0) ||
-            (retention && pad(retention, L.p_r, rg, 0x3f800000u) != 0))
+            (retention && pad(retention, L.p_r, p->retention_per_channel ? rg * p->K : rg, 0x3f800000u) != 0))
             return OSDN_ERR_SHAPE;
         q = ws + L.p_q; k = ws + L.p_k; v = ws + L.p_v; o = ws + L.p_o;
         beta = reinterpret_cast<const float *>(ws + L.p_beta);
@@ -487,7 +491,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
             auto cut = [&](const void *src, void *dst, size_t row) { return move(src, dst, row, false); };
             if (cut(dq, dq_user, rk_) != 0 || cut(dk, dk_user, rk_) != 0 || cut(dv, dv_user, rv_) != 0 ||
                 cut(dbeta, dbeta_user, rg_) != 0 || (log_alpha && cut(dlog_alpha, dg_user, rg_) != 0) ||
-                (retention && cut(dretention, dr_user, rg_) != 0))
+                (retention && cut(dretention, dr_user, p->retention_per_channel ? rg_ * p->K : rg_) != 0))
                 return OSDN_ERR_SHAPE;
         }
         return launch_status();
@@ -506,6 +510,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     pb.B = p->B; pb.T = p->T; pb.H = p->H; pb.K = p->K;
     pb.eta = p->eta; pb.d_min = p->d_min; pb.d_max = p->d_max; pb.eps = p->eps;
     pb.beta_aware = p->beta_aware;
+    pb.ret_vec = p->retention_per_channel;
     pb.k = k; pb.beta = beta; pb.retention = retention;
     pb.d_ckpt = reinterpret_cast<const float *>(ws + L.d_ckpt);
     pb.tok_scalars = reinterpret_cast<float *>(ws + L.tok_scalars);

@@ -26,7 +26,8 @@ struct PrecondArgs {
     int beta_aware;
     const void *k;            // [B,T,H,K] io
     const float *beta;        // [B,T,H]
-    const float *retention;   // [B,T,H] or null
+    const float *retention;   // [B,T,H] ([B,T,H,K] with ret_vec) or null
+    int ret_vec;              // one retention per coordinate
     const float *d_in;        // [B,H,K] or null
     void *k_tilde;            // [B,T,H,K] io
     float *d_out;             // [B,H,K]
@@ -43,7 +44,8 @@ struct PrecondBwdArgs {
     float eta, d_min, d_max, eps;
     int beta_aware;
     const void *k;
-    const float *beta, *retention, *d_ckpt;
+    const float *beta, *retention, *d_ckpt;     // retention [B,T,H], or [B,T,H,K] with ret_vec
+    int ret_vec;
     float *tok_scalars;       // [B,T,H,4] from the forward sweep: (step, <d,k^2>, sum k^2, -); the chain
                               // kernel puts sigma_t into the fourth slot for the post kernel
     uint2 *masks;             // [B,H,T/64,K]: bit i = token i of the chunk stayed inside the box
@@ -53,7 +55,7 @@ struct PrecondBwdArgs {
     const float *dd_out;      // [B,H,K] or null
     void *dk;                 // [B,T,H,K] io
     float *dbeta;             // [B,T,H] in/out
-    float *dretention;        // [B,T,H] or null
+    float *dretention;        // [B,T,H] ([B,T,H,K] with ret_vec) or null
     float *dd_in;             // [B,H,K]
 };
 
@@ -63,7 +65,8 @@ struct StepArgs {
     float scale, eta, d_min, d_max, eps;
     int beta_aware;
     const void *q, *k, *v;            // [B,T,H,*] io
-    const float *beta, *log_alpha, *retention;   // [B,T,H]; log_alpha, retention may be null
+    const float *beta, *log_alpha, *retention;   // [B,T,H]; log_alpha, retention may be null;
+    int ret_vec;                      // retention is [B,T,H,K]: one value per coordinate
     const float *d_in, *S_in;         // [B,H,K], [B,H,V,K]; may be null (ones / zeros)
     void *o;                          // [B,T,H,V] io
     float *S_out, *d_out;             // S_out may be S_in (a workgroup reads its rows before it writes them)

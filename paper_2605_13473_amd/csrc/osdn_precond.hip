@@ -58,8 +58,11 @@ template <> struct Pack<float, 1> {
     static __device__ __forceinline__ Raw pack(const float (&v)[1]) { return v[0]; }
 };
 
-template <typename T, int K, bool HAS_RET>
+// RET: 0 = no retention, 1 = one gate per (token, head), 2 = one per coordinate (diag(r_t))
+template <typename T, int K, int RET>
 __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
+    constexpr bool HAS_RET = RET != 0, RET_VEC = RET == 2;
+    constexpr int RE = RET_VEC ? K / 64 : 1;      // retention values a thread keeps per token
     constexpr int CPT = K / 64;                   // coordinates per thread (adjacent)
     constexpr int NRUN = C / RUN;                 // = wavefronts of the workgroup
     static_assert(NRUN == P1W && RUN == 8, "one wavefront per run of 8 tokens");
@@ -88,7 +91,9 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
 
     if (tid < K) dcur[tid] = a.d_in ? a.d_in[bh * K + tid] : 1.f;
 
+    typedef Pack<float, CPT> Pr;
     typename Pk::Raw kreg[RUN];                  // this thread's k of the next chunk
+    typename Pr::Raw rreg[RET_VEC ? RUN : 1];    // ... and its per-coordinate retention
     float betreg = 0.f, retreg = 1.f;            // gates of token (run, u_own) of the next chunk
 #define OSDN_P1_LOAD(n_)                                                                         \
     {                                                                                            \
@@ -97,11 +102,14 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
         _Pragma("unroll") for (int u = 0; u < RUN; ++u) {                                        \
             const int i_ = min(run * RUN + u, a.T - 1 - t0_);    /* rows past the end: reread */ \
             kreg[u] = *reinterpret_cast<const typename Pk::Raw *>(kp_ + (uint32_t)i_ * kstride + c0); \
+            if (RET_VEC)                                                                         \
+                rreg[u] = *reinterpret_cast<const typename Pr::Raw *>(                           \
+                    a.retention + (((size_t)bt * a.T + t0_) * a.H + h) * K + (uint32_t)i_ * kstride + c0); \
         }                                                                                        \
         const int t = min(t0_ + run * RUN + u_own, a.T - 1);                                     \
         const size_t th = ((size_t)bt * a.T + t) * a.H + h;                                      \
         betreg = a.beta[th];                                                                     \
-        if (HAS_RET) retreg = a.retention[th];                                                   \
+        if (HAS_RET && !RET_VEC) retreg = a.retention[th];                                       \
     }
     OSDN_P1_LOAD(a.n0)
 
@@ -153,9 +161,18 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
             ca = cb * bp;
             c_cur = cb - ca * p_cur;
         }
-        float rv[RUN];
+        float rv[RUN][RE];                      // retention of this thread's coordinates (no-op tokens: 1)
 #pragma unroll
-        for (int u = 0; u < RUN; ++u) rv[u] = HAS_RET ? lane_bcast(run * RUN + u < nvalid ? ret : 1.f, u) : 1.f;
+        for (int u = 0; u < RUN; ++u) {
+            if (RET_VEC) {
+                float r2[CPT];
+                Pr::unpack(rreg[RET_VEC ? u : 0], r2);
+#pragma unroll
+                for (int e = 0; e < RE; ++e) rv[u][e] = run * RUN + u < nvalid ? r2[e] : 1.f;
+            } else {
+                rv[u][0] = HAS_RET ? lane_bcast(run * RUN + u < nvalid ? ret : 1.f, u) : 1.f;
+            }
+        }
         OSDN_TICK(0)
         if (n + 1 < a.n1) OSDN_P1_LOAD(n + 1)
         OSDN_TICK(1)
@@ -175,10 +192,11 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
                 for (int u = 0; u < RUN; ++u) {
                     const float bs = cv[u] * sv[u][e];
                     if (HAS_RET) {
-                        A *= rv[u];
-                        B = __builtin_fmaf(rv[u], B, bs);
-                        L = clip3(__builtin_fmaf(rv[u], L, bs), lo, hi);
-                        H = clip3(__builtin_fmaf(rv[u], H, bs), lo, hi);
+                        const float r = rv[u][RET_VEC ? e : 0];
+                        A *= r;
+                        B = __builtin_fmaf(r, B, bs);
+                        L = clip3(__builtin_fmaf(r, L, bs), lo, hi);
+                        H = clip3(__builtin_fmaf(r, H, bs), lo, hi);
                     } else {
                         B += bs;
                         L = clip3(L + bs, lo, hi);
@@ -207,7 +225,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
                 for (int u = 0; u < RUN; ++u) {
                     dtr[u][e] = d;
                     vp[u] = __builtin_fmaf(sv[u][e], d, vp[u]);
-                    d = clip3(d_bar<HAS_RET>(rv[u], d, cv[u], sv[u][e]), lo, hi);
+                    d = clip3(d_bar<HAS_RET>(rv[u][RET_VEC ? e : 0], d, cv[u], sv[u][e]), lo, hi);
                 }
                 dend[e] = d;
             }
@@ -256,18 +274,19 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     if (tid < K) a.d_out[bh * K + tid] = dcur[tid];
 }
 
-template <typename T, bool HAS_RET>
+template <typename T, int RET>
 static int launch_precond_fwd_t(const PrecondArgs &a, hipStream_t st) {
     dim3 grid((a.seq_chunks ? a.n_seqs : a.B) * a.H), block(P1T);
-    if (a.K == 64) hipLaunchKernelGGL((precond_fwd_kernel<T, 64, HAS_RET>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((precond_fwd_kernel<T, 128, HAS_RET>), grid, block, 0, st, a);
+    if (a.K == 64) hipLaunchKernelGGL((precond_fwd_kernel<T, 64, RET>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((precond_fwd_kernel<T, 128, RET>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
 int launch_precond_fwd(const PrecondArgs &a, bool bf16_io, hipStream_t st) {
-    if (a.retention)
-        return bf16_io ? launch_precond_fwd_t<bf16, true>(a, st) : launch_precond_fwd_t<float, true>(a, st);
-    return bf16_io ? launch_precond_fwd_t<bf16, false>(a, st) : launch_precond_fwd_t<float, false>(a, st);
+    const int ret = a.retention ? (a.ret_vec ? 2 : 1) : 0;
+    if (ret == 2) return bf16_io ? launch_precond_fwd_t<bf16, 2>(a, st) : launch_precond_fwd_t<float, 2>(a, st);
+    if (ret == 1) return bf16_io ? launch_precond_fwd_t<bf16, 1>(a, st) : launch_precond_fwd_t<float, 1>(a, st);
+    return bf16_io ? launch_precond_fwd_t<bf16, 0>(a, st) : launch_precond_fwd_t<float, 0>(a, st);
 }
 
 }  // namespace osdn

@@ -19,8 +19,10 @@
 namespace osdn {
 
 // ---------------------------------------------------------------- precond_mask ----
-template <typename T, int K, bool HAS_RET>
+// RET (all three kernels): 0 = no retention, 1 = one gate per (token, head), 2 = one per coordinate
+template <typename T, int K, int RET>
 __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
+    constexpr bool HAS_RET = RET != 0, RET_VEC = RET == 2;
     __shared__ __attribute__((aligned(16))) float steps[C];
     __shared__ __attribute__((aligned(16))) float rs[C];
     const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
@@ -32,21 +34,26 @@ __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
     if (tid < C) {
         const size_t th = tokc + (size_t)tid * a.H;
         steps[tid] = a.tok_scalars[th * 4];
-        rs[tid] = HAS_RET ? a.retention[th] : 1.f;
+        rs[tid] = (HAS_RET && !RET_VEC) ? a.retention[th] : 1.f;
     }
     const T *kp = static_cast<const T *>(a.k) + tokc * K;
+    const float *rp = RET_VEC ? a.retention + tokc * K : nullptr;
     const uint32_t kstride = (uint32_t)a.H * K;
-    float kv[C];
+    float kv[C], rvv[RET_VEC ? C : 1];
 #pragma unroll
-    for (int i = 0; i < C; ++i) kv[i] = to_f32(kp[(uint32_t)tid + (uint32_t)i * kstride]);
+    for (int i = 0; i < C; ++i) {
+        kv[i] = to_f32(kp[(uint32_t)tid + (uint32_t)i * kstride]);
+        if (RET_VEC) rvv[RET_VEC ? i : 0] = rp[(uint32_t)tid + (uint32_t)i * kstride];
+    }
     float d = a.d_ckpt[(bh * N + n) * K + tid];
     __syncthreads();
     uint32_t mlo = 0u, mhi = 0u;
 #pragma unroll
     for (int i = 0; i < C; ++i) {
         const float sq = kv[i] * kv[i];
-        const uint32_t in = lands_inside<HAS_RET>(rs[i], d, steps[i], sq, lo, hi) ? (1u << (i & 31)) : 0u;
-        d = clip3(d_bar<HAS_RET>(rs[i], d, steps[i], sq), lo, hi);
+        const float r = RET_VEC ? rvv[RET_VEC ? i : 0] : rs[i];
+        const uint32_t in = lands_inside<HAS_RET>(r, d, steps[i], sq, lo, hi) ? (1u << (i & 31)) : 0u;
+        d = clip3(d_bar<HAS_RET>(r, d, steps[i], sq), lo, hi);
         if (i < 32) mlo |= in; else mhi |= in;
     }
     a.masks[(bh * N + n) * K + tid] = make_uint2(mlo, mhi);
@@ -60,8 +67,9 @@ __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
 // through LDS (one fma per run); the TS products s_i abar_i of a thread are folded over the
 // lanes of the wavefront (each lane ends with the sum of one token over a group of lanes) and
 // the sigma of a token is the sum of K / TS such partials.  No tile of the chunk is ever in LDS.
-template <typename T, int K, bool HAS_RET>
+template <typename T, int K, int RET>
 __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
+    constexpr bool HAS_RET = RET != 0, RET_VEC = RET == 2;
     constexpr int NSEG = P1T / K;                 // runs per chunk
     constexpr int TS = C / NSEG;                  // tokens per run
     constexpr int WPS = K / 64;                   // wavefronts per run
@@ -93,6 +101,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
     if (tid < K) ga[tid] = a.dd_out ? a.dd_out[bh * K + tid] : 0.f;
 
     T kreg[TS], greg[TS];
+    float rreg[RET_VEC ? TS : 1];               // per-coordinate retention of the next chunk
     float nrawreg = 1.f, betreg = 0.f, retreg = 1.f;
     uint2 mreg = make_uint2(0xffffffffu, 0xffffffffu);
 #define OSDN_P1_BLOAD(n_)                                                                        \
@@ -103,12 +112,13 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         _Pragma("unroll") for (int u = 0; u < TS; ++u) {                                         \
             const uint32_t o_ = (uint32_t)(sg * TS + u) * kstride + (uint32_t)c;                 \
             kreg[u] = kp_[o_]; greg[u] = gp_[o_];                                                \
+            if (RET_VEC) rreg[RET_VEC ? u : 0] = a.retention[tokc_ * K + o_];                    \
         }                                                                                        \
         if (tid < C) {                                                                           \
             const size_t th = tokc_ + (size_t)tid * a.H;                                         \
             nrawreg = a.tok_scalars[th * 4 + 2];                                                 \
             betreg = a.beta[th];                                                                 \
-            if (HAS_RET) retreg = a.retention[th];                                               \
+            if (HAS_RET && !RET_VEC) retreg = a.retention[th];                                   \
         }                                                                                        \
         if (project) mreg = a.masks[(bth * N + (n_)) * K + c];                                   \
     }
@@ -140,15 +150,15 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         if (tid < K) a.a_ckpt[(bth * N + n) * K + tid] = ga[tid];
         __syncthreads();
         OSDN_TICK(0)
+        float rv[TS];                           // retention of this thread's coordinate, token by token
+        if (HAS_RET) {
+#pragma unroll
+            for (int u = 0; u < TS; ++u) rv[u] = RET_VEC ? rreg[RET_VEC ? u : 0] : rs[sg * TS + u];
+        }
         if (n > a.n0) OSDN_P1_BLOAD(n - 1)      // next chunk: in flight during the sweeps
         // a wavefront whose coordinates never touched the box in this run, without retention:
         // P stays 1 and L is a plain running sum
         const bool plain = !HAS_RET && __all(mbits == ((1u << TS) - 1u));
-        float rv[TS];
-        if (HAS_RET) {
-#pragma unroll
-            for (int u = 0; u < TS; ++u) rv[u] = rs[sg * TS + u];
-        }
         // ---- sweeps for sigma_i = <s_i, abar_i> ----
         float dprev = 0.f, a_left = 0.f;
         for (int sweep = 0; sweep < P1_MAX_SWEEPS; ++sweep) {
@@ -236,15 +246,16 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 //        dk_read (read-side dL/dk), dbeta (partial, from phase 2)
 //   out: dk (io type) = dk_read + d_t . dkt + 2 k_t (step_t abar_t + g_p d_t + g_nraw),
 //        dbeta += sigma_t eta (1 - 2 b' p_t)/n_t,  dretention_t = <abar_t, d_t>
-template <typename T, int K, bool HAS_RET>
+template <typename T, int K, int RET>
 __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void precond_post_kernel(PrecondBwdArgs a) {
+    constexpr bool HAS_RET = RET != 0, RET_VEC = RET == 2;
     constexpr int LD = K + 1;
     __shared__ __attribute__((aligned(16))) float st_s[C];
     __shared__ __attribute__((aligned(16))) float r_s[C];
     __shared__ __attribute__((aligned(16))) float casig_s[C];
     __shared__ __attribute__((aligned(16))) float gp_s[C];
     __shared__ __attribute__((aligned(16))) float gn_s[C];
-    __shared__ float prod[HAS_RET ? C * LD : 1];    // abar_i d_i per coordinate, for dL/dr
+    __shared__ float prod[(HAS_RET && !RET_VEC) ? C * LD : 1];    // abar_i d_i per coordinate, for the scalar gate's dL/dr
     const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int N = a.T / C;
     const size_t bh = (size_t)b * a.H + h;
@@ -260,7 +271,7 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
         const float bp = a.beta_aware ? bet : 1.f;
         const float ca = a.eta * bp / nn * bp;
         st_s[tid] = step;
-        r_s[tid] = HAS_RET ? a.retention[th] : 1.f;
+        r_s[tid] = (HAS_RET && !RET_VEC) ? a.retention[th] : 1.f;
         casig_s[tid] = ca * sg;
         gp_s[tid] = -sg * ca;
         gn_s[tid] = (n_raw >= a.eps) ? -sg * step / nn : 0.f;
@@ -270,6 +281,8 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     const T *kp = static_cast<const T *>(a.k) + tokc * K;
     const T *gp = static_cast<const T *>(a.dkt) + tokc * K, *rp = static_cast<const T *>(a.dk_read) + tokc * K;
     T *op = static_cast<T *>(a.dk) + tokc * K;
+    const float *retp = RET_VEC ? a.retention + tokc * K : nullptr;     // per-coordinate retention and its gradient
+    float *dretp = (RET_VEC && a.dretention) ? a.dretention + tokc * K : nullptr;
     const uint32_t kstride = (uint32_t)a.H * K;
     float Dv[C];
     // which steps landed inside the box: decided once, by the mask kernel
@@ -284,7 +297,8 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
 #pragma unroll
         for (int i = 0; i < C; ++i) {
             Dv[i] = d;
-            d = clip3(d_bar<HAS_RET>(r_s[i], d, st_s[i], kv[i] * kv[i]), lo, hi);
+            const float r = RET_VEC ? retp[(uint32_t)tid + (uint32_t)i * kstride] : r_s[i];
+            d = clip3(d_bar<HAS_RET>(r, d, st_s[i], kv[i] * kv[i]), lo, hi);
         }
     }
     // ---- the chunk's adjoint recurrence, right to left, and the elementwise outputs ----
@@ -293,13 +307,14 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     // the arrays, so that it does not keep the replay's 128 values in registers)
     const float *st_p = st_s, *r_p = r_s, *casig_p = casig_s, *gp_p = gp_s, *gn_p = gn_s;
     asm volatile("" : "+v"(st_p), "+v"(r_p), "+v"(casig_p), "+v"(gp_p), "+v"(gn_p));
-    float kb[2][PB], gb[2][PB], rb[2][PB];
+    float kb[2][PB], gb[2][PB], rb[2][PB], rrb[RET_VEC ? 2 : 1][RET_VEC ? PB : 1];
     uint32_t lofs = (uint32_t)tid + (uint32_t)(C - 1) * kstride;    // offset of the next row to fetch
     asm volatile("" : "+v"(lofs));
     uint32_t sofs = lofs;                                            // ... and of the next row to write
 #define OSDN_PLOAD(buf, ih_)                                                                     \
     _Pragma("unroll") for (int u = 0; u < PB; ++u) {                                             \
         kb[buf][u] = to_f32(kp[lofs]); gb[buf][u] = to_f32(gp[lofs]); rb[buf][u] = to_f32(rp[lofs]); \
+        if (RET_VEC) rrb[RET_VEC ? buf : 0][RET_VEC ? u : 0] = retp[lofs];                       \
         lofs -= kstride;                                                                         \
     }
     OSDN_PLOAD(0, C - 1)
@@ -315,13 +330,15 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
             const float kv = kb[blk & 1][u], g = gb[blk & 1][u], Di = Dv[i];
             const float gsum = st_p[i] * ab + gp_p[i] * Di + gn_p[i];
             op[sofs] = from_f32<T>(rb[blk & 1][u] + Di * g + 2.f * kv * gsum);
+            if (RET_VEC) { if (dretp) dretp[sofs] = ab * Di; }
+            else if (HAS_RET) prod[i * LD + tid] = ab * Di;
             sofs -= kstride;
-            if (HAS_RET) prod[i * LD + tid] = ab * Di;
             const float src = __builtin_fmaf(-casig_p[i], kv * kv, kv * g);
-            av = HAS_RET ? __builtin_fmaf(r_p[i], ab, src) : ab + src;
+            const float r = RET_VEC ? rrb[RET_VEC ? blk & 1 : 0][RET_VEC ? u : 0] : r_p[i];
+            av = HAS_RET ? __builtin_fmaf(r, ab, src) : ab + src;
         }
     }
-    if (HAS_RET) {
+    if (HAS_RET && !RET_VEC) {
         __syncthreads();
         if (tid < C && a.dretention) {
             float s = 0.f;
@@ -333,27 +350,30 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
 }
 
 // -------------------------------------------------------------------- launchers ----
-template <typename T, bool HAS_RET>
+template <typename T, int RET>
 static int launch_precond_bwd_t(const PrecondBwdArgs &a, int which, hipStream_t st) {
     const dim3 per_chunk(a.n1 - a.n0, a.H, a.B);
     const int nchains = (a.seq_chunks ? a.n_seqs : a.B) * a.H;
     if (a.K == 64) {
-        if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 64, HAS_RET>), per_chunk, dim3(64), 0, st, a);
-        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 64, HAS_RET>), dim3(nchains), dim3(P1T), 0, st, a);
-        else hipLaunchKernelGGL((precond_post_kernel<T, 64, HAS_RET>), per_chunk, dim3(64), 0, st, a);
+        if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 64, RET>), per_chunk, dim3(64), 0, st, a);
+        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 64, RET>), dim3(nchains), dim3(P1T), 0, st, a);
+        else hipLaunchKernelGGL((precond_post_kernel<T, 64, RET>), per_chunk, dim3(64), 0, st, a);
     } else if (a.K == 128) {
-        if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 128, HAS_RET>), per_chunk, dim3(128), 0, st, a);
-        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 128, HAS_RET>), dim3(nchains), dim3(P1T), 0, st, a);
-        else hipLaunchKernelGGL((precond_post_kernel<T, 128, HAS_RET>), per_chunk, dim3(128), 0, st, a);
+        if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 128, RET>), per_chunk, dim3(128), 0, st, a);
+        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 128, RET>), dim3(nchains), dim3(P1T), 0, st, a);
+        else hipLaunchKernelGGL((precond_post_kernel<T, 128, RET>), per_chunk, dim3(128), 0, st, a);
     } else {
         return -1;
     }
     return 0;
 }
 static int launch_precond_bwd_any(const PrecondBwdArgs &a, bool bf16_io, int which, hipStream_t st) {
-    if (a.retention)
-        return bf16_io ? launch_precond_bwd_t<bf16, true>(a, which, st) : launch_precond_bwd_t<float, true>(a, which, st);
-    return bf16_io ? launch_precond_bwd_t<bf16, false>(a, which, st) : launch_precond_bwd_t<float, false>(a, which, st);
+    const int ret = a.retention ? (a.ret_vec ? 2 : 1) : 0;
+    if (ret == 2)
+        return bf16_io ? launch_precond_bwd_t<bf16, 2>(a, which, st) : launch_precond_bwd_t<float, 2>(a, which, st);
+    if (ret == 1)
+        return bf16_io ? launch_precond_bwd_t<bf16, 1>(a, which, st) : launch_precond_bwd_t<float, 1>(a, which, st);
+    return bf16_io ? launch_precond_bwd_t<bf16, 0>(a, which, st) : launch_precond_bwd_t<float, 0>(a, which, st);
 }
 int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) { return launch_precond_bwd_any(a, bf16_io, 0, st); }
 int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) { return launch_precond_bwd_any(a, bf16_io, 1, st); }

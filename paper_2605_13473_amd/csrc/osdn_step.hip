@@ -49,7 +49,10 @@ __global__ __launch_bounds__(STEP_T) void step_kernel(StepArgs a) {
         }
         const float bet = a.beta[th];
         const float alpha = a.log_alpha ? __expf(a.log_alpha[th]) : 1.f;
-        const float ret = HAS_RET ? a.retention[th] : 1.f;
+        float ret[CPT];                             // one gate per (token, head), or one per coordinate
+#pragma unroll
+        for (int e = 0; e < CPT; ++e)
+            ret[e] = HAS_RET ? (a.ret_vec ? a.retention[th * K + c0 + e] : a.retention[th]) : 1.f;
         float orow = 0.f;                           // lane r < 4 ends with the output of row v0 + r
 #pragma unroll
         for (int r = 0; r < STEP_RPW; ++r) {
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(STEP_T) void step_kernel(StepArgs a) {
         const float cb = a.eta * bp / nn;
         const float step = cb - cb * bp * sp;
 #pragma unroll
-        for (int e = 0; e < CPT; ++e) d[e] = clip3(d_bar<HAS_RET>(ret, d[e], step, sv[e]), lo, hi);
+        for (int e = 0; e < CPT; ++e) d[e] = clip3(d_bar<HAS_RET>(ret[e], d[e], step, sv[e]), lo, hi);
     }
 #pragma unroll
     for (int r = 0; r < STEP_RPW; ++r)

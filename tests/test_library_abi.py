@@ -33,6 +33,8 @@ def test_workspace_size_and_shape_validation():
     assert 0 < fwd < bwd
     # at least k~ plus W, U, E^T and the per-chunk state
     assert fwd >= 4 * 4096 * 16 * 128 * 2 * 4
+    # per-coordinate retention only matters for the padded copies of a ragged length
+    assert ob.osdn_workspace_bytes(ob.make_params(4, 4096, 16, 128, 128, True, retention_per_channel=True), True) == bwd
     # a ragged length costs the padded copies of the caller's tensors on top
     q = ob.make_params(4, 4096 - 7, 16, 128, 128, True)
     assert ob.osdn_workspace_bytes(q, False) > fwd and ob.osdn_workspace_bytes(q, True) > bwd
@@ -55,6 +57,9 @@ def test_argument_errors_before_any_pointer_is_used():
     assert L.osdn_fwd(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
                       fake, ctypes.c_size_t(1 << 30), None) == -3
     p = ob.make_params(1, 128, 1, 64, 64, False, ob.Hyper(eta=-1.0))
+    assert L.osdn_precond_update(ctypes.byref(p), fake, fake, None, None, fake, fake, None, None) == -5
+    p = ob.make_params(1, 128, 1, 64, 64, False)
+    p.retention_per_channel = 3                            # a flag: 0 or 1
     assert L.osdn_precond_update(ctypes.byref(p), fake, fake, None, None, fake, fake, None, None) == -5
     p = ob.make_params(1, 128, 1, 64, 64, False)
     assert L.osdn_fwd(ctypes.byref(p), None, fake, fake, fake, None, None, None, None, fake, fake, fake,
