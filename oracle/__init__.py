@@ -7,7 +7,8 @@ imports nothing from it.
 
 All arrays are numpy float64, C-contiguous, in the paper's layouts
 (Appendix C, Listing 1): q,k ``[B,T,H,K]``; v,o ``[B,T,H,V]``; beta, log_alpha,
-retention ``[B,T,H]`` (or ``[B,T,H,K]``: one retention per coordinate); d ``[B,H,K]``; S ``[B,H,V,K]``.
+retention ``[B,T,H]`` (or ``[B,T,H,K]``: one retention per coordinate; log_alpha ``[B,T,H,K]``: one state gate
+per key channel, the online-scaled KDA recurrence); d ``[B,H,K]``; S ``[B,H,V,K]``.
 """
 from __future__ import annotations
 
@@ -39,7 +40,8 @@ class _Params(ctypes.Structure):
         ("K", ctypes.c_int), ("V", ctypes.c_int),
         ("scale", ctypes.c_double), ("eta", ctypes.c_double),
         ("d_min", ctypes.c_double), ("d_max", ctypes.c_double),
-        ("eps", ctypes.c_double), ("beta_aware", ctypes.c_int), ("ret_vec", ctypes.c_int),
+        ("eps", ctypes.c_double), ("beta_aware", ctypes.c_int), ("gate_vec", ctypes.c_int),
+        ("ret_vec", ctypes.c_int),
     ]
 
 
@@ -78,13 +80,17 @@ def _f64(a):
     return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
 
 
-def _params(hp: Hyper, B, T, H, K, V, retention=None) -> _Params:
+def _params(hp: Hyper, B, T, H, K, V, retention=None, log_alpha=None) -> _Params:
     scale = float(K) ** -0.5 if hp.scale is None else float(hp.scale)
-    ret_vec = 0
+    ret_vec = gate_vec = 0
     if retention is not None:
         assert retention.shape in ((B, T, H), (B, T, H, K)), retention.shape
         ret_vec = int(retention.ndim == 4)       # one retention per coordinate: diag(r_t)
-    return _Params(B, T, H, K, V, scale, hp.eta, hp.d_min, hp.d_max, hp.eps, int(hp.beta_aware), ret_vec)
+    if log_alpha is not None:
+        assert log_alpha.shape in ((B, T, H), (B, T, H, K)), log_alpha.shape
+        gate_vec = int(log_alpha.ndim == 4)      # one state gate per key channel: Diag(alpha_t)
+    return _Params(B, T, H, K, V, scale, hp.eta, hp.d_min, hp.d_max, hp.eps, int(hp.beta_aware), gate_vec,
+                   ret_vec)
 
 
 def precond(k, beta, retention=None, d_in=None, hp: Hyper = Hyper(), want_traj: bool = False):
@@ -109,7 +115,7 @@ def fwd(q, k, v, beta, log_alpha=None, retention=None, d_in=None, S_in=None, hp:
         _f64, (q, k, v, beta, log_alpha, retention, d_in, S_in))
     B, T, H, K = k.shape
     V = v.shape[-1]
-    P = _params(hp, B, T, H, K, V, retention)
+    P = _params(hp, B, T, H, K, V, retention, log_alpha)
     o = np.empty((B, T, H, V))
     S_out = np.empty((B, H, V, K))
     d_out = np.empty((B, H, K))
@@ -128,11 +134,11 @@ def bwd(q, k, v, beta, dO, log_alpha=None, retention=None, d_in=None, S_in=None,
         _f64, (q, k, v, beta, dO, log_alpha, retention, d_in, S_in, dS_out, dd_out))
     B, T, H, K = k.shape
     V = v.shape[-1]
-    P = _params(hp, B, T, H, K, V, retention)
+    P = _params(hp, B, T, H, K, V, retention, log_alpha)
     g = {
         "dq": np.empty_like(q), "dk": np.empty_like(k), "dv": np.empty_like(v),
         "dbeta": np.empty_like(beta),
-        "dlog_alpha": np.empty_like(beta) if log_alpha is not None else None,
+        "dlog_alpha": np.empty_like(log_alpha) if log_alpha is not None else None,
         "dretention": np.empty_like(retention) if retention is not None else None,
         "dd_in": np.empty((B, H, K)), "dS_in": np.empty((B, H, V, K)),
     }

@@ -20,6 +20,11 @@
  *     of Appendix B.1 ("post-gate" form: decay S first, read with the unscaled
  *     key k, write with k~ = d (.) k), read-out o_t = S_t q_t from Table
  *     "Recurrence and read-out" (post-write state), query scale as Listing 1;
+ *     with gate_vec the gate is one value per key channel, S <- S Diag(alpha_t)
+ *     before the read: the online-scaled KDA recurrence (appendix section
+ *     "Kimi Delta Attention with Online Scaling"; its K x V state is the
+ *     transpose of the S kept here, so its left write key k~ is this file's
+ *     right factor and its read-out S^T q is S q);
  *   - backward: Section 4.5 chain rule (dL/dd_t = k_t (.) dL/dk~_t,
  *     dL/dk_t += d_t (.) dL/dk~_t) and a reverse sweep through the projected
  *     affine recurrence; everything else is ordinary reverse-mode
@@ -27,7 +32,8 @@
  *
  * Layouts (all row-major, fp64): q,k [B,T,H,K]; v,o [B,T,H,V]; beta,
  * log_alpha, retention [B,T,H] (retention and its gradient [B,T,H,K] with
- * ret_vec); d [B,H,K]; S [B,H,V,K].
+ * ret_vec, log_alpha and its gradient [B,T,H,K] with gate_vec); d [B,H,K];
+ * S [B,H,V,K].
  * NULL log_alpha => alpha = 1 (ungated OSDN); NULL retention => r = 1;
  * NULL d_in => ones; NULL S_in => zeros.  d_min > d_max => no projection.
  *
@@ -47,6 +53,11 @@ typedef struct {
     double d_min, d_max;
     double eps;        /* floor of the squared key norm (1e-6) */
     int beta_aware;    /* 1: beta enters the d update; 0: beta replaced by 1 there */
+    int gate_vec;      /* 1: the state gate is one value per key channel, log_alpha [B,T,H,K]:
+                          Diag(alpha_t) in place of alpha_t (the online-scaled KDA recurrence,
+                          appendix on Kimi Delta Attention with online scaling, written here in
+                          this file's S in R^{V x K} convention: a column of S per channel);
+                          0: scalar gate, [B,T,H] */
     int ret_vec;       /* 1: retention is a vector per token and head, [B,T,H,K]: the
                           diag(r_t) extension of the APF step (proposition on APF being a
                           piecewise-affine recurrence, appendix); 0: scalar, [B,T,H] */
@@ -104,15 +115,23 @@ static void phase1_step(const osdn_oracle_params *P, const double *k, double bet
     if (out) { out->n_raw = n_raw; out->n = n; out->p = p; out->bp = bp; out->c = c; }
 }
 
+/* gate of channel j of token-head th (NULL => 1) */
+static double gate_at(const osdn_oracle_params *P, const double *log_alpha, size_t th, int j)
+{
+    if (!log_alpha) return 1.0;
+    return exp(P->gate_vec ? log_alpha[th * (size_t)P->K + j] : log_alpha[th]);
+}
+
 /* ---- one token of phase 2 on S (V x K): decay, read with k, write with k~ ----
- * u (V) receives the residual v - (alpha S) k ; S is updated in place. */
-static void phase2_step(int K, int V, double alpha, double beta, const double *k,
+ * alpha (K): the gate of every key channel (all equal for the scalar gate).
+ * u (V) receives the residual v - (S Diag(alpha)) k ; S is updated in place. */
+static void phase2_step(int K, int V, const double *alpha, double beta, const double *k,
                         const double *k_tilde, const double *v, double *S, double *u)
 {
     for (int a = 0; a < V; ++a) {
         double *row = S + (size_t)a * K;
         double acc = 0.0;
-        for (int j = 0; j < K; ++j) { row[j] *= alpha; acc += row[j] * k[j]; }
+        for (int j = 0; j < K; ++j) { row[j] *= alpha[j]; acc += row[j] * k[j]; }
         u[a] = v[a] - acc;
         double e = beta * u[a];
         for (int j = 0; j < K; ++j) row[j] += e * k_tilde[j];
@@ -156,13 +175,14 @@ int osdn_oracle_fwd(const osdn_oracle_params *P, const double *q, const double *
             double *d = d_out + bh * K;
             double *kt = (double *)malloc(sizeof(double) * K);
             double *u = (double *)malloc(sizeof(double) * V);
-            if (!kt || !u) { fail = 1; free(kt); free(u); continue; }
+            double *alpha = (double *)malloc(sizeof(double) * K);
+            if (!kt || !u || !alpha) { fail = 1; free(kt); free(u); free(alpha); continue; }
             for (int j = 0; j < K; ++j) d[j] = d_in ? d_in[bh * K + j] : 1.0;
             for (size_t i = 0; i < (size_t)V * K; ++i) S[i] = S_in ? S_in[bh * V * K + i] : 0.0;
             for (int t = 0; t < T; ++t) {
                 size_t th = ((size_t)b * T + t) * H + h;
                 const double *kk = k + th * K, *qq = q + th * K, *vv = v + th * V;
-                double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
+                for (int j = 0; j < K; ++j) alpha[j] = gate_at(P, log_alpha, th, j);
                 /* phase 1 for this token: emits k~_t from d_t, then advances d */
                 phase1_step(P, kk, beta[th], retention, th, d, kt, NULL, NULL);
                 /* phase 2 for this token */
@@ -174,7 +194,7 @@ int osdn_oracle_fwd(const osdn_oracle_params *P, const double *q, const double *
                     o[th * V + a] = P->scale * acc;
                 }
             }
-            free(kt); free(u);
+            free(kt); free(u); free(alpha);
         }
     return fail ? -1 : 0;
 }
@@ -222,7 +242,9 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
             double *gkt = (double *)malloc(sizeof(double) * K);
             double *u = (double *)malloc(sizeof(double) * V);
             double *ge = (double *)malloc(sizeof(double) * V);
-            if (!ckS || !ckd || !Sprev || !dtr || !S || !Sbar || !gS || !d || !gd || !gdn ||
+            double *alpha = (double *)malloc(sizeof(double) * K);
+            if (!alpha ||
+                !ckS || !ckd || !Sprev || !dtr || !S || !Sbar || !gS || !d || !gd || !gdn ||
                 !kt || !dbar || !gkt || !u || !ge) {
                 fail = 1;
                 goto done;
@@ -236,7 +258,7 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                     memcpy(ckS + (size_t)(t / SEG) * VK, S, sizeof(double) * VK);
                     memcpy(ckd + (size_t)(t / SEG) * K, d, sizeof(double) * K);
                 }
-                double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
+                for (int j = 0; j < K; ++j) alpha[j] = gate_at(P, log_alpha, th, j);
                 phase1_step(P, k + th * K, beta[th], retention, th, d, kt, NULL, NULL);
                 phase2_step(K, V, alpha, beta[th], k + th * K, kt, v + th * V, S, u);
             }
@@ -253,7 +275,7 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                     size_t th = ((size_t)b * T + t) * H + h;
                     memcpy(Sprev + (size_t)(t - t0) * VK, S, sizeof(double) * VK);
                     memcpy(dtr + (size_t)(t - t0) * K, d, sizeof(double) * K);
-                    double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
+                    for (int j = 0; j < K; ++j) alpha[j] = gate_at(P, log_alpha, th, j);
                     phase1_step(P, k + th * K, beta[th], retention, th, d, kt, NULL, NULL);
                     phase2_step(K, V, alpha, beta[th], k + th * K, kt, v + th * V, S, u);
                 }
@@ -262,7 +284,7 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                     const double *kk = k + th * K, *qq = q + th * K, *vv = v + th * V;
                     const double *go = dO + th * V;
                     const double bt = beta[th];
-                    const double alpha = log_alpha ? exp(log_alpha[th]) : 1.0;
+                    for (int j = 0; j < K; ++j) alpha[j] = gate_at(P, log_alpha, th, j);
                     const double *Sm1 = Sprev + (size_t)(t - t0) * VK;
                     double *gk = dk + th * K;
                     /* recompute this token's forward values from d_t and S_{t-1} */
@@ -274,7 +296,8 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                     /* S_t = phase2(S_{t-1}); keep Sbar = alpha S_{t-1} separately */
                     memcpy(S, Sm1, sizeof(double) * VK);
                     phase2_step(K, V, alpha, bt, kk, kt, vv, S, u);     /* S = S_t, u = residual */
-                    for (size_t i = 0; i < VK; ++i) Sbar[i] *= alpha;
+                    for (int a = 0; a < V; ++a)
+                        for (int j = 0; j < K; ++j) Sbar[(size_t)a * K + j] *= alpha[j];
 
                     for (int j = 0; j < K; ++j) gk[j] = 0.0;
 
@@ -332,9 +355,17 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                             gk[j] -= Sbar[(size_t)a * K + j] * gu;
                         }
                     }
-                    /* Sbar = alpha S_{t-1} */
-                    for (size_t i = 0; i < VK; ++i) { g_alpha += gS[i] * Sm1[i]; gS[i] *= alpha; }
-                    if (dlog_alpha) dlog_alpha[th] = log_alpha ? alpha * g_alpha : 0.0;
+                    /* Sbar = S_{t-1} Diag(alpha): a gate per channel (column), all equal for the scalar gate */
+                    for (int j = 0; j < K; ++j) {
+                        double g_aj = 0.0;
+                        for (int a = 0; a < V; ++a) {
+                            g_aj += gS[(size_t)a * K + j] * Sm1[(size_t)a * K + j];
+                            gS[(size_t)a * K + j] *= alpha[j];
+                        }
+                        if (dlog_alpha && P->gate_vec) dlog_alpha[th * K + j] = log_alpha ? alpha[j] * g_aj : 0.0;
+                        g_alpha += alpha[j] * g_aj;
+                    }
+                    if (dlog_alpha && !P->gate_vec) dlog_alpha[th] = log_alpha ? g_alpha : 0.0;
                     dbeta[th] = gbeta;
                     /* k~ = d_t (.) k */
                     for (int j = 0; j < K; ++j) {
@@ -348,7 +379,7 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
             memcpy(dd_in + bh * K, gd, sizeof(double) * K);
         done:
             free(ckS); free(ckd); free(Sprev); free(dtr); free(S); free(Sbar); free(gS);
-            free(d); free(gd); free(gdn); free(kt); free(dbar); free(gkt); free(u); free(ge);
+            free(d); free(gd); free(gdn); free(kt); free(dbar); free(gkt); free(u); free(ge); free(alpha);
         }
     return fail ? -1 : 0;
 }

@@ -383,6 +383,64 @@ def test_resume_from_carried_state():
     np.testing.assert_allclose(b[2], full[2], atol=1e-14)
 
 
+def test_channel_gate_is_online_scaled_kda():
+    """One state gate per key channel.  (a) The recurrence exactly as the paper writes it for
+    online-scaled KDA, in KDA's own K x V convention with explicit matrices:
+    S_t = (I - beta k~ k^T) Diag(alpha_t) S_{t-1} + beta k~ v^T, o_t = S_t^T q_t.
+    (b) The paper's chunkwise UT form of the same recurrence (M, W, U, state propagation and
+    intra-chunk output with the cumulative channel decays Gamma).  (c) Equal entries reproduce
+    the scalar gate."""
+    rng = np.random.default_rng(19)
+    B, T, H, K, V, C = 1, 48, 2, 6, 5, 16
+    q = rng.standard_normal((B, T, H, K)); k = rng.standard_normal((B, T, H, K))
+    k /= np.linalg.norm(k, axis=-1, keepdims=True)
+    v = rng.standard_normal((B, T, H, V)); beta = rng.uniform(0.1, 0.95, (B, T, H))
+    g = -np.logaddexp(0.0, rng.standard_normal((B, T, H, K)) - 1.0)        # log alpha per channel
+    d0 = rng.uniform(0.6, 1.8, (B, H, K))
+    hp = Hyper(eta=0.4, scale=0.7)
+    o, S_T, d_T = oracle.fwd(q, k, v, beta, g, None, d0, None, hp)
+    kt, _ = oracle.precond(k, beta, None, d0, hp)
+    for h in range(H):
+        # (a) explicit matrices, K x V state
+        S = np.zeros((K, V))
+        for t in range(T):
+            kk, ktl, al = k[0, t, h], kt[0, t, h], np.exp(g[0, t, h])
+            S = (np.eye(K) - beta[0, t, h] * np.outer(ktl, kk)) @ (np.diag(al) @ S) \
+                + beta[0, t, h] * np.outer(ktl, v[0, t, h])
+            np.testing.assert_allclose(o[0, t, h], 0.7 * (S.T @ q[0, t, h]), rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(S_T[0, h], S.T, rtol=1e-11, atol=1e-13)
+        # (b) chunkwise form
+        S = np.zeros((K, V))
+        for n in range(T // C):
+            sl = slice(n * C, (n + 1) * C)
+            Kc, Ktc, Qc, Vc, bc = k[0, sl, h], kt[0, sl, h], q[0, sl, h], v[0, sl, h], beta[0, sl, h]
+            Gam = np.exp(np.cumsum(g[0, sl, h], axis=0))                  # [C,K] cumulative channel decays
+            gamC = Gam[-1]
+            A = np.tril(bc[:, None] * ((Gam * Kc) @ (Ktc / Gam).T), -1)
+            M = np.linalg.inv(np.eye(C) + A) @ np.diag(bc)
+            W, U = M @ (Gam * Kc), M @ Vc
+            E = U - W @ S
+            O = (Gam * Qc) @ S + np.tril((Gam * Qc) @ (Ktc / Gam).T) @ E
+            np.testing.assert_allclose(o[0, sl, h], 0.7 * O, rtol=1e-9, atol=1e-11)
+            S = gamC[:, None] * S + ((gamC / Gam) * Ktc).T @ E
+        np.testing.assert_allclose(S_T[0, h], S.T, rtol=1e-9, atol=1e-11)
+    # (c) equal entries == the scalar gate
+    gs = -np.logaddexp(0.0, rng.standard_normal((B, T, H)))
+    gb = np.ascontiguousarray(np.broadcast_to(gs[..., None], (B, T, H, K)))
+    a = oracle.fwd(q, k, v, beta, gs, None, d0, None, hp)
+    b = oracle.fwd(q, k, v, beta, gb, None, d0, None, hp)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    dO = rng.standard_normal((B, T, H, V))
+    ga = oracle.bwd(q, k, v, beta, dO, gs, None, d0, None, hp=hp)
+    gv = oracle.bwd(q, k, v, beta, dO, gb, None, d0, None, hp=hp)
+    for name in ga:
+        if ga[name] is None:
+            continue
+        ref = gv[name].sum(-1) if name == "dlog_alpha" else gv[name]
+        np.testing.assert_allclose(ref, ga[name], rtol=1e-11, atol=1e-13, err_msg=name)
+
+
 # ---------------------------------------------------------------- backward ----
 def _loss(x, hp, wO, wS, wd):
     o, S, d = oracle.fwd(x["q"], x["k"], x["v"], x["beta"], x["log_alpha"], x["retention"],
@@ -391,7 +449,7 @@ def _loss(x, hp, wO, wS, wd):
 
 
 @pytest.mark.parametrize("case", ["plain", "clamp_active", "non_beta_aware", "ungated_noapf",
-                                  "vector_retention", "vector_retention_clamp_active"])
+                                  "vector_retention", "vector_retention_clamp_active", "channel_gate"])
 def test_backward_against_central_differences(case):
     """Every gradient the oracle returns, against central finite differences of its forward
     (fp64, h = 1e-6), including through the box projection (clamp-active case: coordinates
@@ -405,8 +463,10 @@ def test_backward_against_central_differences(case):
     if case.startswith("vector_retention"):     # one retention per coordinate: diag(r_t)
         x["retention"] = np.clip(x["retention"][..., None]
                                  + 0.04 * np.random.default_rng(17).standard_normal((B, T, H, K)), 0.0, 1.0)
+    if case == "channel_gate":                  # one state gate per key channel: Diag(alpha_t)
+        x["log_alpha"] = -np.logaddexp(0.0, np.random.default_rng(18).standard_normal((B, T, H, K)))
     eta = {"plain": 0.05, "clamp_active": 2.5, "non_beta_aware": 0.05, "ungated_noapf": 0.05,
-           "vector_retention": 0.05, "vector_retention_clamp_active": 2.5}[case]
+           "vector_retention": 0.05, "vector_retention_clamp_active": 2.5, "channel_gate": 0.05}[case]
     if case == "plain":
         x["d_in"] = 1.0 + 0.2 * (x["d_in"] - 1.25)       # stay inside the box
     hp = Hyper(eta=eta, beta_aware=(case != "non_beta_aware"))
