@@ -78,6 +78,12 @@ typedef struct {
                                        1: one per coordinate, [B,T,H,K], diag(r_t) in place of r_t I (the
                                        vector-retention extension stated with the proposition that APF is a
                                        piecewise-affine recurrence); dretention then has that shape too */
+    int32_t gate_per_channel;       /* 0: log_alpha is one state gate per (token, head), [B,T,H];
+                                       1: one per key channel, [B,T,H,K]: S <- S Diag(alpha_t), the
+                                       online-scaled KDA recurrence (appendix section on Kimi Delta
+                                       Attention with online scaling; its K x V state is the transpose
+                                       of the [V,K] state kept here).  osdn_step only: the chunkwise
+                                       entry points return OSDN_ERR_SHAPE when it is set */
 } osdn_params;
 
 /* Bytes of scratch osdn_fwd needs (for_backward == 0) or osdn_fwd followed by osdn_bwd

@@ -32,6 +32,7 @@ class OsdnParams(ctypes.Structure):
         ("scale", ctypes.c_float), ("eta", ctypes.c_float),
         ("d_min", ctypes.c_float), ("d_max", ctypes.c_float), ("eps", ctypes.c_float),
         ("beta_aware", ctypes.c_int32), ("retention_per_channel", ctypes.c_int32),
+        ("gate_per_channel", ctypes.c_int32),
     ]
 
 
@@ -151,7 +152,7 @@ def osdn_step(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out,
     bth, bthk, bthv = (p.B, p.T, p.H), (p.B, p.T, p.H, p.K), (p.B, p.T, p.H, p.V)
     _check(lib().osdn_step(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
-        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
+        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, _gate_shape(p), "log_alpha"),
         _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
         _ptr(S_in, f32, (p.B, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
         _ptr(S_out, f32, (p.B, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (p.B, p.H, p.K), "d_out"),
@@ -165,7 +166,7 @@ def osdn_fwd(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, 
     bth, bthk, bthv = (p.B, p.T, p.H), (p.B, p.T, p.H, p.K), (p.B, p.T, p.H, p.V)
     _check(lib().osdn_fwd(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
-        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
+        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, _gate_shape(p), "log_alpha"),
         _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
         _ptr(S_in, f32, (p.B, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
         _ptr(S_out, f32, (p.B, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (p.B, p.H, p.K), "d_out"),
@@ -181,7 +182,7 @@ def osdn_bwd(params, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out
     bhk, bhvk = (p.B, p.H, p.K), (p.B, p.H, p.V, p.K)
     _check(lib().osdn_bwd(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
-        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
+        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, _gate_shape(p), "log_alpha"),
         _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, bhk, "d_in"),
         _ptr(S_in, f32, bhvk, "S_in"), _ptr(dO, io, bthv, "dO"), _ptr(dS_out, f32, bhvk, "dS_out"),
         _ptr(dd_out, f32, bhk, "dd_out"), _ptr(dq, io, bthk, "dq"), _ptr(dk, io, bthk, "dk"),
@@ -211,7 +212,7 @@ def osdn_fwd_packed(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, 
     bth, bthk, bthv = (p.B, p.T, p.H), (p.B, p.T, p.H, p.K), (p.B, p.T, p.H, p.V)
     _check(lib().osdn_fwd_packed(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
-        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
+        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, _gate_shape(p), "log_alpha"),
         _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, (n, p.H, p.K), "d_in"),
         _ptr(S_in, f32, (n, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
         _ptr(S_out, f32, (n, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (n, p.H, p.K), "d_out"),
@@ -228,7 +229,7 @@ def osdn_bwd_packed(params, q, k, v, beta, log_alpha, retention, d_in, S_in, dO,
     bhk, bhvk = (n, p.H, p.K), (n, p.H, p.V, p.K)
     _check(lib().osdn_bwd_packed(
         ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
-        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, bth, "log_alpha"),
+        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, _gate_shape(p), "log_alpha"),
         _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, bhk, "d_in"),
         _ptr(S_in, f32, bhvk, "S_in"), _ptr(dO, io, bthv, "dO"), _ptr(dS_out, f32, bhvk, "dS_out"),
         _ptr(dd_out, f32, bhk, "dd_out"), _ptr(dq, io, bthk, "dq"), _ptr(dk, io, bthk, "dk"),
@@ -250,14 +251,20 @@ class Hyper:
     beta_aware: bool = True
 
 
-def make_params(B, T, H, K, V, bf16: bool, hp: Hyper = Hyper(), retention_per_channel: bool = False) -> OsdnParams:
+def make_params(B, T, H, K, V, bf16: bool, hp: Hyper = Hyper(), retention_per_channel: bool = False,
+                gate_per_channel: bool = False) -> OsdnParams:
     scale = float(K) ** -0.5 if hp.scale is None else float(hp.scale)
     return OsdnParams(B, T, H, K, V, 64, OSDN_BF16 if bf16 else OSDN_F32, scale, hp.eta, hp.d_min,
-                      hp.d_max, hp.eps, int(hp.beta_aware), int(bool(retention_per_channel)))
+                      hp.d_max, hp.eps, int(hp.beta_aware), int(bool(retention_per_channel)),
+                      int(bool(gate_per_channel)))
 
 
 def _ret_shape(p: OsdnParams):
     return (p.B, p.T, p.H, p.K) if p.retention_per_channel else (p.B, p.T, p.H)
+
+
+def _gate_shape(p: OsdnParams):
+    return (p.B, p.T, p.H, p.K) if p.gate_per_channel else (p.B, p.T, p.H)
 
 
 def _per_channel(retention) -> bool:
@@ -332,7 +339,7 @@ def step(q, k, v, beta, log_alpha=None, retention=None, d_in=None, S_in=None, hp
     is updated where it is (and returned)."""
     B, T, H, K = k.shape
     V = v.shape[-1]
-    p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp, _per_channel(retention))
+    p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp, _per_channel(retention), _per_channel(log_alpha))
     f32 = dict(dtype=torch.float32, device=k.device)
     o = torch.empty_like(v)
     S_out = S_in if (in_place and S_in is not None) else torch.empty(B, H, V, K, **f32)

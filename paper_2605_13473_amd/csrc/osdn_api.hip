@@ -61,6 +61,8 @@ int check_params(const osdn_params *p, bool need_chunks) {
         !std::isfinite(p->scale) || std::isnan(p->d_min) || std::isnan(p->d_max))
         return OSDN_ERR_PARAM;
     if (p->retention_per_channel != 0 && p->retention_per_channel != 1) return OSDN_ERR_PARAM;
+    if (p->gate_per_channel != 0 && p->gate_per_channel != 1) return OSDN_ERR_PARAM;
+    if (need_chunks && p->gate_per_channel) return OSDN_ERR_SHAPE;      // the chunkwise kernels take the scalar gate
     return OSDN_OK;
 }
 
@@ -309,6 +311,7 @@ int osdn_step(const osdn_params *p, const void *q, const void *k, const void *v,
     a.scale = p->scale; a.eta = p->eta; a.d_min = p->d_min; a.d_max = p->d_max; a.eps = p->eps;
     a.beta_aware = p->beta_aware;
     a.ret_vec = p->retention_per_channel;
+    a.gate_vec = p->gate_per_channel;
     a.q = q; a.k = k; a.v = v; a.beta = beta; a.log_alpha = log_alpha; a.retention = retention;
     a.d_in = d_in; a.S_in = S_in; a.o = o; a.S_out = S_out; a.d_out = d_out;
     hipStream_t st = static_cast<hipStream_t>(stream);

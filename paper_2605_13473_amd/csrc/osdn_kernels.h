@@ -67,6 +67,7 @@ struct StepArgs {
     const void *q, *k, *v;            // [B,T,H,*] io
     const float *beta, *log_alpha, *retention;   // [B,T,H]; log_alpha, retention may be null;
     int ret_vec;                      // retention is [B,T,H,K]: one value per coordinate
+    int gate_vec;                     // log_alpha is [B,T,H,K]: one state gate per key channel
     const float *d_in, *S_in;         // [B,H,K], [B,H,V,K]; may be null (ones / zeros)
     void *o;                          // [B,T,H,V] io
     float *S_out, *d_out;             // S_out may be S_in (a workgroup reads its rows before it writes them)

@@ -4,6 +4,8 @@
 //
 //   k~_t = d_t (.) k_t
 //   S   <- alpha_t S ;  e = beta_t (v_t - S k_t) ;  S <- S + e k~_t^T ;  o_t = scale S q_t
+//   (alpha_t a scalar, or one gate per key channel: S <- S Diag(alpha_t), the online-scaled
+//   KDA recurrence in this library's V x K orientation of the state)
 //   d_{t+1} = clip(r_t d_t + eta b'(1 - b' p)/n s),  s = k_t^2, n = max(sum s, eps), p = <d_t, s>
 //
 // A workgroup of four wavefronts owns 16 rows of S of one (batch, head); a wavefront owns 4 of
@@ -48,7 +50,10 @@ __global__ __launch_bounds__(STEP_T) void step_kernel(StepArgs a) {
             kt[e] = d[e] * kf[e];
         }
         const float bet = a.beta[th];
-        const float alpha = a.log_alpha ? __expf(a.log_alpha[th]) : 1.f;
+        float alpha[CPT];                           // one state gate per (token, head), or one per key channel
+#pragma unroll
+        for (int e = 0; e < CPT; ++e)
+            alpha[e] = a.log_alpha ? __expf(a.gate_vec ? a.log_alpha[th * K + c0 + e] : a.log_alpha[th]) : 1.f;
         float ret[CPT];                             // one gate per (token, head), or one per coordinate
 #pragma unroll
         for (int e = 0; e < CPT; ++e)
@@ -58,7 +63,7 @@ __global__ __launch_bounds__(STEP_T) void step_kernel(StepArgs a) {
         for (int r = 0; r < STEP_RPW; ++r) {
             float dot = 0.f;
 #pragma unroll
-            for (int e = 0; e < CPT; ++e) { Sr[r][e] *= alpha; dot = __builtin_fmaf(Sr[r][e], kf[e], dot); }
+            for (int e = 0; e < CPT; ++e) { Sr[r][e] *= alpha[e]; dot = __builtin_fmaf(Sr[r][e], kf[e], dot); }
             dot = wave_sum(dot);
             const float ev = bet * (to_f32(vg[th * a.V + v0 + r]) - dot);
             float od = 0.f;

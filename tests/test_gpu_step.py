@@ -100,6 +100,41 @@ def test_chunk_equals_step_on_one_chunk():
         assert err <= 1e-4 * max(b.abs().max().item(), 1e-30), (name, err)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", [(2, 1, 2, 64, 64), (1, 33, 3, 128, 128), (2, 64, 1, 128, 64)])
+def test_step_with_a_gate_per_key_channel(shape, bf16):
+    """The online-scaled KDA recurrence: S <- S Diag(alpha_t) with one gate per key channel (and,
+    on the last shape, one retention per coordinate as well), against the oracle; launches of
+    one token each, state carried in place, agree with one launch bit for bit."""
+    B, T, H, K, V = shape
+    x = make_stress_inputs(B, T, H, K, V, seed=35, bf16=bf16, retention=0.97)
+    rng = np.random.default_rng(36)
+    x["log_alpha"] = (-np.logaddexp(0.0, rng.standard_normal((B, T, H, K)) - 1.0)).astype(np.float32)
+    if V == 64:
+        x["retention"] = np.clip(x["retention"][..., None] + 0.03 * rng.standard_normal((B, T, H, K)), 0, 1).astype(np.float32)
+    hp = ob.Hyper(eta=0.5)
+    t = to_dev(x, bf16)
+    o, S, d = ob.step(t["q"], t["k"], t["v"], t["beta"], t["log_alpha"], t["retention"], t["d_in"], t["S_in"], hp)
+    torch.cuda.synchronize()
+    oo, oS, od = _oracle_fwd(x, hp)
+    check("o", o, oo, bf16)
+    check("S_out", S, oS, bf16)
+    check("d_out", d, od, False)
+    S2, d2, outs = t["S_in"].clone(), t["d_in"], []
+    for i in range(T):
+        c = lambda a: a[:, i:i + 1].contiguous()
+        oi, S2, d2 = ob.step(c(t["q"]), c(t["k"]), c(t["v"]), c(t["beta"]), c(t["log_alpha"]), c(t["retention"]),
+                             d2, S2, hp, in_place=True)
+        outs.append(oi)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.cat(outs, 1), o) and torch.equal(S2, S) and torch.equal(d2, d)
+
+
+def test_chunkwise_entry_points_refuse_the_channel_gate():
+    p = ob.make_params(1, 64, 1, 64, 64, False, gate_per_channel=True)
+    assert ob.osdn_workspace_bytes(p, False) == 0
+
+
 def test_step_argument_errors():
     p = ob.make_params(1, 65, 1, 64, 64, False)
     z = torch.zeros(1, 65, 1, 64, device="cuda")

@@ -61,6 +61,9 @@ def test_argument_errors_before_any_pointer_is_used():
     p = ob.make_params(1, 128, 1, 64, 64, False)
     p.retention_per_channel = 3                            # a flag: 0 or 1
     assert L.osdn_precond_update(ctypes.byref(p), fake, fake, None, None, fake, fake, None, None) == -5
+    p = ob.make_params(1, 128, 1, 64, 64, False, gate_per_channel=True)     # recurrent step only
+    assert L.osdn_fwd(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
+                      fake, ctypes.c_size_t(1 << 30), None) == -2
     p = ob.make_params(1, 128, 1, 64, 64, False)
     assert L.osdn_fwd(ctypes.byref(p), None, fake, fake, fake, None, None, None, None, fake, fake, fake,
                       fake, ctypes.c_size_t(1 << 30), None) == -1
