@@ -142,6 +142,9 @@ def main():
     ap.add_argument("--decode-batch", type=int, default=0,
                     help="side workload, not the headline: time osdn_step (one token per sequence and launch, state "
                          "updated in place) for this many sequences with the configuration's heads")
+    ap.add_argument("--channel-gate", action="store_true",
+                    help="side workload, not the headline: the configuration's shape with one state gate per key "
+                         "channel (online-scaled KDA), log alpha = -softplus(N(-1,1)) per channel; forward pass only")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain device copy of 1 GiB (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -165,6 +168,9 @@ def main():
         cu = [0]
         while cu[-1] < cfg.T:       # document lengths: 1 + exponential of mean 1200, capped at 4096
             cu.append(min(cfg.T, cu[-1] + min(4096, 1 + int(rng.exponential(1200.0)))))
+    if args.channel_gate:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, backward=False, name=cfg.name + "_channel_gate_fwd")
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     ob.lib()                                        # fail loudly if the HIP library is not built
     x = make_inputs(cfg, seed=0)
@@ -174,9 +180,12 @@ def main():
     tq, tk, tv, tdO = (torch.from_numpy(x[n]).to(dev).to(dt) for n in ("q", "k", "v", "dO"))
     tb = torch.from_numpy(x["beta"]).to(dev)
     tg = None if x["log_alpha"] is None else torch.from_numpy(x["log_alpha"]).to(dev)
+    if args.channel_gate:
+        gen = torch.Generator(device=dev).manual_seed(2)
+        tg = -torch.nn.functional.softplus(torch.randn(cfg.B, cfg.T, cfg.H, cfg.K, device=dev, generator=gen) - 1.0)
     tr = None if x["retention"] is None else torch.from_numpy(x["retention"]).to(dev)
     hp = ob.Hyper()
-    p = ob.make_params(cfg.B, cfg.T, cfg.H, cfg.K, cfg.V, cfg.bf16, hp)
+    p = ob.make_params(cfg.B, cfg.T, cfg.H, cfg.K, cfg.V, cfg.bf16, hp, gate_per_channel=args.channel_gate)
     if cu is None:
         ws = ob.alloc_workspace(p, cfg.backward, dev)
     else:
@@ -264,7 +273,7 @@ def main():
     mfma_peak_frac = total_flops / (ms_per_step * 1e-3) / PEAK_BF16_FLOPS
 
     cpu = None
-    if not args.no_cpu_baseline and cu is None:
+    if not args.no_cpu_baseline and cu is None and not args.channel_gate:
         import oracle
         nthreads = oracle.threads()
         nch = min(cfg.B * cfg.H, 8 * nthreads)       # ~10-30 core-seconds of oracle work

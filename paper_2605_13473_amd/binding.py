@@ -284,7 +284,7 @@ def forward(q, k, v, beta, log_alpha=None, retention=None, d_in=None, S_in=None,
     given: B == 1, one carried entry per sequence).  Returns (o, S_out, d_out, ctx)."""
     B, T, H, K = k.shape
     V = v.shape[-1]
-    p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp, _per_channel(retention))
+    p = make_params(B, T, H, K, V, k.dtype == torch.bfloat16, hp, _per_channel(retention), _per_channel(log_alpha))
     if cu_seqlens is not None:
         cu_seqlens = [int(x) for x in cu_seqlens]
     if workspace is None:

@@ -36,6 +36,7 @@ template <typename F> int timed(int id, hipStream_t st, F &&launch) {
 }
 
 struct Layout {
+    size_t Qg, Kd, gamC;                                                 // per-channel state gate (forward only)
     size_t tables;                                                       // packed sequences: the index tables
     size_t kt, d_ckpt, tok_scalars, Tm, W, Wt, Ktr, Ut, Et, S_ckpt;   // forward
     size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;   // backward only
@@ -62,7 +63,7 @@ int check_params(const osdn_params *p, bool need_chunks) {
         return OSDN_ERR_PARAM;
     if (p->retention_per_channel != 0 && p->retention_per_channel != 1) return OSDN_ERR_PARAM;
     if (p->gate_per_channel != 0 && p->gate_per_channel != 1) return OSDN_ERR_PARAM;
-    if (need_chunks && p->gate_per_channel) return OSDN_ERR_SHAPE;      // the chunkwise kernels take the scalar gate
+
     return OSDN_OK;
 }
 
@@ -116,6 +117,7 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     const size_t es = p->io_dtype == OSDN_BF16 ? 2 : 4;
     const size_t B = p->B, H = p->H, K = p->K, V = p->V, N = (size_t)pk.N, T = N * C;
     const size_t RK = p->retention_per_channel ? K : 1;    // retention values per (token, head)
+    const size_t GK = p->gate_per_channel ? K : 1;         // state gates per (token, head)
     const bool ragged = pk.ragged;
     Layout L{};
     size_t off = 0;
@@ -131,10 +133,13 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     L.Ut = take(B * T * H * V * es);
     L.Et = take(B * T * H * V * es);
     L.S_ckpt = take(B * H * N * V * K * es);
+    if (p->gate_per_channel) {
+        L.Qg = take(B * T * H * K * es); L.Kd = take(B * T * H * K * es); L.gamC = take(B * H * N * K * 4);
+    }
     if (ragged) {
         L.p_q = take(B * T * H * K * es); L.p_k = take(B * T * H * K * es);
         L.p_v = take(B * T * H * V * es); L.p_o = take(B * T * H * V * es);
-        L.p_beta = take(B * T * H * 4); L.p_g = take(B * T * H * 4); L.p_r = take(B * T * H * 4 * RK);
+        L.p_beta = take(B * T * H * 4); L.p_g = take(B * T * H * 4 * GK); L.p_r = take(B * T * H * 4 * RK);
     }
     L.total_fwd = off;
     L.dElt = take(B * T * H * V * es);
@@ -254,6 +259,7 @@ extern "C" {
 
 size_t osdn_workspace_bytes(const osdn_params *p, int for_backward) {
     if (check_params(p, true) != OSDN_OK) return 0;
+    if (for_backward && p->gate_per_channel) return 0;      // no backward pass with a gate per channel
     Packing pk;
     plain_packing(p, pk);
     Layout L = make_layout(p, pk);
@@ -264,6 +270,7 @@ size_t osdn_workspace_bytes_packed(const osdn_params *p, const int32_t *cu_seqle
                                    int for_backward) {
     Packing pk;
     if (check_params(p, true) != OSDN_OK || make_packing(p, cu_seqlens, n_seqs, pk) != OSDN_OK) return 0;
+    if (for_backward && p->gate_per_channel) return 0;
     Layout L = make_layout(p, pk);
     return for_backward ? L.total_bwd : L.total_fwd;
 }
@@ -328,6 +335,7 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     int rc = check_params(p, true);
     if (rc != OSDN_OK) return rc;
     if (!q || !k || !v || !beta || !o || !S_out || !d_out) return OSDN_ERR_NULL;
+    if (p->gate_per_channel && !log_alpha) return OSDN_ERR_NULL;
     Packing pk;
     if (cu_seqlens || n_seqs != 0) {
         rc = make_packing(p, cu_seqlens, n_seqs, pk);
@@ -365,7 +373,7 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
         const size_t es = bf ? 2 : 4, rk = (size_t)p->H * p->K * es, rv = (size_t)p->H * p->V * es, rg = (size_t)p->H * 4;
         auto pad = [&](const void *src, size_t off, size_t row, uint32_t fill) { return move(src, ws + off, row, true, fill); };
         if (pad(q, L.p_q, rk, 0u) != 0 || pad(k, L.p_k, rk, 0u) != 0 || pad(v, L.p_v, rv, 0u) != 0 ||
-            pad(beta, L.p_beta, rg, 0u) != 0 || (log_alpha && pad(log_alpha, L.p_g, rg, 0u) != 0) ||
+            pad(beta, L.p_beta, rg, 0u) != 0 || (log_alpha && pad(log_alpha, L.p_g, p->gate_per_channel ? rg * p->K : rg, 0u) != 0) ||
             (retention && pad(retention, L.p_r, p->retention_per_channel ? rg * p->K : rg, 0x3f800000u) != 0))
             return OSDN_ERR_SHAPE;
         q = ws + L.p_q; k = ws + L.p_k; v = ws + L.p_v; o = ws + L.p_o;
@@ -388,6 +396,16 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     c.q = q; c.k = k; c.v = v; c.beta = beta; c.log_alpha = log_alpha;
     c.o = o; c.S_out = S_out;
     c.n_seqs = pk.n_seqs; c.seq_chunks = seq_chunks; c.S_first = S_in;
+    // one state gate per key channel: chunk_prep folds the channel decays into the operands and
+    // leaves Gamma . Q and K~ / Gamma, on which the state and output kernels run as if ungated
+    const bool gv = p->gate_per_channel != 0;
+    ChunkArgs cg = c;                                  // what state_fwd and output_fwd see
+    if (gv) {
+        c.gate_vec = 1;
+        c.Qg = ws + L.Qg; c.Kd = ws + L.Kd; c.gamC = reinterpret_cast<float *>(ws + L.gamC);
+        cg = c;
+        cg.log_alpha = nullptr; cg.q = c.Qg; cg.kt = c.Kd;
+    }
 
     const int N = p->T / C;
     int S = segment_count(N, pk.longest);
@@ -401,11 +419,12 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
         return timed(KID_PRECOND_FWD, s1, [&] { return launch_precond_fwd(pa, bf, s1); });
     };
     auto phase2 = [&](int kid, int sidx) {
-        seg_range(sidx, c.n0, c.n1);
-        c.S_in = sidx == 0 ? S_in : S_out;           // S is carried in S_out
+        ChunkArgs &ck = (gv && kid != KID_CHUNK_PREP) ? cg : c;
+        seg_range(sidx, ck.n0, ck.n1);
+        ck.S_in = sidx == 0 ? S_in : S_out;          // S is carried in S_out
         return timed(kid, st, [&] {
-            return kid == KID_CHUNK_PREP ? launch_chunk_prep(c, bf, st)
-                 : kid == KID_STATE_FWD ? launch_state_fwd(c, bf, st) : launch_output_fwd(c, bf, st);
+            return kid == KID_CHUNK_PREP ? launch_chunk_prep(ck, bf, st)
+                 : kid == KID_STATE_FWD ? launch_state_fwd(ck, bf, st) : launch_output_fwd(ck, bf, st);
         });
     };
     if (!pl) {
@@ -441,6 +460,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     if (!q || !k || !v || !beta || !dO || !dq || !dk || !dv || !dbeta || !dd_in || !dS_in)
         return OSDN_ERR_NULL;
     if ((log_alpha && !dlog_alpha) || (retention && !dretention)) return OSDN_ERR_NULL;
+    if (p->gate_per_channel) return OSDN_ERR_SHAPE;          // no backward pass with a gate per channel
     (void)d_in; (void)S_in;
     Packing pk;
     if (cu_seqlens || n_seqs != 0) {

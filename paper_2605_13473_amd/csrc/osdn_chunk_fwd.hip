@@ -20,7 +20,15 @@ namespace osdn {
 // for free from the accumulator layout, or from a 0/1 selector product for K~).
 // The row scalings of the right-hand sides move into T: W = (T diag(beta gamma)) K and
 // U = (T diag(beta)) V, so that K and V enter the products as they come from memory.
-template <typename T, int K>
+//
+// GV: one state gate per key channel (the chunkwise UT form of online-scaled KDA, appendix
+// section on Kimi Delta Attention with online scaling).  The cumulative channel decays
+// Gamma [64 x K] do not factor out of the Gram matrix as a 64 x 64 mask, so they are folded
+// into the operands: K <- Gamma . K and K~ <- K~ / Gamma in LDS before anything else, after
+// which the kernel runs as with no gate at all; it also leaves Gamma . Q, K~ / Gamma and the
+// chunk's total decay per channel for the state and output kernels.  1 / Gamma grows like
+// e^{|G|}: the cumulative log-decay of a channel inside a chunk has to stay above about -80.
+template <typename T, int K, bool GV>
 __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDF = C + 1;
     constexpr int NKT = K / 64;                                 // column tiles of a [64 x K] result per wave
@@ -40,6 +48,7 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     T *Tw = reinterpret_cast<T *>(Af);                          // [64][LDC], once A is dead
     T *stage = reinterpret_cast<T *>(Ti);                       // [K][LDC] / [64][LDC], while Ti is not live
     __shared__ float Gs[C], Bs[C];
+    __shared__ float gCs[GV ? K : 1];                           // per-channel decay over the whole chunk
 
     const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -55,7 +64,7 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
 #endif
     if (wave == 0) {
         const size_t th = tok0 + (size_t)lane * tstride;
-        const float g = a.log_alpha ? a.log_alpha[th] : 0.f;
+        const float g = (!GV && a.log_alpha) ? a.log_alpha[th] : 0.f;      // GV: the gates go into the operands
         Gs[lane] = wave_cumsum(g, lane);
         Bs[lane] = a.beta[th];
     }
@@ -66,6 +75,56 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     TileRegs<T, C, C, NT> r_V;
     r_V.fetch(vg, tstride * a.V, tid);
     __syncthreads();
+    if (GV) {
+        // cumulative log-decay of every channel, G [64 x K] in fp32, in the scratch space (not
+        // yet in use): loaded with vector reads, summed down the columns by one thread per
+        // channel, then K <- e^{G} K and K~ <- e^{-G} K~ in LDS and Gamma . Q straight to memory,
+        // all threads on 16-byte vectors
+        constexpr int GLD = K + 4, VN = 16 / sizeof(T);
+        static_assert(C * GLD <= AF_F + (TI_F > STAGE_F ? TI_F : STAGE_F), "G must fit the scratch space");
+        float *Gt = scratch;
+        const size_t rs = tstride * K;
+        const float *gp = a.log_alpha + tok0 * K;
+        for (int v = tid; v < C * K / 4; v += NT) {
+            const int i = v / (K / 4), c = (v % (K / 4)) * 4;
+            *reinterpret_cast<f32x4 *>(Gt + i * GLD + c) = *reinterpret_cast<const f32x4 *>(gp + (size_t)i * rs + c);
+        }
+        __syncthreads();
+        if (tid < K) {
+            float G = 0.f;
+#pragma unroll 16
+            for (int i = 0; i < C; ++i) {
+                G += Gt[i * GLD + tid];
+                Gt[i * GLD + tid] = G;
+            }
+            gCs[GV ? tid : 0] = __expf(G);
+            a.gamC[bhn * K + tid] = __expf(G);
+        }
+        __syncthreads();
+        const T *qp = static_cast<const T *>(a.q) + tok0 * K;
+        T *qg = static_cast<T *>(a.Qg) + tok0 * K;
+        for (int v = tid; v < C * K / VN; v += NT) {
+            const int i = v / (K / VN), c = (v % (K / VN)) * VN;
+            const u32x4 kv = *reinterpret_cast<const u32x4 *>(X1 + i * LDK + c);
+            const u32x4 tv = *reinterpret_cast<const u32x4 *>(X2 + i * LDK + c);
+            const u32x4 qv = *reinterpret_cast<const u32x4 *>(qp + (size_t)i * rs + c);
+            float ko[VN], to[VN], qo[VN];
+#pragma unroll
+            for (int e = 0; e < VN; ++e) {
+                const float G = Gt[i * GLD + c + e];
+                const float gam = __expf(G), inv = __expf(-G);
+                ko[e] = vec_get<T>(kv, e) * gam;
+                to[e] = vec_get<T>(tv, e) * inv;
+                qo[e] = vec_get<T>(qv, e) * gam;
+            }
+            store_vec_t(X1 + i * LDK + c, ko);
+            store_vec_t(X2 + i * LDK + c, to);
+            store_vec_t(qg + (size_t)i * rs + c, qo);
+        }
+        __syncthreads();
+        store_tile_global(static_cast<T *>(a.Kd) + tok0 * K, tstride * K, X2, LDK, C, K, tid, NT);
+        __syncthreads();            // the scratch space is handed over to A
+    }
     OSDN_CTICK(0)
 
     // ---- A = tril(beta_i Gamma_ij <k_i, k~_j>, -1): the ten lower 16x16 tiles ----
@@ -91,6 +150,11 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
                 f32x4 acc = pick16<T>(X2 + jb * 16 * LDK, LDK, nb * 16, lane);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[r] *= __expf(GC - Gs[jb * 16 + acc_row(lane, r)]);
+                if (GV) {                       // (gamma_C / Gamma) . K~ = gamma_C . (K~ / Gamma), channel by channel
+                    const float gc = gCs[GV ? nb * 16 + acc_col(lane) : 0];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[r] *= gc;
+                }
                 store_tile_t(stage + nb * 16 * LDC + jb * 16, LDC, acc, lane);
             }
         }
@@ -214,7 +278,8 @@ constexpr int VS = 32;          // rows of S (values) owned by one workgroup
 constexpr int CT_ = 512;        // threads of a chain workgroup
 constexpr int CL_ = 256;        // ... of which loaders
 
-template <typename T, int K>
+// GV: one state gate per key channel; the chunk's decay per channel comes from chunk_prep.
+template <typename T, int K, bool GV>
 __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
     constexpr int VN = 16 / sizeof(T);
@@ -331,12 +396,19 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
         const int buf = NB == 2 ? (n & 1) : 0;
         const size_t bhn = bth * a.N + n;
         // ---- phase A (compute): S, rounded, into LDS ----
+        f32x4 gch[GV ? NKT : 1];                                    // channel decays of this lane's state rows
         if (!loader) {
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
                 for (int q = 0; q < NKT; ++q)
                     store_tile_t(Sb + vt * 16 * LDK + (wave * NKT + q) * 16, LDK, St[vt][q], lane);
+            if (GV) {
+#pragma unroll
+                for (int q = 0; q < NKT; ++q)
+                    gch[GV ? q : 0] = *reinterpret_cast<const f32x4 *>(
+                        a.gamC + bhn * K + (wave * NKT + q) * 16 + acc_row(lane, 0));
+            }
         }
         OSDN_TICK(0)
         __syncthreads();                                            // barrier 1
@@ -388,7 +460,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
 #pragma unroll
                 for (int q = 0; q < NKT; ++q) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) St[vt][q][r] *= gC;
+                    for (int r = 0; r < 4; ++r) St[vt][q][r] *= GV ? gch[GV ? q : 0][r] : gC;
                     mma_tile<T, true, true>(St[vt][q], &Ktr[buf][(wave * NKT + q) * 16 * LDC], LDC,
                                             Et + vt * 16 * LDC, LDC, C, lane);
                 }
@@ -489,27 +561,31 @@ __global__ __launch_bounds__(NT) void output_fwd_kernel(ChunkArgs a) {
 }
 
 // -------------------------------------------------------------- launchers ----
-template <typename T>
+template <typename T, bool GV>
 static int launch_prep_t(const ChunkArgs &a, hipStream_t st) {
     dim3 grid(a.n1 - a.n0, a.H, a.B), block(NT);
-    if (a.K == 64) hipLaunchKernelGGL((chunk_prep_kernel<T, 64>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((chunk_prep_kernel<T, 128>), grid, block, 0, st, a);
+    if (GV && (!a.log_alpha || !a.Qg || !a.Kd || !a.gamC)) return -1;
+    if (a.K == 64) hipLaunchKernelGGL((chunk_prep_kernel<T, 64, GV>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((chunk_prep_kernel<T, 128, GV>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
 int launch_chunk_prep(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
-    return bf16_io ? launch_prep_t<bf16>(a, st) : launch_prep_t<float>(a, st);
+    if (a.gate_vec) return bf16_io ? launch_prep_t<bf16, true>(a, st) : launch_prep_t<float, true>(a, st);
+    return bf16_io ? launch_prep_t<bf16, false>(a, st) : launch_prep_t<float, false>(a, st);
 }
-template <typename T>
+template <typename T, bool GV>
 static int launch_state_t(const ChunkArgs &a, hipStream_t st) {
     dim3 grid((a.V / VS) * a.H * (a.seq_chunks ? a.n_seqs : a.B)), block(CT_);
-    if (a.K == 64) hipLaunchKernelGGL((state_fwd_kernel<T, 64>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((state_fwd_kernel<T, 128>), grid, block, 0, st, a);
+    if (GV && !a.gamC) return -1;
+    if (a.K == 64) hipLaunchKernelGGL((state_fwd_kernel<T, 64, GV>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((state_fwd_kernel<T, 128, GV>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
 int launch_state_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
-    return bf16_io ? launch_state_t<bf16>(a, st) : launch_state_t<float>(a, st);
+    if (a.gate_vec) return bf16_io ? launch_state_t<bf16, true>(a, st) : launch_state_t<float, true>(a, st);
+    return bf16_io ? launch_state_t<bf16, false>(a, st) : launch_state_t<float, false>(a, st);
 }
 template <typename T>
 static int launch_output_t(const ChunkArgs &a, hipStream_t st) {

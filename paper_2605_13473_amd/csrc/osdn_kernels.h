@@ -98,6 +98,12 @@ struct ChunkArgs {
     void *Ut;                         // [B,H,N,V,64] io   U^T
     void *Et;                         // [B,H,N,V,64] io   E transposed
     void *S_ckpt;                     // [B,H,N,V,K] io    state at the start of each chunk (null: not kept)
+    // one state gate per key channel (gate_vec: log_alpha is [B,T,H,K]; forward only): chunk_prep
+    // folds the cumulative channel decays Gamma into the operands and leaves
+    int gate_vec;
+    void *Qg;                         // [B,T,H,K] io      Gamma . Q
+    void *Kd;                         // [B,T,H,K] io      K~ / Gamma
+    float *gamC;                      // [B,H,N,K] f32     decay of every channel over the whole chunk
     // backward
     const void *dO;                   // [B,T,H,V] io
     const float *dS_out;              // [B,H,V,K] or null

@@ -130,11 +130,6 @@ def test_step_with_a_gate_per_key_channel(shape, bf16):
     assert torch.equal(torch.cat(outs, 1), o) and torch.equal(S2, S) and torch.equal(d2, d)
 
 
-def test_chunkwise_entry_points_refuse_the_channel_gate():
-    p = ob.make_params(1, 64, 1, 64, 64, False, gate_per_channel=True)
-    assert ob.osdn_workspace_bytes(p, False) == 0
-
-
 def test_step_argument_errors():
     p = ob.make_params(1, 65, 1, 64, 64, False)
     z = torch.zeros(1, 65, 1, 64, device="cuda")
