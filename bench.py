@@ -144,7 +144,7 @@ def main():
                          "updated in place) for this many sequences with the configuration's heads")
     ap.add_argument("--channel-gate", action="store_true",
                     help="side workload, not the headline: the configuration's shape with one state gate per key "
-                         "channel (online-scaled KDA), log alpha = -softplus(N(-1,1)) per channel; forward pass only")
+                         "channel (online-scaled KDA), log alpha = -softplus(N(-1,1)) per channel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain device copy of 1 GiB (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -170,7 +170,7 @@ def main():
             cu.append(min(cfg.T, cu[-1] + min(4096, 1 + int(rng.exponential(1200.0)))))
     if args.channel_gate:
         import dataclasses
-        cfg = dataclasses.replace(cfg, backward=False, name=cfg.name + "_channel_gate_fwd")
+        cfg = dataclasses.replace(cfg, name=cfg.name + "_channel_gate")
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     ob.lib()                                        # fail loudly if the HIP library is not built
     x = make_inputs(cfg, seed=0)
@@ -197,7 +197,7 @@ def main():
     d_out = torch.empty(nb, cfg.H, cfg.K, **f32)
     dq, dk, dv = torch.empty_like(tq), torch.empty_like(tk), torch.empty_like(tv)
     dbeta = torch.empty_like(tb)
-    dg = None if tg is None else torch.empty_like(tb)
+    dg = None if tg is None else torch.empty_like(tg)
     dr = None if tr is None else torch.empty_like(tb)
     dd_in = torch.empty(nb, cfg.H, cfg.K, **f32)
     dS_in = torch.empty(nb, cfg.H, cfg.V, cfg.K, **f32)
@@ -242,6 +242,7 @@ def main():
     # summed over the launches of one step (= launch-weighted average rate)
     per_kernel = {k: ms / args.steps for k, (ms, n) in prof.items() if n > 0}
     copies_ms = per_kernel.pop("pad", None)         # moving ragged / packed sequences onto chunk boundaries
+    unfold_ms = per_kernel.pop("unfold", None)      # per-channel gates: gradients of the folded operands mapped back
     launches = {k: n // args.steps for k, (ms, n) in prof.items() if n > 0}
     dominant = max(per_kernel, key=per_kernel.get)
     models, flops = kernel_models(cfg, es)
@@ -263,6 +264,8 @@ def main():
     roof["launches_per_step"] = launches[dominant]
     if copies_ms is not None:
         roof["per_kernel_ms"]["pad (copies)"] = round(copies_ms, 4)
+    if unfold_ms is not None:
+        roof["per_kernel_ms"]["unfold"] = round(unfold_ms, 4)
 
     # whole-path algorithmic flops (MFMA only) per token-head, for the %-of-peak figure
     K, V, C = cfg.K, cfg.V, 64

@@ -82,11 +82,10 @@ typedef struct {
                                        1: one per key channel, [B,T,H,K]: S <- S Diag(alpha_t), the
                                        online-scaled KDA recurrence (appendix section on Kimi Delta
                                        Attention with online scaling; its K x V state is the transpose
-                                       of the [V,K] state kept here).  Forward only: osdn_step,
-                                       osdn_fwd and osdn_fwd_packed take it (the cumulative log-decay
-                                       of a channel inside a chunk of 64 tokens has to stay above
-                                       about -80); osdn_bwd returns OSDN_ERR_SHAPE and
-                                       osdn_workspace_bytes(.., for_backward = 1) returns 0 */
+                                       of the [V,K] state kept here); dlog_alpha then has that shape
+                                       too and log_alpha must not be NULL.  In the chunkwise entry
+                                       points the cumulative log-decay of a channel inside a chunk
+                                       of 64 tokens has to stay above about -80 */
 } osdn_params;
 
 /* Bytes of scratch osdn_fwd needs (for_backward == 0) or osdn_fwd followed by osdn_bwd

@@ -41,7 +41,7 @@ class _Params(ctypes.Structure):
         ("scale", ctypes.c_double), ("eta", ctypes.c_double),
         ("d_min", ctypes.c_double), ("d_max", ctypes.c_double),
         ("eps", ctypes.c_double), ("beta_aware", ctypes.c_int), ("gate_vec", ctypes.c_int),
-        ("ret_vec", ctypes.c_int),
+        ("ret_vec", ctypes.c_int), ("tie_tol", ctypes.c_double), ("tie_inside", ctypes.c_int),
     ]
 
 
@@ -54,6 +54,10 @@ class Hyper:
     d_max: float = 2.0
     eps: float = 1e-6
     beta_aware: bool = True
+    # backward only: unprojected values within tie_tol of a face of the box count as inside
+    # (tie_inside) or outside; 0 = the plain rule (see osdn_oracle.c)
+    tie_tol: float = 0.0
+    tie_inside: bool = True
 
 
 def _load():
@@ -90,7 +94,7 @@ def _params(hp: Hyper, B, T, H, K, V, retention=None, log_alpha=None) -> _Params
         assert log_alpha.shape in ((B, T, H), (B, T, H, K)), log_alpha.shape
         gate_vec = int(log_alpha.ndim == 4)      # one state gate per key channel: Diag(alpha_t)
     return _Params(B, T, H, K, V, scale, hp.eta, hp.d_min, hp.d_max, hp.eps, int(hp.beta_aware), gate_vec,
-                   ret_vec)
+                   ret_vec, float(hp.tie_tol), int(hp.tie_inside))
 
 
 def precond(k, beta, retention=None, d_in=None, hp: Hyper = Hyper(), want_traj: bool = False):

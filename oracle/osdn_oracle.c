@@ -61,6 +61,14 @@ typedef struct {
     int ret_vec;       /* 1: retention is a vector per token and head, [B,T,H,K]: the
                           diag(r_t) extension of the APF step (proposition on APF being a
                           piecewise-affine recurrence, appendix); 0: scalar, [B,T,H] */
+    double tie_tol;    /* backward only, 0 by default.  The derivative of the projection is a
+                          decision (inside the box or not) taken on a floating-point value; an
+                          unprojected value within tie_tol of a face is one that fp32 arithmetic
+                          cannot place on either side reliably.  With tie_tol > 0 every such
+                          value is declared inside (tie_inside = 1) or outside (tie_inside = 0):
+                          the two admissible readings a lower-precision implementation may be
+                          compared with. */
+    int tie_inside;
 } osdn_oracle_params;
 
 /* retention of coordinate j of token-head th (NULL => 1) */
@@ -305,7 +313,13 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                     double g_r = 0.0, g_c = 0.0;
                     for (int j = 0; j < K; ++j) {
                         double g = gd[j];
-                        if (project && !(dbar[j] >= P->d_min && dbar[j] <= P->d_max)) g = 0.0;
+                        if (project) {
+                            int inside = dbar[j] >= P->d_min && dbar[j] <= P->d_max;
+                            if (P->tie_tol > 0.0 && (fabs(dbar[j] - P->d_min) <= P->tie_tol ||
+                                                     fabs(dbar[j] - P->d_max) <= P->tie_tol))
+                                inside = P->tie_inside;
+                            if (!inside) g = 0.0;
+                        }
                         gd[j] = g;                       /* now adjoint of d_bar */
                         if (dretention && P->ret_vec) dretention[th * K + j] = g * dcur[j];
                         g_r += g * dcur[j];

@@ -187,7 +187,7 @@ def osdn_bwd(params, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out
         _ptr(S_in, f32, bhvk, "S_in"), _ptr(dO, io, bthv, "dO"), _ptr(dS_out, f32, bhvk, "dS_out"),
         _ptr(dd_out, f32, bhk, "dd_out"), _ptr(dq, io, bthk, "dq"), _ptr(dk, io, bthk, "dk"),
         _ptr(dv, io, bthv, "dv"), _ptr(dbeta, f32, bth, "dbeta"),
-        _ptr(dlog_alpha, f32, bth, "dlog_alpha"), _ptr(dretention, f32, _ret_shape(p), "dretention"),
+        _ptr(dlog_alpha, f32, _gate_shape(p), "dlog_alpha"), _ptr(dretention, f32, _ret_shape(p), "dretention"),
         _ptr(dd_in, f32, bhk, "dd_in"), _ptr(dS_in, f32, bhvk, "dS_in"),
         _ptr(workspace, torch.uint8, None, "workspace"), ctypes.c_size_t(workspace.numel()),
         _stream_ptr(stream)))
@@ -234,7 +234,7 @@ def osdn_bwd_packed(params, q, k, v, beta, log_alpha, retention, d_in, S_in, dO,
         _ptr(S_in, f32, bhvk, "S_in"), _ptr(dO, io, bthv, "dO"), _ptr(dS_out, f32, bhvk, "dS_out"),
         _ptr(dd_out, f32, bhk, "dd_out"), _ptr(dq, io, bthk, "dq"), _ptr(dk, io, bthk, "dk"),
         _ptr(dv, io, bthv, "dv"), _ptr(dbeta, f32, bth, "dbeta"),
-        _ptr(dlog_alpha, f32, bth, "dlog_alpha"), _ptr(dretention, f32, _ret_shape(p), "dretention"),
+        _ptr(dlog_alpha, f32, _gate_shape(p), "dlog_alpha"), _ptr(dretention, f32, _ret_shape(p), "dretention"),
         _ptr(dd_in, f32, bhk, "dd_in"), _ptr(dS_in, f32, bhvk, "dS_in"),
         cu, n, _ptr(workspace, torch.uint8, None, "workspace"), ctypes.c_size_t(workspace.numel()),
         _stream_ptr(stream)))
@@ -318,7 +318,7 @@ def backward(ctx, dO, dS_out=None, dd_out=None):
     g = {
         "dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v),
         "dbeta": torch.empty_like(beta),
-        "dlog_alpha": torch.empty_like(beta) if log_alpha is not None else None,
+        "dlog_alpha": torch.empty_like(log_alpha) if log_alpha is not None else None,
         "dretention": torch.empty_like(retention) if retention is not None else None,
         "dd_in": torch.empty(nb, p.H, p.K, **f32), "dS_in": torch.empty(nb, p.H, p.V, p.K, **f32),
     }

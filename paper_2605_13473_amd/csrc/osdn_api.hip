@@ -16,10 +16,10 @@ using namespace osdn;
 // Optional per-kernel timing with HIP events on the caller's stream (off by default; the
 // only process-wide state the library has).  Not thread-safe; meant for benchmarks.
 enum { KID_PRECOND_FWD, KID_CHUNK_PREP, KID_STATE_FWD, KID_OUTPUT_FWD, KID_BWD_LOCAL, KID_BWD_CHAIN,
-       KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_STEP, KID_PAD, KID_COUNT };
+       KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_STEP, KID_PAD, KID_UNFOLD, KID_COUNT };
 const char *const kKernelNames[KID_COUNT] = {"precond_fwd", "chunk_prep", "state_fwd", "output_fwd",
                                              "bwd_local", "bwd_chain", "bwd_post", "precond_mask",
-                                             "precond_chain", "precond_post", "step", "pad"};
+                                             "precond_chain", "precond_post", "step", "pad", "unfold"};
 struct Timed { int id; hipEvent_t e0, e1; };
 bool g_prof_on = false;
 std::vector<Timed> g_prof;
@@ -36,7 +36,7 @@ template <typename F> int timed(int id, hipStream_t st, F &&launch) {
 }
 
 struct Layout {
-    size_t Qg, Kd, gamC;                                                 // per-channel state gate (forward only)
+    size_t Qg, Kg, Kd, gamC, dgamC;                                      // per-channel state gate
     size_t tables;                                                       // packed sequences: the index tables
     size_t kt, d_ckpt, tok_scalars, Tm, W, Wt, Ktr, Ut, Et, S_ckpt;   // forward
     size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;   // backward only
@@ -134,7 +134,8 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     L.Et = take(B * T * H * V * es);
     L.S_ckpt = take(B * H * N * V * K * es);
     if (p->gate_per_channel) {
-        L.Qg = take(B * T * H * K * es); L.Kd = take(B * T * H * K * es); L.gamC = take(B * H * N * K * 4);
+        L.Qg = take(B * T * H * K * es); L.Kg = take(B * T * H * K * es); L.Kd = take(B * T * H * K * es);
+        L.gamC = take(B * H * N * K * 4);
     }
     if (ragged) {
         L.p_q = take(B * T * H * K * es); L.p_k = take(B * T * H * K * es);
@@ -151,10 +152,11 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     L.dkt = take(B * T * H * K * es);
     L.masks = take(B * H * N * K * 8);
     L.a_ckpt = take(B * H * N * K * 4);
+    if (p->gate_per_channel) L.dgamC = take(B * H * N * K * 4);
     if (ragged) {
         L.p_dO = take(B * T * H * V * es); L.p_dv = take(B * T * H * V * es);
         L.p_dq = take(B * T * H * K * es); L.p_dk = take(B * T * H * K * es);
-        L.p_dbeta = take(B * T * H * 4); L.p_dg = take(B * T * H * 4); L.p_dr = take(B * T * H * 4 * RK);
+        L.p_dbeta = take(B * T * H * 4); L.p_dg = take(B * T * H * 4 * GK); L.p_dr = take(B * T * H * 4 * RK);
     }
     L.total_bwd = off;
     return L;
@@ -259,7 +261,6 @@ extern "C" {
 
 size_t osdn_workspace_bytes(const osdn_params *p, int for_backward) {
     if (check_params(p, true) != OSDN_OK) return 0;
-    if (for_backward && p->gate_per_channel) return 0;      // no backward pass with a gate per channel
     Packing pk;
     plain_packing(p, pk);
     Layout L = make_layout(p, pk);
@@ -270,7 +271,6 @@ size_t osdn_workspace_bytes_packed(const osdn_params *p, const int32_t *cu_seqle
                                    int for_backward) {
     Packing pk;
     if (check_params(p, true) != OSDN_OK || make_packing(p, cu_seqlens, n_seqs, pk) != OSDN_OK) return 0;
-    if (for_backward && p->gate_per_channel) return 0;
     Layout L = make_layout(p, pk);
     return for_backward ? L.total_bwd : L.total_fwd;
 }
@@ -402,7 +402,7 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     ChunkArgs cg = c;                                  // what state_fwd and output_fwd see
     if (gv) {
         c.gate_vec = 1;
-        c.Qg = ws + L.Qg; c.Kd = ws + L.Kd; c.gamC = reinterpret_cast<float *>(ws + L.gamC);
+        c.Qg = ws + L.Qg; c.Kg = ws + L.Kg; c.Kd = ws + L.Kd; c.gamC = reinterpret_cast<float *>(ws + L.gamC);
         cg = c;
         cg.log_alpha = nullptr; cg.q = c.Qg; cg.kt = c.Kd;
     }
@@ -460,7 +460,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     if (!q || !k || !v || !beta || !dO || !dq || !dk || !dv || !dbeta || !dd_in || !dS_in)
         return OSDN_ERR_NULL;
     if ((log_alpha && !dlog_alpha) || (retention && !dretention)) return OSDN_ERR_NULL;
-    if (p->gate_per_channel) return OSDN_ERR_SHAPE;          // no backward pass with a gate per channel
+    if (p->gate_per_channel && !log_alpha) return OSDN_ERR_NULL;
     (void)d_in; (void)S_in;
     Packing pk;
     if (cu_seqlens || n_seqs != 0) {
@@ -513,7 +513,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
         if (ragged) {
             auto cut = [&](const void *src, void *dst, size_t row) { return move(src, dst, row, false); };
             if (cut(dq, dq_user, rk_) != 0 || cut(dk, dk_user, rk_) != 0 || cut(dv, dv_user, rv_) != 0 ||
-                cut(dbeta, dbeta_user, rg_) != 0 || (log_alpha && cut(dlog_alpha, dg_user, rg_) != 0) ||
+                cut(dbeta, dbeta_user, rg_) != 0 || (log_alpha && cut(dlog_alpha, dg_user, p->gate_per_channel ? rg_ * p->K : rg_) != 0) ||
                 (retention && cut(dretention, dr_user, p->retention_per_channel ? rg_ * p->K : rg_) != 0))
                 return OSDN_ERR_SHAPE;
         }
@@ -529,6 +529,22 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     c.dkt = ws + L.dkt;
     c.dbeta = dbeta; c.dlog_alpha = log_alpha ? dlog_alpha : nullptr;
     c.n_seqs = pk.n_seqs; c.seq_chunks = seq_chunks; c.dS_last = dS_out;
+    // one state gate per key channel: phase 2 runs ungated on the folded operands the forward
+    // pass left (Gamma . Q, Gamma . K, K~ / Gamma) and the unfold kernel maps its gradients back
+    const bool gv = p->gate_per_channel != 0;
+    UnfoldArgs un{};
+    if (gv) {
+        un.B = p->B; un.T = p->T; un.H = p->H; un.K = p->K; un.N = p->T / C;
+        un.log_alpha = log_alpha; un.q = q; un.k = k; un.kt = c.kt;
+        un.dq = dq; un.dk_read = c.dk_read; un.dkt = c.dkt;
+        un.gamC = reinterpret_cast<const float *>(ws + L.gamC);
+        un.dgamC = reinterpret_cast<const float *>(ws + L.dgamC);
+        un.dlog_alpha = dlog_alpha;
+        c.gate_vec = 1;
+        c.q = ws + L.Qg; c.k = ws + L.Kg; c.kt = ws + L.Kd;
+        c.log_alpha = nullptr; c.dlog_alpha = nullptr;
+        c.gamC = reinterpret_cast<float *>(ws + L.gamC); c.dgamC = reinterpret_cast<float *>(ws + L.dgamC);
+    }
     PrecondBwdArgs pb{};
     pb.B = p->B; pb.T = p->T; pb.H = p->H; pb.K = p->K;
     pb.eta = p->eta; pb.d_min = p->d_min; pb.d_max = p->d_max; pb.eps = p->eps;
@@ -552,10 +568,13 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     auto phase2 = [&](int kid, int sidx) {
         seg_range(sidx, c.n0, c.n1);
         c.dS_out = sidx == S - 1 ? dS_out : dS_in;   // dS is carried in dS_in
-        return timed(kid, st, [&] {
+        const int rc2 = timed(kid, st, [&] {
             return kid == KID_BWD_LOCAL ? launch_bwd_local(c, bf, st)
                  : kid == KID_BWD_CHAIN ? launch_bwd_chain(c, bf, st) : launch_bwd_post(c, bf, st);
         });
+        if (rc2 != 0 || !gv || kid != KID_BWD_POST) return rc2;
+        un.n0 = c.n0; un.n1 = c.n1;                    // the segment's gradients, back to q, k, k~ and log alpha
+        return timed(KID_UNFOLD, st, [&] { return launch_unfold(un, bf, st); });
     };
     // the box masks depend on the forward pass only: one launch for the whole sequence, up front
     auto masks = [&](hipStream_t s1) {

@@ -122,7 +122,8 @@ __global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
 // buffer and write the dS' checkpoint and dE^T back.
 constexpr int CT_ = 512, CL_ = 256;
 
-template <typename T, int K>
+// GV: one state gate per key channel (the chunk's decay per channel comes from chunk_prep).
+template <typename T, int K, bool GV>
 __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
     constexpr int VN = 16 / sizeof(T);
@@ -233,12 +234,19 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         const int buf = NB == 2 ? (n & 1) : 0;
         const size_t bhn = bth * a.N + n;
         // ---- phase A (compute): dS', rounded, into LDS ----
+        f32x4 gch[GV ? NKT : 1];                                    // channel decays of this lane's state rows
         if (!loader) {
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
                 for (int q = 0; q < NKT; ++q)
                     store_tile_t(dSb + vt * 16 * LDK + (wave * NKT + q) * 16, LDK, dSt[vt][q], lane);
+            if (GV) {
+#pragma unroll
+                for (int q = 0; q < NKT; ++q)
+                    gch[GV ? q : 0] = *reinterpret_cast<const f32x4 *>(
+                        a.gamC + bhn * K + (wave * NKT + q) * 16 + acc_row(lane, 0));
+            }
         }
         __syncthreads();                                            // barrier 1
         if (loader) {
@@ -282,7 +290,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
 #pragma unroll
                 for (int q = 0; q < NKT; ++q) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) dSt[vt][q][r] *= gC;
+                    for (int r = 0; r < 4; ++r) dSt[vt][q][r] *= GV ? gch[GV ? q : 0][r] : gC;
                     const int ct = (wave * NKT + q) * 16;
                     mma_tile<T, true, true>(dSt[vt][q], &Qtt[buf][ct * LDC], LDC, &dOts[buf][vt * 16 * LDC], LDC, C, lane);
                     mma_tile<T, true, true>(dSt[vt][q], &Wtt[buf][ct * LDC], LDC, dEt + vt * 16 * LDC, LDC, C, lane);
@@ -313,7 +321,10 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
 // slab buffers are reused for Q and K~ once the walk is over.
 constexpr int PT_ = 512, PW_ = PT_ / 64;     // threads / wavefronts of bwd_post
 
-template <typename T, int K>
+// GV: one state gate per key channel.  The kernel then runs on the folded operands with no
+// scalar gate (log_alpha null); the write rows carry the chunk's decay per channel instead of
+// rho, and dL/d(that decay) is collected per channel.
+template <typename T, int K, bool GV>
 __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
     constexpr int VB = sizeof(T) == 2 ? 64 : 32;        // slab width
@@ -330,6 +341,8 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     __shared__ float red3[4 * C];
     __shared__ float dbeta_s[2 * C];
     __shared__ float sdot[PW_];
+    __shared__ float colss[GV ? PT_ : 1];                // <dS', S> column by column (partials)
+    __shared__ float dgam_s[GV ? K : 1];                 // sum_i (K~/Gamma)_ic (E dS')_ic
     // slab buffers, later Q / K~ / cP and the row-dot partials
     constexpr int SLAB_ELEMS = 3 * C * LDV + 2 * VB * LDC + 2 * VB * LDK;
     constexpr int POST_ELEMS = 2 * C * LDK + C * LDC + (3 * PW_ * C * 4) / (int)sizeof(T);
@@ -510,6 +523,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
         cAs[i * LDC + j] = from_f32<T>(0.f);
         cPs[i * LDC + j] = from_f32<T>(0.f);
     }
+    if (GV) colss[GV ? tid : 0] = ss_part;               // thread tid summed rows of column tid % K
     ss_part = wave_sum(ss_part);
     if (lane == 0) sdot[wave] = ss_part;
     for (int idx = tid; idx < 4 * C; idx += PT_) { red[idx] = 0.f; red2[idx] = 0.f; red3[idx] = 0.f; }
@@ -569,6 +583,8 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     T *dq_g = static_cast<T *>(a.dq) + tok0 * K;
     T *dk_g = static_cast<T *>(a.dk_read) + tok0 * K;
     T *dkt_g = static_cast<T *>(a.dkt) + tok0 * K;
+    const float gcv = (GV && has_ct) ? a.gamC[bhn * K + ct + acc_col(lane)] : 1.f;   // this lane's channel
+    float dgc = 0.f;
     if (has_ct) {
 #pragma unroll
         for (int ib = 0; ib < 4; ++ib) {
@@ -598,9 +614,10 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
                 const float gam = __expf(Gs[i]), rho = __expf(Gs[C - 1] - Gs[i]);
                 const float gq = a.scale * gam * dQg[ib][r];         // gamma . d(gamma Q)
                 const float gk = -Bs[i] * gam * dKg[ib][r];           // gamma . d(gamma K)
-                const float gr = rho * dKr[ib][r];                    // rho . d(rho K~)
+                const float gr = (GV ? gcv : rho) * dKr[ib][r];       // rho . d(rho K~)
                 const float qv = to_f32(Qs[i * LDK + c]), kv = to_f32(Ks[i * LDK + c]),
                             ktv = to_f32(Kts[i * LDK + c]);
+                if (GV) dgc = __builtin_fmaf(ktv, dKr[ib][r], dgc);
                 tq[ib][r] += gq * qv;
                 tk[ib][r] += gk * kv;
                 tr[ib][r] += gr * ktv;
@@ -609,6 +626,11 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
                 dkt_g[(size_t)i * tstride * K + c] = from_f32<T>(at[r] + gr);
             }
         }
+    }
+    if (GV && has_ct) {                 // column sums over the rows: lanes 16 apart share a column
+        dgc += __shfl_xor(dgc, 16, 64);
+        dgc += __shfl_xor(dgc, 32, 64);
+        if (lane < 16) dgam_s[GV ? ct + lane : 0] = dgc;
     }
     // per-row sums across the 16 lanes of a row, then across waves through LDS
     float *pk = pq + PW_ * C, *pr = pk + PW_ * C;
@@ -624,6 +646,12 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
         }
     __syncthreads();
     OSDN_PTICK(6)
+    if (GV && tid < K) {                // dL/d(decay of channel tid over the chunk)
+        float sd = dgam_s[GV ? tid : 0];
+#pragma unroll
+        for (int j = 0; j < PT_ / K; ++j) sd += colss[GV ? tid + j * K : 0];
+        a.dgamC[bhn * K + tid] = sd;
+    }
     if (wave == 0) {
         const int i = lane;
         float t_q = 0.f, t_k = 0.f, t_r = 0.f;
@@ -663,27 +691,118 @@ static int launch_local_t(const ChunkArgs &a, hipStream_t st) {
 int launch_bwd_local(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
     return bf16_io ? launch_local_t<bf16>(a, st) : launch_local_t<float>(a, st);
 }
-template <typename T>
+template <typename T, bool GV>
 static int launch_chain_t(const ChunkArgs &a, hipStream_t st) {
     dim3 grid((a.V / VS) * a.H * (a.seq_chunks ? a.n_seqs : a.B)), block(CT_);
-    if (a.K == 64) hipLaunchKernelGGL((bwd_chain_kernel<T, 64>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((bwd_chain_kernel<T, 128>), grid, block, 0, st, a);
+    if (GV && !a.gamC) return -1;
+    if (a.K == 64) hipLaunchKernelGGL((bwd_chain_kernel<T, 64, GV>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((bwd_chain_kernel<T, 128, GV>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
 int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
-    return bf16_io ? launch_chain_t<bf16>(a, st) : launch_chain_t<float>(a, st);
+    if (a.gate_vec) return bf16_io ? launch_chain_t<bf16, true>(a, st) : launch_chain_t<float, true>(a, st);
+    return bf16_io ? launch_chain_t<bf16, false>(a, st) : launch_chain_t<float, false>(a, st);
 }
-template <typename T>
+template <typename T, bool GV>
 static int launch_post_t(const ChunkArgs &a, hipStream_t st) {
     dim3 grid(a.n1 - a.n0, a.H, a.B), block(PT_);
-    if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128>), grid, block, 0, st, a);
+    if (GV && (!a.gamC || !a.dgamC || a.log_alpha || a.dlog_alpha)) return -1;
+    if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64, GV>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128, GV>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
 int launch_bwd_post(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
-    return bf16_io ? launch_post_t<bf16>(a, st) : launch_post_t<float>(a, st);
+    if (a.gate_vec) return bf16_io ? launch_post_t<bf16, true>(a, st) : launch_post_t<float, true>(a, st);
+    return bf16_io ? launch_post_t<bf16, false>(a, st) : launch_post_t<float, false>(a, st);
+}
+
+// ---------------------------------------------------------------- unfold ----
+// One state gate per key channel: phase 2 worked on Qg = Gamma . Q, Kg = Gamma . K and
+// Kd = K~ / Gamma (Gamma = e^{G}, G the cumulative log-decay of every channel inside the
+// chunk), and on gamma_C = Gamma's last row.  Per chunk this kernel rebuilds G and maps
+//     dq = Gamma . dQg,   dk_read = Gamma . dKg,   dk~ = dKd / Gamma             (in place)
+//     dG = dq . q + dk_read . k - dk~ . k~   (elementwise: G reaches the loss through the three
+//          folded operands only),  dG[last token] += gamma_C . dgamma_C,
+//     dlog_alpha = suffix sum of dG over the tokens of the chunk, channel by channel.
+template <typename T, int K>
+__global__ __launch_bounds__(NT) void unfold_kernel(UnfoldArgs a) {
+    constexpr int GLD = K + 4, VN = 16 / sizeof(T);
+    __shared__ __attribute__((aligned(16))) float Gt[C * GLD];     // G, then dG, then dlog_alpha
+    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
+    const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+    const size_t rs = (size_t)a.H * K;                              // elements between consecutive tokens
+    const float *gp = a.log_alpha + tok0 * K;
+    for (int v = tid; v < C * K / 4; v += NT) {
+        const int i = v / (K / 4), c = (v % (K / 4)) * 4;
+        *reinterpret_cast<f32x4 *>(Gt + i * GLD + c) = *reinterpret_cast<const f32x4 *>(gp + (size_t)i * rs + c);
+    }
+    __syncthreads();
+    if (tid < K) {
+        float G = 0.f;
+#pragma unroll 16
+        for (int i = 0; i < C; ++i) {
+            G += Gt[i * GLD + tid];
+            Gt[i * GLD + tid] = G;
+        }
+    }
+    __syncthreads();
+    const T *qp = static_cast<const T *>(a.q) + tok0 * K, *kp = static_cast<const T *>(a.k) + tok0 * K,
+            *tp = static_cast<const T *>(a.kt) + tok0 * K;
+    T *dqp = static_cast<T *>(a.dq) + tok0 * K, *dkp = static_cast<T *>(a.dk_read) + tok0 * K,
+      *dtp = static_cast<T *>(a.dkt) + tok0 * K;
+    for (int v = tid; v < C * K / VN; v += NT) {
+        const int i = v / (K / VN), c = (v % (K / VN)) * VN;
+        const size_t o = (size_t)i * rs + c;
+        const u32x4 qv = *reinterpret_cast<const u32x4 *>(qp + o), kv = *reinterpret_cast<const u32x4 *>(kp + o),
+                    tv = *reinterpret_cast<const u32x4 *>(tp + o);
+        const u32x4 gq = *reinterpret_cast<const u32x4 *>(dqp + o), gk = *reinterpret_cast<const u32x4 *>(dkp + o),
+                    gt = *reinterpret_cast<const u32x4 *>(dtp + o);
+        float oq[VN], ok[VN], ot[VN];
+#pragma unroll
+        for (int e = 0; e < VN; ++e) {
+            const float G = Gt[i * GLD + c + e];
+            const float gam = __expf(G), inv = __expf(-G);
+            oq[e] = vec_get<T>(gq, e) * gam;
+            ok[e] = vec_get<T>(gk, e) * gam;
+            ot[e] = vec_get<T>(gt, e) * inv;
+            Gt[i * GLD + c + e] = oq[e] * vec_get<T>(qv, e) + ok[e] * vec_get<T>(kv, e) - ot[e] * vec_get<T>(tv, e);
+        }
+        store_vec_t(dqp + o, oq);
+        store_vec_t(dkp + o, ok);
+        store_vec_t(dtp + o, ot);
+    }
+    __syncthreads();
+    if (tid < K) {
+        float acc = a.gamC[bhn * K + tid] * a.dgamC[bhn * K + tid];
+#pragma unroll 16
+        for (int i = C - 1; i >= 0; --i) {
+            acc += Gt[i * GLD + tid];
+            Gt[i * GLD + tid] = acc;
+        }
+    }
+    __syncthreads();
+    float *dg = a.dlog_alpha + tok0 * K;
+    for (int v = tid; v < C * K / 4; v += NT) {
+        const int i = v / (K / 4), c = (v % (K / 4)) * 4;
+        *reinterpret_cast<f32x4 *>(dg + (size_t)i * rs + c) = *reinterpret_cast<const f32x4 *>(Gt + i * GLD + c);
+    }
+}
+
+template <typename T>
+static int launch_unfold_t(const UnfoldArgs &a, hipStream_t st) {
+    dim3 grid(a.n1 - a.n0, a.H, a.B), block(NT);
+    if (a.K == 64) hipLaunchKernelGGL((unfold_kernel<T, 64>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((unfold_kernel<T, 128>), grid, block, 0, st, a);
+    else return -1;
+    return 0;
+}
+int launch_unfold(const UnfoldArgs &a, bool bf16_io, hipStream_t st) {
+    if (!a.log_alpha || !a.q || !a.k || !a.kt || !a.dq || !a.dk_read || !a.dkt || !a.gamC || !a.dgamC || !a.dlog_alpha)
+        return -1;
+    return bf16_io ? launch_unfold_t<bf16>(a, st) : launch_unfold_t<float>(a, st);
 }
 
 }  // namespace osdn

@@ -122,6 +122,7 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
             store_vec_t(qg + (size_t)i * rs + c, qo);
         }
         __syncthreads();
+        store_tile_global(static_cast<T *>(a.Kg) + tok0 * K, tstride * K, X1, LDK, C, K, tid, NT);
         store_tile_global(static_cast<T *>(a.Kd) + tok0 * K, tstride * K, X2, LDK, C, K, tid, NT);
         __syncthreads();            // the scratch space is handed over to A
     }
@@ -564,7 +565,7 @@ __global__ __launch_bounds__(NT) void output_fwd_kernel(ChunkArgs a) {
 template <typename T, bool GV>
 static int launch_prep_t(const ChunkArgs &a, hipStream_t st) {
     dim3 grid(a.n1 - a.n0, a.H, a.B), block(NT);
-    if (GV && (!a.log_alpha || !a.Qg || !a.Kd || !a.gamC)) return -1;
+    if (GV && (!a.log_alpha || !a.Qg || !a.Kg || !a.Kd || !a.gamC)) return -1;
     if (a.K == 64) hipLaunchKernelGGL((chunk_prep_kernel<T, 64, GV>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((chunk_prep_kernel<T, 128, GV>), grid, block, 0, st, a);
     else return -1;

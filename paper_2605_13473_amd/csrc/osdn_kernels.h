@@ -102,8 +102,10 @@ struct ChunkArgs {
     // folds the cumulative channel decays Gamma into the operands and leaves
     int gate_vec;
     void *Qg;                         // [B,T,H,K] io      Gamma . Q
+    void *Kg;                         // [B,T,H,K] io      Gamma . K
     void *Kd;                         // [B,T,H,K] io      K~ / Gamma
     float *gamC;                      // [B,H,N,K] f32     decay of every channel over the whole chunk
+    float *dgamC;                     // [B,H,N,K] f32     backward: dL/d(that decay)
     // backward
     const void *dO;                   // [B,T,H,V] io
     const float *dS_out;              // [B,H,V,K] or null
@@ -134,5 +136,20 @@ int launch_output_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 int launch_bwd_local(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 int launch_bwd_post(const ChunkArgs &a, bool bf16_io, hipStream_t st);
+
+// Backward with one state gate per key channel: phase 2 runs on the folded operands
+// (Gamma . Q, Gamma . K, K~ / Gamma) and leaves the gradients with respect to those; this
+// kernel turns them, in place, into the gradients with respect to q, k (read side) and k~,
+// and collects dL/dlog_alpha.
+struct UnfoldArgs {
+    int B, T, H, K, N;
+    int n0, n1;
+    const float *log_alpha;           // [B,T,H,K]
+    const void *q, *k, *kt;           // [B,T,H,K] io: the unfolded operands
+    void *dq, *dk_read, *dkt;         // [B,T,H,K] io: in: w.r.t. the folded operands; out: w.r.t. q, k, k~
+    const float *gamC, *dgamC;        // [B,H,N,K]
+    float *dlog_alpha;                // [B,T,H,K]
+};
+int launch_unfold(const UnfoldArgs &a, bool bf16_io, hipStream_t st);
 
 }  // namespace osdn

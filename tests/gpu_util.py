@@ -50,7 +50,9 @@ def gpu_forward(x, hp: ob.Hyper, bf16, for_backward=False):
     return o, S, d, ctx, t
 
 
-def oracle_hp(hp: ob.Hyper) -> oracle.Hyper:
+def oracle_hp(hp) -> oracle.Hyper:
+    if isinstance(hp, oracle.Hyper):
+        return hp
     return oracle.Hyper(scale=hp.scale, eta=hp.eta, d_min=hp.d_min, d_max=hp.d_max, eps=hp.eps,
                         beta_aware=hp.beta_aware)
 
@@ -66,6 +68,65 @@ def compare_forward(x, hp, bf16):
     return o, S, d
 
 
+# Outputs that depend on the projection's derivative (the reverse sweep through d).
+D_PATH = ("dk", "dbeta", "dretention", "dd_in")
+TIE_TOL = 3e-7      # about one fp32 ulp of the upper face (five of the lower): closer than that, fp32 cannot place a value
+
+
+def _chain(name, a, b, h):
+    """The part of a gradient that belongs to chain (b, h)."""
+    if name in ("dd_in", "dS_in"):
+        return a[b, h]
+    return a[b, :, h]
+
+
+def check_gradients(g, oracle_bwd, hp, bf16):
+    """Compare every gradient with the oracle.  The mask of the projection is a decision taken
+    on a floating-point value: where the oracle's unprojected value lies within TIE_TOL of a
+    face, fp32 cannot be expected to land on the same side, and both readings are derivatives
+    of a valid nearby input.  So if a d-path output disagrees with the plain oracle, every
+    (batch, head) chain must agree, in all its d-path outputs at once, with one of the
+    oracle's admissible readings (plain; near-ties inside; near-ties outside)."""
+    og = oracle_bwd(oracle_hp(hp))
+    errs, failed = {}, []
+    for name, ref in og.items():
+        if ref is None:
+            assert g[name] is None
+            continue
+        try:
+            errs[name] = check(name, g[name], ref, bf16)
+        except AssertionError:
+            if name not in D_PATH:
+                raise
+            failed.append(name)
+    if not failed:
+        return errs
+    import dataclasses
+    variants = [og] + [oracle_bwd(dataclasses.replace(oracle_hp(hp), tie_tol=TIE_TOL, tie_inside=side))
+                       for side in (True, False)]
+    assert any(not np.array_equal(variants[0][n], v[n]) for v in variants[1:] for n in failed), \
+        f"{failed}: disagree with the oracle and no unprojected value is near a face"
+    got = {n: g[n].detach().float().cpu().numpy().astype(np.float64) for n in D_PATH if og.get(n) is not None}
+    B, H = og["dd_in"].shape[:2]
+    for b in range(B):
+        for h in range(H):
+            ok = False
+            for v in variants:
+                try:
+                    for n in got:
+                        mx = np.abs(v[n]).max()
+                        tol = BF16_ABS * max(1.0, mx) if bf16 else F32_REL * max(mx, 1e-30)
+                        assert np.abs(_chain(n, got[n], b, h) - _chain(n, v[n], b, h)).max() <= tol
+                    ok = True
+                    break
+                except AssertionError:
+                    continue
+            assert ok, f"chain (b={b}, h={h}): d-path gradients match no admissible reading of the box mask"
+    for n in failed:
+        errs[n] = float("nan")
+    return errs
+
+
 def compare_backward(x, hp, bf16, dS_out=None, dd_out=None):
     o, S, d, ctx, t = gpu_forward(x, hp, bf16, for_backward=True)
     tdS = None if dS_out is None else torch.from_numpy(dS_out).cuda()
@@ -73,14 +134,11 @@ def compare_backward(x, hp, bf16, dS_out=None, dd_out=None):
     g = ob.backward(ctx, t["dO"], tdS, tdd)
     torch.cuda.synchronize()
     y = f64(x)
-    og = oracle.bwd(y["q"], y["k"], y["v"], y["beta"], y["dO"], y.get("log_alpha"), y.get("retention"),
-                    y.get("d_in"), y.get("S_in"),
-                    dS_out=None if dS_out is None else dS_out.astype(np.float64),
-                    dd_out=None if dd_out is None else dd_out.astype(np.float64), hp=oracle_hp(hp))
-    errs = {}
-    for name, ref in og.items():
-        if ref is None:
-            assert g[name] is None
-            continue
-        errs[name] = check(name, g[name], ref, bf16)
-    return errs
+
+    def oracle_bwd(ohp):
+        return oracle.bwd(y["q"], y["k"], y["v"], y["beta"], y["dO"], y.get("log_alpha"), y.get("retention"),
+                          y.get("d_in"), y.get("S_in"),
+                          dS_out=None if dS_out is None else dS_out.astype(np.float64),
+                          dd_out=None if dd_out is None else dd_out.astype(np.float64), hp=ohp)
+
+    return check_gradients(g, oracle_bwd, hp, bf16)

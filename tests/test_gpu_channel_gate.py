@@ -1,5 +1,6 @@
-"""GPU parity of the chunkwise forward pass with one state gate per key channel (the chunkwise
-UT form of online-scaled KDA) against the CPU oracle's token-by-token recurrence."""
+"""GPU parity of the chunkwise forward and backward passes with one state gate per key channel
+(the chunkwise UT form of online-scaled KDA) against the CPU oracle's token-by-token recurrence
+and its hand-written reverse mode."""
 import numpy as np
 import pytest
 import torch
@@ -7,7 +8,7 @@ import torch
 import oracle
 from paper_2605_13473_amd import binding as ob
 from paper_2605_13473_amd.inputs import make_stress_inputs
-from tests.gpu_util import check, compare_forward, f64, oracle_hp, to_dev
+from tests.gpu_util import check, compare_backward, compare_forward, f64, oracle_hp, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -96,6 +97,36 @@ def test_prefill_then_decode_steps():
     check("d_out", d, od, False)
 
 
-def test_backward_is_refused():
-    p = ob.make_params(1, 64, 1, 64, 64, False, gate_per_channel=True)
-    assert ob.osdn_workspace_bytes(p, False) > 0 and ob.osdn_workspace_bytes(p, True) == 0
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", [(1, 64, 1, 64, 64), (2, 192, 3, 64, 128), (1, 256, 2, 128, 192), (2, 100, 2, 128, 64)])
+def test_backward(shape, bf16):
+    """Every gradient, dlog_alpha per channel included, with terminal adjoints of S and d."""
+    B, T, H, K, V = shape
+    x = _inputs(B, T, H, K, V, seed=89, bf16=bf16)
+    rng = np.random.default_rng(90)
+    dS = rng.standard_normal((B, H, V, K)).astype(np.float32)
+    dd = rng.standard_normal((B, H, K)).astype(np.float32)
+    errs = compare_backward(x, ob.Hyper(eta=0.5), bf16, dS, dd)
+    assert "dlog_alpha" in errs
+
+
+def test_backward_strong_decay_and_long_sequence():
+    """Cumulative channel decays down to e^-50 inside a chunk, enough chunks for the segment
+    pipeline, per-coordinate retention as well."""
+    B, T, H, K, V = 1, 64 * 44, 1, 64, 64
+    x = _inputs(B, T, H, K, V, seed=91, bf16=False, g_mean=0.0)
+    rng = np.random.default_rng(92)
+    x["retention"] = np.clip(x["retention"][..., None] + 0.03 * rng.standard_normal((B, T, H, K)), 0, 1).astype(np.float32)
+    compare_backward(x, ob.Hyper(eta=0.3), False)
+
+
+def test_backward_packed_sequences():
+    from tests.test_gpu_packed import _gpu_packed, _oracle_per_sequence, _packed_inputs
+    lens, H, K, V, bf16, hp = [70, 1, 129, 64], 2, 64, 64, False, ob.Hyper(eta=0.5)
+    x = _packed_inputs(lens, H, K, V, seed=93, bf16=bf16)
+    rng = np.random.default_rng(94)
+    x["log_alpha"] = (-np.logaddexp(0.0, -1.0 + rng.standard_normal((1, sum(lens), H, K)))).astype(np.float32)
+    got, _ = _gpu_packed(x, lens, hp, bf16, backward=True)
+    ref = _oracle_per_sequence(x, lens, hp, backward=True)
+    for name, r in ref.items():
+        check(name, got[name], r, False)

@@ -61,12 +61,15 @@ def test_argument_errors_before_any_pointer_is_used():
     p = ob.make_params(1, 128, 1, 64, 64, False)
     p.retention_per_channel = 3                            # a flag: 0 or 1
     assert L.osdn_precond_update(ctypes.byref(p), fake, fake, None, None, fake, fake, None, None) == -5
-    p = ob.make_params(1, 128, 1, 64, 64, False, gate_per_channel=True)     # forward only, and the gate is required
+    p = ob.make_params(1, 128, 1, 64, 64, False, gate_per_channel=True)     # then the gate is required
     assert L.osdn_fwd(ctypes.byref(p), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
                       fake, ctypes.c_size_t(1 << 30), None) == -1
-    assert L.osdn_bwd(ctypes.byref(p), *([fake] * 19), fake, ctypes.c_size_t(1 << 30), None) == -2
-    assert ob.osdn_workspace_bytes(p, False) > ob.osdn_workspace_bytes(ob.make_params(1, 128, 1, 64, 64, False), False)
-    assert ob.osdn_workspace_bytes(p, True) == 0
+    args = [fake] * 19
+    args[4] = None
+    assert L.osdn_bwd(ctypes.byref(p), *args, fake, ctypes.c_size_t(1 << 30), None) == -1
+    plain = ob.make_params(1, 128, 1, 64, 64, False)
+    assert ob.osdn_workspace_bytes(p, False) > ob.osdn_workspace_bytes(plain, False)
+    assert ob.osdn_workspace_bytes(p, True) > ob.osdn_workspace_bytes(plain, True)
     p = ob.make_params(1, 128, 1, 64, 64, False)
     assert L.osdn_fwd(ctypes.byref(p), None, fake, fake, fake, None, None, None, None, fake, fake, fake,
                       fake, ctypes.c_size_t(1 << 30), None) == -1

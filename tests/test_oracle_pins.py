@@ -509,6 +509,34 @@ def test_backward_clamp_tie_passes_gradient():
     assert g["dd_in"][0, 0, 0] == 1.0
 
 
+def test_near_tie_readings_of_the_box_mask():
+    """tie_tol > 0 changes the backward only where an unprojected value lies within tie_tol of a
+    face: with none it changes nothing; with one planted (a push that misses the face by 1e-9)
+    the plain rule and the matching reading agree and the opposite reading zeroes exactly that
+    coordinate's gradient."""
+    K = 4
+    k = np.zeros((1, 2, 1, K)); k[0, :, 0, 1] = 1.0             # unit keys on coordinate 1
+    beta = np.full((1, 2, 1), 0.5); q = np.zeros_like(k); v = np.zeros((1, 2, 1, 1)); dO = np.zeros_like(v)
+    d0 = np.array([[[1.0, 1.9, 1.0, 1.0]]])
+    # d_bar of coordinate 1 after token 0: 1.9 + eta*0.5*(1 - 0.5*1.9) = 1.9 + 0.025 eta  -> face 2.0 at eta = 4
+    w = np.ones((1, 1, K))
+    plain = Hyper(eta=4.0 - 4e-8)                               # lands 1e-9 below the face: inside
+    assert 0 < 2.0 - (1.9 + 0.025 * plain.eta) < 2e-9
+    import dataclasses
+    g0 = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=plain)
+    gi = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=dataclasses.replace(plain, tie_tol=1e-6, tie_inside=True))
+    go = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=dataclasses.replace(plain, tie_tol=1e-6, tie_inside=False))
+    for n in g0:
+        if g0[n] is not None:
+            assert np.array_equal(g0[n], gi[n]), n
+    assert g0["dd_in"][0, 0, 1] != 0.0 and go["dd_in"][0, 0, 1] == 0.0
+    assert np.array_equal(np.delete(g0["dd_in"], 1, axis=-1), np.delete(go["dd_in"], 1, axis=-1))
+    far = Hyper(eta=0.05)                                        # nothing near a face: the option is inert
+    a = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=far)
+    b = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=dataclasses.replace(far, tie_tol=1e-6, tie_inside=False))
+    assert all(np.array_equal(a[n], b[n]) for n in a if a[n] is not None)
+
+
 def test_chain_rule_through_key_scaling():
     """Section 4.5: with the phase-1 update frozen (eta = 0, r = 1), dL/dd_in = sum_t k_t . dL/dk~_t
     and dL/dk_t = (read-side part) + d . dL/dk~_t, using the chunk model's dL/dk~."""
