@@ -239,3 +239,47 @@ def test_full_size_configs_sampled_chains(ci):
                 continue
             tok = name not in ("dd_in", "dS_in")
             check(name, pick(g[name], tok), ref, cfg.bf16)
+
+
+def test_hip_graph_capture_and_replay():
+    """Forward + backward captured into a HIP graph on a caller stream (the library's side
+    stream joins the capture through its fork / join events; nothing in it allocates or clears
+    memory with a memset node) and replayed several times with eager calls and synchronisations
+    in between: every replay reproduces the eager results bit for bit."""
+    x = make_stress_inputs(2, 1024, 2, 64, 64, seed=41, bf16=True, retention=0.97)
+    t = to_dev(x, True)
+    hp = ob.Hyper(eta=0.3)
+    B, T, H, K = t["k"].shape
+    V = t["v"].shape[-1]
+    p = ob.make_params(B, T, H, K, V, True, hp)
+    ws = ob.alloc_workspace(p, True)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    out = {"o": torch.empty_like(t["v"]), "S": torch.empty(B, H, V, K, **f32), "d": torch.empty(B, H, K, **f32),
+           "dq": torch.empty_like(t["q"]), "dk": torch.empty_like(t["k"]), "dv": torch.empty_like(t["v"]),
+           "dbeta": torch.empty_like(t["beta"]), "dg": torch.empty_like(t["beta"]), "dr": torch.empty_like(t["beta"]),
+           "dd": torch.empty(B, H, K, **f32), "dS": torch.empty(B, H, V, K, **f32)}
+
+    def step():
+        ob.osdn_fwd(p, t["q"], t["k"], t["v"], t["beta"], t["log_alpha"], t["retention"], t["d_in"], t["S_in"],
+                    out["o"], out["S"], out["d"], ws)
+        ob.osdn_bwd(p, t["q"], t["k"], t["v"], t["beta"], t["log_alpha"], t["retention"], t["d_in"], t["S_in"],
+                    t["dO"], None, None, out["dq"], out["dk"], out["dv"], out["dbeta"], out["dg"], out["dr"],
+                    out["dd"], out["dS"], ws)
+
+    step()                                  # also creates the side stream and its events, outside the capture
+    torch.cuda.synchronize()
+    ref = {n: a.clone() for n, a in out.items()}
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for i in range(3):
+        for a in out.values():
+            a.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for n, a in out.items():
+            assert torch.equal(a, ref[n]), (n, i)
+        step()                              # eager work between the replays
+        torch.cuda.synchronize()
+        for n, a in out.items():
+            assert torch.equal(a, ref[n]), (n, i, "eager")
