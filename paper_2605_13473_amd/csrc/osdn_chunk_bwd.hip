@@ -16,6 +16,12 @@
 //             dK~ = cA^T K + cP^T Q + rho . (E dS') ;
 //             dbeta_i = <dR_i, R0_i> + sum_j dA_ij Gamma_ij <k_i,k~_j> ;
 //             dG from every place G enters; dlog_alpha = suffix sums of dG inside the chunk.
+//
+// With one state gate per key channel (GV) the same kernels run, ungated, on the operands in
+// which the forward pass folded the channel decays (Gamma . Q, Gamma . K, K~ / Gamma); the
+// state adjoint decays per channel between chunks, the write rows carry the chunk's decay per
+// channel in place of rho, and the unfold kernel at the end of this file maps the gradients
+// back to q, k, k~ and log alpha.
 #include "osdn_kernels.h"
 
 namespace osdn {

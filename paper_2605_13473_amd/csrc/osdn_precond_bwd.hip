@@ -13,7 +13,8 @@
 //                  boundary and the 64 sigmas of every chunk, nothing else
 //   precond_post   one workgroup per (chain, chunk), all chunks in parallel, one thread per
 //                  coordinate: replays d, re-runs the adjoint recurrence of its chunk from the
-//                  stored boundary value and sigmas, and writes dk, dbeta, dretention
+//                  stored boundary value, sigmas and masks, and writes dk, dbeta, dretention
+// The retention gate is absent, one value per (token, head), or one per coordinate (RET).
 #include "osdn_precond.h"
 
 namespace osdn {
