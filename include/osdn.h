@@ -38,7 +38,9 @@
  *     mutex while they enqueue.  OSDN_SEGMENTS=1 in the environment keeps everything on `stream`.
  *   - retention values are assumed >= 0 (they are sigmoid gates in the paper).  Wherever a
  *     signature says retention / dretention [B,T,H], params->retention_per_channel = 1 makes
- *     it [B,T,H,K]: one value per coordinate.
+ *     it [B,T,H,K]: one value per coordinate.  Likewise params->gate_per_channel = 1 makes
+ *     log_alpha / dlog_alpha [B,T,H,K]: one state gate per key channel, S <- S Diag(alpha_t)
+ *     (online-scaled KDA, appendix section on Kimi Delta Attention with online scaling).
  *   - Supported shapes: chunk == 64; any T >= 1 (osdn_fwd/osdn_bwd pad a ragged last chunk
  *     inside the workspace with tokens that change nothing; osdn_precond_update needs
  *     T % 64 == 0 only when d_ckpt is asked for; 1 <= T <= 64 for osdn_step); K in {64, 128};
