@@ -493,9 +493,11 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
 }
 
 // ------------------------------------------------------------ output_fwd ----
+constexpr int OT_ = 512;        // threads of an output_fwd workgroup: 8 wavefronts, (row block, half of the value tiles)
 template <typename T, int K>
-__global__ __launch_bounds__(NT) void output_fwd_kernel(ChunkArgs a) {
+__global__ __launch_bounds__(OT_) void output_fwd_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
+    constexpr int NW = OT_ / 64;
     __shared__ __attribute__((aligned(16))) T Qs[C * LDK];
     __shared__ __attribute__((aligned(16))) T Kts[C * LDK];     // K~, later the output staging tile
     __shared__ __attribute__((aligned(16))) T Ss[C * LDK];      // 64 rows of the chunk-start state
@@ -513,16 +515,16 @@ __global__ __launch_bounds__(NT) void output_fwd_kernel(ChunkArgs a) {
         const float g = a.log_alpha ? a.log_alpha[tok0 + (size_t)lane * tstride] : 0.f;
         Gs[lane] = wave_cumsum(g, lane);
     }
-    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, NT);
-    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, NT);
+    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, OT_);
+    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, OT_);
     // the slabs of S and E^T travel through registers, one slab ahead of the products
-    TileRegs<T, C, K, NT> r_S;
-    TileRegs<T, C, C, NT> r_E;
+    TileRegs<T, C, K, OT_> r_S;
+    TileRegs<T, C, C, OT_> r_E;
     r_S.fetch(static_cast<const T *>(a.S_ckpt) + bhn * a.V * K, (size_t)K, tid);
     r_E.fetch(static_cast<const T *>(a.Et) + bhn * a.V * C, (size_t)C, tid);
     __syncthreads();
     // P^T tiles (rows j, columns i) so that the store lands k-contiguous in Ps[i][j]
-    for (int idx = wave; idx < 16; idx += 4) {
+    for (int idx = wave; idx < 16; idx += NW) {
         const int ib = idx >> 2, jb = idx & 3;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         if (jb <= ib) {
@@ -545,19 +547,21 @@ __global__ __launch_bounds__(NT) void output_fwd_kernel(ChunkArgs a) {
             r_E.fetch(static_cast<const T *>(a.Et) + (bhn * a.V + v0 + C) * C, (size_t)C, tid);
         }
         __syncthreads();
-        const int kdim = min(C, ((wave + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
+        const int rb = wave & 3;                    // row block of this wavefront; the other bit: which value tiles
+        const int kdim = min(C, ((rb + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
 #pragma unroll
-        for (int vt = 0; vt < 4; ++vt) {
+        for (int vq = 0; vq < 4 / (NW / 4); ++vq) {
+            const int vt = (wave >> 2) * (4 / (NW / 4)) + vq;
             f32x4 a1 = {0.f, 0.f, 0.f, 0.f}, a2 = {0.f, 0.f, 0.f, 0.f};
-            mma_tile<T, true, true>(a1, Qs + wave * 16 * LDK, LDK, Ss + vt * 16 * LDK, LDK, K, lane);
-            mma_tile<T, true, true>(a2, Ps + wave * 16 * LDC, LDC, Ets + vt * 16 * LDC, LDC, kdim, lane);
+            mma_tile<T, true, true>(a1, Qs + rb * 16 * LDK, LDK, Ss + vt * 16 * LDK, LDK, K, lane);
+            mma_tile<T, true, true>(a2, Ps + rb * 16 * LDC, LDC, Ets + vt * 16 * LDC, LDC, kdim, lane);
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                a1[r] = a.scale * (__expf(Gs[wave * 16 + acc_row(lane, r)]) * a1[r] + a2[r]);
-            store_tile(Os + wave * 16 * LDC + vt * 16, LDC, a1, lane);
+                a1[r] = a.scale * (__expf(Gs[rb * 16 + acc_row(lane, r)]) * a1[r] + a2[r]);
+            store_tile(Os + rb * 16 * LDC + vt * 16, LDC, a1, lane);
         }
         __syncthreads();
-        store_tile_global(static_cast<T *>(a.o) + tok0 * a.V + v0, tstride * a.V, Os, LDC, C, C, tid, NT);
+        store_tile_global(static_cast<T *>(a.o) + tok0 * a.V + v0, tstride * a.V, Os, LDC, C, C, tid, OT_);
     }
 }
 
@@ -590,7 +594,7 @@ int launch_state_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T>
 static int launch_output_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.n1 - a.n0, a.H, a.B), block(NT);
+    dim3 grid(a.n1 - a.n0, a.H, a.B), block(OT_);
     if (a.K == 64) hipLaunchKernelGGL((output_fwd_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((output_fwd_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;
