@@ -40,10 +40,11 @@ __device__ __forceinline__ float row16_sum(float x) {
 // ------------------------------------------------------------- bwd_local ----
 // dEl = scale P^T dO, stored transposed; also leaves (scale gamma . Q)^T and dO^T in the layout
 // the chain kernel's MFMA operands want.
+constexpr int BL_ = 512;        // threads of a bwd_local workgroup: 8 wavefronts, (16 rows or columns, half of the tiles)
 template <typename T, int K>
-__global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
+__global__ __launch_bounds__(BL_) void bwd_local_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
-    constexpr int NKT = K / 64;
+    constexpr int NW = BL_ / 64;
     __shared__ __attribute__((aligned(16))) T Qs[C * LDK];
     constexpr int KTS_ELEMS = C * LDK > K * LDC ? C * LDK : K * LDC;
     __shared__ __attribute__((aligned(16))) T Kts[KTS_ELEMS];   // K~, later the (scale gamma Q)^T staging
@@ -63,12 +64,12 @@ __global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
         const float g = a.log_alpha ? a.log_alpha[tok0 + (size_t)lane * tstride] : 0.f;
         Gs[lane] = wave_cumsum(g, lane);
     }
-    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, NT);
-    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, NT);
-    TileRegs<T, C, C, NT> r_dO;          // the slabs of dO travel through registers, one slab ahead
+    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, BL_);
+    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, BL_);
+    TileRegs<T, C, C, BL_> r_dO;          // the slabs of dO travel through registers, one slab ahead
     r_dO.fetch(static_cast<const T *>(a.dO) + tok0 * a.V, tstride * a.V, tid);
     __syncthreads();
-    for (int idx = wave; idx < 16; idx += 4) {
+    for (int idx = wave; idx < 16; idx += NW) {
         const int ib = idx >> 2, jb = idx & 3;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         if (jb <= ib) {
@@ -83,42 +84,41 @@ __global__ __launch_bounds__(NT) void bwd_local_kernel(ChunkArgs a) {
     }
     __syncthreads();                    // K~ is no longer needed: its buffer takes (scale gamma Q)^T
     T *Qtt = Kts;
+    for (int t = wave; t < (K / 16) * 4; t += NW) {       // 16 features x 16 tokens at a time
+        const int nb = t >> 2, ib = t & 3;
+        f32x4 acc = pick16<T>(Qs + ib * 16 * LDK, LDK, nb * 16, lane);
 #pragma unroll
-    for (int qn = 0; qn < NKT; ++qn) {
-        const int nb = wave * NKT + qn;
-#pragma unroll
-        for (int ib = 0; ib < 4; ++ib) {
-            f32x4 acc = pick16<T>(Qs + ib * 16 * LDK, LDK, nb * 16, lane);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[r] *= a.scale * __expf(Gs[ib * 16 + acc_row(lane, r)]);
-            store_tile_t(Qtt + nb * 16 * LDC + ib * 16, LDC, acc, lane);
-        }
+        for (int r = 0; r < 4; ++r) acc[r] *= a.scale * __expf(Gs[ib * 16 + acc_row(lane, r)]);
+        store_tile_t(Qtt + nb * 16 * LDC + ib * 16, LDC, acc, lane);
     }
     __syncthreads();
-    store_tile_global(static_cast<T *>(a.Qt) + bhn * K * C, (size_t)C, Qtt, LDC, K, C, tid, NT);
-    const int k0 = (wave * 16) / Mfma<T>::KSTEP * Mfma<T>::KSTEP;   // P^T rows 16*wave.. are zero left of here
+    store_tile_global(static_cast<T *>(a.Qt) + bhn * K * C, (size_t)C, Qtt, LDC, K, C, tid, BL_);
+    const int wb = wave & 3, wh = wave >> 2;    // 16 rows / columns of this wavefront, and which half of the tiles
+    const int k0 = (wb * 16) / Mfma<T>::KSTEP * Mfma<T>::KSTEP;     // P^T rows 16*wb.. are zero left of here
     for (int v0 = 0; v0 < a.V; v0 += C) {
         __syncthreads();
         r_dO.put(dOs, LDC, tid);
         if (v0 + C < a.V) r_dO.fetch(static_cast<const T *>(a.dO) + tok0 * a.V + v0 + C, tstride * a.V, tid);
         __syncthreads();
-        // dO^T for this slab: wave w transposes the 16 columns 16*w ..
+        // dO^T for this slab: a wavefront transposes 16 columns (wb) of two row blocks (wh)
 #pragma unroll
-        for (int ib = 0; ib < 4; ++ib) {
-            const f32x4 acc = pick16<T>(dOs + ib * 16 * LDC, LDC, wave * 16, lane);
-            store_tile_t(dOt + wave * 16 * LDC + ib * 16, LDC, acc, lane);
+        for (int iq = 0; iq < 2; ++iq) {
+            const int ib = wh * 2 + iq;
+            const f32x4 acc = pick16<T>(dOs + ib * 16 * LDC, LDC, wb * 16, lane);
+            store_tile_t(dOt + wb * 16 * LDC + ib * 16, LDC, acc, lane);
         }
         __syncthreads();
-        store_tile_global(static_cast<T *>(a.dOt) + (bhn * a.V + v0) * C, (size_t)C, dOt, LDC, C, C, tid, NT);
-        // dEl rows j = 16*wave .. : sum_i P^T[j][i] dO[i][v], stored transposed
+        store_tile_global(static_cast<T *>(a.dOt) + (bhn * a.V + v0) * C, (size_t)C, dOt, LDC, C, C, tid, BL_);
+        // dEl rows j = 16*wb .. : sum_i P^T[j][i] dO[i][v], stored transposed
 #pragma unroll
-        for (int vt = 0; vt < 4; ++vt) {
+        for (int vq = 0; vq < 2; ++vq) {
+            const int vt = wh * 2 + vq;
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            mma_tile<T, true, true>(acc, PT + wave * 16 * LDC + k0, LDC, dOt + vt * 16 * LDC + k0, LDC, C - k0, lane);
-            store_tile_t(Os + vt * 16 * LDC + wave * 16, LDC, acc, lane);
+            mma_tile<T, true, true>(acc, PT + wb * 16 * LDC + k0, LDC, dOt + vt * 16 * LDC + k0, LDC, C - k0, lane);
+            store_tile_t(Os + vt * 16 * LDC + wb * 16, LDC, acc, lane);
         }
         __syncthreads();
-        store_tile_global(static_cast<T *>(a.dElt) + (bhn * a.V + v0) * C, (size_t)C, Os, LDC, C, C, tid, NT);
+        store_tile_global(static_cast<T *>(a.dElt) + (bhn * a.V + v0) * C, (size_t)C, Os, LDC, C, C, tid, BL_);
     }
 }
 
@@ -688,7 +688,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
 // -------------------------------------------------------------- launchers ----
 template <typename T>
 static int launch_local_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.n1 - a.n0, a.H, a.B), block(NT);
+    dim3 grid(a.n1 - a.n0, a.H, a.B), block(BL_);
     if (a.K == 64) hipLaunchKernelGGL((bwd_local_kernel<T, 64>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((bwd_local_kernel<T, 128>), grid, block, 0, st, a);
     else return -1;
