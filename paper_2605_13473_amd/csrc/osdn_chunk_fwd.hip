@@ -28,10 +28,11 @@ namespace osdn {
 // which the kernel runs as with no gate at all; it also leaves Gamma . Q, K~ / Gamma and the
 // chunk's total decay per channel for the state and output kernels.  1 / Gamma grows like
 // e^{|G|}: the cumulative log-decay of a channel inside a chunk has to stay above about -80.
+constexpr int CP_ = 512;        // threads of a chunk_prep workgroup (8 wavefronts)
 template <typename T, int K, bool GV>
-__global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
+__global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDF = C + 1;
-    constexpr int NKT = K / 64;                                 // column tiles of a [64 x K] result per wave
+    constexpr int NW = CP_ / 64;
     __shared__ __attribute__((aligned(16))) T X1[C * LDK];      // K, then V slabs
     __shared__ __attribute__((aligned(16))) T X2[C * LDK];      // K~, then W staging
     __shared__ __attribute__((aligned(16))) T Tu[C * LDC];      // T diag(beta)
@@ -68,11 +69,11 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
         Gs[lane] = wave_cumsum(g, lane);
         Bs[lane] = a.beta[th];
     }
-    load_tile(X1, LDK, static_cast<const T *>(a.k) + tok0 * K, tstride * K, C, K, tid, NT);
-    load_tile(X2, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, NT);
+    load_tile(X1, LDK, static_cast<const T *>(a.k) + tok0 * K, tstride * K, C, K, tid, CP_);
+    load_tile(X2, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, CP_);
     // the first slab of V travels through registers while the chunk's T is being built
     const T *vg = static_cast<const T *>(a.v) + tok0 * a.V;
-    TileRegs<T, C, C, NT> r_V;
+    TileRegs<T, C, C, CP_> r_V;
     r_V.fetch(vg, tstride * a.V, tid);
     __syncthreads();
     if (GV) {
@@ -85,7 +86,7 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
         float *Gt = scratch;
         const size_t rs = tstride * K;
         const float *gp = a.log_alpha + tok0 * K;
-        for (int v = tid; v < C * K / 4; v += NT) {
+        for (int v = tid; v < C * K / 4; v += CP_) {
             const int i = v / (K / 4), c = (v % (K / 4)) * 4;
             *reinterpret_cast<f32x4 *>(Gt + i * GLD + c) = *reinterpret_cast<const f32x4 *>(gp + (size_t)i * rs + c);
         }
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
         __syncthreads();
         const T *qp = static_cast<const T *>(a.q) + tok0 * K;
         T *qg = static_cast<T *>(a.Qg) + tok0 * K;
-        for (int v = tid; v < C * K / VN; v += NT) {
+        for (int v = tid; v < C * K / VN; v += CP_) {
             const int i = v / (K / VN), c = (v % (K / VN)) * VN;
             const u32x4 kv = *reinterpret_cast<const u32x4 *>(X1 + i * LDK + c);
             const u32x4 tv = *reinterpret_cast<const u32x4 *>(X2 + i * LDK + c);
@@ -122,14 +123,14 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
             store_vec_t(qg + (size_t)i * rs + c, qo);
         }
         __syncthreads();
-        store_tile_global(static_cast<T *>(a.Kg) + tok0 * K, tstride * K, X1, LDK, C, K, tid, NT);
-        store_tile_global(static_cast<T *>(a.Kd) + tok0 * K, tstride * K, X2, LDK, C, K, tid, NT);
+        store_tile_global(static_cast<T *>(a.Kg) + tok0 * K, tstride * K, X1, LDK, C, K, tid, CP_);
+        store_tile_global(static_cast<T *>(a.Kd) + tok0 * K, tstride * K, X2, LDK, C, K, tid, CP_);
         __syncthreads();            // the scratch space is handed over to A
     }
     OSDN_CTICK(0)
 
     // ---- A = tril(beta_i Gamma_ij <k_i, k~_j>, -1): the ten lower 16x16 tiles ----
-    for (int idx = wave; idx < 10; idx += 4) {
+    for (int idx = wave; idx < 10; idx += NW) {
         const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
         const int jb = idx - (ib * (ib + 1)) / 2;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -143,11 +144,9 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     // ---- (rho . K~)^T: pick 16x16 blocks of K~, scale rows by rho_j, store transposed ----
     {
         const float GC = Gs[C - 1];
-#pragma unroll
-        for (int qn = 0; qn < NKT; ++qn) {
-            const int nb = wave * NKT + qn;                     // 16 features of K~
-#pragma unroll
-            for (int jb = 0; jb < 4; ++jb) {
+        for (int t = wave; t < (K / 16) * 4; t += NW) {
+            const int nb = t >> 2, jb = t & 3;                  // 16 features of K~, 16 tokens
+            {
                 f32x4 acc = pick16<T>(X2 + jb * 16 * LDK, LDK, nb * 16, lane);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[r] *= __expf(GC - Gs[jb * 16 + acc_row(lane, r)]);
@@ -162,13 +161,13 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     }
     __syncthreads();
     OSDN_CTICK(1)
-    store_tile_global(static_cast<T *>(a.Ktr) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, NT);
+    store_tile_global(static_cast<T *>(a.Ktr) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, CP_);
     __syncthreads();                // the staging tile is free again: (I + A)^-1 is built in its place
 
     // ---- T = (I + A)^-1, 16x16 blocks.  Diagonal blocks: forward substitution, one
     //      column per lane.  Block (i,j), i > j: T_ij = -T_ii sum_{m=j}^{i-1} A_im T_mj,
     //      both products on the fp32 MFMA, one wavefront per block. ----
-    if (lane < 16) {
+    if (wave < 4 && lane < 16) {
         const int o = wave * 16;
         float x[16];
 #pragma unroll
@@ -204,7 +203,7 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     {
         constexpr int VN = 16 / sizeof(T);
         T *tg = static_cast<T *>(a.Tm) + bhn * C * C;
-        for (int v = tid; v < C * C / VN; v += NT) {
+        for (int v = tid; v < C * C / VN; v += CP_) {
             const int i = v / (C / VN), j0 = (v % (C / VN)) * VN;
             float plain[VN];
 #pragma unroll
@@ -224,11 +223,9 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
 
     // ---- W = (T diag(beta gamma)) K, and -W^T ----
     {
-#pragma unroll
-        for (int qn = 0; qn < NKT; ++qn) {
-            const int nb = wave * NKT + qn;
-#pragma unroll
-            for (int ib = 0; ib < 4; ++ib) {
+        for (int t = wave; t < (K / 16) * 4; t += NW) {
+            const int nb = t >> 2, ib = t & 3;
+            {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
                 const int kdim = min(C, ((ib + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
                 mma_tile<T, true, false>(acc, Tw + ib * 16 * LDC, LDC, X1 + nb * 16, LDK, kdim, lane);
@@ -241,8 +238,8 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
     }
     __syncthreads();
     OSDN_CTICK(4)
-    store_tile_global(static_cast<T *>(a.W) + bhn * C * K, K, X2, LDK, C, K, tid, NT);
-    store_tile_global(static_cast<T *>(a.Wt) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, NT);
+    store_tile_global(static_cast<T *>(a.W) + bhn * C * K, K, X2, LDK, C, K, tid, CP_);
+    store_tile_global(static_cast<T *>(a.Wt) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, CP_);
     OSDN_CTICK(5)
 
     // ---- U^T = ((T diag(beta)) V)^T, 64 columns of V at a time ----
@@ -252,14 +249,15 @@ __global__ __launch_bounds__(NT) void chunk_prep_kernel(ChunkArgs a) {
         if (v0 + C < a.V) r_V.fetch(vg + v0 + C, tstride * a.V, tid);
         __syncthreads();
 #pragma unroll
-        for (int ib = 0; ib < 4; ++ib) {
+        for (int iq = 0; iq < 2; ++iq) {
+            const int ib = (wave >> 2) * 2 + iq, wb = wave & 3;        // 16 columns of V (wb), two row blocks
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
             const int kdim = min(C, ((ib + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
-            mma_tile<T, true, false>(acc, Tu + ib * 16 * LDC, LDC, X1 + wave * 16, LDC, kdim, lane);
-            store_tile_t(stage + wave * 16 * LDC + ib * 16, LDC, acc, lane);
+            mma_tile<T, true, false>(acc, Tu + ib * 16 * LDC, LDC, X1 + wb * 16, LDC, kdim, lane);
+            store_tile_t(stage + wb * 16 * LDC + ib * 16, LDC, acc, lane);
         }
         __syncthreads();
-        store_tile_global(static_cast<T *>(a.Ut) + (bhn * a.V + v0) * C, (size_t)C, stage, LDC, C, C, tid, NT);
+        store_tile_global(static_cast<T *>(a.Ut) + (bhn * a.V + v0) * C, (size_t)C, stage, LDC, C, C, tid, CP_);
     }
 #ifdef OSDN_DIAG
     OSDN_CTICK(6)
@@ -568,7 +566,7 @@ __global__ __launch_bounds__(OT_) void output_fwd_kernel(ChunkArgs a) {
 // -------------------------------------------------------------- launchers ----
 template <typename T, bool GV>
 static int launch_prep_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.n1 - a.n0, a.H, a.B), block(NT);
+    dim3 grid(a.n1 - a.n0, a.H, a.B), block(CP_);
     if (GV && (!a.log_alpha || !a.Qg || !a.Kg || !a.Kd || !a.gamC)) return -1;
     if (a.K == 64) hipLaunchKernelGGL((chunk_prep_kernel<T, 64, GV>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((chunk_prep_kernel<T, 128, GV>), grid, block, 0, st, a);
