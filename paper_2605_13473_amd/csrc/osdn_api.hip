@@ -38,7 +38,7 @@ template <typename F> int timed(int id, hipStream_t st, F &&launch) {
 struct Layout {
     size_t Qg, Kg, Kd, gamC, dgamC;                                      // per-channel state gate
     size_t tables;                                                       // packed sequences: the index tables
-    size_t kt, d_ckpt, tok_scalars, Tm, W, Wt, Ktr, Ut, Et, S_ckpt;   // forward
+    size_t kt, d_ckpt, tok_scalars, Tm, Wt, Ktr, Ut, Et, S_ckpt;   // forward
     size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;   // backward only
     // padded copies of the caller's tensors, only when T is not a multiple of the chunk length
     size_t p_q, p_k, p_v, p_beta, p_g, p_r, p_o;                        // forward
@@ -127,7 +127,6 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     L.d_ckpt = take(B * H * N * K * 4);
     L.tok_scalars = take(B * T * H * 4 * 4);
     L.Tm = take(B * H * N * C * C * es);
-    L.W = take(B * T * H * K * es);
     L.Wt = take(B * T * H * K * es);
     L.Ktr = take(B * T * H * K * es);
     L.Ut = take(B * T * H * V * es);
@@ -183,7 +182,7 @@ ChunkArgs chunk_args(const osdn_params *p, const Layout &L, char *ws) {      // 
     ChunkArgs c{};
     c.B = p->B; c.T = p->T; c.H = p->H; c.K = p->K; c.V = p->V; c.N = p->T / C;
     c.scale = p->scale;
-    c.kt = ws + L.kt; c.Tm = ws + L.Tm; c.W = ws + L.W; c.Wt = ws + L.Wt; c.Ktr = ws + L.Ktr;
+    c.kt = ws + L.kt; c.Tm = ws + L.Tm; c.Wt = ws + L.Wt; c.Ktr = ws + L.Ktr;
     c.Ut = ws + L.Ut; c.Et = ws + L.Et;
     c.S_ckpt = ws + L.S_ckpt;
     return c;

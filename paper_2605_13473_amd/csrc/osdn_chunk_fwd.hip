@@ -15,7 +15,7 @@
 namespace osdn {
 
 // ------------------------------------------------------------ chunk_prep ----
-// Besides T, W it leaves the tiles the chain kernels consume in exactly the layout their MFMA
+// Besides T it leaves the tiles the chain kernels consume in exactly the layout their MFMA
 // operands want, so that those kernels only copy: -W^T, (rho . K~)^T and U^T (transposes come
 // for free from the accumulator layout, or from a 0/1 selector product for K~).
 // The row scalings of the right-hand sides move into T: W = (T diag(beta gamma)) K and
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     __syncthreads();                // Ti is dead from here on: its space is the staging tile again
     OSDN_CTICK(3)
 
-    // ---- W = (T diag(beta gamma)) K, and -W^T ----
+    // ---- -W^T, W = (T diag(beta gamma)) K (the chain kernels fetch it with transpose reads) ----
     {
         for (int t = wave; t < (K / 16) * 4; t += NW) {
             const int nb = t >> 2, ib = t & 3;
@@ -229,7 +229,6 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
                 const int kdim = min(C, ((ib + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
                 mma_tile<T, true, false>(acc, Tw + ib * 16 * LDC, LDC, X1 + nb * 16, LDK, kdim, lane);
-                store_tile(X2 + ib * 16 * LDK + nb * 16, LDK, acc, lane);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[r] = -acc[r];
                 store_tile_t(stage + nb * 16 * LDC + ib * 16, LDC, acc, lane);
@@ -238,7 +237,6 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     }
     __syncthreads();
     OSDN_CTICK(4)
-    store_tile_global(static_cast<T *>(a.W) + bhn * C * K, K, X2, LDK, C, K, tid, CP_);
     store_tile_global(static_cast<T *>(a.Wt) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, CP_);
     OSDN_CTICK(5)
 
@@ -291,7 +289,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     constexpr int NWV = C * K / VN / LTN;       // 16-byte vectors per loader thread, [64 x K] tile
     constexpr int NUV = VS * C / VN / LTN;
     static_assert(VS * C / VN % LTN == 0 && C * K / VN % LTN == 0, "tiles must split evenly over the loaders");
-    __shared__ __attribute__((aligned(16))) T Ws[NB][C * LDK];
+    __shared__ __attribute__((aligned(16))) T Wts[NB][K * LDC];      // -W^T  [kf][i], as chunk_prep left it
     __shared__ __attribute__((aligned(16))) T Ktr[NB][K * LDC];
     __shared__ __attribute__((aligned(16))) T Uts[NB][VS * LDC];
     __shared__ __attribute__((aligned(16))) T Sb[VS * LDK];     // S in the I/O type
@@ -336,7 +334,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
 #define OSDN_SF_LOAD(n_)                                                                         \
     {                                                                                            \
         const size_t bhn_ = bth * a.N + (n_);                                                    \
-        const T *wg = static_cast<const T *>(a.W) + bhn_ * C * K;                                \
+        const T *wg = static_cast<const T *>(a.Wt) + bhn_ * K * C;                               \
         const T *kg = static_cast<const T *>(a.Ktr) + bhn_ * K * C;                              \
         const T *ug = static_cast<const T *>(a.Ut) + (bhn_ * a.V + vs) * C;                      \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
@@ -355,9 +353,8 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     {                                                                                            \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
             const int i = lti + m * LTN;                                                          \
-            { const int r = i / (K / VN), c = (i % (K / VN)) * VN;                               \
-              *reinterpret_cast<u32x4 *>(&Ws[buf_][r * LDK + c]) = wreg[m]; }                    \
             { const int r = i / (C / VN), c = (i % (C / VN)) * VN;                               \
+              *reinterpret_cast<u32x4 *>(&Wts[buf_][r * LDC + c]) = wreg[m];                     \
               *reinterpret_cast<u32x4 *>(&Ktr[buf_][r * LDC + c]) = kreg[m]; }                   \
         }                                                                                        \
         _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
@@ -434,10 +431,10 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-                mma_tile<T, true, true>(acc, &Ws[buf][wave * 16 * LDK], LDK, Sb + vt * 16 * LDK, LDK, K, lane);
+                mma_tile<T, false, true>(acc, &Wts[buf][wave * 16], LDC, Sb + vt * 16 * LDK, LDK, K, lane);
                 const T *up = &Uts[buf][(vt * 16 + acc_col(lane)) * LDC + wave * 16 + acc_row(lane, 0)];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[r] = to_f32(up[r]) - acc[r];
+                for (int r = 0; r < 4; ++r) acc[r] += to_f32(up[r]);         // U + (-W) S^T
                 store_tile_t(Et + vt * 16 * LDC + wave * 16, LDC, acc, lane);
             }
         }

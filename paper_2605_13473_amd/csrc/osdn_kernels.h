@@ -92,7 +92,6 @@ struct ChunkArgs {
     // workspace (forward)
     void *kt;                         // [B,T,H,K] io      k~
     void *Tm;                         // [B,H,N,64,64] io  (I + A)^-1
-    void *W;                          // [B,H,N,64,K] io
     void *Wt;                         // [B,H,N,K,64] io   -W^T
     void *Ktr;                        // [B,H,N,K,64] io   (rho . K~)^T
     void *Ut;                         // [B,H,N,V,64] io   U^T
