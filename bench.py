@@ -57,9 +57,9 @@ def kernel_models(cfg, es):
     m["precond_mask"] = ("hbm", th * (K * es + g) + nch * K * 8)
     m["precond_chain"] = ("hbm", th * (2 * K * es + 2 * g) + nch * K * (8 + 4))
     m["precond_post"] = ("hbm", th * (4 * K * es + 6 * g) + nch * K * 8)
-    # chunk_prep: read k, k~, v, beta, g ; write T, W, -W^T, (rho k~)^T, U^T
-    m["chunk_prep"] = ("hbm", th * (5 * K * es + 2 * V * es + C * es + 2 * g))
-    # state_fwd: read W, (rho k~)^T, U^T ; write E^T, S checkpoints ; 2 KV-class GEMMs
+    # chunk_prep: read k, k~, v, beta, g ; write T, -W^T, (rho k~)^T, U^T
+    m["chunk_prep"] = ("hbm", th * (4 * K * es + 2 * V * es + C * es + 2 * g))
+    # state_fwd: read -W^T, (rho k~)^T, U^T ; write E^T, S checkpoints ; 2 KV-class GEMMs
     m["state_fwd"] = ("hbm", th * (2 * K * es + 2 * V * es + g) + nch * V * K * es)
     # output_fwd: read q, k~, S ckpt, E^T ; write o
     m["output_fwd"] = ("hbm", th * (2 * K * es + 2 * V * es + g) + nch * V * K * es)
