@@ -325,18 +325,26 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
 // One workgroup of 8 wavefronts per chunk and head (two per SIMD, so that LDS and MFMA
 // latencies of one overlap with the other's issue).  V is walked in slabs of VB columns; the
 // slab buffers are reused for Q and K~ once the walk is over.
-constexpr int PT_ = 512, PW_ = PT_ / 64;     // threads / wavefronts of bwd_post
+// PW_ wavefronts per workgroup (a parameter of the work split below; 8 is what is launched).
 
 // GV: one state gate per key channel.  The kernel then runs on the folded operands with no
 // scalar gate (log_alpha null); the write rows carry the chunk's decay per channel instead of
 // rho, and dL/d(that decay) is collected per channel.
-template <typename T, int K, bool GV>
-__global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
+template <typename T, int K, bool GV, int PW_>
+__global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
+    constexpr int PT_ = PW_ * 64;
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
     constexpr int VB = sizeof(T) == 2 ? 64 : 32;        // slab width
     constexpr int LDV = VB + PAD;
     constexpr int NVT = VB / 16;                         // column tiles of a slab
-    constexpr int NVW = NVT / 2;                         // ... per wave in step (1)
+    constexpr int WPR = PW_ / 4;                         // wavefronts that share a row block in steps (1), (2)
+    constexpr int NVW = NVT / WPR;                       // column tiles of a slab per wavefront there
+    static_assert(NVT % WPR == 0 && NVW >= 1, "slab too narrow for this many wavefronts");
+    constexpr int NCT = K / 16;                          // column tiles of the [64 x K] results
+    constexpr int WPC = PW_ / NCT > 0 ? PW_ / NCT : 1;   // wavefronts per column tile ...
+    constexpr int IBN = 4 / WPC;                         // ... and row blocks per wavefront
+    static_assert(WPC <= 4 && 4 % WPC == 0, "column tiles / wavefronts");
+    constexpr int NLT = (10 + PW_ - 1) / PW_;            // lower 16x16 tiles per wavefront
     constexpr int KS = Mfma<T>::KSTEP;
     // persistent
     __shared__ __attribute__((aligned(16))) T Ks[C * LDK];
@@ -345,10 +353,10 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     __shared__ float red[4 * C];                         // [4][64] partial sums across tiles
     __shared__ float red2[4 * C];
     __shared__ float red3[4 * C];
-    __shared__ float dbeta_s[2 * C];
+    __shared__ float dbeta_s[WPR * C];
     __shared__ float sdot[PW_];
     __shared__ float colss[GV ? PT_ : 1];                // <dS', S> column by column (partials)
-    __shared__ float dgam_s[GV ? K : 1];                 // sum_i (K~/Gamma)_ic (E dS')_ic
+    __shared__ float dgam_s[GV ? (PW_ / (K / 16) > 0 ? PW_ / (K / 16) : 1) * K : 1];   // sum_i (K~/Gamma)_ic (E dS')_ic, per row-block group
     // slab buffers, later Q / K~ / cP and the row-dot partials
     constexpr int SLAB_ELEMS = 3 * C * LDV + 2 * VB * LDC + 2 * VB * LDK;
     constexpr int POST_ELEMS = 2 * C * LDK + C * LDC + (3 * PW_ * C * 4) / (int)sizeof(T);
@@ -372,8 +380,9 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
     const size_t tstride = a.H;
-    const int ct = wave * 16;           // this wave's column tile of the [64 x K] results
-    const bool has_ct = ct < K;
+    const int ct = (wave % NCT) * 16;   // this wave's column tile of the [64 x K] results ...
+    const int ib0 = (wave / NCT) * IBN; // ... and its first row block
+    const bool has_ct = wave < NCT * WPC;
 
     if (wave == 0) {
         const size_t th = tok0 + (size_t)lane * tstride;
@@ -385,19 +394,19 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     load_tile(Tt, LDC, static_cast<const T *>(a.Tm) + bhn * C * C, (size_t)C, C, C, tid, PT_);
 
     // accumulators over the walk
-    f32x4 dP[2], dA[2];                 // the lower tiles idx = wave, wave + 8 (< 10)
-    f32x4 dQg[4], dKg[4], dKr[4];       // [row block], column tile ct
+    f32x4 dP[NLT], dA[NLT];             // the lower tiles idx = wave, wave + PW_ (< 10)
+    f32x4 dQg[IBN], dKg[IBN], dKr[IBN]; // [row block ib0 + .], column tile ct
     float dbeta_part[4] = {0.f, 0.f, 0.f, 0.f};     // rows 16*(wave/2) + acc_row(lane, r), this wave's columns
     float ss_part = 0.f;                // <dS', S>
 #pragma unroll
-    for (int t = 0; t < 2; ++t) { dP[t] = f32x4{0.f, 0.f, 0.f, 0.f}; dA[t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int t = 0; t < NLT; ++t) { dP[t] = f32x4{0.f, 0.f, 0.f, 0.f}; dA[t] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-    for (int ib = 0; ib < 4; ++ib) {
+    for (int ib = 0; ib < IBN; ++ib) {
         dQg[ib] = f32x4{0.f, 0.f, 0.f, 0.f};
         dKg[ib] = f32x4{0.f, 0.f, 0.f, 0.f};
         dKr[ib] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    const int rb = wave >> 1;           // row block of steps (1), (2)
+    const int rb = wave / WPR;          // row block of steps (1), (2)
 
     // the slab tiles travel through registers: the next slab (after the last one: Q and K~) is
     // fetched while the workgroup computes on the current one
@@ -449,7 +458,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
                 typename Mfma<T>::Frag ft = Mfma<T>::template load<false>(Tt + kk * LDC + rb * 16, LDC, lane);
 #pragma unroll
                 for (int q = 0; q < NVW; ++q) {
-                    const int vt = (wave & 1) * NVW + q;
+                    const int vt = (wave % WPR) * NVW + q;
                     typename Mfma<T>::Frag fe = Mfma<T>::template load<true>(dEts + vt * 16 * LDC + kk, LDC, lane);
                     dr[q] = Mfma<T>::mma(ft, fe, dr[q]);
                 }
@@ -458,14 +467,14 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
                 typename Mfma<T>::Frag fk = Mfma<T>::template load<true>(Ks + rb * 16 * LDK + kk, LDK, lane);
 #pragma unroll
                 for (int q = 0; q < NVW; ++q) {
-                    const int vt = (wave & 1) * NVW + q;
+                    const int vt = (wave % WPR) * NVW + q;
                     typename Mfma<T>::Frag fs = Mfma<T>::template load<true>(Ss + vt * 16 * LDK + kk, LDK, lane);
                     ks[q] = Mfma<T>::mma(fk, fs, ks[q]);
                 }
             }
 #pragma unroll
             for (int q = 0; q < NVW; ++q) {
-                const int vt = (wave & 1) * NVW + q;
+                const int vt = (wave % WPR) * NVW + q;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int i = rb * 16 + acc_row(lane, r), c = vt * 16 + acc_col(lane);
@@ -479,7 +488,7 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
         OSDN_PTICK(1)
         // (3,4) dP += dO E^T, dA -= dR E^T on the lower tiles
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < NLT; ++t) {
             const int idx = wave + PW_ * t;
             if (idx < 10) {
                 const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
@@ -499,13 +508,14 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
                 typename Mfma<T>::Frag fs = Mfma<T>::template load<false>(Ss + kk * LDK + ct, LDK, lane);
                 typename Mfma<T>::Frag fd = Mfma<T>::template load<false>(dSs + kk * LDK + ct, LDK, lane);
 #pragma unroll
-                for (int ib = 0; ib < 4; ++ib) {
+                for (int iq = 0; iq < IBN; ++iq) {
+                    const int ib = ib0 + iq;
                     typename Mfma<T>::Frag fo = Mfma<T>::template load<true>(dOs + ib * 16 * LDV + kk, LDV, lane);
                     typename Mfma<T>::Frag fr = Mfma<T>::template load<true>(dRs + ib * 16 * LDV + kk, LDV, lane);
                     typename Mfma<T>::Frag fe = Mfma<T>::template load<false>(Ets + kk * LDC + ib * 16, LDC, lane);
-                    dQg[ib] = Mfma<T>::mma(fo, fs, dQg[ib]);
-                    dKg[ib] = Mfma<T>::mma(fr, fs, dKg[ib]);
-                    dKr[ib] = Mfma<T>::mma(fe, fd, dKr[ib]);
+                    dQg[iq] = Mfma<T>::mma(fo, fs, dQg[iq]);
+                    dKg[iq] = Mfma<T>::mma(fr, fs, dKg[iq]);
+                    dKr[iq] = Mfma<T>::mma(fe, fd, dKr[iq]);
                 }
             }
         }
@@ -533,17 +543,18 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     ss_part = wave_sum(ss_part);
     if (lane == 0) sdot[wave] = ss_part;
     for (int idx = tid; idx < 4 * C; idx += PT_) { red[idx] = 0.f; red2[idx] = 0.f; red3[idx] = 0.f; }
+    for (int idx = tid; idx < 3 * PW_ * C; idx += PT_) pq[idx] = 0.f;      // row-dot partials: a wavefront fills its own row blocks
     // dbeta: the walk's part, reduced over the 16 lanes of a row; two waves share a row block
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const float sred = row16_sum(dbeta_part[r]);
-        if (acc_col(lane) == 0) dbeta_s[(wave & 1) * C + rb * 16 + acc_row(lane, r)] = sred;
+        if (acc_col(lane) == 0) dbeta_s[(wave % WPR) * C + rb * 16 + acc_row(lane, r)] = sred;
     }
     __syncthreads();
     OSDN_PTICK(4)
     // ---- lower tiles: A0, P, X, cA, cP ----
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < NLT; ++t) {
         const int idx = wave + PW_ * t;
         if (idx < 10) {
             const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
@@ -581,9 +592,9 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     __syncthreads();
     OSDN_PTICK(5)
     // ---- dQ, dK (read side), dK~ and the inner products that enter dG (column tile ct) ----
-    float tq[4][4], tk[4][4], tr[4][4];     // [row block][r]: partial row dots over this wave's columns
+    float tq[IBN][4], tk[IBN][4], tr[IBN][4];     // [row block][r]: partial row dots over this wave's columns
 #pragma unroll
-    for (int ib = 0; ib < 4; ++ib)
+    for (int ib = 0; ib < IBN; ++ib)
 #pragma unroll
         for (int r = 0; r < 4; ++r) { tq[ib][r] = 0.f; tk[ib][r] = 0.f; tr[ib][r] = 0.f; }
     T *dq_g = static_cast<T *>(a.dq) + tok0 * K;
@@ -593,7 +604,8 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     float dgc = 0.f;
     if (has_ct) {
 #pragma unroll
-        for (int ib = 0; ib < 4; ++ib) {
+        for (int iq = 0; iq < IBN; ++iq) {
+            const int ib = ib0 + iq;
             f32x4 aq = {0.f, 0.f, 0.f, 0.f}, ak = {0.f, 0.f, 0.f, 0.f}, at = {0.f, 0.f, 0.f, 0.f};
             // cP K~ and cA K~: contraction over j <= i
             const int kd = min(C, ((ib + 1) * 16 + KS - 1) / KS * KS);
@@ -618,15 +630,15 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
             for (int r = 0; r < 4; ++r) {
                 const int i = ib * 16 + acc_row(lane, r), c = ct + acc_col(lane);
                 const float gam = __expf(Gs[i]), rho = __expf(Gs[C - 1] - Gs[i]);
-                const float gq = a.scale * gam * dQg[ib][r];         // gamma . d(gamma Q)
-                const float gk = -Bs[i] * gam * dKg[ib][r];           // gamma . d(gamma K)
-                const float gr = (GV ? gcv : rho) * dKr[ib][r];       // rho . d(rho K~)
+                const float gq = a.scale * gam * dQg[iq][r];         // gamma . d(gamma Q)
+                const float gk = -Bs[i] * gam * dKg[iq][r];           // gamma . d(gamma K)
+                const float gr = (GV ? gcv : rho) * dKr[iq][r];       // rho . d(rho K~)
                 const float qv = to_f32(Qs[i * LDK + c]), kv = to_f32(Ks[i * LDK + c]),
                             ktv = to_f32(Kts[i * LDK + c]);
-                if (GV) dgc = __builtin_fmaf(ktv, dKr[ib][r], dgc);
-                tq[ib][r] += gq * qv;
-                tk[ib][r] += gk * kv;
-                tr[ib][r] += gr * ktv;
+                if (GV) dgc = __builtin_fmaf(ktv, dKr[iq][r], dgc);
+                tq[iq][r] += gq * qv;
+                tk[iq][r] += gk * kv;
+                tr[iq][r] += gr * ktv;
                 dq_g[(size_t)i * tstride * K + c] = from_f32<T>(aq[r] + gq);
                 dk_g[(size_t)i * tstride * K + c] = from_f32<T>(ak[r] + gk);
                 dkt_g[(size_t)i * tstride * K + c] = from_f32<T>(at[r] + gr);
@@ -636,24 +648,28 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
     if (GV && has_ct) {                 // column sums over the rows: lanes 16 apart share a column
         dgc += __shfl_xor(dgc, 16, 64);
         dgc += __shfl_xor(dgc, 32, 64);
-        if (lane < 16) dgam_s[GV ? ct + lane : 0] = dgc;
+        if (lane < 16) dgam_s[GV ? (wave / NCT) * K + ct + lane : 0] = dgc;
     }
     // per-row sums across the 16 lanes of a row, then across waves through LDS
     float *pk = pq + PW_ * C, *pr = pk + PW_ * C;
+    if (has_ct) {
 #pragma unroll
-    for (int ib = 0; ib < 4; ++ib)
+        for (int iq = 0; iq < IBN; ++iq)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float sq = row16_sum(tq[ib][r]), sk = row16_sum(tk[ib][r]), sr = row16_sum(tr[ib][r]);
-            if (acc_col(lane) == 0) {
-                const int i = ib * 16 + acc_row(lane, r);
-                pq[wave * C + i] = sq; pk[wave * C + i] = sk; pr[wave * C + i] = sr;
+            for (int r = 0; r < 4; ++r) {
+                const float sq = row16_sum(tq[iq][r]), sk = row16_sum(tk[iq][r]), sr = row16_sum(tr[iq][r]);
+                if (acc_col(lane) == 0) {
+                    const int i = (ib0 + iq) * 16 + acc_row(lane, r);
+                    pq[wave * C + i] = sq; pk[wave * C + i] = sk; pr[wave * C + i] = sr;
+                }
             }
-        }
+    }
     __syncthreads();
     OSDN_PTICK(6)
     if (GV && tid < K) {                // dL/d(decay of channel tid over the chunk)
-        float sd = dgam_s[GV ? tid : 0];
+        float sd = 0.f;
+#pragma unroll
+        for (int j = 0; j < WPC; ++j) sd += dgam_s[GV ? j * K + tid : 0];
 #pragma unroll
         for (int j = 0; j < PT_ / K; ++j) sd += colss[GV ? tid + j * K : 0];
         a.dgamC[bhn * K + tid] = sd;
@@ -667,7 +683,10 @@ __global__ __launch_bounds__(PT_) void bwd_post_kernel(ChunkArgs a) {
         const float rowx = red2[i] + red2[C + i] + red2[2 * C + i] + red2[3 * C + i];
         const float colx = red3[i] + red3[C + i] + red3[2 * C + i] + red3[3 * C + i];
         const size_t th = tok0 + (size_t)i * tstride;
-        a.dbeta[th] = dbeta_s[i] + dbeta_s[C + i] + rowa;
+        float dbw = rowa;
+#pragma unroll
+        for (int w = 0; w < WPR; ++w) dbw += dbeta_s[w * C + i];
+        a.dbeta[th] = dbw;
         if (a.dlog_alpha) {
             float dG = rowx - colx + t_q + t_k - t_r;
             const float tr_sum = wave_sum(t_r);
@@ -712,10 +731,12 @@ int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
 }
 template <typename T, bool GV>
 static int launch_post_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.n1 - a.n0, a.H, a.B), block(PT_);
+    constexpr int PW = 8;           // wavefronts per workgroup (16 was measured for bf16: the kernel then
+                                    // has to fit 128 registers, spills, and takes twice as long)
+    dim3 grid(a.n1 - a.n0, a.H, a.B), block(PW * 64);
     if (GV && (!a.gamC || !a.dgamC || a.log_alpha || a.dlog_alpha)) return -1;
-    if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64, GV>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128, GV>), grid, block, 0, st, a);
+    if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64, GV, PW>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128, GV, PW>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }

@@ -193,21 +193,21 @@ __device__ __forceinline__ void store_vec_t(bf16 *dst, const float (&v)[8]) {
 // writes the registers into LDS.  NT threads share a [ROWS x COLS] tile.
 template <typename T, int ROWS, int COLS, int NT_>
 struct TileRegs {
-    static constexpr int VN = 16 / sizeof(T), VPR = COLS / VN, NV = ROWS * VPR / NT_;
-    static_assert(ROWS * VPR % NT_ == 0 && NV >= 1, "tile must split evenly over the threads");
+    static constexpr int VN = 16 / sizeof(T), VPR = COLS / VN, TOTAL = ROWS * VPR, NV = (TOTAL + NT_ - 1) / NT_;
+    static_assert(TOTAL % NT_ == 0 || NT_ % TOTAL == 0, "tile must split evenly over (some of) the threads");
     u32x4 v[NV];
     __device__ __forceinline__ void fetch(const T *g, size_t g_ld, int tid) {
 #pragma unroll
         for (int m = 0; m < NV; ++m) {
             const int i = tid + m * NT_, r = i / VPR, c = (i % VPR) * VN;
-            v[m] = *reinterpret_cast<const u32x4 *>(g + (size_t)r * g_ld + c);
+            if (TOTAL % NT_ == 0 || i < TOTAL) v[m] = *reinterpret_cast<const u32x4 *>(g + (size_t)r * g_ld + c);
         }
     }
     __device__ __forceinline__ void put(T *s, int s_ld, int tid) const {
 #pragma unroll
         for (int m = 0; m < NV; ++m) {
             const int i = tid + m * NT_, r = i / VPR, c = (i % VPR) * VN;
-            *reinterpret_cast<u32x4 *>(s + r * s_ld + c) = v[m];
+            if (TOTAL % NT_ == 0 || i < TOTAL) *reinterpret_cast<u32x4 *>(s + r * s_ld + c) = v[m];
         }
     }
 };
