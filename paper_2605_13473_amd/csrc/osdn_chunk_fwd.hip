@@ -164,39 +164,8 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     store_tile_global(static_cast<T *>(a.Ktr) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, CP_);
     __syncthreads();                // the staging tile is free again: (I + A)^-1 is built in its place
 
-    // ---- T = (I + A)^-1, 16x16 blocks.  Diagonal blocks: forward substitution, one
-    //      column per lane.  Block (i,j), i > j: T_ij = -T_ii sum_{m=j}^{i-1} A_im T_mj,
-    //      both products on the fp32 MFMA, one wavefront per block. ----
-    if (wave < 4 && lane < 16) {
-        const int o = wave * 16;
-        float x[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            float v = (i == lane) ? 1.f : 0.f;
-#pragma unroll
-            for (int j = 0; j < i; ++j) v -= Af[(o + i) * LDF + o + j] * x[j];
-            x[i] = v;
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) Ti[(o + i) * LDF + o + lane] = x[i];
-    }
-    __syncthreads();
-    for (int s = 1; s <= 3; ++s) {
-        if (wave < 4 - s) {
-            const int i = s + wave, j = wave;
-            float *xw = Xs + wave * 16 * 17;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            for (int m = j; m < i; ++m)
-                mma_tile<float, true, false>(acc, Af + i * 16 * LDF + m * 16, LDF, Ti + m * 16 * LDF + j * 16, LDF, 16, lane);
-            store_tile(xw, 17, acc, lane);
-            f32x4 t = {0.f, 0.f, 0.f, 0.f};
-            mma_tile<float, true, false>(t, Ti + i * 16 * LDF + i * 16, LDF, xw, 17, 16, lane);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) t[r] = -t[r];
-            store_tile(Ti + i * 16 * LDF + j * 16, LDF, t, lane);
-        }
-        __syncthreads();
-    }
+    // ---- T = (I + A)^-1 in fp32, blocked ----
+    ut_inverse64<LDF>(Af, Ti, Xs, wave, lane);
     OSDN_CTICK(2)
     // ---- T in the I/O type, three times: as it is (straight to memory), with the columns scaled
     //      by beta (for U) and by beta gamma (for W); the upper triangle is exactly zero ----

@@ -91,6 +91,15 @@ __device__ __forceinline__ void mma_tile(f32x4 &acc, const T *A, int lda, const 
     }
 }
 
+// (I + A)^-1 for a strictly lower triangular 64 x 64 A, in fp32 in LDS, in 16 x 16 blocks; only the
+// lower blocks of Ti are written (the rest is zero by definition and never stored).  Diagonal
+// blocks: forward substitution, one column per lane.  Block (i,j), i > j:
+// T_ij = -T_ii sum_{m=j}^{i-1} A_im T_mj, both products on the fp32 MFMA, one wavefront per block.
+// Af, Ti: [64][LDF]; Xs: scratch of 3 x 16 x 17 floats.  Every thread of a workgroup of at least
+// four wavefronts calls it (it synchronises the workgroup); A must be complete before the call.
+template <int LDF>
+__device__ __forceinline__ void ut_inverse64(const float *Af, float *Ti, float *Xs, int wave, int lane);
+
 // position of accumulator element r of this lane inside its 16x16 tile
 __device__ __forceinline__ int acc_row(int lane, int r) { return ((lane >> 4) << 2) + r; }
 __device__ __forceinline__ int acc_col(int lane) { return lane & 15; }
@@ -211,6 +220,40 @@ struct TileRegs {
         }
     }
 };
+
+template <int LDF>
+__device__ __forceinline__ void ut_inverse64(const float *Af, float *Ti, float *Xs, int wave, int lane) {
+    if (wave < 4 && lane < 16) {
+        const int o = wave * 16;
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float v = (i == lane) ? 1.f : 0.f;
+#pragma unroll
+            for (int j = 0; j < i; ++j) v -= Af[(o + i) * LDF + o + j] * x[j];
+            x[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Ti[(o + i) * LDF + o + lane] = x[i];
+    }
+    __syncthreads();
+    for (int s = 1; s <= 3; ++s) {
+        if (wave < 4 - s) {
+            const int i = s + wave, j = wave;
+            float *xw = Xs + wave * 16 * 17;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int m = j; m < i; ++m)
+                mma_tile<float, true, false>(acc, Af + i * 16 * LDF + m * 16, LDF, Ti + m * 16 * LDF + j * 16, LDF, 16, lane);
+            store_tile(xw, 17, acc, lane);
+            f32x4 t = {0.f, 0.f, 0.f, 0.f};
+            mma_tile<float, true, false>(t, Ti + i * 16 * LDF + i * 16, LDF, xw, 17, 16, lane);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) t[r] = -t[r];
+            store_tile(Ti + i * 16 * LDF + j * 16, LDF, t, lane);
+        }
+        __syncthreads();
+    }
+}
 
 // --------------------------------------------------------- wave helpers ----
 template <int CTRL, int ROW_MASK = 0xF>
