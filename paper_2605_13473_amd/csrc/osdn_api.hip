@@ -224,20 +224,32 @@ Pipeline *pipeline_for_current_device() {
     return it->second.ok ? &it->second : nullptr;
 }
 
-// number of segments for a sequence of N chunks: about 20 chunks each, between two (any
-// sequence of at least two chunks, so that short sequences take the same path) and four:
-// more segments buy little overlap and cost launches and cross-stream waits
-// (OSDN_SEGMENTS in the environment overrides it; 1 = no pipelining).
+// Number of segments for a sequence of N chunks (OSDN_SEGMENTS in the environment overrides
+// it; 1 = no pipelining).  At least two (any sequence of at least two chunks, so that short
+// sequences take the same path).  A segment more shortens the stretch of phase 1 that runs with
+// nothing beside it (the first segment of the forward pass, the last of the backward pass) and
+// costs launches, cross-stream waits and partly filled rounds of workgroups.
+//  - forward: about 16 chunks per segment, at most six segments (measured flat beyond).
+//  - backward: a segment more costs more there, because every launch of the phase-2 chain kernel
+//    meets a phase-1 chain kernel on the other stream and the two do not fit on one CU together:
+//    when the workgroups of both (chain_wgs) outnumber the CUs, the count that balances the
+//    exposed tail against that cost is about sqrt(N / 15) (2 at 64 chunks, 4 at 256); when they
+//    all fit side by side, about 32 chunks per segment, at most twelve.
 // Segments cut the chunk axis as a whole.  With packed sequences the sequential kernels of a
 // segment only have the sequences that cross it to work on, one after the other segment by
 // segment, so cutting pays only while one sequence makes up most of the axis; otherwise the
 // many independent chains fill the chip by themselves and everything runs in one piece.
-int segment_count(int N, int longest) {
+constexpr int NUM_CU = 256;
+int segment_count(int N, int longest, long long chain_wgs, bool backward) {
     static const int forced = [] { const char *e = std::getenv("OSDN_SEGMENTS"); return e ? std::atoi(e) : 0; }();
     if (forced <= 0 && (long long)longest * 4 < (long long)N * 3) return 1;
-    int S = forced > 0 ? forced : N / 20;
-    if (forced <= 0 && S > 4) S = 4;
-    if (forced <= 0 && S < 2 && N >= 2) S = 2;
+    int S = forced;
+    if (forced <= 0) {
+        if (!backward) S = N / 16 > 6 ? 6 : N / 16;
+        else if (chain_wgs > NUM_CU) S = (int)std::lround(std::sqrt(N / 15.0)) > 6 ? 6 : (int)std::lround(std::sqrt(N / 15.0));
+        else S = N / 32 > 12 ? 12 : N / 32;
+        if (S < 2 && N >= 2) S = 2;
+    }
     if (S > MAX_SEGMENTS) S = MAX_SEGMENTS;
     if (S > N) S = N;
     return S < 1 ? 1 : S;
@@ -407,7 +419,7 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     }
 
     const int N = p->T / C;
-    int S = segment_count(N, pk.longest);
+    int S = segment_count(N, pk.longest, 0, false);
     std::lock_guard<std::mutex> lock(g_pipe_mu);
     Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
     if (!pl) S = 1;
@@ -559,7 +571,8 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
 
     const int N = p->T / C;
-    int S = segment_count(N, pk.longest);
+    const long long chains = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
+    int S = segment_count(N, pk.longest, chains * (p->V / 32) + chains, true);   // chain kernel: 32 rows of the state per workgroup
     std::lock_guard<std::mutex> lock(g_pipe_mu);
     Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
     if (!pl) S = 1;
