@@ -257,6 +257,19 @@ int segment_count(int N, int longest, long long chain_wgs, bool backward) {
 // first chunk of segment s.  Segment 0 is half as long as the others: it is the one that runs
 // without a partner (phase 1 of it before anything of phase 2 can start in the forward pass,
 // and after everything else in the backward pass).
+// First chunk of segment s when every segment is r times as long as the one before.  Used by
+// the forward pass when phase 2 is the slower of the two phases (many chains): phase 2 then
+// starts early on a short segment and is never left waiting for phase 1, and the long last
+// segment runs when phase 1 is already out of the way.
+inline int seg_begin_grow(int N, int S, int s, double r) {
+    if (s <= 0) return 0;
+    if (s >= S) return N;
+    const double f = (std::pow(r, s) - 1.0) / (std::pow(r, S) - 1.0);
+    int b = (int)std::lround(N * f);
+    if (b < s) b = s;                       // at least one chunk per segment
+    if (b > N - (S - s)) b = N - (S - s);
+    return b;
+}
 inline int seg_begin(int N, int S, int s) {
     if (s <= 0) return 0;
     if (s >= S) return N;
@@ -423,7 +436,13 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     std::lock_guard<std::mutex> lock(g_pipe_mu);
     Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
     if (!pl) S = 1;
-    auto seg_range = [&](int sidx, int &n0, int &n1) { n0 = seg_begin(N, S, sidx); n1 = seg_begin(N, S, sidx + 1); };
+    // chain workgroups of both phases (32 rows of the state per workgroup in state_fwd) against the CUs
+    const long long chains = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
+    const bool crowded = chains * (p->V / 32) + chains > NUM_CU;
+    auto seg_range = [&](int sidx, int &n0, int &n1) {
+        if (crowded) { n0 = seg_begin_grow(N, S, sidx, 1.7); n1 = seg_begin_grow(N, S, sidx + 1, 1.7); return; }
+        n0 = seg_begin(N, S, sidx); n1 = seg_begin(N, S, sidx + 1);
+    };
     auto precond = [&](int sidx, hipStream_t s1) {
         seg_range(sidx, pa.n0, pa.n1);
         pa.d_in = sidx == 0 ? d_in : d_out;          // d is carried in d_out
