@@ -44,6 +44,18 @@ def test_stress_backward(shape, bf16):
     compare_backward(x, ob.Hyper(eta=0.5), bf16, dS, dd)
 
 
+@pytest.mark.parametrize("T", [128, 192, 448])
+def test_many_chains_few_chunks(T):
+    """More chain workgroups than CUs (128 chains): the library then cuts the forward pass into
+    segments that grow and the backward pass into few; with 2, 3 and 7 chunks every segment
+    boundary rule is hit with tiny segments.  eta = 0.5, so d moves and meets the box."""
+    B, H, K, V = 8, 16, 64, 64
+    x = make_stress_inputs(B, T, H, K, V, seed=61, bf16=False, retention=0.0)
+    hp = ob.Hyper(eta=0.5)
+    compare_forward(x, hp, False)
+    compare_backward(x, hp, False)
+
+
 @pytest.mark.parametrize("variant", ["ungated", "no_retention", "non_beta_aware", "no_projection",
                                      "eta_one_clamped", "defaults_null"])
 def test_variants_fwd_bwd_fp32(variant):
