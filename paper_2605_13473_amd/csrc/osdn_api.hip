@@ -279,6 +279,18 @@ inline int seg_begin(int N, int S, int s) {
 
 #define OSDN_HIP_OK(x) do { if ((x) != hipSuccess) return OSDN_ERR_LAUNCH; } while (0)
 
+// Once the side stream has been forked off, every way out of the call joins it back into the
+// caller's stream: also an error return must not leave work behind that the caller's stream does
+// not wait for (or, under stream capture, a branch that never rejoins).
+struct SideJoin {
+    Pipeline *pl;
+    hipStream_t st;
+    bool armed;
+    ~SideJoin() {
+        if (armed && hipEventRecord(pl->join, pl->side) == hipSuccess) (void)hipStreamWaitEvent(st, pl->join, 0);
+    }
+};
+
 }  // namespace
 
 extern "C" {
@@ -468,6 +480,7 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     hipStream_t s1 = pl->side;
     OSDN_HIP_OK(hipEventRecord(pl->fork, st));
     OSDN_HIP_OK(hipStreamWaitEvent(s1, pl->fork, 0));
+    SideJoin rejoin{pl, st, true};
     for (int s = 0; s < S; ++s) {
         if (precond(s, s1) != 0) return OSDN_ERR_SHAPE;
         OSDN_HIP_OK(hipEventRecord(pl->a[s], s1));
@@ -477,6 +490,7 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
         if (phase2(KID_CHUNK_PREP, s) != 0 || phase2(KID_STATE_FWD, s) != 0 || phase2(KID_OUTPUT_FWD, s) != 0)
             return OSDN_ERR_SHAPE;
     }
+    rejoin.armed = false;               // the wait for the last segment's event was the join
     return finish();
 }
 
@@ -630,6 +644,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     hipStream_t s1 = pl->side;
     OSDN_HIP_OK(hipEventRecord(pl->fork, st));
     OSDN_HIP_OK(hipStreamWaitEvent(s1, pl->fork, 0));
+    SideJoin rejoin{pl, st, true};
     if (masks(s1) != 0) return OSDN_ERR_SHAPE;
     for (int s = S - 1; s >= 0; --s) {
         if (phase2(KID_BWD_LOCAL, s) != 0 || phase2(KID_BWD_CHAIN, s) != 0 || phase2(KID_BWD_POST, s) != 0)
@@ -642,6 +657,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     }
     OSDN_HIP_OK(hipEventRecord(pl->join, s1));
     OSDN_HIP_OK(hipStreamWaitEvent(st, pl->join, 0));
+    rejoin.armed = false;
     return finish();
 }
 
