@@ -43,7 +43,7 @@ __device__ __forceinline__ float row16_sum(float x) {
 constexpr int BL_ = 512;        // threads of a bwd_local workgroup: 8 wavefronts, (16 rows or columns, half of the tiles)
 template <typename T, int K>
 __global__ __launch_bounds__(BL_) void bwd_local_kernel(ChunkArgs a) {
-    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
+    constexpr int PAD = Pad<T>::v, LDK = K + (sizeof(T) == 2 ? 16 : PAD), LDC = C + PAD;   // Q, K~: read 16 bytes per lane along k
     constexpr int NW = BL_ / 64;
     __shared__ __attribute__((aligned(16))) T Qs[C * LDK];
     constexpr int KTS_ELEMS = C * LDK > K * LDC ? C * LDK : K * LDC;
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
 template <typename T, int K, bool GV, int PW_>
 __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     constexpr int PT_ = PW_ * 64;
-    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
+    constexpr int PAD = sizeof(T) == 2 ? 16 : Pad<T>::v, LDK = K + PAD, LDC = C + PAD;   // bf16: rows 32 bytes apart modulo 128
     constexpr int VB = sizeof(T) == 2 ? 64 : 32;        // slab width
     constexpr int LDV = VB + PAD;
     constexpr int NVT = VB / 16;                         // column tiles of a slab

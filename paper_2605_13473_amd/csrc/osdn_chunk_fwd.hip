@@ -460,7 +460,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
 constexpr int OT_ = 512;        // threads of an output_fwd workgroup: 8 wavefronts, (row block, half of the value tiles)
 template <typename T, int K>
 __global__ __launch_bounds__(OT_) void output_fwd_kernel(ChunkArgs a) {
-    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
+    constexpr int PAD = sizeof(T) == 2 ? 16 : Pad<T>::v, LDK = K + PAD, LDC = C + PAD;   // bf16: rows 32 bytes apart modulo 128 (every operand read here is 16 bytes per lane along k)
     constexpr int NW = OT_ / 64;
     __shared__ __attribute__((aligned(16))) T Qs[C * LDK];
     __shared__ __attribute__((aligned(16))) T Kts[C * LDK];     // K~, later the output staging tile
