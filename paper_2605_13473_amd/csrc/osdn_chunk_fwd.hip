@@ -31,21 +31,24 @@ namespace osdn {
 constexpr int CP_ = 512;        // threads of a chunk_prep workgroup (8 wavefronts)
 template <typename T, int K, bool GV>
 __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
-    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDF = C + 1;
+    // K and K~ are read 16 bytes per lane along k (Gram matrix, transposes): 32 bytes of padding
+    // for bf16 (not with per-channel gates, where two workgroups would no longer fit a CU); the
+    // tiles that are written transposed keep 16
+    constexpr int PAD = Pad<T>::v, LDK = K + (sizeof(T) == 2 && !GV ? 16 : PAD), LDC = C + PAD, LDF = C + 1;
     constexpr int NW = CP_ / 64;
     __shared__ __attribute__((aligned(16))) T X1[C * LDK];      // K, then V slabs
     __shared__ __attribute__((aligned(16))) T X2[C * LDK];      // K~, then W staging
     __shared__ __attribute__((aligned(16))) T Tu[C * LDC];      // T diag(beta)
-    // scratch: A (fp32) | (I + A)^-1 (fp32) | per-wave 16x16 block products.  A's space later holds
+    // scratch: A (fp32) | (I + A)^-1 (fp32).  A's space later holds
     // T diag(beta gamma); the rest doubles as the staging tile for the transposed outputs.
     constexpr int STAGE_F = (K * LDC * (int)sizeof(T) + 3) / 4;
-    constexpr int TI_F = C * LDF + 3 * 16 * 17;
+    constexpr int TI_F = C * LDF;
     constexpr int TW_F = C * LDC * (int)sizeof(T) / 4;
     constexpr int AF_F = ((C * LDF > TW_F ? C * LDF : TW_F) + 3) & ~3;
     __shared__ __attribute__((aligned(16))) float scratch[AF_F + (TI_F > STAGE_F ? TI_F : STAGE_F)];
     float *Af = scratch;                                        // A (fp32)
     float *Ti = scratch + AF_F;                                 // (I + A)^-1 (fp32), 16-byte aligned
-    float *Xs = Ti + C * LDF;                                   // [3][16][17]: at most three blocks per round
+    float *Xs = reinterpret_cast<float *>(Tu);                  // [3][16][17] block products of the inverse: T diag(beta) comes after it
     T *Tw = reinterpret_cast<T *>(Af);                          // [64][LDC], once A is dead
     T *stage = reinterpret_cast<T *>(Ti);                       // [K][LDC] / [64][LDC], while Ti is not live
     __shared__ float Gs[C], Bs[C];
