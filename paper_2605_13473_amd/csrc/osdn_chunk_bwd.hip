@@ -354,12 +354,12 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     __shared__ float red2[4 * C];
     __shared__ float red3[4 * C];
     __shared__ float dbeta_s[WPR * C];
-    __shared__ float sdot[PW_];
+    __shared__ float sdot[PW_], trsum_s[PW_];
     __shared__ float colss[GV ? PT_ : 1];                // <dS', S> column by column (partials)
     __shared__ float dgam_s[GV ? (PW_ / (K / 16) > 0 ? PW_ / (K / 16) : 1) * K : 1];   // sum_i (K~/Gamma)_ic (E dS')_ic, per row-block group
     // slab buffers, later Q / K~ / cP and the row-dot partials
     constexpr int SLAB_ELEMS = 3 * C * LDV + 2 * VB * LDC + 2 * VB * LDK;
-    constexpr int POST_ELEMS = 2 * C * LDK + C * LDC + (3 * PW_ * C * 4) / (int)sizeof(T);
+    constexpr int POST_ELEMS = 2 * C * LDK + C * LDC + (PW_ * C * 4) / (int)sizeof(T);
     constexpr int POOL = SLAB_ELEMS > POST_ELEMS ? SLAB_ELEMS : POST_ELEMS;
     __shared__ __attribute__((aligned(16))) T pool[POOL];
     T *dOs = pool;                      // [64][LDV]  dO slab (natural), later dV staging
@@ -372,7 +372,7 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     T *Qs = pool;                       // after the walk
     T *Kts = Qs + C * LDK;
     T *cPs = Kts + C * LDK;             // [64][LDC]
-    float *pq = reinterpret_cast<float *>(cPs + C * LDC);        // [PW_][64] x 3
+    float *pq = reinterpret_cast<float *>(cPs + C * LDC);        // [PW_][64]
     T *cAs = Tt;                        // [64][LDC]
 
     const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -543,7 +543,7 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     ss_part = wave_sum(ss_part);
     if (lane == 0) sdot[wave] = ss_part;
     for (int idx = tid; idx < 4 * C; idx += PT_) { red[idx] = 0.f; red2[idx] = 0.f; red3[idx] = 0.f; }
-    for (int idx = tid; idx < 3 * PW_ * C; idx += PT_) pq[idx] = 0.f;      // row-dot partials: a wavefront fills its own row blocks
+    for (int idx = tid; idx < PW_ * C; idx += PT_) pq[idx] = 0.f;          // row-dot partials: a wavefront fills its own row blocks
     // dbeta: the walk's part, reduced over the 16 lanes of a row; two waves share a row block
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -592,11 +592,14 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     __syncthreads();
     OSDN_PTICK(5)
     // ---- dQ, dK (read side), dK~ and the inner products that enter dG (column tile ct) ----
-    float tq[IBN][4], tk[IBN][4], tr[IBN][4];     // [row block][r]: partial row dots over this wave's columns
+    // dG_i takes <d(gamma Q)_i, gamma_i Q_i> + <d(gamma K)_i, gamma_i K_i> - <d(rho K~)_i, rho_i K~_i>
+    // as one number per row; the last term, summed over all rows, goes to the chunk's last token
+    float tc[IBN][4];                             // [row block][r]: that combination over this wave's columns
+    float trs = 0.f;                              // the last term over this lane's elements
 #pragma unroll
     for (int ib = 0; ib < IBN; ++ib)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) { tq[ib][r] = 0.f; tk[ib][r] = 0.f; tr[ib][r] = 0.f; }
+        for (int r = 0; r < 4; ++r) tc[ib][r] = 0.f;
     T *dq_g = static_cast<T *>(a.dq) + tok0 * K;
     T *dk_g = static_cast<T *>(a.dk_read) + tok0 * K;
     T *dkt_g = static_cast<T *>(a.dkt) + tok0 * K;
@@ -636,9 +639,8 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
                 const float qv = to_f32(Qs[i * LDK + c]), kv = to_f32(Ks[i * LDK + c]),
                             ktv = to_f32(Kts[i * LDK + c]);
                 if (GV) dgc = __builtin_fmaf(ktv, dKr[iq][r], dgc);
-                tq[iq][r] += gq * qv;
-                tk[iq][r] += gk * kv;
-                tr[iq][r] += gr * ktv;
+                tc[iq][r] = __builtin_fmaf(gq, qv, __builtin_fmaf(gk, kv, -(gr * ktv)));
+                trs = __builtin_fmaf(gr, ktv, trs);
                 dq_g[(size_t)i * tstride * K + c] = from_f32<T>(aq[r] + gq);
                 dk_g[(size_t)i * tstride * K + c] = from_f32<T>(ak[r] + gk);
                 dkt_g[(size_t)i * tstride * K + c] = from_f32<T>(at[r] + gr);
@@ -651,19 +653,17 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         if (lane < 16) dgam_s[GV ? (wave / NCT) * K + ct + lane : 0] = dgc;
     }
     // per-row sums across the 16 lanes of a row, then across waves through LDS
-    float *pk = pq + PW_ * C, *pr = pk + PW_ * C;
     if (has_ct) {
 #pragma unroll
         for (int iq = 0; iq < IBN; ++iq)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float sq = row16_sum(tq[iq][r]), sk = row16_sum(tk[iq][r]), sr = row16_sum(tr[iq][r]);
-                if (acc_col(lane) == 0) {
-                    const int i = (ib0 + iq) * 16 + acc_row(lane, r);
-                    pq[wave * C + i] = sq; pk[wave * C + i] = sk; pr[wave * C + i] = sr;
-                }
+                const float sc = row16_sum(tc[iq][r]);
+                if (acc_col(lane) == 0) pq[wave * C + (ib0 + iq) * 16 + acc_row(lane, r)] = sc;
             }
     }
+    trs = wave_sum(trs);
+    if (lane == 0) trsum_s[wave] = trs;
     __syncthreads();
     OSDN_PTICK(6)
     if (GV && tid < K) {                // dL/d(decay of channel tid over the chunk)
@@ -676,9 +676,9 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     }
     if (wave == 0) {
         const int i = lane;
-        float t_q = 0.f, t_k = 0.f, t_r = 0.f;
+        float t_c = 0.f;
 #pragma unroll
-        for (int w = 0; w < PW_; ++w) { t_q += pq[w * C + i]; t_k += pk[w * C + i]; t_r += pr[w * C + i]; }
+        for (int w = 0; w < PW_; ++w) t_c += pq[w * C + i];
         const float rowa = red[i] + red[C + i] + red[2 * C + i] + red[3 * C + i];
         const float rowx = red2[i] + red2[C + i] + red2[2 * C + i] + red2[3 * C + i];
         const float colx = red3[i] + red3[C + i] + red3[2 * C + i] + red3[3 * C + i];
@@ -688,11 +688,10 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         for (int w = 0; w < WPR; ++w) dbw += dbeta_s[w * C + i];
         a.dbeta[th] = dbw;
         if (a.dlog_alpha) {
-            float dG = rowx - colx + t_q + t_k - t_r;
-            const float tr_sum = wave_sum(t_r);
-            float ssum = 0.f;
+            float dG = rowx - colx + t_c;
+            float ssum = 0.f, tr_sum = 0.f;
 #pragma unroll
-            for (int w = 0; w < PW_; ++w) ssum += sdot[w];
+            for (int w = 0; w < PW_; ++w) { ssum += sdot[w]; tr_sum += trsum_s[w]; }
             if (i == C - 1) dG += tr_sum + __expf(Gs[C - 1]) * ssum;
             a.dlog_alpha[th] = wave_suffix_sum(dG, lane);
         }
