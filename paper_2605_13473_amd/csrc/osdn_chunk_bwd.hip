@@ -407,6 +407,7 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         dKr[ib] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     const int rb = wave / WPR;          // row block of steps (1), (2)
+    float gam_rb[4] = {1.f, 1.f, 1.f, 1.f};   // gamma of this lane's four rows there (set once G is in LDS)
 
     // the slab tiles travel through registers: the next slab (after the last one: Q and K~) is
     // fetched while the workgroup computes on the current one
@@ -443,10 +444,23 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         }
         __syncthreads();
         OSDN_PTICK(0)
-        // <dS', S> over this slab
-        for (int idx = tid; idx < VB * K; idx += PT_) {
-            const int r = idx / K, c = idx % K;
-            ss_part += to_f32(Ss[r * LDK + c]) * to_f32(dSs[r * LDK + c]);
+        if (v0 == 0) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) gam_rb[r] = __expf(Gs[rb * 16 + acc_row(lane, r)]);
+        }
+        // <dS', S> over this slab (with per-channel gates: column by column, thread tid keeps column tid % K)
+        if (GV) {
+            for (int idx = tid; idx < VB * K; idx += PT_) {
+                const int r = idx / K, c = idx % K;
+                ss_part += to_f32(Ss[r * LDK + c]) * to_f32(dSs[r * LDK + c]);
+            }
+        } else {
+            constexpr int VN = 16 / sizeof(T);
+            for (int v = tid; v < VB * K / VN; v += PT_) {
+                const int r = v / (K / VN), c = (v % (K / VN)) * VN;
+                ss_part = dot_vec<T>(*reinterpret_cast<const u32x4 *>(Ss + r * LDK + c),
+                                     *reinterpret_cast<const u32x4 *>(dSs + r * LDK + c), ss_part);
+            }
         }
         // (1) dR = T^T dE, rows j = 16*rb.. ; (2) R0 = V - gamma . (K S^T), same rows
         {
@@ -478,7 +492,7 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int i = rb * 16 + acc_row(lane, r), c = vt * 16 + acc_col(lane);
-                    const float r0 = to_f32(Vs[i * LDV + c]) - __expf(Gs[i]) * ks[q][r];
+                    const float r0 = to_f32(Vs[i * LDV + c]) - gam_rb[r] * ks[q][r];
                     dbeta_part[r] += dr[q][r] * r0;
                 }
                 store_tile(dRs + rb * 16 * LDV + vt * 16, LDV, dr[q], lane);
@@ -522,9 +536,16 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         __syncthreads();
         OSDN_PTICK(2)
         // dV = beta . dR for this slab, staged through the dO buffer
-        for (int idx = tid; idx < C * VB; idx += PT_) {
-            const int r = idx / VB, c = idx % VB;
-            dOs[r * LDV + c] = from_f32<T>(Bs[r] * to_f32(dRs[r * LDV + c]));
+        {
+            constexpr int VN = 16 / sizeof(T);
+            for (int v = tid; v < C * VB / VN; v += PT_) {
+                const int r = v / (VB / VN), c = (v % (VB / VN)) * VN;
+                const u32x4 in = *reinterpret_cast<const u32x4 *>(dRs + r * LDV + c);
+                float o[VN];
+#pragma unroll
+                for (int e = 0; e < VN; ++e) o[e] = Bs[r] * vec_get<T>(in, e);
+                store_vec_t(dOs + r * LDV + c, o);
+            }
         }
         __syncthreads();
         store_tile_global(static_cast<T *>(a.dv) + tok0 * a.V + v0, tstride * a.V, dOs, LDV, C, VB, tid, PT_);
@@ -534,10 +555,13 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     // ---- after the walk: Q, K~ into the pool ----
     r_Q.put(Qs, LDK, tid);
     r_Kt.put(Kts, LDK, tid);
-    for (int idx = tid; idx < C * C; idx += PT_) {      // upper triangle of cA, cP is zero
-        const int i = idx >> 6, j = idx & 63;
-        cAs[i * LDC + j] = from_f32<T>(0.f);
-        cPs[i * LDC + j] = from_f32<T>(0.f);
+    {                                                   // upper triangle of cA, cP is zero
+        constexpr int VN = 16 / sizeof(T);
+        for (int v = tid; v < C * C / VN; v += PT_) {
+            const int i = v / (C / VN), j = (v % (C / VN)) * VN;
+            *reinterpret_cast<u32x4 *>(cAs + i * LDC + j) = u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4 *>(cPs + i * LDC + j) = u32x4{0u, 0u, 0u, 0u};
+        }
     }
     if (GV) colss[GV ? tid : 0] = ss_part;               // thread tid summed rows of column tid % K
     ss_part = wave_sum(ss_part);

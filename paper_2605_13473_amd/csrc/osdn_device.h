@@ -201,6 +201,22 @@ __device__ __forceinline__ void store_vec_t(bf16 *dst, const float (&v)[8]) {
     *reinterpret_cast<bf16x8 *>(dst) = o;
 }
 
+// acc + <a, b> over 16 bytes of T held in u32x4 (bf16: four two-element dot products in fp32)
+template <typename T> __device__ __forceinline__ float dot_vec(const u32x4 &a, const u32x4 &b, float acc);
+template <> __device__ __forceinline__ float dot_vec<float>(const u32x4 &a, const u32x4 &b, float acc) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc = __builtin_fmaf(vec_get<float>(a, e), vec_get<float>(b, e), acc);
+    return acc;
+}
+template <> __device__ __forceinline__ float dot_vec<bf16>(const u32x4 &a, const u32x4 &b, float acc) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, vec_word(a, w)),
+                                              __builtin_bit_cast(bf16x2, vec_word(b, w)), acc, false);
+    return acc;
+}
+
 // The same copy in two halves, so that the global loads of a tile can be in flight while the
 // workgroup computes on the previous one: tile_fetch issues them into registers, tile_put
 // writes the registers into LDS.  NT threads share a [ROWS x COLS] tile.
