@@ -58,6 +58,8 @@ int check_params(const osdn_params *p, bool need_chunks) {
         if (p->B > 65535 || p->H > 65535) return OSDN_ERR_SHAPE;
     }
     if ((long long)p->B * p->H > 0x7fffffffLL / 64) return OSDN_ERR_SHAPE;
+    // the kernels address the 64 token rows of a chunk with 32-bit byte offsets
+    if ((long long)p->H * (p->K > p->V ? p->K : p->V) * 4 * C >= (1LL << 32)) return OSDN_ERR_SHAPE;
     if (!(p->eta >= 0.f) || !(p->eps > 0.f) || !std::isfinite(p->eta) || !std::isfinite(p->eps) ||
         !std::isfinite(p->scale) || std::isnan(p->d_min) || std::isnan(p->d_max))
         return OSDN_ERR_PARAM;

@@ -465,10 +465,17 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         // (1) dR = T^T dE, rows j = 16*rb.. ; (2) R0 = V - gamma . (K S^T), same rows
         {
             const int k0 = (rb * 16) / KS * KS;         // T[i][j] = 0 for i < j
-            f32x4 dr[NVW], ks[NVW];
+            f32x4 dr[NVW], ks[NVW];             // the first product of each takes 0 as its addend
+            {
+                typename Mfma<T>::Frag ft = Mfma<T>::template load<false>(Tt + k0 * LDC + rb * 16, LDC, lane);
 #pragma unroll
-            for (int q = 0; q < NVW; ++q) { dr[q] = f32x4{0.f, 0.f, 0.f, 0.f}; ks[q] = f32x4{0.f, 0.f, 0.f, 0.f}; }
-            for (int kk = k0; kk < C; kk += KS) {
+                for (int q = 0; q < NVW; ++q) {
+                    const int vt = (wave % WPR) * NVW + q;
+                    typename Mfma<T>::Frag fe = Mfma<T>::template load<true>(dEts + vt * 16 * LDC + k0, LDC, lane);
+                    dr[q] = Mfma<T>::mma(ft, fe, f32x4{0.f, 0.f, 0.f, 0.f});
+                }
+            }
+            for (int kk = k0 + KS; kk < C; kk += KS) {
                 typename Mfma<T>::Frag ft = Mfma<T>::template load<false>(Tt + kk * LDC + rb * 16, LDC, lane);
 #pragma unroll
                 for (int q = 0; q < NVW; ++q) {
@@ -477,13 +484,14 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
                     dr[q] = Mfma<T>::mma(ft, fe, dr[q]);
                 }
             }
+#pragma unroll
             for (int kk = 0; kk < K; kk += KS) {
                 typename Mfma<T>::Frag fk = Mfma<T>::template load<true>(Ks + rb * 16 * LDK + kk, LDK, lane);
 #pragma unroll
                 for (int q = 0; q < NVW; ++q) {
                     const int vt = (wave % WPR) * NVW + q;
                     typename Mfma<T>::Frag fs = Mfma<T>::template load<true>(Ss + vt * 16 * LDK + kk, LDK, lane);
-                    ks[q] = Mfma<T>::mma(fk, fs, ks[q]);
+                    ks[q] = Mfma<T>::mma(fk, fs, kk == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : ks[q]);
                 }
             }
 #pragma unroll
@@ -583,9 +591,8 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         if (idx < 10) {
             const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
             const int jb = idx - (ib * (ib + 1)) / 2;
-            f32x4 kk = {0.f, 0.f, 0.f, 0.f}, qk = {0.f, 0.f, 0.f, 0.f};
-            mma_tile<T, true, true>(kk, Ks + ib * 16 * LDK, LDK, Kts + jb * 16 * LDK, LDK, K, lane);
-            mma_tile<T, true, true>(qk, Qs + ib * 16 * LDK, LDK, Kts + jb * 16 * LDK, LDK, K, lane);
+            const f32x4 kk = mma_tile0<T, true, true>(Ks + ib * 16 * LDK, LDK, Kts + jb * 16 * LDK, LDK, K, lane);
+            const f32x4 qk = mma_tile0<T, true, true>(Qs + ib * 16 * LDK, LDK, Kts + jb * 16 * LDK, LDK, K, lane);
             f32x4 ca, cp;
             float colx = 0.f;
 #pragma unroll
@@ -633,19 +640,28 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
 #pragma unroll
         for (int iq = 0; iq < IBN; ++iq) {
             const int ib = ib0 + iq;
-            f32x4 aq = {0.f, 0.f, 0.f, 0.f}, ak = {0.f, 0.f, 0.f, 0.f}, at = {0.f, 0.f, 0.f, 0.f};
+            f32x4 aq, ak, at;                   // the first product of each takes 0 as its addend
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             // cP K~ and cA K~: contraction over j <= i
             const int kd = min(C, ((ib + 1) * 16 + KS - 1) / KS * KS);
             for (int kk = 0; kk < kd; kk += KS) {
                 typename Mfma<T>::Frag fk = Mfma<T>::template load<false>(Kts + kk * LDK + ct, LDK, lane);
                 typename Mfma<T>::Frag fp = Mfma<T>::template load<true>(cPs + ib * 16 * LDC + kk, LDC, lane);
                 typename Mfma<T>::Frag fa = Mfma<T>::template load<true>(cAs + ib * 16 * LDC + kk, LDC, lane);
-                aq = Mfma<T>::mma(fp, fk, aq);
-                ak = Mfma<T>::mma(fa, fk, ak);
+                if (kk == 0) { aq = Mfma<T>::mma(fp, fk, zero); ak = Mfma<T>::mma(fa, fk, zero); }
+                else { aq = Mfma<T>::mma(fp, fk, aq); ak = Mfma<T>::mma(fa, fk, ak); }
             }
             // cA^T K + cP^T Q: rows j = 16*ib.., contraction over i >= j
             const int k0 = (ib * 16) / KS * KS;
-            for (int kk = k0; kk < C; kk += KS) {
+            {
+                typename Mfma<T>::Frag fat = Mfma<T>::template load<false>(cAs + k0 * LDC + ib * 16, LDC, lane);
+                typename Mfma<T>::Frag fpt = Mfma<T>::template load<false>(cPs + k0 * LDC + ib * 16, LDC, lane);
+                typename Mfma<T>::Frag fkk = Mfma<T>::template load<false>(Ks + k0 * LDK + ct, LDK, lane);
+                typename Mfma<T>::Frag fqq = Mfma<T>::template load<false>(Qs + k0 * LDK + ct, LDK, lane);
+                at = Mfma<T>::mma(fat, fkk, zero);
+                at = Mfma<T>::mma(fpt, fqq, at);
+            }
+            for (int kk = k0 + KS; kk < C; kk += KS) {
                 typename Mfma<T>::Frag fat = Mfma<T>::template load<false>(cAs + kk * LDC + ib * 16, LDC, lane);
                 typename Mfma<T>::Frag fpt = Mfma<T>::template load<false>(cPs + kk * LDC + ib * 16, LDC, lane);
                 typename Mfma<T>::Frag fkk = Mfma<T>::template load<false>(Ks + kk * LDK + ct, LDK, lane);
@@ -665,9 +681,10 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
                 if (GV) dgc = __builtin_fmaf(ktv, dKr[iq][r], dgc);
                 tc[iq][r] = __builtin_fmaf(gq, qv, __builtin_fmaf(gk, kv, -(gr * ktv)));
                 trs = __builtin_fmaf(gr, ktv, trs);
-                dq_g[(size_t)i * tstride * K + c] = from_f32<T>(aq[r] + gq);
-                dk_g[(size_t)i * tstride * K + c] = from_f32<T>(ak[r] + gk);
-                dkt_g[(size_t)i * tstride * K + c] = from_f32<T>(at[r] + gr);
+                const uint32_t go = ((uint32_t)i * (uint32_t)(tstride * K) + (uint32_t)c) * (uint32_t)sizeof(T);
+                *reinterpret_cast<T *>(reinterpret_cast<char *>(dq_g) + go) = from_f32<T>(aq[r] + gq);
+                *reinterpret_cast<T *>(reinterpret_cast<char *>(dk_g) + go) = from_f32<T>(ak[r] + gk);
+                *reinterpret_cast<T *>(reinterpret_cast<char *>(dkt_g) + go) = from_f32<T>(at[r] + gr);
             }
         }
     }

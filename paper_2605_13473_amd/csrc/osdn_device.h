@@ -83,6 +83,21 @@ template <> struct Mfma<bf16> {
     }
 };
 
+// A(16 x kdim) * B(16 x kdim)^T, kdim >= one MFMA step: the first product takes the constant 0
+// as its addend (an operand of the instruction), so no accumulator has to be cleared
+template <typename T, bool A_KC, bool B_KC>
+__device__ __forceinline__ f32x4 mma_tile0(const T *A, int lda, const T *B, int ldb, int kdim, int lane) {
+    constexpr int KS = Mfma<T>::KSTEP;
+    f32x4 acc = Mfma<T>::mma(Mfma<T>::template load<A_KC>(A, lda, lane), Mfma<T>::template load<B_KC>(B, ldb, lane),
+                             f32x4{0.f, 0.f, 0.f, 0.f});
+    for (int k0 = KS; k0 < kdim; k0 += KS) {
+        typename Mfma<T>::Frag a = Mfma<T>::template load<A_KC>(A_KC ? A + k0 : A + k0 * lda, lda, lane);
+        typename Mfma<T>::Frag b = Mfma<T>::template load<B_KC>(B_KC ? B + k0 : B + k0 * ldb, ldb, lane);
+        acc = Mfma<T>::mma(a, b, acc);
+    }
+    return acc;
+}
+
 // acc(16x16) += A(16 x kdim) * B(16 x kdim)^T ; A, B point at (row 0, k 0) of their tiles
 template <typename T, bool A_KC, bool B_KC>
 __device__ __forceinline__ void mma_tile(f32x4 &acc, const T *A, int lda, const T *B, int ldb,
@@ -165,6 +180,20 @@ template <> __device__ __forceinline__ float vec_get<bf16>(const u32x4 &v, int e
     return __builtin_bit_cast(float, (e & 1) ? (w & 0xffff0000u) : (w << 16));
 }
 
+// A tile in global memory is addressed as a wavefront-uniform base pointer plus a 32-bit byte
+// offset per lane (one address register per access instead of a 64-bit computation each; the
+// library only accepts shapes whose tiles span less than 4 GB).
+template <typename T>
+__device__ __forceinline__ const u32x4 *tile_vec(const T *g, size_t g_ld, int r, int c) {
+    const uint32_t off = ((uint32_t)r * (uint32_t)g_ld + (uint32_t)c) * (uint32_t)sizeof(T);
+    return reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(g) + off);
+}
+template <typename T>
+__device__ __forceinline__ u32x4 *tile_vec(T *g, size_t g_ld, int r, int c) {
+    const uint32_t off = ((uint32_t)r * (uint32_t)g_ld + (uint32_t)c) * (uint32_t)sizeof(T);
+    return reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(g) + off);
+}
+
 // copy a [rows x cols] tile of T from global (row stride g_ld elements) into LDS (row
 // stride s_ld), 16 bytes per thread and step; cols must be a multiple of 16/sizeof(T)
 template <typename T>
@@ -174,8 +203,7 @@ __device__ __forceinline__ void load_tile(T *s, int s_ld, const T *g, size_t g_l
     const int vpr = cols / VN;
     for (int i = tid; i < rows * vpr; i += nthreads) {
         const int r = i / vpr, c = (i % vpr) * VN;
-        *reinterpret_cast<u32x4 *>(s + r * s_ld + c) =
-            *reinterpret_cast<const u32x4 *>(g + (size_t)r * g_ld + c);
+        *reinterpret_cast<u32x4 *>(s + r * s_ld + c) = *tile_vec(g, g_ld, r, c);
     }
 }
 template <typename T>
@@ -185,8 +213,7 @@ __device__ __forceinline__ void store_tile_global(T *g, size_t g_ld, const T *s,
     const int vpr = cols / VN;
     for (int i = tid; i < rows * vpr; i += nthreads) {
         const int r = i / vpr, c = (i % vpr) * VN;
-        *reinterpret_cast<u32x4 *>(g + (size_t)r * g_ld + c) =
-            *reinterpret_cast<const u32x4 *>(s + r * s_ld + c);
+        *tile_vec(g, g_ld, r, c) = *reinterpret_cast<const u32x4 *>(s + r * s_ld + c);
     }
 }
 
@@ -229,7 +256,7 @@ struct TileRegs {
 #pragma unroll
         for (int m = 0; m < NV; ++m) {
             const int i = tid + m * NT_, r = i / VPR, c = (i % VPR) * VN;
-            if (TOTAL % NT_ == 0 || i < TOTAL) v[m] = *reinterpret_cast<const u32x4 *>(g + (size_t)r * g_ld + c);
+            if (TOTAL % NT_ == 0 || i < TOTAL) v[m] = *tile_vec(g, g_ld, r, c);
         }
     }
     __device__ __forceinline__ void put(T *s, int s_ld, int tid) const {
