@@ -42,7 +42,7 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     // scratch: A (fp32) | (I + A)^-1 (fp32).  A's space later holds
     // T diag(beta gamma); the rest doubles as the staging tile for the transposed outputs.
     constexpr int STAGE_F = (K * LDC * (int)sizeof(T) + 3) / 4;
-    constexpr int TI_F = C * LDF;
+    constexpr int TI_F = C * LDF + C;               // (I + A)^-1 and one row of column scalars
     constexpr int TW_F = C * LDC * (int)sizeof(T) / 4;
     constexpr int AF_F = ((C * LDF > TW_F ? C * LDF : TW_F) + 3) & ~3;
     __shared__ __attribute__((aligned(16))) float scratch[AF_F + (TI_F > STAGE_F ? TI_F : STAGE_F)];
@@ -136,8 +136,7 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     for (int idx = wave; idx < 10; idx += NW) {
         const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
         const int jb = idx - (ib * (ib + 1)) / 2;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        mma_tile<T, true, true>(acc, X1 + ib * 16 * LDK, LDK, X2 + jb * 16 * LDK, LDK, K, lane);
+        const f32x4 acc = mma_tile0<T, true, true>(X1 + ib * 16 * LDK, LDK, X2 + jb * 16 * LDK, LDK, K, lane);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int i = ib * 16 + acc_row(lane, r), j = jb * 16 + acc_col(lane);
@@ -167,6 +166,9 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     store_tile_global(static_cast<T *>(a.Ktr) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, CP_);
     __syncthreads();                // the staging tile is free again: (I + A)^-1 is built in its place
 
+    // beta_j gamma_j, once per column (behind (I + A)^-1)
+    float *BGs = Ti + C * LDF;
+    if (wave == NW - 1) BGs[lane] = Bs[lane] * __expf(Gs[lane]);
     // ---- T = (I + A)^-1 in fp32, blocked ----
     ut_inverse64<LDF>(Af, Ti, Xs, wave, lane);
     OSDN_CTICK(2)
@@ -177,17 +179,18 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
         T *tg = static_cast<T *>(a.Tm) + bhn * C * C;
         for (int v = tid; v < C * C / VN; v += CP_) {
             const int i = v / (C / VN), j0 = (v % (C / VN)) * VN;
-            float plain[VN];
+            float plain[VN], tu[VN], tw[VN];
 #pragma unroll
             for (int e = 0; e < VN; ++e) {
                 const int j = j0 + e;
                 const float t = j <= i ? Ti[i * LDF + j] : 0.f;
-                const float bj = Bs[j];
                 plain[e] = t;
-                Tu[i * LDC + j] = from_f32<T>(t * bj);
-                Tw[i * LDC + j] = from_f32<T>(t * bj * __expf(Gs[j]));
+                tu[e] = t * Bs[j];
+                tw[e] = t * BGs[j];
             }
             store_vec_t(tg + i * C + j0, plain);
+            store_vec_t(Tu + i * LDC + j0, tu);
+            store_vec_t(Tw + i * LDC + j0, tw);
         }
     }
     __syncthreads();                // Ti is dead from here on: its space is the staging tile again
@@ -198,9 +201,8 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
         for (int t = wave; t < (K / 16) * 4; t += NW) {
             const int nb = t >> 2, ib = t & 3;
             {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
                 const int kdim = min(C, ((ib + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
-                mma_tile<T, true, false>(acc, Tw + ib * 16 * LDC, LDC, X1 + nb * 16, LDK, kdim, lane);
+                f32x4 acc = mma_tile0<T, true, false>(Tw + ib * 16 * LDC, LDC, X1 + nb * 16, LDK, kdim, lane);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[r] = -acc[r];
                 store_tile_t(stage + nb * 16 * LDC + ib * 16, LDC, acc, lane);
@@ -221,9 +223,8 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
 #pragma unroll
         for (int iq = 0; iq < 2; ++iq) {
             const int ib = (wave >> 2) * 2 + iq, wb = wave & 3;        // 16 columns of V (wb), two row blocks
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
             const int kdim = min(C, ((ib + 1) * 16 + Mfma<T>::KSTEP - 1) / Mfma<T>::KSTEP * Mfma<T>::KSTEP);
-            mma_tile<T, true, false>(acc, Tu + ib * 16 * LDC, LDC, X1 + wb * 16, LDC, kdim, lane);
+            const f32x4 acc = mma_tile0<T, true, false>(Tu + ib * 16 * LDC, LDC, X1 + wb * 16, LDC, kdim, lane);
             store_tile_t(stage + wb * 16 * LDC + ib * 16, LDC, acc, lane);
         }
         __syncthreads();
