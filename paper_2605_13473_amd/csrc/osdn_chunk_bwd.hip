@@ -350,6 +350,7 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     __shared__ __attribute__((aligned(16))) T Ks[C * LDK];
     __shared__ __attribute__((aligned(16))) T Tt[C * LDC];       // T; after the walk: cA
     __shared__ float Gs[C], Bs[C];
+    __shared__ float Egs[C], Ers[C];                     // gamma_i = e^{G_i} and rho_i = e^{G_C - G_i}, once per row
     __shared__ float red[4 * C];                         // [4][64] partial sums across tiles
     __shared__ float red2[4 * C];
     __shared__ float red3[4 * C];
@@ -387,7 +388,10 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     if (wave == 0) {
         const size_t th = tok0 + (size_t)lane * tstride;
         const float g = a.log_alpha ? a.log_alpha[th] : 0.f;
-        Gs[lane] = wave_cumsum(g, lane);
+        const float G = wave_cumsum(g, lane);
+        Gs[lane] = G;
+        Egs[lane] = __expf(G);
+        Ers[lane] = __expf(lane_bcast63(G) - G);
         Bs[lane] = a.beta[th];
     }
     load_tile(Ks, LDK, static_cast<const T *>(a.k) + tok0 * K, tstride * K, C, K, tid, PT_);
@@ -446,7 +450,7 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         OSDN_PTICK(0)
         if (v0 == 0) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) gam_rb[r] = __expf(Gs[rb * 16 + acc_row(lane, r)]);
+            for (int r = 0; r < 4; ++r) gam_rb[r] = Egs[rb * 16 + acc_row(lane, r)];
         }
         // <dS', S> over this slab (with per-channel gates: column by column, thread tid keeps column tid % K)
         if (GV) {
@@ -672,7 +676,7 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int i = ib * 16 + acc_row(lane, r), c = ct + acc_col(lane);
-                const float gam = __expf(Gs[i]), rho = __expf(Gs[C - 1] - Gs[i]);
+                const float gam = Egs[i], rho = Ers[i];
                 const float gq = a.scale * gam * dQg[iq][r];         // gamma . d(gamma Q)
                 const float gk = -Bs[i] * gam * dKg[iq][r];           // gamma . d(gamma K)
                 const float gr = (GV ? gcv : rho) * dKr[iq][r];       // rho . d(rho K~)

@@ -320,6 +320,10 @@ __device__ __forceinline__ float wave_sum(float x) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
+// the value of lane 63, in every lane
+__device__ __forceinline__ float lane_bcast63(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
 // inclusive prefix sum over the 64 lanes of a wave
 __device__ __forceinline__ float wave_cumsum(float x, int lane) {
 #pragma unroll
