@@ -113,8 +113,7 @@ __global__ __launch_bounds__(BL_) void bwd_local_kernel(ChunkArgs a) {
 #pragma unroll
         for (int vq = 0; vq < 2; ++vq) {
             const int vt = wh * 2 + vq;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            mma_tile<T, true, true>(acc, PT + wb * 16 * LDC + k0, LDC, dOt + vt * 16 * LDC + k0, LDC, C - k0, lane);
+            f32x4 acc = mma_tile0<T, true, true>(PT + wb * 16 * LDC + k0, LDC, dOt + vt * 16 * LDC + k0, LDC, C - k0, lane);
             store_tile_t(Os + vt * 16 * LDC + wb * 16, LDC, acc, lane);
         }
         __syncthreads();
@@ -272,8 +271,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
             // ---- phase B: dE = dEl + (rho . K~) dS'^T (rows 16*wave ..), kept transposed ----
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-                mma_tile<T, false, true>(acc, &Krt[buf][wave * 16], LDC, dSb + vt * 16 * LDK, LDK, K, lane);
+                f32x4 acc = mma_tile0<T, false, true>(&Krt[buf][wave * 16], LDC, dSb + vt * 16 * LDK, LDK, K, lane);
                 const T *ep = &dEls[buf][(vt * 16 + acc_col(lane)) * LDC + wave * 16 + acc_row(lane, 0)];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[r] += to_f32(ep[r]);

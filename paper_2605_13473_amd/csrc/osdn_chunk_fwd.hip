@@ -403,8 +403,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
             // ---- phase B: E = U - W S^T (rows 16*wave ..), kept transposed ----
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-                mma_tile<T, false, true>(acc, &Wts[buf][wave * 16], LDC, Sb + vt * 16 * LDK, LDK, K, lane);
+                f32x4 acc = mma_tile0<T, false, true>(&Wts[buf][wave * 16], LDC, Sb + vt * 16 * LDK, LDK, K, lane);
                 const T *up = &Uts[buf][(vt * 16 + acc_col(lane)) * LDC + wave * 16 + acc_row(lane, 0)];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[r] += to_f32(up[r]);         // U + (-W) S^T
