@@ -29,6 +29,8 @@ namespace osdn {
 // chunk's total decay per channel for the state and output kernels.  1 / Gamma grows like
 // e^{|G|}: the cumulative log-decay of a channel inside a chunk has to stay above about -80.
 constexpr int CP_ = 512;        // threads of a chunk_prep workgroup (8 wavefronts)
+constexpr int CP_TASKS = 2;     // chunks per workgroup of a large launch
+constexpr int CP_MIN_WGS = 2048;  // ... large: at least this many workgroups of one chunk each (four rounds of two per CU)
 template <typename T, int K, bool GV>
 __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     // K and K~ are read 16 bytes per lane along k (Gram matrix, transposes): 32 bytes of padding
@@ -54,11 +56,41 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     __shared__ float Gs[C], Bs[C];
     __shared__ float gCs[GV ? K : 1];                           // per-channel decay over the whole chunk
 
-    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // A workgroup builds `tasks` adjacent chunks one after the other: while it works on one, the
+    // K, K~ tiles and gates of the next are already on their way (a third of a chunk's time is the
+    // wait for its first loads otherwise).  The launcher asks for two only when the launch still
+    // fills the chip several times over: on a short segment the longer workgroups would only
+    // lengthen the time to its last chunk.
+    const int tasks = (int)gridDim.x < a.n1 - a.n0 ? CP_TASKS : 1;
+    const int n_first = a.n0 + blockIdx.x * tasks, h = blockIdx.y, b = blockIdx.z;
+    const int ntask = min(tasks, a.n1 - n_first);
+    int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const size_t tstride = a.H;                                           // tokens are H rows apart
+    TileRegs<T, C, K, CP_> r_K, r_Kt;
+    TileRegs<T, C, C, CP_> r_V;
+    float r_g = 0.f, r_b = 0.f;
+#define OSDN_CP_ISSUE(n_, with_v_)                                                               \
+    {                                                                                            \
+        const size_t tok_ = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                      \
+        r_K.fetch(static_cast<const T *>(a.k) + tok_ * K, tstride * K, tid);                     \
+        r_Kt.fetch(static_cast<const T *>(a.kt) + tok_ * K, tstride * K, tid);                   \
+        if (with_v_) r_V.fetch(static_cast<const T *>(a.v) + tok_ * a.V, tstride * a.V, tid);    \
+        if (wave == 0) {                                                                         \
+            const size_t th = tok_ + (size_t)lane * tstride;                                     \
+            r_g = (!GV && a.log_alpha) ? a.log_alpha[th] : 0.f;   /* GV: the gates go into the operands */ \
+            r_b = a.beta[th];                                                                    \
+        }                                                                                        \
+    }
+    OSDN_CP_ISSUE(n_first, true)
+#pragma unroll 1
+    for (int task = 0; task < ntask; ++task) {
+    // (the thread index is made opaque once per chunk: otherwise every lane address of the body is
+    // computed ahead of the loop and kept in registers, three times the registers of one chunk)
+    asm volatile("" : "+v"(tid));
+    wave = __builtin_amdgcn_readfirstlane(tid >> 6); lane = tid & 63;
+    const int n = n_first + task;
     const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;      // (b, first token, h)
-    const size_t tstride = a.H;                                           // tokens are H rows apart
 
 #ifdef OSDN_DIAG
     long long cph[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, clast = clock64();
@@ -66,18 +98,16 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
 #else
 #define OSDN_CTICK(j)
 #endif
+    if (task > 0) __syncthreads();      // the previous chunk is through with every LDS tile
     if (wave == 0) {
-        const size_t th = tok0 + (size_t)lane * tstride;
-        const float g = (!GV && a.log_alpha) ? a.log_alpha[th] : 0.f;      // GV: the gates go into the operands
-        Gs[lane] = wave_cumsum(g, lane);
-        Bs[lane] = a.beta[th];
+        Gs[lane] = wave_cumsum(r_g, lane);
+        Bs[lane] = r_b;
     }
-    load_tile(X1, LDK, static_cast<const T *>(a.k) + tok0 * K, tstride * K, C, K, tid, CP_);
-    load_tile(X2, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, CP_);
-    // the first slab of V travels through registers while the chunk's T is being built
+    r_K.put(X1, LDK, tid);
+    r_Kt.put(X2, LDK, tid);
+    // the first slab of V stays in registers while the chunk's T is being built
     const T *vg = static_cast<const T *>(a.v) + tok0 * a.V;
-    TileRegs<T, C, C, CP_> r_V;
-    r_V.fetch(vg, tstride * a.V, tid);
+    if (task + 1 < ntask) OSDN_CP_ISSUE(n + 1, false)
     __syncthreads();
     if (GV) {
         // cumulative log-decay of every channel, G [64 x K] in fp32, in the scratch space (not
@@ -219,6 +249,8 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
         __syncthreads();
         r_V.put(X1, LDC, tid);
         if (v0 + C < a.V) r_V.fetch(vg + v0 + C, tstride * a.V, tid);
+        else if (task + 1 < ntask)          // the next chunk's first slab
+            r_V.fetch(static_cast<const T *>(a.v) + (tok0 + (size_t)C * a.H) * a.V, tstride * a.V, tid);
         __syncthreads();
 #pragma unroll
         for (int iq = 0; iq < 2; ++iq) {
@@ -232,9 +264,10 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     }
 #ifdef OSDN_DIAG
     OSDN_CTICK(6)
-    if (tid == 0 && blockIdx.x == 7 && blockIdx.y == 0 && blockIdx.z == 0)
+    if (tid == 0 && n == a.n0 + 7 && blockIdx.y == 0 && blockIdx.z == 0)
         for (int j = 0; j < 7; ++j) static_cast<T *>(a.Tm)[bhn * C * C + j] = from_f32<T>((float)cph[j] / 64.f);
 #endif
+    }   // task
 }
 
 // ------------------------------------------------------------- state_fwd ----
@@ -535,7 +568,9 @@ __global__ __launch_bounds__(OT_) void output_fwd_kernel(ChunkArgs a) {
 // -------------------------------------------------------------- launchers ----
 template <typename T, bool GV>
 static int launch_prep_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.n1 - a.n0, a.H, a.B), block(CP_);
+    const int chunks = a.n1 - a.n0;
+    const bool pairs = chunks >= 2 && (long long)chunks * a.H * a.B >= CP_MIN_WGS;
+    dim3 grid(pairs ? (chunks + CP_TASKS - 1) / CP_TASKS : chunks, a.H, a.B), block(CP_);
     if (GV && (!a.log_alpha || !a.Qg || !a.Kg || !a.Kd || !a.gamC)) return -1;
     if (a.K == 64) hipLaunchKernelGGL((chunk_prep_kernel<T, 64, GV>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((chunk_prep_kernel<T, 128, GV>), grid, block, 0, st, a);

@@ -56,6 +56,15 @@ def test_many_chains_few_chunks(T):
     compare_backward(x, hp, False)
 
 
+def test_large_launch_of_chunk_prep():
+    """256 chains and 17 chunks: the second forward segment is a launch of more than 2048
+    chunk-heads, where a chunk_prep workgroup builds two chunks in a row (and, the count being
+    odd, the last one of every chain a single chunk)."""
+    B, T, H, K, V = 16, 64 * 17, 16, 64, 64
+    x = make_stress_inputs(B, T, H, K, V, seed=62, bf16=False, retention=0.0)
+    compare_forward(x, ob.Hyper(eta=0.5), False)
+
+
 @pytest.mark.parametrize("variant", ["ungated", "no_retention", "non_beta_aware", "no_projection",
                                      "eta_one_clamped", "defaults_null"])
 def test_variants_fwd_bwd_fp32(variant):
