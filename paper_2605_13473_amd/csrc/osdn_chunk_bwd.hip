@@ -328,7 +328,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
 // GV: one state gate per key channel.  The kernel then runs on the folded operands with no
 // scalar gate (log_alpha null); the write rows carry the chunk's decay per channel instead of
 // rho, and dL/d(that decay) is collected per channel.
-template <typename T, int K, bool GV, int PW_>
+template <typename T, int K, bool GV, int PW_, bool PAIR>
 __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     constexpr int PT_ = PW_ * 64;
     constexpr int PAD = sizeof(T) == 2 ? 16 : Pad<T>::v, LDK = K + PAD, LDC = C + PAD;   // bf16: rows 32 bytes apart modulo 128
@@ -374,26 +374,69 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     float *pq = reinterpret_cast<float *>(cPs + C * LDC);        // [PW_][64]
     T *cAs = Tt;                        // [64][LDC]
 
-    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // PAIR (large launches, bf16): a workgroup does two adjacent chunks one after the other (the
+    // launcher halves the grid): the first loads of the second chunk (gates, K, T, the first slab)
+    // are issued when the walk of the first is over and arrive while its results are finished.
+    constexpr int tasks = PAIR ? 2 : 1;
+    const int n_first = a.n0 + blockIdx.x * tasks, h = blockIdx.y, b = blockIdx.z;
+    const int ntask = min(tasks, a.n1 - n_first);
+    int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const size_t tstride = a.H;
+    // the slab tiles travel through registers: the next slab (after the last one: Q and K~) is
+    // fetched while the workgroup computes on the current one
+    TileRegs<T, C, VB, PT_> r_dO, r_V;
+    TileRegs<T, VB, C, PT_> r_Et, r_dEt;
+    TileRegs<T, VB, K, PT_> r_S, r_dS;
+    TileRegs<T, C, K, PT_> r_Q, r_Kt, r_Kn;
+    TileRegs<T, C, C, PT_> r_Tn;
+    float r_g = 0.f, r_b = 0.f;
+#define OSDN_BP_FETCH(tok_, bhn_, v0_)                                                           \
+    {                                                                                            \
+        r_dO.fetch(static_cast<const T *>(a.dO) + (tok_) * a.V + (v0_), tstride * a.V, tid);     \
+        r_V.fetch(static_cast<const T *>(a.v) + (tok_) * a.V + (v0_), tstride * a.V, tid);       \
+        r_Et.fetch(static_cast<const T *>(a.Et) + ((bhn_) * a.V + (v0_)) * C, (size_t)C, tid);   \
+        r_dEt.fetch(static_cast<const T *>(a.dEt) + ((bhn_) * a.V + (v0_)) * C, (size_t)C, tid); \
+        r_S.fetch(static_cast<const T *>(a.S_ckpt) + ((bhn_) * a.V + (v0_)) * K, (size_t)K, tid); \
+        r_dS.fetch(static_cast<const T *>(a.dS_ckpt) + ((bhn_) * a.V + (v0_)) * K, (size_t)K, tid); \
+    }
+    // gates, K and T of a chunk, then its first slab
+#define OSDN_BP_ISSUE(n_)                                                                        \
+    {                                                                                            \
+        const size_t bhn_i = ((size_t)b * a.H + h) * a.N + (n_);                                 \
+        const size_t tok_i = ((size_t)b * a.T + (size_t)(n_) * C) * a.H + h;                     \
+        if (wave == 0) {                                                                         \
+            const size_t th = tok_i + (size_t)lane * tstride;                                    \
+            r_g = a.log_alpha ? a.log_alpha[th] : 0.f;                                           \
+            r_b = a.beta[th];                                                                    \
+        }                                                                                        \
+        r_Kn.fetch(static_cast<const T *>(a.k) + tok_i * K, tstride * K, tid);                   \
+        r_Tn.fetch(static_cast<const T *>(a.Tm) + bhn_i * C * C, (size_t)C, tid);                \
+        OSDN_BP_FETCH(tok_i, bhn_i, 0)                                                           \
+    }
+    OSDN_BP_ISSUE(n_first)
+#pragma unroll 1
+    for (int task = 0; task < ntask; ++task) {
+    // (the thread index is made opaque once per chunk, so that the lane addresses of the body
+    // are not all computed ahead of the loop and kept in registers)
+    asm volatile("" : "+v"(tid));
+    wave = __builtin_amdgcn_readfirstlane(tid >> 6); lane = tid & 63;
+    const int n = n_first + task;
     const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
-    const size_t tstride = a.H;
     const int ct = (wave % NCT) * 16;   // this wave's column tile of the [64 x K] results ...
     const int ib0 = (wave / NCT) * IBN; // ... and its first row block
     const bool has_ct = wave < NCT * WPC;
 
+    if (task > 0) __syncthreads();      // the previous chunk is through with every LDS tile
     if (wave == 0) {
-        const size_t th = tok0 + (size_t)lane * tstride;
-        const float g = a.log_alpha ? a.log_alpha[th] : 0.f;
-        const float G = wave_cumsum(g, lane);
+        const float G = wave_cumsum(r_g, lane);
         Gs[lane] = G;
         Egs[lane] = __expf(G);
         Ers[lane] = __expf(lane_bcast63(G) - G);
-        Bs[lane] = a.beta[th];
+        Bs[lane] = r_b;
     }
-    load_tile(Ks, LDK, static_cast<const T *>(a.k) + tok0 * K, tstride * K, C, K, tid, PT_);
-    load_tile(Tt, LDC, static_cast<const T *>(a.Tm) + bhn * C * C, (size_t)C, C, C, tid, PT_);
+    r_Kn.put(Ks, LDK, tid);
+    r_Tn.put(Tt, LDC, tid);
 
     // accumulators over the walk
     f32x4 dP[NLT], dA[NLT];             // the lower tiles idx = wave, wave + PW_ (< 10)
@@ -411,22 +454,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     const int rb = wave / WPR;          // row block of steps (1), (2)
     float gam_rb[4] = {1.f, 1.f, 1.f, 1.f};   // gamma of this lane's four rows there (set once G is in LDS)
 
-    // the slab tiles travel through registers: the next slab (after the last one: Q and K~) is
-    // fetched while the workgroup computes on the current one
-    TileRegs<T, C, VB, PT_> r_dO, r_V;
-    TileRegs<T, VB, C, PT_> r_Et, r_dEt;
-    TileRegs<T, VB, K, PT_> r_S, r_dS;
-    TileRegs<T, C, K, PT_> r_Q, r_Kt;
-#define OSDN_BP_FETCH(v0_)                                                                        \
-    {                                                                                            \
-        r_dO.fetch(static_cast<const T *>(a.dO) + tok0 * a.V + (v0_), tstride * a.V, tid);       \
-        r_V.fetch(static_cast<const T *>(a.v) + tok0 * a.V + (v0_), tstride * a.V, tid);         \
-        r_Et.fetch(static_cast<const T *>(a.Et) + (bhn * a.V + (v0_)) * C, (size_t)C, tid);      \
-        r_dEt.fetch(static_cast<const T *>(a.dEt) + (bhn * a.V + (v0_)) * C, (size_t)C, tid);    \
-        r_S.fetch(static_cast<const T *>(a.S_ckpt) + (bhn * a.V + (v0_)) * K, (size_t)K, tid);   \
-        r_dS.fetch(static_cast<const T *>(a.dS_ckpt) + (bhn * a.V + (v0_)) * K, (size_t)K, tid); \
-    }
-    OSDN_BP_FETCH(0)
 #ifdef OSDN_DIAG
     long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
 #define OSDN_PTICK(j) { const long long now_ = clock64(); tph[j] += now_ - tlast; tlast = now_; }
@@ -439,7 +466,7 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         r_Et.put(Ets, LDC, tid); r_dEt.put(dEts, LDC, tid);
         r_S.put(Ss, LDK, tid); r_dS.put(dSs, LDK, tid);
         if (v0 + VB < a.V) {
-            OSDN_BP_FETCH(v0 + VB)
+            OSDN_BP_FETCH(tok0, bhn, v0 + VB)
         } else {
             r_Q.fetch(static_cast<const T *>(a.q) + tok0 * K, tstride * K, tid);
             r_Kt.fetch(static_cast<const T *>(a.kt) + tok0 * K, tstride * K, tid);
@@ -565,6 +592,7 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     // ---- after the walk: Q, K~ into the pool ----
     r_Q.put(Qs, LDK, tid);
     r_Kt.put(Kts, LDK, tid);
+    if (task + 1 < ntask) OSDN_BP_ISSUE(n + 1)
     {                                                   // upper triangle of cA, cP is zero
         constexpr int VN = 16 / sizeof(T);
         for (int v = tid; v < C * C / VN; v += PT_) {
@@ -741,9 +769,10 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     }
 #ifdef OSDN_DIAG
     OSDN_PTICK(7)
-    if (tid == 0 && blockIdx.x == 5 && blockIdx.y == 0 && blockIdx.z == 0 && a.dlog_alpha)
+    if (tid == 0 && n == a.n0 + 5 && blockIdx.y == 0 && blockIdx.z == 0 && a.dlog_alpha)
         for (int j = 0; j < 8; ++j) a.dlog_alpha[tok0 + (size_t)j * tstride] = (float)tph[j];
 #endif
+    }   // task
 }
 
 // -------------------------------------------------------------- launchers ----
@@ -771,14 +800,25 @@ int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
     if (a.gate_vec) return bf16_io ? launch_chain_t<bf16, true>(a, st) : launch_chain_t<float, true>(a, st);
     return bf16_io ? launch_chain_t<bf16, false>(a, st) : launch_chain_t<float, false>(a, st);
 }
+constexpr int BP_MIN_WGS = 2048;
 template <typename T, bool GV>
 static int launch_post_t(const ChunkArgs &a, hipStream_t st) {
     constexpr int PW = 8;           // wavefronts per workgroup (16 was measured for bf16: the kernel then
                                     // has to fit 128 registers, spills, and takes twice as long)
-    dim3 grid(a.n1 - a.n0, a.H, a.B), block(PW * 64);
+    // two chunks per workgroup when the launch still fills the chip many times over (one workgroup per CU)
+    const int chunks = a.n1 - a.n0;
+    constexpr bool PAIRABLE = sizeof(T) == 2 && !GV;     // elsewhere the prefetch registers would spill
+    const bool pairs = PAIRABLE && chunks >= 2 && (long long)chunks * a.H * a.B >= BP_MIN_WGS;
+    dim3 grid(pairs ? (chunks + 1) / 2 : chunks, a.H, a.B), block(PW * 64);
     if (GV && (!a.gamC || !a.dgamC || a.log_alpha || a.dlog_alpha)) return -1;
-    if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64, GV, PW>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128, GV, PW>), grid, block, 0, st, a);
+    if (pairs) {
+        if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64, GV, PW, PAIRABLE>), grid, block, 0, st, a);
+        else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128, GV, PW, PAIRABLE>), grid, block, 0, st, a);
+        else return -1;
+        return 0;
+    }
+    if (a.K == 64) hipLaunchKernelGGL((bwd_post_kernel<T, 64, GV, PW, false>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((bwd_post_kernel<T, 128, GV, PW, false>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }

@@ -56,13 +56,17 @@ def test_many_chains_few_chunks(T):
     compare_backward(x, hp, False)
 
 
-def test_large_launch_of_chunk_prep():
-    """256 chains and 17 chunks: the second forward segment is a launch of more than 2048
-    chunk-heads, where a chunk_prep workgroup builds two chunks in a row (and, the count being
-    odd, the last one of every chain a single chunk)."""
+@pytest.mark.parametrize("bf16", [False, True])
+def test_large_launches_two_chunks_per_workgroup(bf16):
+    """256 chains and 17 chunks: the second segment of either pass is a launch of more than 2048
+    chunk-heads, where a chunk_prep workgroup (and, for bf16, a bwd_post workgroup) does two
+    chunks in a row with the second one's first loads prefetched; the counts are odd, so the
+    last workgroup of every chain has a single chunk."""
     B, T, H, K, V = 16, 64 * 17, 16, 64, 64
-    x = make_stress_inputs(B, T, H, K, V, seed=62, bf16=False, retention=0.0)
-    compare_forward(x, ob.Hyper(eta=0.5), False)
+    x = make_stress_inputs(B, T, H, K, V, seed=62, bf16=bf16, retention=0.0)
+    hp = ob.Hyper(eta=0.5)
+    compare_forward(x, hp, bf16)
+    compare_backward(x, hp, bf16)
 
 
 @pytest.mark.parametrize("variant", ["ungated", "no_retention", "non_beta_aware", "no_projection",
