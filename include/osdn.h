@@ -44,7 +44,8 @@
  *   - Supported shapes: chunk == 64; any T >= 1 (osdn_fwd/osdn_bwd pad a ragged last chunk
  *     inside the workspace with tokens that change nothing; osdn_precond_update needs
  *     T % 64 == 0 only when d_ckpt is asked for; 1 <= T <= 64 for osdn_step); K in {64, 128};
- *     V a multiple of 64 up to 512; B, H >= 1.  Anything else returns OSDN_ERR_SHAPE.
+ *     V a multiple of 64 up to 512; B, H >= 1 with H * max(K, V) < 2^24 (the 64 token rows of
+ *     a chunk are addressed with 32-bit byte offsets).  Anything else returns OSDN_ERR_SHAPE.
  */
 #ifndef OSDN_H
 #define OSDN_H

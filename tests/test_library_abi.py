@@ -38,7 +38,8 @@ def test_workspace_size_and_shape_validation():
     # a ragged length costs the padded copies of the caller's tensors on top
     q = ob.make_params(4, 4096 - 7, 16, 128, 128, True)
     assert ob.osdn_workspace_bytes(q, False) > fwd and ob.osdn_workspace_bytes(q, True) > bwd
-    for bad in (dict(T=0), dict(K=256), dict(K=96), dict(V=96), dict(chunk=32), dict(B=0)):
+    # H * max(K, V) must stay below 2^24 (32-bit byte offsets inside a chunk)
+    for bad in (dict(T=0), dict(K=256), dict(K=96), dict(V=96), dict(chunk=32), dict(B=0), dict(H=40000, V=512)):
         q = ob.make_params(1, 128, 1, 64, 64, False)
         for k, v in bad.items():
             setattr(q, k, v)
