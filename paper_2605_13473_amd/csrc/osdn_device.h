@@ -9,6 +9,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace osdn {
 
@@ -192,6 +193,18 @@ template <typename T>
 __device__ __forceinline__ u32x4 *tile_vec(T *g, size_t g_ld, int r, int c) {
     const uint32_t off = ((uint32_t)r * (uint32_t)g_ld + (uint32_t)c) * (uint32_t)sizeof(T);
     return reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(g) + off);
+}
+
+// The same for single elements: element at a 32-bit byte offset from a wavefront-uniform base,
+// and element `lane` of a wavefront-uniform row.
+template <typename U>
+__device__ __forceinline__ U &at_byte(U *base, uint32_t byte_off) {
+    using B = typename std::conditional<std::is_const<U>::value, const char, char>::type;
+    return *reinterpret_cast<U *>(reinterpret_cast<B *>(base) + byte_off);
+}
+template <typename U>
+__device__ __forceinline__ U &lane_elem(U *row, int lane_index) {
+    return at_byte(row, (uint32_t)lane_index * (uint32_t)sizeof(U));
 }
 
 // copy a [rows x cols] tile of T from global (row stride g_ld elements) into LDS (row

@@ -112,8 +112,8 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         const T *gp_ = static_cast<const T *>(a.dkt) + tokc_ * K;                                \
         _Pragma("unroll") for (int u = 0; u < TS; ++u) {                                         \
             const uint32_t o_ = (uint32_t)(sg * TS + u) * kstride + (uint32_t)c;                 \
-            kreg[u] = kp_[o_]; greg[u] = gp_[o_];                                                \
-            if (RET_VEC) rreg[RET_VEC ? u : 0] = a.retention[tokc_ * K + o_];                    \
+            kreg[u] = lane_elem(kp_, o_); greg[u] = lane_elem(gp_, o_);                          \
+            if (RET_VEC) rreg[RET_VEC ? u : 0] = lane_elem(a.retention + tokc_ * K, o_);         \
         }                                                                                        \
         if (tid < C) {                                                                           \
             const size_t th = tokc_ + (size_t)tid * a.H;                                         \
@@ -292,13 +292,13 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     {   // ---- replay d over the chunk (same arithmetic as the forward kernel) ----
         float kv[C];
 #pragma unroll
-        for (int i = 0; i < C; ++i) kv[i] = to_f32(kp[(uint32_t)tid + (uint32_t)i * kstride]);
+        for (int i = 0; i < C; ++i) kv[i] = to_f32(lane_elem(kp + (size_t)i * kstride, tid));
         float d = a.d_ckpt[(bh * N + n) * K + tid];
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < C; ++i) {
             Dv[i] = d;
-            const float r = RET_VEC ? retp[(uint32_t)tid + (uint32_t)i * kstride] : r_s[i];
+            const float r = RET_VEC ? lane_elem(retp + (size_t)i * kstride, tid) : r_s[i];
             d = clip3(d_bar<HAS_RET>(r, d, st_s[i], kv[i] * kv[i]), lo, hi);
         }
     }
@@ -309,14 +309,18 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     const float *st_p = st_s, *r_p = r_s, *casig_p = casig_s, *gp_p = gp_s, *gn_p = gn_s;
     asm volatile("" : "+v"(st_p), "+v"(r_p), "+v"(casig_p), "+v"(gp_p), "+v"(gn_p));
     float kb[2][PB], gb[2][PB], rb[2][PB], rrb[RET_VEC ? 2 : 1][RET_VEC ? PB : 1];
-    uint32_t lofs = (uint32_t)tid + (uint32_t)(C - 1) * kstride;    // offset of the next row to fetch
+    // byte offsets (in units of T) of the next row to fetch and of the next row to write
+    constexpr uint32_t FS = sizeof(float) / sizeof(T);
+    const uint32_t rowb = kstride * (uint32_t)sizeof(T);
+    uint32_t lofs = ((uint32_t)tid + (uint32_t)(C - 1) * kstride) * (uint32_t)sizeof(T);
     asm volatile("" : "+v"(lofs));
-    uint32_t sofs = lofs;                                            // ... and of the next row to write
+    uint32_t sofs = lofs;
 #define OSDN_PLOAD(buf, ih_)                                                                     \
     _Pragma("unroll") for (int u = 0; u < PB; ++u) {                                             \
-        kb[buf][u] = to_f32(kp[lofs]); gb[buf][u] = to_f32(gp[lofs]); rb[buf][u] = to_f32(rp[lofs]); \
-        if (RET_VEC) rrb[RET_VEC ? buf : 0][RET_VEC ? u : 0] = retp[lofs];                       \
-        lofs -= kstride;                                                                         \
+        kb[buf][u] = to_f32(at_byte(kp, lofs)); gb[buf][u] = to_f32(at_byte(gp, lofs));          \
+        rb[buf][u] = to_f32(at_byte(rp, lofs));                                                  \
+        if (RET_VEC) rrb[RET_VEC ? buf : 0][RET_VEC ? u : 0] = at_byte(retp, lofs * FS);         \
+        lofs -= rowb;                                                                            \
     }
     OSDN_PLOAD(0, C - 1)
 #pragma unroll
@@ -330,10 +334,10 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
             const float ab = bit ? av : 0.f;
             const float kv = kb[blk & 1][u], g = gb[blk & 1][u], Di = Dv[i];
             const float gsum = st_p[i] * ab + gp_p[i] * Di + gn_p[i];
-            op[sofs] = from_f32<T>(rb[blk & 1][u] + Di * g + 2.f * kv * gsum);
-            if (RET_VEC) { if (dretp) dretp[sofs] = ab * Di; }
+            at_byte(op, sofs) = from_f32<T>(rb[blk & 1][u] + Di * g + 2.f * kv * gsum);
+            if (RET_VEC) { if (dretp) at_byte(dretp, sofs * FS) = ab * Di; }
             else if (HAS_RET) prod[i * LD + tid] = ab * Di;
-            sofs -= kstride;
+            sofs -= rowb;
             const float src = __builtin_fmaf(-casig_p[i], kv * kv, kv * g);
             const float r = RET_VEC ? rrb[RET_VEC ? blk & 1 : 0][RET_VEC ? u : 0] : r_p[i];
             av = HAS_RET ? __builtin_fmaf(r, ab, src) : ab + src;
