@@ -35,9 +35,9 @@ PEAK_FP32_VALU = 157.3e12
 # factors a 1 GiB device copy gives: fetch x 2.0, write x 1.0); see
 # profiles/hbm_traffic_configs2_fwd_bwd.txt.  Offline figures: bench.py cannot read PMCs.
 MEASURED_TRAFFIC_CONFIG2 = {
-    "precond_fwd": 153.8e6, "chunk_prep": 447.0e6, "state_fwd": 441.1e6, "output_fwd": 407.8e6,
-    "bwd_local": 404.1e6, "bwd_chain": 558.1e6, "bwd_post": 1049.8e6, "precond_mask": 77.7e6,
-    "precond_chain": 191.2e6, "precond_post": 320.7e6,
+    "precond_fwd": 153.8e6, "chunk_prep": 446.3e6, "state_fwd": 441.1e6, "output_fwd": 407.8e6,
+    "bwd_local": 404.1e6, "bwd_chain": 558.1e6, "bwd_post": 1047.6e6, "precond_mask": 77.7e6,
+    "precond_chain": 191.2e6, "precond_post": 328.7e6,
 }
 
 
