@@ -454,12 +454,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     const int rb = wave / WPR;          // row block of steps (1), (2)
     float gam_rb[4] = {1.f, 1.f, 1.f, 1.f};   // gamma of this lane's four rows there (set once G is in LDS)
 
-#ifdef OSDN_DIAG
-    long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
-#define OSDN_PTICK(j) { const long long now_ = clock64(); tph[j] += now_ - tlast; tlast = now_; }
-#else
-#define OSDN_PTICK(j)
-#endif
     for (int v0 = 0; v0 < a.V; v0 += VB) {
         __syncthreads();
         r_dO.put(dOs, LDV, tid); r_V.put(Vs, LDV, tid);
@@ -472,7 +466,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
             r_Kt.fetch(static_cast<const T *>(a.kt) + tok0 * K, tstride * K, tid);
         }
         __syncthreads();
-        OSDN_PTICK(0)
         if (v0 == 0) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) gam_rb[r] = Egs[rb * 16 + acc_row(lane, r)];
@@ -536,7 +529,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
             }
         }
         __syncthreads();
-        OSDN_PTICK(1)
         // (3,4) dP += dO E^T, dA -= dR E^T on the lower tiles
 #pragma unroll
         for (int t = 0; t < NLT; ++t) {
@@ -571,7 +563,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
             }
         }
         __syncthreads();
-        OSDN_PTICK(2)
         // dV = beta . dR for this slab, staged through the dO buffer
         {
             constexpr int VN = 16 / sizeof(T);
@@ -586,7 +577,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         }
         __syncthreads();
         store_tile_global(static_cast<T *>(a.dv) + tok0 * a.V + v0, tstride * a.V, dOs, LDV, C, VB, tid, PT_);
-        OSDN_PTICK(3)
     }
     __syncthreads();
     // ---- after the walk: Q, K~ into the pool ----
@@ -613,7 +603,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         if (acc_col(lane) == 0) dbeta_s[(wave % WPR) * C + rb * 16 + acc_row(lane, r)] = sred;
     }
     __syncthreads();
-    OSDN_PTICK(4)
     // ---- lower tiles: A0, P, X, cA, cP ----
 #pragma unroll
     for (int t = 0; t < NLT; ++t) {
@@ -651,7 +640,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
         }
     }
     __syncthreads();
-    OSDN_PTICK(5)
     // ---- dQ, dK (read side), dK~ and the inner products that enter dG (column tile ct) ----
     // dG_i takes <d(gamma Q)_i, gamma_i Q_i> + <d(gamma K)_i, gamma_i K_i> - <d(rho K~)_i, rho_i K~_i>
     // as one number per row; the last term, summed over all rows, goes to the chunk's last token
@@ -736,7 +724,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
     trs = wave_sum(trs);
     if (lane == 0) trsum_s[wave] = trs;
     __syncthreads();
-    OSDN_PTICK(6)
     if (GV && tid < K) {                // dL/d(decay of channel tid over the chunk)
         float sd = 0.f;
 #pragma unroll
@@ -767,11 +754,6 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
             a.dlog_alpha[th] = wave_suffix_sum(dG, lane);
         }
     }
-#ifdef OSDN_DIAG
-    OSDN_PTICK(7)
-    if (tid == 0 && n == a.n0 + 5 && blockIdx.y == 0 && blockIdx.z == 0 && a.dlog_alpha)
-        for (int j = 0; j < 8; ++j) a.dlog_alpha[tok0 + (size_t)j * tstride] = (float)tph[j];
-#endif
     }   // task
 }
 

@@ -92,12 +92,6 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
     const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;      // (b, first token, h)
 
-#ifdef OSDN_DIAG
-    long long cph[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, clast = clock64();
-#define OSDN_CTICK(j) { const long long now_ = clock64(); cph[j] += now_ - clast; clast = now_; }
-#else
-#define OSDN_CTICK(j)
-#endif
     if (task > 0) __syncthreads();      // the previous chunk is through with every LDS tile
     if (wave == 0) {
         Gs[lane] = wave_cumsum(r_g, lane);
@@ -160,7 +154,6 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
         store_tile_global(static_cast<T *>(a.Kd) + tok0 * K, tstride * K, X2, LDK, C, K, tid, CP_);
         __syncthreads();            // the scratch space is handed over to A
     }
-    OSDN_CTICK(0)
 
     // ---- A = tril(beta_i Gamma_ij <k_i, k~_j>, -1): the ten lower 16x16 tiles ----
     for (int idx = wave; idx < 10; idx += NW) {
@@ -192,7 +185,6 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
         }
     }
     __syncthreads();
-    OSDN_CTICK(1)
     store_tile_global(static_cast<T *>(a.Ktr) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, CP_);
     __syncthreads();                // the staging tile is free again: (I + A)^-1 is built in its place
 
@@ -201,7 +193,6 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     if (wave == NW - 1) BGs[lane] = Bs[lane] * __expf(Gs[lane]);
     // ---- T = (I + A)^-1 in fp32, blocked ----
     ut_inverse64<LDF>(Af, Ti, Xs, wave, lane);
-    OSDN_CTICK(2)
     // ---- T in the I/O type, three times: as it is (straight to memory), with the columns scaled
     //      by beta (for U) and by beta gamma (for W); the upper triangle is exactly zero ----
     {
@@ -224,7 +215,6 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
         }
     }
     __syncthreads();                // Ti is dead from here on: its space is the staging tile again
-    OSDN_CTICK(3)
 
     // ---- -W^T, W = (T diag(beta gamma)) K (the chain kernels fetch it with transpose reads) ----
     {
@@ -240,9 +230,7 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
         }
     }
     __syncthreads();
-    OSDN_CTICK(4)
     store_tile_global(static_cast<T *>(a.Wt) + bhn * K * C, (size_t)C, stage, LDC, K, C, tid, CP_);
-    OSDN_CTICK(5)
 
     // ---- U^T = ((T diag(beta)) V)^T, 64 columns of V at a time ----
     for (int v0 = 0; v0 < a.V; v0 += C) {
@@ -262,11 +250,6 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
         __syncthreads();
         store_tile_global(static_cast<T *>(a.Ut) + (bhn * a.V + v0) * C, (size_t)C, stage, LDC, C, C, tid, CP_);
     }
-#ifdef OSDN_DIAG
-    OSDN_CTICK(6)
-    if (tid == 0 && n == a.n0 + 7 && blockIdx.y == 0 && blockIdx.z == 0)
-        for (int j = 0; j < 7; ++j) static_cast<T *>(a.Tm)[bhn * C * C + j] = from_f32<T>((float)cph[j] / 64.f);
-#endif
     }   // task
 }
 
@@ -388,12 +371,6 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
         }
     }
 
-#ifdef OSDN_DIAG
-    long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
-#define OSDN_TICK(j) { const long long now_ = clock64(); tph[j] += now_ - tlast; tlast = now_; }
-#else
-#define OSDN_TICK(j)
-#endif
     for (int n = a.n0; n < a.n1; ++n) {
         const int buf = NB == 2 ? (n & 1) : 0;
         const size_t bhn = bth * a.N + n;
@@ -412,22 +389,17 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
                         a.gamC + bhn * K + (wave * NKT + q) * 16 + acc_row(lane, 0));
             }
         }
-        OSDN_TICK(0)
         __syncthreads();                                            // barrier 1
-        OSDN_TICK(1)
         if (loader) {
             if (NB == 2) {
                 if (lgrp == ((n + 1) & 1)) {                        // this group's chunk comes next
                     if (n + 1 < a.n1) {
                         OSDN_SF_STORE((n + 1) & 1)                  // free since barrier 1
-                        OSDN_TICK(5)
                         OSDN_SF_LOAD(min(n + 3, a.n1 - 1))          // (past the end: a harmless reload)
-                        OSDN_TICK(6)
                     }
                 } else if (a.S_ckpt) {
                     // checkpoint of the chunk-start state (read between barrier 1 and barrier 2)
                     store_tile_global(static_cast<T *>(a.S_ckpt) + (bhn * a.V + vs) * K, (size_t)K, Sb, LDK, VS, K, lti, LTN);
-                    OSDN_TICK(7)
                 }
             } else if (a.S_ckpt) {
                 store_tile_global(static_cast<T *>(a.S_ckpt) + (bhn * a.V + vs) * K, (size_t)K, Sb, LDK, VS, K, lt, CL_);
@@ -443,9 +415,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
                 store_tile_t(Et + vt * 16 * LDC + wave * 16, LDC, acc, lane);
             }
         }
-        OSDN_TICK(2)
         __syncthreads();                                            // barrier 2
-        OSDN_TICK(3)
         if (loader) {
             if (NB == 2) {
                 if (lgrp == ((n + 1) & 1))                          // the group with no load wait ahead
@@ -473,14 +443,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
                 OSDN_SF_LOAD(min(n + 2, a.n1 - 1))
             }
         }
-        OSDN_TICK(4)
     }
-#ifdef OSDN_DIAG
-    if (blockIdx.x == 0 && lane == 0 && (wave == 0 || wave == 4 || wave == 6))
-        for (int j = 0; j < 8; ++j) a.S_out[(wave == 0 ? 0 : wave == 4 ? 8 : 16) + j] = (float)tph[j];
-    __syncthreads();
-    if (blockIdx.x == 0) return;
-#endif
     if (!loader) {
 #pragma unroll
         for (int vt = 0; vt < 2; ++vt)

@@ -113,12 +113,6 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     }
     OSDN_P1_LOAD(a.n0)
 
-#ifdef OSDN_DIAG
-    long long tph[6] = {0, 0, 0, 0, 0, 0}, tlast = clock64();
-#define OSDN_TICK(j) { const long long now_ = clock64(); tph[j] += now_ - tlast; tlast = now_; }
-#else
-#define OSDN_TICK(j)
-#endif
     __syncthreads();
     for (int n = a.n0; n < a.n1; ++n) {
         const int t0 = n * C;
@@ -173,9 +167,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
                 rv[u][0] = HAS_RET ? lane_bcast(run * RUN + u < nvalid ? ret : 1.f, u) : 1.f;
             }
         }
-        OSDN_TICK(0)
         if (n + 1 < a.n1) OSDN_P1_LOAD(n + 1)
-        OSDN_TICK(1)
         // ---- fixed-point sweeps ----
         int sweeps_used = 0;
         float dtr[RUN][CPT], dend[CPT];
@@ -206,7 +198,6 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
                 maps[run * K + c0 + e] = make_float4(A, B, L, H);
             }
             __syncthreads();
-            OSDN_TICK(2)
             float vp[RUN];
 #pragma unroll
             for (int u = 0; u < RUN; ++u) vp[u] = 0.f;
@@ -234,7 +225,6 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
             const bool wave_ok = __all(ok);
             if (lane == 0) okflag[run] = wave_ok ? 1 : 0;
             __syncthreads();
-            OSDN_TICK(3)
             bool all_ok = true;
 #pragma unroll
             for (int w = 0; w < NRUN; ++w) all_ok = all_ok && okflag[w] != 0;
@@ -265,12 +255,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
             for (int e = 0; e < CPT; ++e) dcur[c0 + e] = dend[e];
         }
         __syncthreads();
-        OSDN_TICK(4)
     }
-#ifdef OSDN_DIAG
-    if (a.tok_scalars && tid == 0 && blockIdx.x == 0)
-        for (int j = 0; j < 6; ++j) a.tok_scalars[(((size_t)bt * a.T + 2 + j) * a.H + h) * 4 + 3] = (float)tph[j];
-#endif
     if (tid < K) a.d_out[bh * K + tid] = dcur[tid];
 }
 

@@ -125,12 +125,6 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
     }
     OSDN_P1_BLOAD(a.n1 - 1)
 
-#ifdef OSDN_DIAG
-    long long tph[6] = {0, 0, 0, 0, 0, 0}, tlast = clock64();
-#define OSDN_TICK(j) { const long long now_ = clock64(); tph[j] += now_ - tlast; tlast = now_; }
-#else
-#define OSDN_TICK(j)
-#endif
     for (int n = a.n1 - 1; n >= a.n0; --n) {
         const size_t tokc = ((size_t)bt * a.T + (size_t)n * C) * a.H + h;
         // ---- this thread's (s, lambda) = (k^2, k . dL/dk~) and mask bits ----
@@ -150,7 +144,6 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         }
         if (tid < K) a.a_ckpt[(bth * N + n) * K + tid] = ga[tid];
         __syncthreads();
-        OSDN_TICK(0)
         float rv[TS];                           // retention of this thread's coordinate, token by token
         if (HAS_RET) {
 #pragma unroll
@@ -184,11 +177,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
             }
             segL[sg * K + c] = loc;
             segP[sg * K + c] = P;
-#ifdef OSDN_DIAG
-            if (sweep == 0) OSDN_TICK(5)
-#endif
             __syncthreads();
-            OSDN_TICK(1)
             // value of a at the right end of this run: chain the runs to its right
             float carry = ga[c];
 #pragma unroll
@@ -205,7 +194,6 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
             }
             part[wave * 64 + lane] = lane_fold<TS>(prod, lane);
             __syncthreads();
-            OSDN_TICK(2)
             if (tid < C) {
                 const int i = tid, w0 = (i / TS) * WPS, u = i % TS;
                 float sg_ = 0.f;
@@ -224,21 +212,14 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
                 if (tid == 0) done = all_ok ? 1 : 0;
             }
             __syncthreads();
-            OSDN_TICK(3)
             if (done) break;
         }
         // ---- accepted: sig generated a_left ----
         if (tid < C) a.tok_scalars[(tokc + (size_t)tid * a.H) * 4 + 3] = sig[tid];
         if (sg == 0) ga[c] = a_left;
         __syncthreads();
-        OSDN_TICK(4)
     }
     if (tid < K) a.dd_in[bh * K + tid] = ga[tid];
-#ifdef OSDN_DIAG
-    __syncthreads();
-    if (tid == 0 && blockIdx.x == 0)
-        for (int j = 0; j < 6; ++j) a.dd_in[j] = (float)tph[j];
-#endif
 }
 
 // ---------------------------------------------------------------- precond_post ----
