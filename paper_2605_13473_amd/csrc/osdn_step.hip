@@ -17,8 +17,11 @@ namespace osdn {
 
 constexpr int STEP_T = 256, STEP_RPW = 4, STEP_ROWS = (STEP_T / 64) * STEP_RPW;   // 16 rows per workgroup
 
-template <typename T, int K, bool HAS_RET>
+// RET: 0 = no retention, 1 = one gate per (token, head), 2 = one per coordinate; GV: one state
+// gate per key channel
+template <typename T, int K, int RET, bool GV>
 __global__ __launch_bounds__(STEP_T) void step_kernel(StepArgs a) {
+    constexpr bool HAS_RET = RET != 0, RET_VEC = RET == 2;
     constexpr int CPT = K / 64;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nslice = a.V / STEP_ROWS;
@@ -53,11 +56,11 @@ __global__ __launch_bounds__(STEP_T) void step_kernel(StepArgs a) {
         float alpha[CPT];                           // one state gate per (token, head), or one per key channel
 #pragma unroll
         for (int e = 0; e < CPT; ++e)
-            alpha[e] = a.log_alpha ? __expf(a.gate_vec ? a.log_alpha[th * K + c0 + e] : a.log_alpha[th]) : 1.f;
+            alpha[e] = a.log_alpha ? __expf(GV ? a.log_alpha[th * K + c0 + e] : a.log_alpha[th]) : 1.f;
         float ret[CPT];                             // one gate per (token, head), or one per coordinate
 #pragma unroll
         for (int e = 0; e < CPT; ++e)
-            ret[e] = HAS_RET ? (a.ret_vec ? a.retention[th * K + c0 + e] : a.retention[th]) : 1.f;
+            ret[e] = HAS_RET ? (RET_VEC ? a.retention[th * K + c0 + e] : a.retention[th]) : 1.f;
         float orow = 0.f;                           // lane r < 4 ends with the output of row v0 + r
 #pragma unroll
         for (int r = 0; r < STEP_RPW; ++r) {
@@ -96,18 +99,24 @@ __global__ __launch_bounds__(STEP_T) void step_kernel(StepArgs a) {
     }
 }
 
-template <typename T, bool HAS_RET>
+template <typename T, int RET, bool GV>
 static int launch_step_t(const StepArgs &a, hipStream_t st) {
     dim3 grid(a.B * a.H * (a.V / STEP_ROWS)), block(STEP_T);
-    if (a.K == 64) hipLaunchKernelGGL((step_kernel<T, 64, HAS_RET>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((step_kernel<T, 128, HAS_RET>), grid, block, 0, st, a);
+    if (a.K == 64) hipLaunchKernelGGL((step_kernel<T, 64, RET, GV>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((step_kernel<T, 128, RET, GV>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
+template <typename T>
+static int launch_step_io(const StepArgs &a, hipStream_t st) {
+    const int ret = a.retention ? (a.ret_vec ? 2 : 1) : 0;
+    const bool gv = a.log_alpha && a.gate_vec;
+    if (ret == 2) return gv ? launch_step_t<T, 2, true>(a, st) : launch_step_t<T, 2, false>(a, st);
+    if (ret == 1) return gv ? launch_step_t<T, 1, true>(a, st) : launch_step_t<T, 1, false>(a, st);
+    return gv ? launch_step_t<T, 0, true>(a, st) : launch_step_t<T, 0, false>(a, st);
+}
 int launch_step(const StepArgs &a, bool bf16_io, hipStream_t st) {
-    if (a.retention)
-        return bf16_io ? launch_step_t<bf16, true>(a, st) : launch_step_t<float, true>(a, st);
-    return bf16_io ? launch_step_t<bf16, false>(a, st) : launch_step_t<float, false>(a, st);
+    return bf16_io ? launch_step_io<bf16>(a, st) : launch_step_io<float>(a, st);
 }
 
 }  // namespace osdn
