@@ -149,8 +149,8 @@ def main():
                     help="also launch a plain device copy of 1 GiB (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (every (batch, head) chain is independent; "
-              "see DESIGN.md for how the path would shard). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (every (batch, head) chain is independent, "
+              "so the path would shard over batch and heads without communication). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
