@@ -131,8 +131,8 @@ def decode_bench(args, cfg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--packed-tokens", type=int, default=0,
