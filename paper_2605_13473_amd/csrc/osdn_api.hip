@@ -39,6 +39,7 @@ struct Layout {
     size_t Qg, Kg, Kd, gamC, dgamC;                                      // per-channel state gate
     size_t tables;                                                       // packed sequences: the index tables
     size_t kt, d_ckpt, tok_scalars, Tm, Wt, Ktr, Ut, Et, S_ckpt;   // forward
+    size_t piece_start, piece_map, piece_flags;                          // phase 1 as sweeps over the whole sequence
     size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;   // backward only
     // padded copies of the caller's tensors, only when T is not a multiple of the chunk length
     size_t p_q, p_k, p_v, p_beta, p_g, p_r, p_o;                        // forward
@@ -47,6 +48,10 @@ struct Layout {
 };
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Phase 1 as sweeps over the whole sequence: at most this many pieces over all chains, and at
+// most this many sweeps before the sequential kernel takes over.
+constexpr int MAX_PIECES = 512, MAX_PIECE_SWEEPS = 8;
 
 int check_params(const osdn_params *p, bool need_chunks) {
     if (!p) return OSDN_ERR_NULL;
@@ -143,6 +148,9 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
         L.p_v = take(B * T * H * V * es); L.p_o = take(B * T * H * V * es);
         L.p_beta = take(B * T * H * 4); L.p_g = take(B * T * H * 4 * GK); L.p_r = take(B * T * H * 4 * RK);
     }
+    L.piece_start = take((size_t)MAX_PIECES * K * 4);
+    L.piece_map = take((size_t)MAX_PIECES * K * 16);
+    L.piece_flags = take((MAX_PIECE_SWEEPS + 1) * sizeof(int));
     L.total_fwd = off;
     L.dElt = take(B * T * H * V * es);
     L.Qt = take(B * T * H * K * es);
@@ -277,6 +285,36 @@ inline int seg_begin(int N, int S, int s) {
     if (s >= S) return N;
     const int first = N / (2 * S) > 0 ? N / (2 * S) : 1;
     return first + (int)((long long)(N - first) * (s - 1) / (S - 1));
+}
+
+// Phase 1 of the forward pass as sweeps over the whole sequence, for few long chains: with
+// fewer chains than a quarter of the CUs the sequential kernel leaves most of the chip idle and
+// its walk over the chunks is the whole forward pass.  Every chain is cut into pieces (two
+// workgroups per CU over all chains, at least 8 chunks each); a sweep runs all pieces side by
+// side, each from its current start value, and leaves every piece as a composed map per
+// coordinate; a scan over those maps gives the next start values; the sweeps end when no start
+// value moves any more.  Plain batches only.  OSDN_P1_PIECES in the environment forces a number
+// of pieces per chain (0: never), OSDN_P1_PIECE_SWEEPS the sweep limit.
+inline void pieces_plan(int N, long long chains, bool packed, int &pieces, int &piece_chunks, int &sweeps) {
+    pieces = 0; piece_chunks = 0; sweeps = MAX_PIECE_SWEEPS;
+    if (packed || chains > MAX_PIECES / 2) return;
+    const char *e = std::getenv("OSDN_P1_PIECES");
+    const int forced = e ? std::atoi(e) : -1;
+    int target, min_chunks;
+    if (forced >= 0) { target = forced; min_chunks = 1; }
+    else if (chains * 4 <= NUM_CU && N >= 64) { target = (int)(2 * NUM_CU / chains); min_chunks = 8; }
+    else return;
+    if ((long long)target * chains > MAX_PIECES) target = (int)(MAX_PIECES / chains);
+    if (target < 2) return;
+    int len = (N + target - 1) / target;
+    if (len < min_chunks) len = min_chunks;
+    const int P = (N + len - 1) / len;
+    if (P < 2) return;
+    pieces = P; piece_chunks = len;
+    if (const char *w = std::getenv("OSDN_P1_PIECE_SWEEPS")) {
+        const int v = std::atoi(w);
+        if (v >= 1 && v <= MAX_PIECE_SWEEPS) sweeps = v;
+    }
 }
 
 #define OSDN_HIP_OK(x) do { if ((x) != hipSuccess) return OSDN_ERR_LAUNCH; } while (0)
@@ -446,12 +484,14 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     }
 
     const int N = p->T / C;
-    int S = segment_count(N, pk.longest, 0, false);
+    const long long chains = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
+    int pieces, piece_chunks, piece_sweeps;
+    pieces_plan(N, chains, pk.n_seqs != 0, pieces, piece_chunks, piece_sweeps);
+    int S = pieces ? 1 : segment_count(N, pk.longest, 0, false);
     std::lock_guard<std::mutex> lock(g_pipe_mu);
     Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
     if (!pl) S = 1;
     // chain workgroups of both phases (32 rows of the state per workgroup in state_fwd) against the CUs
-    const long long chains = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
     const bool crowded = chains * (p->V / 32) + chains > NUM_CU;
     auto seg_range = [&](int sidx, int &n0, int &n1) {
         if (crowded) { n0 = seg_begin_grow(N, S, sidx, 1.7); n1 = seg_begin_grow(N, S, sidx + 1, 1.7); return; }
@@ -471,9 +511,30 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
                  : kid == KID_STATE_FWD ? launch_state_fwd(ck, bf, st) : launch_output_fwd(ck, bf, st);
         });
     };
+    // phase 1 as sweeps over the pieces of every chain; flags[i] != 0: sweep i + 1 has to run
+    // (flags[sweeps]: none of them ended the iteration, the sequential kernel runs)
+    auto precond_pieces = [&]() {
+        int *flags = reinterpret_cast<int *>(ws + L.piece_flags);
+        PrecondArgs pp = pa;
+        pp.n0 = 0; pp.n1 = N; pp.d_in = d_in;
+        pp.pieces = pieces; pp.piece_chunks = piece_chunks;
+        pp.piece_start = reinterpret_cast<float *>(ws + L.piece_start);
+        pp.piece_map = reinterpret_cast<float4 *>(ws + L.piece_map);
+        if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_pieces_init(pp, flags, MAX_PIECE_SWEEPS + 1, st); }) != 0)
+            return -1;
+        for (int i = 0; i < piece_sweeps; ++i) {
+            pp.run_if = flags + i; pp.changed_out = flags + i + 1;
+            if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(pp, bf, st); }) != 0) return -1;
+            if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_pieces_scan(pp, st); }) != 0) return -1;
+        }
+        pa.n0 = 0; pa.n1 = N; pa.d_in = d_in; pa.run_if = flags + piece_sweeps;
+        const int rc1 = timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(pa, bf, st); });
+        pa.run_if = nullptr;
+        return rc1;
+    };
     if (!pl) {
-        if (precond(0, st) != 0 || phase2(KID_CHUNK_PREP, 0) != 0 || phase2(KID_STATE_FWD, 0) != 0 ||
-            phase2(KID_OUTPUT_FWD, 0) != 0)
+        if ((pieces ? precond_pieces() : precond(0, st)) != 0 || phase2(KID_CHUNK_PREP, 0) != 0 ||
+            phase2(KID_STATE_FWD, 0) != 0 || phase2(KID_OUTPUT_FWD, 0) != 0)
             return OSDN_ERR_SHAPE;
         return finish();
     }

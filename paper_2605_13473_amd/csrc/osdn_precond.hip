@@ -71,10 +71,18 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     __shared__ __attribute__((aligned(16))) float4 maps[NRUN * K];   // (A, B, L, H) per run and coordinate
     __shared__ int okflag[NRUN];
 
+    if (a.run_if && *a.run_if == 0) return;       // (the same for every thread of the launch)
     const int tid = threadIdx.x, run = tid >> 6, lane = tid & 63;
     const int c0 = lane * CPT;                    // first coordinate of this thread
     const int u_own = lane & (RUN - 1);           // the token of the run whose scalars this lane keeps
-    const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;     // b: batch entry, or packed sequence
+    const int piece = a.pieces ? blockIdx.x % a.pieces : 0;
+    const int chain = a.pieces ? blockIdx.x / a.pieces : blockIdx.x;
+    const int b = chain / a.H, h = chain % a.H;               // b: batch entry, or packed sequence
+    if (a.pieces) {
+        a.n0 += piece * a.piece_chunks;
+        a.n1 = min(a.n1, a.n0 + a.piece_chunks);
+        if (a.n0 >= a.n1) return;
+    }
     const size_t bh = (size_t)b * a.H + h;                    // the chain: indexes d_in / d_out
     int bt = b;                                               // batch entry of the token tensors
     if (a.seq_chunks) {
@@ -89,7 +97,9 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     const int N = (a.T + C - 1) / C;
     const uint32_t kstride = (uint32_t)a.H * K;   // elements between consecutive tokens
 
-    if (tid < K) dcur[tid] = a.d_in ? a.d_in[bh * K + tid] : 1.f;
+    if (tid < K)
+        dcur[tid] = a.pieces ? a.piece_start[(bh * a.pieces + piece) * K + tid] : a.d_in ? a.d_in[bh * K + tid] : 1.f;
+    float PA = 1.f, PB = 0.f, PL = -FLT_MAX, PH = FLT_MAX;    // thread c < K: the piece so far, as a map of coordinate c
 
     typedef Pack<float, CPT> Pr;
     typename Pk::Raw kreg[RUN];                  // this thread's k of the next chunk
@@ -254,14 +264,61 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
 #pragma unroll
             for (int e = 0; e < CPT; ++e) dcur[c0 + e] = dend[e];
         }
+        if (a.pieces && tid < K) {                // the accepted run maps, applied after the piece so far
+#pragma unroll
+            for (int j = 0; j < NRUN; ++j) {
+                const float4 m = maps[j * K + tid];
+                PA *= m.x;
+                PB = __builtin_fmaf(m.x, PB, m.y);
+                PL = clip3(__builtin_fmaf(m.x, PL, m.y), m.z, m.w);
+                PH = clip3(__builtin_fmaf(m.x, PH, m.y), m.z, m.w);
+            }
+        }
         __syncthreads();
     }
-    if (tid < K) a.d_out[bh * K + tid] = dcur[tid];
+    if (a.pieces && tid < K) a.piece_map[(bh * a.pieces + piece) * K + tid] = make_float4(PA, PB, PL, PH);
+    if (tid < K && (!a.pieces || piece == a.pieces - 1)) a.d_out[bh * K + tid] = dcur[tid];
+}
+
+// ---- whole-sequence sweeps: the pieces of a chain side by side ----
+// First guess: every piece starts from the chain's own start value.  flags[0] = 1 (the first
+// sweep always runs), the others 0.
+__global__ void precond_pieces_init_kernel(PrecondArgs a, int *flags, int n_flags) {
+    const int chain = blockIdx.x, c = threadIdx.x;
+    const float x = a.d_in ? a.d_in[(size_t)chain * a.K + c] : 1.f;
+    for (int p = 0; p < a.pieces; ++p) a.piece_start[((size_t)chain * a.pieces + p) * a.K + c] = x;
+    if (chain == 0 && c < n_flags) flags[c] = c == 0 ? 1 : 0;
+}
+// One thread per coordinate walks the piece maps of its chain: the value that arrives at a piece
+// becomes its next start value.  A start value that moved by more than the tolerance of the
+// sweeps asks for another sweep.
+__global__ void precond_pieces_scan_kernel(PrecondArgs a) {
+    if (a.run_if && *a.run_if == 0) return;
+    const int chain = blockIdx.x, c = threadIdx.x;
+    float x = a.d_in ? a.d_in[(size_t)chain * a.K + c] : 1.f;
+    bool moved = false;
+    for (int p = 0; p < a.pieces; ++p) {
+        const size_t i = ((size_t)chain * a.pieces + p) * a.K + c;
+        const float old = a.piece_start[i];
+        if (!(fabsf(x - old) <= P1_TOL * fmaxf(fabsf(x), fabsf(old)))) moved = true;
+        a.piece_start[i] = x;
+        const float4 m = a.piece_map[i];
+        x = clip3(__builtin_fmaf(m.x, x, m.y), m.z, m.w);
+    }
+    if (__syncthreads_or(moved) && c == 0) atomicAdd(a.changed_out, 1);
+}
+int launch_precond_pieces_init(const PrecondArgs &a, int *flags, int n_flags, hipStream_t st) {
+    hipLaunchKernelGGL(precond_pieces_init_kernel, dim3(a.B * a.H), dim3(a.K), 0, st, a, flags, n_flags);
+    return 0;
+}
+int launch_precond_pieces_scan(const PrecondArgs &a, hipStream_t st) {
+    hipLaunchKernelGGL(precond_pieces_scan_kernel, dim3(a.B * a.H), dim3(a.K), 0, st, a);
+    return 0;
 }
 
 template <typename T, int RET>
 static int launch_precond_fwd_t(const PrecondArgs &a, hipStream_t st) {
-    dim3 grid((a.seq_chunks ? a.n_seqs : a.B) * a.H), block(P1T);
+    dim3 grid((a.seq_chunks ? a.n_seqs : a.B) * a.H * (a.pieces ? a.pieces : 1)), block(P1T);
     if (a.K == 64) hipLaunchKernelGGL((precond_fwd_kernel<T, 64, RET>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((precond_fwd_kernel<T, 128, RET>), grid, block, 0, st, a);
     else return -1;

@@ -56,6 +56,27 @@ def test_many_chains_few_chunks(T):
     compare_backward(x, hp, False)
 
 
+@pytest.mark.parametrize("case", ["box_and_retention", "no_projection", "no_retention_bf16", "k128_ragged",
+                                  "one_sweep_then_sequential"])
+def test_phase1_as_sweeps_over_pieces(case, monkeypatch):
+    """Few long chains: phase 1 of the forward pass runs as sweeps over pieces of the sequence
+    (every piece from a guessed start value, a scan over the pieces' composed maps, until no
+    start value moves).  Forced here on small shapes through the environment: 5 pieces per chain
+    over 20 (19.6) chunks, eta = 0.5 so that d moves, meets the box and couples the pieces; the
+    last case allows a single sweep, after which the sequential kernel has to take over."""
+    monkeypatch.setenv("OSDN_P1_PIECES", "5")
+    if case == "one_sweep_then_sequential":
+        monkeypatch.setenv("OSDN_P1_PIECE_SWEEPS", "1")
+    bf16 = case == "no_retention_bf16"
+    K = 128 if case == "k128_ragged" else 64
+    T = 64 * 20 - 25 if case == "k128_ragged" else 64 * 20
+    x = make_stress_inputs(2, T, 2, K, 64, seed=71, bf16=bf16,
+                           retention=0.0 if case == "no_retention_bf16" else 0.97)
+    hp = ob.Hyper(eta=0.2, d_min=1.0, d_max=0.0) if case == "no_projection" else ob.Hyper(eta=0.5)
+    compare_forward(x, hp, bf16)
+    compare_backward(x, hp, bf16)
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_large_launches_two_chunks_per_workgroup(bf16):
     """256 chains and 17 chunks: the second segment of either pass is a launch of more than 2048
