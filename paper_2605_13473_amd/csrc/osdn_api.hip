@@ -288,9 +288,9 @@ inline int seg_begin(int N, int S, int s) {
 }
 
 // Phase 1 of the forward pass as sweeps over the whole sequence, for few long chains: with
-// fewer chains than a quarter of the CUs the sequential kernel leaves most of the chip idle and
-// its walk over the chunks is the whole forward pass.  Every chain is cut into pieces (two
-// workgroups per CU over all chains, at least 8 chunks each); a sweep runs all pieces side by
+// chains on at most an eighth of the CUs the sequential kernel leaves most of the chip idle and
+// its walk over the chunks is the whole forward pass.  Every chain is cut into pieces (one
+// workgroup per CU over all chains, at least 8 chunks each); a sweep runs all pieces side by
 // side, each from its current start value, and leaves every piece as a composed map per
 // coordinate; a scan over those maps gives the next start values; the sweeps end when no start
 // value moves any more.  Plain batches only.  OSDN_P1_PIECES in the environment forces a number
@@ -302,7 +302,7 @@ inline void pieces_plan(int N, long long chains, bool packed, int &pieces, int &
     const int forced = e ? std::atoi(e) : -1;
     int target, min_chunks;
     if (forced >= 0) { target = forced; min_chunks = 1; }
-    else if (chains * 4 <= NUM_CU && N >= 64) { target = (int)(2 * NUM_CU / chains); min_chunks = 8; }
+    else if (chains * 8 <= NUM_CU && N >= 64) { target = (int)(NUM_CU / chains); min_chunks = 8; }
     else return;
     if ((long long)target * chains > MAX_PIECES) target = (int)(MAX_PIECES / chains);
     if (target < 2) return;
