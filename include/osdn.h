@@ -36,6 +36,10 @@
  *     preconditioner phase on it, forked from and joined back into `stream`, so that to the
  *     caller all work still is ordered as if enqueued on `stream`.  Calls are serialised by a
  *     mutex while they enqueue.  OSDN_SEGMENTS=1 in the environment keeps everything on `stream`.
+ *     With at most 32 (batch, head) chains of at least 64 chunks, osdn_fwd computes the
+ *     preconditioner as a few sweeps over pieces of the sequence that run side by side, all on
+ *     `stream` (same results to the tolerance of the sweeps, 1e-6 relative; OSDN_P1_PIECES=0 in
+ *     the environment keeps the one sequential sweep per chain).
  *   - retention values are assumed >= 0 (they are sigmoid gates in the paper).  Wherever a
  *     signature says retention / dretention [B,T,H], params->retention_per_channel = 1 makes
  *     it [B,T,H,K]: one value per coordinate.  Likewise params->gate_per_channel = 1 makes

@@ -20,6 +20,12 @@
 // fma + median-of-three per run), and with its run's starting value known the thread replays
 // its 8 tokens.  The products s d are folded over the lanes of the wavefront and the p of a
 // token is the sum of 8 partials.  All arithmetic is fp32; k~ is rounded once, from fp32 d k.
+//
+// For few long chains the same composition is taken one level up: the chain is cut into pieces,
+// one workgroup per piece walks its chunks from a start value it is given and also composes the
+// accepted run maps into one map for the piece; a scan over the piece maps gives the next start
+// values, and the sweeps over all pieces repeat until no start value moves (the caller launches
+// them ahead of time; a launch reads a device flag and returns at once when it is not needed).
 #include "osdn_precond.h"
 
 #include <cfloat>
