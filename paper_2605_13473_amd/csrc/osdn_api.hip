@@ -51,7 +51,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Phase 1 as sweeps over the whole sequence: at most this many pieces over all chains, and at
 // most this many sweeps before the sequential kernel takes over.
-constexpr int MAX_PIECES = 512, MAX_PIECE_SWEEPS = 8;
+constexpr int MAX_PIECES = 512, MAX_PIECE_SWEEPS = 12;
 
 int check_params(const osdn_params *p, bool need_chunks) {
     if (!p) return OSDN_ERR_NULL;
@@ -296,7 +296,11 @@ inline int seg_begin(int N, int S, int s) {
 // value moves any more.  Plain batches only.  OSDN_P1_PIECES in the environment forces a number
 // of pieces per chain (0: never), OSDN_P1_PIECE_SWEEPS the sweep limit.
 inline void pieces_plan(int N, long long chains, bool packed, int &pieces, int &piece_chunks, int &sweeps) {
-    pieces = 0; piece_chunks = 0; sweeps = MAX_PIECE_SWEEPS;
+    pieces = 0; piece_chunks = 0;
+    // sweeps needed without retention, measured: 4 at 64 and 128 chunks, then one more per
+    // doubling (7 at 1024); the limit leaves two in hand
+    sweeps = 6;
+    for (int n = 128; n < N && sweeps < MAX_PIECE_SWEEPS; n *= 2) ++sweeps;
     if (packed || chains > MAX_PIECES / 2) return;
     const char *e = std::getenv("OSDN_P1_PIECES");
     const int forced = e ? std::atoi(e) : -1;
