@@ -287,11 +287,15 @@ def test_full_size_configs_sampled_chains(ci):
             check(name, pick(g[name], tok), ref, cfg.bf16)
 
 
-def test_hip_graph_capture_and_replay():
+@pytest.mark.parametrize("pieces", [False, True])
+def test_hip_graph_capture_and_replay(pieces, monkeypatch):
     """Forward + backward captured into a HIP graph on a caller stream (the library's side
     stream joins the capture through its fork / join events; nothing in it allocates or clears
     memory with a memset node) and replayed several times with eager calls and synchronisations
-    in between: every replay reproduces the eager results bit for bit."""
+    in between: every replay reproduces the eager results bit for bit.  Also with phase 1 as
+    sweeps over pieces of the sequence, whose launches decide on device flags whether to run."""
+    if pieces:
+        monkeypatch.setenv("OSDN_P1_PIECES", "4")
     x = make_stress_inputs(2, 1024, 2, 64, 64, seed=41, bf16=True, retention=0.97)
     t = to_dev(x, True)
     hp = ob.Hyper(eta=0.3)
