@@ -65,7 +65,8 @@ template <> struct Pack<float, 1> {
 };
 
 // RET: 0 = no retention, 1 = one gate per (token, head), 2 = one per coordinate (diag(r_t))
-template <typename T, int K, int RET>
+// PIECES: one workgroup per piece of a chain (sweeps over the whole sequence) instead of one per chain
+template <typename T, int K, int RET, bool PIECES>
 __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     constexpr bool HAS_RET = RET != 0, RET_VEC = RET == 2;
     constexpr int RE = RET_VEC ? K / 64 : 1;      // retention values a thread keeps per token
@@ -81,10 +82,10 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     const int tid = threadIdx.x, run = tid >> 6, lane = tid & 63;
     const int c0 = lane * CPT;                    // first coordinate of this thread
     const int u_own = lane & (RUN - 1);           // the token of the run whose scalars this lane keeps
-    const int piece = a.pieces ? blockIdx.x % a.pieces : 0;
-    const int chain = a.pieces ? blockIdx.x / a.pieces : blockIdx.x;
+    const int piece = PIECES ? blockIdx.x % a.pieces : 0;
+    const int chain = PIECES ? blockIdx.x / a.pieces : blockIdx.x;
     const int b = chain / a.H, h = chain % a.H;               // b: batch entry, or packed sequence
-    if (a.pieces) {
+    if (PIECES) {
         a.n0 += piece * a.piece_chunks;
         a.n1 = min(a.n1, a.n0 + a.piece_chunks);
         if (a.n0 >= a.n1) return;
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     const uint32_t kstride = (uint32_t)a.H * K;   // elements between consecutive tokens
 
     if (tid < K)
-        dcur[tid] = a.pieces ? a.piece_start[(bh * a.pieces + piece) * K + tid] : a.d_in ? a.d_in[bh * K + tid] : 1.f;
+        dcur[tid] = PIECES ? a.piece_start[(bh * a.pieces + piece) * K + tid] : a.d_in ? a.d_in[bh * K + tid] : 1.f;
     float PA = 1.f, PB = 0.f, PL = -FLT_MAX, PH = FLT_MAX;    // thread c < K: the piece so far, as a map of coordinate c
 
     typedef Pack<float, CPT> Pr;
@@ -270,7 +271,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
 #pragma unroll
             for (int e = 0; e < CPT; ++e) dcur[c0 + e] = dend[e];
         }
-        if (a.pieces && tid < K) {                // the accepted run maps, applied after the piece so far
+        if (PIECES && tid < K) {                 // the accepted run maps, applied after the piece so far
 #pragma unroll
             for (int j = 0; j < NRUN; ++j) {
                 const float4 m = maps[j * K + tid];
@@ -282,8 +283,8 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
         }
         __syncthreads();
     }
-    if (a.pieces && tid < K) a.piece_map[(bh * a.pieces + piece) * K + tid] = make_float4(PA, PB, PL, PH);
-    if (tid < K && (!a.pieces || piece == a.pieces - 1)) a.d_out[bh * K + tid] = dcur[tid];
+    if (PIECES && tid < K) a.piece_map[(bh * a.pieces + piece) * K + tid] = make_float4(PA, PB, PL, PH);
+    if (tid < K && (!PIECES || piece == a.pieces - 1)) a.d_out[bh * K + tid] = dcur[tid];
 }
 
 // ---- whole-sequence sweeps: the pieces of a chain side by side ----
@@ -322,13 +323,17 @@ int launch_precond_pieces_scan(const PrecondArgs &a, hipStream_t st) {
     return 0;
 }
 
-template <typename T, int RET>
-static int launch_precond_fwd_t(const PrecondArgs &a, hipStream_t st) {
-    dim3 grid((a.seq_chunks ? a.n_seqs : a.B) * a.H * (a.pieces ? a.pieces : 1)), block(P1T);
-    if (a.K == 64) hipLaunchKernelGGL((precond_fwd_kernel<T, 64, RET>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((precond_fwd_kernel<T, 128, RET>), grid, block, 0, st, a);
+template <typename T, int RET, bool PIECES>
+static int launch_precond_fwd_tp(const PrecondArgs &a, hipStream_t st) {
+    dim3 grid((a.seq_chunks ? a.n_seqs : a.B) * a.H * (PIECES ? a.pieces : 1)), block(P1T);
+    if (a.K == 64) hipLaunchKernelGGL((precond_fwd_kernel<T, 64, RET, PIECES>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((precond_fwd_kernel<T, 128, RET, PIECES>), grid, block, 0, st, a);
     else return -1;
     return 0;
+}
+template <typename T, int RET>
+static int launch_precond_fwd_t(const PrecondArgs &a, hipStream_t st) {
+    return a.pieces ? launch_precond_fwd_tp<T, RET, true>(a, st) : launch_precond_fwd_tp<T, RET, false>(a, st);
 }
 int launch_precond_fwd(const PrecondArgs &a, bool bf16_io, hipStream_t st) {
     const int ret = a.retention ? (a.ret_vec ? 2 : 1) : 0;
