@@ -51,7 +51,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Phase 1 as sweeps over the whole sequence: at most this many pieces over all chains, and at
 // most this many sweeps before the sequential kernel takes over.
-constexpr int MAX_PIECES = 512, MAX_PIECE_SWEEPS = 12;
+constexpr int MAX_PIECES = 512, MAX_PIECE_SWEEPS = 13;
 
 int check_params(const osdn_params *p, bool need_chunks) {
     if (!p) return OSDN_ERR_NULL;
@@ -148,9 +148,9 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
         L.p_v = take(B * T * H * V * es); L.p_o = take(B * T * H * V * es);
         L.p_beta = take(B * T * H * 4); L.p_g = take(B * T * H * 4 * GK); L.p_r = take(B * T * H * 4 * RK);
     }
-    L.piece_start = take((size_t)MAX_PIECES * K * 4);
-    L.piece_map = take((size_t)MAX_PIECES * K * 16);
-    L.piece_flags = take((MAX_PIECE_SWEEPS + 1) * sizeof(int));
+    L.piece_start = take((size_t)2 * MAX_PIECES * K * 4);
+    L.piece_map = take((size_t)2 * MAX_PIECES * K * 16);
+    L.piece_flags = take((MAX_PIECES / 2) * sizeof(int));       // one "settled" flag per chain
     L.total_fwd = off;
     L.dElt = take(B * T * H * V * es);
     L.Qt = take(B * T * H * K * es);
@@ -292,14 +292,14 @@ inline int seg_begin(int N, int S, int s) {
 // its walk over the chunks is the whole forward pass.  Every chain is cut into pieces (one
 // workgroup per CU over all chains, at least 8 chunks each); a sweep runs all pieces side by
 // side, each from its current start value, and leaves every piece as a composed map per
-// coordinate; a scan over those maps gives the next start values; the sweeps end when no start
-// value moves any more.  Plain batches only.  OSDN_P1_PIECES in the environment forces a number
+// coordinate; the next sweep walks those maps for its start values; a chain is settled when none
+// of its start values moves any more.  Plain batches only.  OSDN_P1_PIECES in the environment forces a number
 // of pieces per chain (0: never), OSDN_P1_PIECE_SWEEPS the sweep limit.
 inline void pieces_plan(int N, long long chains, bool packed, int &pieces, int &piece_chunks, int &sweeps) {
     pieces = 0; piece_chunks = 0;
     // sweeps needed without retention, measured: 4 at 64 and 128 chunks, then one more per
     // doubling (7 at 1024); the limit leaves two in hand
-    sweeps = 6;
+    sweeps = 7;                                  // (the last one only finds that nothing moved)
     for (int n = 128; n < N && sweeps < MAX_PIECE_SWEEPS; n *= 2) ++sweeps;
     if (packed || chains > MAX_PIECES / 2) return;
     const char *e = std::getenv("OSDN_P1_PIECES");
@@ -515,25 +515,23 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
                  : kid == KID_STATE_FWD ? launch_state_fwd(ck, bf, st) : launch_output_fwd(ck, bf, st);
         });
     };
-    // phase 1 as sweeps over the pieces of every chain; flags[i] != 0: sweep i + 1 has to run
-    // (flags[sweeps]: none of them ended the iteration, the sequential kernel runs)
+    // phase 1 as sweeps over the pieces of every chain, launched ahead of time; behind them the
+    // sequential kernel for the chains that have not settled by then
     auto precond_pieces = [&]() {
-        int *flags = reinterpret_cast<int *>(ws + L.piece_flags);
+        int *settled = reinterpret_cast<int *>(ws + L.piece_flags);
         PrecondArgs pp = pa;
         pp.n0 = 0; pp.n1 = N; pp.d_in = d_in;
         pp.pieces = pieces; pp.piece_chunks = piece_chunks;
         pp.piece_start = reinterpret_cast<float *>(ws + L.piece_start);
         pp.piece_map = reinterpret_cast<float4 *>(ws + L.piece_map);
-        if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_pieces_init(pp, flags, MAX_PIECE_SWEEPS + 1, st); }) != 0)
-            return -1;
+        pp.settled = settled;
         for (int i = 0; i < piece_sweeps; ++i) {
-            pp.run_if = flags + i; pp.changed_out = flags + i + 1;
+            pp.sweep = i;
             if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(pp, bf, st); }) != 0) return -1;
-            if (timed(KID_PRECOND_FWD, st, [&] { return launch_precond_pieces_scan(pp, st); }) != 0) return -1;
         }
-        pa.n0 = 0; pa.n1 = N; pa.d_in = d_in; pa.run_if = flags + piece_sweeps;
+        pa.n0 = 0; pa.n1 = N; pa.d_in = d_in; pa.settled = settled;
         const int rc1 = timed(KID_PRECOND_FWD, st, [&] { return launch_precond_fwd(pa, bf, st); });
-        pa.run_if = nullptr;
+        pa.settled = nullptr;
         return rc1;
     };
     if (!pl) {

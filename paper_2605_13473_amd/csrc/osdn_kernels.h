@@ -34,13 +34,13 @@ struct PrecondArgs {
     float *d_ckpt;            // [B,H,T/64,K] or null
     float *tok_scalars;       // [B,T,H,4] or null: per token (step, <d,k^2>, sum k^2, unused), kept for the backward
     // Sweeps over the whole sequence (pieces > 0, plain batches only): a chain is cut into
-    // pieces of piece_chunks chunks, one workgroup per piece, each starting from piece_start
-    // and leaving its piece as a map x -> clip3(A x + B, L, H) per coordinate in piece_map.
-    int pieces, piece_chunks;
-    float *piece_start;       // [B*H, pieces, K]
-    float4 *piece_map;        // [B*H, pieces, K]  (A, B, L, H)
-    const int *run_if;        // null, or: the launch does nothing unless *run_if != 0
-    int *changed_out;         // the scan over the pieces adds 1 here when a start value moved
+    // pieces of piece_chunks chunks, one workgroup per piece.  Sweep number `sweep` reads the
+    // start values and piece maps x -> clip3(A x + B, L, H) that sweep - 1 left (two buffers
+    // each, used in turn) and returns at once for a chain whose start values no longer move.
+    int pieces, piece_chunks, sweep;
+    float *piece_start;       // [2][B*H*pieces, K]
+    float4 *piece_map;        // [2][B*H*pieces, K]  (A, B, L, H)
+    int *settled;             // [B*H] or null: a chain whose entry is set is left alone
 };
 
 struct PrecondBwdArgs {
@@ -128,9 +128,6 @@ struct ChunkArgs {
 };
 
 int launch_precond_fwd(const PrecondArgs &a, bool bf16_io, hipStream_t st);
-// whole-sequence sweeps: first guesses and flags; the scan over the pieces of every chain
-int launch_precond_pieces_init(const PrecondArgs &a, int *flags, int n_flags, hipStream_t st);
-int launch_precond_pieces_scan(const PrecondArgs &a, hipStream_t st);
 int launch_step(const StepArgs &a, bool bf16_io, hipStream_t st);
 int launch_copy_rows(const void *src, int Ts, void *dst, int Td, int B, size_t row_bytes, uint32_t fill,
                      hipStream_t st);

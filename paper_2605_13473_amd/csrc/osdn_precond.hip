@@ -23,9 +23,10 @@
 //
 // For few long chains the same composition is taken one level up: the chain is cut into pieces,
 // one workgroup per piece walks its chunks from a start value it is given and also composes the
-// accepted run maps into one map for the piece; a scan over the piece maps gives the next start
-// values, and the sweeps over all pieces repeat until no start value moves (the caller launches
-// them ahead of time; a launch reads a device flag and returns at once when it is not needed).
+// accepted run maps into one map for the piece; the next sweep carries the chain's start value
+// through those maps to get its start values, and the sweeps over all pieces repeat until no
+// start value of a chain moves (the caller launches them ahead of time; the workgroups of a
+// settled chain return at once).
 #include "osdn_precond.h"
 
 #include <cfloat>
@@ -78,13 +79,13 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     __shared__ __attribute__((aligned(16))) float4 maps[NRUN * K];   // (A, B, L, H) per run and coordinate
     __shared__ int okflag[NRUN];
 
-    if (a.run_if && *a.run_if == 0) return;       // (the same for every thread of the launch)
     const int tid = threadIdx.x, run = tid >> 6, lane = tid & 63;
     const int c0 = lane * CPT;                    // first coordinate of this thread
     const int u_own = lane & (RUN - 1);           // the token of the run whose scalars this lane keeps
     const int piece = PIECES ? blockIdx.x % a.pieces : 0;
     const int chain = PIECES ? blockIdx.x / a.pieces : blockIdx.x;
     const int b = chain / a.H, h = chain % a.H;               // b: batch entry, or packed sequence
+    if (a.settled && !(PIECES && a.sweep == 0) && a.settled[chain]) return;
     if (PIECES) {
         a.n0 += piece * a.piece_chunks;
         a.n1 = min(a.n1, a.n0 + a.piece_chunks);
@@ -104,8 +105,39 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     const int N = (a.T + C - 1) / C;
     const uint32_t kstride = (uint32_t)a.H * K;   // elements between consecutive tokens
 
-    if (tid < K)
-        dcur[tid] = PIECES ? a.piece_start[(bh * a.pieces + piece) * K + tid] : a.d_in ? a.d_in[bh * K + tid] : 1.f;
+    if (!PIECES) {
+        if (tid < K) dcur[tid] = a.d_in ? a.d_in[bh * K + tid] : 1.f;
+    } else {
+        // The start value of this piece: the chain's own start value carried through the maps
+        // that the previous sweep left for the pieces before this one (first sweep: the chain's
+        // start value itself, as a guess).  Every workgroup of the chain walks all its pieces and
+        // so sees whether any start value moved by more than the tolerance of the sweeps; if
+        // none did, what the previous sweep wrote stands and the chain is settled.
+        const size_t buf = (size_t)gridDim.x * K;                 // elements of one buffer
+        const size_t cur = (a.sweep & 1) * buf, prev = buf - cur;
+        float x = 1.f, xs = 1.f;
+        bool moved = a.sweep == 0;
+        if (tid < K) {
+            x = xs = a.d_in ? a.d_in[bh * K + tid] : 1.f;
+            if (a.sweep > 0)
+                for (int q = 0; q < a.pieces; ++q) {
+                    const size_t i = (bh * a.pieces + q) * K + tid;
+                    const float old = a.piece_start[prev + i];
+                    if (q == piece) xs = x;
+                    if (!(fabsf(x - old) <= P1_TOL * fmaxf(fabsf(x), fabsf(old)))) moved = true;
+                    const float4 m = a.piece_map[prev + i];
+                    x = clip3(__builtin_fmaf(m.x, x, m.y), m.z, m.w);
+                }
+        }
+        const bool any = __syncthreads_or(moved);
+        if (piece == 0 && tid == 0) a.settled[chain] = any ? 0 : 1;
+        if (!any) return;
+        if (tid < K) {
+            dcur[tid] = xs;
+            a.piece_start[cur + (bh * a.pieces + piece) * K + tid] = xs;
+        }
+        a.piece_map += cur;
+    }
     float PA = 1.f, PB = 0.f, PL = -FLT_MAX, PH = FLT_MAX;    // thread c < K: the piece so far, as a map of coordinate c
 
     typedef Pack<float, CPT> Pr;
@@ -285,42 +317,6 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     }
     if (PIECES && tid < K) a.piece_map[(bh * a.pieces + piece) * K + tid] = make_float4(PA, PB, PL, PH);
     if (tid < K && (!PIECES || piece == a.pieces - 1)) a.d_out[bh * K + tid] = dcur[tid];
-}
-
-// ---- whole-sequence sweeps: the pieces of a chain side by side ----
-// First guess: every piece starts from the chain's own start value.  flags[0] = 1 (the first
-// sweep always runs), the others 0.
-__global__ void precond_pieces_init_kernel(PrecondArgs a, int *flags, int n_flags) {
-    const int chain = blockIdx.x, c = threadIdx.x;
-    const float x = a.d_in ? a.d_in[(size_t)chain * a.K + c] : 1.f;
-    for (int p = 0; p < a.pieces; ++p) a.piece_start[((size_t)chain * a.pieces + p) * a.K + c] = x;
-    if (chain == 0 && c < n_flags) flags[c] = c == 0 ? 1 : 0;
-}
-// One thread per coordinate walks the piece maps of its chain: the value that arrives at a piece
-// becomes its next start value.  A start value that moved by more than the tolerance of the
-// sweeps asks for another sweep.
-__global__ void precond_pieces_scan_kernel(PrecondArgs a) {
-    if (a.run_if && *a.run_if == 0) return;
-    const int chain = blockIdx.x, c = threadIdx.x;
-    float x = a.d_in ? a.d_in[(size_t)chain * a.K + c] : 1.f;
-    bool moved = false;
-    for (int p = 0; p < a.pieces; ++p) {
-        const size_t i = ((size_t)chain * a.pieces + p) * a.K + c;
-        const float old = a.piece_start[i];
-        if (!(fabsf(x - old) <= P1_TOL * fmaxf(fabsf(x), fabsf(old)))) moved = true;
-        a.piece_start[i] = x;
-        const float4 m = a.piece_map[i];
-        x = clip3(__builtin_fmaf(m.x, x, m.y), m.z, m.w);
-    }
-    if (__syncthreads_or(moved) && c == 0) atomicAdd(a.changed_out, 1);
-}
-int launch_precond_pieces_init(const PrecondArgs &a, int *flags, int n_flags, hipStream_t st) {
-    hipLaunchKernelGGL(precond_pieces_init_kernel, dim3(a.B * a.H), dim3(a.K), 0, st, a, flags, n_flags);
-    return 0;
-}
-int launch_precond_pieces_scan(const PrecondArgs &a, hipStream_t st) {
-    hipLaunchKernelGGL(precond_pieces_scan_kernel, dim3(a.B * a.H), dim3(a.K), 0, st, a);
-    return 0;
 }
 
 template <typename T, int RET, bool PIECES>
