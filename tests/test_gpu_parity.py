@@ -145,9 +145,12 @@ def test_precond_checkpoints_and_carry():
             assert (d2 - d_out).abs().max() <= 1e-5
 
 
-def test_resume_split_sequence():
+def test_resume_split_sequence(monkeypatch):
     """One call on T tokens equals two calls on T/2 with (S, d) carried (both vs the oracle, and
-    the two GPU results against each other bit for bit at a chunk boundary)."""
+    the two GPU results against each other bit for bit at a chunk boundary).  Bit for bit holds
+    for the sequential sweep of phase 1, which short sequences always take; the sweeps over
+    pieces agree to their tolerance only, so they are kept out even if the environment asks."""
+    monkeypatch.setenv("OSDN_P1_PIECES", "0")
     x = make_stress_inputs(2, 256, 2, 64, 128, seed=27, retention=0.97)
     hp = ob.Hyper(eta=0.3)
     o, S, d, _, t = gpu_forward(x, hp, False)
