@@ -244,20 +244,34 @@ Pipeline *pipeline_for_current_device() {
 //    meets a phase-1 chain kernel on the other stream and the two do not fit on one CU together:
 //    when the workgroups of both (chain_wgs) outnumber the CUs, the count that balances the
 //    exposed tail against that cost is about sqrt(N / 15) (2 at 64 chunks, 4 at 256); when they
-//    all fit side by side, about 32 chunks per segment, at most twelve.
+//    all fit side by side, about 32 chunks per segment, at most twelve: of that count and the two
+//    above it, the one whose segments fill whole rounds of bwd_post workgroups (one per chunk and
+//    chain, one per CU at a time) best.
 // Segments cut the chunk axis as a whole.  With packed sequences the sequential kernels of a
 // segment only have the sequences that cross it to work on, one after the other segment by
 // segment, so cutting pays only while one sequence makes up most of the axis; otherwise the
 // many independent chains fill the chip by themselves and everything runs in one piece.
 constexpr int NUM_CU = 256;
-int segment_count(int N, int longest, long long chain_wgs, bool backward) {
+int segment_count(int N, int longest, long long chain_wgs, bool backward, long long chains = 0) {
     static const int forced = [] { const char *e = std::getenv("OSDN_SEGMENTS"); return e ? std::atoi(e) : 0; }();
     if (forced <= 0 && (long long)longest * 4 < (long long)N * 3) return 1;
     int S = forced;
     if (forced <= 0) {
         if (!backward) S = N / 16 > 6 ? 6 : N / 16;
         else if (chain_wgs > NUM_CU) S = (int)std::lround(std::sqrt(N / 15.0)) > 6 ? 6 : (int)std::lround(std::sqrt(N / 15.0));
-        else S = N / 32 > 12 ? 12 : N / 32;
+        else {
+            S = N / 32 > 12 ? 12 : N / 32;
+            if (S < 2) S = 2;
+            double best = 0.0;
+            int pick = S;
+            for (int c = S; c <= S + 2 && c <= 12 && c <= N && chains > 0; ++c) {
+                const int first = N / (2 * c) > 0 ? N / (2 * c) : 1;
+                const double wgs = (double)(N - first) / (c - 1) * (double)chains;   // bwd_post workgroups of a segment
+                const double fill = wgs / (std::ceil(wgs / NUM_CU) * NUM_CU);
+                if (fill > best + 1e-9) { best = fill; pick = c; }
+            }
+            S = pick;
+        }
         if (S < 2 && N >= 2) S = 2;
     }
     if (S > MAX_SEGMENTS) S = MAX_SEGMENTS;
@@ -670,7 +684,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
 
     const int N = p->T / C;
     const long long chains = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
-    int S = segment_count(N, pk.longest, chains * (p->V / 32) + chains, true);   // chain kernel: 32 rows of the state per workgroup
+    int S = segment_count(N, pk.longest, chains * (p->V / 32) + chains, true, chains);   // chain kernel: 32 rows of the state per workgroup
     std::lock_guard<std::mutex> lock(g_pipe_mu);
     Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
     if (!pl) S = 1;
