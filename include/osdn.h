@@ -205,6 +205,18 @@ int osdn_bwd_packed(const osdn_params *p, const void *q, const void *k, const vo
                     void *stream);
 
 /*
+ * Diagnostic query for tests: the decisions of the projection's derivative (Section 4.5,
+ * reverse sweep through the projected affine recurrence) that osdn_bwd took, as it left them
+ * in the workspace.  Returns the byte offset, inside a workspace of a plain (not packed) batch
+ * that osdn_bwd has processed, of an array [B, H, ceil(T/64), K] of 64-bit words (low 32 bits
+ * first): bit i of word (b, h, n, c) is set iff the unprojected update of coordinate c at
+ * token 64 n + i landed inside the box [d_min, d_max], faces included.  Bits of tokens past T
+ * are unspecified; with d_min > d_max (no projection) the array is not written.  Returns 0 for
+ * invalid parameters.  Host-only: launches nothing.
+ */
+size_t osdn_debug_mask_offset(const osdn_params *p);
+
+/*
  * Optional per-kernel timing (for benchmarks; off by default; not thread-safe -- this switch
  * and its event list are the only process-wide state of the library).  While enabled, every
  * kernel an entry point launches is bracketed by a pair of HIP events on the caller's stream.

@@ -41,7 +41,7 @@ class _Params(ctypes.Structure):
         ("scale", ctypes.c_double), ("eta", ctypes.c_double),
         ("d_min", ctypes.c_double), ("d_max", ctypes.c_double),
         ("eps", ctypes.c_double), ("beta_aware", ctypes.c_int), ("gate_vec", ctypes.c_int),
-        ("ret_vec", ctypes.c_int), ("tie_tol", ctypes.c_double), ("tie_inside", ctypes.c_int),
+        ("ret_vec", ctypes.c_int),
     ]
 
 
@@ -54,10 +54,6 @@ class Hyper:
     d_max: float = 2.0
     eps: float = 1e-6
     beta_aware: bool = True
-    # backward only: unprojected values within tie_tol of a face of the box count as inside
-    # (tie_inside) or outside; 0 = the plain rule (see osdn_oracle.c)
-    tie_tol: float = 0.0
-    tie_inside: bool = True
 
 
 def _load():
@@ -94,7 +90,7 @@ def _params(hp: Hyper, B, T, H, K, V, retention=None, log_alpha=None) -> _Params
         assert log_alpha.shape in ((B, T, H), (B, T, H, K)), log_alpha.shape
         gate_vec = int(log_alpha.ndim == 4)      # one state gate per key channel: Diag(alpha_t)
     return _Params(B, T, H, K, V, scale, hp.eta, hp.d_min, hp.d_max, hp.eps, int(hp.beta_aware), gate_vec,
-                   ret_vec, float(hp.tie_tol), int(hp.tie_inside))
+                   ret_vec)
 
 
 def precond(k, beta, retention=None, d_in=None, hp: Hyper = Hyper(), want_traj: bool = False):
@@ -130,9 +126,13 @@ def fwd(q, k, v, beta, log_alpha=None, retention=None, d_in=None, S_in=None, hp:
 
 
 def bwd(q, k, v, beta, dO, log_alpha=None, retention=None, d_in=None, S_in=None,
-        dS_out=None, dd_out=None, hp: Hyper = Hyper()):
+        dS_out=None, dd_out=None, hp: Hyper = Hyper(), mask_force=None, want_dbar: bool = False):
     """Backward of ``fwd``.  Returns a dict with dq, dk, dv, dbeta, dlog_alpha,
-    dretention (None when the input was None), dd_in, dS_in."""
+    dretention (None when the input was None), dd_in, dS_in.
+
+    ``mask_force`` (int8 ``[B,T,H,K]``; 1 = inside, 0 = outside, negative = plain rule)
+    overrides single decisions of the projection's derivative; ``want_dbar`` adds
+    ``"dbar"``: every unprojected value r d_t + c s, ``[B,T,H,K]``."""
     lib = _load()
     q, k, v, beta, dO, log_alpha, retention, d_in, S_in, dS_out, dd_out = map(
         _f64, (q, k, v, beta, dO, log_alpha, retention, d_in, S_in, dS_out, dd_out))
@@ -146,10 +146,18 @@ def bwd(q, k, v, beta, dO, log_alpha=None, retention=None, d_in=None, S_in=None,
         "dretention": np.empty_like(retention) if retention is not None else None,
         "dd_in": np.empty((B, H, K)), "dS_in": np.empty((B, H, V, K)),
     }
-    rc = lib.osdn_oracle_bwd(ctypes.byref(P), _p(q), _p(k), _p(v), _p(beta), _p(log_alpha),
-                             _p(retention), _p(d_in), _p(S_in), _p(dO), _p(dS_out), _p(dd_out),
-                             _p(g["dq"]), _p(g["dk"]), _p(g["dv"]), _p(g["dbeta"]),
-                             _p(g["dlog_alpha"]), _p(g["dretention"]), _p(g["dd_in"]),
-                             _p(g["dS_in"]))
+    mf = None
+    if mask_force is not None:
+        mf = np.ascontiguousarray(mask_force, dtype=np.int8)
+        assert mf.shape == (B, T, H, K)
+    dbar = np.empty_like(k) if want_dbar else None
+    rc = lib.osdn_oracle_bwd_masked(
+        ctypes.byref(P), _p(q), _p(k), _p(v), _p(beta), _p(log_alpha),
+        _p(retention), _p(d_in), _p(S_in), _p(dO), _p(dS_out), _p(dd_out),
+        _p(g["dq"]), _p(g["dk"]), _p(g["dv"]), _p(g["dbeta"]),
+        _p(g["dlog_alpha"]), _p(g["dretention"]), _p(g["dd_in"]), _p(g["dS_in"]),
+        None if mf is None else mf.ctypes.data_as(ctypes.c_void_p), _p(dbar))
     assert rc == 0
+    if want_dbar:
+        g["dbar"] = dbar
     return g

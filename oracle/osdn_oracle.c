@@ -61,14 +61,6 @@ typedef struct {
     int ret_vec;       /* 1: retention is a vector per token and head, [B,T,H,K]: the
                           diag(r_t) extension of the APF step (proposition on APF being a
                           piecewise-affine recurrence, appendix); 0: scalar, [B,T,H] */
-    double tie_tol;    /* backward only, 0 by default.  The derivative of the projection is a
-                          decision (inside the box or not) taken on a floating-point value; an
-                          unprojected value within tie_tol of a face is one that fp32 arithmetic
-                          cannot place on either side reliably.  With tie_tol > 0 every such
-                          value is declared inside (tie_inside = 1) or outside (tie_inside = 0):
-                          the two admissible readings a lower-precision implementation may be
-                          compared with. */
-    int tie_inside;
 } osdn_oracle_params;
 
 /* retention of coordinate j of token-head th (NULL => 1) */
@@ -217,14 +209,26 @@ int osdn_oracle_fwd(const osdn_oracle_params *P, const double *q, const double *
  *
  * dS_out / dd_out: incoming adjoints of the returned S_T and d_{T+1} (NULL => 0).
  * dlog_alpha may be NULL when log_alpha is NULL; dretention NULL when retention is.
+ *
+ * The derivative of the projection (Section 4.5, "projected affine recurrence") is a
+ * decision per token and coordinate: the adjoint passes where the unprojected value
+ * d_bar = r d_t + c s lies inside the box (faces included) and is zero elsewhere.
+ *   dbar_out   (optional, [B,T,H,K]) receives every unprojected value, so that a caller can
+ *              see how far each decision was from a face;
+ *   mask_force (optional, [B,T,H,K], signed char) overrides single decisions: 1 = treat as
+ *              inside, 0 = treat as outside, negative = the plain rule.  A lower-precision
+ *              implementation cannot place a value that lies within its own rounding error
+ *              of a face on the same side as fp64 does; with its decisions forced at exactly
+ *              those positions, everything else must still agree.
  */
 #define SEG 64
-int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *k,
+int osdn_oracle_bwd_masked(const osdn_oracle_params *P, const double *q, const double *k,
                     const double *v, const double *beta, const double *log_alpha,
                     const double *retention, const double *d_in, const double *S_in,
                     const double *dO, const double *dS_out, const double *dd_out,
                     double *dq, double *dk, double *dv, double *dbeta, double *dlog_alpha,
-                    double *dretention, double *dd_in, double *dS_in)
+                    double *dretention, double *dd_in, double *dS_in,
+                    const signed char *mask_force, double *dbar_out)
 {
     const int B = P->B, T = P->T, H = P->H, K = P->K, V = P->V;
     const size_t VK = (size_t)V * K;
@@ -315,11 +319,10 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
                         double g = gd[j];
                         if (project) {
                             int inside = dbar[j] >= P->d_min && dbar[j] <= P->d_max;
-                            if (P->tie_tol > 0.0 && (fabs(dbar[j] - P->d_min) <= P->tie_tol ||
-                                                     fabs(dbar[j] - P->d_max) <= P->tie_tol))
-                                inside = P->tie_inside;
+                            if (mask_force && mask_force[th * K + j] >= 0) inside = mask_force[th * K + j];
                             if (!inside) g = 0.0;
                         }
+                        if (dbar_out) dbar_out[th * K + j] = dbar[j];
                         gd[j] = g;                       /* now adjoint of d_bar */
                         if (dretention && P->ret_vec) dretention[th * K + j] = g * dcur[j];
                         g_r += g * dcur[j];
@@ -396,4 +399,16 @@ int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *
             free(d); free(gd); free(gdn); free(kt); free(dbar); free(gkt); free(u); free(ge); free(alpha);
         }
     return fail ? -1 : 0;
+}
+
+int osdn_oracle_bwd(const osdn_oracle_params *P, const double *q, const double *k,
+                    const double *v, const double *beta, const double *log_alpha,
+                    const double *retention, const double *d_in, const double *S_in,
+                    const double *dO, const double *dS_out, const double *dd_out,
+                    double *dq, double *dk, double *dv, double *dbeta, double *dlog_alpha,
+                    double *dretention, double *dd_in, double *dS_in)
+{
+    return osdn_oracle_bwd_masked(P, q, k, v, beta, log_alpha, retention, d_in, S_in, dO, dS_out,
+                                  dd_out, dq, dk, dv, dbeta, dlog_alpha, dretention, dd_in, dS_in,
+                                  NULL, NULL);
 }

@@ -55,6 +55,8 @@ def lib():
         pp = ctypes.POINTER(OsdnParams)
         L.osdn_workspace_bytes.restype = ctypes.c_size_t
         L.osdn_workspace_bytes.argtypes = [pp, ctypes.c_int]
+        L.osdn_debug_mask_offset.restype = ctypes.c_size_t
+        L.osdn_debug_mask_offset.argtypes = [pp]
         L.osdn_strerror.restype = ctypes.c_char_p
         L.osdn_strerror.argtypes = [ctypes.c_int]
         L.osdn_precond_update.restype = ctypes.c_int
@@ -104,6 +106,10 @@ def osdn_strerror(status: int) -> str:
 
 def osdn_workspace_bytes(params: OsdnParams, for_backward: bool) -> int:
     return int(lib().osdn_workspace_bytes(ctypes.byref(params), int(bool(for_backward))))
+
+
+def osdn_debug_mask_offset(params: OsdnParams) -> int:
+    return int(lib().osdn_debug_mask_offset(ctypes.byref(params)))
 
 
 def _io_torch_dtype(params: OsdnParams):

@@ -3,27 +3,48 @@ from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libosdn.so")
-SOURCES = ["osdn_api.hip", "osdn_precond.hip", "osdn_precond_bwd.hip", "osdn_step.hip", "osdn_pad.hip", "osdn_chunk_fwd.hip", "osdn_chunk_bwd.hip"]
+SOURCES = ["osdn_api.hip", "osdn_precond.hip", "osdn_precond_bwd.hip", "osdn_step.hip", "osdn_pad.hip",
+           "osdn_chunk_fwd.hip", "osdn_chunk_bwd.hip"]
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every HIP source of the library into one shared object."""
+def build(verbose: bool = False, only=None) -> str:
+    """Compile every HIP source of the library (side by side, one hipcc per file) and link
+    them into one shared object.  `only`: recompile just these sources and reuse the other
+    objects of an earlier build (for quick iteration; the default compiles everything)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.check_call(cmd)
+    os.makedirs(OBJ, exist_ok=True)
+
+    def compile_one(src):
+        obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+        if only is not None and src not in only and os.path.exists(obj):
+            return obj
+        cmd = [hipcc, *FLAGS, "-c", "-o", obj, os.path.join(CSRC, src)]
+        if verbose:
+            print(" ".join(cmd))
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0 or verbose:
+            print(r.stdout)
+        if r.returncode != 0:
+            raise subprocess.CalledProcessError(r.returncode, cmd)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, only=sys.argv[1:] or None))

@@ -369,6 +369,13 @@ size_t osdn_workspace_bytes_packed(const osdn_params *p, const int32_t *cu_seqle
     return for_backward ? L.total_bwd : L.total_fwd;
 }
 
+size_t osdn_debug_mask_offset(const osdn_params *p) {
+    if (check_params(p, true) != OSDN_OK) return 0;
+    Packing pk;
+    plain_packing(p, pk);
+    return make_layout(p, pk).masks;
+}
+
 const char *osdn_strerror(int status) {
     switch (status) {
         case OSDN_OK: return "ok";

@@ -106,10 +106,15 @@ def make_inputs(cfg: Config, seed: int = 0) -> dict:
 
 
 def make_stress_inputs(B, T, H, K, V, seed=0, bf16=False, peaky=True, gated=True,
-                       retention=0.0, d_lo=0.5, d_hi=2.0):
+                       retention=0.0, d_lo=0.5, d_hi=2.0, key_norms=None, tiny_key_frac=0.0):
     """Inputs that make the preconditioner move by O(1) (for use with a large eta):
     keys with a few large coordinates, an initial d drawn uniformly in
-    [d_lo, d_hi], optional constant-mean retention.  Same draw-order discipline."""
+    [d_lo, d_hi], optional constant-mean retention.  Same draw-order discipline.
+    key_norms = (lo, hi): keys are not normalised; every token's norm is drawn log-uniformly
+    from [lo, hi], and a fraction tiny_key_frac of the tokens gets a norm of 1e-4 to 1e-3
+    (squared norm below the usual floor eps = 1e-6); beta is then capped token by token so
+    that the recurrence stays bounded.  These draws come last, so the other tensors (beta's cap
+    aside) do not depend on them."""
     rng = np.random.Generator(np.random.Philox(seed))
     f32 = np.float32
     q = _unit(rng.standard_normal((B, T, H, K), dtype=f32))
@@ -126,6 +131,15 @@ def make_stress_inputs(B, T, H, K, V, seed=0, bf16=False, peaky=True, gated=True
     r = None
     if retention > 0.0:
         r = np.clip(retention + 0.02 * rng.standard_normal((B, T, H), dtype=f32), 0.0, 1.0).astype(f32)
+    if key_norms is not None:
+        lo, hi = key_norms
+        norm = np.exp(np.log(lo) + (np.log(hi) - np.log(lo)) * rng.random((B, T, H, 1), dtype=f32))
+        tiny = rng.random((B, T, H, 1), dtype=f32) < tiny_key_frac
+        norm = np.where(tiny, 1e-4 * (1.0 + 9.0 * rng.random((B, T, H, 1), dtype=f32)), norm)
+        k = (k * norm).astype(f32)
+        # keep the tokens with long keys from blowing the state up over a long sequence: the write
+        # scales the state along k by 1 - beta <k, d k>, so beta is capped at 0.95 / (d_hi |k|^2)
+        beta = np.minimum(beta, 0.95 / (d_hi * (norm[..., 0] ** 2))).astype(f32)
     if bf16:
         q, k, v, dO = (round_to_bf16(a) for a in (q, k, v, dO))
     return {

@@ -7,7 +7,8 @@ import torch
 import oracle
 from paper_2605_13473_amd import binding as ob
 from paper_2605_13473_amd.inputs import CONFIGS, make_inputs, make_stress_inputs
-from tests.gpu_util import check, compare_backward, compare_forward, f64, gpu_forward, oracle_hp, to_dev
+from tests.gpu_util import (check, check_gradients, compare_backward, compare_forward, f64, gpu_forward,
+                            oracle_hp, to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -243,51 +244,86 @@ def test_argument_errors_launch_nothing():
     assert bool((o == 7.0).all())
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape,retention", [((2, 320, 2, 64, 128), 0.97), ((1, 448, 3, 128, 64), 0.0)])
+def test_keys_not_normalised(shape, retention, bf16):
+    """Keys as they come, not normalised: per-token norms log-uniform in [0.2, 4] and one token in
+    twenty with a squared norm below eps.  The 1 / max(|k|^2, eps) factor of the d update, the
+    floor itself, the derivative through the norm in the reverse sweep and large entries of the
+    UT system (beta <k_i, k~_j> up to about 2) are then all live, forward and backward."""
+    B, T, H, K, V = shape
+    x = make_stress_inputs(B, T, H, K, V, seed=81, bf16=bf16, retention=retention, key_norms=(0.2, 4.0),
+                           tiny_key_frac=0.05)
+    n2 = (x["k"].astype(np.float64) ** 2).sum(-1)
+    assert (n2 < 1e-6).any() and n2.max() > 9.0
+    rng = np.random.default_rng(82)
+    dS = rng.standard_normal((B, H, V, K)).astype(np.float32)
+    dd = rng.standard_normal((B, H, K)).astype(np.float32)
+    hp = ob.Hyper(eta=0.5)
+    compare_forward(x, hp, bf16)
+    compare_backward(x, hp, bf16, dS, dd)
+    _, _, traj = oracle.precond(x["k"], x["beta"], x["retention"], x["d_in"], oracle_hp(hp), want_traj=True)
+    assert traj.max() - traj.min() > 0.5
+
+
+@pytest.mark.parametrize("seed", [91, 92, 93])
+def test_eta_one_no_retention_coordinates_on_the_upper_face(seed):
+    """eta = 1, no retention, 320 tokens: coordinates sit on the upper face of the box for
+    hundreds of tokens and take pushes of either sign that are smaller than an ulp of the face,
+    so single projection decisions of the fp32 library and the fp64 oracle differ.  The parity
+    helper checks every such decision's distance to the face and compares the gradients under
+    the library's own decisions at exactly those positions."""
+    x = make_stress_inputs(2, 320, 2, 64, 64, seed=seed, bf16=False, retention=0.0)
+    hp = ob.Hyper(eta=1.0)
+    compare_forward(x, hp, False)
+    compare_backward(x, hp, False)
+    _, _, traj = oracle.precond(x["k"], x["beta"], None, x["d_in"], oracle_hp(hp), want_traj=True)
+    assert (traj == 2.0).mean() > 0.02
+
+
 # ----------------------------------------------------------- full-size configs ----
-def _sample_chains(x, chains):
-    """Slice (b,h) chains out of a full batch as a [1, T, n, .] batch (chains are independent)."""
-    out = {}
-    for name, a in x.items():
-        if a is None:
-            out[name] = None
-        elif name in ("d_in",):
-            out[name] = np.stack([a[b, h] for b, h in chains], 0)[None]
-        elif name in ("S_in",):
-            out[name] = np.stack([a[b, h] for b, h in chains], 0)[None]
-        else:
-            out[name] = np.stack([a[b, :, h] for b, h in chains], 1)[None]
-    return out
-
-
-@pytest.mark.parametrize("ci", [1, 2, 3, 4])
-def test_full_size_configs_sampled_chains(ci):
-    """The benchmark configurations at full size, in the launch configuration the benchmark
-    times; the oracle recomputes two whole (b,h) chains (first and last)."""
-    cfg = CONFIGS[ci]
-    x = make_inputs(cfg, seed=0)
-    hp = ob.Hyper()
+def _full_size(x, hp, cfg):
+    """One full-size launch, every (batch, head) chain compared with the oracle."""
     o, S, d, ctx, t = gpu_forward(x, hp, cfg.bf16, for_backward=cfg.backward)
-    assert torch.isfinite(o.float()).all()
-    assert float(d.min()) >= hp.d_min and float(d.max()) <= hp.d_max
-    chains = [(0, 0), (cfg.B - 1, cfg.H - 1)]
-    y = f64(_sample_chains(x, chains))
-    oo, oS, od = oracle.fwd(y["q"], y["k"], y["v"], y["beta"], y["log_alpha"], y["retention"], None, None,
-                            oracle_hp(hp))
-    pick = lambda tns, tok: torch.stack([tns[b, :, h] for b, h in chains], 1)[None] if tok else \
-        torch.stack([tns[b, h] for b, h in chains], 0)[None]
-    check("o", pick(o, True), oo, cfg.bf16)
-    check("S_out", pick(S, False), oS, cfg.bf16)
-    check("d_out", pick(d, False), od, False)
+    y = f64(x)
+    oo, oS, od = oracle.fwd(y["q"], y["k"], y["v"], y["beta"], y.get("log_alpha"), y.get("retention"),
+                            y.get("d_in"), y.get("S_in"), oracle_hp(hp))
+    check("o", o, oo, cfg.bf16)
+    check("S_out", S, oS, cfg.bf16)
+    check("d_out", d, od, False)
+    del oo, oS
     if cfg.backward:
         g = ob.backward(ctx, t["dO"])
         torch.cuda.synchronize()
-        og = oracle.bwd(y["q"], y["k"], y["v"], y["beta"], y["dO"], y["log_alpha"], y["retention"],
-                        None, None, hp=oracle_hp(hp))
-        for name, ref in og.items():
-            if ref is None:
-                continue
-            tok = name not in ("dd_in", "dS_in")
-            check(name, pick(g[name], tok), ref, cfg.bf16)
+
+        def oracle_bwd(ohp, mask_force=None, want_dbar=False):
+            return oracle.bwd(y["q"], y["k"], y["v"], y["beta"], y["dO"], y.get("log_alpha"), y.get("retention"),
+                              y.get("d_in"), y.get("S_in"), hp=ohp, mask_force=mask_force, want_dbar=want_dbar)
+
+        check_gradients(g, oracle_bwd, hp, cfg.bf16, ctx)
+    return od
+
+
+@pytest.mark.parametrize("ci", [1, 2, 3, 4])
+def test_full_size_configs_every_chain(ci):
+    """The benchmark configurations at full size, in the launch configuration the benchmark
+    times; the oracle recomputes every (batch, head) chain, forward and (where the
+    configuration has one) backward."""
+    cfg = CONFIGS[ci]
+    hp = ob.Hyper()
+    od = _full_size(make_inputs(cfg, seed=0), hp, cfg)
+    assert od.min() >= hp.d_min and od.max() <= hp.d_max
+
+
+def test_full_size_config2_with_a_live_preconditioner():
+    """Configuration 2's shape and launch configuration with the stress inputs at eta = 0.5: at
+    the paper's eta = 0.003 d moves by about 0.02 over a sequence, so the full-size run above
+    could not tell a wrong d path from a right one; here d moves by O(1), meets both faces of
+    the box, and every chain is compared forward and backward."""
+    cfg = CONFIGS[2]
+    x = make_stress_inputs(cfg.B, cfg.T, cfg.H, cfg.K, cfg.V, seed=83, bf16=True, retention=0.0)
+    od = _full_size(x, ob.Hyper(eta=0.5), cfg)
+    assert od.max() - od.min() > 1.0
 
 
 @pytest.mark.parametrize("pieces", [False, True])

@@ -233,6 +233,40 @@ def test_projection_retention_and_flags():
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
 
 
+def test_eps_is_a_floor_of_the_denominator_and_beta_enters_only_where_stated():
+    """Two properties that fix where eps and the beta-aware flag enter, without restating the
+    update (the unfloored beta-aware step is pinned by the hypergradient's definition above).
+    (1) One token from the same d: a key with |k|^2 = m < eps moves d by exactly m / eps times
+        what it does when the floor is out of reach (eps' << m), and a key with |k|^2 >= eps is
+        untouched by eps: eps only floors the denominator (Eq. (dt_update): max(|k|^2, eps)).
+    (2) The non-beta-aware sweep equals the beta-aware one run with beta = 1 in every d, while
+        k~_t = d_t (.) k_t; the state's own beta is not part of phase 1 at all."""
+    rng = np.random.default_rng(33)
+    K = 6
+    d0 = rng.uniform(0.6, 1.9, (1, 1, K))
+    beta = np.full((1, 1, 1), 0.7)
+    nobox = dict(d_min=1.0, d_max=0.0)
+    for norm2, floored in ((1e-8, True), (3e-6, False), (1.0, False)):
+        k = rng.standard_normal((1, 1, 1, K))
+        k *= np.sqrt(norm2) / np.linalg.norm(k)
+        m = float((k * k).sum())
+        _, d_eps = oracle.precond(k, beta, d_in=d0, hp=Hyper(eta=0.4, eps=1e-6, **nobox))
+        _, d_free = oracle.precond(k, beta, d_in=d0, hp=Hyper(eta=0.4, eps=1e-30, **nobox))
+        ratio = m / 1e-6 if floored else 1.0
+        np.testing.assert_allclose(d_eps - d0, ratio * (d_free - d0), rtol=1e-9, atol=1e-18)
+        assert np.abs(d_free - d0).max() > 0
+    B, T, H = 2, 40, 2
+    k = rng.standard_normal((B, T, H, K)) * rng.choice([0.3, 1.0, 2.0], (B, T, H, 1))
+    beta = rng.uniform(0.05, 0.95, (B, T, H))
+    r = rng.uniform(0.8, 1.0, (B, T, H))
+    d0 = rng.uniform(0.5, 2.0, (B, H, K))
+    kt_a, d_a, tr_a = oracle.precond(k, beta, r, d0, Hyper(eta=0.2, beta_aware=False), want_traj=True)
+    kt_b, d_b, tr_b = oracle.precond(k, np.ones_like(beta), r, d0, Hyper(eta=0.2, beta_aware=True), want_traj=True)
+    assert np.array_equal(d_a, d_b) and np.array_equal(tr_a, tr_b) and np.array_equal(kt_a, kt_b)
+    kt_c, d_c = oracle.precond(k, beta, r, d0, Hyper(eta=0.2, beta_aware=True))
+    assert np.abs(d_c - d_a).max() > 1e-3                        # the flag is not inert
+
+
 def test_pure_retention_closed_form():
     """eta = 0, r < 1: d_T = max(d_min, prod r * d_0)."""
     rng = np.random.default_rng(11)
@@ -509,32 +543,82 @@ def test_backward_clamp_tie_passes_gradient():
     assert g["dd_in"][0, 0, 0] == 1.0
 
 
-def test_near_tie_readings_of_the_box_mask():
-    """tie_tol > 0 changes the backward only where an unprojected value lies within tie_tol of a
-    face: with none it changes nothing; with one planted (a push that misses the face by 1e-9)
-    the plain rule and the matching reading agree and the opposite reading zeroes exactly that
-    coordinate's gradient."""
+def test_forced_box_decisions_planted_near_tie():
+    """mask_force changes the backward only at the positions it names: forcing the plain
+    decisions everywhere changes nothing; with a push planted 1e-9 below the upper face,
+    forcing that one decision to "outside" zeroes exactly that coordinate's gradient; dbar
+    reports the unprojected values (here: the planted distance to the face)."""
     K = 4
     k = np.zeros((1, 2, 1, K)); k[0, :, 0, 1] = 1.0             # unit keys on coordinate 1
     beta = np.full((1, 2, 1), 0.5); q = np.zeros_like(k); v = np.zeros((1, 2, 1, 1)); dO = np.zeros_like(v)
     d0 = np.array([[[1.0, 1.9, 1.0, 1.0]]])
     # d_bar of coordinate 1 after token 0: 1.9 + eta*0.5*(1 - 0.5*1.9) = 1.9 + 0.025 eta  -> face 2.0 at eta = 4
     w = np.ones((1, 1, K))
-    plain = Hyper(eta=4.0 - 4e-8)                               # lands 1e-9 below the face: inside
-    assert 0 < 2.0 - (1.9 + 0.025 * plain.eta) < 2e-9
-    import dataclasses
-    g0 = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=plain)
-    gi = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=dataclasses.replace(plain, tie_tol=1e-6, tie_inside=True))
-    go = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=dataclasses.replace(plain, tie_tol=1e-6, tie_inside=False))
-    for n in g0:
-        if g0[n] is not None:
-            assert np.array_equal(g0[n], gi[n]), n
+    hp = Hyper(eta=4.0 - 4e-8)                                  # lands 1e-9 below the face: inside
+    g0 = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=hp, want_dbar=True)
+    dbar = g0.pop("dbar")
+    assert 0 < 2.0 - dbar[0, 0, 0, 1] < 2e-9 and dbar[0, 0, 0, 0] == 1.0
+    plain = ((dbar >= hp.d_min) & (dbar <= hp.d_max)).astype(np.int8)
+    for force in (plain, np.full_like(plain, -1)):
+        gi = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=hp, mask_force=force)
+        assert all(np.array_equal(g0[n], gi[n]) for n in g0 if g0[n] is not None)
+    force = np.full_like(plain, -1); force[0, 0, 0, 1] = 0
+    go = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=hp, mask_force=force)
     assert g0["dd_in"][0, 0, 1] != 0.0 and go["dd_in"][0, 0, 1] == 0.0
     assert np.array_equal(np.delete(g0["dd_in"], 1, axis=-1), np.delete(go["dd_in"], 1, axis=-1))
-    far = Hyper(eta=0.05)                                        # nothing near a face: the option is inert
-    a = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=far)
-    b = oracle.bwd(q, k, v, beta, dO, None, None, d0, None, dd_out=w, hp=dataclasses.replace(far, tie_tol=1e-6, tie_inside=False))
-    assert all(np.array_equal(a[n], b[n]) for n in a if a[n] is not None)
+
+
+@pytest.mark.parametrize("retention", [False, True])
+def test_forced_box_decisions_against_frozen_mask_differences(retention):
+    """The reverse sweep under an arbitrary 0/1 pattern M of projection decisions, against
+    central differences of an independently coded phase 1 whose projection is replaced by the
+    affine map with that frozen derivative: d_{t+1} = clip(dbar0_t) + M_t (.) (dbar_t - dbar0_t)
+    (same trajectory at the base point, derivative M_t).  Loss: <w, d_T>."""
+    rng = np.random.default_rng(5)
+    T, K = 12, 6
+    k = rng.standard_normal((T, K)) * (0.5 + rng.random((T, 1)))     # norms away from 1
+    beta = 1 / (1 + np.exp(-rng.standard_normal(T)))
+    r = 0.8 + 0.2 * rng.random(T) if retention else np.ones(T)
+    d0 = 0.5 + 1.5 * rng.random(K)
+    w = rng.standard_normal(K)
+    eta, lo, hi, eps = 1.5, 0.5, 2.0, 1e-6
+    M = rng.random((T, K)) < 0.6
+
+    def dbar_of(d, kt, bt, rt):
+        s = kt * kt
+        n = max(s.sum(), eps)
+        return rt * d + eta * bt * (1 - bt * (d @ s)) / n * s
+
+    base_dbar, d = [], d0.copy()
+    for t in range(T):
+        base_dbar.append(dbar_of(d, k[t], beta[t], r[t]))
+        d = np.clip(base_dbar[-1], lo, hi)
+    assert any(((b < lo) | (b > hi)).any() for b in base_dbar)          # the box is active
+
+    def loss(d_in, kk, bb, rr):
+        d = d_in.copy()
+        for t in range(T):
+            d = np.clip(base_dbar[t], lo, hi) + M[t] * (dbar_of(d, kk[t], bb[t], rr[t]) - base_dbar[t])
+        return w @ d
+
+    sh = lambda a: a.reshape((1, T, 1) + a.shape[1:])
+    g = oracle.bwd(np.zeros((1, T, 1, K)), sh(k), np.zeros((1, T, 1, 1)), sh(beta), np.zeros((1, T, 1, 1)),
+                   None, sh(r) if retention else None, d0.reshape(1, 1, K), None, dd_out=w.reshape(1, 1, K),
+                   hp=Hyper(eta=eta, d_min=lo, d_max=hi, eps=eps), mask_force=sh(M.astype(np.int8)))
+    h = 1e-6
+    args = {"dd_in": d0, "dk": k, "dbeta": beta}
+    if retention:
+        args["dretention"] = r
+    for gname, arr in args.items():
+        flat = arr.reshape(-1)
+        an = g[gname].reshape(-1)
+        for i in range(flat.size):
+            old = flat[i]
+            flat[i] = old + h; lp = loss(d0, k, beta, r)
+            flat[i] = old - h; lm = loss(d0, k, beta, r)
+            flat[i] = old
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - an[i]) <= 2e-6 * max(1.0, abs(fd)), (gname, i, fd, an[i])
 
 
 def test_chain_rule_through_key_scaling():
