@@ -31,14 +31,38 @@ PEAK_BF16_FLOPS = 2.5e15       # MI355X dense bf16 MFMA
 PEAK_HBM_BYTES = 8.0e12        # MI355X HBM3E
 PEAK_FP32_VALU = 157.3e12
 
-# HBM bytes per step (summed over a kernel's launches) on configs[2], from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by the
-# factors a 1 GiB device copy gives: fetch x 2.0, write x 1.0); see
-# profiles/hbm_traffic_configs2_fwd_bwd.txt.  Offline figures: bench.py cannot read PMCs.
-MEASURED_TRAFFIC_CONFIG2 = {
-    "precond_fwd": 153.8e6, "chunk_prep": 446.3e6, "state_fwd": 441.1e6, "output_fwd": 407.8e6,
-    "bwd_local": 404.1e6, "bwd_chain": 558.1e6, "bwd_post": 1047.6e6, "precond_mask": 77.7e6,
-    "precond_chain": 191.2e6, "precond_post": 328.7e6,
-}
+
+
+def measured_traffic(config_index):
+    """HBM bytes per step and kernel from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of
+    this workload (bench.py cannot read performance counters itself): {kernel: bytes}, or {}."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_configs{config_index}_fwd_bwd.txt")
+    out = {}
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 7 and f[0].replace("_", "").isalpha():
+                try:
+                    out[f[0]] = float(f[6]) * 1e6          # column "total MB"
+                except ValueError:
+                    pass
+    except OSError:
+        pass
+    return out
+
+
+def algorithmic_bytes(cfg, es, backward_pass):
+    """Compulsory HBM bytes of one pass with perfect fusion, per token-head: every input and
+    output once, nothing for intermediates or checkpoints (gates fp32).
+    forward: q, k, v in, o out, beta and log alpha;  backward: q, k, v, dO in, dq, dk, dv out,
+    beta, log alpha and their gradients;  retention and its gradient on top with APF."""
+    K, V = cfg.K, cfg.V
+    if not backward_pass:
+        return (2 * K + 2 * V) * es + 8 + (4 if cfg.apf else 0)
+    return (4 * K + 3 * V) * es + 16 + (8 if cfg.apf else 0)
+
+
+FORWARD_KERNELS = ("precond_fwd", "chunk_prep", "state_fwd", "output_fwd")
 
 
 def kernel_models(cfg, es):
@@ -78,6 +102,23 @@ def kernel_models(cfg, es):
         "bwd_post": th * (C * V + 2 * K * V + 2 * C * V + 6 * K * V + 2 * C * K + 4 * C * K),
     }
     return m, flops
+
+
+def copy_rate(torch, dev, gib=1, reps=5):
+    """Measured rate of a plain device copy of `gib` GiB (bytes read + written per second, GB/s):
+    what this machine's HBM sustains, next to the 8 TB/s peak the fractions are quoted against."""
+    n = gib << 28
+    src = torch.empty(n, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * 4 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
 def decode_bench(args, cfg):
@@ -146,7 +187,8 @@ def main():
                     help="side workload, not the headline: the configuration's shape with one state gate per key "
                          "channel (online-scaled KDA), log alpha = -softplus(N(-1,1)) per channel")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also launch a plain device copy of 1 GiB (reference for the HBM byte counters)")
+                    help="also launch one plain device copy of 1 GiB before the steps (the reference that scales "
+                         "the rocprofv3 HBM byte counters; its rate is printed with every result anyway)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every (batch, head) chain is independent, "
@@ -246,22 +288,23 @@ def main():
     launches = {k: n // args.steps for k, (ms, n) in prof.items() if n > 0}
     dominant = max(per_kernel, key=per_kernel.get)
     models, flops = kernel_models(cfg, es)
-    bound, nbytes = models[dominant]
+    th = cfg.B * cfg.T * cfg.H                          # token-heads of one step
     dur = per_kernel[dominant] * 1e-3
-    hbm_frac = nbytes / dur / PEAK_HBM_BYTES
-    mfma_frac = flops.get(dominant, 0.0) / dur / PEAK_BF16_FLOPS if cfg.bf16 else 0.0
-    if mfma_frac > hbm_frac:
-        roof = {"bound": "mfma", "achieved": flops[dominant] / dur / 1e12, "peak": PEAK_BF16_FLOPS / 1e12,
-                "unit": "TFLOP/s", "frac": mfma_frac, "traffic": None}
-    else:
-        roof = {"bound": "hbm", "achieved": nbytes / dur / 1e9, "peak": PEAK_HBM_BYTES / 1e9,
-                "unit": "GB/s", "frac": hbm_frac, "traffic": None}
-    if args.config == 2 and cu is None:
-        roof["traffic"] = MEASURED_TRAFFIC_CONFIG2.get(dominant)
-    roof["kernel"] = dominant
-    roof["kernel_ms"] = per_kernel[dominant]
-    roof["per_kernel_ms"] = {k: round(v, 4) for k, v in per_kernel.items()}
-    roof["launches_per_step"] = launches[dominant]
+    # algorithmic bytes of the pass the dominant kernel belongs to (perfect fusion: no
+    # intermediates), over that kernel's time per step
+    in_bwd = dominant not in FORWARD_KERNELS
+    alg_bytes = th * algorithmic_bytes(cfg, es, in_bwd)
+    own_io = models[dominant][1]                        # the kernel's own inputs and outputs, every tensor once
+    roof = {"bound": "hbm", "achieved": alg_bytes / dur / 1e9, "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s",
+            "frac": alg_bytes / dur / PEAK_HBM_BYTES,
+            "traffic": measured_traffic(args.config).get(dominant) if cu is None and not args.channel_gate else None,
+            "kernel": dominant, "kernel_ms": per_kernel[dominant], "launches_per_step": launches[dominant],
+            "algorithmic_bytes": alg_bytes,
+            "algorithmic_bytes_of": ("backward" if in_bwd else "forward") + " pass, perfect fusion",
+            "own_io_model": {"bytes": own_io, "GB/s": own_io / dur / 1e9, "frac": own_io / dur / PEAK_HBM_BYTES,
+                             "note": "the kernel's own inputs and outputs once each, intermediates included"},
+            "mfma_frac_of_kernel": flops.get(dominant, 0.0) / dur / PEAK_BF16_FLOPS if cfg.bf16 else None,
+            "per_kernel_ms": {k: round(v, 4) for k, v in per_kernel.items()}}
     if copies_ms is not None:
         roof["per_kernel_ms"]["pad (copies)"] = round(copies_ms, 4)
     if unfold_ms is not None:
@@ -271,9 +314,15 @@ def main():
     K, V, C = cfg.K, cfg.V, 64
     f_fwd = 6 * K * V + 3 * C * K + 2 * C * V + C * C / 3.0
     f_bwd = 12 * K * V + 4 * C * K + 4 * C * V
-    th = cfg.B * cfg.T * cfg.H
     total_flops = th * (f_fwd + (f_bwd if cfg.backward else 0.0))
     mfma_peak_frac = total_flops / (ms_per_step * 1e-3) / PEAK_BF16_FLOPS
+    path_bytes = th * (algorithmic_bytes(cfg, es, False) + (algorithmic_bytes(cfg, es, True) if cfg.backward else 0))
+    path_hbm_frac = path_bytes / (ms_per_step * 1e-3) / PEAK_HBM_BYTES
+    binding = "hbm" if path_bytes / PEAK_HBM_BYTES > total_flops / PEAK_BF16_FLOPS else "mfma"
+    prop = torch.cuda.get_device_properties(0)
+    device = {"name": prop.name, "compute_units": prop.multi_processor_count,
+              "clock_mhz": getattr(prop, "clock_rate", 0) / 1e3 or None,
+              "hbm_gib": round(prop.total_memory / 2 ** 30, 1), "copy_GBps": copy_rate(torch, dev)}
 
     cpu = None
     if not args.no_cpu_baseline and cu is None and not args.channel_gate:
@@ -310,6 +359,10 @@ def main():
                    "global_batch": cfg.B, "seq_len": cfg.T, "apf": cfg.apf,
                    **({} if cu is None else {"packed_sequences": len(cu) - 1})},
         "mfma_peak_frac": mfma_peak_frac,
+        "path_roofline": {"binding": binding, "algorithmic_bytes": path_bytes, "algorithmic_flops": total_flops,
+                          "hbm_frac": path_hbm_frac, "mfma_frac": mfma_peak_frac,
+                          "t_hbm_ms": 1e3 * path_bytes / PEAK_HBM_BYTES, "t_mfma_ms": 1e3 * total_flops / PEAK_BF16_FLOPS},
+        "device": device,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

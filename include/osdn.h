@@ -30,16 +30,19 @@
  *   - Return value: OSDN_OK (0) or a negative osdn_status.  On an argument error nothing
  *     is launched.  osdn_strerror() gives a static description.
  *   - The library allocates no device memory: scratch comes from the caller's `workspace`
- *     (256-byte aligned, at least osdn_workspace_bytes()).  Its only process-wide state is the
- *     optional profiling switch at the end of this file and, created on first use and kept
- *     (one per device), a side stream with a few events: osdn_fwd / osdn_bwd run the
- *     preconditioner phase on it, forked from and joined back into `stream`, so that to the
- *     caller all work still is ordered as if enqueued on `stream`.  Calls are serialised by a
- *     mutex while they enqueue.  OSDN_SEGMENTS=1 in the environment keeps everything on `stream`.
+ *     (256-byte aligned, at least osdn_workspace_bytes()).  It reads no environment variables.
+ *     Process-wide state: the optional profiling switch at the end of this file and, created on
+ *     first use and kept until the process ends, one side stream with a few events per
+ *     (device, caller stream): osdn_fwd / osdn_bwd run the preconditioner phase on it, forked
+ *     from and joined back into `stream` with events, so that to the caller all work still is
+ *     ordered as if enqueued on `stream` (also under stream capture: the side stream joins the
+ *     capture and leaves it inside the call).  Calls on different streams share nothing; calls
+ *     that share one stream must be issued one after the other, as any work on one stream.
+ *     params->segments = 1 keeps everything on `stream`.
  *     With at most 32 (batch, head) chains of at least 64 chunks, osdn_fwd computes the
  *     preconditioner as a few sweeps over pieces of the sequence that run side by side, all on
- *     `stream` (same results to the tolerance of the sweeps, 1e-6 relative; OSDN_P1_PIECES=0 in
- *     the environment keeps the one sequential sweep per chain).
+ *     `stream` (same results to the tolerance of the sweeps, 1e-6 relative; params->p1_pieces = -1
+ *     keeps the one sequential sweep per chain).
  *   - retention values are assumed >= 0 (they are sigmoid gates in the paper).  Wherever a
  *     signature says retention / dretention [B,T,H], params->retention_per_channel = 1 makes
  *     it [B,T,H,K]: one value per coordinate.  Likewise params->gate_per_channel = 1 makes
@@ -47,8 +50,9 @@
  *     (online-scaled KDA, appendix section on Kimi Delta Attention with online scaling).
  *   - Supported shapes: chunk == 64; any T >= 1 (osdn_fwd/osdn_bwd pad a ragged last chunk
  *     inside the workspace with tokens that change nothing; osdn_precond_update needs
- *     T % 64 == 0 only when d_ckpt is asked for; 1 <= T <= 64 for osdn_step); K in {64, 128};
- *     V a multiple of 64 up to 512; B, H >= 1 with H * max(K, V) < 2^24 (the 64 token rows of
+ *     T % 64 == 0 only when d_ckpt is asked for; 1 <= T <= 64 for osdn_step); K in {64, 128}
+ *     (K = 256 is not built: the [64 x K] operand tiles of the chain and backward kernels would
+ *     no longer fit the 160 KB of LDS next to each other); V a multiple of 64 up to 512; B, H >= 1 with H * max(K, V) < 2^24 (the 64 token rows of
  *     a chunk are addressed with 32-bit byte offsets).  Anything else returns OSDN_ERR_SHAPE.
  */
 #ifndef OSDN_H
@@ -93,6 +97,14 @@ typedef struct {
                                        too and log_alpha must not be NULL.  In the chunkwise entry
                                        points the cumulative log-decay of a channel inside a chunk
                                        of 64 tokens has to stay above about -80 */
+    /* Scheduling knobs; 0 everywhere = the library decides (what the benchmarks use).  They change
+       how the work is cut, not what is computed (p1_pieces: to the sweeps' tolerance, see above). */
+    int32_t segments;               /* > 0: cut the sequence into this many segments of chunks for the
+                                       two-stream pipeline of osdn_fwd / osdn_bwd (1: one stream) */
+    int32_t p1_pieces;              /* > 0: osdn_fwd runs the preconditioner as sweeps over this many
+                                       pieces per chain; -1: never (always the sequential sweep) */
+    int32_t p1_piece_sweeps;        /* > 0: at most this many such sweeps (up to 13) before the sequential
+                                       sweep finishes the chains that have not settled */
 } osdn_params;
 
 /* Bytes of scratch osdn_fwd needs (for_backward == 0) or osdn_fwd followed by osdn_bwd

@@ -4,7 +4,6 @@
 #include "osdn_kernels.h"
 
 #include <cmath>
-#include <cstdlib>
 #include <map>
 #include <mutex>
 #include <vector>
@@ -63,14 +62,17 @@ int check_params(const osdn_params *p, bool need_chunks) {
         if (p->B > 65535 || p->H > 65535) return OSDN_ERR_SHAPE;
     }
     if ((long long)p->B * p->H > 0x7fffffffLL / 64) return OSDN_ERR_SHAPE;
-    // the kernels address the 64 token rows of a chunk with 32-bit byte offsets
-    if ((long long)p->H * (p->K > p->V ? p->K : p->V) * 4 * C >= (1LL << 32)) return OSDN_ERR_SHAPE;
+    // the kernels address the 64 token rows of a chunk with 32-bit byte offsets (V only matters to
+    // the entry points that have a value tensor)
+    const int widest = (need_chunks && p->V > p->K) ? p->V : p->K;
+    if ((long long)p->H * widest * 4 * C >= (1LL << 32)) return OSDN_ERR_SHAPE;
     if (!(p->eta >= 0.f) || !(p->eps > 0.f) || !std::isfinite(p->eta) || !std::isfinite(p->eps) ||
         !std::isfinite(p->scale) || std::isnan(p->d_min) || std::isnan(p->d_max))
         return OSDN_ERR_PARAM;
     if (p->retention_per_channel != 0 && p->retention_per_channel != 1) return OSDN_ERR_PARAM;
     if (p->gate_per_channel != 0 && p->gate_per_channel != 1) return OSDN_ERR_PARAM;
-
+    if (p->segments < 0 || p->p1_pieces < -1 || p->p1_piece_sweeps < 0 || p->p1_piece_sweeps > MAX_PIECE_SWEEPS)
+        return OSDN_ERR_PARAM;
     return OSDN_OK;
 }
 
@@ -215,12 +217,19 @@ struct Pipeline {
     bool ok = false;
 };
 std::mutex g_pipe_mu;
-std::map<int, Pipeline> g_pipes;
+std::map<std::pair<int, hipStream_t>, Pipeline> g_pipes;
 
-Pipeline *pipeline_for_current_device() {
+// The side stream and events that go with one caller stream on the current device (created on
+// first use, kept until the process ends).  One set per caller stream: a call that is being
+// captured into a graph on one stream pulls only its own side stream into the capture, and
+// calls on other streams, from other threads, neither wait for it nor enqueue into it.  Calls
+// that share a caller stream have to be ordered by the caller, as for any work on one stream.
+Pipeline *pipeline_for(hipStream_t caller) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return nullptr;
-    auto it = g_pipes.find(dev);
+    std::lock_guard<std::mutex> lock(g_pipe_mu);
+    const auto key = std::make_pair(dev, caller);
+    auto it = g_pipes.find(key);
     if (it == g_pipes.end()) {
         Pipeline pl;
         bool ok = hipStreamCreateWithFlags(&pl.side, hipStreamNonBlocking) == hipSuccess;
@@ -229,13 +238,13 @@ Pipeline *pipeline_for_current_device() {
         for (int i = 0; ok && i < MAX_SEGMENTS; ++i)
             ok = hipEventCreateWithFlags(&pl.a[i], hipEventDisableTiming) == hipSuccess;
         pl.ok = ok;
-        it = g_pipes.emplace(dev, pl).first;
+        it = g_pipes.emplace(key, pl).first;
     }
     return it->second.ok ? &it->second : nullptr;
 }
 
-// Number of segments for a sequence of N chunks (OSDN_SEGMENTS in the environment overrides
-// it; 1 = no pipelining).  At least two (any sequence of at least two chunks, so that short
+// Number of segments for a sequence of N chunks (params->segments > 0 overrides it; 1 = no
+// pipelining).  At least two (any sequence of at least two chunks, so that short
 // sequences take the same path).  A segment more shortens the stretch of phase 1 that runs with
 // nothing beside it (the first segment of the forward pass, the last of the backward pass) and
 // costs launches, cross-stream waits and partly filled rounds of workgroups.
@@ -252,8 +261,7 @@ Pipeline *pipeline_for_current_device() {
 // segment, so cutting pays only while one sequence makes up most of the axis; otherwise the
 // many independent chains fill the chip by themselves and everything runs in one piece.
 constexpr int NUM_CU = 256;
-int segment_count(int N, int longest, long long chain_wgs, bool backward, long long chains = 0) {
-    static const int forced = [] { const char *e = std::getenv("OSDN_SEGMENTS"); return e ? std::atoi(e) : 0; }();
+int segment_count(int forced, int N, int longest, long long chain_wgs, bool backward, long long chains = 0) {
     if (forced <= 0 && (long long)longest * 4 < (long long)N * 3) return 1;
     int S = forced;
     if (forced <= 0) {
@@ -307,19 +315,19 @@ inline int seg_begin(int N, int S, int s) {
 // workgroup per CU over all chains, at least 8 chunks each); a sweep runs all pieces side by
 // side, each from its current start value, and leaves every piece as a composed map per
 // coordinate; the next sweep walks those maps for its start values; a chain is settled when none
-// of its start values moves any more.  Plain batches only.  OSDN_P1_PIECES in the environment forces a number
-// of pieces per chain (0: never), OSDN_P1_PIECE_SWEEPS the sweep limit.
-inline void pieces_plan(int N, long long chains, bool packed, int &pieces, int &piece_chunks, int &sweeps) {
+// of its start values moves any more.  Plain batches only.  params->p1_pieces forces a number of
+// pieces per chain (-1: never), params->p1_piece_sweeps the sweep limit.
+inline void pieces_plan(const osdn_params *p, int N, long long chains, bool packed, int &pieces, int &piece_chunks,
+                        int &sweeps) {
     pieces = 0; piece_chunks = 0;
     // sweeps needed without retention, measured: 4 at 64 and 128 chunks, then one more per
     // doubling (7 at 1024); the limit leaves two in hand
     sweeps = 7;                                  // (the last one only finds that nothing moved)
     for (int n = 128; n < N && sweeps < MAX_PIECE_SWEEPS; n *= 2) ++sweeps;
     if (packed || chains > MAX_PIECES / 2) return;
-    const char *e = std::getenv("OSDN_P1_PIECES");
-    const int forced = e ? std::atoi(e) : -1;
+    const int forced = p->p1_pieces;              // 0: decide here; -1: never; n > 0: n pieces per chain
     int target, min_chunks;
-    if (forced >= 0) { target = forced; min_chunks = 1; }
+    if (forced != 0) { target = forced > 0 ? forced : 0; min_chunks = 1; }
     else if (chains * 8 <= NUM_CU && N >= 64) { target = (int)(NUM_CU / chains); min_chunks = 8; }
     else return;
     if ((long long)target * chains > MAX_PIECES) target = (int)(MAX_PIECES / chains);
@@ -329,10 +337,7 @@ inline void pieces_plan(int N, long long chains, bool packed, int &pieces, int &
     const int P = (N + len - 1) / len;
     if (P < 2) return;
     pieces = P; piece_chunks = len;
-    if (const char *w = std::getenv("OSDN_P1_PIECE_SWEEPS")) {
-        const int v = std::atoi(w);
-        if (v >= 1 && v <= MAX_PIECE_SWEEPS) sweeps = v;
-    }
+    if (p->p1_piece_sweeps >= 1) sweeps = p->p1_piece_sweeps;
 }
 
 #define OSDN_HIP_OK(x) do { if ((x) != hipSuccess) return OSDN_ERR_LAUNCH; } while (0)
@@ -511,10 +516,9 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     const int N = p->T / C;
     const long long chains = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
     int pieces, piece_chunks, piece_sweeps;
-    pieces_plan(N, chains, pk.n_seqs != 0, pieces, piece_chunks, piece_sweeps);
-    int S = pieces ? 1 : segment_count(N, pk.longest, 0, false);
-    std::lock_guard<std::mutex> lock(g_pipe_mu);
-    Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
+    pieces_plan(p, N, chains, pk.n_seqs != 0, pieces, piece_chunks, piece_sweeps);
+    int S = pieces ? 1 : segment_count(p->segments, N, pk.longest, 0, false);
+    Pipeline *pl = S > 1 ? pipeline_for(st) : nullptr;
     if (!pl) S = 1;
     // chain workgroups of both phases (32 rows of the state per workgroup in state_fwd) against the CUs
     const bool crowded = chains * (p->V / 32) + chains > NUM_CU;
@@ -691,9 +695,8 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
 
     const int N = p->T / C;
     const long long chains = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
-    int S = segment_count(N, pk.longest, chains * (p->V / 32) + chains, true, chains);   // chain kernel: 32 rows of the state per workgroup
-    std::lock_guard<std::mutex> lock(g_pipe_mu);
-    Pipeline *pl = S > 1 ? pipeline_for_current_device() : nullptr;
+    int S = segment_count(p->segments, N, pk.longest, chains * (p->V / 32) + chains, true, chains);   // chain kernel: 32 rows of the state per workgroup
+    Pipeline *pl = S > 1 ? pipeline_for(st) : nullptr;
     if (!pl) S = 1;
     auto seg_range = [&](int sidx, int &n0, int &n1) { n0 = seg_begin(N, S, sidx); n1 = seg_begin(N, S, sidx + 1); };
     auto phase2 = [&](int kid, int sidx) {

@@ -59,21 +59,19 @@ def test_many_chains_few_chunks(T):
 
 @pytest.mark.parametrize("case", ["box_and_retention", "no_projection", "no_retention_bf16", "k128_ragged",
                                   "one_sweep_then_sequential"])
-def test_phase1_as_sweeps_over_pieces(case, monkeypatch):
+def test_phase1_as_sweeps_over_pieces(case):
     """Few long chains: phase 1 of the forward pass runs as sweeps over pieces of the sequence
     (every piece from a guessed start value, a scan over the pieces' composed maps, until no
-    start value moves).  Forced here on small shapes through the environment: 5 pieces per chain
+    start value moves).  Forced here on small shapes through the scheduling fields: 5 pieces per chain
     over 20 (19.6) chunks, eta = 0.5 so that d moves, meets the box and couples the pieces; the
     last case allows a single sweep, after which the sequential kernel has to take over."""
-    monkeypatch.setenv("OSDN_P1_PIECES", "5")
-    if case == "one_sweep_then_sequential":
-        monkeypatch.setenv("OSDN_P1_PIECE_SWEEPS", "1")
+    knobs = dict(p1_pieces=5, p1_piece_sweeps=1 if case == "one_sweep_then_sequential" else 0)
     bf16 = case == "no_retention_bf16"
     K = 128 if case == "k128_ragged" else 64
     T = 64 * 20 - 25 if case == "k128_ragged" else 64 * 20
     x = make_stress_inputs(2, T, 2, K, 64, seed=71, bf16=bf16,
                            retention=0.0 if case == "no_retention_bf16" else 0.97)
-    hp = ob.Hyper(eta=0.2, d_min=1.0, d_max=0.0) if case == "no_projection" else ob.Hyper(eta=0.5)
+    hp = ob.Hyper(eta=0.2, d_min=1.0, d_max=0.0, **knobs) if case == "no_projection" else ob.Hyper(eta=0.5, **knobs)
     compare_forward(x, hp, bf16)
     compare_backward(x, hp, bf16)
 
@@ -146,14 +144,13 @@ def test_precond_checkpoints_and_carry():
             assert (d2 - d_out).abs().max() <= 1e-5
 
 
-def test_resume_split_sequence(monkeypatch):
+def test_resume_split_sequence():
     """One call on T tokens equals two calls on T/2 with (S, d) carried (both vs the oracle, and
     the two GPU results against each other bit for bit at a chunk boundary).  Bit for bit holds
     for the sequential sweep of phase 1, which short sequences always take; the sweeps over
-    pieces agree to their tolerance only, so they are kept out even if the environment asks."""
-    monkeypatch.setenv("OSDN_P1_PIECES", "0")
+    pieces agree to their tolerance only, so they are switched off."""
     x = make_stress_inputs(2, 256, 2, 64, 128, seed=27, retention=0.97)
-    hp = ob.Hyper(eta=0.3)
+    hp = ob.Hyper(eta=0.3, p1_pieces=-1)
     o, S, d, _, t = gpu_forward(x, hp, False)
     h = 128
     cut = lambda a, s: None if a is None else a[:, s].contiguous()
@@ -327,17 +324,15 @@ def test_full_size_config2_with_a_live_preconditioner():
 
 
 @pytest.mark.parametrize("pieces", [False, True])
-def test_hip_graph_capture_and_replay(pieces, monkeypatch):
+def test_hip_graph_capture_and_replay(pieces):
     """Forward + backward captured into a HIP graph on a caller stream (the library's side
     stream joins the capture through its fork / join events; nothing in it allocates or clears
     memory with a memset node) and replayed several times with eager calls and synchronisations
     in between: every replay reproduces the eager results bit for bit.  Also with phase 1 as
     sweeps over pieces of the sequence, whose launches decide on device flags whether to run."""
-    if pieces:
-        monkeypatch.setenv("OSDN_P1_PIECES", "4")
     x = make_stress_inputs(2, 1024, 2, 64, 64, seed=41, bf16=True, retention=0.97)
     t = to_dev(x, True)
-    hp = ob.Hyper(eta=0.3)
+    hp = ob.Hyper(eta=0.3, p1_pieces=4 if pieces else 0)
     B, T, H, K = t["k"].shape
     V = t["v"].shape[-1]
     p = ob.make_params(B, T, H, K, V, True, hp)

@@ -39,13 +39,12 @@ def test_forward_backward(shape, bf16):
     assert traj.max() - traj.min() > 0.5
 
 
-def test_phase1_over_pieces_with_retention_per_coordinate(monkeypatch):
+def test_phase1_over_pieces_with_retention_per_coordinate():
     """The sweeps over pieces of the sequence (forced: 4 pieces per chain over 12 chunks) compose
     the piece maps with one retention per coordinate."""
-    monkeypatch.setenv("OSDN_P1_PIECES", "4")
     B, T, H, K, V = 1, 64 * 12, 2, 128, 64
     x = _inputs(B, T, H, K, V, seed=75, bf16=False)
-    hp = ob.Hyper(eta=0.5)
+    hp = ob.Hyper(eta=0.5, p1_pieces=4)
     compare_forward(x, hp, False)
     compare_backward(x, hp, False)
 

@@ -126,3 +126,45 @@ def test_binding_rejects_cpu_tensors_and_wrong_dtypes():
     k = torch.zeros(1, 64, 1, 64)
     with pytest.raises(TypeError):
         ob.osdn_precond_update(p, k, k[..., 0], None, None, k.clone(), torch.zeros(1, 1, 64))
+
+
+def test_scheduling_fields_and_mask_offset_query():
+    """The scheduling knobs are plain fields of the parameter block (the library reads no
+    environment variables): zeros mean "the library decides", out-of-range values are parameter
+    errors reported before any pointer is used, and they never change the workspace size.  The
+    diagnostic mask query is host-only and points inside the backward part of the workspace."""
+    L = ob.lib()
+    fake = ctypes.c_void_p(0x1000)
+    base = ob.make_params(2, 4096, 2, 128, 128, True)
+    assert (base.segments, base.p1_pieces, base.p1_piece_sweeps) == (0, 0, 0)
+    fwd, bwd = ob.osdn_workspace_bytes(base, False), ob.osdn_workspace_bytes(base, True)
+    tuned = ob.make_params(2, 4096, 2, 128, 128, True, ob.Hyper(segments=3, p1_pieces=4, p1_piece_sweeps=2))
+    assert (tuned.segments, tuned.p1_pieces, tuned.p1_piece_sweeps) == (3, 4, 2)
+    assert ob.osdn_workspace_bytes(tuned, False) == fwd and ob.osdn_workspace_bytes(tuned, True) == bwd
+    never = ob.make_params(2, 4096, 2, 128, 128, True, ob.Hyper(p1_pieces=-1, segments=1))
+    assert ob.osdn_workspace_bytes(never, True) == bwd
+    for bad in (dict(segments=-1), dict(p1_pieces=-2), dict(p1_piece_sweeps=-1), dict(p1_piece_sweeps=14)):
+        q = ob.make_params(2, 4096, 2, 128, 128, True, ob.Hyper(**bad))
+        assert ob.osdn_workspace_bytes(q, False) == 0, bad
+        assert L.osdn_fwd(ctypes.byref(q), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
+                          fake, ctypes.c_size_t(1 << 40), None) == -5, bad
+    off = ob.osdn_debug_mask_offset(base)
+    assert fwd <= off and off % 256 == 0 and off + 2 * 2 * 64 * 128 * 8 <= bwd
+    bad = ob.make_params(2, 4096, 2, 96, 128, True)
+    assert ob.osdn_debug_mask_offset(bad) == 0
+    # the environment is not consulted: a variable the library once read changes nothing
+    os.environ["OSDN_SEGMENTS"] = "-7"
+    try:
+        assert ob.osdn_workspace_bytes(base, True) == bwd
+    finally:
+        del os.environ["OSDN_SEGMENTS"]
+
+
+def test_precond_update_ignores_the_value_width():
+    """osdn_precond_update has no value tensor: V takes no part in its shape checks."""
+    L = ob.lib()
+    fake = ctypes.c_void_p(0x1000)
+    p = ob.make_params(1, 128, 40000, 64, 64, False)        # H * K * 256 < 2^32 ...
+    p.V = 1 << 20                                           # ... whatever V holds
+    p.eta = -1.0                                            # reaches the scalar checks: the shape passed
+    assert L.osdn_precond_update(ctypes.byref(p), fake, fake, None, None, fake, fake, None, None) == -5
