@@ -161,6 +161,28 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
              void *stream);
 
 /*
+ * osdn_fwd for callers that cannot allocate device memory and have no workspace to hand in
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * same computation with the scratch taken from a fixed device array that is part of the
+ * library, OSDN_NOALLOC_MAX_WORKSPACE bytes, which every GPU the library is used on holds from
+ * the moment the library is loaded until the process ends.  The call allocates nothing, creates
+ * no stream or event, and runs entirely on `stream`; all other arguments are those of osdn_fwd.
+ *   - Problems whose osdn_workspace_bytes(p, 0) exceeds OSDN_NOALLOC_MAX_WORKSPACE return
+ *     OSDN_ERR_WORKSPACE and launch nothing; if the array's address cannot be obtained,
+ *     OSDN_ERR_LAUNCH.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in time (different
+ *     streams, different threads) race on it and must be ordered by the caller.  Nothing in it
+ *     has to start at zero (every buffer is written before it is read), so what the previous
+ *     call left behind is harmless.
+ *   - The scratch is not a workspace for osdn_bwd: use osdn_fwd with a caller workspace when a
+ *     backward pass follows.
+ */
+#define OSDN_NOALLOC_MAX_WORKSPACE ((size_t)64 << 20)
+int osdn_fwd_noalloc(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+                     const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+                     void *o, float *S_out, float *d_out, void *stream);
+
+/*
  * Backward of osdn_fwd (Section 4.5: phase 2 yields dL/dk~; dL/dd_t = k_t (.) dL/dk~_t,
  * dL/dk_t += d_t (.) dL/dk~_t; reverse sweep through the projected affine d recurrence,
  * whose projection passes gradient where d_min <= unprojected value <= d_max).

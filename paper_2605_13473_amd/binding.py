@@ -64,6 +64,8 @@ def lib():
         L.osdn_precond_update.argtypes = [pp, vp, fp, fp, fp, vp, fp, fp, vp]
         L.osdn_fwd.restype = ctypes.c_int
         L.osdn_fwd.argtypes = [pp, vp, vp, vp, fp, fp, fp, fp, fp, vp, fp, fp, vp, ctypes.c_size_t, vp]
+        L.osdn_fwd_noalloc.restype = ctypes.c_int
+        L.osdn_fwd_noalloc.argtypes = [pp, vp, vp, vp, fp, fp, fp, fp, fp, vp, fp, fp, vp]
         L.osdn_bwd.restype = ctypes.c_int
         L.osdn_bwd.argtypes = [pp] + [vp] * 19 + [vp, ctypes.c_size_t, vp]
         ip = ctypes.POINTER(ctypes.c_int32)
@@ -178,6 +180,19 @@ def osdn_fwd(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, 
         _ptr(S_in, f32, (p.B, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
         _ptr(S_out, f32, (p.B, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (p.B, p.H, p.K), "d_out"),
         _ptr(workspace, torch.uint8, None, "workspace"), ctypes.c_size_t(workspace.numel()),
+        _stream_ptr(stream)))
+
+
+def osdn_fwd_noalloc(params, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, stream=None):
+    p = params
+    io, f32 = _io_torch_dtype(p), torch.float32
+    bth, bthk, bthv = (p.B, p.T, p.H), (p.B, p.T, p.H, p.K), (p.B, p.T, p.H, p.V)
+    _check(lib().osdn_fwd_noalloc(
+        ctypes.byref(p), _ptr(q, io, bthk, "q"), _ptr(k, io, bthk, "k"), _ptr(v, io, bthv, "v"),
+        _ptr(beta, f32, bth, "beta"), _ptr(log_alpha, f32, _gate_shape(p), "log_alpha"),
+        _ptr(retention, f32, _ret_shape(p), "retention"), _ptr(d_in, f32, (p.B, p.H, p.K), "d_in"),
+        _ptr(S_in, f32, (p.B, p.H, p.V, p.K), "S_in"), _ptr(o, io, bthv, "o"),
+        _ptr(S_out, f32, (p.B, p.H, p.V, p.K), "S_out"), _ptr(d_out, f32, (p.B, p.H, p.K), "d_out"),
         _stream_ptr(stream)))
 
 

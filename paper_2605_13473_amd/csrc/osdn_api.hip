@@ -342,6 +342,30 @@ inline void pieces_plan(const osdn_params *p, int N, long long chains, bool pack
 
 #define OSDN_HIP_OK(x) do { if ((x) != hipSuccess) return OSDN_ERR_LAUNCH; } while (0)
 
+// ---- scratch of osdn_fwd_noalloc: device memory that belongs to the library ---------------
+// A file-scope device array (every GPU the library runs on holds its own copy, at its own
+// address, from the moment the code object is loaded until the process ends).  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the address kernels can use is looked
+// up once per device, with that device current, and only that pointer is ever passed on.
+constexpr size_t STATIC_SCRATCH_BYTES = OSDN_NOALLOC_MAX_WORKSPACE;
+static __device__ __align__(256) unsigned char g_static_scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of the current device's copy of the array (null on failure).
+void *static_scratch_for_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
 // Once the side stream has been forked off, every way out of the call joins it back into the
 // caller's stream: also an error return must not leave work behind that the caller's stream does
 // not wait for (or, under stream capture, a branch that never rejoins).
@@ -756,6 +780,23 @@ int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, 
              void *stream) {
     return fwd_impl(p, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, nullptr, 0, workspace,
                     workspace_bytes, stream);
+}
+
+int osdn_fwd_noalloc(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
+                     const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
+                     void *o, float *S_out, float *d_out, void *stream) {
+    int rc = check_params(p, true);
+    if (rc != OSDN_OK) return rc;
+    // everything on the caller's stream: no side stream or event is ever created from here
+    osdn_params one = *p;
+    one.segments = 1;
+    Packing pk;
+    plain_packing(&one, pk);
+    if (make_layout(&one, pk).total_fwd > STATIC_SCRATCH_BYTES) return OSDN_ERR_WORKSPACE;
+    void *scratch = static_scratch_for_current_device();
+    if (!scratch) return OSDN_ERR_LAUNCH;
+    return fwd_impl(&one, q, k, v, beta, log_alpha, retention, d_in, S_in, o, S_out, d_out, nullptr, 0, scratch,
+                    STATIC_SCRATCH_BYTES, stream);
 }
 
 int osdn_fwd_packed(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
