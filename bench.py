@@ -186,6 +186,9 @@ def main():
     ap.add_argument("--channel-gate", action="store_true",
                     help="side workload, not the headline: the configuration's shape with one state gate per key "
                          "channel (online-scaled KDA), log alpha = -softplus(N(-1,1)) per channel")
+    ap.add_argument("--segments", type=int, default=0,
+                    help="experiments: force the number of segments of the two-stream pipeline (osdn_params.segments; "
+                         "0 = the library decides, 1 = every kernel alone on one stream)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain device copy of 1 GiB before the steps (the reference that scales "
                          "the rocprofv3 HBM byte counters; its rate is printed with every result anyway)")
@@ -226,7 +229,7 @@ def main():
         gen = torch.Generator(device=dev).manual_seed(2)
         tg = -torch.nn.functional.softplus(torch.randn(cfg.B, cfg.T, cfg.H, cfg.K, device=dev, generator=gen) - 1.0)
     tr = None if x["retention"] is None else torch.from_numpy(x["retention"]).to(dev)
-    hp = ob.Hyper()
+    hp = ob.Hyper(segments=args.segments)
     p = ob.make_params(cfg.B, cfg.T, cfg.H, cfg.K, cfg.V, cfg.bf16, hp, gate_per_channel=args.channel_gate)
     if cu is None:
         ws = ob.alloc_workspace(p, cfg.backward, dev)

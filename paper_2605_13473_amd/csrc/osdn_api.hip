@@ -15,10 +15,11 @@ using namespace osdn;
 // Optional per-kernel timing with HIP events on the caller's stream (off by default; the
 // only process-wide state the library has).  Not thread-safe; meant for benchmarks.
 enum { KID_PRECOND_FWD, KID_CHUNK_PREP, KID_STATE_FWD, KID_OUTPUT_FWD, KID_BWD_LOCAL, KID_BWD_CHAIN,
-       KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_STEP, KID_PAD, KID_UNFOLD, KID_COUNT };
+       KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_STEP, KID_PAD, KID_UNFOLD, KID_PRECOND_LIN,
+       KID_COUNT };
 const char *const kKernelNames[KID_COUNT] = {"precond_fwd", "chunk_prep", "state_fwd", "output_fwd",
                                              "bwd_local", "bwd_chain", "bwd_post", "precond_mask",
-                                             "precond_chain", "precond_post", "step", "pad", "unfold"};
+                                             "precond_chain", "precond_post", "step", "pad", "unfold", "precond_lin"};
 struct Timed { int id; hipEvent_t e0, e1; };
 bool g_prof_on = false;
 std::vector<Timed> g_prof;
@@ -40,6 +41,7 @@ struct Layout {
     size_t kt, d_ckpt, tok_scalars, Tm, Wt, Ktr, Ut, Et, S_ckpt;   // forward
     size_t piece_start, piece_map, piece_flags;                          // phase 1 as sweeps over the whole sequence
     size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;   // backward only
+    size_t lin_clean, lin_M, lin_r0, lin_t0;                             // backward: chunks of phase 1 in solved form
     // padded copies of the caller's tensors, only when T is not a multiple of the chunk length
     size_t p_q, p_k, p_v, p_beta, p_g, p_r, p_o;                        // forward
     size_t p_dO, p_dq, p_dk, p_dv, p_dbeta, p_dg, p_dr;                 // backward
@@ -163,6 +165,10 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     L.dkt = take(B * T * H * K * es);
     L.masks = take(B * H * N * K * 8);
     L.a_ckpt = take(B * H * N * K * 4);
+    L.lin_clean = take(B * H * N * 4);
+    L.lin_M = take(B * H * N * C * C * 4);
+    L.lin_r0 = take(B * H * N * C * 4);
+    L.lin_t0 = take(B * H * N * K * 4);
     if (p->gate_per_channel) L.dgamC = take(B * H * N * K * 4);
     if (ragged) {
         L.p_dO = take(B * T * H * V * es); L.p_dv = take(B * T * H * V * es);
@@ -716,6 +722,12 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     pb.dkt = c.dkt; pb.dk_read = c.dk_read;
     pb.n_seqs = pk.n_seqs; pb.seq_chunks = seq_chunks; pb.dd_last = dd_out;
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
+    if (!retention) {                   // chunks that never met the box take the solved form
+        pb.lin_clean = reinterpret_cast<int *>(ws + L.lin_clean);
+        pb.lin_M = reinterpret_cast<float *>(ws + L.lin_M);
+        pb.lin_r0 = reinterpret_cast<float *>(ws + L.lin_r0);
+        pb.lin_t0 = reinterpret_cast<float *>(ws + L.lin_t0);
+    }
 
     const int N = p->T / C;
     const long long chains = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
@@ -743,6 +755,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     auto phase1 = [&](int sidx, hipStream_t s1) {
         seg_range(sidx, pb.n0, pb.n1);
         pb.dd_out = sidx == S - 1 ? dd_out : dd_in;  // the adjoint of d is carried in dd_in
+        if (pb.lin_clean && timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, s1); }) != 0) return -1;
         if (timed(KID_PRECOND_CHAIN, s1, [&] { return launch_precond_chain(pb, bf, s1); }) != 0) return -1;
         return timed(KID_PRECOND_POST, s1, [&] { return launch_precond_post(pb, bf, s1); });
     };

@@ -65,6 +65,12 @@ struct PrecondBwdArgs {
     float *dbeta;             // [B,T,H] in/out
     float *dretention;        // [B,T,H] ([B,T,H,K] with ret_vec) or null
     float *dd_in;             // [B,H,K]
+    // chunks in solved form (no retention; null: never): per chunk, whether it qualifies (no
+    // coordinate met the box), the inverse (I + U)^-1, rho0 and the chunk's sum of lambda
+    int *lin_clean;           // [B,H,T/64]
+    float *lin_M;             // [B,H,T/64,64,64]
+    float *lin_r0;            // [B,H,T/64,64]
+    float *lin_t0;            // [B,H,T/64,K]
 };
 
 // The recurrent step (decode): state in registers, 1..64 tokens per launch.
@@ -135,6 +141,7 @@ int launch_upload_ints(const int *host, size_t count, int *dst, hipStream_t st);
 int launch_move_chunk_rows(const void *src, void *dst, const int *chunk_row, const int *chunk_len, int n_chunks,
                            size_t row_bytes, bool to_padded, uint32_t fill, hipStream_t st);
 int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
+int launch_precond_lin_bwd(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_post(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_chunk_prep(const ChunkArgs &a, bool bf16_io, hipStream_t st);

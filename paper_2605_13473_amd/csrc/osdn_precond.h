@@ -98,6 +98,40 @@ __device__ __forceinline__ float lane_fold8_all(const float (&v)[8], int lane) {
     y += __shfl_xor(y, 32, 64);
     return y;
 }
+// ---- a chunk of the recurrence in solved form ---------------------------------------------
+// Where a chunk of 64 tokens has no retention and no coordinate meets the box, both sweeps are
+// linear in the K-vector they carry (d forward, its adjoint backward) and couple the tokens only
+// through 64 scalars (the inner products <d_t, s_t>, resp. sigma_t = <s_t, abar_t>), which solve a
+// unit triangular 64 x 64 system built from the Gram matrix of the squared keys.  That system is
+// inverted for all chunks side by side; what stays sequential per chunk is
+//     x = S v + r0 ;  y = M x ;  w = w(y) ;  v' = v + t0 +- S^T w
+// (S = the 64 x K tile of squared keys, v the carried vector): two matrix-vector products with
+// S and one with the 64 x 64 inverse M.  Thread layouts of a 512-thread workgroup:
+//   rows   : thread (i = tid / 8, part = tid % 8) owns coordinates [part * EPT, (part + 1) * EPT) of token i
+//            (resp. columns [8 part, 8 part + 8) of row i of M); sums over the 8 lanes of a token
+//   columns: thread (c = tid / NG, tg = tid % NG) owns tokens u * NG + tg of coordinate c; sums over NG lanes
+template <int K> struct Lin {
+    static constexpr int EPT = K / 8;
+    static constexpr int NG = P1T / K;
+    static constexpr int LD = K + (K == 128 ? 8 : 4);     // row stride of the s tile: column reads of a half-wave hit 32 banks
+    static constexpr int VSTR = EPT + 4;                  // a thread's slice of a K-vector: slices start 16 bytes off a bank period
+    static constexpr int XSTR = 12;                       // ... of a 64-vector (8 entries per slice)
+    static __device__ __forceinline__ int vidx(int c) { return (c / EPT) * VSTR + c % EPT; }
+    static __device__ __forceinline__ int xidx(int i) { return (i >> 3) * XSTR + (i & 7); }
+};
+// sum over the 8 (4) adjacent lanes of an aligned group, returned to all of them
+__device__ __forceinline__ float sum_lanes8(float x) {
+    x += dpp_f32<0xB1>(x);
+    x += dpp_f32<0x4E>(x);
+    x += lane_xor4(x);
+    return x;
+}
+__device__ __forceinline__ float sum_lanes4(float x) {
+    x += dpp_f32<0xB1>(x);
+    x += dpp_f32<0x4E>(x);
+    return x;
+}
+
 __device__ __forceinline__ float lane_bcast(float x, int src_lane) {     // src_lane uniform
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), src_lane));
 }

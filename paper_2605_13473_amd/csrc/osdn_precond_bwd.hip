@@ -15,6 +15,17 @@
 //                  coordinate: replays d, re-runs the adjoint recurrence of its chunk from the
 //                  stored boundary value, sigmas and masks, and writes dk, dbeta, dretention
 // The retention gate is absent, one value per (token, head), or one per coordinate (RET).
+//
+// Without retention, on a chunk in which no coordinate met the box (every mask bit set), the
+// recurrence is linear with constant coefficients:  abar_i = g + sum_{j>i} (lambda_j - ca_j
+// sigma_j s_j)  (g = the adjoint at the chunk's right end, lambda_j = k_j (.) dL/dk~_j), hence
+//     (I + U) sigma = S g + rho0,   U_ij = <s_i, s_j> ca_j (j > i),   rho0_i = <s_i, sum_{j>i} lambda_j>,
+//     a_left = g + sum_j lambda_j - S^T (ca (.) sigma).
+//   precond_lin    one workgroup per (chain, chunk), all chunks in parallel, before the chain:
+//                  decides whether the chunk qualifies and, if so, leaves (I + U)^-1 (Gram matrix
+//                  and blocked inverse on the fp32 MFMA), rho0 and sum_j lambda_j;
+// on such a chunk precond_chain only has the three matrix-vector products left (osdn_precond.h,
+// "a chunk of the recurrence in solved form"); on any other chunk it runs its sweeps.
 #include "osdn_precond.h"
 
 namespace osdn {
@@ -60,6 +71,129 @@ __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
     a.masks[(bh * N + n) * K + tid] = make_uint2(mlo, mhi);
 }
 
+// ----------------------------------------------------------------- precond_lin ----
+template <typename T, int K>
+__global__ __launch_bounds__(P1T) void precond_lin_bwd_kernel(PrecondBwdArgs a) {
+    typedef Lin<K> LN;
+    constexpr int EPT = LN::EPT, VN = 16 / sizeof(T), NVK = EPT / VN;
+    constexpr int LDT = K + 4;                   // s and lambda tiles: MFMA fragment reads (row = lane % 16, k = lane / 16) spread over the banks
+    constexpr int LDF = C + 1;
+    constexpr int NGK = P1T / K, TS = C / NGK;   // column layout: thread (c = tid % K, tg = tid / K) owns TS consecutive tokens
+    constexpr int INV_F = 2 * C * LDF + 3 * 16 * 17;
+    constexpr int POOL = C * LDT > INV_F ? C * LDT : INV_F;
+    __shared__ __attribute__((aligned(16))) float Ss[C * LDT];      // s = k^2
+    __shared__ __attribute__((aligned(16))) float pool[POOL];       // lambda -> its exclusive suffix sums; then A | (I + A)^-1 | block products
+    __shared__ float tot[NGK * K];
+    __shared__ float cas[C];
+    float *Lam = pool, *Af = pool, *Ti = pool + C * LDF, *Xs = pool + 2 * C * LDF;
+
+    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int N = a.T / C;
+    const size_t bhn = ((size_t)b * a.H + h) * N + n;
+    const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+    // ---- does the chunk qualify?  (no coordinate met the box at any of its tokens) ----
+    bool ok = true;
+    if (a.d_min <= a.d_max && tid < K) {
+        const uint2 m = a.masks[bhn * K + tid];
+        ok = (m.x & m.y) == 0xffffffffu;
+    }
+    const int clean = __syncthreads_and(ok ? 1 : 0);
+    if (tid == 0) a.lin_clean[bhn] = clean;
+    if (!clean) return;
+
+    const int i = tid >> 3, part = tid & 7;
+    const uint32_t kstride = (uint32_t)a.H * K;
+    {
+        const uint32_t off = ((uint32_t)i * kstride + (uint32_t)(part * EPT)) * (uint32_t)sizeof(T);
+        const T *kp = static_cast<const T *>(a.k) + tokc * K, *gp = static_cast<const T *>(a.dkt) + tokc * K;
+#pragma unroll
+        for (int m = 0; m < NVK; ++m) {
+            const u32x4 kv = at_byte(reinterpret_cast<const u32x4 *>(kp), off + 16 * m);
+            const u32x4 gv = at_byte(reinterpret_cast<const u32x4 *>(gp), off + 16 * m);
+#pragma unroll
+            for (int e4 = 0; e4 < VN; e4 += 4) {
+                float sq[4], lm[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float kf = vec_get<T>(kv, e4 + e);
+                    sq[e] = kf * kf;
+                    lm[e] = kf * vec_get<T>(gv, e4 + e);
+                }
+                store_vec(Ss + i * LDT + part * EPT + m * VN + e4, sq);
+                store_vec(Lam + i * LDT + part * EPT + m * VN + e4, lm);
+            }
+        }
+    }
+    if (tid < C) {
+        const size_t th = tokc + (size_t)tid * a.H;
+        const float nn = fmaxf(a.tok_scalars[th * 4 + 2], a.eps);
+        const float bp = a.beta_aware ? a.beta[th] : 1.f;
+        cas[tid] = a.eta * bp / nn * bp;
+    }
+    __syncthreads();
+    // ---- exclusive suffix sums of lambda down every column, in place ----
+    {
+        const int c = tid % K, tg = tid / K;
+        float acc = 0.f;
+#pragma unroll
+        for (int u = TS - 1; u >= 0; --u) {
+            float &cell = Lam[(tg * TS + u) * LDT + c];
+            const float t = cell;
+            cell = acc;
+            acc += t;
+        }
+        tot[tg * K + c] = acc;
+        __syncthreads();
+        float offs = 0.f;
+#pragma unroll
+        for (int g2 = NGK - 1; g2 > 0; --g2)
+            if (g2 > tg) offs += tot[g2 * K + c];
+        if (tg == 0) a.lin_t0[bhn * K + c] = acc + offs;        // sum of lambda over the chunk
+        if (tg < NGK - 1) {
+#pragma unroll
+            for (int u = 0; u < TS; ++u) Lam[(tg * TS + u) * LDT + c] += offs;
+        }
+    }
+    __syncthreads();
+    // ---- rho0_i = <s_i, sum_{j > i} lambda_j> ----
+    {
+        float r = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) r = __builtin_fmaf(Ss[i * LDT + part * EPT + e], Lam[i * LDT + part * EPT + e], r);
+        r = sum_lanes8(r);
+        if (part == 0) a.lin_r0[bhn * C + i] = r;
+    }
+    __syncthreads();                                             // the lambda tile is dead: its space takes A
+    // ---- A = tril(ca_i <s_i, s_j>, -1): the transpose of U; (I + A)^-1 = ((I + U)^-1)^T ----
+    for (int idx = wave; idx < 10; idx += P1W) {
+        const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
+        const int jb = idx - (ib * (ib + 1)) / 2;
+        const f32x4 acc = mma_tile0<float, true, true>(Ss + ib * 16 * LDT, LDT, Ss + jb * 16 * LDT, LDT, K, lane);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int ii = ib * 16 + acc_row(lane, r), jj = jb * 16 + acc_col(lane);
+            Af[ii * LDF + jj] = (jj < ii) ? cas[ii] * acc[r] : 0.f;
+        }
+    }
+    __syncthreads();
+    ut_inverse64<LDF>(Af, Ti, Xs, wave, lane);
+    // ---- (I + U)^-1, row i: entries j >= i are column i of the lower inverse ----
+    {
+        float *mg = a.lin_M + bhn * C * C + i * C + part * 8;
+#pragma unroll
+        for (int e4 = 0; e4 < 8; e4 += 4) {
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = part * 8 + e4 + e;
+                o[e] = j >= i ? Ti[j * LDF + i] : 0.f;
+            }
+            store_vec(mg + e4, o);
+        }
+    }
+}
+
 // --------------------------------------------------------------- precond_chain ----
 // The adjoint recurrence is linear in a (the masks are data of the forward pass), so a chunk
 // is cut into NSEG = 512 / K runs of TS tokens and every thread owns one coordinate of one
@@ -82,9 +216,18 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
     __shared__ __attribute__((aligned(16))) float casig[C];
     __shared__ float part[P1W * 64];
     __shared__ int done;
+    // chunks in solved form (see the top of this file)
+    typedef Lin<K> LN;
+    constexpr int EPT = LN::EPT, VN = 16 / sizeof(T), NVK = EPT / VN, NG = LN::NG;
+    __shared__ __attribute__((aligned(16))) float Sl[C * LN::LD];       // s = k^2 of the chunk
+    __shared__ __attribute__((aligned(16))) float gp[8 * LN::VSTR];     // copy of ga, sliced per thread of the row layout
+    __shared__ __attribute__((aligned(16))) float xs[8 * LN::XSTR];     // S g + rho0
+    __shared__ float ws[C];                                             // ca (.) sigma
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c = tid % K, sg = tid / K;          // coordinate and run of this thread
+    const int li = tid >> 3, lpart = tid & 7;     // row layout of the solved form: token, slice
+    const int lc = tid / NG, ltg = tid % NG;      // column layout: coordinate, token group
     const int b = blockIdx.x / a.H, h = blockIdx.x % a.H;     // b: batch entry, or packed sequence
     const size_t bh = (size_t)b * a.H + h;                    // the chain: indexes dd_out / dd_in
     int bt = b;                                               // batch entry of the token tensors
@@ -99,7 +242,11 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
     const int N = a.T / C;
     const uint32_t kstride = (uint32_t)a.H * K;   // elements between consecutive tokens
 
-    if (tid < K) ga[tid] = a.dd_out ? a.dd_out[bh * K + tid] : 0.f;
+    if (tid < K) {
+        const float g0 = a.dd_out ? a.dd_out[bh * K + tid] : 0.f;
+        ga[tid] = g0;
+        gp[LN::vidx(tid)] = g0;
+    }
 
     T kreg[TS], greg[TS];
     float rreg[RET_VEC ? TS : 1];               // per-coordinate retention of the next chunk
@@ -123,11 +270,129 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         }                                                                                        \
         if (project) mreg = a.masks[(bth * N + (n_)) * K + c];                                   \
     }
-    OSDN_P1_BLOAD(a.n1 - 1)
+    // Registers of a chunk in solved form: the thread's slice of its key row and of its row of
+    // the inverse, the token's scalars (slice 0 only), the coordinate's sum of lambda (group 0 only).
+    struct LinRegs {
+        u32x4 kq[NVK];
+        f32x4 mq[2];
+        float rho, nraw, beta, t0;
+    };
+#define OSDN_P1_LLOAD(n_, R)                                                                     \
+    {                                                                                            \
+        __builtin_amdgcn_sched_barrier(0);     /* the sets are requested in program order */     \
+        const size_t tokc_ = ((size_t)bt * a.T + (size_t)(n_) * C) * a.H + h;                    \
+        const size_t bhn_ = bth * N + (n_);                                                      \
+        const uint32_t off_ = ((uint32_t)li * kstride + (uint32_t)(lpart * EPT)) * (uint32_t)sizeof(T); \
+        const u32x4 *kp_ = reinterpret_cast<const u32x4 *>(static_cast<const T *>(a.k) + tokc_ * K); \
+        _Pragma("unroll") for (int m_ = 0; m_ < NVK; ++m_) R.kq[m_] = at_byte(kp_, off_ + 16 * m_); \
+        const f32x4 *mp_ = reinterpret_cast<const f32x4 *>(a.lin_M + bhn_ * C * C + li * C + lpart * 8); \
+        R.mq[0] = mp_[0]; R.mq[1] = mp_[1];                                                      \
+        const size_t th = tokc_ + (size_t)li * a.H;      /* (every lane of a token loads its scalars) */ \
+        R.nraw = a.tok_scalars[th * 4 + 2];                                                      \
+        R.beta = a.beta[th];                                                                     \
+        R.rho = a.lin_r0[bhn_ * C + li];                                                         \
+        R.t0 = a.lin_t0[bhn_ * K + lc];                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                       \
+    }
+    // One chunk in solved form from the registers R; when they have been read, they are
+    // refilled with the chunk three further on (past the end of the run: a harmless reload of its
+    // last chunk).  No load or store of the step sits under a branch, and lanes that hold the
+    // same value all store it: the loads of the other two register sets then stay in flight
+    // across the step (behind a branch the compiler can no longer count what is outstanding and
+    // waits for everything).
+#define OSDN_P1_LSTEP(n_, R, m_lo)                                                               \
+    {                                                                                            \
+        const size_t tokc_s = ((size_t)bt * a.T + (size_t)(n_) * C) * a.H + h;                   \
+        a.a_ckpt[(bth * N + (n_)) * K + c] = ga[c];                                              \
+        /* x = S g + rho0, and the s tile into LDS for the product with S^T */                   \
+        float y = 0.f;                                                                           \
+        _Pragma("unroll") for (int m_ = 0; m_ < NVK; ++m_)                                       \
+            _Pragma("unroll") for (int e4 = 0; e4 < VN; e4 += 4) {                               \
+                const f32x4 gv = *reinterpret_cast<const f32x4 *>(gp + lpart * LN::VSTR + m_ * VN + e4); \
+                float sq[4];                                                                     \
+                _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                  \
+                    const float kf = vec_get<T>(R.kq[m_], e4 + e);                               \
+                    sq[e] = kf * kf;                                                             \
+                    y = __builtin_fmaf(sq[e], gv[e], y);                                         \
+                }                                                                                \
+                store_vec(Sl + li * LN::LD + lpart * EPT + m_ * VN + e4, sq);                    \
+            }                                                                                    \
+        y = sum_lanes8(y);                                                                       \
+        const float nn_ = fmaxf(R.nraw, a.eps);                                                  \
+        const float bp_ = a.beta_aware ? R.beta : 1.f;                                           \
+        const float ca_i = a.eta * bp_ / nn_ * bp_;                                              \
+        xs[LN::xidx(li)] = y + R.rho;                                                            \
+        __syncthreads();                                                                         \
+        /* sigma = (I + U)^-1 x */                                                               \
+        float sgm = 0.f;                                                                         \
+        _Pragma("unroll") for (int h4 = 0; h4 < 2; ++h4) {                                       \
+            const f32x4 xv = *reinterpret_cast<const f32x4 *>(xs + lpart * LN::XSTR + 4 * h4);   \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) sgm = __builtin_fmaf(R.mq[h4][e], xv[e], sgm); \
+        }                                                                                        \
+        sgm = sum_lanes8(sgm);                                                                   \
+        ws[li] = ca_i * sgm;                                                                     \
+        a.tok_scalars[(tokc_s + (size_t)li * a.H) * 4 + 3] = sgm;                                \
+        const float pre_ = ga[lc] + R.t0;       /* (no loaded value is kept past the refill) */  \
+        OSDN_P1_LLOAD(max((n_) - 3, (m_lo)), R)                                                  \
+        __syncthreads();                                                                         \
+        /* a_left = g + sum lambda - S^T (ca (.) sigma) */                                       \
+        float acc_ = 0.f;                                                                        \
+        _Pragma("unroll") for (int u = 0; u < C / NG; ++u)                                       \
+            acc_ = __builtin_fmaf(Sl[(u * NG + ltg) * LN::LD + lc], ws[u * NG + ltg], acc_);     \
+        acc_ = NG == 4 ? sum_lanes4(acc_) : sum_lanes8(acc_);                                    \
+        const float gn = pre_ - acc_;                                                            \
+        ga[lc] = gn;                                                                             \
+        gp[LN::vidx(lc)] = gn;                                                                   \
+        __syncthreads();                                                                         \
+    }
+    // Which chunks take the solved form: the flags precond_lin left, as bits in LDS (bit n - n0;
+    // chunks past the table's reach sweep).  Without retention only the solved form prefetches
+    // (three chunks deep, inside a run of such chunks); a chunk that has to sweep fetches its
+    // operands when it starts: keeping both sets of registers alive across the loop would spill.
+    constexpr bool LINK = !HAS_RET;
+    constexpr int FLAG_WORDS = 512;
+    __shared__ uint32_t flagw[LINK ? FLAG_WORDS : 1];
+    const bool lin = LINK && a.lin_clean != nullptr;
+    if (lin) {
+        for (int base = 0; base < a.n1 - a.n0 && base < FLAG_WORDS * 32; base += P1T) {
+            const int nn = a.n0 + base + tid;
+            const int f = nn < a.n1 ? a.lin_clean[bth * N + nn] : 0;
+            const unsigned long long bits = __ballot(f != 0);
+            if (lane == 0) {
+                flagw[(base >> 5) + 2 * wave] = (uint32_t)bits;
+                flagw[(base >> 5) + 2 * wave + 1] = (uint32_t)(bits >> 32);
+            }
+        }
+    }
+    if (!LINK) OSDN_P1_BLOAD(a.n1 - 1)
+    __syncthreads();
+    auto solved = [&](int nn) -> bool {            // uniform
+        const int r = nn - a.n0;
+        return lin && r < FLAG_WORDS * 32 && ((flagw[LINK ? r >> 5 : 0] >> (r & 31)) & 1u) != 0;
+    };
 
     for (int n = a.n1 - 1; n >= a.n0; --n) {
         const size_t tokc = ((size_t)bt * a.T + (size_t)n * C) * a.H + h;
+        if (LINK && solved(n)) {
+            // the run [m, n] of chunks in solved form, three chunks in flight
+            int m = n;
+            while (m > a.n0 && solved(m - 1)) --m;
+            LinRegs r0, r1, r2;
+            OSDN_P1_LLOAD(n, r0)
+            OSDN_P1_LLOAD(max(n - 1, m), r1)
+            OSDN_P1_LLOAD(max(n - 2, m), r2)
+            for (int j = n; j >= m; j -= 3) {
+                OSDN_P1_LSTEP(j, r0, m)
+                if (j - 1 < m) break;
+                OSDN_P1_LSTEP(j - 1, r1, m)
+                if (j - 2 < m) break;
+                OSDN_P1_LSTEP(j - 2, r2, m)
+            }
+            n = m;                                  // (the loop's own decrement moves past the run)
+            continue;
+        }
         // ---- this thread's (s, lambda) = (k^2, k . dL/dk~) and mask bits ----
+        if (LINK) OSDN_P1_BLOAD(n)
         float sv[TS], lam[TS];
 #pragma unroll
         for (int u = 0; u < TS; ++u) {
@@ -149,7 +414,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
 #pragma unroll
             for (int u = 0; u < TS; ++u) rv[u] = RET_VEC ? rreg[RET_VEC ? u : 0] : rs[sg * TS + u];
         }
-        if (n > a.n0) OSDN_P1_BLOAD(n - 1)      // next chunk: in flight during the sweeps
+        if (!LINK && n > a.n0) OSDN_P1_BLOAD(n - 1)      // next chunk: in flight during the sweeps
         // a wavefront whose coordinates never touched the box in this run, without retention:
         // P stays 1 and L is a plain running sum
         const bool plain = !HAS_RET && __all(mbits == ((1u << TS) - 1u));
@@ -216,7 +481,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         }
         // ---- accepted: sig generated a_left ----
         if (tid < C) a.tok_scalars[(tokc + (size_t)tid * a.H) * 4 + 3] = sig[tid];
-        if (sg == 0) ga[c] = a_left;
+        if (sg == 0) { ga[c] = a_left; gp[LN::vidx(c)] = a_left; }
         __syncthreads();
     }
     if (tid < K) a.dd_in[bh * K + tid] = ga[tid];
@@ -360,6 +625,19 @@ static int launch_precond_bwd_any(const PrecondBwdArgs &a, bool bf16_io, int whi
     if (ret == 1)
         return bf16_io ? launch_precond_bwd_t<bf16, 1>(a, which, st) : launch_precond_bwd_t<float, 1>(a, which, st);
     return bf16_io ? launch_precond_bwd_t<bf16, 0>(a, which, st) : launch_precond_bwd_t<float, 0>(a, which, st);
+}
+template <typename T>
+static int launch_precond_lin_t(const PrecondBwdArgs &a, hipStream_t st) {
+    const dim3 per_chunk(a.n1 - a.n0, a.H, a.B);
+    if (a.K == 64) hipLaunchKernelGGL((precond_lin_bwd_kernel<T, 64>), per_chunk, dim3(P1T), 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((precond_lin_bwd_kernel<T, 128>), per_chunk, dim3(P1T), 0, st, a);
+    else return -1;
+    return 0;
+}
+// only without retention; needs the masks (when there is a box) and dL/dk~ of the chunks [n0, n1)
+int launch_precond_lin_bwd(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) {
+    if (a.retention || !a.lin_clean || !a.lin_M || !a.lin_r0 || !a.lin_t0) return -1;
+    return bf16_io ? launch_precond_lin_t<bf16>(a, st) : launch_precond_lin_t<float>(a, st);
 }
 int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) { return launch_precond_bwd_any(a, bf16_io, 0, st); }
 int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) { return launch_precond_bwd_any(a, bf16_io, 1, st); }

@@ -37,6 +37,21 @@ def test_strong_decay(bf16):
     compare_forward(x, ob.Hyper(eta=0.3), bf16)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_decay_near_the_documented_limit(bf16):
+    """The chunk path folds e^{+|G|} into the write keys, so the documented limit on a channel's
+    cumulative log-decay inside a chunk is about -80 (the exponent range of fp32 and bf16).
+    Gates scaled so that the strongest channel reaches -70 to -75: forward and backward still
+    agree with the oracle, and nothing overflows."""
+    x = _inputs(1, 192, 2, 64, 64, seed=83, bf16=bf16, g_mean=0.0)
+    worst = np.cumsum(x["log_alpha"].reshape(1, 3, 64, 2, 64), axis=2).min()
+    x["log_alpha"] = (x["log_alpha"] * np.float32(-72.5 / worst)).astype(np.float32)
+    worst = np.cumsum(x["log_alpha"].reshape(1, 3, 64, 2, 64), axis=2).min()
+    assert -75.0 < worst < -70.0
+    compare_forward(x, ob.Hyper(eta=0.3), bf16)
+    compare_backward(x, ob.Hyper(eta=0.3), bf16)
+
+
 def test_equal_entries_reproduce_the_scalar_gate():
     B, T, H, K, V = 2, 192, 2, 128, 128
     x = make_stress_inputs(B, T, H, K, V, seed=83, retention=0.95)
