@@ -189,6 +189,12 @@ def main():
     ap.add_argument("--segments", type=int, default=0,
                     help="experiments: force the number of segments of the two-stream pipeline (osdn_params.segments; "
                          "0 = the library decides, 1 = every kernel alone on one stream)")
+    ap.add_argument("--p1-solved", type=int, default=0,
+                    help="experiments: osdn_params.p1_solved (1: reverse sweep in solved form where it applies, "
+                         "-1: never, 0: the library decides)")
+    ap.add_argument("--no-retention", action="store_true", help="experiments: drop the configuration's retention")
+    ap.add_argument("--backward", action="store_true",
+                    help="experiments: also run the backward pass of a configuration that is forward-only in the list")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain device copy of 1 GiB before the steps (the reference that scales "
                          "the rocprofv3 HBM byte counters; its rate is printed with every result anyway)")
@@ -203,6 +209,9 @@ def main():
     from paper_2605_13473_amd.inputs import CONFIGS, make_inputs
 
     cfg = CONFIGS[args.config]
+    if args.backward and not cfg.backward:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, backward=True, name=cfg.name + "_with_backward")
     if args.decode_batch > 0:
         return decode_bench(args, cfg)
     cu = None
@@ -228,8 +237,8 @@ def main():
     if args.channel_gate:
         gen = torch.Generator(device=dev).manual_seed(2)
         tg = -torch.nn.functional.softplus(torch.randn(cfg.B, cfg.T, cfg.H, cfg.K, device=dev, generator=gen) - 1.0)
-    tr = None if x["retention"] is None else torch.from_numpy(x["retention"]).to(dev)
-    hp = ob.Hyper(segments=args.segments)
+    tr = None if x["retention"] is None or args.no_retention else torch.from_numpy(x["retention"]).to(dev)
+    hp = ob.Hyper(segments=args.segments, p1_solved=args.p1_solved)
     p = ob.make_params(cfg.B, cfg.T, cfg.H, cfg.K, cfg.V, cfg.bf16, hp, gate_per_channel=args.channel_gate)
     if cu is None:
         ws = ob.alloc_workspace(p, cfg.backward, dev)

@@ -34,6 +34,7 @@ class OsdnParams(ctypes.Structure):
         ("beta_aware", ctypes.c_int32), ("retention_per_channel", ctypes.c_int32),
         ("gate_per_channel", ctypes.c_int32),
         ("segments", ctypes.c_int32), ("p1_pieces", ctypes.c_int32), ("p1_piece_sweeps", ctypes.c_int32),
+        ("p1_solved", ctypes.c_int32),
     ]
 
 
@@ -275,6 +276,7 @@ class Hyper:
     segments: int = 0
     p1_pieces: int = 0
     p1_piece_sweeps: int = 0
+    p1_solved: int = 0
 
 
 def make_params(B, T, H, K, V, bf16: bool, hp: Hyper = Hyper(), retention_per_channel: bool = False,
@@ -282,7 +284,8 @@ def make_params(B, T, H, K, V, bf16: bool, hp: Hyper = Hyper(), retention_per_ch
     scale = float(K) ** -0.5 if hp.scale is None else float(hp.scale)
     return OsdnParams(B, T, H, K, V, 64, OSDN_BF16 if bf16 else OSDN_F32, scale, hp.eta, hp.d_min,
                       hp.d_max, hp.eps, int(hp.beta_aware), int(bool(retention_per_channel)),
-                      int(bool(gate_per_channel)), int(hp.segments), int(hp.p1_pieces), int(hp.p1_piece_sweeps))
+                      int(bool(gate_per_channel)), int(hp.segments), int(hp.p1_pieces), int(hp.p1_piece_sweeps),
+                      int(hp.p1_solved))
 
 
 def _ret_shape(p: OsdnParams):

@@ -73,7 +73,8 @@ int check_params(const osdn_params *p, bool need_chunks) {
         return OSDN_ERR_PARAM;
     if (p->retention_per_channel != 0 && p->retention_per_channel != 1) return OSDN_ERR_PARAM;
     if (p->gate_per_channel != 0 && p->gate_per_channel != 1) return OSDN_ERR_PARAM;
-    if (p->segments < 0 || p->p1_pieces < -1 || p->p1_piece_sweeps < 0 || p->p1_piece_sweeps > MAX_PIECE_SWEEPS)
+    if (p->segments < 0 || p->p1_pieces < -1 || p->p1_piece_sweeps < 0 || p->p1_piece_sweeps > MAX_PIECE_SWEEPS ||
+        p->p1_solved < -1 || p->p1_solved > 1)
         return OSDN_ERR_PARAM;
     return OSDN_OK;
 }
@@ -722,7 +723,13 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     pb.dkt = c.dkt; pb.dk_read = c.dk_read;
     pb.n_seqs = pk.n_seqs; pb.seq_chunks = seq_chunks; pb.dd_last = dd_out;
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
-    if (!retention) {                   // chunks that never met the box take the solved form
+    // Without retention, chunks that never met the box can take the solved form of the reverse
+    // sweep: a shorter dependent chain for about 0.9 KB more memory traffic per token-head.  It
+    // pays when the chains are few (the chain is then what the chip waits for); with chains on
+    // more than an eighth of the CUs the pass is bound by its memory traffic and the sweeps stay.
+    const long long chains_all = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
+    const bool solved = !retention && (p->p1_solved > 0 || (p->p1_solved == 0 && chains_all * 8 <= NUM_CU));
+    if (solved) {
         pb.lin_clean = reinterpret_cast<int *>(ws + L.lin_clean);
         pb.lin_M = reinterpret_cast<float *>(ws + L.lin_M);
         pb.lin_r0 = reinterpret_cast<float *>(ws + L.lin_r0);
@@ -747,15 +754,19 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
         return timed(KID_UNFOLD, st, [&] { return launch_unfold(un, bf, st); });
     };
     // the box masks depend on the forward pass only: one launch for the whole sequence, up front
+    // (and with them which chunks take the solved form, and their inverses)
     auto masks = [&](hipStream_t s1) {
-        if (!(pb.d_min <= pb.d_max)) return 0;
         pb.n0 = 0; pb.n1 = N;
-        return timed(KID_PRECOND_MASK, s1, [&] { return launch_precond_mask(pb, bf, s1); });
+        if (pb.d_min <= pb.d_max && timed(KID_PRECOND_MASK, s1, [&] { return launch_precond_mask(pb, bf, s1); }) != 0)
+            return -1;
+        if (pb.lin_clean && timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, true, s1); }) != 0)
+            return -1;
+        return 0;
     };
     auto phase1 = [&](int sidx, hipStream_t s1) {
         seg_range(sidx, pb.n0, pb.n1);
         pb.dd_out = sidx == S - 1 ? dd_out : dd_in;  // the adjoint of d is carried in dd_in
-        if (pb.lin_clean && timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, s1); }) != 0) return -1;
+        if (pb.lin_clean && timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, false, s1); }) != 0) return -1;
         if (timed(KID_PRECOND_CHAIN, s1, [&] { return launch_precond_chain(pb, bf, s1); }) != 0) return -1;
         return timed(KID_PRECOND_POST, s1, [&] { return launch_precond_post(pb, bf, s1); });
     };

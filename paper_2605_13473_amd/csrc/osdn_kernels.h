@@ -141,7 +141,7 @@ int launch_upload_ints(const int *host, size_t count, int *dst, hipStream_t st);
 int launch_move_chunk_rows(const void *src, void *dst, const int *chunk_row, const int *chunk_len, int n_chunks,
                            size_t row_bytes, bool to_padded, uint32_t fill, hipStream_t st);
 int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
-int launch_precond_lin_bwd(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
+int launch_precond_lin_bwd(const PrecondBwdArgs &a, bool bf16_io, bool m_part, hipStream_t st);
 int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_post(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_chunk_prep(const ChunkArgs &a, bool bf16_io, hipStream_t st);

@@ -117,6 +117,10 @@ template <int K> struct Lin {
     static constexpr int VSTR = EPT + 4;                  // a thread's slice of a K-vector: slices start 16 bytes off a bank period
     static constexpr int XSTR = 12;                       // ... of a 64-vector (8 entries per slice)
     static __device__ __forceinline__ int vidx(int c) { return (c / EPT) * VSTR + c % EPT; }
+    // Position of coordinate c inside a row of the s tile: the 16-byte groups of a 16-coordinate
+    // slice are rotated by half the slice index, so that the 8 threads that write one group each
+    // for 8 adjacent slices (128 bytes apart) cover all 32 banks; column reads stay conflict-free.
+    static __device__ __forceinline__ int swz(int c) { return (c & ~12) | ((((c >> 2) + (c >> 5)) & 3) << 2); }
     static __device__ __forceinline__ int xidx(int i) { return (i >> 3) * XSTR + (i & 7); }
 };
 // sum over the 8 (4) adjacent lanes of an aligned group, returned to all of them

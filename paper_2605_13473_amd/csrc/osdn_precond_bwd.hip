@@ -72,26 +72,43 @@ __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
 }
 
 // ----------------------------------------------------------------- precond_lin ----
+// Two kernels, both one workgroup per (chain, chunk).  precond_lin_m needs the forward pass only
+// (keys, step scalars, masks): it decides whether the chunk qualifies and inverts the system.
+// precond_lin_r needs dL/dk~ of the chunk as well: rho0 and the sum of lambda.
 template <typename T, int K>
-__global__ __launch_bounds__(P1T) void precond_lin_bwd_kernel(PrecondBwdArgs a) {
+__global__ __launch_bounds__(P1T) void precond_lin_m_kernel(PrecondBwdArgs a) {
     typedef Lin<K> LN;
     constexpr int EPT = LN::EPT, VN = 16 / sizeof(T), NVK = EPT / VN;
-    constexpr int LDT = K + 4;                   // s and lambda tiles: MFMA fragment reads (row = lane % 16, k = lane / 16) spread over the banks
+    constexpr int LDT = K + 4;                   // s tile: MFMA fragment reads (row = lane % 16, k = lane / 16) spread over the banks
     constexpr int LDF = C + 1;
-    constexpr int NGK = P1T / K, TS = C / NGK;   // column layout: thread (c = tid % K, tg = tid / K) owns TS consecutive tokens
-    constexpr int INV_F = 2 * C * LDF + 3 * 16 * 17;
-    constexpr int POOL = C * LDT > INV_F ? C * LDT : INV_F;
-    __shared__ __attribute__((aligned(16))) float Ss[C * LDT];      // s = k^2
-    __shared__ __attribute__((aligned(16))) float pool[POOL];       // lambda -> its exclusive suffix sums; then A | (I + A)^-1 | block products
-    __shared__ float tot[NGK * K];
+    constexpr int TI_F = C * LDF + 3 * 16 * 17;  // (I + A)^-1 and the block products: in the s tile's space once A is built
+    static_assert(TI_F <= C * LDT || K == 64, "the inverse reuses the s tile");
+    __shared__ __attribute__((aligned(16))) float Ss[C * LDT > TI_F ? C * LDT : TI_F];
+    __shared__ __attribute__((aligned(16))) float Af[C * LDF];
     __shared__ float cas[C];
-    float *Lam = pool, *Af = pool, *Ti = pool + C * LDF, *Xs = pool + 2 * C * LDF;
+    float *Ti = Ss, *Xs = Ss + C * LDF;
 
     const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int N = a.T / C;
     const size_t bhn = ((size_t)b * a.H + h) * N + n;
     const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+    const int i = tid >> 3, part = tid & 7;
+    const uint32_t kstride = (uint32_t)a.H * K;
+    // the keys are requested before the masks decide whether they are needed
+    u32x4 kv[NVK];
+    {
+        const uint32_t off = ((uint32_t)i * kstride + (uint32_t)(part * EPT)) * (uint32_t)sizeof(T);
+        const u32x4 *kp = reinterpret_cast<const u32x4 *>(static_cast<const T *>(a.k) + tokc * K);
+#pragma unroll
+        for (int m = 0; m < NVK; ++m) kv[m] = at_byte(kp, off + 16 * m);
+    }
+    float nraw = 1.f, bet = 0.f;
+    if (tid < C) {
+        const size_t th = tokc + (size_t)tid * a.H;
+        nraw = a.tok_scalars[th * 4 + 2];
+        bet = a.beta[th];
+    }
     // ---- does the chunk qualify?  (no coordinate met the box at any of its tokens) ----
     bool ok = true;
     if (a.d_min <= a.d_max && tid < K) {
@@ -101,70 +118,24 @@ __global__ __launch_bounds__(P1T) void precond_lin_bwd_kernel(PrecondBwdArgs a) 
     const int clean = __syncthreads_and(ok ? 1 : 0);
     if (tid == 0) a.lin_clean[bhn] = clean;
     if (!clean) return;
-
-    const int i = tid >> 3, part = tid & 7;
-    const uint32_t kstride = (uint32_t)a.H * K;
-    {
-        const uint32_t off = ((uint32_t)i * kstride + (uint32_t)(part * EPT)) * (uint32_t)sizeof(T);
-        const T *kp = static_cast<const T *>(a.k) + tokc * K, *gp = static_cast<const T *>(a.dkt) + tokc * K;
 #pragma unroll
-        for (int m = 0; m < NVK; ++m) {
-            const u32x4 kv = at_byte(reinterpret_cast<const u32x4 *>(kp), off + 16 * m);
-            const u32x4 gv = at_byte(reinterpret_cast<const u32x4 *>(gp), off + 16 * m);
+    for (int m = 0; m < NVK; ++m)
 #pragma unroll
-            for (int e4 = 0; e4 < VN; e4 += 4) {
-                float sq[4], lm[4];
+        for (int e4 = 0; e4 < VN; e4 += 4) {
+            float sq[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float kf = vec_get<T>(kv, e4 + e);
-                    sq[e] = kf * kf;
-                    lm[e] = kf * vec_get<T>(gv, e4 + e);
-                }
-                store_vec(Ss + i * LDT + part * EPT + m * VN + e4, sq);
-                store_vec(Lam + i * LDT + part * EPT + m * VN + e4, lm);
+            for (int e = 0; e < 4; ++e) {
+                const float kf = vec_get<T>(kv[m], e4 + e);
+                sq[e] = kf * kf;
             }
+            store_vec(Ss + i * LDT + part * EPT + m * VN + e4, sq);
         }
-    }
     if (tid < C) {
-        const size_t th = tokc + (size_t)tid * a.H;
-        const float nn = fmaxf(a.tok_scalars[th * 4 + 2], a.eps);
-        const float bp = a.beta_aware ? a.beta[th] : 1.f;
+        const float nn = fmaxf(nraw, a.eps);
+        const float bp = a.beta_aware ? bet : 1.f;
         cas[tid] = a.eta * bp / nn * bp;
     }
     __syncthreads();
-    // ---- exclusive suffix sums of lambda down every column, in place ----
-    {
-        const int c = tid % K, tg = tid / K;
-        float acc = 0.f;
-#pragma unroll
-        for (int u = TS - 1; u >= 0; --u) {
-            float &cell = Lam[(tg * TS + u) * LDT + c];
-            const float t = cell;
-            cell = acc;
-            acc += t;
-        }
-        tot[tg * K + c] = acc;
-        __syncthreads();
-        float offs = 0.f;
-#pragma unroll
-        for (int g2 = NGK - 1; g2 > 0; --g2)
-            if (g2 > tg) offs += tot[g2 * K + c];
-        if (tg == 0) a.lin_t0[bhn * K + c] = acc + offs;        // sum of lambda over the chunk
-        if (tg < NGK - 1) {
-#pragma unroll
-            for (int u = 0; u < TS; ++u) Lam[(tg * TS + u) * LDT + c] += offs;
-        }
-    }
-    __syncthreads();
-    // ---- rho0_i = <s_i, sum_{j > i} lambda_j> ----
-    {
-        float r = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) r = __builtin_fmaf(Ss[i * LDT + part * EPT + e], Lam[i * LDT + part * EPT + e], r);
-        r = sum_lanes8(r);
-        if (part == 0) a.lin_r0[bhn * C + i] = r;
-    }
-    __syncthreads();                                             // the lambda tile is dead: its space takes A
     // ---- A = tril(ca_i <s_i, s_j>, -1): the transpose of U; (I + A)^-1 = ((I + U)^-1)^T ----
     for (int idx = wave; idx < 10; idx += P1W) {
         const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
@@ -176,7 +147,7 @@ __global__ __launch_bounds__(P1T) void precond_lin_bwd_kernel(PrecondBwdArgs a) 
             Af[ii * LDF + jj] = (jj < ii) ? cas[ii] * acc[r] : 0.f;
         }
     }
-    __syncthreads();
+    __syncthreads();                                             // the s tile is dead: its space takes the inverse
     ut_inverse64<LDF>(Af, Ti, Xs, wave, lane);
     // ---- (I + U)^-1, row i: entries j >= i are column i of the lower inverse ----
     {
@@ -194,6 +165,60 @@ __global__ __launch_bounds__(P1T) void precond_lin_bwd_kernel(PrecondBwdArgs a) 
     }
 }
 
+// rho0_i = <s_i, sum_{j > i} lambda_j> and sum_j lambda_j, lambda_j = k_j (.) dL/dk~_j: thread
+// (c = tid % K, tg = tid / K) keeps TS consecutive tokens of coordinate c in registers; the suffix
+// sums run down its tokens and across the runs through LDS; the row dots are folded over the lanes
+// as in the sweeps of precond_chain.
+template <typename T, int K>
+__global__ __launch_bounds__(P1T) void precond_lin_r_kernel(PrecondBwdArgs a) {
+    constexpr int NSEG = P1T / K, TS = C / NSEG, WPS = K / 64, NPART = K / TS;
+    __shared__ float tot[NSEG * K];
+    __shared__ float part[P1W * 64];
+    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c = tid % K, sg = tid / K;
+    const int N = a.T / C;
+    const size_t bhn = ((size_t)b * a.H + h) * N + n;
+    if (!a.lin_clean[bhn]) return;                               // (uniform)
+    const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
+    const uint32_t kstride = (uint32_t)a.H * K;
+    const T *kp = static_cast<const T *>(a.k) + tokc * K, *gp = static_cast<const T *>(a.dkt) + tokc * K;
+    float sv[TS], lam[TS];
+#pragma unroll
+    for (int u = 0; u < TS; ++u) {
+        const uint32_t o = (uint32_t)(sg * TS + u) * kstride + (uint32_t)c;
+        const float kf = to_f32(lane_elem(kp, o));
+        sv[u] = kf * kf;
+        lam[u] = kf * to_f32(lane_elem(gp, o));
+    }
+    float acc = 0.f;
+#pragma unroll
+    for (int u = TS - 1; u >= 0; --u) {                          // exclusive suffix sums inside the run
+        const float t = lam[u];
+        lam[u] = acc;
+        acc += t;
+    }
+    tot[sg * K + c] = acc;
+    __syncthreads();
+    float offs = 0.f;
+#pragma unroll
+    for (int g2 = NSEG - 1; g2 > 0; --g2)
+        if (g2 > sg) offs += tot[g2 * K + c];
+    if (sg == 0) a.lin_t0[bhn * K + c] = acc + offs;
+    float prod[TS];
+#pragma unroll
+    for (int u = 0; u < TS; ++u) prod[u] = sv[u] * (lam[u] + offs);
+    part[wave * 64 + lane] = lane_fold<TS>(prod, lane);
+    __syncthreads();
+    if (tid < C) {
+        const int w0 = (tid / TS) * WPS, u = tid % TS;
+        float r = 0.f;
+#pragma unroll
+        for (int j = 0; j < NPART; ++j) r += part[(w0 + j / (64 / TS)) * 64 + (j % (64 / TS)) * TS + u];
+        a.lin_r0[bhn * C + tid] = r;
+    }
+}
+
 // --------------------------------------------------------------- precond_chain ----
 // The adjoint recurrence is linear in a (the masks are data of the forward pass), so a chunk
 // is cut into NSEG = 512 / K runs of TS tokens and every thread owns one coordinate of one
@@ -202,8 +227,10 @@ __global__ __launch_bounds__(P1T) void precond_lin_bwd_kernel(PrecondBwdArgs a) 
 // through LDS (one fma per run); the TS products s_i abar_i of a thread are folded over the
 // lanes of the wavefront (each lane ends with the sum of one token over a group of lanes) and
 // the sigma of a token is the sum of K / TS such partials.  No tile of the chunk is ever in LDS.
-template <typename T, int K, int RET>
+// LINK: chunks that qualify take the solved form (no retention only; see the top of this file)
+template <typename T, int K, int RET, bool LINK>
 __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
+    static_assert(!LINK || RET == 0, "the solved form has no retention");
     constexpr bool HAS_RET = RET != 0, RET_VEC = RET == 2;
     constexpr int NSEG = P1T / K;                 // runs per chunk
     constexpr int TS = C / NSEG;                  // tokens per run
@@ -294,14 +321,17 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         R.t0 = a.lin_t0[bhn_ * K + lc];                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                       \
     }
-    // One chunk in solved form from the registers R; when they have been read, they are
-    // refilled with the chunk three further on (past the end of the run: a harmless reload of its
-    // last chunk).  No load or store of the step sits under a branch, and lanes that hold the
+    // One chunk in solved form from the registers R (a step outside the run [m_lo, n_hi] does
+    // nothing but the refill); when they have been read, they are refilled with the chunk three
+    // further on (clamped to the run: past its end a harmless reload of its last chunk).  No load or store of the step sits under a branch, and lanes that hold the
     // same value all store it: the loads of the other two register sets then stay in flight
     // across the step (behind a branch the compiler can no longer count what is outstanding and
     // waits for everything).
-#define OSDN_P1_LSTEP(n_, R, m_lo)                                                               \
+#define OSDN_P1_LSTEP(n_, R, m_lo, n_hi)                                                         \
     {                                                                                            \
+        const bool act_ = (n_) <= (n_hi) && (n_) >= (m_lo);       /* uniform */                  \
+        float pre_ = 0.f;                                                                        \
+        if (act_) {                                                                              \
         const size_t tokc_s = ((size_t)bt * a.T + (size_t)(n_) * C) * a.H + h;                   \
         a.a_ckpt[(bth * N + (n_)) * K + c] = ga[c];                                              \
         /* x = S g + rho0, and the s tile into LDS for the product with S^T */                   \
@@ -315,7 +345,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
                     sq[e] = kf * kf;                                                             \
                     y = __builtin_fmaf(sq[e], gv[e], y);                                         \
                 }                                                                                \
-                store_vec(Sl + li * LN::LD + lpart * EPT + m_ * VN + e4, sq);                    \
+                store_vec(Sl + li * LN::LD + LN::swz(lpart * EPT + m_ * VN + e4), sq);                    \
             }                                                                                    \
         y = sum_lanes8(y);                                                                       \
         const float nn_ = fmaxf(R.nraw, a.eps);                                                  \
@@ -332,24 +362,27 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         sgm = sum_lanes8(sgm);                                                                   \
         ws[li] = ca_i * sgm;                                                                     \
         a.tok_scalars[(tokc_s + (size_t)li * a.H) * 4 + 3] = sgm;                                \
-        const float pre_ = ga[lc] + R.t0;       /* (no loaded value is kept past the refill) */  \
-        OSDN_P1_LLOAD(max((n_) - 3, (m_lo)), R)                                                  \
+        pre_ = ga[lc] + R.t0;                   /* (no loaded value is kept past the refill, */  \
+        asm volatile("" : "+v"(pre_));          /*  and this sum is not moved behind it)     */  \
+        }                                                                                        \
+        OSDN_P1_LLOAD(min(max((n_) - 3, (m_lo)), (n_hi)), R)                                     \
+        if (act_) {                                                                              \
         __syncthreads();                                                                         \
         /* a_left = g + sum lambda - S^T (ca (.) sigma) */                                       \
         float acc_ = 0.f;                                                                        \
         _Pragma("unroll") for (int u = 0; u < C / NG; ++u)                                       \
-            acc_ = __builtin_fmaf(Sl[(u * NG + ltg) * LN::LD + lc], ws[u * NG + ltg], acc_);     \
+            acc_ = __builtin_fmaf(Sl[(u * NG + ltg) * LN::LD + LN::swz(lc)], ws[u * NG + ltg], acc_);     \
         acc_ = NG == 4 ? sum_lanes4(acc_) : sum_lanes8(acc_);                                    \
         const float gn = pre_ - acc_;                                                            \
         ga[lc] = gn;                                                                             \
         gp[LN::vidx(lc)] = gn;                                                                   \
         __syncthreads();                                                                         \
+        }                                                                                        \
     }
     // Which chunks take the solved form: the flags precond_lin left, as bits in LDS (bit n - n0;
-    // chunks past the table's reach sweep).  Without retention only the solved form prefetches
-    // (three chunks deep, inside a run of such chunks); a chunk that has to sweep fetches its
-    // operands when it starts: keeping both sets of registers alive across the loop would spill.
-    constexpr bool LINK = !HAS_RET;
+    // chunks past the table's reach sweep).  With LINK only the solved form prefetches (three
+    // chunks deep, inside a run of such chunks); a chunk that has to sweep fetches its operands
+    // when it starts: keeping both sets of registers alive across the loop would spill.
     constexpr int FLAG_WORDS = 512;
     __shared__ uint32_t flagw[LINK ? FLAG_WORDS : 1];
     const bool lin = LINK && a.lin_clean != nullptr;
@@ -377,16 +410,13 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
             // the run [m, n] of chunks in solved form, three chunks in flight
             int m = n;
             while (m > a.n0 && solved(m - 1)) --m;
+            // (the first three steps only request operands: with nothing requested ahead of the
+            // loop, the compiler's count of what is outstanding at the top of the loop is exact)
             LinRegs r0, r1, r2;
-            OSDN_P1_LLOAD(n, r0)
-            OSDN_P1_LLOAD(max(n - 1, m), r1)
-            OSDN_P1_LLOAD(max(n - 2, m), r2)
-            for (int j = n; j >= m; j -= 3) {
-                OSDN_P1_LSTEP(j, r0, m)
-                if (j - 1 < m) break;
-                OSDN_P1_LSTEP(j - 1, r1, m)
-                if (j - 2 < m) break;
-                OSDN_P1_LSTEP(j - 2, r2, m)
+            for (int j = n + 3; j >= m; j -= 3) {
+                OSDN_P1_LSTEP(j, r0, m, n)
+                OSDN_P1_LSTEP(j - 1, r1, m, n)
+                OSDN_P1_LSTEP(j - 2, r2, m, n)
             }
             n = m;                                  // (the loop's own decrement moves past the run)
             continue;
@@ -601,17 +631,27 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
 }
 
 // -------------------------------------------------------------------- launchers ----
+template <typename T, int K, int RET>
+static void launch_chain_k(const PrecondBwdArgs &a, int nchains, hipStream_t st) {
+    if constexpr (RET == 0) {
+        if (a.lin_clean) {
+            hipLaunchKernelGGL((precond_chain_kernel<T, K, 0, true>), dim3(nchains), dim3(P1T), 0, st, a);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((precond_chain_kernel<T, K, RET, false>), dim3(nchains), dim3(P1T), 0, st, a);
+}
 template <typename T, int RET>
 static int launch_precond_bwd_t(const PrecondBwdArgs &a, int which, hipStream_t st) {
     const dim3 per_chunk(a.n1 - a.n0, a.H, a.B);
     const int nchains = (a.seq_chunks ? a.n_seqs : a.B) * a.H;
     if (a.K == 64) {
         if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 64, RET>), per_chunk, dim3(64), 0, st, a);
-        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 64, RET>), dim3(nchains), dim3(P1T), 0, st, a);
+        else if (which == 1) launch_chain_k<T, 64, RET>(a, nchains, st);
         else hipLaunchKernelGGL((precond_post_kernel<T, 64, RET>), per_chunk, dim3(64), 0, st, a);
     } else if (a.K == 128) {
         if (which == 0) hipLaunchKernelGGL((precond_mask_kernel<T, 128, RET>), per_chunk, dim3(128), 0, st, a);
-        else if (which == 1) hipLaunchKernelGGL((precond_chain_kernel<T, 128, RET>), dim3(nchains), dim3(P1T), 0, st, a);
+        else if (which == 1) launch_chain_k<T, 128, RET>(a, nchains, st);
         else hipLaunchKernelGGL((precond_post_kernel<T, 128, RET>), per_chunk, dim3(128), 0, st, a);
     } else {
         return -1;
@@ -627,17 +667,24 @@ static int launch_precond_bwd_any(const PrecondBwdArgs &a, bool bf16_io, int whi
     return bf16_io ? launch_precond_bwd_t<bf16, 0>(a, which, st) : launch_precond_bwd_t<float, 0>(a, which, st);
 }
 template <typename T>
-static int launch_precond_lin_t(const PrecondBwdArgs &a, hipStream_t st) {
+static int launch_precond_lin_t(const PrecondBwdArgs &a, bool m_part, hipStream_t st) {
     const dim3 per_chunk(a.n1 - a.n0, a.H, a.B);
-    if (a.K == 64) hipLaunchKernelGGL((precond_lin_bwd_kernel<T, 64>), per_chunk, dim3(P1T), 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((precond_lin_bwd_kernel<T, 128>), per_chunk, dim3(P1T), 0, st, a);
-    else return -1;
+    if (a.K == 64) {
+        if (m_part) hipLaunchKernelGGL((precond_lin_m_kernel<T, 64>), per_chunk, dim3(P1T), 0, st, a);
+        else hipLaunchKernelGGL((precond_lin_r_kernel<T, 64>), per_chunk, dim3(P1T), 0, st, a);
+    } else if (a.K == 128) {
+        if (m_part) hipLaunchKernelGGL((precond_lin_m_kernel<T, 128>), per_chunk, dim3(P1T), 0, st, a);
+        else hipLaunchKernelGGL((precond_lin_r_kernel<T, 128>), per_chunk, dim3(P1T), 0, st, a);
+    } else {
+        return -1;
+    }
     return 0;
 }
-// only without retention; needs the masks (when there is a box) and dL/dk~ of the chunks [n0, n1)
-int launch_precond_lin_bwd(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) {
+// only without retention.  m_part: flags and inverses of the chunks [n0, n1) (needs the masks when
+// there is a box); else rho0 and the sums of lambda (needs the flags and dL/dk~ of those chunks)
+int launch_precond_lin_bwd(const PrecondBwdArgs &a, bool bf16_io, bool m_part, hipStream_t st) {
     if (a.retention || !a.lin_clean || !a.lin_M || !a.lin_r0 || !a.lin_t0) return -1;
-    return bf16_io ? launch_precond_lin_t<bf16>(a, st) : launch_precond_lin_t<float>(a, st);
+    return bf16_io ? launch_precond_lin_t<bf16>(a, m_part, st) : launch_precond_lin_t<float>(a, m_part, st);
 }
 int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) { return launch_precond_bwd_any(a, bf16_io, 0, st); }
 int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st) { return launch_precond_bwd_any(a, bf16_io, 1, st); }

@@ -76,6 +76,41 @@ def test_phase1_as_sweeps_over_pieces(case):
     compare_backward(x, hp, bf16)
 
 
+@pytest.mark.parametrize("solved", [1, -1])
+@pytest.mark.parametrize("case", ["paper_eta", "box_met_in_some_chunks", "no_projection", "k128_bf16_ragged",
+                                  "non_beta_aware_long"])
+def test_reverse_sweep_in_solved_form(case, solved):
+    """Without retention the reverse sweep through the preconditioner takes every chunk in which no
+    coordinate met the box in solved form (the 64 x 64 triangular system of the chunk, inverted for
+    all chunks side by side, three matrix-vector products left on the chain); chunks that met the box
+    sweep.  Forced on and forced off: at the paper's eta (every chunk qualifies), at eta = 0.5 with
+    d_in inside the box (runs of qualifying chunks between chunks that do not), without a box and
+    with strong coupling, with K = 128 in bf16 on a ragged length, and over 40 chunks (several
+    segments, the carried adjoint handed from one launch to the next)."""
+    bf16 = case == "k128_bf16_ragged"
+    B, T, H, K, V = {"paper_eta": (2, 448, 2, 64, 64), "box_met_in_some_chunks": (2, 640, 3, 64, 64),
+                     "no_projection": (1, 320, 2, 128, 64), "k128_bf16_ragged": (2, 64 * 9 - 17, 2, 128, 128),
+                     "non_beta_aware_long": (1, 64 * 40, 2, 64, 64)}[case]
+    x = make_stress_inputs(B, T, H, K, V, seed=111, bf16=bf16, retention=0.0,
+                           d_lo=0.7 if case == "box_met_in_some_chunks" else 0.5,
+                           d_hi=1.6 if case == "box_met_in_some_chunks" else 2.0)
+    hp = {"paper_eta": ob.Hyper(p1_solved=solved),
+          "box_met_in_some_chunks": ob.Hyper(eta=0.5, p1_solved=solved),
+          "no_projection": ob.Hyper(eta=0.3, d_min=1.0, d_max=0.0, p1_solved=solved),
+          "k128_bf16_ragged": ob.Hyper(eta=0.02, p1_solved=solved),
+          "non_beta_aware_long": ob.Hyper(eta=0.05, beta_aware=False, p1_solved=solved)}[case]
+    if case == "paper_eta":
+        x["d_in"] = (0.8 + 0.4 * (x["d_in"] - 0.5) / 1.5).astype(np.float32)      # well inside the box
+    rng = np.random.default_rng(112)
+    dS = rng.standard_normal((B, H, V, K)).astype(np.float32)
+    dd = rng.standard_normal((B, H, K)).astype(np.float32)
+    compare_backward(x, hp, bf16, dS, dd)
+    if case == "box_met_in_some_chunks":        # the input really mixes the two kinds of chunk
+        _, _, traj = oracle.precond(x["k"], x["beta"], None, x["d_in"], oracle_hp(hp), want_traj=True)
+        on_face = ((traj == 0.5) | (traj == 2.0)).reshape(B, T // 64, 64, H, K).any(axis=(2, 4))
+        assert on_face.any() and not on_face.all()
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_large_launches_two_chunks_per_workgroup(bf16):
     """256 chains and 17 chunks: the second segment of either pass is a launch of more than 2048

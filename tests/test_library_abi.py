@@ -136,14 +136,15 @@ def test_scheduling_fields_and_mask_offset_query():
     L = ob.lib()
     fake = ctypes.c_void_p(0x1000)
     base = ob.make_params(2, 4096, 2, 128, 128, True)
-    assert (base.segments, base.p1_pieces, base.p1_piece_sweeps) == (0, 0, 0)
+    assert (base.segments, base.p1_pieces, base.p1_piece_sweeps, base.p1_solved) == (0, 0, 0, 0)
     fwd, bwd = ob.osdn_workspace_bytes(base, False), ob.osdn_workspace_bytes(base, True)
     tuned = ob.make_params(2, 4096, 2, 128, 128, True, ob.Hyper(segments=3, p1_pieces=4, p1_piece_sweeps=2))
     assert (tuned.segments, tuned.p1_pieces, tuned.p1_piece_sweeps) == (3, 4, 2)
     assert ob.osdn_workspace_bytes(tuned, False) == fwd and ob.osdn_workspace_bytes(tuned, True) == bwd
     never = ob.make_params(2, 4096, 2, 128, 128, True, ob.Hyper(p1_pieces=-1, segments=1))
     assert ob.osdn_workspace_bytes(never, True) == bwd
-    for bad in (dict(segments=-1), dict(p1_pieces=-2), dict(p1_piece_sweeps=-1), dict(p1_piece_sweeps=14)):
+    for bad in (dict(segments=-1), dict(p1_pieces=-2), dict(p1_piece_sweeps=-1), dict(p1_piece_sweeps=14),
+                dict(p1_solved=2), dict(p1_solved=-2)):
         q = ob.make_params(2, 4096, 2, 128, 128, True, ob.Hyper(**bad))
         assert ob.osdn_workspace_bytes(q, False) == 0, bad
         assert L.osdn_fwd(ctypes.byref(q), fake, fake, fake, fake, None, None, None, None, fake, fake, fake,
