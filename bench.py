@@ -85,20 +85,17 @@ def kernel_models(cfg, es):
     m["chunk_prep"] = ("hbm", th * (4 * K * es + 2 * V * es + C * es + 2 * g))
     # state_fwd: read -W^T, (rho k~)^T, U^T ; write E^T, S checkpoints ; 2 KV-class GEMMs
     m["state_fwd"] = ("hbm", th * (2 * K * es + 2 * V * es + g) + nch * V * K * es)
-    # output_fwd: read q, k~, S ckpt, E^T ; write o
-    m["output_fwd"] = ("hbm", th * (2 * K * es + 2 * V * es + g) + nch * V * K * es)
-    # bwd_local: read q, k~, dO ; write (gamma q)^T, dO^T, dEl^T
-    m["bwd_local"] = ("hbm", th * (3 * K * es + 3 * V * es + g))
-    # bwd_chain: read -W^T, k~, (gamma q)^T, dO^T, dEl^T ; write dE^T, dS' checkpoints
-    m["bwd_chain"] = ("hbm", th * (3 * K * es + 3 * V * es + g) + nch * V * K * es)
+    # output_fwd: read q, k~, S ckpt, E^T ; write o (and P when a backward pass follows)
+    m["output_fwd"] = ("hbm", th * (2 * K * es + 2 * V * es + g + (C * es if cfg.backward else 0)) + nch * V * K * es)
+    # bwd_chain: read -W^T, (rho k~)^T, q, dO, P ; write dE^T, dS' checkpoints
+    m["bwd_chain"] = ("hbm", th * (3 * K * es + 2 * V * es + C * es + g) + nch * V * K * es)
     # bwd_post: read q, k, k~, v, dO, E^T, dE^T, T, S and dS' ckpts ; write dq, dv, dk (read side), dk~, dbeta, dg
     m["bwd_post"] = ("hbm", th * (6 * K * es + 5 * V * es + C * es + 4 * g) + 2 * nch * V * K * es)
     flops = {
         "chunk_prep": th * (C * K + C * K + C * V + C * C / 3.0),               # Gram, W, U (half), inverse
         "state_fwd": th * 4 * K * V,
         "output_fwd": th * (C * K + 2 * K * V + C * V),
-        "bwd_local": th * (C * K + C * V),
-        "bwd_chain": th * 6 * K * V,
+        "bwd_chain": th * (6 * K * V + C * V),
         "bwd_post": th * (C * V + 2 * K * V + 2 * C * V + 6 * K * V + 2 * C * K + 4 * C * K),
     }
     return m, flops

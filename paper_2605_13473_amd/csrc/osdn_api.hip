@@ -14,11 +14,11 @@ using namespace osdn;
 
 // Optional per-kernel timing with HIP events on the caller's stream (off by default; the
 // only process-wide state the library has).  Not thread-safe; meant for benchmarks.
-enum { KID_PRECOND_FWD, KID_CHUNK_PREP, KID_STATE_FWD, KID_OUTPUT_FWD, KID_BWD_LOCAL, KID_BWD_CHAIN,
+enum { KID_PRECOND_FWD, KID_CHUNK_PREP, KID_STATE_FWD, KID_OUTPUT_FWD, KID_BWD_CHAIN,
        KID_BWD_POST, KID_PRECOND_MASK, KID_PRECOND_CHAIN, KID_PRECOND_POST, KID_STEP, KID_PAD, KID_UNFOLD, KID_PRECOND_LIN,
        KID_COUNT };
 const char *const kKernelNames[KID_COUNT] = {"precond_fwd", "chunk_prep", "state_fwd", "output_fwd",
-                                             "bwd_local", "bwd_chain", "bwd_post", "precond_mask",
+                                             "bwd_chain", "bwd_post", "precond_mask",
                                              "precond_chain", "precond_post", "step", "pad", "unfold", "precond_lin"};
 struct Timed { int id; hipEvent_t e0, e1; };
 bool g_prof_on = false;
@@ -38,9 +38,10 @@ template <typename F> int timed(int id, hipStream_t st, F &&launch) {
 struct Layout {
     size_t Qg, Kg, Kd, gamC, dgamC;                                      // per-channel state gate
     size_t tables;                                                       // packed sequences: the index tables
-    size_t kt, d_ckpt, tok_scalars, Tm, Wt, Ktr, Ut, Et, S_ckpt;   // forward
+    size_t kt, d_ckpt, tok_scalars, Wt, Ktr, Ut, Et, S_ckpt;       // forward
     size_t piece_start, piece_map, piece_flags;                          // phase 1 as sweeps over the whole sequence
-    size_t dElt, Qt, dOt, dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;   // backward only
+    size_t Tm, Pm;                                                       // written by the forward pass for the backward pass only
+    size_t dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;                    // backward only
     size_t lin_clean, lin_M, lin_r0, lin_t0;                             // backward: chunks of phase 1 in solved form
     // padded copies of the caller's tensors, only when T is not a multiple of the chunk length
     size_t p_q, p_k, p_v, p_beta, p_g, p_r, p_o;                        // forward
@@ -138,7 +139,6 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     L.kt = take(B * T * H * K * es);
     L.d_ckpt = take(B * H * N * K * 4);
     L.tok_scalars = take(B * T * H * 4 * 4);
-    L.Tm = take(B * H * N * C * C * es);
     L.Wt = take(B * T * H * K * es);
     L.Ktr = take(B * T * H * K * es);
     L.Ut = take(B * T * H * V * es);
@@ -157,9 +157,8 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     L.piece_map = take((size_t)2 * MAX_PIECES * K * 16);
     L.piece_flags = take((MAX_PIECES / 2) * sizeof(int));       // one "settled" flag per chain
     L.total_fwd = off;
-    L.dElt = take(B * T * H * V * es);
-    L.Qt = take(B * T * H * K * es);
-    L.dOt = take(B * T * H * V * es);
+    L.Tm = take(B * H * N * C * C * es);
+    L.Pm = take(B * H * N * C * C * es);
     L.dEt = take(B * T * H * V * es);
     L.dS_ckpt = take(B * H * N * V * K * es);
     L.dk_read = take(B * T * H * K * es);
@@ -201,7 +200,7 @@ ChunkArgs chunk_args(const osdn_params *p, const Layout &L, char *ws) {      // 
     ChunkArgs c{};
     c.B = p->B; c.T = p->T; c.H = p->H; c.K = p->K; c.V = p->V; c.N = p->T / C;
     c.scale = p->scale;
-    c.kt = ws + L.kt; c.Tm = ws + L.Tm; c.Wt = ws + L.Wt; c.Ktr = ws + L.Ktr;
+    c.kt = ws + L.kt; c.Wt = ws + L.Wt; c.Ktr = ws + L.Ktr;
     c.Ut = ws + L.Ut; c.Et = ws + L.Et;
     c.S_ckpt = ws + L.S_ckpt;
     return c;
@@ -532,6 +531,9 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     ChunkArgs c = chunk_args(p, L, ws);
     c.q = q; c.k = k; c.v = v; c.beta = beta; c.log_alpha = log_alpha;
     c.o = o; c.S_out = S_out;
+    // (I + A)^-1 and P are only of use to a backward pass: they are written when the workspace is
+    // the one osdn_workspace_bytes(p, 1) asks for, which osdn_bwd requires anyway
+    if (workspace_bytes >= L.total_bwd) { c.Tm = ws + L.Tm; c.Pm = ws + L.Pm; }
     c.n_seqs = pk.n_seqs; c.seq_chunks = seq_chunks; c.S_first = S_in;
     // one state gate per key channel: chunk_prep folds the channel decays into the operands and
     // leaves Gamma . Q and K~ / Gamma, on which the state and output kernels run as if ungated
@@ -688,7 +690,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     ChunkArgs c = chunk_args(p, L, ws);
     c.q = q; c.k = k; c.v = v; c.beta = beta; c.log_alpha = log_alpha;
     c.dO = dO; c.dS_out = dS_out;
-    c.dElt = ws + L.dElt; c.Qt = ws + L.Qt; c.dOt = ws + L.dOt; c.dEt = ws + L.dEt; c.dS_ckpt = ws + L.dS_ckpt;
+    c.Tm = ws + L.Tm; c.Pm = ws + L.Pm; c.dEt = ws + L.dEt; c.dS_ckpt = ws + L.dS_ckpt;
     c.dS_in = dS_in; c.dq = dq; c.dv = dv;
     c.dk_read = ws + L.dk_read;
     c.dkt = ws + L.dkt;
@@ -746,8 +748,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
         seg_range(sidx, c.n0, c.n1);
         c.dS_out = sidx == S - 1 ? dS_out : dS_in;   // dS is carried in dS_in
         const int rc2 = timed(kid, st, [&] {
-            return kid == KID_BWD_LOCAL ? launch_bwd_local(c, bf, st)
-                 : kid == KID_BWD_CHAIN ? launch_bwd_chain(c, bf, st) : launch_bwd_post(c, bf, st);
+            return kid == KID_BWD_CHAIN ? launch_bwd_chain(c, bf, st) : launch_bwd_post(c, bf, st);
         });
         if (rc2 != 0 || !gv || kid != KID_BWD_POST) return rc2;
         un.n0 = c.n0; un.n1 = c.n1;                    // the segment's gradients, back to q, k, k~ and log alpha
@@ -771,7 +772,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
         return timed(KID_PRECOND_POST, s1, [&] { return launch_precond_post(pb, bf, s1); });
     };
     if (!pl) {
-        if (phase2(KID_BWD_LOCAL, 0) != 0 || phase2(KID_BWD_CHAIN, 0) != 0 || phase2(KID_BWD_POST, 0) != 0 ||
+        if (phase2(KID_BWD_CHAIN, 0) != 0 || phase2(KID_BWD_POST, 0) != 0 ||
             masks(st) != 0 || phase1(0, st) != 0)
             return OSDN_ERR_SHAPE;
         return finish();
@@ -784,7 +785,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     SideJoin rejoin{pl, st, true};
     if (masks(s1) != 0) return OSDN_ERR_SHAPE;
     for (int s = S - 1; s >= 0; --s) {
-        if (phase2(KID_BWD_LOCAL, s) != 0 || phase2(KID_BWD_CHAIN, s) != 0 || phase2(KID_BWD_POST, s) != 0)
+        if (phase2(KID_BWD_CHAIN, s) != 0 || phase2(KID_BWD_POST, s) != 0)
             return OSDN_ERR_SHAPE;
         OSDN_HIP_OK(hipEventRecord(pl->a[s], st));
     }

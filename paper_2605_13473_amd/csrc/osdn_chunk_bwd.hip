@@ -7,9 +7,9 @@
 //   forward:  A = tril(beta_i Gamma_ij <k_i,k~_j>, -1), T = (I+A)^-1, R0 = V - gamma.(K S^T),
 //             E = T (beta . R0), P = tril(Gamma . Q K~^T), O = scale[gamma.(Q S^T) + P E],
 //             S' = gamma_C S + E^T (rho . K~)
-//   bwd_local (parallel):  dEl = scale P^T dO
 //   bwd_chain (sequential, right to left, per (b, h, slice of V)):
-//             dE = dEl + (rho . K~) dS'^T ;  dS = gamma_C dS' + scale dO^T (gamma . Q) - dE^T W
+//             dE = scale P^T dO + (rho . K~) dS'^T ;  dS = gamma_C dS' + scale dO^T (gamma . Q) - dE^T W
+//             (P is the tile output_fwd left; q and dO are read where the caller put them)
 //   bwd_post  (parallel):  dR = T^T dE ; dV = beta . dR ; dA = -tril(dR E^T, -1) ;
 //             dP = scale tril(dO E^T) ; cA = dA . beta_i Gamma ; cP = dP . Gamma ;
 //             dQ = cP K~ + scale gamma . (dO S) ; dK = cA K~ - gamma beta . (dR S) ;
@@ -37,115 +37,47 @@ __device__ __forceinline__ float row16_sum(float x) {
     return x;
 }
 
-// ------------------------------------------------------------- bwd_local ----
-// dEl = scale P^T dO, stored transposed; also leaves (scale gamma . Q)^T and dO^T in the layout
-// the chain kernel's MFMA operands want.
-constexpr int BL_ = 512;        // threads of a bwd_local workgroup: 8 wavefronts, (16 rows or columns, half of the tiles)
-template <typename T, int K>
-__global__ __launch_bounds__(BL_) void bwd_local_kernel(ChunkArgs a) {
-    constexpr int PAD = Pad<T>::v, LDK = K + (sizeof(T) == 2 ? 16 : PAD), LDC = C + PAD;   // Q, K~: read 16 bytes per lane along k
-    constexpr int NW = BL_ / 64;
-    __shared__ __attribute__((aligned(16))) T Qs[C * LDK];
-    constexpr int KTS_ELEMS = C * LDK > K * LDC ? C * LDK : K * LDC;
-    __shared__ __attribute__((aligned(16))) T Kts[KTS_ELEMS];   // K~, later the (scale gamma Q)^T staging
-    __shared__ __attribute__((aligned(16))) T PT[C * LDC];      // scale * P^T
-    __shared__ __attribute__((aligned(16))) T dOs[C * LDC];
-    __shared__ __attribute__((aligned(16))) T dOt[C * LDC];
-    __shared__ __attribute__((aligned(16))) T Os[C * LDC];
-    __shared__ float Gs[C];
-
-    const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const size_t bhn = ((size_t)b * a.H + h) * a.N + n;
-    const size_t tok0 = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
-    const size_t tstride = a.H;
-
-    if (wave == 0) {
-        const float g = a.log_alpha ? a.log_alpha[tok0 + (size_t)lane * tstride] : 0.f;
-        Gs[lane] = wave_cumsum(g, lane);
-    }
-    load_tile(Qs, LDK, static_cast<const T *>(a.q) + tok0 * K, tstride * K, C, K, tid, BL_);
-    load_tile(Kts, LDK, static_cast<const T *>(a.kt) + tok0 * K, tstride * K, C, K, tid, BL_);
-    TileRegs<T, C, C, BL_> r_dO;          // the slabs of dO travel through registers, one slab ahead
-    r_dO.fetch(static_cast<const T *>(a.dO) + tok0 * a.V, tstride * a.V, tid);
-    __syncthreads();
-    for (int idx = wave; idx < 16; idx += NW) {
-        const int ib = idx >> 2, jb = idx & 3;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        if (jb <= ib) {
-            mma_tile<T, true, true>(acc, Qs + ib * 16 * LDK, LDK, Kts + jb * 16 * LDK, LDK, K, lane);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = ib * 16 + acc_row(lane, r), j = jb * 16 + acc_col(lane);
-                acc[r] = (j <= i) ? a.scale * __expf(Gs[i] - Gs[j]) * acc[r] : 0.f;
-            }
-        }
-        store_tile_t(PT + jb * 16 * LDC + ib * 16, LDC, acc, lane);
-    }
-    __syncthreads();                    // K~ is no longer needed: its buffer takes (scale gamma Q)^T
-    T *Qtt = Kts;
-    for (int t = wave; t < (K / 16) * 4; t += NW) {       // 16 features x 16 tokens at a time
-        const int nb = t >> 2, ib = t & 3;
-        f32x4 acc = pick16<T>(Qs + ib * 16 * LDK, LDK, nb * 16, lane);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[r] *= a.scale * __expf(Gs[ib * 16 + acc_row(lane, r)]);
-        store_tile_t(Qtt + nb * 16 * LDC + ib * 16, LDC, acc, lane);
-    }
-    __syncthreads();
-    store_tile_global(static_cast<T *>(a.Qt) + bhn * K * C, (size_t)C, Qtt, LDC, K, C, tid, BL_);
-    const int wb = wave & 3, wh = wave >> 2;    // 16 rows / columns of this wavefront, and which half of the tiles
-    const int k0 = (wb * 16) / Mfma<T>::KSTEP * Mfma<T>::KSTEP;     // P^T rows 16*wb.. are zero left of here
-    for (int v0 = 0; v0 < a.V; v0 += C) {
-        __syncthreads();
-        r_dO.put(dOs, LDC, tid);
-        if (v0 + C < a.V) r_dO.fetch(static_cast<const T *>(a.dO) + tok0 * a.V + v0 + C, tstride * a.V, tid);
-        __syncthreads();
-        // dO^T for this slab: a wavefront transposes 16 columns (wb) of two row blocks (wh)
-#pragma unroll
-        for (int iq = 0; iq < 2; ++iq) {
-            const int ib = wh * 2 + iq;
-            const f32x4 acc = pick16<T>(dOs + ib * 16 * LDC, LDC, wb * 16, lane);
-            store_tile_t(dOt + wb * 16 * LDC + ib * 16, LDC, acc, lane);
-        }
-        __syncthreads();
-        store_tile_global(static_cast<T *>(a.dOt) + (bhn * a.V + v0) * C, (size_t)C, dOt, LDC, C, C, tid, BL_);
-        // dEl rows j = 16*wb .. : sum_i P^T[j][i] dO[i][v], stored transposed
-#pragma unroll
-        for (int vq = 0; vq < 2; ++vq) {
-            const int vt = wh * 2 + vq;
-            f32x4 acc = mma_tile0<T, true, true>(PT + wb * 16 * LDC + k0, LDC, dOt + vt * 16 * LDC + k0, LDC, C - k0, lane);
-            store_tile_t(Os + vt * 16 * LDC + wb * 16, LDC, acc, lane);
-        }
-        __syncthreads();
-        store_tile_global(static_cast<T *>(a.dElt) + (bhn * a.V + v0) * C, (size_t)C, Os, LDC, C, C, tid, BL_);
-    }
-}
+// a one-value (fp32) MFMA fragment times a scalar; the 8-value bf16 fragments are never scaled
+__device__ __forceinline__ float scale_frag(float f, float s) { return f * s; }
+__device__ __forceinline__ bf16x8 scale_frag(bf16x8 f, float) { return f; }
 
 // ------------------------------------------------------------- bwd_chain ----
 // Mirror image of state_fwd, right to left: wavefronts 0-3 carry dS (transposed, fp32, in
 // MFMA accumulators), wavefronts 4-7 bring the next chunk's operand tiles into the other LDS
-// buffer and write the dS' checkpoint and dE^T back.
+// buffer and write the dS' checkpoint and dE^T back.  The operands come as the forward pass and
+// the caller left them: (rho . K~)^T and -W^T from chunk_prep, P from output_fwd, q and the
+// slice of dO in their natural [token][feature] layout (operands whose contraction index runs
+// along the rows are fetched with the LDS transpose read), so no kernel has to run ahead of this
+// one.  The local part of dE, scale P^T dO, is formed here as well.  The loader wavefronts move
+// the three [64 x K] tiles; the small ones (P, the slice of dO) are fetched by the compute
+// wavefronts themselves, a chunk ahead, into registers they have to spare.
 constexpr int CT_ = 512, CL_ = 256;
 
 // GV: one state gate per key channel (the chunk's decay per channel comes from chunk_prep).
 template <typename T, int K, bool GV>
 __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
-    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
+    constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDS_ = VS + PAD;
     constexpr int VN = 16 / sizeof(T);
     constexpr int NKT = K / 64;
-    constexpr int NB = sizeof(T) == 2 ? 2 : 1;
+    constexpr int KS = Mfma<T>::KSTEP;
+    constexpr bool BF = sizeof(T) == 2;
+    constexpr int NB = BF ? 2 : 1;
     constexpr int LTN = NB == 2 ? CL_ / 2 : CL_;    // two loader groups (one per chunk parity) when double-buffered
-    constexpr int NWV = C * K / VN / LTN;
-    constexpr int NUV = VS * C / VN / LTN;
-    static_assert(VS * C / VN % LTN == 0 && C * K / VN % LTN == 0, "tiles must split evenly over the loaders");
+    constexpr int NWV = C * K / VN / LTN;           // vectors per loader thread: a [64 x K] or [K x 64] tile
+    constexpr int NCW = CT_ - CL_;                  // compute threads
+    constexpr int NPV = C * C / VN / NCW;           // vectors per compute thread: the [64 x 64] tile P
+    constexpr int NUV = C * VS / VN / NCW;          // ... the [64 x VS] slice of dO
+    static_assert(C * K / VN % LTN == 0 && C * VS / VN % NCW == 0 && C * C / VN % NCW == 0, "tiles must split evenly");
     __shared__ __attribute__((aligned(16))) T Krt[NB][K * LDC];     // (rho . K~)^T   [kf][i], as chunk_prep left it
-    __shared__ __attribute__((aligned(16))) T Wtt[NB][K * LDC];     // -W^T        [kf][i]
-    __shared__ __attribute__((aligned(16))) T Qtt[NB][K * LDC];     // (scale gamma . Q)^T
-    __shared__ __attribute__((aligned(16))) T dOts[NB][VS * LDC];   // dO^T slice  [v][i]
-    __shared__ __attribute__((aligned(16))) T dEls[NB][VS * LDC];   // dEl^T slice [v][i]
+    __shared__ __attribute__((aligned(16))) T Wtt[NB][K * LDC];     // -W^T           [kf][i]
+    __shared__ __attribute__((aligned(16))) T Qn[NB][C * LDK];      // q              [i][kf]
+    __shared__ __attribute__((aligned(16))) T Pn[NB][C * LDC];      // P              [i][j]
+    __shared__ __attribute__((aligned(16))) T dOn[NB][C * LDS_];    // dO slice       [i][v]
+    __shared__ __attribute__((aligned(16))) T dOg[BF ? NB : 1][BF ? C * LDS_ : 1];   // scale gamma_i dO (bf16: a tile of its own)
     __shared__ __attribute__((aligned(16))) T dSb[VS * LDK];        // dS' in the I/O type [v][kf]
     __shared__ __attribute__((aligned(16))) T dEt[VS * LDC];        // dE^T [v][i]
     __shared__ float gCs[NB];
+    __shared__ float sgam[NB][C];                                   // scale gamma_i
 
     int chain, slice;
     chain_slice_of(blockIdx.x, a.V / VS, (a.seq_chunks ? a.n_seqs : a.B) * a.H, chain, slice);
@@ -177,7 +109,8 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
                 else dSt[vt][q] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
     }
-    u32x4 kreg[NWV], wreg[NWV], qreg[NWV], oreg[NUV], ereg[NUV];
+    u32x4 kreg[NWV], wreg[NWV], qreg[NWV];          // loaders
+    u32x4 preg[NPV], oreg[NUV];                     // compute wavefronts
     float greg = 0.f;
 #define OSDN_BC_LOAD(n_)                                                                         \
     {                                                                                            \
@@ -185,19 +118,12 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         const size_t tok_ = ((size_t)bt * a.T + (size_t)(n_) * C) * a.H + h;                     \
         const T *kg = static_cast<const T *>(a.Ktr) + bhn_ * K * C;                              \
         const T *wg = static_cast<const T *>(a.Wt) + bhn_ * K * C;                               \
-        const T *qg = static_cast<const T *>(a.Qt) + bhn_ * K * C;                               \
-        const T *og = static_cast<const T *>(a.dOt) + (bhn_ * a.V + vs) * C;                     \
-        const T *eg = static_cast<const T *>(a.dElt) + (bhn_ * a.V + vs) * C;                    \
+        const T *qg = static_cast<const T *>(a.q) + tok_ * K;                                    \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
             const int i = lti + m * LTN;                                                          \
             kreg[m] = *reinterpret_cast<const u32x4 *>(kg + (size_t)i * VN);                     \
             wreg[m] = *reinterpret_cast<const u32x4 *>(wg + (size_t)i * VN);                     \
-            qreg[m] = *reinterpret_cast<const u32x4 *>(qg + (size_t)i * VN);                     \
-        }                                                                                        \
-        _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
-            const int i = lti + m * LTN;                                                          \
-            oreg[m] = *reinterpret_cast<const u32x4 *>(og + (size_t)i * VN);                     \
-            ereg[m] = *reinterpret_cast<const u32x4 *>(eg + (size_t)i * VN);                     \
+            qreg[m] = *tile_vec(qg, tstride * K, i / (K / VN), (i % (K / VN)) * VN);             \
         }                                                                                        \
         greg = a.log_alpha ? a.log_alpha[tok_ + (size_t)lane * tstride] : 0.f;                   \
     }
@@ -205,20 +131,51 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     {                                                                                            \
         const float G_ = wave_cumsum(greg, lane);                                                \
         const float GC_ = __shfl(G_, 63, 64);                                                    \
+        const float sg_ = a.scale * __expf(G_);              /* scale gamma of token `lane` */   \
         _Pragma("unroll") for (int m = 0; m < NWV; ++m) {                                        \
             const int i = lti + m * LTN;                                                          \
             { const int r = i / (C / VN), c = (i % (C / VN)) * VN;                               \
               *reinterpret_cast<u32x4 *>(&Krt[buf_][r * LDC + c]) = kreg[m];                     \
-              *reinterpret_cast<u32x4 *>(&Wtt[buf_][r * LDC + c]) = wreg[m];                     \
-              *reinterpret_cast<u32x4 *>(&Qtt[buf_][r * LDC + c]) = qreg[m]; }                   \
+              *reinterpret_cast<u32x4 *>(&Wtt[buf_][r * LDC + c]) = wreg[m]; }                   \
+            { const int r = i / (K / VN), c = (i % (K / VN)) * VN;                               \
+              *reinterpret_cast<u32x4 *>(&Qn[buf_][r * LDK + c]) = qreg[m]; }                    \
+        }                                                                                        \
+        if (lti < C) sgam[buf_][lti] = sg_;              /* (the first wave of the group: lane = lti) */ \
+        if (lti == 0) gCs[buf_] = __expf(GC_);                                                   \
+    }
+    // the compute wavefronts' own operands: P and the slice of dO of chunk n_ into registers, and
+    // from there into the LDS buffer of that chunk (bf16: also dO with its rows scaled by scale gamma)
+#define OSDN_BC_CLOAD(n_)                                                                        \
+    {                                                                                            \
+        const size_t bhn_ = bth * a.N + (n_);                                                    \
+        const size_t tok_ = ((size_t)bt * a.T + (size_t)(n_) * C) * a.H + h;                     \
+        const T *pg = static_cast<const T *>(a.Pm) + bhn_ * C * C;                               \
+        const T *og = static_cast<const T *>(a.dO) + tok_ * a.V + vs;                            \
+        _Pragma("unroll") for (int m = 0; m < NPV; ++m)                                          \
+            preg[m] = *reinterpret_cast<const u32x4 *>(pg + (size_t)(tid + m * NCW) * VN);       \
+        _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
+            const int i = tid + m * NCW;                                                          \
+            oreg[m] = *tile_vec(og, tstride * a.V, i / (VS / VN), (i % (VS / VN)) * VN);         \
+        }                                                                                        \
+    }
+#define OSDN_BC_CSTORE(buf_)                                                                     \
+    {                                                                                            \
+        _Pragma("unroll") for (int m = 0; m < NPV; ++m) {                                        \
+            const int i = tid + m * NCW, r = i / (C / VN), c = (i % (C / VN)) * VN;               \
+            *reinterpret_cast<u32x4 *>(&Pn[buf_][r * LDC + c]) = preg[m];                        \
         }                                                                                        \
         _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
-            const int i = lti + m * LTN, r = i / (C / VN), c = (i % (C / VN)) * VN;               \
-            *reinterpret_cast<u32x4 *>(&dOts[buf_][r * LDC + c]) = oreg[m];                      \
-            *reinterpret_cast<u32x4 *>(&dEls[buf_][r * LDC + c]) = ereg[m];                      \
+            const int i = tid + m * NCW, r = i / (VS / VN), c = (i % (VS / VN)) * VN;             \
+            *reinterpret_cast<u32x4 *>(&dOn[buf_][r * LDS_ + c]) = oreg[m];                      \
+            if (BF) {                                                                            \
+                const float f_ = sgam[buf_][r];                                                  \
+                float o_[VN];                                                                    \
+                _Pragma("unroll") for (int e = 0; e < VN; ++e) o_[e] = f_ * vec_get<T>(oreg[m], e); \
+                store_vec_t(&dOg[BF ? buf_ : 0][BF ? r * LDS_ + c : 0], o_);                     \
+            }                                                                                    \
         }                                                                                        \
-        if (lti == 0) gCs[buf_] = __expf(GC_);                                                 \
     }
+    if (!loader) OSDN_BC_CLOAD(a.n1 - 1)
     if (loader) {
         if (NB == 2) {
             if (lgrp == ((a.n1 - 1) & 1)) {
@@ -233,6 +190,12 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
             OSDN_BC_STORE(0)
             OSDN_BC_LOAD(max(a.n1 - 2, a.n0))
         }
+    }
+
+    __syncthreads();                    // (scale gamma of the first chunk is in LDS)
+    if (!loader) {
+        OSDN_BC_CSTORE(NB == 2 ? (a.n1 - 1) & 1 : 0)
+        OSDN_BC_CLOAD(max(a.n1 - 2, a.n0))
     }
 
     for (int n = a.n1 - 1; n >= a.n0; --n) {
@@ -268,13 +231,15 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
                 store_tile_global(static_cast<T *>(a.dS_ckpt) + (bhn * a.V + vs) * K, (size_t)K, dSb, LDK, VS, K, lt, CL_);
             }
         } else {
-            // ---- phase B: dE = dEl + (rho . K~) dS'^T (rows 16*wave ..), kept transposed ----
+            // ---- phase B: dE = scale P^T dO + (rho . K~) dS'^T (rows 16*wave ..), kept transposed ----
+            const int k0 = (wave * 16) / KS * KS;                   // P[i'][i] = 0 for i' < i
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt) {
                 f32x4 acc = mma_tile0<T, false, true>(&Krt[buf][wave * 16], LDC, dSb + vt * 16 * LDK, LDK, K, lane);
-                const T *ep = &dEls[buf][(vt * 16 + acc_col(lane)) * LDC + wave * 16 + acc_row(lane, 0)];
+                const f32x4 loc = mma_tile0<T, false, false>(&Pn[buf][k0 * LDC + wave * 16], LDC,
+                                                             &dOn[buf][k0 * LDS_ + vt * 16], LDS_, C - k0, lane);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[r] += to_f32(ep[r]);
+                for (int r = 0; r < 4; ++r) acc[r] = __builtin_fmaf(a.scale, loc[r], acc[r]);
                 store_tile_t(dEt + vt * 16 * LDC + wave * 16, LDC, acc, lane);
             }
         }
@@ -287,7 +252,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
                 store_tile_global(static_cast<T *>(a.dEt) + (bhn * a.V + vs) * C, (size_t)C, dEt, LDC, VS, C, lt, CL_);
             }
         } else {
-            // ---- phase C: dS <- gamma_C dS' + scale dO^T (gamma . Q) - dE^T W, transposed ----
+            // ---- phase C: dS <- gamma_C dS' + (scale gamma . dO)^T Q - dE^T W, transposed ----
             const float gC = gCs[buf];
 #pragma unroll
             for (int vt = 0; vt < 2; ++vt)
@@ -296,15 +261,31 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) dSt[vt][q][r] *= GV ? gch[GV ? q : 0][r] : gC;
                     const int ct = (wave * NKT + q) * 16;
-                    mma_tile<T, true, true>(dSt[vt][q], &Qtt[buf][ct * LDC], LDC, &dOts[buf][vt * 16 * LDC], LDC, C, lane);
+                    if (BF) {
+                        mma_tile<T, false, false>(dSt[vt][q], &Qn[buf][ct], LDK, &dOg[BF ? buf : 0][BF ? vt * 16 : 0], LDS_, C, lane);
+                    } else {
+                        // fp32: one value per lane and operand, scaled on the way (no second tile)
+                        for (int kk = 0; kk < C; kk += KS) {
+                            typename Mfma<T>::Frag fa = Mfma<T>::template load<false>(&Qn[buf][kk * LDK + ct], LDK, lane);
+                            typename Mfma<T>::Frag fb = Mfma<T>::template load<false>(&dOn[buf][kk * LDS_ + vt * 16], LDS_, lane);
+                            fb = scale_frag(fb, sgam[buf][kk + (lane >> 4)]);
+                            dSt[vt][q] = Mfma<T>::mma(fa, fb, dSt[vt][q]);
+                        }
+                    }
                     mma_tile<T, true, true>(dSt[vt][q], &Wtt[buf][ct * LDC], LDC, dEt + vt * 16 * LDC, LDC, C, lane);
                 }
         }
-        if (NB == 1) {
-            __syncthreads();
-            if (loader && n > a.n0) {
+        if (NB == 1) __syncthreads();                               // single buffer: everyone is through with it
+        if (n > a.n0) {
+            if (NB == 1 && loader) {
                 OSDN_BC_STORE(0)
                 OSDN_BC_LOAD(max(n - 2, a.n0))
+            }
+            if (!loader) {
+                // the next chunk's small tiles into its buffer (free since barrier 1 of this chunk;
+                // its scale gamma table was written before barrier 2), then the request for the one after
+                OSDN_BC_CSTORE(NB == 2 ? (n - 1) & 1 : 0)
+                OSDN_BC_CLOAD(max(n - 2, a.n0))
             }
         }
     }
@@ -758,21 +739,10 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
 }
 
 // -------------------------------------------------------------- launchers ----
-template <typename T>
-static int launch_local_t(const ChunkArgs &a, hipStream_t st) {
-    dim3 grid(a.n1 - a.n0, a.H, a.B), block(BL_);
-    if (a.K == 64) hipLaunchKernelGGL((bwd_local_kernel<T, 64>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((bwd_local_kernel<T, 128>), grid, block, 0, st, a);
-    else return -1;
-    return 0;
-}
-int launch_bwd_local(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
-    return bf16_io ? launch_local_t<bf16>(a, st) : launch_local_t<float>(a, st);
-}
 template <typename T, bool GV>
 static int launch_chain_t(const ChunkArgs &a, hipStream_t st) {
     dim3 grid((a.V / VS) * a.H * (a.seq_chunks ? a.n_seqs : a.B)), block(CT_);
-    if (GV && !a.gamC) return -1;
+    if ((GV && !a.gamC) || !a.Pm || !a.q || !a.dO) return -1;
     if (a.K == 64) hipLaunchKernelGGL((bwd_chain_kernel<T, 64, GV>), grid, block, 0, st, a);
     else if (a.K == 128) hipLaunchKernelGGL((bwd_chain_kernel<T, 128, GV>), grid, block, 0, st, a);
     else return -1;

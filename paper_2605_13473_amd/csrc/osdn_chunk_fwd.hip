@@ -6,7 +6,8 @@
 //                T = (I + A)^-1 in fp32,  W = T (beta gamma . K),  U = T (beta . V)
 //   state_fwd    (sequential over chunks, parallel over (b, h, slice of V)):
 //                E = U - W S^T ;  S <- gamma_C S + E^T (rho . K~)      (S fp32 in registers)
-//   output_fwd   (parallel over chunks):  O = scale [ gamma . (Q S^T) + tril(Gamma . Q K~^T) E ]
+//   output_fwd   (parallel over chunks):  O = scale [ gamma . (Q S^T) + P E ],  P = tril(Gamma . Q K~^T)
+//                (P is also written out when a backward pass follows)
 //
 // All contractions run on MFMA with fp32 accumulation; operands are staged in LDS in the
 // I/O element type.
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
     //      by beta (for U) and by beta gamma (for W); the upper triangle is exactly zero ----
     {
         constexpr int VN = 16 / sizeof(T);
-        T *tg = static_cast<T *>(a.Tm) + bhn * C * C;
+        T *tg = a.Tm ? static_cast<T *>(a.Tm) + bhn * C * C : nullptr;      // (kept for the backward pass only)
         for (int v = tid; v < C * C / VN; v += CP_) {
             const int i = v / (C / VN), j0 = (v % (C / VN)) * VN;
             float plain[VN], tu[VN], tw[VN];
@@ -209,7 +210,7 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
                 tu[e] = t * Bs[j];
                 tw[e] = t * BGs[j];
             }
-            store_vec_t(tg + i * C + j0, plain);
+            if (tg) store_vec_t(tg + i * C + j0, plain);
             store_vec_t(Tu + i * LDC + j0, tu);
             store_vec_t(Tw + i * LDC + j0, tw);
         }
@@ -503,6 +504,8 @@ __global__ __launch_bounds__(OT_) void output_fwd_kernel(ChunkArgs a) {
     T *Os = Kts;
     for (int v0 = 0; v0 < a.V; v0 += C) {
         __syncthreads();
+        // P is kept for the backward pass (its chain kernel forms scale P^T dO from it)
+        if (v0 == 0 && a.Pm) store_tile_global(static_cast<T *>(a.Pm) + bhn * C * C, (size_t)C, Ps, LDC, C, C, tid, OT_);
         r_S.put(Ss, LDK, tid);
         r_E.put(Ets, LDC, tid);
         if (v0 + C < a.V) {

@@ -111,6 +111,8 @@ struct ChunkArgs {
     void *Ut;                         // [B,H,N,V,64] io   U^T
     void *Et;                         // [B,H,N,V,64] io   E transposed
     void *S_ckpt;                     // [B,H,N,V,K] io    state at the start of each chunk (null: not kept)
+    void *Pm;                         // [B,H,N,64,64] io  P = tril(Gamma . Q K~^T), from output_fwd for the backward
+                                      //                   chain (null: not kept; Tm may be null likewise)
     // one state gate per key channel (gate_vec: log_alpha is [B,T,H,K]; forward only): chunk_prep
     // folds the cumulative channel decays Gamma into the operands and leaves
     int gate_vec;
@@ -122,9 +124,6 @@ struct ChunkArgs {
     // backward
     const void *dO;                   // [B,T,H,V] io
     const float *dS_out;              // [B,H,V,K] or null
-    void *dElt;                       // [B,H,N,V,64] io   local part of dE, transposed: (scale P^T dO)^T
-    void *Qt;                         // [B,H,N,K,64] io   (scale gamma . Q)^T
-    void *dOt;                        // [B,H,N,V,64] io   dO^T
     void *dEt;                        // [B,H,N,V,64] io   dE transposed (complete)
     void *dS_ckpt;                    // [B,H,N,V,K] io    adjoint of the state at the END of each chunk
     float *dS_in;                     // [B,H,V,K]
@@ -147,7 +146,6 @@ int launch_precond_post(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_chunk_prep(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 int launch_state_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 int launch_output_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st);
-int launch_bwd_local(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 int launch_bwd_post(const ChunkArgs &a, bool bf16_io, hipStream_t st);
 
