@@ -81,6 +81,9 @@ def kernel_models(cfg, es):
     m["precond_mask"] = ("hbm", th * (K * es + g) + nch * K * 8)
     m["precond_chain"] = ("hbm", th * (2 * K * es + 2 * g) + nch * K * (8 + 4))
     m["precond_post"] = ("hbm", th * (4 * K * es + 6 * g) + nch * K * 8)
+    # solved form of the reverse sweep (only without retention): read k twice and dk~; write the
+    # 64 x 64 fp32 inverse, rho0 and the chunk's sum of lambda per chunk
+    m["precond_lin"] = ("hbm", th * 3 * K * es + nch * (C * C * 4 + C * 4 + K * 4 + K * 8))
     # chunk_prep: read k, k~, v, beta, g ; write T, -W^T, (rho k~)^T, U^T
     m["chunk_prep"] = ("hbm", th * (4 * K * es + 2 * V * es + C * es + 2 * g))
     # state_fwd: read -W^T, (rho k~)^T, U^T ; write E^T, S checkpoints ; 2 KV-class GEMMs

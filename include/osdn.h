@@ -157,6 +157,9 @@ int osdn_step(const osdn_params *p, const void *q, const void *k, const void *v,
  *   S_out     [B,H,V,K] fp32      out: state after the last token
  *   d_out     [B,H,K]   fp32      out
  *   workspace: scratch; when osdn_bwd follows, pass the same buffer, untouched, to it.
+ *     What only a backward pass reads (the chunks' (I + A)^-1 and intra-chunk scores) is written
+ *     iff workspace_bytes >= osdn_workspace_bytes(p, 1); osdn_bwd rejects a smaller workspace, so a
+ *     forward call that is to be followed by osdn_bwd must already be given the larger size.
  */
 int osdn_fwd(const osdn_params *p, const void *q, const void *k, const void *v, const float *beta,
              const float *log_alpha, const float *retention, const float *d_in, const float *S_in,
