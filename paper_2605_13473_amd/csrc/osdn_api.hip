@@ -555,6 +555,10 @@ static int fwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     if (!pl) S = 1;
     // chain workgroups of both phases (32 rows of the state per workgroup in state_fwd) against the CUs
     const bool crowded = chains * (p->V / 32) + chains > NUM_CU;
+    // Few chains: the state kernel takes slices of 16 values instead of 32 when its workgroups then
+    // still find a CU each (beside those of phase 1, unless phase 1 runs ahead as sweeps over pieces):
+    // its time per chunk is latency, not work, and half the work per workgroup shortens it.
+    c.narrow_slices = cg.narrow_slices = chains * (p->V / 16) + (pieces ? 0 : chains) <= NUM_CU;
     auto seg_range = [&](int sidx, int &n0, int &n1) {
         if (crowded) { n0 = seg_begin_grow(N, S, sidx, 1.7); n1 = seg_begin_grow(N, S, sidx + 1, 1.7); return; }
         n0 = seg_begin(N, S, sidx); n1 = seg_begin(N, S, sidx + 1);
@@ -741,6 +745,9 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     const int N = p->T / C;
     const long long chains = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
     int S = segment_count(p->segments, N, pk.longest, chains * (p->V / 32) + chains, true, chains);   // chain kernel: 32 rows of the state per workgroup
+    // (the backward chain keeps slices of 32 values: with 16 the kernel itself is a fifth faster on
+    // few chains, but its workgroups then hold twice the CUs and what they take from the phase-1
+    // chain beside them, which bounds the pass there, costs more)
     Pipeline *pl = S > 1 ? pipeline_for(st) : nullptr;
     if (!pl) S = 1;
     auto seg_range = [&](int sidx, int &n0, int &n1) { n0 = seg_begin(N, S, sidx); n1 = seg_begin(N, S, sidx + 1); };

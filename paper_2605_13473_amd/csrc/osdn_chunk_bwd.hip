@@ -26,7 +26,6 @@
 
 namespace osdn {
 
-constexpr int VS = 32;      // rows of S owned by one workgroup of the chain kernel
 
 // sum over the 16 lanes of a DPP row (lanes sharing lane>>4), returned to all of them
 __device__ __forceinline__ float row16_sum(float x) {
@@ -54,8 +53,11 @@ __device__ __forceinline__ bf16x8 scale_frag(bf16x8 f, float) { return f; }
 constexpr int CT_ = 512, CL_ = 256;
 
 // GV: one state gate per key channel (the chunk's decay per channel comes from chunk_prep).
-template <typename T, int K, bool GV>
+// VS: rows of S (values) owned by one workgroup, 32 or 16 (the narrow slice when the chains are few:
+// twice the workgroups, each with half the work on the dependent path per chunk).
+template <typename T, int K, bool GV, int VS>
 __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
+    constexpr int NVT = VS / 16;                    // value tiles per compute wave
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD, LDS_ = VS + PAD;
     constexpr int VN = 16 / sizeof(T);
     constexpr int NKT = K / 64;
@@ -66,8 +68,9 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     constexpr int NWV = C * K / VN / LTN;           // vectors per loader thread: a [64 x K] or [K x 64] tile
     constexpr int NCW = CT_ - CL_;                  // compute threads
     constexpr int NPV = C * C / VN / NCW;           // vectors per compute thread: the [64 x 64] tile P
-    constexpr int NUV = C * VS / VN / NCW;          // ... the [64 x VS] slice of dO
-    static_assert(C * K / VN % LTN == 0 && C * VS / VN % NCW == 0 && C * C / VN % NCW == 0, "tiles must split evenly");
+    constexpr int NOV = C * VS / VN;                // vectors of the [64 x VS] slice of dO
+    constexpr int NUV = (NOV + NCW - 1) / NCW;      // ... per compute thread (NOV < NCW: the upper threads repeat the lower ones' vectors)
+    static_assert(C * K / VN % LTN == 0 && (NOV % NCW == 0 || NCW % NOV == 0) && C * C / VN % NCW == 0, "tiles must split evenly");
     __shared__ __attribute__((aligned(16))) T Krt[NB][K * LDC];     // (rho . K~)^T   [kf][i], as chunk_prep left it
     __shared__ __attribute__((aligned(16))) T Wtt[NB][K * LDC];     // -W^T           [kf][i]
     __shared__ __attribute__((aligned(16))) T Qn[NB][C * LDK];      // q              [i][kf]
@@ -98,10 +101,10 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     const size_t bth = (size_t)bt * a.H + h;    // indexes the per-chunk buffers
     const size_t tstride = a.H;
 
-    f32x4 dSt[2][NKT];                  // rows = features, cols = values
+    f32x4 dSt[NVT][NKT];                  // rows = features, cols = values
     if (!loader) {
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
+        for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
             for (int q = 0; q < NKT; ++q) {
                 const int v = vs + vt * 16 + acc_col(lane), c0 = (wave * NKT + q) * 16 + acc_row(lane, 0);
@@ -154,7 +157,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         _Pragma("unroll") for (int m = 0; m < NPV; ++m)                                          \
             preg[m] = *reinterpret_cast<const u32x4 *>(pg + (size_t)(tid + m * NCW) * VN);       \
         _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
-            const int i = tid + m * NCW;                                                          \
+            const int i = (tid + m * NCW) % NOV;                                                  \
             oreg[m] = *tile_vec(og, tstride * a.V, i / (VS / VN), (i % (VS / VN)) * VN);         \
         }                                                                                        \
     }
@@ -165,7 +168,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
             *reinterpret_cast<u32x4 *>(&Pn[buf_][r * LDC + c]) = preg[m];                        \
         }                                                                                        \
         _Pragma("unroll") for (int m = 0; m < NUV; ++m) {                                        \
-            const int i = tid + m * NCW, r = i / (VS / VN), c = (i % (VS / VN)) * VN;             \
+            const int i = (tid + m * NCW) % NOV, r = i / (VS / VN), c = (i % (VS / VN)) * VN;     \
             *reinterpret_cast<u32x4 *>(&dOn[buf_][r * LDS_ + c]) = oreg[m];                      \
             if (BF) {                                                                            \
                 const float f_ = sgam[buf_][r];                                                  \
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
         f32x4 gch[GV ? NKT : 1];                                    // channel decays of this lane's state rows
         if (!loader) {
 #pragma unroll
-            for (int vt = 0; vt < 2; ++vt)
+            for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
                 for (int q = 0; q < NKT; ++q)
                     store_tile_t(dSb + vt * 16 * LDK + (wave * NKT + q) * 16, LDK, dSt[vt][q], lane);
@@ -234,7 +237,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
             // ---- phase B: dE = scale P^T dO + (rho . K~) dS'^T (rows 16*wave ..), kept transposed ----
             const int k0 = (wave * 16) / KS * KS;                   // P[i'][i] = 0 for i' < i
 #pragma unroll
-            for (int vt = 0; vt < 2; ++vt) {
+            for (int vt = 0; vt < NVT; ++vt) {
                 f32x4 acc = mma_tile0<T, false, true>(&Krt[buf][wave * 16], LDC, dSb + vt * 16 * LDK, LDK, K, lane);
                 const f32x4 loc = mma_tile0<T, false, false>(&Pn[buf][k0 * LDC + wave * 16], LDC,
                                                              &dOn[buf][k0 * LDS_ + vt * 16], LDS_, C - k0, lane);
@@ -255,7 +258,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
             // ---- phase C: dS <- gamma_C dS' + (scale gamma . dO)^T Q - dE^T W, transposed ----
             const float gC = gCs[buf];
 #pragma unroll
-            for (int vt = 0; vt < 2; ++vt)
+            for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
                 for (int q = 0; q < NKT; ++q) {
 #pragma unroll
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(CT_) void bwd_chain_kernel(ChunkArgs a) {
     }
     if (!loader) {
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
+        for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
             for (int q = 0; q < NKT; ++q) {
                 const int v = vs + vt * 16 + acc_col(lane), c0 = (wave * NKT + q) * 16 + acc_row(lane, 0);
@@ -739,18 +742,23 @@ __global__ __launch_bounds__(PW_ * 64) void bwd_post_kernel(ChunkArgs a) {
 }
 
 // -------------------------------------------------------------- launchers ----
-template <typename T, bool GV>
+template <typename T, bool GV, int VS>
 static int launch_chain_t(const ChunkArgs &a, hipStream_t st) {
     dim3 grid((a.V / VS) * a.H * (a.seq_chunks ? a.n_seqs : a.B)), block(CT_);
     if ((GV && !a.gamC) || !a.Pm || !a.q || !a.dO) return -1;
-    if (a.K == 64) hipLaunchKernelGGL((bwd_chain_kernel<T, 64, GV>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((bwd_chain_kernel<T, 128, GV>), grid, block, 0, st, a);
+    if (a.K == 64) hipLaunchKernelGGL((bwd_chain_kernel<T, 64, GV, VS>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((bwd_chain_kernel<T, 128, GV, VS>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
+// Slices of 16 values when the caller asks for them (few chains: see ChunkArgs::narrow_slices).
+template <typename T, bool GV>
+static int launch_chain_v(const ChunkArgs &a, hipStream_t st) {
+    return a.narrow_slices ? launch_chain_t<T, GV, 16>(a, st) : launch_chain_t<T, GV, 32>(a, st);
+}
 int launch_bwd_chain(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
-    if (a.gate_vec) return bf16_io ? launch_chain_t<bf16, true>(a, st) : launch_chain_t<float, true>(a, st);
-    return bf16_io ? launch_chain_t<bf16, false>(a, st) : launch_chain_t<float, false>(a, st);
+    if (a.gate_vec) return bf16_io ? launch_chain_v<bf16, true>(a, st) : launch_chain_v<float, true>(a, st);
+    return bf16_io ? launch_chain_v<bf16, false>(a, st) : launch_chain_v<float, false>(a, st);
 }
 constexpr int BP_MIN_WGS = 2048;
 template <typename T, bool GV>

@@ -261,13 +261,15 @@ __global__ __launch_bounds__(CP_) void chunk_prep_kernel(ChunkArgs a) {
 // LDS with vector stores.  Wavefronts 4-7 only move data: they bring the next chunk's W,
 // (rho . K~)^T and U^T tiles (already in operand layout) into the other LDS buffer and write
 // the state checkpoint and E^T back, off the chain.  Two barriers per chunk.
-constexpr int VS = 32;          // rows of S (values) owned by one workgroup
 constexpr int CT_ = 512;        // threads of a chain workgroup
 constexpr int CL_ = 256;        // ... of which loaders
 
 // GV: one state gate per key channel; the chunk's decay per channel comes from chunk_prep.
-template <typename T, int K, bool GV>
+// VS: rows of S (values) owned by one workgroup, 32 or 16.  With few chains the narrow slice
+// gives twice the workgroups, each with half the work on the dependent path per chunk.
+template <typename T, int K, bool GV, int VS>
 __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
+    constexpr int NVT = VS / 16;                // value tiles per compute wave
     constexpr int PAD = Pad<T>::v, LDK = K + PAD, LDC = C + PAD;
     constexpr int VN = 16 / sizeof(T);
     constexpr int NKT = K / 64;                 // state row tiles (features) per compute wave
@@ -307,10 +309,10 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     const size_t tstride = a.H;
 
     // ---- compute waves: state slice, transposed: St[vt][q] rows = features, cols = values ----
-    f32x4 St[2][NKT];
+    f32x4 St[NVT][NKT];
     if (!loader) {
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
+        for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
             for (int q = 0; q < NKT; ++q) {
                 const int v = vs + vt * 16 + acc_col(lane), c0 = (wave * NKT + q) * 16 + acc_row(lane, 0);
@@ -379,7 +381,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
         f32x4 gch[GV ? NKT : 1];                                    // channel decays of this lane's state rows
         if (!loader) {
 #pragma unroll
-            for (int vt = 0; vt < 2; ++vt)
+            for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
                 for (int q = 0; q < NKT; ++q)
                     store_tile_t(Sb + vt * 16 * LDK + (wave * NKT + q) * 16, LDK, St[vt][q], lane);
@@ -408,7 +410,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
         } else {
             // ---- phase B: E = U - W S^T (rows 16*wave ..), kept transposed ----
 #pragma unroll
-            for (int vt = 0; vt < 2; ++vt) {
+            for (int vt = 0; vt < NVT; ++vt) {
                 f32x4 acc = mma_tile0<T, false, true>(&Wts[buf][wave * 16], LDC, Sb + vt * 16 * LDK, LDK, K, lane);
                 const T *up = &Uts[buf][(vt * 16 + acc_col(lane)) * LDC + wave * 16 + acc_row(lane, 0)];
 #pragma unroll
@@ -428,7 +430,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
             // ---- phase C: S <- gamma_C S + E^T (rho . K~), transposed ----
             const float gC = gCs[buf];
 #pragma unroll
-            for (int vt = 0; vt < 2; ++vt)
+            for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
                 for (int q = 0; q < NKT; ++q) {
 #pragma unroll
@@ -447,7 +449,7 @@ __global__ __launch_bounds__(CT_) void state_fwd_kernel(ChunkArgs a) {
     }
     if (!loader) {
 #pragma unroll
-        for (int vt = 0; vt < 2; ++vt)
+        for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
             for (int q = 0; q < NKT; ++q) {
                 const int v = vs + vt * 16 + acc_col(lane), c0 = (wave * NKT + q) * 16 + acc_row(lane, 0);
@@ -547,18 +549,23 @@ int launch_chunk_prep(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
     if (a.gate_vec) return bf16_io ? launch_prep_t<bf16, true>(a, st) : launch_prep_t<float, true>(a, st);
     return bf16_io ? launch_prep_t<bf16, false>(a, st) : launch_prep_t<float, false>(a, st);
 }
-template <typename T, bool GV>
+template <typename T, bool GV, int VS>
 static int launch_state_t(const ChunkArgs &a, hipStream_t st) {
     dim3 grid((a.V / VS) * a.H * (a.seq_chunks ? a.n_seqs : a.B)), block(CT_);
     if (GV && !a.gamC) return -1;
-    if (a.K == 64) hipLaunchKernelGGL((state_fwd_kernel<T, 64, GV>), grid, block, 0, st, a);
-    else if (a.K == 128) hipLaunchKernelGGL((state_fwd_kernel<T, 128, GV>), grid, block, 0, st, a);
+    if (a.K == 64) hipLaunchKernelGGL((state_fwd_kernel<T, 64, GV, VS>), grid, block, 0, st, a);
+    else if (a.K == 128) hipLaunchKernelGGL((state_fwd_kernel<T, 128, GV, VS>), grid, block, 0, st, a);
     else return -1;
     return 0;
 }
+// Slices of 16 values when the caller asks for them (few chains: see ChunkArgs::narrow_slices).
+template <typename T, bool GV>
+static int launch_state_v(const ChunkArgs &a, hipStream_t st) {
+    return a.narrow_slices ? launch_state_t<T, GV, 16>(a, st) : launch_state_t<T, GV, 32>(a, st);
+}
 int launch_state_fwd(const ChunkArgs &a, bool bf16_io, hipStream_t st) {
-    if (a.gate_vec) return bf16_io ? launch_state_t<bf16, true>(a, st) : launch_state_t<float, true>(a, st);
-    return bf16_io ? launch_state_t<bf16, false>(a, st) : launch_state_t<float, false>(a, st);
+    if (a.gate_vec) return bf16_io ? launch_state_v<bf16, true>(a, st) : launch_state_v<float, true>(a, st);
+    return bf16_io ? launch_state_v<bf16, false>(a, st) : launch_state_v<float, false>(a, st);
 }
 template <typename T>
 static int launch_output_t(const ChunkArgs &a, hipStream_t st) {

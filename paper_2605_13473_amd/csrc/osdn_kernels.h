@@ -113,6 +113,7 @@ struct ChunkArgs {
     void *S_ckpt;                     // [B,H,N,V,K] io    state at the start of each chunk (null: not kept)
     void *Pm;                         // [B,H,N,64,64] io  P = tril(Gamma . Q K~^T), from output_fwd for the backward
                                       //                   chain (null: not kept; Tm may be null likewise)
+    int narrow_slices;                // chain kernels: 16 rows of the state per workgroup instead of 32
     // one state gate per key channel (gate_vec: log_alpha is [B,T,H,K]; forward only): chunk_prep
     // folds the cumulative channel decays Gamma into the operands and leaves
     int gate_vec;
