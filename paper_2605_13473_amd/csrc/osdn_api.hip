@@ -166,7 +166,7 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     L.masks = take(B * H * N * K * 8);
     L.a_ckpt = take(B * H * N * K * 4);
     L.lin_clean = take(B * H * N * 4);
-    L.lin_M = take(B * H * N * C * C * 4);
+    L.lin_M = take(B * H * N * C * C * es);
     L.lin_r0 = take(B * H * N * C * 4);
     L.lin_t0 = take(B * H * N * K * 4);
     if (p->gate_per_channel) L.dgamC = take(B * H * N * K * 4);
@@ -219,7 +219,7 @@ ChunkArgs chunk_args(const osdn_params *p, const Layout &L, char *ws) {      // 
 constexpr int MAX_SEGMENTS = 16;
 struct Pipeline {
     hipStream_t side = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr, a[MAX_SEGMENTS] = {};
+    hipEvent_t fork = nullptr, join = nullptr, early[2] = {}, a[MAX_SEGMENTS] = {};
     bool ok = false;
 };
 std::mutex g_pipe_mu;
@@ -241,6 +241,7 @@ Pipeline *pipeline_for(hipStream_t caller) {
         bool ok = hipStreamCreateWithFlags(&pl.side, hipStreamNonBlocking) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&pl.fork, hipEventDisableTiming) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&pl.join, hipEventDisableTiming) == hipSuccess;
+        for (int i = 0; ok && i < 2; ++i) ok = hipEventCreateWithFlags(&pl.early[i], hipEventDisableTiming) == hipSuccess;
         for (int i = 0; ok && i < MAX_SEGMENTS; ++i)
             ok = hipEventCreateWithFlags(&pl.a[i], hipEventDisableTiming) == hipSuccess;
         pl.ok = ok;
@@ -730,14 +731,15 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     pb.n_seqs = pk.n_seqs; pb.seq_chunks = seq_chunks; pb.dd_last = dd_out;
     pb.dk = dk; pb.dbeta = dbeta; pb.dretention = retention ? dretention : nullptr; pb.dd_in = dd_in;
     // Without retention, chunks that never met the box can take the solved form of the reverse
-    // sweep: a shorter dependent chain for about 0.9 KB more memory traffic per token-head.  It
-    // pays when the chains are few (the chain is then what the chip waits for); with chains on
-    // more than an eighth of the CUs the pass is bound by its memory traffic and the sweeps stay.
+    // sweep: a dependent chain less than half as long for about 0.6 KB more memory traffic per
+    // token-head.  It pays while the phase-1 chain is what the pass waits for: chains on at most a
+    // quarter of the CUs (measured at 64 chains: 3 % of forward + backward; with more chains the
+    // chains fill the chip by themselves and the pass is bound by its memory traffic).
     const long long chains_all = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
-    const bool solved = !retention && (p->p1_solved > 0 || (p->p1_solved == 0 && chains_all * 8 <= NUM_CU));
+    const bool solved = !retention && (p->p1_solved > 0 || (p->p1_solved == 0 && chains_all * 4 <= NUM_CU));
     if (solved) {
         pb.lin_clean = reinterpret_cast<int *>(ws + L.lin_clean);
-        pb.lin_M = reinterpret_cast<float *>(ws + L.lin_M);
+        pb.lin_M = ws + L.lin_M;
         pb.lin_r0 = reinterpret_cast<float *>(ws + L.lin_r0);
         pb.lin_t0 = reinterpret_cast<float *>(ws + L.lin_t0);
     }
@@ -762,42 +764,69 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
         return timed(KID_UNFOLD, st, [&] { return launch_unfold(un, bf, st); });
     };
     // the box masks depend on the forward pass only: one launch for the whole sequence, up front
-    // (and with them which chunks take the solved form, and their inverses)
     auto masks = [&](hipStream_t s1) {
         pb.n0 = 0; pb.n1 = N;
-        if (pb.d_min <= pb.d_max && timed(KID_PRECOND_MASK, s1, [&] { return launch_precond_mask(pb, bf, s1); }) != 0)
-            return -1;
-        if (pb.lin_clean && timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, true, s1); }) != 0)
-            return -1;
-        return 0;
+        if (pb.d_min > pb.d_max) return 0;
+        return timed(KID_PRECOND_MASK, s1, [&] { return launch_precond_mask(pb, bf, s1); });
+    };
+    // solved form: which of the chunks [n0, n1) take it, and their inverses (forward data and the masks only)
+    auto lin_m = [&](int n0, int n1, hipStream_t s1) {
+        if (!pb.lin_clean) return 0;
+        pb.n0 = n0; pb.n1 = n1;
+        return timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, true, s1); });
+    };
+    // solved form: what its chunks need from dk~ (rho0, the sums of lambda)
+    auto lin_r = [&](int sidx, hipStream_t s1) {
+        if (!pb.lin_clean) return 0;
+        seg_range(sidx, pb.n0, pb.n1);
+        return timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, false, s1); });
     };
     auto phase1 = [&](int sidx, hipStream_t s1) {
         seg_range(sidx, pb.n0, pb.n1);
         pb.dd_out = sidx == S - 1 ? dd_out : dd_in;  // the adjoint of d is carried in dd_in
-        if (pb.lin_clean && timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, false, s1); }) != 0) return -1;
         if (timed(KID_PRECOND_CHAIN, s1, [&] { return launch_precond_chain(pb, bf, s1); }) != 0) return -1;
         return timed(KID_PRECOND_POST, s1, [&] { return launch_precond_post(pb, bf, s1); });
     };
     if (!pl) {
         if (phase2(KID_BWD_CHAIN, 0) != 0 || phase2(KID_BWD_POST, 0) != 0 ||
-            masks(st) != 0 || phase1(0, st) != 0)
+            masks(st) != 0 || lin_m(0, N, st) != 0 || lin_r(0, st) != 0 || phase1(0, st) != 0)
             return OSDN_ERR_SHAPE;
         return finish();
     }
     // main: phase 2, segments right to left          (a[s]: phase 2 of segment s done)
     // side: the masks at once, then phase 1 of segment s once a[s] has fired; joined back at the end
+    // The small kernels of the solved form go where they find CUs: when the workgroups of bwd_chain
+    // fill the chip (they share a CU with nothing), a kernel on the side stream that becomes ready
+    // while bwd_chain runs waits until that is through, and the phase-1 chain behind it waits too.
+    // Then the inverses of the first segment are built on the side stream at once (beside
+    // bwd_post), and everything else runs on the caller's stream behind the segment's bwd_post,
+    // where the phase-1 chain of the segment before covers it.
+    const bool lin_on_main = pb.lin_clean && chains * (p->V / 32) + chains > NUM_CU;
     hipStream_t s1 = pl->side;
     OSDN_HIP_OK(hipEventRecord(pl->fork, st));
     OSDN_HIP_OK(hipStreamWaitEvent(s1, pl->fork, 0));
     SideJoin rejoin{pl, st, true};
     if (masks(s1) != 0) return OSDN_ERR_SHAPE;
+    if (lin_on_main) {
+        OSDN_HIP_OK(hipEventRecord(pl->early[0], s1));               // the masks are there
+        if (lin_m(seg_begin(N, S, S - 1), N, s1) != 0) return OSDN_ERR_SHAPE;
+        OSDN_HIP_OK(hipEventRecord(pl->early[1], s1));               // ... and the first segment's inverses
+    } else if (lin_m(0, N, s1) != 0) {
+        return OSDN_ERR_SHAPE;
+    }
     for (int s = S - 1; s >= 0; --s) {
         if (phase2(KID_BWD_CHAIN, s) != 0 || phase2(KID_BWD_POST, s) != 0)
             return OSDN_ERR_SHAPE;
+        if (lin_on_main) {
+            OSDN_HIP_OK(hipStreamWaitEvent(st, pl->early[s == S - 1 ? 1 : 0], 0));
+            if (s < S - 1 && lin_m(seg_begin(N, S, s), seg_begin(N, S, s + 1), st) != 0) return OSDN_ERR_SHAPE;
+            if (lin_r(s, st) != 0) return OSDN_ERR_SHAPE;
+        }
         OSDN_HIP_OK(hipEventRecord(pl->a[s], st));
     }
     for (int s = S - 1; s >= 0; --s) {
         OSDN_HIP_OK(hipStreamWaitEvent(s1, pl->a[s], 0));
+        if (!lin_on_main && lin_r(s, s1) != 0) return OSDN_ERR_SHAPE;
         if (phase1(s, s1) != 0) return OSDN_ERR_SHAPE;
     }
     OSDN_HIP_OK(hipEventRecord(pl->join, s1));

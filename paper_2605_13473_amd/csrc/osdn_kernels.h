@@ -68,7 +68,7 @@ struct PrecondBwdArgs {
     // chunks in solved form (no retention; null: never): per chunk, whether it qualifies (no
     // coordinate met the box), the inverse (I + U)^-1, rho0 and the chunk's sum of lambda
     int *lin_clean;           // [B,H,T/64]
-    float *lin_M;             // [B,H,T/64,64,64]
+    void *lin_M;              // [B,H,T/64,64,64] io
     float *lin_r0;            // [B,H,T/64,64]
     float *lin_t0;            // [B,H,T/64,K]
 };

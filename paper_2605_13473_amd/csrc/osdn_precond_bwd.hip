@@ -150,13 +150,16 @@ __global__ __launch_bounds__(P1T) void precond_lin_m_kernel(PrecondBwdArgs a) {
     __syncthreads();                                             // the s tile is dead: its space takes the inverse
     ut_inverse64<LDF>(Af, Ti, Xs, wave, lane);
     // ---- (I + U)^-1, row i: entries j >= i are column i of the lower inverse ----
+    // (kept in the I/O type: its diagonal is 1 and the rest is of the size of the step, so with
+    // bf16 I/O the rounding is far inside what that I/O type's other operands carry)
     {
-        float *mg = a.lin_M + bhn * C * C + i * C + part * 8;
+        T *mg = static_cast<T *>(a.lin_M) + bhn * C * C + i * C + part * 8;
+        constexpr int VNM = 16 / sizeof(T);
 #pragma unroll
-        for (int e4 = 0; e4 < 8; e4 += 4) {
-            float o[4];
+        for (int e4 = 0; e4 < 8; e4 += VNM) {
+            float o[VNM];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < VNM; ++e) {
                 const int j = part * 8 + e4 + e;
                 o[e] = j >= i ? Ti[j * LDF + i] : 0.f;
             }
@@ -301,7 +304,7 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
     // the inverse, the token's scalars (slice 0 only), the coordinate's sum of lambda (group 0 only).
     struct LinRegs {
         u32x4 kq[NVK];
-        f32x4 mq[2];
+        u32x4 mq[8 * sizeof(T) / 16];
         float rho, nraw, beta, t0;
     };
 #define OSDN_P1_LLOAD(n_, R)                                                                     \
@@ -312,8 +315,8 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         const uint32_t off_ = ((uint32_t)li * kstride + (uint32_t)(lpart * EPT)) * (uint32_t)sizeof(T); \
         const u32x4 *kp_ = reinterpret_cast<const u32x4 *>(static_cast<const T *>(a.k) + tokc_ * K); \
         _Pragma("unroll") for (int m_ = 0; m_ < NVK; ++m_) R.kq[m_] = at_byte(kp_, off_ + 16 * m_); \
-        const f32x4 *mp_ = reinterpret_cast<const f32x4 *>(a.lin_M + bhn_ * C * C + li * C + lpart * 8); \
-        R.mq[0] = mp_[0]; R.mq[1] = mp_[1];                                                      \
+        const u32x4 *mp_ = reinterpret_cast<const u32x4 *>(static_cast<const T *>(a.lin_M) + bhn_ * C * C + li * C + lpart * 8); \
+        _Pragma("unroll") for (int m_ = 0; m_ < (int)(8 * sizeof(T) / 16); ++m_) R.mq[m_] = mp_[m_]; \
         const size_t th = tokc_ + (size_t)li * a.H;      /* (every lane of a token loads its scalars) */ \
         R.nraw = a.tok_scalars[th * 4 + 2];                                                      \
         R.beta = a.beta[th];                                                                     \
@@ -357,7 +360,8 @@ __global__ __launch_bounds__(P1T) void precond_chain_kernel(PrecondBwdArgs a) {
         float sgm = 0.f;                                                                         \
         _Pragma("unroll") for (int h4 = 0; h4 < 2; ++h4) {                                       \
             const f32x4 xv = *reinterpret_cast<const f32x4 *>(xs + lpart * LN::XSTR + 4 * h4);   \
-            _Pragma("unroll") for (int e = 0; e < 4; ++e) sgm = __builtin_fmaf(R.mq[h4][e], xv[e], sgm); \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e)                                        \
+                sgm = __builtin_fmaf(vec_get<T>(R.mq[(4 * h4 + e) / VN], (4 * h4 + e) % VN), xv[e], sgm); \
         }                                                                                        \
         sgm = sum_lanes8(sgm);                                                                   \
         ws[li] = ca_i * sgm;                                                                     \
