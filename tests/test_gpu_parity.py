@@ -19,6 +19,19 @@ def test_config0_tiny_fp32_forward():
     compare_forward(x, ob.Hyper(), bf16=False)
 
 
+@pytest.mark.parametrize("segments", [0, 3, 5])
+def test_solved_form_when_the_chain_kernel_fills_the_chip(segments):
+    """64 chains of 128 values: the workgroups of the backward chain kernel then fill every CU, and
+    the helper kernels of the solved form (flags and inverses, rho0 and the sums of lambda) run on
+    the caller's stream behind each segment's bwd_post, ordered after the first segment's flags
+    by an event; with the library's own segment count and with three and five segments, on an
+    input that mixes chunks that qualify with chunks that met the box."""
+    B, T, H, K, V = 4, 64 * 20, 16, 128, 128
+    x = make_stress_inputs(B, T, H, K, V, seed=121, bf16=True, retention=0.0, d_lo=0.7, d_hi=1.6)
+    hp = ob.Hyper(eta=0.5, p1_solved=1, segments=segments)
+    compare_backward(x, hp, True)
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("shape", [(1, 64, 1, 64, 64), (2, 192, 3, 64, 128), (1, 256, 2, 128, 192),
                                    (3, 128, 1, 128, 64)])
