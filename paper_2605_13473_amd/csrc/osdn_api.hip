@@ -766,7 +766,7 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     // the box masks depend on the forward pass only: one launch for the whole sequence, up front
     auto masks = [&](hipStream_t s1) {
         pb.n0 = 0; pb.n1 = N;
-        if (pb.d_min > pb.d_max) return 0;
+        if (pb.d_min > pb.d_max || pb.lin_clean) return 0;      // (the solved form's first kernel writes them itself)
         return timed(KID_PRECOND_MASK, s1, [&] { return launch_precond_mask(pb, bf, s1); });
     };
     // solved form: which of the chunks [n0, n1) take it, and their inverses (forward data and the masks only)

@@ -73,7 +73,9 @@ __global__ __launch_bounds__(K) void precond_mask_kernel(PrecondBwdArgs a) {
 
 // ----------------------------------------------------------------- precond_lin ----
 // Two kernels, both one workgroup per (chain, chunk).  precond_lin_m needs the forward pass only
-// (keys, step scalars, masks): it decides whether the chunk qualifies and inverts the system.
+// (keys, step scalars, d at the chunk start): it replays d over the chunk for the box masks (what
+// precond_mask does when this form is off: the same arithmetic, from the s tile it builds anyway),
+// decides from them whether the chunk qualifies, and inverts the system.
 // precond_lin_r needs dL/dk~ of the chunk as well: rho0 and the sum of lambda.
 template <typename T, int K>
 __global__ __launch_bounds__(P1T) void precond_lin_m_kernel(PrecondBwdArgs a) {
@@ -86,6 +88,7 @@ __global__ __launch_bounds__(P1T) void precond_lin_m_kernel(PrecondBwdArgs a) {
     __shared__ __attribute__((aligned(16))) float Ss[C * LDT > TI_F ? C * LDT : TI_F];
     __shared__ __attribute__((aligned(16))) float Af[C * LDF];
     __shared__ float cas[C];
+    __shared__ float steps[C];
     float *Ti = Ss, *Xs = Ss + C * LDF;
 
     const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -95,7 +98,6 @@ __global__ __launch_bounds__(P1T) void precond_lin_m_kernel(PrecondBwdArgs a) {
     const size_t tokc = ((size_t)b * a.T + (size_t)n * C) * a.H + h;
     const int i = tid >> 3, part = tid & 7;
     const uint32_t kstride = (uint32_t)a.H * K;
-    // the keys are requested before the masks decide whether they are needed
     u32x4 kv[NVK];
     {
         const uint32_t off = ((uint32_t)i * kstride + (uint32_t)(part * EPT)) * (uint32_t)sizeof(T);
@@ -103,21 +105,16 @@ __global__ __launch_bounds__(P1T) void precond_lin_m_kernel(PrecondBwdArgs a) {
 #pragma unroll
         for (int m = 0; m < NVK; ++m) kv[m] = at_byte(kp, off + 16 * m);
     }
-    float nraw = 1.f, bet = 0.f;
+    const bool project = a.d_min <= a.d_max;
+    float nraw = 1.f, bet = 0.f, d = 1.f;
     if (tid < C) {
         const size_t th = tokc + (size_t)tid * a.H;
-        nraw = a.tok_scalars[th * 4 + 2];
+        const float4 sc = *reinterpret_cast<const float4 *>(a.tok_scalars + th * 4);
+        steps[tid] = sc.x;
+        nraw = sc.z;
         bet = a.beta[th];
     }
-    // ---- does the chunk qualify?  (no coordinate met the box at any of its tokens) ----
-    bool ok = true;
-    if (a.d_min <= a.d_max && tid < K) {
-        const uint2 m = a.masks[bhn * K + tid];
-        ok = (m.x & m.y) == 0xffffffffu;
-    }
-    const int clean = __syncthreads_and(ok ? 1 : 0);
-    if (tid == 0) a.lin_clean[bhn] = clean;
-    if (!clean) return;
+    if (project && tid < K) d = a.d_ckpt[bhn * K + tid];
 #pragma unroll
     for (int m = 0; m < NVK; ++m)
 #pragma unroll
@@ -130,6 +127,24 @@ __global__ __launch_bounds__(P1T) void precond_lin_m_kernel(PrecondBwdArgs a) {
             }
             store_vec(Ss + i * LDT + part * EPT + m * VN + e4, sq);
         }
+    __syncthreads();
+    // ---- the box masks of the chunk; does it qualify?  (no coordinate met the box at any token) ----
+    bool ok = true;
+    if (project && tid < K) {
+        uint32_t mlo = 0u, mhi = 0u;
+#pragma unroll 8
+        for (int t = 0; t < C; ++t) {
+            const float sq = Ss[t * LDT + tid], st = steps[t];
+            const uint32_t in = lands_inside<false>(1.f, d, st, sq, a.d_min, a.d_max) ? (1u << (t & 31)) : 0u;
+            d = clip3(d_bar<false>(1.f, d, st, sq), a.d_min, a.d_max);
+            if (t < 32) mlo |= in; else mhi |= in;
+        }
+        a.masks[bhn * K + tid] = make_uint2(mlo, mhi);
+        ok = (mlo & mhi) == 0xffffffffu;
+    }
+    const int clean = __syncthreads_and(ok ? 1 : 0);
+    if (tid == 0) a.lin_clean[bhn] = clean;
+    if (!clean) return;
     if (tid < C) {
         const float nn = fmaxf(nraw, a.eps);
         const float bp = a.beta_aware ? bet : 1.f;
