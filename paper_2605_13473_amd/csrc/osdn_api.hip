@@ -734,9 +734,10 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     // sweep: a dependent chain less than half as long for about 0.6 KB more memory traffic per
     // token-head.  It pays while the phase-1 chain is what the pass waits for: chains on at most a
     // quarter of the CUs (measured at 64 chains: 3 % of forward + backward; with more chains the
-    // chains fill the chip by themselves and the pass is bound by its memory traffic).
+    // chains fill the chip by themselves and the pass is bound by its memory traffic).  With fp32
+    // I/O the inverses are twice the size and the form stops paying earlier: an eighth of the CUs.
     const long long chains_all = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
-    const bool solved = !retention && (p->p1_solved > 0 || (p->p1_solved == 0 && chains_all * 4 <= NUM_CU));
+    const bool solved = !retention && (p->p1_solved > 0 || (p->p1_solved == 0 && chains_all * (bf ? 4 : 8) <= NUM_CU));
     if (solved) {
         pb.lin_clean = reinterpret_cast<int *>(ws + L.lin_clean);
         pb.lin_M = ws + L.lin_M;
@@ -749,7 +750,9 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     int S = segment_count(p->segments, N, pk.longest, chains * (p->V / 32) + chains, true, chains);   // chain kernel: 32 rows of the state per workgroup
     // (the backward chain keeps slices of 32 values: with 16 the kernel itself is a fifth faster on
     // few chains, but its workgroups then hold twice the CUs and what they take from the phase-1
-    // chain beside them, which bounds the pass there, costs more)
+    // chain beside them, which bounds the pass there, costs more.  The exception is fp32 I/O at
+    // K = 128, where the wide slice does not fit the registers: 131 spilled against 19.)
+    c.narrow_slices = !bf && p->K == 128;
     Pipeline *pl = S > 1 ? pipeline_for(st) : nullptr;
     if (!pl) S = 1;
     auto seg_range = [&](int sidx, int &n0, int &n1) { n0 = seg_begin(N, S, sidx); n1 = seg_begin(N, S, sidx + 1); };
