@@ -76,7 +76,10 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
     static_assert(NRUN == P1W && RUN == 8, "one wavefront per run of 8 tokens");
     typedef Pack<T, CPT> Pk;
     __shared__ float dcur[K];                    // d at the start of the chunk
-    __shared__ __attribute__((aligned(16))) float4 maps[NRUN * K];   // (A, B, L, H) per run and coordinate
+    // (A, B, L, H) per run and coordinate, [run][e][lane] for coordinate lane * CPT + e: the 16-byte
+    // accesses of adjacent lanes are then adjacent (a lane's own coordinates 32 bytes apart made
+    // every such access a two-way bank conflict)
+    __shared__ __attribute__((aligned(16))) float4 maps[NRUN * K];
     __shared__ int okflag[NRUN];
 
     const int tid = threadIdx.x, run = tid >> 6, lane = tid & 63;
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
                         H = clip3(H + bs, lo, hi);
                     }
                 }
-                maps[run * K + c0 + e] = make_float4(A, B, L, H);
+                maps[(run * CPT + e) * 64 + lane] = make_float4(A, B, L, H);
             }
             __syncthreads();
             float vp[RUN];
@@ -257,7 +260,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
 #pragma unroll
                 for (int j = 0; j < NRUN - 1; ++j)
                     if (j < run) {
-                        const float4 m = maps[j * K + c0 + e];
+                        const float4 m = maps[(j * CPT + e) * 64 + lane];
                         d = clip3(__builtin_fmaf(m.x, d, m.y), m.z, m.w);
                     }
                 // replay of the run's tokens (the same arithmetic as the reverse sweep's replay)
@@ -306,7 +309,7 @@ __global__ __launch_bounds__(P1T) void precond_fwd_kernel(PrecondArgs a) {
         if (PIECES && tid < K) {                 // the accepted run maps, applied after the piece so far
 #pragma unroll
             for (int j = 0; j < NRUN; ++j) {
-                const float4 m = maps[j * K + tid];
+                const float4 m = maps[(j * CPT + tid % CPT) * 64 + tid / CPT];
                 PA *= m.x;
                 PB = __builtin_fmaf(m.x, PB, m.y);
                 PL = clip3(__builtin_fmaf(m.x, PL, m.y), m.z, m.w);
