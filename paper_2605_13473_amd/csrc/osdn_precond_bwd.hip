@@ -551,7 +551,10 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     __shared__ __attribute__((aligned(16))) float casig_s[C];
     __shared__ __attribute__((aligned(16))) float gp_s[C];
     __shared__ __attribute__((aligned(16))) float gn_s[C];
-    __shared__ float prod[(HAS_RET && !RET_VEC) ? C * LD : 1];    // abar_i d_i per coordinate, for the scalar gate's dL/dr
+    // the scalar gate's dL/dr_i = sum over the coordinates of abar_i d_i: folded over the lanes of a
+    // wavefront eight tokens at a time, one partial per wavefront and token here
+    __shared__ float rpart[(HAS_RET && !RET_VEC) ? (K / 64) * C : 1];
+    static_assert(PB == 8, "the fold takes eight values per lane");
     const int n = a.n0 + blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int N = a.T / C;
     const size_t bh = (size_t)b * a.H + h;
@@ -622,6 +625,7 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     for (int blk = 0; blk < C / PB; ++blk) {
         const int ih = C - 1 - blk * PB;
         if (blk + 1 < C / PB) OSDN_PLOAD((blk + 1) & 1, ih - PB)
+        float pr[PB];
 #pragma unroll
         for (int u = 0; u < PB; ++u) {
             const int i = ih - u;
@@ -631,19 +635,24 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
             const float gsum = st_p[i] * ab + gp_p[i] * Di + gn_p[i];
             at_byte(op, sofs) = from_f32<T>(rb[blk & 1][u] + Di * g + 2.f * kv * gsum);
             if (RET_VEC) { if (dretp) at_byte(dretp, sofs * FS) = ab * Di; }
-            else if (HAS_RET) prod[i * LD + tid] = ab * Di;
+            pr[u] = ab * Di;
             sofs -= rowb;
             const float src = __builtin_fmaf(-casig_p[i], kv * kv, kv * g);
             const float r = RET_VEC ? rrb[RET_VEC ? blk & 1 : 0][RET_VEC ? u : 0] : r_p[i];
             av = HAS_RET ? __builtin_fmaf(r, ab, src) : ab + src;
+        }
+        if (HAS_RET && !RET_VEC) {
+            const int lane = tid & 63;
+            const float tot = lane_fold8_all(pr, lane);     // lane l: token ih - l % 8, summed over the wavefront
+            if (lane < PB) rpart[(HAS_RET && !RET_VEC) ? (tid >> 6) * C + ih - lane : 0] = tot;
         }
     }
     if (HAS_RET && !RET_VEC) {
         __syncthreads();
         if (tid < C && a.dretention) {
             float s = 0.f;
-#pragma unroll 8
-            for (int c = 0; c < K; ++c) s += prod[tid * LD + c];
+#pragma unroll
+            for (int w = 0; w < K / 64; ++w) s += rpart[(HAS_RET && !RET_VEC) ? w * C + tid : 0];
             a.dretention[tokc + (size_t)tid * a.H] = s;
         }
     }
