@@ -21,9 +21,12 @@
 // sigma_j s_j)  (g = the adjoint at the chunk's right end, lambda_j = k_j (.) dL/dk~_j), hence
 //     (I + U) sigma = S g + rho0,   U_ij = <s_i, s_j> ca_j (j > i),   rho0_i = <s_i, sum_{j>i} lambda_j>,
 //     a_left = g + sum_j lambda_j - S^T (ca (.) sigma).
-//   precond_lin    one workgroup per (chain, chunk), all chunks in parallel, before the chain:
-//                  decides whether the chunk qualifies and, if so, leaves (I + U)^-1 (Gram matrix
-//                  and blocked inverse on the fp32 MFMA), rho0 and sum_j lambda_j;
+//   precond_lin_m  one workgroup per (chain, chunk), all chunks in parallel, needs the forward
+//                  pass only: writes the chunk's masks (in place of precond_mask, which is not
+//                  launched when this form is on), decides whether the chunk qualifies and, if
+//                  so, leaves (I + U)^-1 (Gram matrix and blocked inverse on the fp32 MFMA), kept
+//                  in the I/O type;
+//   precond_lin_r  the same grid, once dL/dk~ of the chunk is there: rho0 and sum_j lambda_j;
 // on such a chunk precond_chain only has the three matrix-vector products left (osdn_precond.h,
 // "a chunk of the recurrence in solved form"); on any other chunk it runs its sweeps.
 #include "osdn_precond.h"
@@ -584,7 +587,7 @@ __global__ __launch_bounds__(K) __attribute__((amdgpu_waves_per_eu(2, 8))) void 
     float *dretp = (RET_VEC && a.dretention) ? a.dretention + tokc * K : nullptr;
     const uint32_t kstride = (uint32_t)a.H * K;
     float Dv[C];
-    // which steps landed inside the box: decided once, by the mask kernel
+    // which steps landed inside the box: decided once, by precond_mask (or precond_lin_m)
     const uint2 mbits = project ? a.masks[(bh * N + n) * K + tid] : make_uint2(0xffffffffu, 0xffffffffu);
     const uint32_t mlo = mbits.x, mhi = mbits.y;
     {   // ---- replay d over the chunk (same arithmetic as the forward kernel) ----
