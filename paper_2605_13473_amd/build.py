@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libosdn.so")
-SOURCES = ["osdn_api.hip", "osdn_precond.hip", "osdn_precond_bwd.hip", "osdn_step.hip", "osdn_pad.hip",
+SOURCES = ["osdn_api.hip", "osdn_precond.hip", "osdn_precond_bwd.hip", "osdn_precond_gen.hip", "osdn_step.hip", "osdn_pad.hip",
            "osdn_chunk_fwd.hip", "osdn_chunk_bwd.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -42,7 +42,7 @@ struct Layout {
     size_t piece_start, piece_map, piece_flags;                          // phase 1 as sweeps over the whole sequence
     size_t Tm, Pm;                                                       // written by the forward pass for the backward pass only
     size_t dEt, dS_ckpt, dk_read, dkt, masks, a_ckpt;                    // backward only
-    size_t lin_clean, lin_M, lin_r0, lin_t0;                             // backward: chunks of phase 1 in solved form
+    size_t lin_clean, lin_M, lin_r0, lin_t0, lin_aux;                           // backward: chunks of phase 1 in solved form
     // padded copies of the caller's tensors, only when T is not a multiple of the chunk length
     size_t p_q, p_k, p_v, p_beta, p_g, p_r, p_o;                        // forward
     size_t p_dO, p_dq, p_dk, p_dv, p_dbeta, p_dg, p_dr;                 // backward
@@ -169,6 +169,7 @@ Layout make_layout(const osdn_params *p, const Packing &pk) {
     L.lin_M = take(B * H * N * C * C * es);
     L.lin_r0 = take(B * H * N * C * 4);
     L.lin_t0 = take(B * H * N * K * 4);
+    L.lin_aux = take(B * H * N * 2048);
     if (p->gate_per_channel) L.dgamC = take(B * H * N * K * 4);
     if (ragged) {
         L.p_dO = take(B * T * H * V * es); L.p_dv = take(B * T * H * V * es);
@@ -737,12 +738,15 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     // chains fill the chip by themselves and the pass is bound by its memory traffic).  With fp32
     // I/O the inverses are twice the size and the form stops paying earlier: an eighth of the CUs.
     const long long chains_all = (long long)(pk.n_seqs ? pk.n_seqs : p->B) * p->H;
-    const bool solved = !retention && (p->p1_solved > 0 || (p->p1_solved == 0 && chains_all * (bf ? 4 : 8) <= NUM_CU));
+    const bool general = retention && !p->retention_per_channel;      // the form with a retention gate and any masks
+    const bool solved = general ? p->p1_solved > 0
+                                : !retention && (p->p1_solved > 0 || (p->p1_solved == 0 && chains_all * (bf ? 4 : 8) <= NUM_CU));
     if (solved) {
         pb.lin_clean = reinterpret_cast<int *>(ws + L.lin_clean);
         pb.lin_M = ws + L.lin_M;
         pb.lin_r0 = reinterpret_cast<float *>(ws + L.lin_r0);
         pb.lin_t0 = reinterpret_cast<float *>(ws + L.lin_t0);
+        pb.lin_aux = reinterpret_cast<unsigned char *>(ws + L.lin_aux);
     }
 
     const int N = p->T / C;
@@ -776,18 +780,18 @@ static int bwd_impl(const osdn_params *p, const void *q, const void *k, const vo
     auto lin_m = [&](int n0, int n1, hipStream_t s1) {
         if (!pb.lin_clean) return 0;
         pb.n0 = n0; pb.n1 = n1;
-        return timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, true, s1); });
+        return timed(KID_PRECOND_LIN, s1, [&] { return general ? launch_precond_gen(pb, bf, 0, s1) : launch_precond_lin_bwd(pb, bf, true, s1); });
     };
     // solved form: what its chunks need from dk~ (rho0, the sums of lambda)
     auto lin_r = [&](int sidx, hipStream_t s1) {
         if (!pb.lin_clean) return 0;
         seg_range(sidx, pb.n0, pb.n1);
-        return timed(KID_PRECOND_LIN, s1, [&] { return launch_precond_lin_bwd(pb, bf, false, s1); });
+        return timed(KID_PRECOND_LIN, s1, [&] { return general ? launch_precond_gen(pb, bf, 1, s1) : launch_precond_lin_bwd(pb, bf, false, s1); });
     };
     auto phase1 = [&](int sidx, hipStream_t s1) {
         seg_range(sidx, pb.n0, pb.n1);
         pb.dd_out = sidx == S - 1 ? dd_out : dd_in;  // the adjoint of d is carried in dd_in
-        if (timed(KID_PRECOND_CHAIN, s1, [&] { return launch_precond_chain(pb, bf, s1); }) != 0) return -1;
+        if (timed(KID_PRECOND_CHAIN, s1, [&] { return (general && pb.lin_clean) ? launch_precond_gen(pb, bf, 2, s1) : launch_precond_chain(pb, bf, s1); }) != 0) return -1;
         return timed(KID_PRECOND_POST, s1, [&] { return launch_precond_post(pb, bf, s1); });
     };
     if (!pl) {

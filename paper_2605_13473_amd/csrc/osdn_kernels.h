@@ -71,6 +71,7 @@ struct PrecondBwdArgs {
     void *lin_M;              // [B,H,T/64,64,64] io
     float *lin_r0;            // [B,H,T/64,64]
     float *lin_t0;            // [B,H,T/64,K]
+    unsigned char *lin_aux;   // [B,H,T/64,2048]: with a retention gate, the indicators and retention products of the chunk
 };
 
 // The recurrent step (decode): state in registers, 1..64 tokens per launch.
@@ -141,6 +142,9 @@ int launch_upload_ints(const int *host, size_t count, int *dst, hipStream_t st);
 int launch_move_chunk_rows(const void *src, void *dst, const int *chunk_row, const int *chunk_len, int n_chunks,
                            size_t row_bytes, bool to_padded, uint32_t fill, hipStream_t st);
 int launch_precond_mask(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
+// solved form with a retention gate per (token, head): which = 0 masks, inverse and indicators (forward
+// data only), 1 rho0 and t0 (needs dL/dk~), 2 the chain; chunks [n0, n1)
+int launch_precond_gen(const PrecondBwdArgs &a, bool bf16_io, int which, hipStream_t st);
 int launch_precond_lin_bwd(const PrecondBwdArgs &a, bool bf16_io, bool m_part, hipStream_t st);
 int launch_precond_chain(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);
 int launch_precond_post(const PrecondBwdArgs &a, bool bf16_io, hipStream_t st);

@@ -19,6 +19,33 @@ def test_config0_tiny_fp32_forward():
     compare_forward(x, ob.Hyper(), bf16=False)
 
 
+@pytest.mark.parametrize("case", ["apf_k64", "apf_k128_bf16_ragged", "strong_forgetting", "no_box", "eta_one_faces",
+                                  "long_segments", "non_beta_aware"])
+def test_reverse_sweep_in_solved_form_with_a_retention_gate(case):
+    """With one retention value per (token, head) and any box masks the reverse sweep is still
+    linear once the masks are known: every chunk takes the solved form (the triangular system then
+    carries the retention products and, per coordinate, the runs of set mask bits).  Forced on:
+    APF-like retention with eta = 0.5 (coordinates enter and leave the box inside chunks), K = 128
+    in bf16 on a ragged length, strong forgetting, no box at all, eta = 1 (coordinates riding a
+    face), 40 chunks over several segments, and the non-beta-aware step."""
+    bf16 = case == "apf_k128_bf16_ragged"
+    B, T, H, K, V = {"apf_k64": (2, 448, 2, 64, 64), "apf_k128_bf16_ragged": (2, 64 * 9 - 17, 2, 128, 128),
+                     "strong_forgetting": (1, 320, 3, 128, 64), "no_box": (1, 320, 2, 128, 64),
+                     "eta_one_faces": (2, 384, 2, 64, 64), "long_segments": (1, 64 * 40, 2, 64, 64),
+                     "non_beta_aware": (2, 256, 2, 64, 128)}[case]
+    ret = {"strong_forgetting": 0.7, "long_segments": 0.999}.get(case, 0.97)
+    x = make_stress_inputs(B, T, H, K, V, seed=131, bf16=bf16, retention=ret)
+    hp = {"apf_k64": ob.Hyper(eta=0.5, p1_solved=1), "apf_k128_bf16_ragged": ob.Hyper(eta=0.3, p1_solved=1),
+          "strong_forgetting": ob.Hyper(eta=0.5, p1_solved=1),
+          "no_box": ob.Hyper(eta=0.3, d_min=1.0, d_max=0.0, p1_solved=1),
+          "eta_one_faces": ob.Hyper(eta=1.0, p1_solved=1), "long_segments": ob.Hyper(eta=0.1, p1_solved=1),
+          "non_beta_aware": ob.Hyper(eta=0.2, beta_aware=False, p1_solved=1)}[case]
+    rng = np.random.default_rng(132)
+    dS = rng.standard_normal((B, H, V, K)).astype(np.float32)
+    dd = rng.standard_normal((B, H, K)).astype(np.float32)
+    compare_backward(x, hp, bf16, dS, dd)
+
+
 @pytest.mark.parametrize("segments", [0, 3, 5])
 def test_solved_form_when_the_chain_kernel_fills_the_chip(segments):
     """64 chains of 128 values: the workgroups of the backward chain kernel then fill every CU, and
