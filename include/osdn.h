@@ -105,9 +105,11 @@ typedef struct {
                                        pieces per chain; -1: never (always the sequential sweep) */
     int32_t p1_piece_sweeps;        /* > 0: at most this many such sweeps (up to 13) before the sequential
                                        sweep finishes the chains that have not settled */
-    int32_t p1_solved;              /* osdn_bwd without retention: 1: the reverse sweep always takes chunks in
-                                       which no coordinate met the box in solved form (a 64 x 64 triangular
-                                       system per chunk, inverted for all chunks side by side); -1: never */
+    int32_t p1_solved;              /* osdn_bwd: 1: the reverse sweep takes chunks in solved form (a 64 x 64
+                                       triangular system per chunk, inverted for all chunks side by side):
+                                       without retention the chunks in which no coordinate met the box, with
+                                       one retention value per (token, head) every chunk; -1: never; 0: the
+                                       library decides (only ever without retention) */
 } osdn_params;
 
 /* Bytes of scratch osdn_fwd needs (for_backward == 0) or osdn_fwd followed by osdn_bwd

@@ -50,8 +50,8 @@ __global__ __launch_bounds__(P1T) void precond_gen_m_kernel(PrecondBwdArgs a) {
     static_assert(TI_F <= C * LDT || K == 64, "the inverse reuses the s tile");
     __shared__ __attribute__((aligned(16))) float Ss[C * LDT > TI_F ? C * LDT : TI_F];
     __shared__ __attribute__((aligned(16))) float Af[C * LDF];
-    __shared__ float Pf[HAS_RET ? C * LDF : 1];
     __shared__ float cas[C], steps[C], rs[C];
+    __shared__ float rpre_s[C + 1];              // R(0..t-1), t = 0..64
     __shared__ uint2 mw[K];
     __shared__ int mixl[K];
     __shared__ int wcnt[K / 64];
@@ -132,15 +132,25 @@ __global__ __launch_bounds__(P1T) void precond_gen_m_kernel(PrecondBwdArgs a) {
         // (position inside this wavefront's part of the list; the offset of the part follows below)
         if (mixed) mixl[wave * 64 + __builtin_popcountll(mb & ((1ull << lane) - 1ull))] = tid;
     } else if (tid >= P1T - C) {
-        const int t = tid - (P1T - C);
-        float pre = 1.f, suf = 1.f;
+        // prefix and suffix products of the retention over the 64 tokens (one wavefront, lane = token)
+        const int t = lane;
+        float inc = HAS_RET ? rs[t] : 1.f, dec = inc;            // inclusive scans from the left / from the right
         if (HAS_RET) {
-            for (int l = 0; l < t; ++l) pre *= rs[l];
-            for (int l = t + 1; l < C; ++l) suf *= rs[l];
+#pragma unroll
+            for (int sft = 1; sft < C; sft <<= 1) {
+                const float up = __shfl_up(inc, sft, 64), dn = __shfl_down(dec, sft, 64);
+                if (t >= sft) inc *= up;
+                if (t + sft < C) dec *= dn;
+            }
         }
+        float pre = __shfl_up(inc, 1, 64), suf = __shfl_down(dec, 1, 64);
+        if (t == 0) pre = 1.f;
+        if (t == C - 1) suf = 1.f;
+        rpre_s[t] = pre;
+        if (t == C - 1) rpre_s[C] = inc;
         *reinterpret_cast<float *>(aux + GA_RPRE + 4 * t) = pre;
         *reinterpret_cast<float *>(aux + GA_RSUF + 4 * t) = suf;
-        if (t == C - 1) *reinterpret_cast<float *>(aux + GA_RALL) = pre * (HAS_RET ? rs[C - 1] : 1.f);
+        if (t == C - 1) *reinterpret_cast<float *>(aux + GA_RALL) = inc;
     }
     __syncthreads();
     // ---- W_c(t..63) for this thread's token and coordinates ----
@@ -183,24 +193,11 @@ __global__ __launch_bounds__(P1T) void precond_gen_m_kernel(PrecondBwdArgs a) {
         }
         __syncthreads();
     }
-    {
-        // R(t+1..j-1) for this thread's pairs, by running products (no division: r may be 0)
-        float P = 1.f;
-        if (HAS_RET)
-            for (int l = i + 1; l < i + 1 + part && l < C; ++l) P *= rs[l];
+    // ---- Gram matrix of the coordinates whose bits are all set (if there are any), on the MFMA ----
+    bool anyclean = false;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int j = i + 1 + 8 * q + part;
-            if (j < C) {
-                Af[j * LDF + i] = acc[q];
-                if (HAS_RET) Pf[HAS_RET ? j * LDF + i : 0] = P;
-            }
-            if (HAS_RET)
-                for (int l = j; l < j + 8 && l < C; ++l) P *= rs[l];
-        }
-    }
-    // ---- the s tile with only the coordinates whose bits are all set ----
-    {
+    for (int w = 0; w < K / 32; ++w) anyclean = anyclean || cleanw[w] != 0u;     // (uniform)
+    if (anyclean) {
         const uint32_t cw = cleanw[(part * EPT) >> 5] >> ((part * EPT) & 31);
 #pragma unroll
         for (int m = 0; m < NVK; ++m)
@@ -214,19 +211,33 @@ __global__ __launch_bounds__(P1T) void precond_gen_m_kernel(PrecondBwdArgs a) {
                 }
                 store_vec(Ss + i * LDT + part * EPT + m * VN + e4, sq);
             }
-    }
-    __syncthreads();
-    // ---- A = U^T (lower triangular): Gram part on the MFMA plus the pair sums, times ca_j R ----
-    for (int idx = wave; idx < 10; idx += P1W) {
-        const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
-        const int jb = idx - (ib * (ib + 1)) / 2;
-        const f32x4 g4 = mma_tile0<float, true, true>(Ss + ib * 16 * LDT, LDT, Ss + jb * 16 * LDT, LDT, K, lane);
+        __syncthreads();
+        for (int idx = wave; idx < 10; idx += P1W) {
+            const int ib = idx < 1 ? 0 : idx < 3 ? 1 : idx < 6 ? 2 : 3;
+            const int jb = idx - (ib * (ib + 1)) / 2;
+            const f32x4 g4 = mma_tile0<float, true, true>(Ss + ib * 16 * LDT, LDT, Ss + jb * 16 * LDT, LDT, K, lane);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int ii = ib * 16 + acc_row(lane, r), jj = jb * 16 + acc_col(lane);
-            float v = 0.f;
-            if (jj < ii) v = cas[ii] * (HAS_RET ? Pf[HAS_RET ? ii * LDF + jj : 0] : 1.f) * (g4[r] + Af[ii * LDF + jj]);
-            Af[ii * LDF + jj] = v;
+            for (int r = 0; r < 4; ++r) Af[(ib * 16 + acc_row(lane, r)) * LDF + jb * 16 + acc_col(lane)] = g4[r];
+        }
+        __syncthreads();
+    }
+    // ---- A = U^T, strictly lower triangular: A_jt = ca_j R(t+1..j-1) (Gram part + pair sums), by the
+    //      thread that owns the pair.  R(t+1..j-1) = R(0..j-1) / R(0..t); where that prefix has run
+    //      to zero, the product term by term. ----
+    {
+        const float den = HAS_RET ? rpre_s[i + 1] : 1.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int j = i + 1 + 8 * q + part;
+            if (j < C) {
+                float P = 1.f;
+                if (HAS_RET) {
+                    if (den > 1e-30f) P = rpre_s[j] / den;
+                    else for (int l = i + 1; l < j; ++l) P *= rs[l];
+                }
+                const float gram = anyclean ? Af[j * LDF + i] : 0.f;
+                Af[j * LDF + i] = cas[j] * P * (gram + acc[q]);
+            }
         }
     }
     __syncthreads();                                             // the s tile is dead: its space takes the inverse
