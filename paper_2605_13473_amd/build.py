@@ -25,9 +25,16 @@ def build(verbose: bool = False, only=None) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ, exist_ok=True)
 
+    # an object is reused only if it is newer than every header (the kernels pass their arguments
+    # in structs declared there: an object built against an older layout must never be linked)
+    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    headers.append(os.path.join(os.path.dirname(HERE), "include", "osdn.h"))
+    newest_header = max(os.path.getmtime(h) for h in headers if os.path.exists(h))
+
     def compile_one(src):
         obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-        if only is not None and src not in only and os.path.exists(obj):
+        if (only is not None and src not in only and os.path.exists(obj)
+                and os.path.getmtime(obj) > max(newest_header, os.path.getmtime(os.path.join(CSRC, src)))):
             return obj
         cmd = [hipcc, *FLAGS, "-c", "-o", obj, os.path.join(CSRC, src)]
         if verbose:
