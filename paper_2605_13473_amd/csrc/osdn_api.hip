@@ -215,8 +215,8 @@ ChunkArgs chunk_args(const osdn_params *p, const Layout &L, char *ws) {      // 
 // segment, and phase 2 follows one segment behind on the caller's stream (in the backward
 // pass the other way round, right to left).  The side stream is forked from and joined back
 // into the caller's stream with events, so to the caller the call still behaves as work
-// enqueued on its stream.  One side stream and one set of events per device, created on first
-// use and kept; calls are serialised by a mutex while they enqueue.
+// enqueued on its stream.  One side stream and one set of events per (device, caller stream),
+// created on first use and kept (pipeline_for below); a mutex guards only the table of them.
 constexpr int MAX_SEGMENTS = 16;
 struct Pipeline {
     hipStream_t side = nullptr;
