@@ -114,6 +114,15 @@ def test_dominant_sequence_is_pipelined_over_segments(lens):
     _compare(lens, H=1, K=64, V=64, seed=67, bf16=False, hp=ob.Hyper(eta=0.3))
 
 
+@pytest.mark.parametrize("retention", [0.95, 0.0])
+def test_reverse_sweep_in_solved_form_on_a_packed_axis(retention):
+    """The solved forms of the reverse sweep (with a retention gate: every chunk; without: the
+    chunks that never met the box), forced on, with sequences that begin and end inside a launch's
+    chunk range and one long enough for several segments."""
+    _compare([150, 1400, 64, 1, 333], H=2, K=64, V=64, seed=68, bf16=False, hp=ob.Hyper(eta=0.3, p1_solved=1),
+             retention=retention)
+
+
 def test_defaults_null_ungated_no_retention():
     _compare([100, 28, 130], H=2, K=128, V=64, seed=64, bf16=False, hp=ob.Hyper(eta=0.5), retention=0.0,
              gated=False, carried=False)
